@@ -1,0 +1,262 @@
+/*
+ * mdh.h -- C ABI of libmdh: tiled evaluation of multi-dimensional homomorphisms
+ *
+ *     md_hom(f, (op_1, ..., op_D))            (paper: Definition "Higher-Order Function md_hom")
+ *
+ * on one AMD MI355X (gfx950 / CDNA4).  A scalar function f is applied at every
+ * point of a D-dimensional index space and dimension d is combined with op_d,
+ * which is either concatenation (++) -- the dimension indexes the output -- or a
+ * point-wise reduction operator (+, or the user-defined max-with-index).
+ *
+ * The library evaluates four fixed instances of the paper's example table
+ * (Figure "Data-parallel computations expressed in our high-level
+ * representation"): MatMul, Jacobi-3D, multi-channel convolution (MCC) and a
+ * record-linkage style custom reduction.  Each call takes the index-space sizes
+ * N_1..N_D, the operand buffers the input/output views address, and one
+ * configuration of the paper's tuning parameters (Table "Tuning parameters of
+ * our low-level expressions"), restricted as in Section "Auto-Tuning".
+ *
+ * Conventions for every entry point
+ *   - every buffer pointer is a DEVICE pointer owned by the caller; the library
+ *     never allocates, frees or synchronises; a call only enqueues kernels on
+ *     `stream` (a hipStream_t passed as void*, NULL = the default stream);
+ *   - inputs are never written; outputs are fully overwritten (the paper's
+ *     re-composition overrides on first write, it does not accumulate into the
+ *     destination: Appendix "Code Generation", re-composition phase);
+ *   - all buffers are dense row-major (layout [1,2,...] in the paper's notation);
+ *   - errors are reported through mdh_status only; an invalid call enqueues
+ *     nothing; results are bit-identical run to run for fixed parameters.
+ */
+#ifndef MDH_H
+#define MDH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum mdh_status {
+  MDH_OK = 0,
+  MDH_ERR_NULL = 1,              /* a required pointer is NULL                                  */
+  MDH_ERR_SIZE = 2,              /* a size is negative, a reduction extent is 0, or a buffer
+                                    would exceed 2^31-1 elements                                */
+  MDH_ERR_TILE_NOT_DIVIDING = 3, /* prod_l #PRT(l,d) * blk[d] != N_d (algorithmic constraint
+                                    of tuning parameter 0)                                      */
+  MDH_ERR_TILE_RESOURCES = 4,    /* model constraint violated: > 1024 lanes per workgroup,
+                                    LDS or register budget exceeded                             */
+  MDH_ERR_WORKSPACE = 5,         /* workspace missing or too small for a split reduction        */
+  MDH_ERR_UNSUPPORTED = 6,       /* valid in the paper's space but no kernel instantiation      */
+  MDH_ERR_LAUNCH = 7             /* the HIP runtime refused the launch                          */
+} mdh_status;
+
+/* Instances (index into the library's table of md_hom expressions). */
+typedef enum mdh_instance {
+  MDH_MATMUL = 0,        /* md_hom(*, (++, ++, +)),            dims (i, j, k)              */
+  MDH_STENCIL = 1,       /* md_hom(J_3D, (++, ++, ++)),        dims (i, j, k)              */
+  MDH_MCC = 2,           /* md_hom(*, (++,++,++,++, +,+,+)),   dims (n, p, q, k, c, r, s)  */
+  MDH_CUSTOM_REDUCE = 3  /* md_hom(wght, (++, max_idx)),       dims (a, b)                 */
+} mdh_instance;
+
+/*
+ * Abstract System Model of the target (paper: Definition "Abstract System
+ * Model"): ASM_CDNA4 = (3 memory layers, 3 core layers), the analogue of the
+ * paper's ASM_CUDA+WRP.  Parts on a memory layer are processed sequentially,
+ * parts on a core layer in parallel.
+ */
+enum {
+  MDH_L_HBM = 0,  /* memory layer: sequential tiles streamed from device memory */
+  MDH_L_LDS = 1,  /* memory layer: sequential tiles inside an LDS-resident tile  */
+  MDH_L_VGPR = 2, /* memory layer: sequential elements inside a register tile    */
+  MDH_L_WG = 3,   /* core layer: workgroups                                      */
+  MDH_L_WAVE = 4, /* core layer: wavefronts (64 lanes) of a workgroup            */
+  MDH_L_LANE = 5, /* core layer: lanes of a wavefront                            */
+  MDH_NUM_LAYERS = 6,
+  MDH_MAX_D = 7
+};
+
+/* Memory regions (parameters D3/S3/S5/R3). */
+enum { MDH_MR_HBM = 0, MDH_MR_LDS = 1, MDH_MR_VGPR = 2 };
+
+/*
+ * One configuration of the tuning parameters, under the paper's own
+ * restrictions (Section "Auto-Tuning": one fused loop nest, i.e. D1=S1=R1 and
+ * D2=S2=R2; blocked or strided assignment only; full tiles per memory region).
+ *
+ * prt[l][d]  parameter 0, #PRT(l,d): number of parts of dimension d on layer l.
+ * blk[d]     extent of the innermost block evaluated as one unit.  1 everywhere
+ *            is the paper's full partitioning; the contractions use the FP32
+ *            MFMA block (the coarser partitioning the paper names as future
+ *            work for matrix hardware).  Constraint:
+ *                prod_l prt[l][d] * blk[d] == N_d          (ragged == 0)
+ *                prod_l prt[l][d] * blk[d] >= N_d          (ragged == 1; the
+ *                tail parts are predicated -- an extension, the paper requires
+ *                equality)
+ * order[]    parameters D1=S1=R1: the fused loop order, outermost first, each
+ *            entry = l * MDH_MAX_D + d; only the first MDH_NUM_LAYERS*D entries
+ *            are used.  The library supports the order its kernel implements
+ *            (returned by mdh_default_params) and rejects any other.
+ * strided    parameters D2=S2=R2 restricted to two values: 0 = blocked (outer
+ *            parallelism: a core owns one contiguous part), 1 = strided.
+ * lane_fast_dim  which md_hom dimension follows the fastest lane index (the
+ *            paper's swizzle choice; decides coalescing).
+ * in_region[b] / out_region   parameters D3/S3 and R3/S5: the fastest memory
+ *            region input buffer b is staged in / results are combined in.
+ * in_transposed[b] / out_transposed  parameters D4/S4, R4/S6 for 2-D tiles.
+ */
+typedef struct mdh_tile_params {
+  int32_t D;
+  int32_t prt[MDH_NUM_LAYERS][MDH_MAX_D];
+  int32_t blk[MDH_MAX_D];
+  uint8_t order[MDH_NUM_LAYERS * MDH_MAX_D];
+  uint8_t strided;
+  uint8_t lane_fast_dim;
+  uint8_t ragged;
+  uint8_t in_region[4];
+  uint8_t out_region;
+  uint8_t in_transposed[4];
+  uint8_t out_transposed;
+  uint8_t reserved[3];
+} mdh_tile_params;
+
+/* ------------------------------------------------------------------------- */
+/* Host-only helpers (no GPU needed)                                          */
+/* ------------------------------------------------------------------------- */
+
+/* Human-readable text for a status code; never NULL. */
+const char* mdh_strerror(mdh_status s);
+
+/* Library version, "major.minor". */
+const char* mdh_version(void);
+
+/*
+ * Uniform MDA partitioning (paper: Appendix, Definition "MDA Partitioning").
+ * For one dimension of extent N cut on L layers into P[0..L-1] parts, the part
+ * addressed by p[0..L-1] starts at
+ *     OS = sum_l p[l] * N / (P[0]*...*P[l])      and has      PS = N / prod_l P[l]
+ * elements.  Returns MDH_ERR_TILE_NOT_DIVIDING unless prod_l P[l] divides N,
+ * MDH_ERR_SIZE if some p[l] is outside [0,P[l]).
+ */
+mdh_status mdh_part_offset(int64_t N, int32_t L, const int32_t* P, const int32_t* p,
+                           int64_t* offset, int64_t* part_size);
+
+/*
+ * The library's tuned default configuration for (instance, sizes).
+ * `sizes` holds the D index-space extents in the dimension order listed at
+ * mdh_instance; for MDH_MCC two more entries follow: stride_h, stride_w.
+ * Host only; writes *out.
+ */
+mdh_status mdh_default_params(mdh_instance inst, const int64_t* sizes, mdh_tile_params* out);
+
+/*
+ * Check a configuration against the algorithmic constraint of parameter 0 and
+ * the model constraints (paper: Appendix "Constraints of Programming Models":
+ * at most 1024 lanes per workgroup; memory budgets), and against the set of
+ * kernel instantiations this library has.  Host only, launches nothing.
+ */
+mdh_status mdh_validate_params(mdh_instance inst, const int64_t* sizes, const mdh_tile_params* p);
+
+/*
+ * Bytes of device workspace a call needs: non-zero only when a reduction
+ * dimension is split over workgroups (prt[MDH_L_WG][d] > 1 for a non-++
+ * dimension d), because workgroup results can only be combined in device
+ * memory (paper: model constraint on R3 for the block layer).  params == NULL
+ * means the default configuration.  Returns 0 on invalid arguments.
+ */
+size_t mdh_workspace_size(mdh_instance inst, const int64_t* sizes, const mdh_tile_params* params);
+
+/* ------------------------------------------------------------------------- */
+/* Device entry points                                                        */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * MatMul: C[i,j] = sum_k A[i,k] * B[k,j]  =  md_hom(*, (++,++,+)) with input
+ * view (i,j,k)->A[i,k], (i,j,k)->B[k,j] and output view (i,j,0)->C[i,j]
+ * (paper: Section "Examples", Subfigure 1).
+ *   A: M x K, B: K x N, C: M x N, fp32, row-major, device.  K >= 1.
+ *   M == 0 or N == 0 is a valid empty call.
+ *   FP32 MFMA arithmetic, fp32 accumulation; if prt[MDH_L_WG][k] = S > 1 the
+ *   S partial results go to `workspace` (S*M*N floats) and a second kernel adds
+ *   them in ascending part order.
+ */
+mdh_status mdh_matmul(int64_t M, int64_t N, int64_t K, const float* A, const float* B, float* C,
+                      const mdh_tile_params* params, void* workspace, size_t workspace_bytes,
+                      void* stream);
+
+/*
+ * Jacobi-3D, one sweep of the 7-point stencil: md_hom(J_3D, (++,++,++)) whose
+ * input view reads one buffer seven times with offset index functions (paper:
+ * Section "Examples", Subfigure 4; 1-D form in Example "Input View -- Jacobi1D"):
+ *   out[i,j,k] = c0*in[i+1,j+1,k+1] + c1*( in[i,j+1,k+1] + in[i+2,j+1,k+1]
+ *              + in[i+1,j,k+1] + in[i+1,j+2,k+1] + in[i+1,j+1,k] + in[i+1,j+1,k+2] )
+ *   in : (nx+2) x (ny+2) x (nz+2) fp32 (size rule N_buf = 1 + max index),
+ *   out: nx x ny x nz fp32, compact (output view (i,j,k)->(i,j,k)).
+ *   Any of nx, ny, nz == 0 is a valid empty call.
+ */
+mdh_status mdh_stencil(int64_t nx, int64_t ny, int64_t nz, const float* in, float* out, float c0,
+                       float c1, const mdh_tile_params* params, void* stream);
+
+/*
+ * Multi-channel convolution: 7-dimensional md_hom(*, (++,++,++,++,+,+,+)) over
+ * (n,p,q,k,c,r,s) with index functions p*stride_h+r, q*stride_w+s (paper:
+ * Section "Examples", Subfigure 2; data characteristics table in the appendix):
+ *   out[n,p,q,k] = sum_{c,r,s} in[n, p*stride_h + r, q*stride_w + s, c] * filt[k,r,s,c]
+ *   in: N x H x W x C (NHWC), filt: K x R x S x C (KRSC), out: N x P x Q x K,
+ *   P = (H-R)/stride_h + 1, Q = (W-S)/stride_w + 1 (no implicit padding),
+ *   fp32, device.  C, R, S >= 1; H >= R; W >= S; strides >= 1.
+ */
+mdh_status mdh_mcc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                   int64_t stride_h, int64_t stride_w, const float* in, const float* filt,
+                   float* out, const mdh_tile_params* params, void* workspace,
+                   size_t workspace_bytes, void* stream);
+
+/*
+ * Record-linkage style custom reduction: md_hom(wght, (++, max_idx)) over (a,b)
+ * with an index-carrying scalar function (paper: Section "Examples",
+ * Subfigure 5, and Appendix "Design Decisions: md_hom" for scalar functions
+ * that receive MDA indices):
+ *   wght(a,b)  = ( sum_f (A[a,f] == B[b,f] ? w_agree[f] : w_disagree[f]) , b )
+ *   (s1,b1) max_idx (s2,b2) = the pair with the larger score; on equal scores
+ *                             the pair with the smaller index
+ *   out_score[a], out_index[a] = max_idx over all b.
+ *   A: nA x nF, B: nB x nF, weights: nF, outputs: nA; all int32, device.
+ *   1 <= nF <= 16, nB >= 1 (the operator has no neutral element), nA == 0 is an
+ *   empty call.  The caller guarantees that no sum of nF weights overflows
+ *   int32.  Integer arithmetic: the result is unique and reproduced bit-exactly.
+ *   If B is split over workgroups (prt[MDH_L_WG][b] = S > 1) the S partial
+ *   (score,index) pairs go to `workspace` (2*S*nA int32) and a second kernel
+ *   combines them.
+ */
+mdh_status mdh_custom_reduce(int64_t nA, int64_t nB, int32_t nF, const int32_t* A,
+                             const int32_t* B, const int32_t* w_agree, const int32_t* w_disagree,
+                             int32_t* out_score, int32_t* out_index,
+                             const mdh_tile_params* params, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+/*
+ * Small per-workload tile-parameter search (paper: Section "Auto-Tuning", with
+ * the search space shrunk to this library's kernel instantiations): runs every
+ * valid candidate for (instance, sizes) on the given buffers, times each with
+ * events on `stream`, and writes the fastest configuration to *best and its
+ * time to *best_ms.  `buffers` are the device pointers of the instance's entry
+ * point in declaration order (inputs then outputs); outputs are overwritten.
+ * `scalars` carries c0,c1 for the stencil and is ignored otherwise.
+ * Synchronises `stream`.  Not for use under graph capture.
+ */
+mdh_status mdh_tune(mdh_instance inst, const int64_t* sizes, void* const* buffers,
+                    const float* scalars, void* workspace, size_t workspace_bytes, void* stream,
+                    int32_t reps, mdh_tile_params* best, float* best_ms);
+
+/*
+ * Number of candidate configurations mdh_tune would try for (instance, sizes),
+ * and the idx-th of them (host only).
+ */
+int32_t mdh_num_candidates(mdh_instance inst, const int64_t* sizes);
+mdh_status mdh_candidate(mdh_instance inst, const int64_t* sizes, int32_t idx,
+                         mdh_tile_params* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MDH_H */

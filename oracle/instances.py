@@ -1,0 +1,113 @@
+"""The four md_hom instances written in the paper's high-level form
+
+        out_view( md_hom(f, (op_1..op_D)) ( inp_view(bufs) ) )
+
+with the generic evaluator of ``mdhom.py`` -- TEST INFRASTRUCTURE.  Pure Python,
+exact arithmetic where the inputs allow it (ints / Fractions), for index spaces
+of a few hundred points.  These are the brute-force cross-check of the nested
+loops in ``mdh_oracle.c``: same definition, evaluated through a different
+mechanism (iterated combine operators on MDAs instead of loop nests).
+"""
+from __future__ import annotations
+
+from . import mdhom as H
+
+
+def _add(x, y):
+    return x + y
+
+
+def matmul(A, B):
+    """md_hom(*, (++,++,+)); views (i,j,k)->A[i,k], (i,j,k)->B[k,j]; (i,j,0)->C[i,j]
+    (Section "Examples", Subfigure 1).  A, B nested lists; returns nested list C."""
+    M, K, N = len(A), len(A[0]), len(B[0])
+    iv = H.inp_view([[lambda i, j, k: (i, k)], [lambda i, j, k: (k, j)]])
+    h = H.md_hom(lambda ab: ab[0] * ab[1], (H.concat(0), H.concat(1), H.pointwise(2, _add)))
+    ov = H.out_view([[lambda i, j, k: (i, j)]])
+    (c,) = ov(h(iv([A, B], [range(M), range(N), range(K)])))
+    return [[c[(i, j)] for j in range(N)] for i in range(M)]
+
+
+def jacobi3d(x, c0, c1):
+    """md_hom(J_3D, (++,++,++)); the input view reads the one buffer seven times
+    with offset index functions; output view (i,j,k)->(i,j,k)."""
+    nx, ny, nz = len(x) - 2, len(x[0]) - 2, len(x[0][0]) - 2
+    iv = H.inp_view(
+        [
+            [
+                lambda i, j, k: (i + 1, j + 1, k + 1),
+                lambda i, j, k: (i + 0, j + 1, k + 1),
+                lambda i, j, k: (i + 2, j + 1, k + 1),
+                lambda i, j, k: (i + 1, j + 0, k + 1),
+                lambda i, j, k: (i + 1, j + 2, k + 1),
+                lambda i, j, k: (i + 1, j + 1, k + 0),
+                lambda i, j, k: (i + 1, j + 1, k + 2),
+            ]
+        ]
+    )
+
+    def J3D(t):
+        return c0 * t[0] + c1 * (t[1] + t[2] + t[3] + t[4] + t[5] + t[6])
+
+    h = H.md_hom(J3D, (H.concat(0), H.concat(1), H.concat(2)))
+    ov = H.out_view([[lambda i, j, k: (i, j, k)]])
+    (o,) = ov(h(iv([x], [range(nx), range(ny), range(nz)])))
+    return [[[o[(i, j, k)] for k in range(nz)] for j in range(ny)] for i in range(nx)]
+
+
+def mcc(x, filt, stride=(1, 1)):
+    """7-dimensional md_hom(*, (++,++,++,++,+,+,+)) over (n,p,q,k,c,r,s); index
+    functions p*sh+r and q*sw+s (Section "Examples", Subfigure 2)."""
+    N, Hh, W, C = len(x), len(x[0]), len(x[0][0]), len(x[0][0][0])
+    K, R, S = len(filt), len(filt[0]), len(filt[0][0])
+    sh, sw = stride
+    P, Q = (Hh - R) // sh + 1, (W - S) // sw + 1
+    iv = H.inp_view(
+        [
+            [lambda n, p, q, k, c, r, s: (n, p * sh + r, q * sw + s, c)],
+            [lambda n, p, q, k, c, r, s: (k, r, s, c)],
+        ]
+    )
+    ops = (
+        H.concat(0),
+        H.concat(1),
+        H.concat(2),
+        H.concat(3),
+        H.pointwise(4, _add),
+        H.pointwise(5, _add),
+        H.pointwise(6, _add),
+    )
+    h = H.md_hom(lambda t: t[0] * t[1], ops)
+    ov = H.out_view([[lambda n, p, q, k, c, r, s: (n, p, q, k)]])
+    (o,) = ov(h(iv([x, filt], [range(N), range(P), range(Q), range(K), range(C), range(R), range(S)])))
+    return [[[[o[(n, p, q, k)] for k in range(K)] for q in range(Q)] for p in range(P)] for n in range(N)]
+
+
+def max_idx(u, v):
+    """The user-defined combine operator on (score, index) pairs."""
+    (s1, b1), (s2, b2) = u, v
+    if s1 > s2:
+        return (s1, b1)
+    if s2 > s1:
+        return (s2, b2)
+    return (s1, min(b1, b2))
+
+
+def custom_reduce(A, B, w_agree, w_disagree):
+    """md_hom(wght, (++, pw(max_idx))) over (a,b) with an index-carrying scalar
+    function (USE_MDA_INDICES variant); output view writes the pair's two
+    components to two buffers at (a)."""
+    nA, nB, nF = len(A), len(B), len(w_agree)
+    iv = H.inp_view([[lambda a, b: (a,)], [lambda a, b: (b,)]])
+
+    def wght(t, point):
+        ra, rb = t
+        s = 0
+        for f in range(nF):
+            s += w_agree[f] if ra[f] == rb[f] else w_disagree[f]
+        return (s, point[1])
+
+    h = H.md_hom(wght, (H.concat(0), H.pointwise(1, max_idx)), use_mda_indices=True)
+    ov = H.out_view([[lambda a, b: (a,)], [lambda a, b: (a,)]])
+    sc, ix = ov(h(iv([A, B], [range(nA), range(nB)])))
+    return [sc[(a,)] for a in range(nA)], [ix[(a,)] for a in range(nA)]
