@@ -144,7 +144,8 @@ mdh_status mdh_part_offset(int64_t N, int32_t L, const int32_t* P, const int32_t
 /*
  * The library's tuned default configuration for (instance, sizes).
  * `sizes` holds the D index-space extents in the dimension order listed at
- * mdh_instance; for MDH_MCC two more entries follow: stride_h, stride_w.
+ * mdh_instance; for MDH_MCC two more entries follow: stride_h, stride_w; for
+ * MDH_CUSTOM_REDUCE one more entry follows: nF (read by mdh_tune only).
  * Host only; writes *out.
  */
 mdh_status mdh_default_params(mdh_instance inst, const int64_t* sizes, mdh_tile_params* out);

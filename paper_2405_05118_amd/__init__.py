@@ -1,0 +1,30 @@
+"""MI355X-native tiled evaluation of multi-dimensional homomorphisms (md_hom).
+
+The product is the C-ABI library ``libmdh.so`` (HIP kernels for gfx950, declared in
+``include/mdh.h``); this package is a thin binding with the same entry-point names
+(``mdh_matmul``, ``mdh_stencil``, ``mdh_mcc``, ``mdh_custom_reduce`` ...) that only
+marshals arguments.  PyTorch is used for device memory and streams, nothing else.
+There is no CPU fallback: if the library is missing, loading fails loudly.
+"""
+from .binding import (  # noqa: F401
+    MDH_CUSTOM_REDUCE,
+    MDH_MATMUL,
+    MDH_MCC,
+    MDH_STENCIL,
+    MdhError,
+    TileParams,
+    lib,
+    mdh_candidate,
+    mdh_custom_reduce,
+    mdh_default_params,
+    mdh_matmul,
+    mdh_mcc,
+    mdh_num_candidates,
+    mdh_part_offset,
+    mdh_stencil,
+    mdh_strerror,
+    mdh_tune,
+    mdh_validate_params,
+    mdh_version,
+    mdh_workspace_size,
+)

@@ -1,0 +1,249 @@
+"""ctypes binding of libmdh.so: argument marshalling only.
+
+Device buffers are torch tensors on ``cuda`` (ROCm); their ``data_ptr()`` and the
+current torch stream's handle are what crosses the C ABI.  Every step of the
+computation runs inside the library's kernels.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmdh.so")
+
+MDH_MATMUL, MDH_STENCIL, MDH_MCC, MDH_CUSTOM_REDUCE = 0, 1, 2, 3
+MDH_NUM_LAYERS, MDH_MAX_D = 6, 7
+L_HBM, L_LDS, L_VGPR, L_WG, L_WAVE, L_LANE = range(6)
+
+EXPORTS = (
+    "mdh_strerror", "mdh_version", "mdh_part_offset", "mdh_default_params", "mdh_validate_params",
+    "mdh_workspace_size", "mdh_matmul", "mdh_stencil", "mdh_mcc", "mdh_custom_reduce", "mdh_tune",
+    "mdh_num_candidates", "mdh_candidate",
+)
+
+
+class TileParams(ctypes.Structure):
+    """Mirror of ``mdh_tile_params`` (include/mdh.h)."""
+
+    _fields_ = [
+        ("D", ctypes.c_int32),
+        ("prt", (ctypes.c_int32 * MDH_MAX_D) * MDH_NUM_LAYERS),
+        ("blk", ctypes.c_int32 * MDH_MAX_D),
+        ("order", ctypes.c_uint8 * (MDH_NUM_LAYERS * MDH_MAX_D)),
+        ("strided", ctypes.c_uint8),
+        ("lane_fast_dim", ctypes.c_uint8),
+        ("ragged", ctypes.c_uint8),
+        ("in_region", ctypes.c_uint8 * 4),
+        ("out_region", ctypes.c_uint8),
+        ("in_transposed", ctypes.c_uint8 * 4),
+        ("out_transposed", ctypes.c_uint8),
+        ("reserved", ctypes.c_uint8 * 3),
+    ]
+
+    def copy(self) -> "TileParams":
+        c = TileParams()
+        ctypes.memmove(ctypes.byref(c), ctypes.byref(self), ctypes.sizeof(TileParams))
+        return c
+
+    def extent(self, d: int) -> int:
+        e = self.blk[d]
+        for l in range(MDH_NUM_LAYERS):
+            e *= self.prt[l][d]
+        return e
+
+    def table(self):
+        return [[self.prt[l][d] for d in range(self.D)] for l in range(MDH_NUM_LAYERS)]
+
+
+class MdhError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, mdh_strerror(status), status))
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libmdh.so (built in-tree by ``build.py``).  No fallback: raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libmdh.so is not built: run `python -m paper_2405_05118_amd.build` "
+                "(or __graft_entry__.build()); there is no CPU fallback"
+            )
+        L = ctypes.CDLL(LIB_PATH)
+        i64, i32, vp, sz, f32 = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float
+        pp = ctypes.POINTER(TileParams)
+        p64 = ctypes.POINTER(i64)
+        L.mdh_strerror.restype = ctypes.c_char_p
+        L.mdh_strerror.argtypes = [ctypes.c_int]
+        L.mdh_version.restype = ctypes.c_char_p
+        L.mdh_part_offset.argtypes = [i64, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), p64, p64]
+        L.mdh_default_params.argtypes = [ctypes.c_int, p64, pp]
+        L.mdh_validate_params.argtypes = [ctypes.c_int, p64, pp]
+        L.mdh_workspace_size.restype = sz
+        L.mdh_workspace_size.argtypes = [ctypes.c_int, p64, pp]
+        L.mdh_matmul.argtypes = [i64, i64, i64, vp, vp, vp, pp, vp, sz, vp]
+        L.mdh_stencil.argtypes = [i64, i64, i64, vp, vp, f32, f32, pp, vp]
+        L.mdh_mcc.argtypes = [i64] * 9 + [vp, vp, vp, pp, vp, sz, vp]
+        L.mdh_custom_reduce.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, pp, vp, sz, vp]
+        L.mdh_tune.argtypes = [ctypes.c_int, p64, ctypes.POINTER(vp), ctypes.POINTER(f32), vp, sz, vp, i32, pp,
+                               ctypes.POINTER(f32)]
+        L.mdh_num_candidates.restype = i32
+        L.mdh_num_candidates.argtypes = [ctypes.c_int, p64]
+        L.mdh_candidate.argtypes = [ctypes.c_int, p64, i32, pp]
+        _lib = L
+    return _lib
+
+
+def _sizes(sizes: Sequence[int]):
+    return (ctypes.c_int64 * len(sizes))(*[int(s) for s in sizes])
+
+
+def _pref(p: Optional[TileParams]):
+    return ctypes.byref(p) if p is not None else None
+
+
+def _check(st: int, where: str):
+    if st != 0:
+        raise MdhError(st, where)
+
+
+def _stream() -> int:
+    import torch
+
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, name):
+    import torch
+
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous %s tensor on the GPU" % (name, dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _ws(ws):
+    if ws is None:
+        return None, 0
+    return ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size()
+
+
+# ------------------------------------------------------------------ host-only helpers
+
+
+def mdh_strerror(status: int) -> str:
+    return lib().mdh_strerror(int(status)).decode()
+
+
+def mdh_version() -> str:
+    return lib().mdh_version().decode()
+
+
+def mdh_part_offset(N: int, P: Sequence[int], p: Sequence[int]):
+    L = len(P)
+    os_, ps = ctypes.c_int64(), ctypes.c_int64()
+    st = lib().mdh_part_offset(int(N), L, (ctypes.c_int32 * L)(*P), (ctypes.c_int32 * L)(*p), ctypes.byref(os_), ctypes.byref(ps))
+    _check(st, "mdh_part_offset")
+    return os_.value, ps.value
+
+
+def mdh_default_params(inst: int, sizes: Sequence[int]) -> TileParams:
+    p = TileParams()
+    _check(lib().mdh_default_params(inst, _sizes(sizes), ctypes.byref(p)), "mdh_default_params")
+    return p
+
+
+def mdh_validate_params(inst: int, sizes: Sequence[int], p: TileParams) -> int:
+    return int(lib().mdh_validate_params(inst, _sizes(sizes), ctypes.byref(p)))
+
+
+def mdh_workspace_size(inst: int, sizes: Sequence[int], p: Optional[TileParams] = None) -> int:
+    return int(lib().mdh_workspace_size(inst, _sizes(sizes), _pref(p)))
+
+
+def mdh_num_candidates(inst: int, sizes: Sequence[int]) -> int:
+    return int(lib().mdh_num_candidates(inst, _sizes(sizes)))
+
+
+def mdh_candidate(inst: int, sizes: Sequence[int], idx: int) -> TileParams:
+    p = TileParams()
+    _check(lib().mdh_candidate(inst, _sizes(sizes), idx, ctypes.byref(p)), "mdh_candidate")
+    return p
+
+
+# ------------------------------------------------------------------ device entry points
+
+
+def mdh_matmul(A, B, C, params: Optional[TileParams] = None, workspace=None):
+    import torch
+
+    M, K = A.shape
+    K2, N = B.shape
+    assert K == K2 and tuple(C.shape) == (M, N)
+    wp, wb = _ws(workspace)
+    st = lib().mdh_matmul(M, N, K, _dev(A, torch.float32, "A"), _dev(B, torch.float32, "B"), _dev(C, torch.float32, "C"),
+                          _pref(params), wp, wb, ctypes.c_void_p(_stream()))
+    _check(st, "mdh_matmul")
+    return C
+
+
+def mdh_stencil(x, out, c0: float, c1: float, params: Optional[TileParams] = None):
+    import torch
+
+    nx, ny, nz = (s - 2 for s in x.shape)
+    assert tuple(out.shape) == (nx, ny, nz)
+    st = lib().mdh_stencil(nx, ny, nz, _dev(x, torch.float32, "in"), _dev(out, torch.float32, "out"), float(c0), float(c1),
+                           _pref(params), ctypes.c_void_p(_stream()))
+    _check(st, "mdh_stencil")
+    return out
+
+
+def mdh_mcc(x, filt, out, stride=(1, 1), params: Optional[TileParams] = None, workspace=None):
+    import torch
+
+    N, H, W, C = x.shape
+    K, R, S, C2 = filt.shape
+    assert C == C2
+    sh, sw = stride
+    P, Q = (H - R) // sh + 1, (W - S) // sw + 1
+    assert tuple(out.shape) == (N, P, Q, K)
+    wp, wb = _ws(workspace)
+    st = lib().mdh_mcc(N, H, W, C, K, R, S, sh, sw, _dev(x, torch.float32, "in"), _dev(filt, torch.float32, "filt"),
+                       _dev(out, torch.float32, "out"), _pref(params), wp, wb, ctypes.c_void_p(_stream()))
+    _check(st, "mdh_mcc")
+    return out
+
+
+def mdh_custom_reduce(A, B, w_agree, w_disagree, out_score, out_index, params: Optional[TileParams] = None,
+                      workspace=None):
+    import torch
+
+    nA, nF = A.shape
+    nB, nF2 = B.shape
+    assert nF == nF2 == w_agree.numel() == w_disagree.numel()
+    assert out_score.numel() == nA and out_index.numel() == nA
+    i32 = torch.int32
+    wp, wb = _ws(workspace)
+    st = lib().mdh_custom_reduce(nA, nB, nF, _dev(A, i32, "A"), _dev(B, i32, "B"), _dev(w_agree, i32, "w_agree"),
+                                 _dev(w_disagree, i32, "w_disagree"), _dev(out_score, i32, "out_score"),
+                                 _dev(out_index, i32, "out_index"), _pref(params), wp, wb, ctypes.c_void_p(_stream()))
+    _check(st, "mdh_custom_reduce")
+    return out_score, out_index
+
+
+def mdh_tune(inst: int, sizes: Sequence[int], buffers, scalars=None, workspace=None, reps: int = 3):
+    """Time every candidate configuration on the given device buffers; returns (best params, ms)."""
+    n = len(buffers)
+    bufs = (ctypes.c_void_p * n)(*[ctypes.c_void_p(b.data_ptr()) for b in buffers])
+    sc = (ctypes.c_float * 2)(*scalars) if scalars is not None else None
+    wp, wb = _ws(workspace)
+    best, ms = TileParams(), ctypes.c_float()
+    st = lib().mdh_tune(inst, _sizes(sizes), bufs, sc, wp, wb, ctypes.c_void_p(_stream()), reps, ctypes.byref(best),
+                        ctypes.byref(ms))
+    _check(st, "mdh_tune")
+    return best, ms.value

@@ -1,0 +1,198 @@
+// Custom-combine instance md_hom(wght, (++, max_idx)) over (a,b) for gfx950
+// (record-linkage style; paper: Section "Examples", Subfigure 5).
+//
+//   wght(a,b) = ( sum_f (A[a,f]==B[b,f] ? w_agree[f] : w_disagree[f]) , b )       index-carrying f
+//   (s1,b1) max_idx (s2,b2) = larger score wins; equal scores: smaller index wins  user-defined op
+//
+// The work is nA*nB scalar-function evaluations on a few MiB of data: it is bound by
+// integer vector-ALU issue, not by memory.  De-composition, dims (a,b):
+//   workgroup layer : nA/(WA*64*RA) x S        -- S > 1 splits the reduction dimension b
+//   wavefront layer : WA x WB                  -- WB wavefronts of a workgroup split b again
+//   lane layer      : 64 x 1                   -- the ++ dimension a runs over the lanes
+//   VGPR layer      : RA records of A per lane, held in registers for the whole kernel
+//   HBM layer       : nB/(S*WB) records of B, sequential; a record of B is the same for all
+//                     lanes of a wavefront, so it is fetched with scalar loads into SGPRs
+// Re-composition of b with max_idx: in registers over a lane's sequential parts; across the
+// WB wavefronts in LDS; across the S workgroups through a device-memory workspace and a
+// second kernel (workgroup results combine in device memory only).
+#include <limits.h>
+
+#include "mdh_internal.h"
+
+namespace mdh {
+namespace {
+
+struct Best {
+  int s, i;
+};
+
+__device__ __forceinline__ void max_idx(Best& x, int s, int i) {
+  const bool take = (s > x.s) || (s == x.s && i < x.i);
+  x.s = take ? s : x.s;
+  x.i = take ? i : x.i;
+}
+
+// NF: number of fields the unrolled loops cover; if EXACT, nF == NF and a record of B is NF
+// consecutive ints; otherwise nF < NF, the weights of the padding fields are 0 and their
+// loads are clamped to the last real field (whatever they compare, they add 0).
+template <int NF, bool EXACT, int RA, int WB, int WA>
+__global__ __launch_bounds__(WA* WB * 64) void prl_kernel(
+    const int* __restrict__ A, const int* __restrict__ B, const int* __restrict__ wp,
+    const int* __restrict__ wm, int* __restrict__ out_s, int* __restrict__ out_i,
+    int* __restrict__ ws, int nA, int nB, int nF, int S, int bchunk) {
+  __shared__ int red_s[WB > 1 ? (WB - 1) * WA * RA * 64 : 1];
+  __shared__ int red_i[WB > 1 ? (WB - 1) * WA * RA * 64 : 1];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wa = wave % WA, wb = wave / WA;
+  const int nWGa = (nA + WA * 64 * RA - 1) / (WA * 64 * RA);
+  const int ga = blockIdx.x % nWGa;  // workgroup part of a
+  const int gs = blockIdx.x / nWGa;  // workgroup part of b
+  const int abase = (ga * WA + wa) * 64 * RA;
+
+  // weights: score = sum_f w_disagree[f] + sum_f [agree_f] * (w_agree[f] - w_disagree[f]),
+  // evaluated in wrap-around unsigned arithmetic (exact whenever the true sums fit int32)
+  unsigned dw[NF];
+  unsigned base = 0;
+#pragma unroll
+  for (int f = 0; f < NF; ++f) {
+    const bool real = EXACT || f < nF;
+    const unsigned p = real ? (unsigned)wp[f] : 0u, m = real ? (unsigned)wm[f] : 0u;
+    dw[f] = p - m;
+    base += m;
+  }
+
+  // the lane's records of A (record a = abase + ra*64 + lane)
+  int ar[RA][NF];
+#pragma unroll
+  for (int ra = 0; ra < RA; ++ra) {
+    const int a = min(abase + ra * 64 + lane, nA - 1);
+#pragma unroll
+    for (int f = 0; f < NF; ++f) ar[ra][f] = A[(int64_t)a * nF + (EXACT ? f : min(f, nF - 1))];
+  }
+
+  Best best[RA];
+#pragma unroll
+  for (int ra = 0; ra < RA; ++ra) best[ra] = Best{INT_MIN, INT_MAX};
+
+  const int part = gs * WB + wb;
+  const int b0 = min((int64_t)part * bchunk, (int64_t)nB);
+  const int b1 = min((int64_t)b0 + bchunk, (int64_t)nB);
+  for (int b = b0; b < b1; ++b) {
+    int br[NF];  // wavefront-uniform: scalar loads
+    const int* rb = B + (int64_t)b * nF;
+#pragma unroll
+    for (int f = 0; f < NF; ++f) br[f] = rb[EXACT ? f : min(f, nF - 1)];
+#pragma unroll
+    for (int ra = 0; ra < RA; ++ra) {
+      unsigned sc = base;
+#pragma unroll
+      for (int f = 0; f < NF; ++f) sc += (ar[ra][f] == br[f]) ? dw[f] : 0u;
+      // b ascends, so a strict improvement keeps the smallest index among equal scores
+      const int s = (int)sc;
+      const bool take = s > best[ra].s;
+      best[ra].s = take ? s : best[ra].s;
+      best[ra].i = take ? b : best[ra].i;
+    }
+  }
+
+  // wavefront layer -> workgroup: combine the WB partial results in LDS
+  if (WB > 1) {
+    if (wb > 0) {
+#pragma unroll
+      for (int ra = 0; ra < RA; ++ra) {
+        const int o = (((wb - 1) * WA + wa) * RA + ra) * 64 + lane;
+        red_s[o] = best[ra].s;
+        red_i[o] = best[ra].i;
+      }
+    }
+    __syncthreads();
+    if (wb > 0) return;
+#pragma unroll
+    for (int w = 1; w < WB; ++w)
+#pragma unroll
+      for (int ra = 0; ra < RA; ++ra) {
+        const int o = (((w - 1) * WA + wa) * RA + ra) * 64 + lane;
+        max_idx(best[ra], red_s[o], red_i[o]);
+      }
+  }
+
+  // output view (a,0) -> out_score[a], out_index[a]; or the workspace of part gs
+#pragma unroll
+  for (int ra = 0; ra < RA; ++ra) {
+    const int a = abase + ra * 64 + lane;
+    if (a < nA) {
+      if (S > 1) {
+        ws[(int64_t)gs * nA + a] = best[ra].s;
+        ws[(int64_t)(S + gs) * nA + a] = best[ra].i;
+      } else {
+        out_s[a] = best[ra].s;
+        out_i[a] = best[ra].i;
+      }
+    }
+  }
+}
+
+// Second pass: fold the S workgroup-layer partial results with max_idx.
+__global__ __launch_bounds__(256) void combine_maxidx_kernel(const int* __restrict__ ws,
+                                                             int* __restrict__ out_s,
+                                                             int* __restrict__ out_i, int nA, int S) {
+  const int a = blockIdx.x * 256 + threadIdx.x;
+  if (a >= nA) return;
+  Best x{ws[a], ws[(int64_t)S * nA + a]};
+  for (int s = 1; s < S; ++s) max_idx(x, ws[(int64_t)s * nA + a], ws[(int64_t)(S + s) * nA + a]);
+  out_s[a] = x.s;
+  out_i[a] = x.i;
+}
+
+template <int NF, bool EXACT, int RA, int WB, int WA>
+mdh_status launch_t(const PrlPlan& pl, int64_t nA, int64_t nB, int nF, const int32_t* A,
+                    const int32_t* B, const int32_t* wp, const int32_t* wm, int32_t* score,
+                    int32_t* index, void* ws, hipStream_t st) {
+  const int64_t nWGa = cdiv(nA, (int64_t)WA * 64 * RA);
+  const int64_t nblocks = nWGa * pl.S;
+  if (nblocks > 0x7fffffff) return MDH_ERR_SIZE;
+  const int64_t bchunk = cdiv(nB, (int64_t)pl.S * WB);
+  clear_stale_error();
+  hipLaunchKernelGGL((prl_kernel<NF, EXACT, RA, WB, WA>), dim3((unsigned)nblocks), dim3(WA * WB * 64),
+                     0, st, A, B, wp, wm, score, index, (int*)ws, (int)nA, (int)nB, nF, pl.S,
+                     (int)bchunk);
+  mdh_status r = launch_status();
+  if (r != MDH_OK || pl.S <= 1) return r;
+  clear_stale_error();
+  hipLaunchKernelGGL(combine_maxidx_kernel, dim3((unsigned)cdiv(nA, 256)), dim3(256), 0, st,
+                     (const int*)ws, score, index, (int)nA, pl.S);
+  return launch_status();
+}
+
+template <int RA, int WB, int WA>
+mdh_status launch_nf(const PrlPlan& pl, int64_t nA, int64_t nB, int nF, const int32_t* A,
+                     const int32_t* B, const int32_t* wp, const int32_t* wm, int32_t* score,
+                     int32_t* index, void* ws, hipStream_t st) {
+  if (nF == 8) return launch_t<8, true, RA, WB, WA>(pl, nA, nB, nF, A, B, wp, wm, score, index, ws, st);
+  if (nF <= 4) return launch_t<4, false, RA, WB, WA>(pl, nA, nB, nF, A, B, wp, wm, score, index, ws, st);
+  if (nF < 8) return launch_t<8, false, RA, WB, WA>(pl, nA, nB, nF, A, B, wp, wm, score, index, ws, st);
+  return launch_t<16, false, RA, WB, WA>(pl, nA, nB, nF, A, B, wp, wm, score, index, ws, st);
+}
+
+}  // namespace
+
+mdh_status launch_prl(const PrlPlan& pl, int64_t nA, int64_t nB, int nF, const int32_t* A,
+                      const int32_t* B, const int32_t* wp, const int32_t* wm, int32_t* score,
+                      int32_t* index, void* ws, hipStream_t st) {
+#define MDH_PRL(ra, wb, wa) \
+  if (pl.RA == ra && pl.WB == wb && pl.WA == wa) return launch_nf<ra, wb, wa>(pl, nA, nB, nF, A, B, wp, wm, score, index, ws, st);
+  MDH_PRL(2, 4, 1)
+  MDH_PRL(4, 4, 1)
+  MDH_PRL(1, 4, 1)
+  MDH_PRL(2, 2, 2)
+  MDH_PRL(4, 2, 2)
+  MDH_PRL(2, 1, 4)
+  MDH_PRL(4, 1, 4)
+  MDH_PRL(2, 8, 1)
+  MDH_PRL(4, 8, 1)
+#undef MDH_PRL
+  return MDH_ERR_UNSUPPORTED;
+}
+
+}  // namespace mdh

@@ -1,0 +1,82 @@
+// Internal declarations shared by the host planner and the kernel launchers of libmdh.
+// Nothing here is part of the C ABI (see include/mdh.h for that).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "mdh.h"
+
+namespace mdh {
+
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- launch descriptors the planner derives from a tile-parameter configuration ----
+
+// Jacobi-3D: a workgroup owns TJ = TY*RJ rows (j) x KT = LK*4 columns (k) and marches
+// over SI consecutive planes (i).  Lanes run along k (4 outputs each), TY lane-rows
+// along j, RJ rows per lane in registers.
+struct StencilPlan {
+  int RJ, TY, LK;  // kernel instantiation
+  int SI;          // planes per workgroup (sequential HBM-layer parts of dimension i)
+  int ragged;
+};
+
+// MatMul / MCC contraction core: workgroup tile BM x BN, K-step BK through LDS,
+// WM x WN per wavefront out of 32x32x2 FP32 MFMA blocks, split factor S over k.
+struct GemmPlan {
+  int BM, BN, BK, WM, WN;
+  int S;  // workgroup-layer parts of the reduction dimension
+  int ragged;
+};
+
+// MCC: workgroup tile TP x TQ output pixels x BN output channels, CK channels per LDS stage.
+struct MccPlan {
+  int TP, TQ, BN, CK, WM, WN;
+  int ragged;
+};
+
+// Custom reduce: RA records of A per lane, WB wavefronts of a workgroup split B,
+// S workgroup-layer parts of B.
+struct PrlPlan {
+  int RA, WB, WA;  // WA wavefronts along a
+  int S;
+  int ragged;
+};
+
+mdh_status plan_stencil(const int64_t* sizes, const mdh_tile_params* p, StencilPlan* out);
+mdh_status plan_matmul(const int64_t* sizes, const mdh_tile_params* p, GemmPlan* out);
+mdh_status plan_mcc(const int64_t* sizes, const mdh_tile_params* p, MccPlan* out);
+mdh_status plan_prl(const int64_t* sizes, const mdh_tile_params* p, PrlPlan* out);
+
+// Fill a full parameter table (prt/blk/order/regions) from a launch descriptor.
+void params_from_plan(const int64_t* sizes, const StencilPlan& pl, mdh_tile_params* out);
+void params_from_plan(const int64_t* sizes, const GemmPlan& pl, mdh_tile_params* out);
+void params_from_plan(const int64_t* sizes, const MccPlan& pl, mdh_tile_params* out);
+void params_from_plan(const int64_t* sizes, const PrlPlan& pl, mdh_tile_params* out);
+
+// Candidate menus (defaults are candidate 0).
+int stencil_candidates(const int64_t* sizes, StencilPlan* out, int cap);
+int matmul_candidates(const int64_t* sizes, GemmPlan* out, int cap);
+int mcc_candidates(const int64_t* sizes, MccPlan* out, int cap);
+int prl_candidates(const int64_t* sizes, PrlPlan* out, int cap);
+
+// ---- launchers (defined in the .hip files) ----
+mdh_status launch_stencil(const StencilPlan& pl, int64_t nx, int64_t ny, int64_t nz, const float* in,
+                          float* out, float c0, float c1, hipStream_t st);
+mdh_status launch_matmul(const GemmPlan& pl, int64_t M, int64_t N, int64_t K, const float* A,
+                         const float* B, float* C, void* ws, hipStream_t st);
+mdh_status launch_mcc(const MccPlan& pl, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
+                      int64_t R, int64_t S, int64_t sh, int64_t sw, const float* in,
+                      const float* filt, float* out, hipStream_t st);
+mdh_status launch_prl(const PrlPlan& pl, int64_t nA, int64_t nB, int nF, const int32_t* A,
+                      const int32_t* B, const int32_t* wp, const int32_t* wm, int32_t* score,
+                      int32_t* index, void* ws, hipStream_t st);
+
+// The runtime's "last error" is sticky per thread and other users of the runtime in the same
+// process leave harmless codes there (an event query that is not ready yet, for instance):
+// clear it before a launch so that the status read after the launch is that launch's own.
+inline void clear_stale_error() { (void)hipGetLastError(); }
+inline mdh_status launch_status() {
+  return hipGetLastError() == hipSuccess ? MDH_OK : MDH_ERR_LAUNCH;
+}
+
+}  // namespace mdh

@@ -1,0 +1,256 @@
+// MatMul instance of md_hom(*, (++,++,+)) for gfx950: C[i,j] = sum_k A[i,k]*B[k,j].
+//
+// De-composition (tuning parameter 0 / D2 of the paper's table), dims (i,j,k):
+//   workgroup layer : (M/BM) x (N/BN) x S     -- S > 1 splits the reduction dimension
+//   HBM layer       : K/(S*BK) sequential k-tiles, each staged in LDS (double buffered)
+//   wavefront layer : (BM/WM) x (BN/WN)
+//   LDS layer       : BK/2 sequential k-steps inside the staged tile
+//   VGPR layer      : (WM/32) x (WN/32) accumulator blocks per wavefront
+//   block           : 32 x 32 x 2, one v_mfma_f32_32x32x2_f32 (true fp32 multiply-add)
+// Re-composition of the + dimension: inside the MFMA accumulators (register region) over
+// the sequential parts; if S > 1 the S workgroup results are written to a device-memory
+// workspace and a second kernel adds them in ascending part order (workgroup results can
+// only be combined in device memory; Appendix "Constraints of Programming Models").
+#include "mdh_internal.h"
+
+namespace mdh {
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+typedef float f16 __attribute__((ext_vector_type(16)));
+
+template <int BM, int BN, int BK, int WM, int WN>
+struct GemmCfg {
+  static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
+  static constexpr int NT = WAVES_M * WAVES_N * 64;
+  static constexpr int PA = BK + 4;  // floats per LDS row of the A tile [BM][PA] (k contiguous)
+  static constexpr int PB = BN + 4;  // floats per LDS row of the B tile [BK][PB] (n contiguous)
+  static constexpr int A_STAGE = BM * PA, B_STAGE = BK * PB;
+  static constexpr int STAGE = A_STAGE + B_STAGE;
+  static constexpr int LDS_BYTES = 2 * STAGE * 4;
+  static constexpr int A_F4 = BM * BK / 4, B_F4 = BK * BN / 4;  // float4 per tile
+  static constexpr int A_LD = (A_F4 + NT - 1) / NT, B_LD = (B_F4 + NT - 1) / NT;
+  static constexpr int MI = WM / 32, NI = WN / 32;
+};
+
+template <int BM, int BN, int BK, int WM, int WN, bool GUARD>
+__device__ __forceinline__ void gemm_tile(const float* __restrict__ A, const float* __restrict__ B,
+                                          float* __restrict__ Cout, int M, int N, int K, int m0,
+                                          int n0, int kbeg, int kend, float* lds) {
+  using C = GemmCfg<BM, BN, BK, WM, WN>;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+  const int l32 = lane & 31, lh = lane >> 5;
+
+  f4 ga[C::A_LD], gb[C::B_LD];
+
+  auto load_global = [&](int k0) {
+#pragma unroll
+    for (int x = 0; x < C::A_LD; ++x) {
+      const int f = tid + x * C::NT;
+      const int row = f / (BK / 4), c4 = f % (BK / 4);
+      f4 v = {0.f, 0.f, 0.f, 0.f};
+      if (C::A_F4 % C::NT == 0 || f < C::A_F4) {
+        const float* p = A + (int64_t)(m0 + row) * K + (k0 + c4 * 4);
+        if (!GUARD) {
+          v = *(const f4u*)p;
+        } else if (m0 + row < M) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (k0 + c4 * 4 + e < kend) v[e] = p[e];
+        }
+      }
+      ga[x] = v;
+    }
+#pragma unroll
+    for (int x = 0; x < C::B_LD; ++x) {
+      const int f = tid + x * C::NT;
+      const int row = f / (BN / 4), c4 = f % (BN / 4);
+      f4 v = {0.f, 0.f, 0.f, 0.f};
+      if (C::B_F4 % C::NT == 0 || f < C::B_F4) {
+        const float* p = B + (int64_t)(k0 + row) * N + (n0 + c4 * 4);
+        if (!GUARD) {
+          v = *(const f4u*)p;
+        } else if (k0 + row < kend) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (n0 + c4 * 4 + e < N) v[e] = p[e];
+        }
+      }
+      gb[x] = v;
+    }
+  };
+  auto store_lds = [&](float* st) {
+#pragma unroll
+    for (int x = 0; x < C::A_LD; ++x) {
+      const int f = tid + x * C::NT;
+      const int row = f / (BK / 4), c4 = f % (BK / 4);
+      if (C::A_F4 % C::NT == 0 || f < C::A_F4) *(f4*)(st + row * C::PA + c4 * 4) = ga[x];
+    }
+#pragma unroll
+    for (int x = 0; x < C::B_LD; ++x) {
+      const int f = tid + x * C::NT;
+      const int row = f / (BN / 4), c4 = f % (BN / 4);
+      if (C::B_F4 % C::NT == 0 || f < C::B_F4) *(f4*)(st + C::A_STAGE + row * C::PB + c4 * 4) = gb[x];
+    }
+  };
+
+  f16 acc[C::MI][C::NI];
+#pragma unroll
+  for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+  // One MFMA consumes k = {kk, kk+4} (lanes 0-31 supply the first, lanes 32-63 the second
+  // column of A / row of B), so that a lane's four consecutive k of A come from one 16-byte
+  // LDS read; the order in which the k are added is free (+ is the combine operator of k).
+  auto compute = [&](const float* st) {
+    const float* as = st + (wm * WM + l32) * C::PA + lh * 4;
+    const float* bs = st + C::A_STAGE + (lh * 4) * C::PB + wn * WN + l32;
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 8) {
+      f4 af[C::MI];
+      float bf[C::NI][4];
+#pragma unroll
+      for (int mi = 0; mi < C::MI; ++mi) af[mi] = *(const f4*)(as + mi * 32 * C::PA + kk);
+#pragma unroll
+      for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) bf[ni][t] = bs[(kk + t) * C::PB + ni * 32];
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < C::NI; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi][t], bf[ni][t], acc[mi][ni], 0, 0, 0);
+    }
+  };
+
+  const int nk = (kend - kbeg + BK - 1) / BK;
+  load_global(kbeg);
+  store_lds(lds);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    float* cur = lds + (kt & 1) * C::STAGE;
+    float* nxt = lds + ((kt + 1) & 1) * C::STAGE;
+    if (kt + 1 < nk) load_global(kbeg + (kt + 1) * BK);
+    compute(cur);
+    if (kt + 1 < nk) store_lds(nxt);
+    __syncthreads();
+  }
+
+  // output view (i,j,0) -> C[i,j]: accumulator register r of lane l holds
+  // row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32 block
+#pragma unroll
+  for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < C::NI; ++ni) {
+      const int col = n0 + wn * WN + ni * 32 + l32;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * WM + mi * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+        if (!GUARD || (row < M && col < N)) Cout[(int64_t)row * N + col] = acc[mi][ni][r];
+      }
+    }
+}
+
+template <int BM, int BN, int BK, int WM, int WN>
+__global__ __launch_bounds__((GemmCfg<BM, BN, BK, WM, WN>::NT)) void matmul_kernel(
+    const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C,
+    float* __restrict__ ws, int M, int N, int K, int tiles_m, int tiles_n, int S, int kchunk) {
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  // XCD-aware tile order: workgroup ids are dealt round-robin to the 8 XCDs; hand each XCD a
+  // contiguous run of tiles, walked in bands of 8 tile-rows so that the tiles resident on one
+  // XCD at a time share few panels of A and B in that XCD's L2.
+  int b = blockIdx.x;
+  const int nb = gridDim.x;
+  if ((nb & 7) == 0) b = (b & 7) * (nb >> 3) + (b >> 3);
+  const int tiles = tiles_m * tiles_n;
+  const int s = b / tiles;
+  int t = b % tiles;
+  constexpr int GM = 8;
+  const int band = t / (GM * tiles_n);
+  const int band_rows = min(GM, tiles_m - band * GM);
+  const int in_band = t - band * GM * tiles_n;
+  const int tm = band * GM + in_band % band_rows;
+  const int tn = in_band / band_rows;
+
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int kbeg = s * kchunk;
+  const int kend = min(K, kbeg + kchunk);
+  float* out = S > 1 ? ws + (int64_t)s * M * N : C;
+  const bool full = (m0 + BM <= M) && (n0 + BN <= N) && kend > kbeg && ((kend - kbeg) % BK == 0);
+  if (full)
+    gemm_tile<BM, BN, BK, WM, WN, false>(A, B, out, M, N, K, m0, n0, kbeg, kend, lds);
+  else
+    gemm_tile<BM, BN, BK, WM, WN, true>(A, B, out, M, N, K, m0, n0, kbeg, kend, lds);
+}
+
+// Second pass of the re-composition: C = part_0 + part_1 + ... + part_{S-1}, in that order.
+__global__ __launch_bounds__(256) void combine_sum_kernel(const float* __restrict__ ws,
+                                                          float* __restrict__ C, int64_t n, int S) {
+  const int64_t i4 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i4 + 3 < n) {
+    f4 a = *(const f4u*)(ws + i4);
+    for (int s = 1; s < S; ++s) a += *(const f4u*)(ws + (int64_t)s * n + i4);
+    *(f4u*)(C + i4) = a;
+  } else {
+    for (int64_t i = i4; i < n; ++i) {
+      float a = ws[i];
+      for (int s = 1; s < S; ++s) a += ws[(int64_t)s * n + i];
+      C[i] = a;
+    }
+  }
+}
+
+template <int BM, int BN, int BK, int WM, int WN>
+mdh_status launch_t(const GemmPlan& pl, int64_t M, int64_t N, int64_t K, const float* A,
+                    const float* B, float* C, void* ws, hipStream_t st) {
+  using Cfg = GemmCfg<BM, BN, BK, WM, WN>;
+  static bool attr_done = false;
+  auto kern = matmul_kernel<BM, BN, BK, WM, WN>;
+  if (!attr_done) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            Cfg::LDS_BYTES) != hipSuccess)
+      return MDH_ERR_LAUNCH;
+    attr_done = true;
+  }
+  const int64_t tm = cdiv(M, BM), tn = cdiv(N, BN);
+  const int64_t kchunk = cdiv(cdiv(K, pl.S), BK) * BK;
+  const int64_t nblocks = tm * tn * pl.S;
+  if (nblocks > 0x7fffffff) return MDH_ERR_SIZE;
+  clear_stale_error();
+  hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, st, A, B, C,
+                     (float*)ws, (int)M, (int)N, (int)K, (int)tm, (int)tn, pl.S, (int)kchunk);
+  mdh_status r = launch_status();
+  if (r != MDH_OK || pl.S <= 1) return r;
+  const int64_t n = M * N;
+  clear_stale_error();
+  hipLaunchKernelGGL(combine_sum_kernel, dim3((unsigned)cdiv(n, 1024)), dim3(256), 0, st,
+                     (const float*)ws, C, n, pl.S);
+  return launch_status();
+}
+
+}  // namespace
+
+mdh_status launch_matmul(const GemmPlan& pl, int64_t M, int64_t N, int64_t K, const float* A,
+                         const float* B, float* C, void* ws, hipStream_t st) {
+#define MDH_MM(bm, bn, bk, wm, wn)                                                   \
+  if (pl.BM == bm && pl.BN == bn && pl.BK == bk && pl.WM == wm && pl.WN == wn)       \
+    return launch_t<bm, bn, bk, wm, wn>(pl, M, N, K, A, B, C, ws, st);
+  MDH_MM(128, 128, 16, 64, 64)
+  MDH_MM(256, 128, 16, 128, 64)
+  MDH_MM(128, 64, 16, 64, 32)
+  MDH_MM(64, 64, 16, 32, 32)
+  MDH_MM(128, 128, 32, 64, 64)
+  MDH_MM(256, 128, 32, 128, 64)
+#undef MDH_MM
+  return MDH_ERR_UNSUPPORTED;
+}
+
+}  // namespace mdh

@@ -1,0 +1,686 @@
+// Host-side de-composition planner: turns a configuration of the paper's tuning
+// parameters (Table "Tuning parameters of our low-level expressions") into a launch
+// descriptor of one of the library's kernel instantiations and back, and checks the
+// algorithmic constraint of parameter 0 (prod_l #PRT(l,d) = N_d) and the model
+// constraints (lanes per workgroup, LDS budget; Appendix "Constraints of Programming
+// Models").  Integer arithmetic only; no GPU call in this file.
+#include <string.h>
+
+#include "mdh_internal.h"
+
+namespace mdh {
+
+namespace {
+
+constexpr int kMaxLanesPerWG = 1024;        // model constraint 0 of the CUDA/OpenCL tables
+constexpr int64_t kLdsBytesPerWG = 160 * 1024;  // gfx950 LDS per workgroup
+
+void clear_params(mdh_tile_params* p, int D) {
+  memset(p, 0, sizeof(*p));
+  p->D = D;
+  for (int l = 0; l < MDH_NUM_LAYERS; ++l)
+    for (int d = 0; d < MDH_MAX_D; ++d) p->prt[l][d] = 1;
+  for (int d = 0; d < MDH_MAX_D; ++d) p->blk[d] = 1;
+}
+
+// Fused loop order D1=S1=R1: workgroup parts outermost (one workgroup = one iteration of
+// them), then the sequential HBM-layer parts, then wavefront and lane parts (parallel
+// inside the workgroup), then the LDS- and VGPR-layer sequential parts; within a layer,
+// dimensions in the given order.
+void set_order(mdh_tile_params* p, const int* dim_order) {
+  static const int layer_order[MDH_NUM_LAYERS] = {MDH_L_WG,   MDH_L_HBM, MDH_L_WAVE,
+                                                  MDH_L_LANE, MDH_L_LDS, MDH_L_VGPR};
+  int n = 0;
+  for (int li = 0; li < MDH_NUM_LAYERS; ++li)
+    for (int di = 0; di < p->D; ++di)
+      p->order[n++] = (uint8_t)(layer_order[li] * MDH_MAX_D + dim_order[di]);
+}
+
+int64_t extent(const mdh_tile_params* p, int d) {
+  int64_t e = p->blk[d];
+  for (int l = 0; l < MDH_NUM_LAYERS; ++l) e *= p->prt[l][d];
+  return e;
+}
+
+// Algorithmic constraint of parameter 0 (with the predicated-tail extension).
+mdh_status check_products(const mdh_tile_params* p, const int64_t* sizes, bool* ragged) {
+  *ragged = false;
+  for (int d = 0; d < p->D; ++d) {
+    if (p->blk[d] < 1) return MDH_ERR_TILE_NOT_DIVIDING;
+    for (int l = 0; l < MDH_NUM_LAYERS; ++l)
+      if (p->prt[l][d] < 1) return MDH_ERR_TILE_NOT_DIVIDING;
+    const int64_t e = extent(p, d);
+    if (e == sizes[d]) continue;
+    if (!p->ragged || e < sizes[d]) return MDH_ERR_TILE_NOT_DIVIDING;
+    *ragged = true;
+  }
+  return MDH_OK;
+}
+
+mdh_status check_lanes(const mdh_tile_params* p) {
+  int64_t lanes = 1;
+  for (int d = 0; d < p->D; ++d) lanes *= (int64_t)p->prt[MDH_L_WAVE][d] * p->prt[MDH_L_LANE][d];
+  return lanes > kMaxLanesPerWG ? MDH_ERR_TILE_RESOURCES : MDH_OK;
+}
+
+// A configuration is supported iff regenerating the table from the derived launch
+// descriptor reproduces it (apart from the ragged flag).
+bool same_table(const mdh_tile_params& a, const mdh_tile_params& b) {
+  mdh_tile_params x = a, y = b;
+  x.ragged = y.ragged = 0;
+  memset(x.reserved, 0, sizeof(x.reserved));
+  memset(y.reserved, 0, sizeof(y.reserved));
+  return memcmp(&x, &y, sizeof(x)) == 0;
+}
+
+int64_t ws64(int64_t x) { return x; }
+
+}  // namespace
+
+// =============================================================================== stencil
+
+static bool stencil_inst(int RJ, int TY, int LK) {
+  static const int menu[][3] = {{4, 2, 128}, {2, 2, 128}, {8, 2, 128}, {4, 4, 128}, {2, 4, 128},
+                                {4, 1, 128}, {8, 1, 128}, {4, 4, 64},  {2, 4, 64},  {4, 2, 64}};
+  for (auto& m : menu)
+    if (m[0] == RJ && m[1] == TY && m[2] == LK) return true;
+  return false;
+}
+
+int64_t stencil_lds_bytes(int RJ, int TY, int LK) {
+  return 2ll * (TY * RJ + 2) * (LK * 4 + 8) * 4;
+}
+
+void params_from_plan(const int64_t* sizes, const StencilPlan& pl, mdh_tile_params* p) {
+  clear_params(p, 3);
+  const int TJ = pl.TY * pl.RJ, KT = pl.LK * 4;
+  p->prt[MDH_L_WG][0] = (int32_t)cdiv(sizes[0], pl.SI);
+  p->prt[MDH_L_WG][1] = (int32_t)cdiv(sizes[1], TJ);
+  p->prt[MDH_L_WG][2] = (int32_t)cdiv(sizes[2], KT);
+  p->prt[MDH_L_HBM][0] = pl.SI;
+  p->prt[MDH_L_WAVE][1] = pl.TY;
+  p->prt[MDH_L_WAVE][2] = pl.LK / 64;
+  p->prt[MDH_L_LANE][2] = 64;
+  p->prt[MDH_L_VGPR][1] = pl.RJ;
+  p->prt[MDH_L_VGPR][2] = 4;
+  static const int dims[3] = {0, 1, 2};
+  set_order(p, dims);
+  p->strided = 0;
+  p->lane_fast_dim = 2;            // k is contiguous in both buffers
+  p->in_region[0] = MDH_MR_LDS;    // current plane staged in LDS
+  p->out_region = MDH_MR_VGPR;     // results leave from registers
+  p->ragged = (uint8_t)pl.ragged;
+}
+
+static StencilPlan stencil_default(const int64_t* s) {
+  StencilPlan pl;
+  pl.RJ = 4;
+  pl.TY = 2;
+  pl.LK = s[2] <= 256 ? 64 : 128;
+  if (pl.LK == 64) pl.TY = 4;
+  pl.SI = 32;
+  const int TJ = pl.TY * pl.RJ, KT = pl.LK * 4;
+  // keep at least ~1024 workgroups in flight when the grid is small
+  while (pl.SI > 4 && cdiv(s[0], pl.SI) * cdiv(s[1], TJ) * cdiv(s[2], KT) < 1024) pl.SI /= 2;
+  if (s[0] > 0 && pl.SI > s[0]) pl.SI = (int)s[0];
+  pl.ragged = (s[0] % pl.SI) || (s[1] % TJ) || (s[2] % KT);
+  return pl;
+}
+
+int stencil_candidates(const int64_t* s, StencilPlan* out, int cap) {
+  int n = 0;
+  auto push = [&](int RJ, int TY, int LK, int SI) {
+    if (n >= cap) return;
+    if (s[0] > 0 && SI > s[0]) SI = (int)s[0];
+    StencilPlan pl{RJ, TY, LK, SI, 0};
+    pl.ragged = (s[0] % SI) || (s[1] % (TY * RJ)) || (s[2] % (LK * 4));
+    for (int i = 0; i < n; ++i)
+      if (out[i].RJ == RJ && out[i].TY == TY && out[i].LK == LK && out[i].SI == SI) return;
+    out[n++] = pl;
+  };
+  StencilPlan d = stencil_default(s);
+  push(d.RJ, d.TY, d.LK, d.SI);
+  static const int menu[][3] = {{4, 2, 128}, {2, 2, 128}, {8, 2, 128}, {4, 4, 128}, {2, 4, 128},
+                                {4, 1, 128}, {8, 1, 128}, {4, 4, 64},  {2, 4, 64},  {4, 2, 64}};
+  static const int sis[] = {16, 32, 64, 128};
+  for (auto& m : menu)
+    for (int si : sis) push(m[0], m[1], m[2], si);
+  return n;
+}
+
+mdh_status plan_stencil(const int64_t* s, const mdh_tile_params* p, StencilPlan* out) {
+  if (!p) {
+    *out = stencil_default(s);
+    return MDH_OK;
+  }
+  if (p->D != 3) return MDH_ERR_UNSUPPORTED;
+  bool ragged;
+  mdh_status st = check_products(p, s, &ragged);
+  if (st != MDH_OK) return st;
+  if ((st = check_lanes(p)) != MDH_OK) return st;
+  StencilPlan pl;
+  pl.RJ = p->prt[MDH_L_VGPR][1];
+  pl.TY = p->prt[MDH_L_WAVE][1];
+  pl.LK = p->prt[MDH_L_WAVE][2] * 64;
+  pl.SI = p->prt[MDH_L_HBM][0];
+  pl.ragged = ragged;
+  if (stencil_lds_bytes(pl.RJ, pl.TY, pl.LK) > kLdsBytesPerWG) return MDH_ERR_TILE_RESOURCES;
+  mdh_tile_params chk;
+  params_from_plan(s, pl, &chk);
+  if (!same_table(chk, *p) || !stencil_inst(pl.RJ, pl.TY, pl.LK)) return MDH_ERR_UNSUPPORTED;
+  *out = pl;
+  return MDH_OK;
+}
+
+// =============================================================================== matmul
+
+struct GemmInst {
+  int BM, BN, BK, WM, WN;
+};
+static const GemmInst kGemmMenu[] = {
+    {128, 128, 16, 64, 64}, {256, 128, 16, 128, 64}, {128, 64, 16, 64, 32},
+    {64, 64, 16, 32, 32},   {128, 128, 32, 64, 64},  {256, 128, 32, 128, 64},
+};
+
+static bool gemm_inst(const GemmPlan& pl) {
+  for (auto& m : kGemmMenu)
+    if (m.BM == pl.BM && m.BN == pl.BN && m.BK == pl.BK && m.WM == pl.WM && m.WN == pl.WN)
+      return true;
+  return false;
+}
+
+int64_t gemm_lds_bytes(int BM, int BN, int BK) {
+  // two stages of an A tile [BM][BK+4] and a B tile [BK][BN+4]
+  return 2ll * ((int64_t)BM * (BK + 4) + (int64_t)BK * (BN + 4)) * 4;
+}
+
+void params_from_plan(const int64_t* s, const GemmPlan& pl, mdh_tile_params* p) {
+  clear_params(p, 3);
+  p->blk[0] = 32;
+  p->blk[1] = 32;
+  p->blk[2] = 2;  // one v_mfma_f32_32x32x2_f32
+  p->prt[MDH_L_WG][0] = (int32_t)cdiv(s[0], pl.BM);
+  p->prt[MDH_L_WG][1] = (int32_t)cdiv(s[1], pl.BN);
+  p->prt[MDH_L_WG][2] = pl.S;
+  p->prt[MDH_L_HBM][2] = (int32_t)cdiv(cdiv(s[2], pl.S), pl.BK);
+  p->prt[MDH_L_WAVE][0] = pl.BM / pl.WM;
+  p->prt[MDH_L_WAVE][1] = pl.BN / pl.WN;
+  p->prt[MDH_L_LDS][2] = pl.BK / 2;
+  p->prt[MDH_L_VGPR][0] = pl.WM / 32;
+  p->prt[MDH_L_VGPR][1] = pl.WN / 32;
+  static const int dims[3] = {0, 1, 2};
+  set_order(p, dims);
+  p->strided = 0;
+  p->lane_fast_dim = 1;
+  p->in_region[0] = MDH_MR_LDS;
+  p->in_region[1] = MDH_MR_LDS;
+  p->out_region = MDH_MR_VGPR;
+  p->ragged = (uint8_t)pl.ragged;
+}
+
+static int gemm_ragged(const int64_t* s, const GemmPlan& pl) {
+  return (s[0] % pl.BM) || (s[1] % pl.BN) || (s[2] % ((int64_t)pl.S * pl.BK));
+}
+
+static GemmPlan gemm_default(const int64_t* s) {
+  const int64_t M = s[0], N = s[1], K = s[2];
+  GemmPlan pl{128, 128, 16, 64, 64, 1, 0};
+  if (N <= 64 || M <= 64) pl = GemmPlan{128, 64, 16, 64, 32, 1, 0};
+  if (M <= 64 && N <= 64) pl = GemmPlan{64, 64, 16, 32, 32, 1, 0};
+  if (M > 64 && N > 64 && M * N <= 512 * 512) pl = GemmPlan{64, 64, 16, 32, 32, 1, 0};
+  // split the reduction dimension over workgroups until the chip (256 CUs) is covered
+  const int64_t tiles = cdiv(M, pl.BM) * cdiv(N, pl.BN);
+  int S = 1;
+  while (tiles * S < 1024 && S < 64 && K / (S * 2) >= 4 * pl.BK) S *= 2;
+  pl.S = S;
+  pl.ragged = gemm_ragged(s, pl);
+  return pl;
+}
+
+int matmul_candidates(const int64_t* s, GemmPlan* out, int cap) {
+  int n = 0;
+  auto push = [&](GemmPlan pl) {
+    if (n >= cap) return;
+    if (pl.S > 1 && s[2] / pl.S < pl.BK) return;
+    pl.ragged = gemm_ragged(s, pl);
+    for (int i = 0; i < n; ++i)
+      if (out[i].BM == pl.BM && out[i].BN == pl.BN && out[i].BK == pl.BK && out[i].WM == pl.WM &&
+          out[i].S == pl.S)
+        return;
+    out[n++] = pl;
+  };
+  push(gemm_default(s));
+  static const int splits[] = {1, 2, 4, 8, 16};
+  for (auto& m : kGemmMenu)
+    for (int S : splits) {
+      const int64_t tiles = cdiv(s[0], m.BM) * cdiv(s[1], m.BN);
+      if (S > 1 && tiles * (S / 2) >= 2048) continue;  // splitting a full grid only adds traffic
+      push(GemmPlan{m.BM, m.BN, m.BK, m.WM, m.WN, S, 0});
+    }
+  return n;
+}
+
+mdh_status plan_matmul(const int64_t* s, const mdh_tile_params* p, GemmPlan* out) {
+  if (!p) {
+    *out = gemm_default(s);
+    return MDH_OK;
+  }
+  if (p->D != 3) return MDH_ERR_UNSUPPORTED;
+  bool ragged;
+  mdh_status st = check_products(p, s, &ragged);
+  if (st != MDH_OK) return st;
+  if ((st = check_lanes(p)) != MDH_OK) return st;
+  GemmPlan pl;
+  pl.WM = p->prt[MDH_L_VGPR][0] * 32;
+  pl.WN = p->prt[MDH_L_VGPR][1] * 32;
+  pl.BM = p->prt[MDH_L_WAVE][0] * pl.WM;
+  pl.BN = p->prt[MDH_L_WAVE][1] * pl.WN;
+  pl.BK = p->prt[MDH_L_LDS][2] * 2;
+  pl.S = p->prt[MDH_L_WG][2];
+  pl.ragged = ragged;
+  if (p->blk[0] != 32 || p->blk[1] != 32 || p->blk[2] != 2) return MDH_ERR_UNSUPPORTED;
+  if (gemm_lds_bytes(pl.BM, pl.BN, pl.BK) > kLdsBytesPerWG) return MDH_ERR_TILE_RESOURCES;
+  if ((int64_t)p->prt[MDH_L_WAVE][0] * p->prt[MDH_L_WAVE][1] * 64 > kMaxLanesPerWG)
+    return MDH_ERR_TILE_RESOURCES;
+  mdh_tile_params chk;
+  params_from_plan(s, pl, &chk);
+  if (!same_table(chk, *p) || !gemm_inst(pl)) return MDH_ERR_UNSUPPORTED;
+  *out = pl;
+  return MDH_OK;
+}
+
+// =============================================================================== MCC
+
+struct MccInst {
+  int TP, TQ, BN, CK, WM, WN;
+};
+static const MccInst kMccMenu[] = {
+    {4, 32, 128, 16, 64, 64},
+    {8, 32, 128, 16, 128, 64},
+    {2, 32, 64, 16, 32, 32},
+    {4, 32, 64, 16, 64, 32},
+};
+
+static bool mcc_inst(const MccPlan& pl) {
+  for (auto& m : kMccMenu)
+    if (m.TP == pl.TP && m.TQ == pl.TQ && m.BN == pl.BN && m.CK == pl.CK && m.WM == pl.WM &&
+        m.WN == pl.WN)
+      return true;
+  return false;
+}
+
+int64_t mcc_lds_bytes(const MccPlan& pl, int64_t R, int64_t S, int64_t sh, int64_t sw) {
+  const int64_t ph = (pl.TP - 1) * sh + R, pw = (pl.TQ - 1) * sw + S;
+  return (ph * pw * (pl.CK + 4) + 2ll * pl.BN * (pl.CK + 4)) * 4;
+}
+
+void params_from_plan(const int64_t* s, const MccPlan& pl, mdh_tile_params* p) {
+  // dims: 0 n, 1 p, 2 q, 3 k, 4 c, 5 r, 6 s
+  clear_params(p, 7);
+  p->blk[2] = 32;  // 32 consecutive q of one output row
+  p->blk[3] = 32;  // 32 output channels
+  p->blk[4] = 2;   // 2 input channels per MFMA
+  p->prt[MDH_L_WG][0] = (int32_t)s[0];
+  p->prt[MDH_L_WG][1] = (int32_t)cdiv(s[1], pl.TP);
+  p->prt[MDH_L_WG][2] = (int32_t)cdiv(s[2], pl.TQ);
+  p->prt[MDH_L_WG][3] = (int32_t)cdiv(s[3], pl.BN);
+  p->prt[MDH_L_HBM][4] = (int32_t)cdiv(s[4], pl.CK);
+  p->prt[MDH_L_LDS][4] = pl.CK / 2;
+  p->prt[MDH_L_LDS][5] = (int32_t)s[5];
+  p->prt[MDH_L_LDS][6] = (int32_t)s[6];
+  // wavefront grid: (TP*TQ/WM) along the pixels (rows of p first), BN/WN along k
+  const int wm_rows = pl.WM / pl.TQ > 0 ? pl.WM / pl.TQ : 1;  // output rows per wavefront
+  p->prt[MDH_L_WAVE][1] = pl.TP / wm_rows;
+  p->prt[MDH_L_WAVE][3] = pl.BN / pl.WN;
+  p->prt[MDH_L_VGPR][1] = wm_rows;
+  p->prt[MDH_L_VGPR][2] = pl.TQ / 32;
+  p->prt[MDH_L_VGPR][3] = pl.WN / 32;
+  static const int dims[7] = {0, 1, 2, 3, 4, 5, 6};
+  set_order(p, dims);
+  p->strided = 0;
+  p->lane_fast_dim = 3;
+  p->in_region[0] = MDH_MR_LDS;
+  p->in_region[1] = MDH_MR_LDS;
+  p->out_region = MDH_MR_VGPR;
+  p->ragged = (uint8_t)pl.ragged;
+}
+
+static int mcc_ragged(const int64_t* s, const MccPlan& pl) {
+  return (s[1] % pl.TP) || (s[2] % pl.TQ) || (s[3] % pl.BN) || (s[4] % pl.CK);
+}
+
+static MccPlan mcc_default(const int64_t* s) {
+  MccPlan pl{4, 32, 128, 16, 64, 64, 0};
+  if (s[3] <= 64) pl = MccPlan{4, 32, 64, 16, 64, 32, 0};
+  pl.ragged = mcc_ragged(s, pl);
+  return pl;
+}
+
+int mcc_candidates(const int64_t* s, MccPlan* out, int cap) {
+  int n = 0;
+  auto push = [&](MccPlan pl) {
+    if (n >= cap) return;
+    if (mcc_lds_bytes(pl, s[5], s[6], s[7], s[8]) > kLdsBytesPerWG) return;
+    pl.ragged = mcc_ragged(s, pl);
+    for (int i = 0; i < n; ++i)
+      if (out[i].TP == pl.TP && out[i].TQ == pl.TQ && out[i].BN == pl.BN && out[i].WM == pl.WM)
+        return;
+    out[n++] = pl;
+  };
+  push(mcc_default(s));
+  for (auto& m : kMccMenu) push(MccPlan{m.TP, m.TQ, m.BN, m.CK, m.WM, m.WN, 0});
+  return n;
+}
+
+mdh_status plan_mcc(const int64_t* s, const mdh_tile_params* p, MccPlan* out) {
+  if (!p) {
+    *out = mcc_default(s);
+    if (mcc_lds_bytes(*out, s[5], s[6], s[7], s[8]) > kLdsBytesPerWG) return MDH_ERR_TILE_RESOURCES;
+    return MDH_OK;
+  }
+  if (p->D != 7) return MDH_ERR_UNSUPPORTED;
+  bool ragged;
+  mdh_status st = check_products(p, s, &ragged);
+  if (st != MDH_OK) return st;
+  if ((st = check_lanes(p)) != MDH_OK) return st;
+  MccPlan pl;
+  pl.TQ = p->prt[MDH_L_VGPR][2] * 32;
+  pl.TP = p->prt[MDH_L_WAVE][1] * p->prt[MDH_L_VGPR][1];
+  pl.WM = p->prt[MDH_L_VGPR][1] * pl.TQ;
+  pl.WN = p->prt[MDH_L_VGPR][3] * 32;
+  pl.BN = p->prt[MDH_L_WAVE][3] * pl.WN;
+  pl.CK = p->prt[MDH_L_LDS][4] * 2;
+  pl.ragged = ragged;
+  if (mcc_lds_bytes(pl, s[5], s[6], s[7], s[8]) > kLdsBytesPerWG) return MDH_ERR_TILE_RESOURCES;
+  mdh_tile_params chk;
+  params_from_plan(s, pl, &chk);
+  if (!same_table(chk, *p) || !mcc_inst(pl)) return MDH_ERR_UNSUPPORTED;
+  *out = pl;
+  return MDH_OK;
+}
+
+// =============================================================================== custom reduce
+
+static bool prl_inst(const PrlPlan& pl) {
+  static const int menu[][3] = {{2, 4, 1}, {4, 4, 1}, {1, 4, 1}, {2, 2, 2}, {4, 2, 2},
+                                {2, 1, 4}, {4, 1, 4}, {2, 8, 1}, {4, 8, 1}};
+  for (auto& m : menu)
+    if (m[0] == pl.RA && m[1] == pl.WB && m[2] == pl.WA) return true;
+  return false;
+}
+
+void params_from_plan(const int64_t* s, const PrlPlan& pl, mdh_tile_params* p) {
+  clear_params(p, 2);
+  p->prt[MDH_L_WG][0] = (int32_t)cdiv(s[0], (int64_t)pl.WA * 64 * pl.RA);
+  p->prt[MDH_L_WG][1] = pl.S;
+  p->prt[MDH_L_WAVE][0] = pl.WA;
+  p->prt[MDH_L_WAVE][1] = pl.WB;
+  p->prt[MDH_L_LANE][0] = 64;
+  p->prt[MDH_L_VGPR][0] = pl.RA;
+  p->prt[MDH_L_HBM][1] = (int32_t)cdiv(s[1], (int64_t)pl.S * pl.WB);
+  static const int dims[2] = {0, 1};
+  set_order(p, dims);
+  p->strided = 0;
+  p->lane_fast_dim = 0;
+  p->in_region[0] = MDH_MR_VGPR;  // a lane's records of A stay in registers
+  p->in_region[1] = MDH_MR_HBM;   // records of B are wavefront-uniform: scalar loads, no staging
+  p->out_region = MDH_MR_VGPR;
+  p->ragged = (uint8_t)pl.ragged;
+}
+
+static int prl_ragged(const int64_t* s, const PrlPlan& pl) {
+  return (s[0] % ((int64_t)pl.WA * 64 * pl.RA)) || (s[1] % ((int64_t)pl.S * pl.WB));
+}
+
+static PrlPlan prl_default(const int64_t* s) {
+  PrlPlan pl{2, 4, 1, 1, 0};
+  const int64_t wgs_a = cdiv(s[0], (int64_t)pl.WA * 64 * pl.RA);
+  int S = 1;
+  // 256 CUs x 4 SIMDs x 2 wavefronts each: split B over workgroups until the chip is covered
+  while (wgs_a * S * pl.WB * pl.WA < 4096 && S < 256 && s[1] / (2ll * S * pl.WB) >= 256) S *= 2;
+  pl.S = S;
+  pl.ragged = prl_ragged(s, pl);
+  return pl;
+}
+
+int prl_candidates(const int64_t* s, PrlPlan* out, int cap) {
+  int n = 0;
+  auto push = [&](PrlPlan pl) {
+    if (n >= cap) return;
+    if (s[1] / ((int64_t)pl.S * pl.WB) < 1) return;
+    pl.ragged = prl_ragged(s, pl);
+    for (int i = 0; i < n; ++i)
+      if (out[i].RA == pl.RA && out[i].WB == pl.WB && out[i].WA == pl.WA && out[i].S == pl.S) return;
+    out[n++] = pl;
+  };
+  PrlPlan d = prl_default(s);
+  push(d);
+  static const int menu[][3] = {{2, 4, 1}, {4, 4, 1}, {1, 4, 1}, {2, 2, 2}, {4, 2, 2},
+                                {2, 1, 4}, {4, 1, 4}, {2, 8, 1}, {4, 8, 1}};
+  for (auto& m : menu)
+    for (int S = d.S / 2 > 0 ? d.S / 2 : 1; S <= d.S * 2; S *= 2) push(PrlPlan{m[0], m[1], m[2], S, 0});
+  return n;
+}
+
+mdh_status plan_prl(const int64_t* s, const mdh_tile_params* p, PrlPlan* out) {
+  if (!p) {
+    *out = prl_default(s);
+    return MDH_OK;
+  }
+  if (p->D != 2) return MDH_ERR_UNSUPPORTED;
+  bool ragged;
+  mdh_status st = check_products(p, s, &ragged);
+  if (st != MDH_OK) return st;
+  if ((st = check_lanes(p)) != MDH_OK) return st;
+  PrlPlan pl;
+  pl.RA = p->prt[MDH_L_VGPR][0];
+  pl.WA = p->prt[MDH_L_WAVE][0];
+  pl.WB = p->prt[MDH_L_WAVE][1];
+  pl.S = p->prt[MDH_L_WG][1];
+  pl.ragged = ragged;
+  mdh_tile_params chk;
+  params_from_plan(s, pl, &chk);
+  if (!same_table(chk, *p) || !prl_inst(pl)) return MDH_ERR_UNSUPPORTED;
+  *out = pl;
+  return MDH_OK;
+}
+
+}  // namespace mdh
+
+// =============================================================================== C ABI (host-only part)
+
+using namespace mdh;
+
+extern "C" {
+
+const char* mdh_strerror(mdh_status s) {
+  switch (s) {
+    case MDH_OK: return "ok";
+    case MDH_ERR_NULL: return "a required pointer is NULL";
+    case MDH_ERR_SIZE: return "invalid size (negative, empty reduction dimension, or beyond 2^31-1 elements)";
+    case MDH_ERR_TILE_NOT_DIVIDING: return "tile parameters violate prod_l #PRT(l,d) * blk[d] == N_d";
+    case MDH_ERR_TILE_RESOURCES: return "tile parameters exceed lanes-per-workgroup or LDS budget";
+    case MDH_ERR_WORKSPACE: return "workspace missing or too small for the split reduction";
+    case MDH_ERR_UNSUPPORTED: return "no kernel instantiation for this configuration";
+    case MDH_ERR_LAUNCH: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+const char* mdh_version(void) { return "0.1"; }
+
+mdh_status mdh_part_offset(int64_t N, int32_t L, const int32_t* P, const int32_t* p,
+                           int64_t* offset, int64_t* part_size) {
+  if (!P || !p || !offset || !part_size) return MDH_ERR_NULL;
+  if (N < 0 || L < 0) return MDH_ERR_SIZE;
+  int64_t prod = 1, os = 0;
+  for (int l = 0; l < L; ++l) {
+    if (P[l] < 1) return MDH_ERR_TILE_NOT_DIVIDING;
+    if (p[l] < 0 || p[l] >= P[l]) return MDH_ERR_SIZE;
+    prod *= P[l];
+    if (N % prod) return MDH_ERR_TILE_NOT_DIVIDING;
+    os += (int64_t)p[l] * (N / prod);
+  }
+  *offset = os;
+  *part_size = N / prod;
+  return MDH_OK;
+}
+
+static mdh_status check_sizes(mdh_instance inst, const int64_t* s) {
+  if (!s) return MDH_ERR_NULL;
+  const int D = inst == MDH_MCC ? 9 : inst == MDH_CUSTOM_REDUCE ? 2 : 3;
+  for (int d = 0; d < D; ++d)
+    if (s[d] < 0 || s[d] > 0x7fffffff) return MDH_ERR_SIZE;
+  switch (inst) {
+    case MDH_MATMUL:
+      if (s[2] < 1) return MDH_ERR_SIZE;
+      break;
+    case MDH_STENCIL:
+      break;
+    case MDH_MCC:
+      if (s[4] < 1 || s[5] < 1 || s[6] < 1 || s[7] < 1 || s[8] < 1) return MDH_ERR_SIZE;
+      break;
+    case MDH_CUSTOM_REDUCE:
+      if (s[1] < 1) return MDH_ERR_SIZE;
+      break;
+    default:
+      return MDH_ERR_UNSUPPORTED;
+  }
+  return MDH_OK;
+}
+
+mdh_status mdh_default_params(mdh_instance inst, const int64_t* sizes, mdh_tile_params* out) {
+  if (!out) return MDH_ERR_NULL;
+  mdh_status st = check_sizes(inst, sizes);
+  if (st != MDH_OK) return st;
+  switch (inst) {
+    case MDH_MATMUL: {
+      GemmPlan pl;
+      if ((st = plan_matmul(sizes, nullptr, &pl)) == MDH_OK) params_from_plan(sizes, pl, out);
+      return st;
+    }
+    case MDH_STENCIL: {
+      StencilPlan pl;
+      if ((st = plan_stencil(sizes, nullptr, &pl)) == MDH_OK) params_from_plan(sizes, pl, out);
+      return st;
+    }
+    case MDH_MCC: {
+      MccPlan pl;
+      if ((st = plan_mcc(sizes, nullptr, &pl)) == MDH_OK) params_from_plan(sizes, pl, out);
+      return st;
+    }
+    case MDH_CUSTOM_REDUCE: {
+      PrlPlan pl;
+      if ((st = plan_prl(sizes, nullptr, &pl)) == MDH_OK) params_from_plan(sizes, pl, out);
+      return st;
+    }
+  }
+  return MDH_ERR_UNSUPPORTED;
+}
+
+mdh_status mdh_validate_params(mdh_instance inst, const int64_t* sizes, const mdh_tile_params* p) {
+  if (!p) return MDH_ERR_NULL;
+  mdh_status st = check_sizes(inst, sizes);
+  if (st != MDH_OK) return st;
+  switch (inst) {
+    case MDH_MATMUL: {
+      GemmPlan pl;
+      return plan_matmul(sizes, p, &pl);
+    }
+    case MDH_STENCIL: {
+      StencilPlan pl;
+      return plan_stencil(sizes, p, &pl);
+    }
+    case MDH_MCC: {
+      MccPlan pl;
+      return plan_mcc(sizes, p, &pl);
+    }
+    case MDH_CUSTOM_REDUCE: {
+      PrlPlan pl;
+      return plan_prl(sizes, p, &pl);
+    }
+  }
+  return MDH_ERR_UNSUPPORTED;
+}
+
+size_t mdh_workspace_size(mdh_instance inst, const int64_t* sizes, const mdh_tile_params* params) {
+  if (check_sizes(inst, sizes) != MDH_OK) return 0;
+  switch (inst) {
+    case MDH_MATMUL: {
+      GemmPlan pl;
+      if (plan_matmul(sizes, params, &pl) != MDH_OK || pl.S <= 1) return 0;
+      return (size_t)pl.S * (size_t)sizes[0] * (size_t)sizes[1] * sizeof(float);
+    }
+    case MDH_CUSTOM_REDUCE: {
+      PrlPlan pl;
+      if (plan_prl(sizes, params, &pl) != MDH_OK || pl.S <= 1) return 0;
+      return (size_t)pl.S * (size_t)sizes[0] * 2 * sizeof(int32_t);
+    }
+    default:
+      return 0;
+  }
+}
+
+int32_t mdh_num_candidates(mdh_instance inst, const int64_t* sizes) {
+  if (check_sizes(inst, sizes) != MDH_OK) return 0;
+  constexpr int CAP = 128;
+  switch (inst) {
+    case MDH_MATMUL: {
+      GemmPlan c[CAP];
+      return matmul_candidates(sizes, c, CAP);
+    }
+    case MDH_STENCIL: {
+      StencilPlan c[CAP];
+      return stencil_candidates(sizes, c, CAP);
+    }
+    case MDH_MCC: {
+      MccPlan c[CAP];
+      return mcc_candidates(sizes, c, CAP);
+    }
+    case MDH_CUSTOM_REDUCE: {
+      PrlPlan c[CAP];
+      return prl_candidates(sizes, c, CAP);
+    }
+  }
+  return 0;
+}
+
+mdh_status mdh_candidate(mdh_instance inst, const int64_t* sizes, int32_t idx, mdh_tile_params* out) {
+  if (!out) return MDH_ERR_NULL;
+  mdh_status st = check_sizes(inst, sizes);
+  if (st != MDH_OK) return st;
+  constexpr int CAP = 128;
+  switch (inst) {
+    case MDH_MATMUL: {
+      GemmPlan c[CAP];
+      int n = matmul_candidates(sizes, c, CAP);
+      if (idx < 0 || idx >= n) return MDH_ERR_SIZE;
+      params_from_plan(sizes, c[idx], out);
+      return MDH_OK;
+    }
+    case MDH_STENCIL: {
+      StencilPlan c[CAP];
+      int n = stencil_candidates(sizes, c, CAP);
+      if (idx < 0 || idx >= n) return MDH_ERR_SIZE;
+      params_from_plan(sizes, c[idx], out);
+      return MDH_OK;
+    }
+    case MDH_MCC: {
+      MccPlan c[CAP];
+      int n = mcc_candidates(sizes, c, CAP);
+      if (idx < 0 || idx >= n) return MDH_ERR_SIZE;
+      params_from_plan(sizes, c[idx], out);
+      return MDH_OK;
+    }
+    case MDH_CUSTOM_REDUCE: {
+      PrlPlan c[CAP];
+      int n = prl_candidates(sizes, c, CAP);
+      if (idx < 0 || idx >= n) return MDH_ERR_SIZE;
+      params_from_plan(sizes, c[idx], out);
+      return MDH_OK;
+    }
+  }
+  return MDH_ERR_UNSUPPORTED;
+}
+
+}  // extern "C"

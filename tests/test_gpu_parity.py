@@ -1,0 +1,275 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element
+on seeded inputs.  Sizes span several tiles and ragged tails; every candidate tile
+configuration is a valid (de/re)-composition and must give the same result.
+
+Tolerances (the design doc derives them):
+  MatMul / MCC : max |gpu - ref| / sum_k |a*b|  <= 1e-4   (componentwise-scaled error)
+  Jacobi-3D    : max |gpu - ref| / ref          <= 1e-6   (all terms non-negative)
+  custom reduce: bit-exact (int32)
+"""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2405_05118_amd as mdh
+from paper_2405_05118_amd import binding as B
+from paper_2405_05118_amd import workloads as W
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL_CONTRACTION = 1e-4
+TOL_STENCIL = 1e-6
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def workspace(inst, sizes, p):
+    n = mdh.mdh_workspace_size(inst, sizes, p)
+    return torch.empty(max(n, 4) // 4, dtype=torch.int32, device="cuda") if n else None
+
+
+def candidates(inst, sizes, limit=None):
+    n = mdh.mdh_num_candidates(inst, sizes)
+    idx = list(range(n))
+    if limit is not None and n > limit:
+        step = n / float(limit)
+        idx = sorted({int(i * step) for i in range(limit)} | {0})
+    return [None] + [mdh.mdh_candidate(inst, sizes, i) for i in idx]
+
+
+# ------------------------------------------------------------------------------ MatMul
+
+
+def run_matmul(A, Bm, p):
+    M, K = A.shape
+    N = Bm.shape[1]
+    C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    ws = workspace(mdh.MDH_MATMUL, (M, N, K), p)
+    mdh.mdh_matmul(dev(A), dev(Bm), C, p, ws)
+    torch.cuda.synchronize()
+    return C.cpu().numpy().astype(np.float64)
+
+
+def scaled_err(got, ref, refabs):
+    den = np.where(refabs > 0, refabs, 1.0)
+    return float(np.max(np.abs(got - ref) / den))
+
+
+@pytest.mark.parametrize("shape", [(256, 256, 256), (300, 200, 100), (129, 65, 33), (64, 64, 8), (1, 1, 1), (70, 260, 1030)])
+def test_matmul_small_all_candidates(shape):
+    M, N, K = shape
+    cfg = W.MatmulCfg(M, N, K, W.SEED_BASE + 11)
+    A, Bm = W.matmul_inputs(cfg)
+    ref, refabs = oracle.matmul(A, Bm, with_abs=True)
+    for p in candidates(mdh.MDH_MATMUL, shape, limit=14):
+        got = run_matmul(A, Bm, p)
+        assert np.all(np.isfinite(got)), "output not fully overwritten"
+        assert scaled_err(got, ref, refabs) <= TOL_CONTRACTION, (shape, p and p.table())
+
+
+def test_matmul_closed_forms():
+    # all-ones gives K in every cell (exact in fp32); identity returns A
+    M, N, K = 200, 136, 520
+    got = run_matmul(np.ones((M, K), np.float32), np.ones((K, N), np.float32), None)
+    assert np.all(got == K)
+    A = W.uniform(5, 1, (192, 192), -1, 1)
+    assert np.array_equal(run_matmul(A, np.eye(192, dtype=np.float32), None), A.astype(np.float64))
+
+
+def test_matmul_split_is_deterministic_and_homomorphic():
+    shape = (128, 64, 2048)
+    A, Bm = W.matmul_inputs(W.MatmulCfg(*shape, W.SEED_BASE + 12))
+    ref, refabs = oracle.matmul(A, Bm, with_abs=True)
+    split = [p for p in candidates(mdh.MDH_MATMUL, shape) if p is not None and p.prt[B.L_WG][2] > 1]
+    assert split, "no split-k candidate for a tall reduction"
+    for p in split[:4]:
+        g1 = run_matmul(A, Bm, p)
+        g2 = run_matmul(A, Bm, p)
+        assert np.array_equal(g1, g2)
+        assert scaled_err(g1, ref, refabs) <= TOL_CONTRACTION
+    # homomorphic property on the GPU path: split k by hand, add the halves
+    h = run_matmul(np.ascontiguousarray(A[:, :1000]), Bm[:1000], None) + run_matmul(np.ascontiguousarray(A[:, 1000:]), Bm[1000:], None)
+    assert scaled_err(h, ref, refabs) <= TOL_CONTRACTION
+
+
+# ------------------------------------------------------------------------------ Jacobi-3D
+
+
+def run_stencil(x, c0, c1, p):
+    nx, ny, nz = (s - 2 for s in x.shape)
+    out = torch.full((nx, ny, nz), float("nan"), dtype=torch.float32, device="cuda")
+    mdh.mdh_stencil(dev(x), out, c0, c1, p)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64)
+
+
+def rel_err(got, ref):
+    den = np.where(ref != 0, np.abs(ref), 1.0)
+    return float(np.max(np.abs(got - ref) / den))
+
+
+@pytest.mark.parametrize("shape", [(64, 64, 64), (37, 29, 70), (5, 8, 512), (16, 24, 520), (3, 1, 1), (40, 17, 1030)])
+def test_stencil_small_all_candidates(shape):
+    cfg = W.StencilCfg(*shape, 0.5, float(np.float32(1.0 / 12.0)), W.SEED_BASE + 21)
+    x = W.stencil_inputs(cfg)
+    ref = oracle.jacobi3d(x, cfg.c0, cfg.c1)
+    for p in candidates(mdh.MDH_STENCIL, shape, limit=12):
+        got = run_stencil(x, cfg.c0, cfg.c1, p)
+        assert np.all(np.isfinite(got)), "output not fully overwritten"
+        assert rel_err(got, ref) <= TOL_STENCIL, (shape, p and p.table())
+
+
+def test_stencil_closed_forms_and_halo_untouched():
+    nx, ny, nz = 20, 24, 36
+    c0, c1 = 0.5, float(np.float32(1.0 / 12.0))
+    const = np.full((nx + 2, ny + 2, nz + 2), 3.0, np.float32)
+    assert np.allclose(run_stencil(const, c0, c1, None), 3.0, rtol=3e-7, atol=0)
+    # a single 1 lands in exactly seven outputs
+    x = np.zeros((nx + 2, ny + 2, nz + 2), np.float32)
+    x[5, 9, 17] = 1.0
+    got = run_stencil(x, 0.5, 0.125, None)
+    want = np.zeros((nx, ny, nz))
+    want[4, 8, 16] = 0.5
+    for d in ((1, 0, 0), (-1, 0, 0), (0, 1, 0), (0, -1, 0), (0, 0, 1), (0, 0, -1)):
+        want[4 + d[0], 8 + d[1], 16 + d[2]] = 0.125
+    assert np.array_equal(got, want)
+    # inputs are never written
+    xin = dev(W.uniform(3, 1, (nx + 2, ny + 2, nz + 2), 0, 1))
+    keep = xin.clone()
+    out = torch.empty((nx, ny, nz), dtype=torch.float32, device="cuda")
+    mdh.mdh_stencil(xin, out, c0, c1)
+    torch.cuda.synchronize()
+    assert torch.equal(xin, keep)
+
+
+# ------------------------------------------------------------------------------ MCC
+
+
+def run_mcc(x, f, stride, p):
+    N, H, Wd, C = x.shape
+    K, R, S, _ = f.shape
+    P, Q = (H - R) // stride[0] + 1, (Wd - S) // stride[1] + 1
+    out = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
+    mdh.mdh_mcc(dev(x), dev(f), out, stride, p)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64)
+
+
+MCC_SMALL = [
+    # N, H, W, C, K, R, S, stride
+    (2, 38, 38, 32, 128, 7, 7, (1, 1)),   # full tiles: P = Q = 32
+    (1, 20, 45, 16, 64, 3, 3, (1, 1)),    # ragged q
+    (2, 15, 17, 5, 9, 3, 2, (2, 2)),      # strided, ragged everything, C not a multiple of 4
+    (1, 9, 9, 3, 4, 1, 1, (1, 1)),        # 1x1 filter
+    (3, 1, 1, 40, 7, 1, 1, (1, 1)),       # reduces to a matmul
+]
+
+
+@pytest.mark.parametrize("case", MCC_SMALL)
+def test_mcc_small_all_candidates(case):
+    N, H, Wd, C, K, R, S, stride = case
+    cfg = W.MccCfg(N, H, Wd, C, K, R, S, stride, W.SEED_BASE + 31)
+    x, f = W.mcc_inputs(cfg)
+    ref, refabs = oracle.mcc(x, f, stride, with_abs=True)
+    P, Q = ref.shape[1:3]
+    sizes = (N, P, Q, K, C, R, S, stride[0], stride[1])
+    for p in candidates(mdh.MDH_MCC, sizes):
+        got = run_mcc(x, f, stride, p)
+        assert np.all(np.isfinite(got)), "output not fully overwritten"
+        assert scaled_err(got, ref, refabs) <= TOL_CONTRACTION, (case, p and p.table())
+
+
+def test_mcc_closed_forms():
+    x = np.ones((1, 12, 40, 16), np.float32)
+    f = np.ones((32, 5, 5, 16), np.float32)
+    assert np.all(run_mcc(x, f, (1, 1), None) == 16 * 25)
+    x = W.normal(9, 1, (1, 10, 40, 8))
+    f = np.zeros((4, 3, 4, 8), np.float32)
+    f[1, 2, 3, 5] = 1.0  # output channel 1 = input channel 5 shifted by (2,3)
+    got = run_mcc(x, f, (1, 1), None)
+    assert np.array_equal(got[..., 1], x[:, 2:10, 3:40, 5].astype(np.float64))
+    assert np.all(got[..., 0] == 0)
+
+
+# ------------------------------------------------------------------------------ custom reduce
+
+
+def run_prl(A, Bt, wp, wm, p):
+    nA, nF = A.shape
+    s = torch.full((nA,), -12345, dtype=torch.int32, device="cuda")
+    i = torch.full((nA,), -12345, dtype=torch.int32, device="cuda")
+    ws = workspace(mdh.MDH_CUSTOM_REDUCE, (nA, Bt.shape[0], nF), p)
+    mdh.mdh_custom_reduce(dev(A), dev(Bt), dev(wp), dev(wm), s, i, p, ws)
+    torch.cuda.synchronize()
+    return s.cpu().numpy(), i.cpu().numpy()
+
+
+@pytest.mark.parametrize("shape", [(1000, 3000, 8), (1, 1, 8), (130, 5, 8), (777, 1234, 5), (300, 900, 12), (64, 4097, 16), (513, 700, 1)])
+def test_custom_reduce_small_all_candidates(shape):
+    nA, nB, nF = shape
+    A, Bt, wp, wm = W.prl_inputs(W.PrlCfg(nA, nB, nF, W.SEED_BASE + 41))
+    rs, ri = oracle.custom_reduce(A, Bt, wp, wm)
+    for p in candidates(mdh.MDH_CUSTOM_REDUCE, shape, limit=16):
+        s, i = run_prl(A, Bt, wp, wm, p)
+        assert np.array_equal(s, rs) and np.array_equal(i, ri), (shape, p and p.table())
+
+
+def test_custom_reduce_ties_and_extreme_weights():
+    # tiny alphabets: most records tie -> the smallest index must win on every path
+    rng = np.random.default_rng(7)
+    A = rng.integers(0, 2, (500, 8)).astype(np.int32)
+    Bt = rng.integers(0, 2, (2500, 8)).astype(np.int32)
+    wp = rng.integers(1, 4, 8).astype(np.int32)
+    wm = rng.integers(-3, 1, 8).astype(np.int32)
+    rs, ri = oracle.custom_reduce(A, Bt, wp, wm)
+    for p in candidates(mdh.MDH_CUSTOM_REDUCE, (500, 2500, 8), limit=16):
+        s, i = run_prl(A, Bt, wp, wm, p)
+        assert np.array_equal(s, rs) and np.array_equal(i, ri)
+    # equal weights: every b ties, index 0 everywhere
+    w = np.full(8, 9, np.int32)
+    s, i = run_prl(A, Bt, w, w, None)
+    assert np.all(s == 72) and np.all(i == 0)
+    # weights near the int32 range whose sums still fit
+    big = np.array([2**27] * 8, np.int32)
+    s, i = run_prl(A, Bt, big, -big, None)
+    rs, ri = oracle.custom_reduce(A, Bt, big, -big)
+    assert np.array_equal(s, rs) and np.array_equal(i, ri)
+
+
+# ------------------------------------------------------------------------------ edge cases
+
+
+def test_empty_and_error_paths_on_device():
+    z = torch.empty((0, 5), dtype=torch.float32, device="cuda")
+    b = torch.empty((5, 7), dtype=torch.float32, device="cuda")
+    c = torch.empty((0, 7), dtype=torch.float32, device="cuda")
+    mdh.mdh_matmul(z, b, c)  # empty ++ dimension: nothing to do, no error
+    x = torch.zeros((2, 6, 6), dtype=torch.float32, device="cuda")
+    o = torch.empty((0, 4, 4), dtype=torch.float32, device="cuda")
+    mdh.mdh_stencil(x, o, 0.5, 0.1)
+    # a non-dividing explicit configuration is refused and leaves the output untouched
+    s = (256, 256, 256)
+    p = mdh.mdh_default_params(mdh.MDH_MATMUL, s)
+    p.prt[B.L_WG][0] += 1
+    A = torch.ones((256, 256), dtype=torch.float32, device="cuda")
+    C = torch.full((256, 256), 7.0, dtype=torch.float32, device="cuda")
+    with pytest.raises(mdh.MdhError) as e:
+        mdh.mdh_matmul(A, A, C, p)
+    assert e.value.status == 3
+    torch.cuda.synchronize()
+    assert torch.all(C == 7.0)
+
+
+def test_tune_returns_a_valid_configuration():
+    shape = (256, 256, 256)
+    A, Bm = W.matmul_inputs(W.MatmulCfg(*shape, W.SEED_BASE + 1))
+    a, b = dev(A), dev(Bm)
+    c = torch.empty((256, 256), dtype=torch.float32, device="cuda")
+    ws = torch.empty(16 * 256 * 256, dtype=torch.float32, device="cuda")
+    best, ms = mdh.mdh_tune(mdh.MDH_MATMUL, shape, [a, b, c], workspace=ws, reps=2)
+    assert ms > 0 and mdh.mdh_validate_params(mdh.MDH_MATMUL, shape, best) == 0
+    ref, refabs = oracle.matmul(A, Bm, with_abs=True)
+    assert scaled_err(run_matmul(A, Bm, best), ref, refabs) <= TOL_CONTRACTION

@@ -1,0 +1,189 @@
+"""Host-side logic of libmdh (no GPU, no compute calls): the library loads, exports every
+symbol include/mdh.h declares, and the planner enforces the paper's constraints."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2405_05118_amd as mdh
+from paper_2405_05118_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+OK, E_NULL, E_SIZE, E_NOTDIV, E_RES, E_WS, E_UNSUP, E_LAUNCH = range(8)
+
+CASES = [
+    (mdh.MDH_MATMUL, (256, 256, 256)),
+    (mdh.MDH_MATMUL, (4096, 4096, 4096)),
+    (mdh.MDH_MATMUL, (65536, 64, 4096)),
+    (mdh.MDH_MATMUL, (300, 200, 100)),
+    (mdh.MDH_STENCIL, (512, 512, 512)),
+    (mdh.MDH_STENCIL, (37, 29, 70)),
+    (mdh.MDH_MCC, (16, 224, 224, 128, 64, 7, 7, 1, 1)),
+    (mdh.MDH_MCC, (2, 14, 14, 40, 12, 3, 3, 2, 2)),
+    (mdh.MDH_CUSTOM_REDUCE, (1 << 16, 1 << 18, 8)),
+    (mdh.MDH_CUSTOM_REDUCE, (1000, 3000, 5)),
+]
+
+
+def test_every_declared_symbol_is_exported():
+    text = open(os.path.join(ROOT, "include", "mdh.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(mdh_[a-z_]+)\s*\(", text))
+    assert declared, "no declarations found in the header"
+    L = mdh.lib()
+    for name in sorted(declared):
+        assert hasattr(L, name), "libmdh.so does not export " + name
+    assert declared == set(B.EXPORTS)
+
+
+def test_struct_layout_matches_header():
+    # 4 + 6*7*4 + 7*4 + 42 + 3 + 4 + 1 + 4 + 1 + 3 = 258 -> padded to 260 (int32 alignment)
+    assert ctypes.sizeof(mdh.TileParams) == 260
+    assert mdh.mdh_version() == "0.1"
+    assert "NULL" in mdh.mdh_strerror(E_NULL)
+
+
+def test_part_offset_worked_example(golden):
+    # Appendix Definition "MDA Partitioning" on the MatVec 512 x 4096 example
+    for ln in golden("matvec_partitioning.txt"):
+        if not ln:
+            continue
+        _, N, P = [t.strip() for t in ln.split(";")]
+        N, P = int(N), [int(t) for t in P.split()]
+        assert mdh.mdh_part_offset(N, P, [0] * len(P)) == (0, 1)
+        assert mdh.mdh_part_offset(N, P, [x - 1 for x in P]) == (N - 1, 1)
+    assert mdh.mdh_part_offset(512, [2, 8, 32], [1, 3, 5]) == (357, 1)
+    assert mdh.mdh_part_offset(4096, [4, 16], [3, 15]) == (4032, 64)
+    with pytest.raises(mdh.MdhError) as e:
+        mdh.mdh_part_offset(10, [4], [0])
+    assert e.value.status == E_NOTDIV
+    with pytest.raises(mdh.MdhError) as e:
+        mdh.mdh_part_offset(16, [4], [4])
+    assert e.value.status == E_SIZE
+
+
+def test_tvm_layering_is_expressible(golden):
+    # a real schedule's part counts multiply to the sizes; our offset formula walks it
+    for ln in golden("tvm_matmul_resnet50_layers.txt"):
+        if not ln:
+            continue
+        _, N, P = [t.strip() for t in ln.split(";")]
+        N, P = int(N), [int(t) for t in P.split()]
+        assert mdh.mdh_part_offset(N, P, [x - 1 for x in P]) == (N - 1, 1)
+
+
+@pytest.mark.parametrize("inst,sizes", CASES)
+def test_default_params_satisfy_the_constraints(inst, sizes):
+    p = mdh.mdh_default_params(inst, sizes)
+    D = p.D
+    assert D == {0: 3, 1: 3, 2: 7, 3: 2}[inst]
+    for d in range(D):
+        e = p.extent(d)
+        if p.ragged:
+            assert e >= sizes[d]
+        else:
+            assert e == sizes[d]  # algorithmic constraint of parameter 0
+    lanes = 1
+    for d in range(D):
+        lanes *= p.prt[B.L_WAVE][d] * p.prt[B.L_LANE][d]
+    assert lanes <= 1024  # model constraint: lanes per workgroup
+    # the order is a permutation of all (layer, dim) pairs
+    used = sorted(p.order[i] for i in range(6 * D))
+    assert used == sorted(l * 7 + d for l in range(6) for d in range(D))
+    assert mdh.mdh_validate_params(inst, sizes, p) == OK
+
+
+@pytest.mark.parametrize("inst,sizes", CASES)
+def test_all_candidates_are_valid(inst, sizes):
+    n = mdh.mdh_num_candidates(inst, sizes)
+    assert n >= 1
+    first = mdh.mdh_candidate(inst, sizes, 0)
+    default = mdh.mdh_default_params(inst, sizes)
+    assert bytes(first) == bytes(default)
+    for i in range(n):
+        p = mdh.mdh_candidate(inst, sizes, i)
+        assert mdh.mdh_validate_params(inst, sizes, p) == OK
+    with pytest.raises(mdh.MdhError):
+        mdh.mdh_candidate(inst, sizes, n)
+
+
+def test_non_dividing_tiles_are_rejected():
+    s = (4096, 4096, 4096)
+    p = mdh.mdh_default_params(mdh.MDH_MATMUL, s)
+    q = p.copy()
+    q.prt[B.L_WG][0] += 1  # product no longer equals M
+    assert mdh.mdh_validate_params(mdh.MDH_MATMUL, s, q) == E_NOTDIV
+    q = p.copy()
+    q.prt[B.L_HBM][2] //= 2  # covers only half of K
+    assert mdh.mdh_validate_params(mdh.MDH_MATMUL, s, q) == E_NOTDIV
+    q = p.copy()
+    q.prt[B.L_LDS][2] = 0
+    assert mdh.mdh_validate_params(mdh.MDH_MATMUL, s, q) == E_NOTDIV
+    # ragged sizes need the explicit extension flag
+    s2 = (300, 200, 100)
+    r = mdh.mdh_default_params(mdh.MDH_MATMUL, s2)
+    assert r.ragged == 1
+    r.ragged = 0
+    assert mdh.mdh_validate_params(mdh.MDH_MATMUL, s2, r) == E_NOTDIV
+
+
+def test_resource_and_support_limits():
+    s = (512, 512, 512)
+    p = mdh.mdh_default_params(mdh.MDH_STENCIL, s)
+    q = p.copy()
+    q.prt[B.L_WAVE][1] = 16  # 16 lane-rows x 128 lanes = 2048 lanes per workgroup
+    q.prt[B.L_WG][1] = 512 // (16 * q.prt[B.L_VGPR][1])
+    assert mdh.mdh_validate_params(mdh.MDH_STENCIL, s, q) == E_RES
+    q = p.copy()
+    q.prt[B.L_VGPR][1] = 1  # valid partitioning, but no kernel keeps 1 row per lane
+    q.prt[B.L_WG][1] = 512 // q.prt[B.L_WAVE][1]
+    assert mdh.mdh_validate_params(mdh.MDH_STENCIL, s, q) == E_UNSUP
+    q = p.copy()
+    q.order[0], q.order[1] = q.order[1], q.order[0]  # another loop order
+    assert mdh.mdh_validate_params(mdh.MDH_STENCIL, s, q) == E_UNSUP
+
+
+def test_workspace_only_for_split_reductions():
+    s = (65536, 64, 4096)
+    for i in range(mdh.mdh_num_candidates(mdh.MDH_MATMUL, s)):
+        p = mdh.mdh_candidate(mdh.MDH_MATMUL, s, i)
+        S = p.prt[B.L_WG][2]
+        want = S * s[0] * s[1] * 4 if S > 1 else 0
+        assert mdh.mdh_workspace_size(mdh.MDH_MATMUL, s, p) == want
+    assert mdh.mdh_workspace_size(mdh.MDH_STENCIL, (64, 64, 64)) == 0
+    s = (1 << 16, 1 << 18, 8)
+    p = mdh.mdh_default_params(mdh.MDH_CUSTOM_REDUCE, s)
+    S = p.prt[B.L_WG][1]
+    assert S > 1 and mdh.mdh_workspace_size(mdh.MDH_CUSTOM_REDUCE, s, p) == S * s[0] * 2 * 4
+
+
+def test_size_errors_before_any_launch():
+    L = mdh.lib()
+    null = None
+    # K = 0: the reduction dimension has no neutral element to return
+    assert L.mdh_matmul(4, 4, 0, null, null, null, null, null, 0, null) == E_SIZE
+    assert L.mdh_matmul(-1, 4, 4, null, null, null, null, null, 0, null) == E_SIZE
+    assert L.mdh_matmul(4, 4, 4, null, null, null, null, null, 0, null) == E_NULL
+    assert L.mdh_matmul(0, 4, 4, null, null, null, null, null, 0, null) == OK  # empty ++ dimension
+    assert L.mdh_stencil(0, 8, 8, null, null, 0.5, 0.1, null, null) == OK
+    assert L.mdh_stencil(8, 8, 8, null, null, 0.5, 0.1, null, null) == E_NULL
+    assert L.mdh_stencil(2000, 2000, 2000, null, null, 0.5, 0.1, null, null) == E_SIZE
+    assert L.mdh_custom_reduce(8, 0, 8, null, null, null, null, null, null, null, null, 0, null) == E_SIZE
+    assert L.mdh_custom_reduce(8, 8, 17, null, null, null, null, null, null, null, null, 0, null) == E_SIZE
+    assert L.mdh_custom_reduce(0, 8, 8, null, null, null, null, null, null, null, null, 0, null) == OK
+    assert L.mdh_mcc(1, 6, 6, 4, 4, 7, 7, 1, 1, null, null, null, null, null, 0, null) == E_SIZE  # H < R
+    assert L.mdh_mcc(1, 8, 8, 4, 4, 3, 3, 0, 1, null, null, null, null, null, 0, null) == E_SIZE  # stride 0
+    assert L.mdh_mcc(0, 8, 8, 4, 4, 3, 3, 1, 1, null, null, null, null, null, 0, null) == OK
+    # a split reduction without workspace is refused, nothing is launched
+    s = (65536, 64, 4096)
+    p = None
+    for i in range(mdh.mdh_num_candidates(mdh.MDH_MATMUL, s)):
+        c = mdh.mdh_candidate(mdh.MDH_MATMUL, s, i)
+        if c.prt[B.L_WG][2] > 1:
+            p = c
+            break
+    assert p is not None
+    one = ctypes.c_void_p(16)  # non-NULL dummy addresses: the call must stop at the workspace check
+    assert L.mdh_matmul(*s, one, one, one, ctypes.byref(p), null, 0, null) == E_WS
