@@ -1,0 +1,295 @@
+#!/usr/bin/env python3
+"""Benchmark of the md_hom hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-instances]
+
+A step is one pass of the hot path (one library call: de-composition, scalar phase,
+re-composition, including the second-pass combine where a reduction dimension is split)
+over one batch of seeded synthetic input that is already resident in HBM.  The headline
+line is the Jacobi-3D 512^3 configuration; the other configurations are measured the same
+way and reported under "instances" in the same JSON line.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "per-instance GFLOP/s or GB/s and % of roofline on 1 MI355X"
+
+# MI355X published peaks
+PEAK_HBM_GBS = 8000.0
+PEAK_FP32_MFMA_TFLOPS = 157.3
+# plain 32-bit integer vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
+PEAK_INT_VALU_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+
+# lane-ops the emitted instruction mix spends per (a,b) pair at nF = 8: 8 compares,
+# 8 selects, 4.5 three-operand adds, compare + max + select for max_idx, 0.5 index move
+PRL_LANE_OPS_PER_PAIR = 24.0
+
+# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/);
+# None until measured for that workload
+TRAFFIC_BYTES = {
+    "jacobi3d_512": 1098534592,  # profiles/stencil_kernel_jacobi3d_512_pmc.md
+    "matmul_4096": None,
+    "matmul_ts": None,
+    "mcc_resnet": None,
+    "prl_2p16_2p18": None,
+    "matmul_256": None,
+}
+
+
+def _events_ms(torch, fn, steps, warmup):
+    """(events ms, wall ms) per step: `steps` launches bracketed by synchronize on both sides;
+    HIP events on the launch stream give the device time, the host clock the whole-job time."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / steps, wall_ms / steps
+
+
+def _ws(torch, mdh, inst, sizes):
+    n = mdh.mdh_workspace_size(inst, sizes)
+    return torch.empty(max(n, 4) // 4, dtype=torch.int32, device="cuda") if n else None
+
+
+def bench_stencil(torch, mdh, W, name, steps, warmup, cpu):
+    cfg = W.CONFIGS[name]
+    x = W.device_uniform(cfg.seed, 1, (cfg.nx + 2, cfg.ny + 2, cfg.nz + 2), 0.0, 1.0)
+    out = torch.empty((cfg.nx, cfg.ny, cfg.nz), dtype=torch.float32, device="cuda")
+    ms, wall = _events_ms(torch, lambda: mdh.mdh_stencil(x, out, cfg.c0, cfg.c1), steps, warmup)
+    nbytes = 4 * ((cfg.nx + 2) * (cfg.ny + 2) * (cfg.nz + 2) + cfg.nx * cfg.ny * cfg.nz)
+    gbs = nbytes / ms / 1e6
+    res = {
+        "value": nbytes / wall / 1e6, "unit": "GB/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "f32",
+        "kernel": "stencil_kernel",
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES.get(name)},
+        "algorithmic_bytes": nbytes,
+    }
+    if cpu:
+        import numpy as np
+
+        import oracle
+
+        xh = x.cpu().numpy()
+        best = None
+        for _ in range(3):
+            t0 = time.perf_counter()
+            oracle.jacobi3d(xh, cfg.c0, cfg.c1)
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+        res["cpu_baseline"] = {"value": nbytes / best / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": "whole %dx%dx%d grid, best of 3 sweeps (%.3f s)" % (cfg.nx, cfg.ny, cfg.nz, best)}
+        del xh, np
+    return res
+
+
+def bench_matmul(torch, mdh, W, name, steps, warmup, cpu):
+    cfg = W.CONFIGS[name]
+    sizes = (cfg.M, cfg.N, cfg.K)
+    a = W.device_uniform(cfg.seed, 1, (cfg.M, cfg.K), -1.0, 1.0)
+    b = W.device_uniform(cfg.seed, 2, (cfg.K, cfg.N), -1.0, 1.0)
+    c = torch.empty((cfg.M, cfg.N), dtype=torch.float32, device="cuda")
+    ws = _ws(torch, mdh, mdh.MDH_MATMUL, sizes)
+    ms, wall = _events_ms(torch, lambda: mdh.mdh_matmul(a, b, c, None, ws), steps, warmup)
+    flop = 2.0 * cfg.M * cfg.N * cfg.K
+    tf = flop / ms / 1e9
+    p = mdh.mdh_default_params(mdh.MDH_MATMUL, sizes)
+    res = {
+        "value": flop / wall / 1e6, "unit": "GFLOP/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "f32",
+        "kernel": "matmul_kernel" + (" + combine_sum_kernel" if p.prt[3][2] > 1 else ""),
+        "split_k": int(p.prt[3][2]),
+        "roofline": {"bound": "mfma", "achieved": tf, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tf / PEAK_FP32_MFMA_TFLOPS, "traffic": TRAFFIC_BYTES.get(name)},
+        "algorithmic_flop": flop,
+        "algorithmic_bytes": 4 * (cfg.M * cfg.K + cfg.K * cfg.N + cfg.M * cfg.N),
+    }
+    if cpu:
+        import oracle
+
+        rows = max(1, min(cfg.M, int(6e8 // (cfg.N * cfg.K))))
+        ah, bh = a[:rows].cpu().numpy(), b.cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.matmul(ah, bh)
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": 2.0 * rows * cfg.N * cfg.K / dt / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": "first %d rows of C (%.2f s)" % (rows, dt)}
+    return res
+
+
+def bench_mcc(torch, mdh, W, name, steps, warmup, cpu):
+    cfg = W.CONFIGS[name]
+    P = (cfg.H - cfg.R) // cfg.stride[0] + 1
+    Q = (cfg.W - cfg.S) // cfg.stride[1] + 1
+    x = W.device_normal(cfg.seed, 1, (cfg.N, cfg.H, cfg.W, cfg.C))
+    f = W.device_normal(cfg.seed, 2, (cfg.K, cfg.R, cfg.S, cfg.C))
+    o = torch.empty((cfg.N, P, Q, cfg.K), dtype=torch.float32, device="cuda")
+    ms, wall = _events_ms(torch, lambda: mdh.mdh_mcc(x, f, o, cfg.stride), steps, warmup)
+    flop = 2.0 * cfg.N * P * Q * cfg.K * cfg.C * cfg.R * cfg.S
+    tf = flop / ms / 1e9
+    res = {
+        "value": flop / wall / 1e6, "unit": "GFLOP/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "f32",
+        "kernel": "mcc_kernel",
+        "roofline": {"bound": "mfma", "achieved": tf, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tf / PEAK_FP32_MFMA_TFLOPS, "traffic": TRAFFIC_BYTES.get(name)},
+        "algorithmic_flop": flop,
+        "algorithmic_bytes": 4 * (x.numel() + f.numel() + o.numel()),
+    }
+    if cpu:
+        import numpy as np
+
+        import oracle
+
+        xh, fh = x[:1, : cfg.R + 3].cpu().numpy(), f.cpu().numpy()  # 4 output rows of image 0
+        t0 = time.perf_counter()
+        r = oracle.mcc(np.ascontiguousarray(xh), fh, cfg.stride)
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": 2.0 * r.size * cfg.C * cfg.R * cfg.S / dt / 1e9, "unit": "GFLOP/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "output rows p<%d of image 0 (%.2f s)" % (r.shape[1], dt)}
+    return res
+
+
+def bench_prl(torch, mdh, W, name, steps, warmup, cpu):
+    cfg = W.CONFIGS[name]
+    sizes = (cfg.nA, cfg.nB, cfg.nF)
+    alph = W.prl_alphabets(cfg.nF)
+    A = torch.stack([W.device_integers(cfg.seed, 1 + 2 * f, (cfg.nA,), 0, a - 1) for f, a in enumerate(alph)], 1).contiguous()
+    B = torch.stack([W.device_integers(cfg.seed, 2 + 2 * f, (cfg.nB,), 0, a - 1) for f, a in enumerate(alph)], 1).contiguous()
+    wp = W.device_integers(cfg.seed, 40, (cfg.nF,), 1, W.PRL_WEIGHT_MAX)
+    wm = W.device_integers(cfg.seed, 41, (cfg.nF,), -W.PRL_WEIGHT_MAX, 0)
+    s = torch.empty(cfg.nA, dtype=torch.int32, device="cuda")
+    i = torch.empty(cfg.nA, dtype=torch.int32, device="cuda")
+    ws = _ws(torch, mdh, mdh.MDH_CUSTOM_REDUCE, sizes)
+    ms, wall = _events_ms(torch, lambda: mdh.mdh_custom_reduce(A, B, wp, wm, s, i, None, ws), steps, warmup)
+    pairs = float(cfg.nA) * cfg.nB
+    tops = pairs * PRL_LANE_OPS_PER_PAIR / ms / 1e9
+    nbytes = 4 * (A.numel() + B.numel() + 2 * cfg.nF + 2 * cfg.nA)
+    res = {
+        "value": pairs / wall / 1e6, "unit": "Gpairs/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "i32",
+        "kernel": "prl_kernel + combine_maxidx_kernel",
+        "roofline": {"bound": "alu", "achieved": tops, "peak": PEAK_INT_VALU_TOPS, "unit": "Tlane-op/s",
+                     "frac": tops / PEAK_INT_VALU_TOPS, "traffic": TRAFFIC_BYTES.get(name)},
+        "lane_ops_per_pair": PRL_LANE_OPS_PER_PAIR,
+        "algorithmic_bytes": nbytes,
+        "hbm_GBs_algorithmic": nbytes / ms / 1e6,
+    }
+    if cpu:
+        import oracle
+
+        rows = list(range(0, cfg.nA, cfg.nA // 512))[:512]
+        Ah, Bh = A.cpu().numpy(), B.cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.custom_reduce_rows(Ah, Bh, wp.cpu().numpy(), wm.cpu().numpy(), rows)
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": len(rows) * cfg.nB / dt / 1e9, "unit": "Gpairs/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": "%d records of A against all of B (%.2f s)" % (len(rows), dt)}
+    return res
+
+
+BENCHES = {
+    "jacobi3d_512": bench_stencil,
+    "matmul_4096": bench_matmul,
+    "matmul_ts": bench_matmul,
+    "mcc_resnet": bench_mcc,
+    "prl_2p16_2p18": bench_prl,
+    "matmul_256": bench_matmul,
+}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="jacobi3d_512", choices=sorted(BENCHES))
+    ap.add_argument("--no-instances", action="store_true", help="measure only --workload")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="run a 512 MiB device copy first (reference kernel for --pmc byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+                         "use --gpus 1\n")
+        return 2
+
+    import torch
+
+    import paper_2405_05118_amd as mdh
+    from paper_2405_05118_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py needs the GPU (and libmdh.so); there is no CPU fallback\n")
+        return 3
+    torch.cuda.set_device(0)
+    mdh.lib()
+
+    if args.calibration_copy:
+        # a plain device copy of known size (512 MiB read + 512 MiB written), outside every timed
+        # region: the reference the FETCH_SIZE / WRITE_SIZE counters of a --pmc run are scaled by
+        src = torch.ones(128 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+
+    torch.cuda.synchronize()
+    head = BENCHES[args.workload](torch, mdh, W, args.workload, args.steps, args.warmup, not args.no_cpu)
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+
+    line = {
+        "metric": METRIC,
+        "value": head["value"],
+        "unit": head["unit"],
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": head["dtype"],
+        "data": "synthetic",
+        "config": {"workload": args.workload, "params": "library default"},
+        "roofline": head["roofline"],
+    }
+    if "cpu_baseline" in head:
+        line["cpu_baseline"] = head["cpu_baseline"]
+    line["detail"] = {k: v for k, v in head.items() if k not in ("roofline", "cpu_baseline", "value", "unit")}
+
+    if not args.no_instances:
+        inst = {}
+        for name, fn in BENCHES.items():
+            if name == args.workload:
+                continue
+            steps = max(5, min(args.steps, 30 if name in ("mcc_resnet", "prl_2p16_2p18") else 100))
+            inst[name] = fn(torch, mdh, W, name, steps, max(2, min(args.warmup, 5)), not args.no_cpu)
+            torch.cuda.synchronize()
+            torch.cuda.empty_cache()
+        line["instances"] = inst
+
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -127,6 +127,9 @@ typedef struct mdh_tile_params {
 /* Human-readable text for a status code; never NULL. */
 const char* mdh_strerror(mdh_status s);
 
+/* Runtime's text for the error behind the calling thread's most recent MDH_ERR_LAUNCH. */
+const char* mdh_last_launch_error(void);
+
 /* Library version, "major.minor". */
 const char* mdh_version(void);
 

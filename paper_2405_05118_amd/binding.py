@@ -20,7 +20,7 @@ L_HBM, L_LDS, L_VGPR, L_WG, L_WAVE, L_LANE = range(6)
 EXPORTS = (
     "mdh_strerror", "mdh_version", "mdh_part_offset", "mdh_default_params", "mdh_validate_params",
     "mdh_workspace_size", "mdh_matmul", "mdh_stencil", "mdh_mcc", "mdh_custom_reduce", "mdh_tune",
-    "mdh_num_candidates", "mdh_candidate",
+    "mdh_num_candidates", "mdh_candidate", "mdh_last_launch_error",
 )
 
 
@@ -60,7 +60,10 @@ class TileParams(ctypes.Structure):
 class MdhError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__("%s: %s (status %d)" % (where, mdh_strerror(status), status))
+        msg = "%s: %s (status %d)" % (where, mdh_strerror(status), status)
+        if status == 7:
+            msg += " [" + lib().mdh_last_launch_error().decode() + "]"
+        super().__init__(msg)
 
 
 _lib = None
@@ -75,6 +78,11 @@ def lib() -> ctypes.CDLL:
                 "libmdh.so is not built: run `python -m paper_2405_05118_amd.build` "
                 "(or __graft_entry__.build()); there is no CPU fallback"
             )
+        # torch ships its own copy of the HIP runtime; it has to be the first one the process
+        # loads so that libmdh.so binds to the runtime that owns torch's device memory and streams
+        # (loaded the other way round, launches fail with "no ROCm-capable device")
+        import torch  # noqa: F401
+
         L = ctypes.CDLL(LIB_PATH)
         i64, i32, vp, sz, f32 = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float
         pp = ctypes.POINTER(TileParams)
@@ -82,6 +90,7 @@ def lib() -> ctypes.CDLL:
         L.mdh_strerror.restype = ctypes.c_char_p
         L.mdh_strerror.argtypes = [ctypes.c_int]
         L.mdh_version.restype = ctypes.c_char_p
+        L.mdh_last_launch_error.restype = ctypes.c_char_p
         L.mdh_part_offset.argtypes = [i64, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), p64, p64]
         L.mdh_default_params.argtypes = [ctypes.c_int, p64, pp]
         L.mdh_validate_params.argtypes = [ctypes.c_int, p64, pp]

@@ -14,7 +14,13 @@ bool too_big(int64_t n) { return n < 0 || n > kMaxElems; }
 
 }  // namespace
 
+namespace mdh {
+thread_local hipError_t g_last_launch_error = hipSuccess;
+}
+
 extern "C" {
+
+const char* mdh_last_launch_error(void) { return hipGetErrorString(mdh::g_last_launch_error); }
 
 mdh_status mdh_matmul(int64_t M, int64_t N, int64_t K, const float* A, const float* B, float* C,
                       const mdh_tile_params* params, void* workspace, size_t workspace_bytes,

@@ -75,8 +75,12 @@ mdh_status launch_prl(const PrlPlan& pl, int64_t nA, int64_t nB, int nF, const i
 // process leave harmless codes there (an event query that is not ready yet, for instance):
 // clear it before a launch so that the status read after the launch is that launch's own.
 inline void clear_stale_error() { (void)hipGetLastError(); }
+extern thread_local hipError_t g_last_launch_error;
 inline mdh_status launch_status() {
-  return hipGetLastError() == hipSuccess ? MDH_OK : MDH_ERR_LAUNCH;
+  const hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return MDH_OK;
+  g_last_launch_error = e;
+  return MDH_ERR_LAUNCH;
 }
 
 }  // namespace mdh

@@ -118,10 +118,10 @@ static StencilPlan stencil_default(const int64_t* s) {
   pl.TY = 2;
   pl.LK = s[2] <= 256 ? 64 : 128;
   if (pl.LK == 64) pl.TY = 4;
-  pl.SI = 32;
+  pl.SI = 64;
   const int TJ = pl.TY * pl.RJ, KT = pl.LK * 4;
   // keep at least ~1024 workgroups in flight when the grid is small
-  while (pl.SI > 4 && cdiv(s[0], pl.SI) * cdiv(s[1], TJ) * cdiv(s[2], KT) < 1024) pl.SI /= 2;
+  while (pl.SI > 4 && cdiv(s[0], pl.SI) * cdiv(s[1], TJ) * cdiv(s[2], KT) < 512) pl.SI /= 2;
   if (s[0] > 0 && pl.SI > s[0]) pl.SI = (int)s[0];
   pl.ragged = (s[0] % pl.SI) || (s[1] % TJ) || (s[2] % KT);
   return pl;
@@ -224,14 +224,14 @@ static int gemm_ragged(const int64_t* s, const GemmPlan& pl) {
 
 static GemmPlan gemm_default(const int64_t* s) {
   const int64_t M = s[0], N = s[1], K = s[2];
-  GemmPlan pl{128, 128, 16, 64, 64, 1, 0};
+  GemmPlan pl{128, 128, 32, 64, 64, 1, 0};
   if (N <= 64 || M <= 64) pl = GemmPlan{128, 64, 16, 64, 32, 1, 0};
   if (M <= 64 && N <= 64) pl = GemmPlan{64, 64, 16, 32, 32, 1, 0};
   if (M > 64 && N > 64 && M * N <= 512 * 512) pl = GemmPlan{64, 64, 16, 32, 32, 1, 0};
   // split the reduction dimension over workgroups until the chip (256 CUs) is covered
   const int64_t tiles = cdiv(M, pl.BM) * cdiv(N, pl.BN);
   int S = 1;
-  while (tiles * S < 1024 && S < 64 && K / (S * 2) >= 4 * pl.BK) S *= 2;
+  while (tiles * S < 1024 && S < 64 && K / (S * 2) >= pl.BK) S *= 2;
   pl.S = S;
   pl.ragged = gemm_ragged(s, pl);
   return pl;
@@ -433,11 +433,11 @@ static int prl_ragged(const int64_t* s, const PrlPlan& pl) {
 }
 
 static PrlPlan prl_default(const int64_t* s) {
-  PrlPlan pl{2, 4, 1, 1, 0};
+  PrlPlan pl{2, 8, 1, 1, 0};
   const int64_t wgs_a = cdiv(s[0], (int64_t)pl.WA * 64 * pl.RA);
   int S = 1;
   // 256 CUs x 4 SIMDs x 2 wavefronts each: split B over workgroups until the chip is covered
-  while (wgs_a * S * pl.WB * pl.WA < 4096 && S < 256 && s[1] / (2ll * S * pl.WB) >= 256) S *= 2;
+  while (wgs_a * S * pl.WB * pl.WA < 16384 && S < 256 && s[1] / (2ll * S * pl.WB) >= 256) S *= 2;
   pl.S = S;
   pl.ragged = prl_ragged(s, pl);
   return pl;

@@ -168,3 +168,80 @@ def prl_inputs(cfg: PrlCfg):
     w_agree = integers(cfg.seed, 40, (cfg.nF,), 1, PRL_WEIGHT_MAX)
     w_disagree = integers(cfg.seed, 41, (cfg.nF,), -PRL_WEIGHT_MAX, 0)
     return A, B, w_agree, w_disagree
+
+
+# ---------------------------------------------------------------------------
+# The same generator on the GPU (torch integer ops), for filling large benchmark
+# buffers without a long host loop.  uniform and integers reproduce the numpy
+# versions bit for bit (integer arithmetic mod 2^64, then exactly rounded fp64
+# multiply/add); normal may differ in the last place (device log/cos/sqrt).
+# ---------------------------------------------------------------------------
+
+
+def _s64(c: int) -> int:
+    c &= 0xFFFFFFFFFFFFFFFF
+    return c - (1 << 64) if c >= (1 << 63) else c
+
+
+def _lsr(x, k: int):
+    return (x >> k) & ((1 << (64 - k)) - 1)
+
+
+def _splitmix64_t(x):
+    z = x + _s64(0x9E3779B97F4A7C15)
+    z = (z ^ _lsr(z, 30)) * _s64(0xBF58476D1CE4E5B9)
+    z = (z ^ _lsr(z, 27)) * _s64(0x94D049BB133111EB)
+    return z ^ _lsr(z, 31)
+
+
+def _draw_t(seed, tid, start, count, device, stride=1, phase=0):
+    import torch
+
+    base = _s64(seed ^ (tid << 56))
+    n = torch.arange(start, start + count, dtype=torch.int64, device=device)
+    return _splitmix64_t(n * stride + (base + phase))
+
+
+def _unit_t(x):
+    import torch
+
+    return _lsr(x, 11).to(torch.float64) * (1.0 / 9007199254740992.0)
+
+
+def device_uniform(seed: int, tid: int, shape, lo: float, hi: float, device="cuda"):
+    import torch
+
+    total = int(np.prod(shape))
+    out = torch.empty(total, dtype=torch.float32, device=device)
+    step = 1 << 24
+    for s in range(0, total, step):
+        c = min(step, total - s)
+        out[s : s + c] = (lo + (hi - lo) * _unit_t(_draw_t(seed, tid, s, c, device))).to(torch.float32)
+    return out.reshape(shape)
+
+
+def device_normal(seed: int, tid: int, shape, device="cuda"):
+    import math
+
+    import torch
+
+    total = int(np.prod(shape))
+    out = torch.empty(total, dtype=torch.float32, device=device)
+    step = 1 << 24
+    for s in range(0, total, step):
+        c = min(step, total - s)
+        u1 = 1.0 - _unit_t(_draw_t(seed, tid, s, c, device, stride=2, phase=0))
+        u2 = _unit_t(_draw_t(seed, tid, s, c, device, stride=2, phase=1))
+        out[s : s + c] = (torch.sqrt(-2.0 * torch.log(u1)) * torch.cos(2.0 * math.pi * u2)).to(torch.float32)
+    return out.reshape(shape)
+
+
+def device_integers(seed: int, tid: int, shape, lo: int, hi: int, device="cuda"):
+    import torch
+
+    total = int(np.prod(shape))
+    span = hi - lo + 1
+    x = _draw_t(seed, tid, 0, total, device)
+    # unsigned x mod span from the signed representation: split off the top bit
+    r = (_lsr(x, 1) % span * 2 + (x & 1)) % span
+    return (r + lo).to(torch.int32).reshape(shape)
