@@ -100,17 +100,29 @@ def bench_stencil(torch, mdh, W, name, steps, warmup, cpu):
     return res
 
 
-def bench_matmul(torch, mdh, W, name, steps, warmup, cpu):
+def _split_variant(mdh, sizes, S):
+    """The default tile configuration with the reduction dimension split S ways over workgroups."""
+    d = mdh.mdh_default_params(mdh.MDH_MATMUL, sizes)
+    for i in range(mdh.mdh_num_candidates(mdh.MDH_MATMUL, sizes)):
+        p = mdh.mdh_candidate(mdh.MDH_MATMUL, sizes, i)
+        same_tile = all(list(p.prt[l][:3]) == list(d.prt[l][:3]) for l in (1, 2, 4, 5))
+        if same_tile and p.prt[3][2] == S:
+            return p
+    return None
+
+
+def bench_matmul(torch, mdh, W, name, steps, warmup, cpu, split=None):
     cfg = W.CONFIGS[name]
     sizes = (cfg.M, cfg.N, cfg.K)
     a = W.device_uniform(cfg.seed, 1, (cfg.M, cfg.K), -1.0, 1.0)
     b = W.device_uniform(cfg.seed, 2, (cfg.K, cfg.N), -1.0, 1.0)
     c = torch.empty((cfg.M, cfg.N), dtype=torch.float32, device="cuda")
-    ws = _ws(torch, mdh, mdh.MDH_MATMUL, sizes)
-    ms, wall = _events_ms(torch, lambda: mdh.mdh_matmul(a, b, c, None, ws), steps, warmup)
+    p = mdh.mdh_default_params(mdh.MDH_MATMUL, sizes) if split is None else _split_variant(mdh, sizes, split)
+    nws = mdh.mdh_workspace_size(mdh.MDH_MATMUL, sizes, p)
+    ws = torch.empty(max(nws, 4) // 4, dtype=torch.int32, device="cuda") if nws else None
+    ms, wall = _events_ms(torch, lambda: mdh.mdh_matmul(a, b, c, p, ws), steps, warmup)
     flop = 2.0 * cfg.M * cfg.N * cfg.K
     tf = flop / ms / 1e9
-    p = mdh.mdh_default_params(mdh.MDH_MATMUL, sizes)
     res = {
         "value": flop / wall / 1e6, "unit": "GFLOP/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "f32",
         "kernel": "matmul_kernel" + (" + combine_sum_kernel" if p.prt[3][2] > 1 else ""),
@@ -285,6 +297,11 @@ def main() -> int:
             inst[name] = fn(torch, mdh, W, name, steps, max(2, min(args.warmup, 5)), not args.no_cpu)
             torch.cuda.synchronize()
             torch.cuda.empty_cache()
+        # the tall-skinny MatMul again with the reduction dimension split over workgroups
+        # (partial results in a device-memory workspace + second-pass combine)
+        inst["matmul_ts_split_k4"] = bench_matmul(torch, mdh, W, "matmul_ts", 100, 5, False, split=4)
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
         line["instances"] = inst
 
     print(json.dumps(line))

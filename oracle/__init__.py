@@ -71,6 +71,25 @@ def num_threads() -> int:
     return int(_load().oracle_num_threads())
 
 
+def dot(x, y):
+    x, y = _f32(x).ravel(), _f32(y).ravel()
+    assert x.shape == y.shape
+    out = ctypes.c_double()
+    outabs = ctypes.c_double()
+    _load().oracle_dot(_i64(len(x)), _p(x), _p(y), ctypes.byref(out), ctypes.byref(outabs))
+    return out.value, outabs.value
+
+
+def matvec(A, x, with_abs: bool = False):
+    A, x = _f32(A), _f32(x).ravel()
+    M, K = A.shape
+    assert len(x) == K
+    y = np.empty(M, dtype=np.float64)
+    yabs = np.empty(M, dtype=np.float64) if with_abs else None
+    _load().oracle_matvec(_i64(M), _i64(K), _p(A), _p(x), _p(y), _p(yabs) if with_abs else None)
+    return (y, yabs) if with_abs else y
+
+
 def matmul(A, B, with_abs: bool = False):
     A, B = _f32(A), _f32(B)
     M, K = A.shape

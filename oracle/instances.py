@@ -17,6 +17,23 @@ def _add(x, y):
     return x + y
 
 
+def dot(x, y):
+    """md_hom(*, (+)) over (k); output view (0)->() (a scalar)."""
+    iv = H.inp_view([[lambda k: (k,)], [lambda k: (k,)]])
+    h = H.md_hom(lambda t: t[0] * t[1], (H.pointwise(0, _add),))
+    (o,) = H.out_view([[lambda k: ()]])(h(iv([x, y], [range(len(x))])))
+    return o[()]
+
+
+def matvec(A, x):
+    """md_hom(*, (++,+)) over (i,k); views (i,k)->A[i,k], (i,k)->x[k]; (i,0)->y[i]."""
+    M, K = len(A), len(x)
+    iv = H.inp_view([[lambda i, k: (i, k)], [lambda i, k: (k,)]])
+    h = H.md_hom(lambda t: t[0] * t[1], (H.concat(0), H.pointwise(1, _add)))
+    (y,) = H.out_view([[lambda i, k: (i,)]])(h(iv([A, x], [range(M), range(K)])))
+    return [y[(i,)] for i in range(M)]
+
+
 def matmul(A, B):
     """md_hom(*, (++,++,+)); views (i,j,k)->A[i,k], (i,j,k)->B[k,j]; (i,j,0)->C[i,j]
     (Section "Examples", Subfigure 1).  A, B nested lists; returns nested list C."""

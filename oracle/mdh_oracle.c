@@ -31,6 +31,35 @@
 #include <omp.h>
 #endif
 
+/* ---- Dot: md_hom(*, (+)) over (k); views (k)->x[k], (k)->y[k]; (0)->out (a scalar)
+ * (Section "Examples", Subfigure 1, first routine).  outabs (nullable) receives sum_k |x*y|. */
+void oracle_dot(int64_t K, const float* x, const float* y, double* out, double* outabs) {
+  double acc = 0.0, aabs = 0.0;
+  for (int64_t k = 0; k < K; ++k) {
+    double t = (double)x[k] * (double)y[k];
+    acc += t;
+    aabs += fabs(t);
+  }
+  *out = acc;
+  if (outabs) *outabs = aabs;
+}
+
+/* ---- MatVec: md_hom(*, (++,+)) over (i,k); views (i,k)->A[i,k], (i,k)->x[k]; (i,0)->y[i]
+ * (the paper's introductory example and the worked low-level example). */
+void oracle_matvec(int64_t M, int64_t K, const float* A, const float* x, double* y, double* yabs) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < M; ++i) {
+    double acc = 0.0, aabs = 0.0;
+    for (int64_t k = 0; k < K; ++k) {
+      double t = (double)A[i * K + k] * (double)x[k];
+      acc += t;
+      aabs += fabs(t);
+    }
+    y[i] = acc;
+    if (yabs) yabs[i] = aabs;
+  }
+}
+
 /* ---- MatMul: md_hom(*, (++,++,+)), views (i,j,k)->A[i,k], B[k,j]; (i,j,0)->C[i,j] ----
  * (Section "Examples", Subfigure 1).  Cabs (nullable) receives sum_k |A[i,k]*B[k,j]|,
  * the denominator of the componentwise error measure the tests use. */

@@ -106,23 +106,33 @@ __device__ __forceinline__ void mcc_tile(const float* __restrict__ in, const flo
     }
   };
   // lanes 0-31 of an MFMA supply channels {cc..cc+3}, lanes 32-63 {cc+4..cc+7} of both operands
+  struct Frag {
+    f4 a[Cf::MI], b[Cf::NI];
+  };
+  const int a_row = sh * PW * Cf::PC;  // LDS distance between consecutive output rows of the patch
+  auto load_frag = [&](Frag& f, const float* as, const float* bs, int cc) {
+#pragma unroll
+    for (int mi = 0; mi < Cf::MI; ++mi) f.a[mi] = *(const f4*)(as + mi * a_row + cc);
+#pragma unroll
+    for (int ni = 0; ni < Cf::NI; ++ni) f.b[ni] = *(const f4*)(bs + ni * 32 * Cf::PC + cc);
+  };
+  auto mma = [&](const Frag& f) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int mi = 0; mi < Cf::MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < Cf::NI; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[mi][t], f.b[ni][t], acc[mi][ni], 0, 0, 0);
+  };
   auto compute = [&](const float* fst, int r, int s) {
     const float* as = ps + (((wm * Cf::MI) * sh + r) * PW + l32 * sw + s) * Cf::PC + lh * 4;
     const float* bs = fst + (wn * WN + l32) * Cf::PC + lh * 4;
 #pragma unroll
     for (int cc = 0; cc < CK; cc += 8) {
-      f4 af[Cf::MI], bf[Cf::NI];
-#pragma unroll
-      for (int mi = 0; mi < Cf::MI; ++mi) af[mi] = *(const f4*)(as + mi * sh * PW * Cf::PC + cc);
-#pragma unroll
-      for (int ni = 0; ni < Cf::NI; ++ni) bf[ni] = *(const f4*)(bs + ni * 32 * Cf::PC + cc);
-#pragma unroll
-      for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int mi = 0; mi < Cf::MI; ++mi)
-#pragma unroll
-          for (int ni = 0; ni < Cf::NI; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi][t], bf[ni][t], acc[mi][ni], 0, 0, 0);
+      Frag f;
+      load_frag(f, as, bs, cc);
+      mma(f);
     }
   };
 

@@ -115,13 +115,12 @@ void params_from_plan(const int64_t* sizes, const StencilPlan& pl, mdh_tile_para
 static StencilPlan stencil_default(const int64_t* s) {
   StencilPlan pl;
   pl.RJ = 4;
-  pl.TY = 2;
+  pl.TY = 4;
   pl.LK = s[2] <= 256 ? 64 : 128;
-  if (pl.LK == 64) pl.TY = 4;
   pl.SI = 64;
   const int TJ = pl.TY * pl.RJ, KT = pl.LK * 4;
-  // keep at least ~1024 workgroups in flight when the grid is small
-  while (pl.SI > 4 && cdiv(s[0], pl.SI) * cdiv(s[1], TJ) * cdiv(s[2], KT) < 512) pl.SI /= 2;
+  // keep at least one workgroup per compute unit when the grid is small
+  while (pl.SI > 4 && cdiv(s[0], pl.SI) * cdiv(s[1], TJ) * cdiv(s[2], KT) < 256) pl.SI /= 2;
   if (s[0] > 0 && pl.SI > s[0]) pl.SI = (int)s[0];
   pl.ragged = (s[0] % pl.SI) || (s[1] % TJ) || (s[2] % KT);
   return pl;
@@ -180,6 +179,8 @@ struct GemmInst {
 static const GemmInst kGemmMenu[] = {
     {128, 128, 16, 64, 64}, {256, 128, 16, 128, 64}, {128, 64, 16, 64, 32},
     {64, 64, 16, 32, 32},   {128, 128, 32, 64, 64},  {256, 128, 32, 128, 64},
+    {256, 64, 16, 64, 64},  {256, 64, 32, 64, 64},   {128, 64, 32, 64, 32},
+    {128, 64, 64, 64, 32},  {256, 64, 64, 64, 64},   {64, 64, 32, 32, 32},
 };
 
 static bool gemm_inst(const GemmPlan& pl) {
@@ -225,13 +226,14 @@ static int gemm_ragged(const int64_t* s, const GemmPlan& pl) {
 static GemmPlan gemm_default(const int64_t* s) {
   const int64_t M = s[0], N = s[1], K = s[2];
   GemmPlan pl{128, 128, 32, 64, 64, 1, 0};
-  if (N <= 64 || M <= 64) pl = GemmPlan{128, 64, 16, 64, 32, 1, 0};
+  if (N <= 64 || M <= 64) pl = GemmPlan{128, 64, 32, 64, 32, 1, 0};
   if (M <= 64 && N <= 64) pl = GemmPlan{64, 64, 16, 32, 32, 1, 0};
   if (M > 64 && N > 64 && M * N <= 512 * 512) pl = GemmPlan{64, 64, 16, 32, 32, 1, 0};
-  // split the reduction dimension over workgroups until the chip (256 CUs) is covered
+  // split the reduction dimension over workgroups until every compute unit (256) has two
+  // workgroups; beyond that the extra pass over the partial results costs more than it hides
   const int64_t tiles = cdiv(M, pl.BM) * cdiv(N, pl.BN);
   int S = 1;
-  while (tiles * S < 1024 && S < 64 && K / (S * 2) >= pl.BK) S *= 2;
+  while (tiles * S < 512 && S < 64 && K / (S * 2) >= pl.BK) S *= 2;
   pl.S = S;
   pl.ragged = gemm_ragged(s, pl);
   return pl;
@@ -242,6 +244,7 @@ int matmul_candidates(const int64_t* s, GemmPlan* out, int cap) {
   auto push = [&](GemmPlan pl) {
     if (n >= cap) return;
     if (pl.S > 1 && s[2] / pl.S < pl.BK) return;
+    if (gemm_lds_bytes(pl.BM, pl.BN, pl.BK) > kLdsBytesPerWG) return;
     pl.ragged = gemm_ragged(s, pl);
     for (int i = 0; i < n; ++i)
       if (out[i].BM == pl.BM && out[i].BN == pl.BN && out[i].BK == pl.BK && out[i].WM == pl.WM &&

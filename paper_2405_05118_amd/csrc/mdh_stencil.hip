@@ -21,6 +21,22 @@ namespace {
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
 
+// Streaming accesses: the centre rows of the input and the whole output are touched once per
+// kernel.  MDH_STENCIL_NT bit 0: non-temporal stores, bit 1: non-temporal centre-row loads.
+#ifndef MDH_STENCIL_NT
+#define MDH_STENCIL_NT 3
+#endif
+__device__ __forceinline__ f4 ld_stream(const float* p) {
+  if (MDH_STENCIL_NT & 2) return __builtin_nontemporal_load((const f4u*)p);
+  return *(const f4u*)p;
+}
+__device__ __forceinline__ void st_stream(float* p, f4 v) {
+  if (MDH_STENCIL_NT & 1)
+    __builtin_nontemporal_store(v, (f4u*)p);
+  else
+    *(f4u*)p = v;
+}
+
 template <int RJ, int TY, int LK>
 struct StencilCfg {
   static constexpr int TJ = TY * RJ;
@@ -58,7 +74,7 @@ __device__ __forceinline__ void stencil_tile(const float* __restrict__ in, float
 #pragma unroll
     for (int jj = 0; jj < RJ; ++jj) {
       if (!GUARD) {
-        b.v[jj] = *(const f4u*)(base + jj * sy);
+        b.v[jj] = ld_stream(base + jj * sy);
       } else {
         // guard on the INPUT coordinates (row j0+jj+1 <= ny+1, column k0+e+1 <= nz+1): the
         // cells just outside a ragged tile's valid outputs are still neighbours of valid cells
@@ -84,7 +100,7 @@ __device__ __forceinline__ void stencil_tile(const float* __restrict__ in, float
         const int jr = jt0 + (side ? C::TJ + 1 : 0);  // input row
         const float* p = pl + (int64_t)jr * sy + (k0 + 1);
         if (!GUARD) {
-          t = *(const f4u*)p;
+          t = *(const f4u*)p;  // halo rows are shared with the neighbouring workgroup: keep them cached
         } else if (jr < ny + 2) {
 #pragma unroll
           for (int e = 0; e < 4; ++e)
@@ -158,7 +174,7 @@ __device__ __forceinline__ void stencil_tile(const float* __restrict__ in, float
 #pragma unroll
       for (int e = 0; e < 4; ++e) r[e] = __builtin_fmaf(c0, cc.v[jj][e], c1 * nb[e]);
       if (!GUARD) {
-        *(f4u*)(orow + (int64_t)jj * nz) = r;
+        st_stream(orow + (int64_t)jj * nz, r);
       } else if (j0 + jj < ny) {
 #pragma unroll
         for (int e = 0; e < 4; ++e)

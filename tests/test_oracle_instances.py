@@ -306,3 +306,46 @@ def test_custom_reduce_permuting_B_only_moves_indices():
     assert np.array_equal(scores.max(1), s)
     assert np.array_equal(scores.argmax(1), i)  # numpy's argmax returns the first maximum
     assert np.array_equal(scores[np.arange(25), perm[i2]], s)
+
+
+# --------------------------------------------------------------------------- Dot / MatVec
+
+
+def test_dot_and_matvec_bruteforce_vs_generic():
+    x, y = _small_ints((7,)), _small_ints((7,))
+    d, dabs = oracle.dot(x, y)
+    assert d == G.dot([int(v) for v in x], [int(v) for v in y])
+    assert dabs == float(np.abs(x.astype(np.float64) * y).sum())
+    A = _small_ints((4, 7))
+    got, gabs = oracle.matvec(A, x, with_abs=True)
+    assert got.tolist() == G.matvec([[int(v) for v in r] for r in A], [int(v) for v in x])
+    assert np.array_equal(gabs, np.abs(A.astype(np.float64)) @ np.abs(x.astype(np.float64)))
+
+
+def test_dot_and_matvec_closed_forms_and_reductions_to_matmul():
+    K = 1000
+    ones = np.ones(K, np.float32)
+    assert oracle.dot(ones, ones)[0] == K
+    ramp = np.arange(K, dtype=np.float32)
+    assert oracle.dot(ramp, ones)[0] == K * (K - 1) / 2
+    # a unit vector picks a column of A (fails if A is read transposed)
+    A = rng.uniform(-1, 1, (9, 13)).astype(np.float32)
+    e = np.zeros(13, np.float32)
+    e[5] = 1
+    assert np.array_equal(oracle.matvec(A, e), A[:, 5].astype(np.float64))
+    # MatVec is MatMul with N = 1, Dot is MatVec with M = 1
+    x = rng.uniform(-1, 1, 13).astype(np.float32)
+    assert np.array_equal(oracle.matvec(A, x), oracle.matmul(A, x.reshape(13, 1)).ravel())
+    assert oracle.dot(A[2], x)[0] == oracle.matvec(A[2:3], x)[0]
+    assert np.allclose(oracle.matvec(A, x), A.astype(np.float64) @ x.astype(np.float64), rtol=0, atol=1e-14)
+
+
+def test_dot_and_matvec_split_property():
+    A = rng.uniform(-1, 1, (6, 40)).astype(np.float32)
+    x = rng.uniform(-1, 1, 40).astype(np.float32)
+    whole = oracle.matvec(A, x)
+    assert np.array_equal(np.concatenate([oracle.matvec(A[:2], x), oracle.matvec(A[2:], x)]), whole)
+    parts = oracle.matvec(np.ascontiguousarray(A[:, :17]), x[:17]) + oracle.matvec(np.ascontiguousarray(A[:, 17:]), x[17:])
+    assert np.allclose(parts, whole, rtol=0, atol=1e-14)
+    d = oracle.dot(A[0], x)[0]
+    assert abs(oracle.dot(A[0, :9], x[:9])[0] + oracle.dot(A[0, 9:], x[9:])[0] - d) <= 1e-14

@@ -14,6 +14,9 @@ SRC = os.path.join(os.path.dirname(oracle.__file__), "mdh_oracle.c")
 
 # (name, text in the source, replacement)
 MUTANTS = [
+    ("dot_drops_last", "for (int64_t k = 0; k < K; ++k) {\n    double t = (double)x[k] * (double)y[k];", "for (int64_t k = 0; k < K - 1; ++k) {\n    double t = (double)x[k] * (double)y[k];"),
+    ("matvec_x_indexed_by_row", "(double)A[i * K + k] * (double)x[k]", "(double)A[i * K + k] * (double)x[(k + i) % K]"),
+    ("matvec_abs_forgotten", "aabs += fabs(t);\n    }\n    y[i] = acc;", "aabs += t;\n    }\n    y[i] = acc;"),
     ("matmul_B_column_mirrored", "(double)B[k * N + j];\n        acc += t;\n        aabs += fabs(t);\n      }\n      C[i * N + j]",
      "(double)B[k * N + (N - 1 - j)];\n        acc += t;\n        aabs += fabs(t);\n      }\n      C[i * N + j]"),
     ("matmul_k_mismatched", "double t = (double)A[i * K + k] * (double)B[k * N + j];\n        acc += t;\n        aabs += fabs(t);\n      }\n      C[i * N + j]",
