@@ -215,7 +215,69 @@ def bench_prl(torch, mdh, W, name, steps, warmup, cpu):
     return res
 
 
+def bench_dot(torch, mdh, W, name, steps, warmup, cpu):
+    K = 1 << 28
+    seed = W.SEED_BASE + 7
+    x = W.device_uniform(seed, 1, (K,), -1.0, 1.0)
+    y = W.device_uniform(seed, 2, (K,), -1.0, 1.0)
+    out = torch.empty(1, dtype=torch.float32, device="cuda")
+    ws = _ws(torch, mdh, mdh.MDH_DOT, (K,))
+    ms, wall = _events_ms(torch, lambda: mdh.mdh_dot(x, y, out, None, ws), steps, warmup)
+    nbytes = 8 * K
+    gbs = nbytes / ms / 1e6
+    res = {
+        "value": nbytes / wall / 1e6, "unit": "GB/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "f32",
+        "kernel": "dot_kernel + dot_combine_kernel", "K": K,
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES.get(name)},
+        "algorithmic_bytes": nbytes,
+    }
+    if cpu:
+        import oracle
+
+        n = 1 << 26
+        xh, yh = x[:n].cpu().numpy(), y[:n].cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.dot(xh, yh)
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": 8 * n / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": "first 2^26 elements (%.2f s; the scalar reduction is sequential)" % dt}
+    return res
+
+
+def bench_matvec(torch, mdh, W, name, steps, warmup, cpu):
+    M = K = 16384
+    seed = W.SEED_BASE + 8
+    A = W.device_uniform(seed, 1, (M, K), -1.0, 1.0)
+    x = W.device_uniform(seed, 2, (K,), -1.0, 1.0)
+    y = torch.empty(M, dtype=torch.float32, device="cuda")
+    ws = _ws(torch, mdh, mdh.MDH_MATVEC, (M, K))
+    ms, wall = _events_ms(torch, lambda: mdh.mdh_matvec(A, x, y, None, ws), steps, warmup)
+    nbytes = 4 * (M * K + K + M)
+    gbs = nbytes / ms / 1e6
+    res = {
+        "value": nbytes / wall / 1e6, "unit": "GB/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "f32",
+        "kernel": "matvec_kernel", "M": M, "K": K,
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES.get(name)},
+        "algorithmic_bytes": nbytes,
+    }
+    if cpu:
+        import oracle
+
+        rows = 4096
+        Ah, xh = A[:rows].cpu().numpy(), x.cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.matvec(Ah, xh)
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": 4 * rows * K / dt / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": "first %d rows (%.2f s)" % (rows, dt)}
+    return res
+
+
 BENCHES = {
+    "dot_2p28": bench_dot,
+    "matvec_16384": bench_matvec,
     "jacobi3d_512": bench_stencil,
     "matmul_4096": bench_matmul,
     "matmul_ts": bench_matmul,

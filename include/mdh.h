@@ -56,7 +56,9 @@ typedef enum mdh_instance {
   MDH_MATMUL = 0,        /* md_hom(*, (++, ++, +)),            dims (i, j, k)              */
   MDH_STENCIL = 1,       /* md_hom(J_3D, (++, ++, ++)),        dims (i, j, k)              */
   MDH_MCC = 2,           /* md_hom(*, (++,++,++,++, +,+,+)),   dims (n, p, q, k, c, r, s)  */
-  MDH_CUSTOM_REDUCE = 3  /* md_hom(wght, (++, max_idx)),       dims (a, b)                 */
+  MDH_CUSTOM_REDUCE = 3, /* md_hom(wght, (++, max_idx)),       dims (a, b)                 */
+  MDH_DOT = 4,           /* md_hom(*, (+)),                    dims (k)                    */
+  MDH_MATVEC = 5         /* md_hom(*, (++, +)),                dims (i, k)                 */
 } mdh_instance;
 
 /*
@@ -237,6 +239,32 @@ mdh_status mdh_custom_reduce(int64_t nA, int64_t nB, int32_t nF, const int32_t* 
                              int32_t* out_score, int32_t* out_index,
                              const mdh_tile_params* params, void* workspace,
                              size_t workspace_bytes, void* stream);
+
+/*
+ * Dot product: out = sum_k x[k] * y[k]  =  md_hom(*, (+)) over (k) with output
+ * view (0) -> the scalar `out` (paper: Section "Examples", Subfigure 1, first
+ * routine).  The only dimension is a reduction: it is split over lanes
+ * (combined across the wavefront in registers), wavefronts (combined in LDS)
+ * and, if prt[MDH_L_WG][k] = S > 1, workgroups (S partial sums in `workspace`,
+ * S floats, combined by a second kernel in ascending part order).
+ *   x, y: K fp32 each, device; out: 1 fp32, device.  K >= 1.
+ */
+mdh_status mdh_dot(int64_t K, const float* x, const float* y, float* out,
+                   const mdh_tile_params* params, void* workspace, size_t workspace_bytes,
+                   void* stream);
+
+/*
+ * Matrix-vector product: y[i] = sum_k A[i,k] * x[k]  =  md_hom(*, (++, +)) over
+ * (i,k) with views (i,k)->A[i,k], (i,k)->x[k], (i,0)->y[i] (paper: the
+ * introductory example, and the worked example of Section "Low-Level
+ * Representation").  k is the contiguous dimension of A and runs over the lanes,
+ * so the reduction is re-composed lane -> wavefront -> workgroup -> (if
+ * prt[MDH_L_WG][k] = S > 1) grid through `workspace` (S*M floats).
+ *   A: M x K, x: K, y: M, fp32, row-major, device.  K >= 1; M == 0 is an empty call.
+ */
+mdh_status mdh_matvec(int64_t M, int64_t K, const float* A, const float* x, float* y,
+                      const mdh_tile_params* params, void* workspace, size_t workspace_bytes,
+                      void* stream);
 
 /*
  * Small per-workload tile-parameter search (paper: Section "Auto-Tuning", with

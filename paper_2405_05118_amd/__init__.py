@@ -8,6 +8,8 @@ There is no CPU fallback: if the library is missing, loading fails loudly.
 """
 from .binding import (  # noqa: F401
     MDH_CUSTOM_REDUCE,
+    MDH_DOT,
+    MDH_MATVEC,
     MDH_MATMUL,
     MDH_MCC,
     MDH_STENCIL,
@@ -17,6 +19,8 @@ from .binding import (  # noqa: F401
     mdh_candidate,
     mdh_custom_reduce,
     mdh_default_params,
+    mdh_dot,
+    mdh_matvec,
     mdh_matmul,
     mdh_mcc,
     mdh_num_candidates,

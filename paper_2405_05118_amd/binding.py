@@ -13,14 +13,14 @@ from typing import Optional, Sequence
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libmdh.so")
 
-MDH_MATMUL, MDH_STENCIL, MDH_MCC, MDH_CUSTOM_REDUCE = 0, 1, 2, 3
+MDH_MATMUL, MDH_STENCIL, MDH_MCC, MDH_CUSTOM_REDUCE, MDH_DOT, MDH_MATVEC = 0, 1, 2, 3, 4, 5
 MDH_NUM_LAYERS, MDH_MAX_D = 6, 7
 L_HBM, L_LDS, L_VGPR, L_WG, L_WAVE, L_LANE = range(6)
 
 EXPORTS = (
     "mdh_strerror", "mdh_version", "mdh_part_offset", "mdh_default_params", "mdh_validate_params",
     "mdh_workspace_size", "mdh_matmul", "mdh_stencil", "mdh_mcc", "mdh_custom_reduce", "mdh_tune",
-    "mdh_num_candidates", "mdh_candidate", "mdh_last_launch_error",
+    "mdh_num_candidates", "mdh_candidate", "mdh_last_launch_error", "mdh_dot", "mdh_matvec",
 )
 
 
@@ -100,6 +100,8 @@ def lib() -> ctypes.CDLL:
         L.mdh_stencil.argtypes = [i64, i64, i64, vp, vp, f32, f32, pp, vp]
         L.mdh_mcc.argtypes = [i64] * 9 + [vp, vp, vp, pp, vp, sz, vp]
         L.mdh_custom_reduce.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, pp, vp, sz, vp]
+        L.mdh_dot.argtypes = [i64, vp, vp, vp, pp, vp, sz, vp]
+        L.mdh_matvec.argtypes = [i64, i64, vp, vp, vp, pp, vp, sz, vp]
         L.mdh_tune.argtypes = [ctypes.c_int, p64, ctypes.POINTER(vp), ctypes.POINTER(f32), vp, sz, vp, i32, pp,
                                ctypes.POINTER(f32)]
         L.mdh_num_candidates.restype = i32
@@ -243,6 +245,30 @@ def mdh_custom_reduce(A, B, w_agree, w_disagree, out_score, out_index, params: O
                                  _dev(out_index, i32, "out_index"), _pref(params), wp, wb, ctypes.c_void_p(_stream()))
     _check(st, "mdh_custom_reduce")
     return out_score, out_index
+
+
+def mdh_dot(x, y, out, params: Optional[TileParams] = None, workspace=None):
+    import torch
+
+    K = x.numel()
+    assert y.numel() == K and out.numel() == 1
+    wp, wb = _ws(workspace)
+    st = lib().mdh_dot(K, _dev(x, torch.float32, "x"), _dev(y, torch.float32, "y"), _dev(out, torch.float32, "out"),
+                       _pref(params), wp, wb, ctypes.c_void_p(_stream()))
+    _check(st, "mdh_dot")
+    return out
+
+
+def mdh_matvec(A, x, y, params: Optional[TileParams] = None, workspace=None):
+    import torch
+
+    M, K = A.shape
+    assert x.numel() == K and y.numel() == M
+    wp, wb = _ws(workspace)
+    st = lib().mdh_matvec(M, K, _dev(A, torch.float32, "A"), _dev(x, torch.float32, "x"), _dev(y, torch.float32, "y"),
+                          _pref(params), wp, wb, ctypes.c_void_p(_stream()))
+    _check(st, "mdh_matvec")
+    return y
 
 
 def mdh_tune(inst: int, sizes: Sequence[int], buffers, scalars=None, workspace=None, reps: int = 3):

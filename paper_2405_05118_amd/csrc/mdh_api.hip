@@ -2,6 +2,8 @@
 // launches.  No allocation, no synchronisation (except mdh_tune, which times candidates).
 #include <string.h>
 
+#include <functional>
+
 #include "mdh_internal.h"
 
 using namespace mdh;
@@ -101,6 +103,36 @@ mdh_status mdh_custom_reduce(int64_t nA, int64_t nB, int32_t nF, const int32_t* 
                     (hipStream_t)stream);
 }
 
+mdh_status mdh_dot(int64_t K, const float* x, const float* y, float* out,
+                   const mdh_tile_params* params, void* workspace, size_t workspace_bytes,
+                   void* stream) {
+  if (K < 1 || too_big(K)) return MDH_ERR_SIZE;
+  const int64_t sizes[1] = {K};
+  DotPlan pl;
+  mdh_status st = plan_dot(sizes, params, &pl);
+  if (st != MDH_OK) return st;
+  if (!x || !y || !out) return MDH_ERR_NULL;
+  if (pl.S > 1 && (!workspace || workspace_bytes < (size_t)pl.S * sizeof(float))) return MDH_ERR_WORKSPACE;
+  return launch_dot(pl, K, x, y, out, workspace, (hipStream_t)stream);
+}
+
+mdh_status mdh_matvec(int64_t M, int64_t K, const float* A, const float* x, float* y,
+                      const mdh_tile_params* params, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+  if (M < 0 || K < 1 || too_big(M) || too_big(K) || too_big(M * K)) return MDH_ERR_SIZE;
+  const int64_t sizes[2] = {M, K};
+  MatVecPlan pl;
+  mdh_status st = plan_matvec(sizes, params, &pl);
+  if (st != MDH_OK) return st;
+  if (M == 0) return MDH_OK;
+  if (!A || !x || !y) return MDH_ERR_NULL;
+  if (pl.S > 1) {
+    if (too_big((int64_t)pl.S * M)) return MDH_ERR_SIZE;
+    if (!workspace || workspace_bytes < (size_t)pl.S * (size_t)M * sizeof(float)) return MDH_ERR_WORKSPACE;
+  }
+  return launch_matvec(pl, M, K, A, x, y, workspace, (hipStream_t)stream);
+}
+
 // ------------------------------------------------------------------------------ tile search
 
 mdh_status mdh_tune(mdh_instance inst, const int64_t* sizes, void* const* buffers,
@@ -118,7 +150,7 @@ mdh_status mdh_tune(mdh_instance inst, const int64_t* sizes, void* const* buffer
   for (int c = 0; c < n; ++c) {
     mdh_tile_params p;
     if (mdh_candidate(inst, sizes, c, &p) != MDH_OK) continue;
-    auto run = [&]() -> mdh_status {
+    std::function<mdh_status()> run = [&]() -> mdh_status {
       switch (inst) {
         case MDH_MATMUL:
           return mdh_matmul(sizes[0], sizes[1], sizes[2], (const float*)buffers[0],
@@ -142,6 +174,15 @@ mdh_status mdh_tune(mdh_instance inst, const int64_t* sizes, void* const* buffer
       }
       return MDH_ERR_UNSUPPORTED;
     };
+    if (inst == MDH_DOT || inst == MDH_MATVEC) {
+      run = [&]() -> mdh_status {
+        if (inst == MDH_DOT)
+          return mdh_dot(sizes[0], (const float*)buffers[0], (const float*)buffers[1], (float*)buffers[2],
+                         &p, workspace, workspace_bytes, stream);
+        return mdh_matvec(sizes[0], sizes[1], (const float*)buffers[0], (const float*)buffers[1],
+                          (float*)buffers[2], &p, workspace, workspace_bytes, stream);
+      };
+    }
     mdh_status r = run();  // warm-up; candidates that need more workspace are skipped
     if (r != MDH_OK) {
       last = r;

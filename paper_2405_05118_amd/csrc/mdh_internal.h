@@ -42,6 +42,42 @@ struct PrlPlan {
   int ragged;
 };
 
+// helpers of the planner shared by its translation units (defined in mdh_plan.cpp)
+namespace detail {
+void clear_params(mdh_tile_params* p, int D);
+void set_order(mdh_tile_params* p, const int* dim_order);
+mdh_status check_products(const mdh_tile_params* p, const int64_t* sizes, bool* ragged);
+mdh_status check_lanes(const mdh_tile_params* p);
+bool same_table(const mdh_tile_params& a, const mdh_tile_params& b);
+}  // namespace detail
+
+// Dot: WAVES wavefronts per workgroup, S workgroup-layer parts of k; a lane owns 4
+// consecutive k per step, steps are strided over the lanes of the workgroup.
+struct DotPlan {
+  int WAVES;
+  int S;
+  int ragged;
+};
+
+// MatVec: a wavefront owns RM rows; WM wavefronts along i, WK wavefronts along k per
+// workgroup; lanes along k (4 consecutive k each); S workgroup-layer parts of k.
+struct MatVecPlan {
+  int RM, WM, WK;
+  int S;
+  int ragged;
+};
+
+mdh_status plan_dot(const int64_t* sizes, const mdh_tile_params* p, DotPlan* out);
+mdh_status plan_matvec(const int64_t* sizes, const mdh_tile_params* p, MatVecPlan* out);
+void params_from_plan(const int64_t* sizes, const DotPlan& pl, mdh_tile_params* out);
+void params_from_plan(const int64_t* sizes, const MatVecPlan& pl, mdh_tile_params* out);
+int dot_candidates(const int64_t* sizes, DotPlan* out, int cap);
+int matvec_candidates(const int64_t* sizes, MatVecPlan* out, int cap);
+mdh_status launch_dot(const DotPlan& pl, int64_t K, const float* x, const float* y, float* out,
+                      void* ws, hipStream_t st);
+mdh_status launch_matvec(const MatVecPlan& pl, int64_t M, int64_t K, const float* A, const float* x,
+                         float* y, void* ws, hipStream_t st);
+
 mdh_status plan_stencil(const int64_t* sizes, const mdh_tile_params* p, StencilPlan* out);
 mdh_status plan_matmul(const int64_t* sizes, const mdh_tile_params* p, GemmPlan* out);
 mdh_status plan_mcc(const int64_t* sizes, const mdh_tile_params* p, MccPlan* out);

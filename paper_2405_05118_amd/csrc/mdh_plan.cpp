@@ -11,9 +11,11 @@
 namespace mdh {
 
 namespace {
-
 constexpr int kMaxLanesPerWG = 1024;        // model constraint 0 of the CUDA/OpenCL tables
 constexpr int64_t kLdsBytesPerWG = 160 * 1024;  // gfx950 LDS per workgroup
+}  // namespace
+
+namespace detail {
 
 void clear_params(mdh_tile_params* p, int D) {
   memset(p, 0, sizeof(*p));
@@ -73,9 +75,8 @@ bool same_table(const mdh_tile_params& a, const mdh_tile_params& b) {
   return memcmp(&x, &y, sizeof(x)) == 0;
 }
 
-int64_t ws64(int64_t x) { return x; }
-
-}  // namespace
+}  // namespace detail
+using namespace detail;
 
 // =============================================================================== stencil
 
@@ -531,10 +532,17 @@ mdh_status mdh_part_offset(int64_t N, int32_t L, const int32_t* P, const int32_t
 
 static mdh_status check_sizes(mdh_instance inst, const int64_t* s) {
   if (!s) return MDH_ERR_NULL;
-  const int D = inst == MDH_MCC ? 9 : inst == MDH_CUSTOM_REDUCE ? 2 : 3;
+  const int D = inst == MDH_MCC ? 9 : (inst == MDH_CUSTOM_REDUCE || inst == MDH_MATVEC) ? 2
+                                  : inst == MDH_DOT ? 1 : 3;
   for (int d = 0; d < D; ++d)
     if (s[d] < 0 || s[d] > 0x7fffffff) return MDH_ERR_SIZE;
   switch (inst) {
+    case MDH_DOT:
+      if (s[0] < 1) return MDH_ERR_SIZE;
+      break;
+    case MDH_MATVEC:
+      if (s[1] < 1) return MDH_ERR_SIZE;
+      break;
     case MDH_MATMUL:
       if (s[2] < 1) return MDH_ERR_SIZE;
       break;
@@ -577,6 +585,16 @@ mdh_status mdh_default_params(mdh_instance inst, const int64_t* sizes, mdh_tile_
       if ((st = plan_prl(sizes, nullptr, &pl)) == MDH_OK) params_from_plan(sizes, pl, out);
       return st;
     }
+    case MDH_DOT: {
+      DotPlan pl;
+      if ((st = plan_dot(sizes, nullptr, &pl)) == MDH_OK) params_from_plan(sizes, pl, out);
+      return st;
+    }
+    case MDH_MATVEC: {
+      MatVecPlan pl;
+      if ((st = plan_matvec(sizes, nullptr, &pl)) == MDH_OK) params_from_plan(sizes, pl, out);
+      return st;
+    }
   }
   return MDH_ERR_UNSUPPORTED;
 }
@@ -602,6 +620,14 @@ mdh_status mdh_validate_params(mdh_instance inst, const int64_t* sizes, const md
       PrlPlan pl;
       return plan_prl(sizes, p, &pl);
     }
+    case MDH_DOT: {
+      DotPlan pl;
+      return plan_dot(sizes, p, &pl);
+    }
+    case MDH_MATVEC: {
+      MatVecPlan pl;
+      return plan_matvec(sizes, p, &pl);
+    }
   }
   return MDH_ERR_UNSUPPORTED;
 }
@@ -618,6 +644,16 @@ size_t mdh_workspace_size(mdh_instance inst, const int64_t* sizes, const mdh_til
       PrlPlan pl;
       if (plan_prl(sizes, params, &pl) != MDH_OK || pl.S <= 1) return 0;
       return (size_t)pl.S * (size_t)sizes[0] * 2 * sizeof(int32_t);
+    }
+    case MDH_DOT: {
+      DotPlan pl;
+      if (plan_dot(sizes, params, &pl) != MDH_OK || pl.S <= 1) return 0;
+      return (size_t)pl.S * sizeof(float);
+    }
+    case MDH_MATVEC: {
+      MatVecPlan pl;
+      if (plan_matvec(sizes, params, &pl) != MDH_OK || pl.S <= 1) return 0;
+      return (size_t)pl.S * (size_t)sizes[0] * sizeof(float);
     }
     default:
       return 0;
@@ -643,6 +679,14 @@ int32_t mdh_num_candidates(mdh_instance inst, const int64_t* sizes) {
     case MDH_CUSTOM_REDUCE: {
       PrlPlan c[CAP];
       return prl_candidates(sizes, c, CAP);
+    }
+    case MDH_DOT: {
+      DotPlan c[CAP];
+      return dot_candidates(sizes, c, CAP);
+    }
+    case MDH_MATVEC: {
+      MatVecPlan c[CAP];
+      return matvec_candidates(sizes, c, CAP);
     }
   }
   return 0;
@@ -678,6 +722,20 @@ mdh_status mdh_candidate(mdh_instance inst, const int64_t* sizes, int32_t idx, m
     case MDH_CUSTOM_REDUCE: {
       PrlPlan c[CAP];
       int n = prl_candidates(sizes, c, CAP);
+      if (idx < 0 || idx >= n) return MDH_ERR_SIZE;
+      params_from_plan(sizes, c[idx], out);
+      return MDH_OK;
+    }
+    case MDH_DOT: {
+      DotPlan c[CAP];
+      int n = dot_candidates(sizes, c, CAP);
+      if (idx < 0 || idx >= n) return MDH_ERR_SIZE;
+      params_from_plan(sizes, c[idx], out);
+      return MDH_OK;
+    }
+    case MDH_MATVEC: {
+      MatVecPlan c[CAP];
+      int n = matvec_candidates(sizes, c, CAP);
       if (idx < 0 || idx >= n) return MDH_ERR_SIZE;
       params_from_plan(sizes, c[idx], out);
       return MDH_OK;

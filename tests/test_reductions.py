@@ -1,0 +1,167 @@
+"""Dot = md_hom(*, (+)) and MatVec = md_hom(*, (++,+)): the instances whose reduction dimension
+climbs the whole re-composition ladder (lane -> wavefront -> workgroup -> grid).
+Host-side planner checks run everywhere; the parity tests need the GPU."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2405_05118_amd as mdh
+from paper_2405_05118_amd import binding as B
+from paper_2405_05118_amd import workloads as W
+
+TOL = 1e-4  # max |gpu - ref| / sum_k |a*b|, as for the other contractions
+
+HOST_CASES = [
+    (mdh.MDH_DOT, (1 << 28,)),
+    (mdh.MDH_DOT, (1000003,)),
+    (mdh.MDH_DOT, (5,)),
+    (mdh.MDH_MATVEC, (16384, 16384)),
+    (mdh.MDH_MATVEC, (512, 4096)),  # the paper's worked example size
+    (mdh.MDH_MATVEC, (3, 100000)),
+    (mdh.MDH_MATVEC, (1000, 37)),
+]
+
+
+@pytest.mark.parametrize("inst,sizes", HOST_CASES)
+def test_default_and_candidates_satisfy_the_constraints(inst, sizes):
+    p = mdh.mdh_default_params(inst, sizes)
+    assert p.D == len(sizes)
+    assert p.strided == 1  # lanes own the inner parts of k ("inner parallelism")
+    for d in range(p.D):
+        e = p.extent(d)
+        assert e >= sizes[d] if p.ragged else e == sizes[d]
+    lanes = 1
+    for d in range(p.D):
+        lanes *= p.prt[B.L_WAVE][d] * p.prt[B.L_LANE][d]
+    assert lanes <= 1024
+    n = mdh.mdh_num_candidates(inst, sizes)
+    assert n >= 1
+    for i in range(n):
+        c = mdh.mdh_candidate(inst, sizes, i)
+        assert mdh.mdh_validate_params(inst, sizes, c) == 0
+        S = c.prt[B.L_WG][c.D - 1]
+        rows = sizes[0] if inst == mdh.MDH_MATVEC else 1
+        assert mdh.mdh_workspace_size(inst, sizes, c) == (S * rows * 4 if S > 1 else 0)
+
+
+def test_worked_matvec_example_is_a_valid_partitioning():
+    # Section "Low-Level Representation": MatVec on a 512 x 4096 matrix; any table whose parts
+    # multiply to the sizes is a legal (de/re)-composition -- the library's is one of them
+    p = mdh.mdh_default_params(mdh.MDH_MATVEC, (512, 4096))
+    assert p.extent(0) == 512 and p.extent(1) == 4096 and p.ragged == 0
+    q = p.copy()
+    q.prt[B.L_HBM][1] *= 2  # covers k twice
+    assert mdh.mdh_validate_params(mdh.MDH_MATVEC, (512, 4096), q) == 3
+    L = mdh.lib()
+    assert L.mdh_dot(0, None, None, None, None, None, 0, None) == 2  # empty reduction
+    assert L.mdh_matvec(4, 0, None, None, None, None, None, 0, None) == 2
+    assert L.mdh_matvec(0, 8, None, None, None, None, None, 0, None) == 0  # empty ++ dimension
+    assert L.mdh_dot(8, None, None, None, None, None, 0, None) == 1
+
+
+# ------------------------------------------------------------------------------ GPU parity
+
+torch = pytest.importorskip("torch")
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def ws_for(inst, sizes, p):
+    n = mdh.mdh_workspace_size(inst, sizes, p)
+    return torch.empty(max(n, 4) // 4, dtype=torch.int32, device="cuda") if n else None
+
+
+def all_params(inst, sizes):
+    return [None] + [mdh.mdh_candidate(inst, sizes, i) for i in range(mdh.mdh_num_candidates(inst, sizes))]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("K", [1, 3, 64, 1000, 4096, 100003, 1 << 20, (1 << 22) + 5])
+def test_dot_all_candidates(K):
+    x = W.uniform(W.SEED_BASE + 51, 1, (K,), -1, 1)
+    y = W.uniform(W.SEED_BASE + 51, 2, (K,), -1, 1)
+    ref, refabs = oracle.dot(x, y)
+    dx, dy = dev(x), dev(y)
+    for p in all_params(mdh.MDH_DOT, (K,)):
+        out = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
+        mdh.mdh_dot(dx, dy, out, p, ws_for(mdh.MDH_DOT, (K,), p))
+        got = float(out.cpu()[0])
+        assert abs(got - ref) / refabs <= TOL, (K, p and p.table())
+        out2 = torch.empty(1, dtype=torch.float32, device="cuda")
+        mdh.mdh_dot(dx, dy, out2, p, ws_for(mdh.MDH_DOT, (K,), p))
+        assert float(out2.cpu()[0]) == got  # fixed combination order: bit-identical run to run
+
+
+@pytest.mark.gpu
+def test_dot_closed_forms():
+    K = 123457
+    ones = torch.ones(K, dtype=torch.float32, device="cuda")
+    out = torch.empty(1, dtype=torch.float32, device="cuda")
+    mdh.mdh_dot(ones, ones, out, None, ws_for(mdh.MDH_DOT, (K,), None))
+    assert float(out.cpu()[0]) == K  # exact in fp32
+    e = torch.zeros(K, dtype=torch.float32, device="cuda")
+    e[K - 1] = 2.0
+    x = dev(W.uniform(3, 1, (K,), -1, 1))
+    mdh.mdh_dot(x, e, out, None, ws_for(mdh.MDH_DOT, (K,), None))
+    assert float(out.cpu()[0]) == 2.0 * float(x[K - 1].cpu())  # the ragged tail is read
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape", [(512, 4096), (1, 1), (3, 100000), (1000, 37), (257, 1025), (64, 256), (5000, 300), (17, 8192)])
+def test_matvec_all_candidates(shape):
+    M, K = shape
+    A = W.uniform(W.SEED_BASE + 52, 1, (M, K), -1, 1)
+    x = W.uniform(W.SEED_BASE + 52, 2, (K,), -1, 1)
+    ref, refabs = oracle.matvec(A, x, with_abs=True)
+    dA, dx = dev(A), dev(x)
+    for p in all_params(mdh.MDH_MATVEC, shape):
+        y = torch.full((M,), float("nan"), dtype=torch.float32, device="cuda")
+        mdh.mdh_matvec(dA, dx, y, p, ws_for(mdh.MDH_MATVEC, shape, p))
+        got = y.cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(got))
+        assert float(np.max(np.abs(got - ref) / np.where(refabs > 0, refabs, 1.0))) <= TOL, (shape, p and p.table())
+
+
+@pytest.mark.gpu
+def test_matvec_closed_forms_and_homomorphism():
+    M, K = 300, 777
+    A = W.uniform(9, 1, (M, K), -1, 1)
+    e = np.zeros(K, np.float32)
+    e[K - 2] = 1.0  # a unit vector picks a column of A, here one inside the ragged tail of k
+    y = torch.empty(M, dtype=torch.float32, device="cuda")
+    mdh.mdh_matvec(dev(A), dev(e), y, None, ws_for(mdh.MDH_MATVEC, (M, K), None))
+    assert np.array_equal(y.cpu().numpy(), A[:, K - 2])
+    ones = np.ones((M, K), np.float32)
+    mdh.mdh_matvec(dev(ones), dev(np.ones(K, np.float32)), y, None, ws_for(mdh.MDH_MATVEC, (M, K), None))
+    assert np.all(y.cpu().numpy() == K)
+    # homomorphic property on the GPU path: split k by hand, add the halves
+    x = W.uniform(9, 2, (K,), -1, 1)
+    ref, refabs = oracle.matvec(A, x, with_abs=True)
+    y1 = torch.empty(M, dtype=torch.float32, device="cuda")
+    y2 = torch.empty(M, dtype=torch.float32, device="cuda")
+    mdh.mdh_matvec(dev(A[:, :300]), dev(x[:300]), y1, None, ws_for(mdh.MDH_MATVEC, (M, 300), None))
+    mdh.mdh_matvec(dev(A[:, 300:]), dev(x[300:]), y2, None, ws_for(mdh.MDH_MATVEC, (M, K - 300), None))
+    got = y1.cpu().numpy().astype(np.float64) + y2.cpu().numpy()
+    assert float(np.max(np.abs(got - ref) / refabs)) <= TOL
+
+
+@pytest.mark.gpu
+def test_reductions_at_benchmark_sizes():
+    # Dot 2^28 and MatVec 16384^2 in the library's default configuration; oracle on the host
+    K = 1 << 28
+    x = W.device_uniform(W.SEED_BASE + 7, 1, (K,), -1.0, 1.0)
+    y = W.device_uniform(W.SEED_BASE + 7, 2, (K,), -1.0, 1.0)
+    out = torch.empty(1, dtype=torch.float32, device="cuda")
+    mdh.mdh_dot(x, y, out, None, ws_for(mdh.MDH_DOT, (K,), None))
+    ref, refabs = oracle.dot(x.cpu().numpy(), y.cpu().numpy())
+    assert abs(float(out.cpu()[0]) - ref) / refabs <= TOL
+    del x, y
+    M = Kc = 16384
+    A = W.device_uniform(W.SEED_BASE + 8, 1, (M, Kc), -1.0, 1.0)
+    xv = W.device_uniform(W.SEED_BASE + 8, 2, (Kc,), -1.0, 1.0)
+    yv = torch.empty(M, dtype=torch.float32, device="cuda")
+    mdh.mdh_matvec(A, xv, yv, None, ws_for(mdh.MDH_MATVEC, (M, Kc), None))
+    ref, refabs = oracle.matvec(A.cpu().numpy(), xv.cpu().numpy(), with_abs=True)
+    assert float(np.max(np.abs(yv.cpu().numpy() - ref) / refabs)) <= TOL
