@@ -36,12 +36,15 @@ PRL_LANE_OPS_PER_PAIR = 24.0
 # HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/);
 # None until measured for that workload
 TRAFFIC_BYTES = {
-    "jacobi3d_512": 1098534592,  # profiles/stencil_kernel_jacobi3d_512_pmc.md
-    "matmul_4096": None,
-    "matmul_ts": None,
-    "mcc_resnet": None,
-    "prl_2p16_2p18": None,
-    "matmul_256": None,
+    # profiles/all_kernels_hbm_traffic_pmc.md (main kernel of each workload)
+    "jacobi3d_512": 1109672283,
+    "dot_2p28": 2147433877,
+    "matvec_16384": 1074504826,
+    "matmul_4096": 604096517,
+    "matmul_ts": None,  # only measured mixed with the split-k run (same kernel name)
+    "mcc_resnet": 851363442,
+    "prl_2p16_2p18": 138923866,
+    "matmul_256": 4809399,
 }
 
 
