@@ -58,7 +58,8 @@ typedef enum mdh_instance {
   MDH_MCC = 2,           /* md_hom(*, (++,++,++,++, +,+,+)),   dims (n, p, q, k, c, r, s)  */
   MDH_CUSTOM_REDUCE = 3, /* md_hom(wght, (++, max_idx)),       dims (a, b)                 */
   MDH_DOT = 4,           /* md_hom(*, (+)),                    dims (k)                    */
-  MDH_MATVEC = 5         /* md_hom(*, (++, +)),                dims (i, k)                 */
+  MDH_MATVEC = 5,        /* md_hom(*, (++, +)),                dims (i, k)                 */
+  MDH_BMATMUL = 6        /* md_hom(*, (++, ++, ++, +)),        dims (b, i, j, k)           */
 } mdh_instance;
 
 /*
@@ -265,6 +266,25 @@ mdh_status mdh_dot(int64_t K, const float* x, const float* y, float* out,
 mdh_status mdh_matvec(int64_t M, int64_t K, const float* A, const float* x, float* y,
                       const mdh_tile_params* params, void* workspace, size_t workspace_bytes,
                       void* stream);
+
+/*
+ * Batched MatMul with transposed views: bMatMul = md_hom(*, (++,++,++,+)) over
+ * (b,i,j,k); MatMul^T is the same md_hom with other index functions (paper:
+ * Section "Examples", Subfigure 1, routines 4 and 5):
+ *   C_b[i,j] = sum_k A_b[i,k] * B_b[k,j]   for every batch entry b < batch
+ *   trans_a: A_b is stored K x M and read through (b,i,j,k)->A[b,k,i]
+ *   trans_b: B_b is stored N x K and read through (b,i,j,k)->B[b,j,k]
+ *   trans_c: C_b is stored N x M, written through (b,i,j,0)->C[b,j,i]
+ * All buffers dense, batch-major, fp32, device.  K >= 1; batch, M or N == 0 is an
+ * empty call; batch <= 65535.  Split reductions need batch*S*M*N floats of workspace.
+ * For mdh_default_params etc. the `sizes` of MDH_BMATMUL are
+ * (batch, M, N, K, trans_a, trans_b, trans_c); a configuration's in_transposed[0..1]
+ * and out_transposed must equal the call's flags.
+ */
+mdh_status mdh_matmul_ex(int64_t batch, int64_t M, int64_t N, int64_t K, const float* A,
+                         int32_t trans_a, const float* B, int32_t trans_b, float* C,
+                         int32_t trans_c, const mdh_tile_params* params, void* workspace,
+                         size_t workspace_bytes, void* stream);
 
 /*
  * Small per-workload tile-parameter search (paper: Section "Auto-Tuning", with

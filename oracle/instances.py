@@ -45,6 +45,25 @@ def matmul(A, B):
     return [[c[(i, j)] for j in range(N)] for i in range(M)]
 
 
+def bmatmul_t(A, B, trans_a=False, trans_b=False, trans_c=False):
+    """bMatMul = md_hom(*, (++,++,++,+)) over (b,i,j,k) with the transposed views of
+    MatMul^T: (b,i,j,k)->A[b,k,i] if trans_a else A[b,i,k]; B[b,j,k] if trans_b else B[b,k,j];
+    output (b,i,j,0)->C[b,j,i] if trans_c else C[b,i,j]  (Section "Examples", Subfigure 1,
+    routines 4 and 5).  A, B nested lists with the batch as first index."""
+    nb = len(A)
+    M = len(A[0][0]) if trans_a else len(A[0])
+    K = len(A[0]) if trans_a else len(A[0][0])
+    N = len(B[0]) if trans_b else len(B[0][0])
+    ia = (lambda b, i, j, k: (b, k, i)) if trans_a else (lambda b, i, j, k: (b, i, k))
+    ib = (lambda b, i, j, k: (b, j, k)) if trans_b else (lambda b, i, j, k: (b, k, j))
+    ic = (lambda b, i, j, k: (b, j, i)) if trans_c else (lambda b, i, j, k: (b, i, j))
+    iv = H.inp_view([[ia], [ib]])
+    h = H.md_hom(lambda t: t[0] * t[1], (H.concat(0), H.concat(1), H.concat(2), H.pointwise(3, _add)))
+    (c,) = H.out_view([[ic]])(h(iv([A, B], [range(nb), range(M), range(N), range(K)])))
+    rows, cols = (N, M) if trans_c else (M, N)
+    return [[[c[(b, r, q)] for q in range(cols)] for r in range(rows)] for b in range(nb)]
+
+
 def jacobi3d(x, c0, c1):
     """md_hom(J_3D, (++,++,++)); the input view reads the one buffer seven times
     with offset index functions; output view (i,j,k)->(i,j,k)."""

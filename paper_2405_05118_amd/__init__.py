@@ -8,6 +8,7 @@ There is no CPU fallback: if the library is missing, loading fails loudly.
 """
 from .binding import (  # noqa: F401
     MDH_CUSTOM_REDUCE,
+    MDH_BMATMUL,
     MDH_DOT,
     MDH_MATVEC,
     MDH_MATMUL,
@@ -22,6 +23,7 @@ from .binding import (  # noqa: F401
     mdh_dot,
     mdh_matvec,
     mdh_matmul,
+    mdh_matmul_ex,
     mdh_mcc,
     mdh_num_candidates,
     mdh_part_offset,

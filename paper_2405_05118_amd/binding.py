@@ -13,7 +13,7 @@ from typing import Optional, Sequence
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libmdh.so")
 
-MDH_MATMUL, MDH_STENCIL, MDH_MCC, MDH_CUSTOM_REDUCE, MDH_DOT, MDH_MATVEC = 0, 1, 2, 3, 4, 5
+MDH_MATMUL, MDH_STENCIL, MDH_MCC, MDH_CUSTOM_REDUCE, MDH_DOT, MDH_MATVEC, MDH_BMATMUL = 0, 1, 2, 3, 4, 5, 6
 MDH_NUM_LAYERS, MDH_MAX_D = 6, 7
 L_HBM, L_LDS, L_VGPR, L_WG, L_WAVE, L_LANE = range(6)
 
@@ -21,6 +21,7 @@ EXPORTS = (
     "mdh_strerror", "mdh_version", "mdh_part_offset", "mdh_default_params", "mdh_validate_params",
     "mdh_workspace_size", "mdh_matmul", "mdh_stencil", "mdh_mcc", "mdh_custom_reduce", "mdh_tune",
     "mdh_num_candidates", "mdh_candidate", "mdh_last_launch_error", "mdh_dot", "mdh_matvec",
+    "mdh_matmul_ex",
 )
 
 
@@ -100,6 +101,7 @@ def lib() -> ctypes.CDLL:
         L.mdh_stencil.argtypes = [i64, i64, i64, vp, vp, f32, f32, pp, vp]
         L.mdh_mcc.argtypes = [i64] * 9 + [vp, vp, vp, pp, vp, sz, vp]
         L.mdh_custom_reduce.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, pp, vp, sz, vp]
+        L.mdh_matmul_ex.argtypes = [i64, i64, i64, i64, vp, i32, vp, i32, vp, i32, pp, vp, sz, vp]
         L.mdh_dot.argtypes = [i64, vp, vp, vp, pp, vp, sz, vp]
         L.mdh_matvec.argtypes = [i64, i64, vp, vp, vp, pp, vp, sz, vp]
         L.mdh_tune.argtypes = [ctypes.c_int, p64, ctypes.POINTER(vp), ctypes.POINTER(f32), vp, sz, vp, i32, pp,
@@ -245,6 +247,26 @@ def mdh_custom_reduce(A, B, w_agree, w_disagree, out_score, out_index, params: O
                                  _dev(out_index, i32, "out_index"), _pref(params), wp, wb, ctypes.c_void_p(_stream()))
     _check(st, "mdh_custom_reduce")
     return out_score, out_index
+
+
+def mdh_matmul_ex(A, B, C, trans_a=False, trans_b=False, trans_c=False, params: Optional[TileParams] = None,
+                  workspace=None):
+    """A: (batch, M, K) or (batch, K, M) if trans_a; B: (batch, K, N) or (batch, N, K) if trans_b;
+    C: (batch, M, N) or (batch, N, M) if trans_c."""
+    import torch
+
+    batch = A.shape[0]
+    M, K = (A.shape[2], A.shape[1]) if trans_a else (A.shape[1], A.shape[2])
+    N = B.shape[1] if trans_b else B.shape[2]
+    assert B.shape[0] == batch and C.shape[0] == batch
+    assert tuple(B.shape[1:]) == ((N, K) if trans_b else (K, N))
+    assert tuple(C.shape[1:]) == ((N, M) if trans_c else (M, N))
+    wp, wb = _ws(workspace)
+    st = lib().mdh_matmul_ex(batch, M, N, K, _dev(A, torch.float32, "A"), int(trans_a), _dev(B, torch.float32, "B"),
+                             int(trans_b), _dev(C, torch.float32, "C"), int(trans_c), _pref(params), wp, wb,
+                             ctypes.c_void_p(_stream()))
+    _check(st, "mdh_matmul_ex")
+    return C
 
 
 def mdh_dot(x, y, out, params: Optional[TileParams] = None, workspace=None):

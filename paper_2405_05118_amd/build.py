@@ -13,12 +13,14 @@ LIB = os.path.join(HERE, "libmdh.so")
 SOURCES = [
     "mdh_plan.cpp",
     "mdh_plan_reduce.cpp",
+    "mdh_plan_ex.cpp",
     "mdh_api.hip",
     "mdh_stencil.hip",
     "mdh_matmul.hip",
     "mdh_mcc.hip",
     "mdh_custom_reduce.hip",
     "mdh_reduce.hip",
+    "mdh_matmul_ex.hip",
 ]
 
 # packed-fp32 VALU ops are switched off on purpose ("Build flags")

@@ -103,6 +103,28 @@ mdh_status mdh_custom_reduce(int64_t nA, int64_t nB, int32_t nF, const int32_t* 
                     (hipStream_t)stream);
 }
 
+mdh_status mdh_matmul_ex(int64_t batch, int64_t M, int64_t N, int64_t K, const float* A,
+                         int32_t trans_a, const float* B, int32_t trans_b, float* C,
+                         int32_t trans_c, const mdh_tile_params* params, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  if (batch < 0 || M < 0 || N < 0 || K < 1 || batch > 65535) return MDH_ERR_SIZE;
+  if (too_big(M) || too_big(N) || too_big(K) || too_big(M * K) || too_big(K * N) || too_big(M * N))
+    return MDH_ERR_SIZE;
+  if (too_big(batch * M * K) || too_big(batch * K * N) || too_big(batch * M * N)) return MDH_ERR_SIZE;
+  const int64_t sizes[7] = {batch, M, N, K, trans_a ? 1 : 0, trans_b ? 1 : 0, trans_c ? 1 : 0};
+  GemmExPlan pl;
+  mdh_status st = plan_matmul_ex(sizes, params, &pl);
+  if (st != MDH_OK) return st;
+  if (batch == 0 || M == 0 || N == 0) return MDH_OK;
+  if (!A || !B || !C) return MDH_ERR_NULL;
+  if (pl.g.S > 1) {
+    if (too_big((int64_t)pl.g.S * batch * M * N)) return MDH_ERR_SIZE;
+    const size_t need = (size_t)pl.g.S * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
+    if (!workspace || workspace_bytes < need) return MDH_ERR_WORKSPACE;
+  }
+  return launch_matmul_ex(pl, batch, M, N, K, A, B, C, workspace, (hipStream_t)stream);
+}
+
 mdh_status mdh_dot(int64_t K, const float* x, const float* y, float* out,
                    const mdh_tile_params* params, void* workspace, size_t workspace_bytes,
                    void* stream) {

@@ -67,6 +67,19 @@ struct MatVecPlan {
   int ragged;
 };
 
+// bMatMul / MatMul^T: the MatMul descriptor plus the transposition of the three views
+struct GemmExPlan {
+  GemmPlan g;
+  int ta, tb, tc;
+};
+mdh_status plan_matmul_ex(const int64_t* sizes, const mdh_tile_params* p, GemmExPlan* out);
+void params_from_plan(const int64_t* sizes, const GemmExPlan& pl, mdh_tile_params* out);
+int matmul_ex_candidates(const int64_t* sizes, GemmExPlan* out, int cap);
+mdh_status launch_matmul_ex(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, int64_t K,
+                            const float* A, const float* B, float* C, void* ws, hipStream_t st);
+// dst[i] = part_0[i] + ... + part_{S-1}[i], i < n (defined in mdh_matmul.hip)
+mdh_status launch_combine_sum(const float* ws, float* dst, int64_t n, int S, hipStream_t st);
+
 mdh_status plan_dot(const int64_t* sizes, const mdh_tile_params* p, DotPlan* out);
 mdh_status plan_matvec(const int64_t* sizes, const mdh_tile_params* p, MatVecPlan* out);
 void params_from_plan(const int64_t* sizes, const DotPlan& pl, mdh_tile_params* out);

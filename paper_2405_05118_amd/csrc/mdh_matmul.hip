@@ -288,6 +288,12 @@ mdh_status launch_t(const GemmPlan& pl, int64_t M, int64_t N, int64_t K, const f
 
 }  // namespace
 
+mdh_status launch_combine_sum(const float* ws, float* dst, int64_t n, int S, hipStream_t st) {
+  clear_stale_error();
+  hipLaunchKernelGGL(combine_sum_kernel, dim3((unsigned)cdiv(n, 1024)), dim3(256), 0, st, ws, dst, n, S);
+  return launch_status();
+}
+
 mdh_status launch_matmul(const GemmPlan& pl, int64_t M, int64_t N, int64_t K, const float* A,
                          const float* B, float* C, void* ws, hipStream_t st) {
 #define MDH_MM(bm, bn, bk, wm, wn)                                                   \

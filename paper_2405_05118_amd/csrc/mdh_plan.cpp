@@ -533,12 +533,15 @@ mdh_status mdh_part_offset(int64_t N, int32_t L, const int32_t* P, const int32_t
 static mdh_status check_sizes(mdh_instance inst, const int64_t* s) {
   if (!s) return MDH_ERR_NULL;
   const int D = inst == MDH_MCC ? 9 : (inst == MDH_CUSTOM_REDUCE || inst == MDH_MATVEC) ? 2
-                                  : inst == MDH_DOT ? 1 : 3;
+                                  : inst == MDH_DOT ? 1 : inst == MDH_BMATMUL ? 7 : 3;
   for (int d = 0; d < D; ++d)
     if (s[d] < 0 || s[d] > 0x7fffffff) return MDH_ERR_SIZE;
   switch (inst) {
     case MDH_DOT:
       if (s[0] < 1) return MDH_ERR_SIZE;
+      break;
+    case MDH_BMATMUL:
+      if (s[3] < 1 || s[0] > 65535 || s[4] > 1 || s[5] > 1 || s[6] > 1) return MDH_ERR_SIZE;
       break;
     case MDH_MATVEC:
       if (s[1] < 1) return MDH_ERR_SIZE;
@@ -590,6 +593,11 @@ mdh_status mdh_default_params(mdh_instance inst, const int64_t* sizes, mdh_tile_
       if ((st = plan_dot(sizes, nullptr, &pl)) == MDH_OK) params_from_plan(sizes, pl, out);
       return st;
     }
+    case MDH_BMATMUL: {
+      GemmExPlan pl;
+      if ((st = plan_matmul_ex(sizes, nullptr, &pl)) == MDH_OK) params_from_plan(sizes, pl, out);
+      return st;
+    }
     case MDH_MATVEC: {
       MatVecPlan pl;
       if ((st = plan_matvec(sizes, nullptr, &pl)) == MDH_OK) params_from_plan(sizes, pl, out);
@@ -624,6 +632,10 @@ mdh_status mdh_validate_params(mdh_instance inst, const int64_t* sizes, const md
       DotPlan pl;
       return plan_dot(sizes, p, &pl);
     }
+    case MDH_BMATMUL: {
+      GemmExPlan pl;
+      return plan_matmul_ex(sizes, p, &pl);
+    }
     case MDH_MATVEC: {
       MatVecPlan pl;
       return plan_matvec(sizes, p, &pl);
@@ -649,6 +661,11 @@ size_t mdh_workspace_size(mdh_instance inst, const int64_t* sizes, const mdh_til
       DotPlan pl;
       if (plan_dot(sizes, params, &pl) != MDH_OK || pl.S <= 1) return 0;
       return (size_t)pl.S * sizeof(float);
+    }
+    case MDH_BMATMUL: {
+      GemmExPlan pl;
+      if (plan_matmul_ex(sizes, params, &pl) != MDH_OK || pl.g.S <= 1) return 0;
+      return (size_t)pl.g.S * (size_t)sizes[0] * (size_t)sizes[1] * (size_t)sizes[2] * sizeof(float);
     }
     case MDH_MATVEC: {
       MatVecPlan pl;
@@ -683,6 +700,10 @@ int32_t mdh_num_candidates(mdh_instance inst, const int64_t* sizes) {
     case MDH_DOT: {
       DotPlan c[CAP];
       return dot_candidates(sizes, c, CAP);
+    }
+    case MDH_BMATMUL: {
+      GemmExPlan c[CAP];
+      return matmul_ex_candidates(sizes, c, CAP);
     }
     case MDH_MATVEC: {
       MatVecPlan c[CAP];
@@ -729,6 +750,13 @@ mdh_status mdh_candidate(mdh_instance inst, const int64_t* sizes, int32_t idx, m
     case MDH_DOT: {
       DotPlan c[CAP];
       int n = dot_candidates(sizes, c, CAP);
+      if (idx < 0 || idx >= n) return MDH_ERR_SIZE;
+      params_from_plan(sizes, c[idx], out);
+      return MDH_OK;
+    }
+    case MDH_BMATMUL: {
+      GemmExPlan c[CAP];
+      int n = matmul_ex_candidates(sizes, c, CAP);
       if (idx < 0 || idx >= n) return MDH_ERR_SIZE;
       params_from_plan(sizes, c[idx], out);
       return MDH_OK;

@@ -88,7 +88,18 @@ __global__ __launch_bounds__(WAVES * 64) void dot_kernel(const float* __restrict
 __global__ __launch_bounds__(64) void dot_combine_kernel(const float* __restrict__ ws,
                                                          float* __restrict__ out, int S) {
   float a = 0.f;
-  for (int i = threadIdx.x; i < S; i += 64) a += ws[i];
+  // 16 independent loads per lane and round (one round covers the default S = 1024), so that
+  // the loads overlap instead of each addition waiting for its own load
+  for (int base = 0; base < S; base += 1024) {
+    float v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int i = base + u * 64 + threadIdx.x;
+      v[u] = i < S ? ws[i] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) a += v[u];
+  }
   a = wave_sum(a);
   if (threadIdx.x == 0) out[0] = a;
 }

@@ -1,0 +1,124 @@
+"""bMatMul and MatMul^T (batched MatMul with transposed views): same md_hom as MatMul, one
+more concatenation dimension, other index functions.  The reference is the MatMul oracle
+applied to the arrays the transposed views describe; that reading of the views is itself pinned
+against the generic evaluator with the paper's index functions."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2405_05118_amd as mdh
+from oracle import instances as G
+from paper_2405_05118_amd import binding as B
+from paper_2405_05118_amd import workloads as W
+
+TOL = 1e-4
+
+
+def reference(A, Bm, ta, tb, tc):
+    """MatMul oracle on the logical operands: A_b (M x K) = stored A_b transposed if ta, etc."""
+    outs, outabs = [], []
+    for b in range(A.shape[0]):
+        a = np.ascontiguousarray(A[b].T) if ta else A[b]
+        bb = np.ascontiguousarray(Bm[b].T) if tb else Bm[b]
+        c, cabs = oracle.matmul(a, bb, with_abs=True)
+        outs.append(c.T if tc else c)
+        outabs.append(cabs.T if tc else cabs)
+    return np.stack(outs), np.stack(outabs)
+
+
+def test_transposed_views_against_generic_evaluator():
+    rng = np.random.default_rng(5)
+    for ta, tb, tc in itertools.product((False, True), repeat=3):
+        nb, M, N, K = 2, 3, 4, 5
+        A = rng.integers(-4, 5, (nb, K, M) if ta else (nb, M, K)).astype(np.float32)
+        Bm = rng.integers(-4, 5, (nb, N, K) if tb else (nb, K, N)).astype(np.float32)
+        want = G.bmatmul_t(A.astype(int).tolist(), Bm.astype(int).tolist(), ta, tb, tc)
+        got, _ = reference(A, Bm, ta, tb, tc)
+        assert np.array_equal(got, np.array(want, dtype=np.float64)), (ta, tb, tc)
+
+
+HOST_SIZES = [
+    (1, 16, 1000, 2048, 0, 0, 0),   # ResNet-50 training MatMul of the paper's low-level example
+    (1, 1, 1000, 2048, 0, 0, 0),    # ResNet-50 inference
+    (1, 16, 4096, 25088, 0, 0, 0),  # VGG-16 training
+    (8, 300, 200, 100, 1, 1, 1),
+    (3, 1024, 1024, 1024, 1, 0, 1),
+]
+
+
+@pytest.mark.parametrize("sizes", HOST_SIZES)
+def test_planner(sizes):
+    inst = mdh.MDH_BMATMUL
+    p = mdh.mdh_default_params(inst, sizes)
+    assert p.D == 4
+    assert (p.in_transposed[0], p.in_transposed[1], p.out_transposed) == sizes[4:]
+    for d in range(4):
+        e = p.extent(d)
+        assert e >= sizes[d] if p.ragged else e == sizes[d]
+    n = mdh.mdh_num_candidates(inst, sizes)
+    assert n >= 2
+    for i in range(n):
+        c = mdh.mdh_candidate(inst, sizes, i)
+        assert mdh.mdh_validate_params(inst, sizes, c) == 0
+    # a configuration written for other views is not the configuration of this call
+    q = p.copy()
+    q.in_transposed[0] ^= 1
+    assert mdh.mdh_validate_params(inst, sizes, q) == 6
+    # small M: the default spends workgroups on the reduction dimension
+    if sizes[1] <= 16:
+        assert p.prt[B.L_WG][3] > 1 and mdh.mdh_workspace_size(inst, sizes, p) == p.prt[B.L_WG][3] * sizes[0] * sizes[1] * sizes[2] * 4
+
+
+torch = pytest.importorskip("torch")
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run(A, Bm, ta, tb, tc, p):
+    nb = A.shape[0]
+    M, K = (A.shape[2], A.shape[1]) if ta else (A.shape[1], A.shape[2])
+    N = Bm.shape[1] if tb else Bm.shape[2]
+    sizes = (nb, M, N, K, int(ta), int(tb), int(tc))
+    C = torch.full((nb, N, M) if tc else (nb, M, N), float("nan"), dtype=torch.float32, device="cuda")
+    n = mdh.mdh_workspace_size(mdh.MDH_BMATMUL, sizes, p)
+    ws = torch.empty(max(n, 4) // 4, dtype=torch.int32, device="cuda") if n else None
+    mdh.mdh_matmul_ex(dev(A), dev(Bm), C, ta, tb, tc, p, ws)
+    torch.cuda.synchronize()
+    return C.cpu().numpy().astype(np.float64), sizes
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape", [(1, 128, 128, 64), (3, 70, 45, 33), (2, 16, 200, 300), (1, 1, 130, 257), (5, 33, 31, 8)])
+def test_all_views_all_candidates(shape):
+    nb, M, N, K = shape
+    for ta, tb, tc in itertools.product((False, True), repeat=3):
+        A = W.uniform(W.SEED_BASE + 61, 1, (nb, K, M) if ta else (nb, M, K), -1, 1)
+        Bm = W.uniform(W.SEED_BASE + 61, 2, (nb, N, K) if tb else (nb, K, N), -1, 1)
+        ref, refabs = reference(A, Bm, ta, tb, tc)
+        sizes = (nb, M, N, K, int(ta), int(tb), int(tc))
+        cands = [None] + [mdh.mdh_candidate(mdh.MDH_BMATMUL, sizes, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_BMATMUL, sizes))]
+        for p in cands[:: max(1, len(cands) // 6)]:
+            got, _ = run(A, Bm, ta, tb, tc, p)
+            assert np.all(np.isfinite(got))
+            err = float(np.max(np.abs(got - ref) / np.where(refabs > 0, refabs, 1.0)))
+            assert err <= TOL, (shape, ta, tb, tc, p and p.table())
+
+
+@pytest.mark.gpu
+def test_paper_shapes_small_m():
+    # MatMul sizes of the paper's deep-learning study: (M, N, K) = (16, 1000, 2048) and (1, 1000, 2048)
+    for M in (16, 1):
+        A = W.uniform(W.SEED_BASE + 62, 1, (1, M, 2048), -1, 1)
+        Bm = W.uniform(W.SEED_BASE + 62, 2, (1, 2048, 1000), -1, 1)
+        ref, refabs = reference(A, Bm, False, False, False)
+        got, sizes = run(A, Bm, False, False, False, None)
+        assert float(np.max(np.abs(got - ref) / refabs)) <= TOL
+        # all-ones closed form through the transposed views
+        ones_a = np.ones((1, 2048, M), np.float32)
+        ones_b = np.ones((1, 1000, 2048), np.float32)
+        got, _ = run(ones_a, ones_b, True, True, True, None)
+        assert got.shape == (1, 1000, M) and np.all(got == 2048)
