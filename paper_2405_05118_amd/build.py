@@ -18,6 +18,7 @@ SOURCES = [
     "mdh_stencil.hip",
     "mdh_matmul.hip",
     "mdh_mcc.hip",
+    "mdh_mcc_flat.hip",
     "mdh_custom_reduce.hip",
     "mdh_reduce.hip",
     "mdh_matmul_ex.hip",

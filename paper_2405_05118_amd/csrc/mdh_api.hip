@@ -78,6 +78,8 @@ mdh_status mdh_mcc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_
   if (st != MDH_OK) return st;
   if (N == 0 || K == 0) return MDH_OK;
   if (!in || !filt || !out) return MDH_ERR_NULL;
+  if (pl.flat)
+    return launch_mcc_flat(pl, N, H, W, C, K, R, S, stride_h, stride_w, in, filt, out, (hipStream_t)stream);
   return launch_mcc(pl, N, H, W, C, K, R, S, stride_h, stride_w, in, filt, out, (hipStream_t)stream);
 }
 

@@ -32,6 +32,7 @@ struct GemmPlan {
 struct MccPlan {
   int TP, TQ, BN, CK, WM, WN;
   int ragged;
+  int flat;  // 1: few-channel kernel that walks s and c as one fused dimension (TQ = block width)
 };
 
 // Custom reduce: RA records of A per lane, WB wavefronts of a workgroup split B,
@@ -116,6 +117,9 @@ mdh_status launch_matmul(const GemmPlan& pl, int64_t M, int64_t N, int64_t K, co
 mdh_status launch_mcc(const MccPlan& pl, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
                       int64_t R, int64_t S, int64_t sh, int64_t sw, const float* in,
                       const float* filt, float* out, hipStream_t st);
+mdh_status launch_mcc_flat(const MccPlan& pl, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
+                           int64_t R, int64_t S, int64_t sh, int64_t sw, const float* in,
+                           const float* filt, float* out, hipStream_t st);
 mdh_status launch_prl(const PrlPlan& pl, int64_t nA, int64_t nB, int nF, const int32_t* A,
                       const int32_t* B, const int32_t* wp, const int32_t* wm, int32_t* score,
                       int32_t* index, void* ws, hipStream_t st);

@@ -1,0 +1,180 @@
+// Multi-channel convolution for FEW input channels (e.g. the first layer of an image network,
+// C = 3, stride 2; paper: Appendix "Data Characteristics used in Deep Neural Networks").
+//
+// With few channels the reduction dimensions c and s cannot each fill the two-wide k of an
+// MFMA, but in NHWC / KRSC they are adjacent in memory: for a fixed row r,
+//     in  [n, p*sh + r, q*sw + s, c]  =  row_in [ (q*sw)*C + (s*C + c) ]
+//     filt[k, r, s, c]               =  row_flt[ s*C + c ]
+// so s and c are re-composed as ONE sequential dimension sc of extent S*C (any order of the +
+// parts is a valid evaluation).  sc is padded to a multiple of 8 with zero filter entries.
+//
+// De-composition, dims (n,p,q,k,c,r,s):
+//   workgroup layer : N x (P/TP) x (Q/QB) x (K/BN)
+//   LDS             : the whole input patch ((TP-1)*sh + R rows of (QB-1)*sw*C + S*C floats) and the
+//                     BN x R x S*C filter slice are staged once per workgroup
+//   wavefront layer : WAVES_M along p  x  WAVES_N along k
+//   block           : (32/QB rows of p) x (QB consecutive q) x 32 output channels x 2 of sc
+#include "mdh_internal.h"
+
+namespace mdh {
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f16 __attribute__((ext_vector_type(16)));
+
+template <int QB, int MI, int NI, int WAVES_M, int WAVES_N>
+struct FlatCfg {
+  static constexpr int RB = 32 / QB;  // output rows per MFMA block
+  static constexpr int TP = WAVES_M * MI * RB, TQ = QB;
+  static constexpr int BN = WAVES_N * NI * 32;
+  static constexpr int NT = WAVES_M * WAVES_N * 64;
+};
+
+template <int QB, int MI, int NI, int WAVES_M, int WAVES_N>
+__global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
+    const float* __restrict__ in, const float* __restrict__ filt, float* __restrict__ out, int H,
+    int W, int C, int K, int R, int S, int sh, int sw, int P, int Q, int tp_n, int tq_n, int tk_n,
+    int SCP, int PWF, int PFR) {
+  using Cf = FlatCfg<QB, MI, NI, WAVES_M, WAVES_N>;
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int l32 = lane & 31, lh = lane >> 5;
+  int b = blockIdx.x;
+  const int nb = gridDim.x;
+  if ((nb & 7) == 0) b = (b & 7) * (nb >> 3) + (b >> 3);  // contiguous run of tiles per XCD
+  const int tk = b % tk_n;
+  const int tq = (b / tk_n) % tq_n;
+  const int tp = (b / (tk_n * tq_n)) % tp_n;
+  const int n = b / (tk_n * tq_n * tp_n);
+  const int p0 = tp * Cf::TP, q0 = tq * Cf::TQ, k0 = tk * Cf::BN;
+  const int SC = S * C, WC = W * C;
+  const int PH = (Cf::TP - 1) * sh + R;
+  float* fs = lds;                    // filter slice [BN][PFR]: row k holds R groups of SCP floats
+  float* ps = lds + Cf::BN * PFR;     // input patch [PH][PWF]
+
+  // stage the filter slice, zero in the padding of sc and in absent output channels
+  for (int idx = tid; idx < Cf::BN * R * SCP; idx += Cf::NT) {
+    const int k = idx / (R * SCP), rem = idx - k * (R * SCP);
+    const int r = rem / SCP, x = rem - r * SCP;
+    float v = 0.f;
+    if (k0 + k < K && x < SC) v = filt[((int64_t)(k0 + k) * R + r) * SC + x];
+    fs[k * PFR + r * SCP + x] = v;
+  }
+  // stage the input patch; cells outside the image read as 0 (they only meet zero filter entries
+  // or outputs that are not stored)
+  for (int idx = tid; idx < PH * PWF; idx += Cf::NT) {
+    const int ph = idx / PWF, x = idx - ph * PWF;
+    const int hy = p0 * sh + ph, gx = q0 * sw * C + x;
+    float v = 0.f;
+    if (hy < H && gx < WC) v = in[((int64_t)n * H + hy) * WC + gx];
+    ps[idx] = v;
+  }
+  __syncthreads();
+
+  f16 acc[MI][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+  // the lane's pixel inside a block: dp rows down, dq columns right
+  const int dp = l32 / QB, dq = l32 % QB;
+  const float* arow = ps + ((wm * MI * Cf::RB + dp) * sh) * PWF + dq * sw * C + lh * 4;
+  const float* brow = fs + (wn * NI * 32 + l32) * PFR + lh * 4;
+  for (int r = 0; r < R; ++r) {
+    for (int sc0 = 0; sc0 < SCP; sc0 += 8) {
+      f4 af[MI], bf[NI];
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+        const float* a = arow + (mi * Cf::RB * sh + r) * PWF + sc0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) af[mi][t] = a[t];
+      }
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) bf[ni] = *(const f4*)(brow + ni * 32 * PFR + r * SCP + sc0);
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < NI; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi][t], bf[ni][t], acc[mi][ni], 0, 0, 0);
+    }
+  }
+
+  // output view (n,p,q,k,0,0,0) -> out[n,p,q,k]
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+      const int k = k0 + (wn * NI + ni) * 32 + l32;
+#pragma unroll
+      for (int rg = 0; rg < 16; ++rg) {
+        const int m = 8 * (rg / 4) + 4 * lh + (rg % 4);  // pixel of the block this register holds
+        const int p = p0 + (wm * MI + mi) * Cf::RB + m / QB, q = q0 + m % QB;
+        if (p < P && q < Q && k < K) out[(((int64_t)n * P + p) * Q + q) * K + k] = acc[mi][ni][rg];
+      }
+    }
+}
+
+template <int QB, int MI, int NI, int WAVES_M, int WAVES_N>
+mdh_status launch_t(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                    int64_t sh, int64_t sw, const float* in, const float* filt, float* out,
+                    hipStream_t st) {
+  using Cf = FlatCfg<QB, MI, NI, WAVES_M, WAVES_N>;
+  const int64_t P = (H - R) / sh + 1, Q = (W - S) / sw + 1;
+  const int64_t SCP = cdiv(S * C, 8) * 8;
+  const int64_t PWF = cdiv((Cf::TQ - 1) * sw * C + SCP + 4, 4) * 4;
+  const int64_t PFR = R * SCP + 4;
+  const int64_t PH = (Cf::TP - 1) * sh + R;
+  const int64_t lds_bytes = (Cf::BN * PFR + PH * PWF) * 4;
+  if (lds_bytes > 160 * 1024) return MDH_ERR_TILE_RESOURCES;
+  auto kern = mcc_flat_kernel<QB, MI, NI, WAVES_M, WAVES_N>;
+  static int64_t attr_bytes = 0;
+  if (lds_bytes > attr_bytes) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+      return MDH_ERR_LAUNCH;
+    attr_bytes = lds_bytes;
+  }
+  const int64_t tp_n = cdiv(P, Cf::TP), tq_n = cdiv(Q, Cf::TQ), tk_n = cdiv(K, Cf::BN);
+  const int64_t nblocks = N * tp_n * tq_n * tk_n;
+  if (nblocks > 0x7fffffff) return MDH_ERR_SIZE;
+  clear_stale_error();
+  hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cf::NT), (size_t)lds_bytes, st, in, filt, out,
+                     (int)H, (int)W, (int)C, (int)K, (int)R, (int)S, (int)sh, (int)sw, (int)P, (int)Q,
+                     (int)tp_n, (int)tq_n, (int)tk_n, (int)SCP, (int)PWF, (int)PFR);
+  return launch_status();
+}
+
+}  // namespace
+
+// LDS bytes of the flat kernel for a tile; used by the planner to decide whether it applies.
+int64_t mcc_flat_lds_bytes(int QB, int TP, int BN, int64_t C, int64_t R, int64_t S, int64_t sh, int64_t sw) {
+  const int64_t SCP = cdiv(S * C, 8) * 8;
+  const int64_t PWF = cdiv((QB - 1) * sw * C + SCP + 4, 4) * 4;
+  return ((int64_t)BN * (R * SCP + 4) + ((TP - 1) * sh + R) * PWF) * 4;
+}
+
+mdh_status launch_mcc_flat(const MccPlan& pl, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
+                           int64_t R, int64_t S, int64_t sh, int64_t sw, const float* in,
+                           const float* filt, float* out, hipStream_t st) {
+  // pl.TQ is the block width QB, pl.TP the rows per workgroup, pl.BN the channels per workgroup
+#define MDH_FL(qb, mi, ni, wm, wn)                                                              \
+  if (pl.TQ == qb && pl.TP == wm * mi * (32 / qb) && pl.BN == wn * ni * 32 && pl.WM == mi * 32 && \
+      pl.WN == ni * 32)                                                                         \
+    return launch_t<qb, mi, ni, wm, wn>(N, H, W, C, K, R, S, sh, sw, in, filt, out, st);
+  MDH_FL(16, 1, 2, 4, 1)  // 8 x 16 pixels x 64 channels
+  MDH_FL(32, 1, 2, 4, 1)  // 4 x 32 pixels x 64 channels
+  MDH_FL(16, 1, 1, 4, 1)  // 8 x 16 pixels x 32 channels
+  MDH_FL(32, 1, 1, 4, 1)  // 4 x 32 pixels x 32 channels
+  MDH_FL(16, 2, 2, 2, 2)  // 8 x 16 pixels x 128 channels
+  MDH_FL(32, 2, 2, 2, 2)  // 4 x 32 pixels x 128 channels
+#undef MDH_FL
+  return MDH_ERR_UNSUPPORTED;
+}
+
+}  // namespace mdh

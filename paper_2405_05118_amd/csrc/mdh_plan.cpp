@@ -295,50 +295,73 @@ mdh_status plan_matmul(const int64_t* s, const mdh_tile_params* p, GemmPlan* out
 
 // =============================================================================== MCC
 
+int64_t mcc_flat_lds_bytes(int QB, int TP, int BN, int64_t C, int64_t R, int64_t S, int64_t sh, int64_t sw);
+
 struct MccInst {
   int TP, TQ, BN, CK, WM, WN;
 };
-static const MccInst kMccMenu[] = {
+static const MccInst kMccMenu[] = {  // channel-chunked kernel
     {4, 32, 128, 16, 64, 64},
     {8, 32, 128, 16, 128, 64},
     {2, 32, 64, 16, 32, 32},
     {4, 32, 64, 16, 64, 32},
 };
+// few-channel kernel (s and c fused): TP rows x TQ = QB columns of pixels, BN channels, WM, WN
+static const MccInst kMccFlatMenu[] = {
+    {8, 16, 64, 0, 32, 64},  {4, 32, 64, 0, 32, 64},   {8, 16, 32, 0, 32, 32},
+    {4, 32, 32, 0, 32, 32},  {8, 16, 128, 0, 64, 64},  {4, 32, 128, 0, 64, 64},
+};
 
 static bool mcc_inst(const MccPlan& pl) {
-  for (auto& m : kMccMenu)
-    if (m.TP == pl.TP && m.TQ == pl.TQ && m.BN == pl.BN && m.CK == pl.CK && m.WM == pl.WM &&
-        m.WN == pl.WN)
+  const MccInst* menu = pl.flat ? kMccFlatMenu : kMccMenu;
+  const int n = pl.flat ? (int)(sizeof(kMccFlatMenu) / sizeof(MccInst)) : (int)(sizeof(kMccMenu) / sizeof(MccInst));
+  for (int i = 0; i < n; ++i) {
+    const MccInst& m = menu[i];
+    if (m.TP == pl.TP && m.TQ == pl.TQ && m.BN == pl.BN && m.CK == pl.CK && m.WM == pl.WM && m.WN == pl.WN)
       return true;
+  }
   return false;
 }
 
-int64_t mcc_lds_bytes(const MccPlan& pl, int64_t R, int64_t S, int64_t sh, int64_t sw) {
-  const int64_t ph = (pl.TP - 1) * sh + R, pw = (pl.TQ - 1) * sw + S;
+// sizes: N, P, Q, K, C, R, S, stride_h, stride_w
+int64_t mcc_lds_bytes(const MccPlan& pl, const int64_t* s) {
+  if (pl.flat) return mcc_flat_lds_bytes(pl.TQ, pl.TP, pl.BN, s[4], s[5], s[6], s[7], s[8]);
+  const int64_t ph = (pl.TP - 1) * s[7] + s[5], pw = (pl.TQ - 1) * s[8] + s[6];
   return (ph * pw * (pl.CK + 4) + 2ll * pl.BN * (pl.CK + 4)) * 4;
 }
 
 void params_from_plan(const int64_t* s, const MccPlan& pl, mdh_tile_params* p) {
   // dims: 0 n, 1 p, 2 q, 3 k, 4 c, 5 r, 6 s
   clear_params(p, 7);
-  p->blk[2] = 32;  // 32 consecutive q of one output row
-  p->blk[3] = 32;  // 32 output channels
-  p->blk[4] = 2;   // 2 input channels per MFMA
   p->prt[MDH_L_WG][0] = (int32_t)s[0];
   p->prt[MDH_L_WG][1] = (int32_t)cdiv(s[1], pl.TP);
   p->prt[MDH_L_WG][2] = (int32_t)cdiv(s[2], pl.TQ);
   p->prt[MDH_L_WG][3] = (int32_t)cdiv(s[3], pl.BN);
-  p->prt[MDH_L_HBM][4] = (int32_t)cdiv(s[4], pl.CK);
-  p->prt[MDH_L_LDS][4] = pl.CK / 2;
   p->prt[MDH_L_LDS][5] = (int32_t)s[5];
   p->prt[MDH_L_LDS][6] = (int32_t)s[6];
-  // wavefront grid: (TP*TQ/WM) along the pixels (rows of p first), BN/WN along k
-  const int wm_rows = pl.WM / pl.TQ > 0 ? pl.WM / pl.TQ : 1;  // output rows per wavefront
-  p->prt[MDH_L_WAVE][1] = pl.TP / wm_rows;
   p->prt[MDH_L_WAVE][3] = pl.BN / pl.WN;
-  p->prt[MDH_L_VGPR][1] = wm_rows;
-  p->prt[MDH_L_VGPR][2] = pl.TQ / 32;
   p->prt[MDH_L_VGPR][3] = pl.WN / 32;
+  p->blk[3] = 32;  // 32 output channels
+  if (pl.flat) {
+    // few channels: the block is (32/QB rows of p) x (QB consecutive q); s and c are walked as one
+    // sequential LDS-layer dimension of S*C single steps (two of them feed one MFMA)
+    const int rb = 32 / pl.TQ, mi = pl.WM / 32;
+    p->blk[1] = rb;
+    p->blk[2] = pl.TQ;
+    p->prt[MDH_L_LDS][4] = (int32_t)s[4];
+    p->prt[MDH_L_WAVE][1] = pl.TP / (rb * mi);
+    p->prt[MDH_L_VGPR][1] = mi;
+  } else {
+    p->blk[2] = 32;  // 32 consecutive q of one output row
+    p->blk[4] = 2;   // 2 input channels per MFMA
+    p->prt[MDH_L_HBM][4] = (int32_t)cdiv(s[4], pl.CK);
+    p->prt[MDH_L_LDS][4] = pl.CK / 2;
+    // wavefront grid: (TP*TQ/WM) along the pixels (rows of p first), BN/WN along k
+    const int wm_rows = pl.WM / pl.TQ > 0 ? pl.WM / pl.TQ : 1;  // output rows per wavefront
+    p->prt[MDH_L_WAVE][1] = pl.TP / wm_rows;
+    p->prt[MDH_L_VGPR][1] = wm_rows;
+    p->prt[MDH_L_VGPR][2] = pl.TQ / 32;
+  }
   static const int dims[7] = {0, 1, 2, 3, 4, 5, 6};
   set_order(p, dims);
   p->strided = 0;
@@ -350,12 +373,28 @@ void params_from_plan(const int64_t* s, const MccPlan& pl, mdh_tile_params* p) {
 }
 
 static int mcc_ragged(const int64_t* s, const MccPlan& pl) {
+  if (pl.flat) return (s[1] % pl.TP) || (s[2] % pl.TQ) || (s[3] % pl.BN);
   return (s[1] % pl.TP) || (s[2] % pl.TQ) || (s[3] % pl.BN) || (s[4] % pl.CK);
 }
 
+static MccPlan mcc_flat_plan(const int64_t* s) {
+  // block width 16 when it divides Q and 32 does not (e.g. Q = 112); channels per workgroup by K
+  const int qb = (s[2] % 32 != 0 && s[2] % 16 == 0) ? 16 : 32;
+  const int tp = qb == 16 ? 8 : 4;
+  MccPlan pl{tp, qb, 64, 0, 32, 64, 0, 1};
+  if (s[3] <= 32) pl = MccPlan{tp, qb, 32, 0, 32, 32, 0, 1};
+  if (s[3] > 64) pl = MccPlan{tp, qb, 128, 0, 64, 64, 0, 1};
+  pl.ragged = mcc_ragged(s, pl);
+  return pl;
+}
+
 static MccPlan mcc_default(const int64_t* s) {
-  MccPlan pl{4, 32, 128, 16, 64, 64, 0};
-  if (s[3] <= 64) pl = MccPlan{4, 32, 64, 16, 64, 32, 0};
+  if (s[4] <= 8) {  // fewer channels than half a channel chunk: fuse s and c
+    MccPlan f = mcc_flat_plan(s);
+    if (mcc_lds_bytes(f, s) <= kLdsBytesPerWG) return f;
+  }
+  MccPlan pl{4, 32, 128, 16, 64, 64, 0, 0};
+  if (s[3] <= 64) pl = MccPlan{4, 32, 64, 16, 64, 32, 0, 0};
   pl.ragged = mcc_ragged(s, pl);
   return pl;
 }
@@ -364,22 +403,25 @@ int mcc_candidates(const int64_t* s, MccPlan* out, int cap) {
   int n = 0;
   auto push = [&](MccPlan pl) {
     if (n >= cap) return;
-    if (mcc_lds_bytes(pl, s[5], s[6], s[7], s[8]) > kLdsBytesPerWG) return;
+    if (mcc_lds_bytes(pl, s) > kLdsBytesPerWG) return;
     pl.ragged = mcc_ragged(s, pl);
     for (int i = 0; i < n; ++i)
-      if (out[i].TP == pl.TP && out[i].TQ == pl.TQ && out[i].BN == pl.BN && out[i].WM == pl.WM)
+      if (out[i].flat == pl.flat && out[i].TP == pl.TP && out[i].TQ == pl.TQ && out[i].BN == pl.BN &&
+          out[i].WM == pl.WM)
         return;
     out[n++] = pl;
   };
   push(mcc_default(s));
-  for (auto& m : kMccMenu) push(MccPlan{m.TP, m.TQ, m.BN, m.CK, m.WM, m.WN, 0});
+  for (auto& m : kMccMenu) push(MccPlan{m.TP, m.TQ, m.BN, m.CK, m.WM, m.WN, 0, 0});
+  if (s[4] <= 16)
+    for (auto& m : kMccFlatMenu) push(MccPlan{m.TP, m.TQ, m.BN, m.CK, m.WM, m.WN, 0, 1});
   return n;
 }
 
 mdh_status plan_mcc(const int64_t* s, const mdh_tile_params* p, MccPlan* out) {
   if (!p) {
     *out = mcc_default(s);
-    if (mcc_lds_bytes(*out, s[5], s[6], s[7], s[8]) > kLdsBytesPerWG) return MDH_ERR_TILE_RESOURCES;
+    if (mcc_lds_bytes(*out, s) > kLdsBytesPerWG) return MDH_ERR_TILE_RESOURCES;
     return MDH_OK;
   }
   if (p->D != 7) return MDH_ERR_UNSUPPORTED;
@@ -388,14 +430,23 @@ mdh_status plan_mcc(const int64_t* s, const mdh_tile_params* p, MccPlan* out) {
   if (st != MDH_OK) return st;
   if ((st = check_lanes(p)) != MDH_OK) return st;
   MccPlan pl;
-  pl.TQ = p->prt[MDH_L_VGPR][2] * 32;
-  pl.TP = p->prt[MDH_L_WAVE][1] * p->prt[MDH_L_VGPR][1];
-  pl.WM = p->prt[MDH_L_VGPR][1] * pl.TQ;
+  pl.flat = p->blk[4] == 1 ? 1 : 0;
   pl.WN = p->prt[MDH_L_VGPR][3] * 32;
   pl.BN = p->prt[MDH_L_WAVE][3] * pl.WN;
-  pl.CK = p->prt[MDH_L_LDS][4] * 2;
+  if (pl.flat) {
+    pl.TQ = p->blk[2];
+    if (pl.TQ != 16 && pl.TQ != 32) return MDH_ERR_UNSUPPORTED;
+    pl.WM = p->prt[MDH_L_VGPR][1] * 32;
+    pl.TP = p->prt[MDH_L_WAVE][1] * p->prt[MDH_L_VGPR][1] * (32 / pl.TQ);
+    pl.CK = 0;
+  } else {
+    pl.TQ = p->prt[MDH_L_VGPR][2] * 32;
+    pl.TP = p->prt[MDH_L_WAVE][1] * p->prt[MDH_L_VGPR][1];
+    pl.WM = p->prt[MDH_L_VGPR][1] * pl.TQ;
+    pl.CK = p->prt[MDH_L_LDS][4] * 2;
+  }
   pl.ragged = ragged;
-  if (mcc_lds_bytes(pl, s[5], s[6], s[7], s[8]) > kLdsBytesPerWG) return MDH_ERR_TILE_RESOURCES;
+  if (mcc_lds_bytes(pl, s) > kLdsBytesPerWG) return MDH_ERR_TILE_RESOURCES;
   mdh_tile_params chk;
   params_from_plan(s, pl, &chk);
   if (!same_table(chk, *p) || !mcc_inst(pl)) return MDH_ERR_UNSUPPORTED;

@@ -64,7 +64,7 @@ static GemmExPlan ex_default(const int64_t* s) {
   // small-M deep-learning shapes)
   const int64_t tiles = batch * cdiv(M, g.BM) * cdiv(N, g.BN);
   int S = 1;
-  while (tiles * S < 512 && S < 64 && K / (S * 2) >= g.BK) S *= 2;
+  while (tiles * S < 1024 && S < 64 && K / (S * 2) >= 4 * g.BK) S *= 2;
   g.S = S;
   g.ragged = ex_ragged(s, g);
   return GemmExPlan{g, (int)s[4], (int)s[5], (int)s[6]};

@@ -1,0 +1,105 @@
+"""Multi-channel convolution with few input channels and strides (the first-layer shapes of the
+paper's deep-learning study: ResNet-50 N x 230 x 230 x 3 -> 64 channels, 7x7, stride 2; MobileNet
+N x 225 x 225 x 3 -> 32 channels, 3x3, stride 2).  The library fuses the reduction dimensions s
+and c there; the definition (and the oracle) is unchanged."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2405_05118_amd as mdh
+from paper_2405_05118_amd import workloads as W
+
+TOL = 1e-4
+
+RESNET50 = dict(H=230, W=230, C=3, K=64, R=7, S=7, stride=(2, 2))
+MOBILENET = dict(H=225, W=225, C=3, K=32, R=3, S=3, stride=(2, 2))
+
+
+def sizes_of(N, H, Wd, C, K, R, S, stride):
+    P, Q = (H - R) // stride[0] + 1, (Wd - S) // stride[1] + 1
+    return (N, P, Q, K, C, R, S, stride[0], stride[1])
+
+
+def test_default_fuses_s_and_c_for_few_channels():
+    for net in (RESNET50, MOBILENET):
+        s = sizes_of(16, net["H"], net["W"], net["C"], net["K"], net["R"], net["S"], net["stride"])
+        p = mdh.mdh_default_params(mdh.MDH_MCC, s)
+        assert p.blk[4] == 1 and p.prt[1][4] == net["C"]  # c walked in single steps inside LDS
+        assert p.prt[0][4] == 1  # and not chunked over the HBM layer
+        assert mdh.mdh_validate_params(mdh.MDH_MCC, s, p) == 0
+        for d in range(7):
+            assert p.extent(d) >= s[d] if p.ragged else p.extent(d) == s[d]
+    # ResNet's 112 output columns are 7 blocks of 16, not a multiple of 32: no ragged columns
+    s = sizes_of(1, 230, 230, 3, 64, 7, 7, (2, 2))
+    p = mdh.mdh_default_params(mdh.MDH_MCC, s)
+    assert p.blk[2] == 16 and p.extent(2) == 112
+    # many channels keep the channel-chunked kernel
+    p = mdh.mdh_default_params(mdh.MDH_MCC, (16, 224, 224, 128, 64, 7, 7, 1, 1))
+    assert p.blk[4] == 2
+
+
+torch = pytest.importorskip("torch")
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run(x, f, stride, p):
+    N, H, Wd, C = x.shape
+    K, R, S, _ = f.shape
+    P, Q = (H - R) // stride[0] + 1, (Wd - S) // stride[1] + 1
+    out = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
+    mdh.mdh_mcc(dev(x), dev(f), out, stride, p)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64)
+
+
+SMALL = [
+    # N, H, W, C, K, R, S, stride
+    (2, 37, 37, 3, 64, 7, 7, (2, 2)),
+    (1, 21, 40, 3, 32, 3, 3, (2, 2)),
+    (2, 12, 19, 1, 5, 3, 2, (1, 1)),
+    (1, 30, 30, 4, 70, 5, 5, (1, 2)),
+    (1, 9, 70, 8, 130, 1, 1, (1, 1)),
+    (3, 10, 11, 2, 33, 2, 3, (3, 1)),
+]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("case", SMALL)
+def test_small_all_candidates(case):
+    N, H, Wd, C, K, R, S, stride = case
+    x, f = W.mcc_inputs(W.MccCfg(N, H, Wd, C, K, R, S, stride, W.SEED_BASE + 71))
+    ref, refabs = oracle.mcc(x, f, stride, with_abs=True)
+    s = sizes_of(N, H, Wd, C, K, R, S, stride)
+    cands = [None] + [mdh.mdh_candidate(mdh.MDH_MCC, s, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_MCC, s))]
+    assert any(p is not None and p.blk[4] == 1 for p in cands), "the fused (s,c) kernel is not among the candidates"
+    for p in cands:
+        got = run(x, f, stride, p)
+        assert np.all(np.isfinite(got)), "output not fully overwritten"
+        err = float(np.max(np.abs(got - ref) / np.where(refabs > 0, refabs, 1.0)))
+        assert err <= TOL, (case, p and p.table(), p and list(p.blk))
+
+
+@pytest.mark.gpu
+def test_all_ones_closed_form():
+    x = np.ones((1, 23, 39, 3), np.float32)
+    f = np.ones((64, 7, 7, 3), np.float32)
+    got = run(x, f, (2, 2), None)
+    assert got.shape == (1, 9, 17, 64) and np.all(got == 147)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("net,N", [(RESNET50, 16), (RESNET50, 1), (MOBILENET, 16)])
+def test_paper_shapes_sampled(net, N):
+    cfg = W.MccCfg(N, net["H"], net["W"], net["C"], net["K"], net["R"], net["S"], net["stride"], W.SEED_BASE + 72)
+    x, f = W.mcc_inputs(cfg)
+    got = run(x, f, cfg.stride, None)
+    _, P, Q, K = got.shape
+    rng = np.random.default_rng(8)
+    pos = np.array([[rng.integers(0, N), rng.integers(0, P), rng.integers(0, Q), rng.integers(0, K)] for _ in range(3000)]
+                   + [[0, 0, 0, 0], [N - 1, P - 1, Q - 1, K - 1], [0, P - 1, 0, K - 1], [N - 1, 7, 15, 31], [0, 8, 16, 32 % K]], dtype=np.int64)
+    ref, refabs = oracle.mcc_at(x, f, pos, cfg.stride)
+    err = np.abs(got[tuple(pos.T)] - ref) / refabs
+    assert float(err.max()) <= TOL
