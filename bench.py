@@ -160,7 +160,7 @@ def bench_mcc(torch, mdh, W, name, steps, warmup, cpu):
     tf = flop / ms / 1e9
     res = {
         "value": flop / wall / 1e6, "unit": "GFLOP/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "f32",
-        "kernel": "mcc_kernel",
+        "kernel": "mcc_flat_kernel" if cfg.C <= 8 else "mcc_kernel",
         "roofline": {"bound": "mfma", "achieved": tf, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": tf / PEAK_FP32_MFMA_TFLOPS, "traffic": TRAFFIC_BYTES.get(name)},
         "algorithmic_flop": flop,
@@ -171,13 +171,16 @@ def bench_mcc(torch, mdh, W, name, steps, warmup, cpu):
 
         import oracle
 
-        xh, fh = x[:1, : cfg.R + 3].cpu().numpy(), f.cpu().numpy()  # 4 output rows of image 0
+        if cfg.C <= 8:
+            xh, fh = x[:4].cpu().numpy(), f.cpu().numpy()  # four whole images
+        else:
+            xh, fh = x[:1, : cfg.R + 3].cpu().numpy(), f.cpu().numpy()  # 4 output rows of image 0
         t0 = time.perf_counter()
         r = oracle.mcc(np.ascontiguousarray(xh), fh, cfg.stride)
         dt = time.perf_counter() - t0
         res["cpu_baseline"] = {"value": 2.0 * r.size * cfg.C * cfg.R * cfg.S / dt / 1e9, "unit": "GFLOP/s",
                                "cores": oracle.num_threads(), "kind": "oracle",
-                               "sample": "output rows p<%d of image 0 (%.2f s)" % (r.shape[1], dt)}
+                               "sample": "output rows p<%d of the first %d image(s) (%.2f s)" % (r.shape[1], r.shape[0], dt)}
     return res
 
 
@@ -278,6 +281,77 @@ def bench_matvec(torch, mdh, W, name, steps, warmup, cpu):
     return res
 
 
+def bench_matmul_ex(torch, mdh, W, name, steps, warmup, cpu):
+    """Small-M MatMul through the batched / transposed entry point (batch 1, no transposes)."""
+    cfg = W.CONFIGS[name]
+    sizes = (1, cfg.M, cfg.N, cfg.K, 0, 0, 0)
+    a = W.device_uniform(cfg.seed, 1, (1, cfg.M, cfg.K), -1.0, 1.0)
+    b = W.device_uniform(cfg.seed, 2, (1, cfg.K, cfg.N), -1.0, 1.0)
+    c = torch.empty((1, cfg.M, cfg.N), dtype=torch.float32, device="cuda")
+    p = mdh.mdh_default_params(mdh.MDH_BMATMUL, sizes)
+    ws = _ws(torch, mdh, mdh.MDH_BMATMUL, sizes)
+    ms, wall = _events_ms(torch, lambda: mdh.mdh_matmul_ex(a, b, c, False, False, False, None, ws), steps, warmup)
+    flop = 2.0 * cfg.M * cfg.N * cfg.K
+    nbytes = 4 * (cfg.M * cfg.K + cfg.K * cfg.N + cfg.M * cfg.N)
+    gbs = nbytes / ms / 1e6
+    # 2M/4 FLOP per byte of B: far below the ridge (19.7 FLOP/B), so B streaming from HBM is the bound
+    res = {
+        "value": flop / wall / 1e6, "unit": "GFLOP/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "f32",
+        "kernel": "matmul_ex / skinny kernel + combine", "split_k": int(p.prt[3][3]),
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES.get(name)},
+        "algorithmic_flop": flop,
+        "algorithmic_bytes": nbytes,
+    }
+    if cpu:
+        import oracle
+
+        cols = max(1, min(cfg.N, int(4e8 // (cfg.M * cfg.K))))
+        ah, bh = a[0].cpu().numpy(), b[0, :, :cols].contiguous().cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.matmul(ah, bh)
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": 2.0 * cfg.M * cols * cfg.K / dt / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": "first %d columns of C (%.2f s)" % (cols, dt)}
+    return res
+
+
+def calibration(torch, mdh):
+    """Attainable rates of this chip on the resources that bound the instances, from the library's
+    calibration kernels (HIP events on the launch stream, 20 launches each)."""
+    n = 256 * 1024 * 1024  # 1 GiB of fp32: four times the 256 MB last-level cache
+    src = torch.ones(n, dtype=torch.float32, device="cuda")
+    dst = torch.empty(n // 2, dtype=torch.float32, device="cuda")
+    out = torch.empty(mdh.binding.MDH_CALIB_BLOCKS * 256, dtype=torch.float32, device="cuda")
+    outi = torch.empty(mdh.binding.MDH_CALIB_BLOCKS * 256, dtype=torch.int32, device="cuda")
+    res = {}
+    ms, _ = _events_ms(torch, lambda: mdh.mdh_calib_copy(src[: n // 2], dst), 20, 3)
+    res["copy_GBs"] = 2 * 4 * (n // 2) / ms / 1e6
+    ms, _ = _events_ms(torch, lambda: mdh.mdh_calib_read(src, out), 20, 3)
+    res["read_GBs"] = 4 * n / ms / 1e6
+    flop = [0]
+
+    def mf():
+        flop[0] = mdh.mdh_calib_mfma(out, 4096)
+
+    ms, _ = _events_ms(torch, mf, 20, 3)
+    res["fp32_mfma_TFLOPs"] = flop[0] / ms / 1e9
+    # 16 MFMAs x 64 cycles per iteration, 8 wavefronts per SIMD one after the other
+    res["clock_GHz_under_mfma"] = 4096 * 16 * 64 * (mdh.binding.MDH_CALIB_BLOCKS * 4 / 1024) / ms / 1e6
+    ops = [0]
+
+    def va():
+        ops[0] = mdh.mdh_calib_valu(outi, 16384)
+
+    ms, _ = _events_ms(torch, va, 20, 3)
+    res["int_valu_Tlaneops"] = ops[0] / ms / 1e9
+    res["peaks"] = {"hbm_GBs": PEAK_HBM_GBS, "fp32_mfma_TFLOPs": PEAK_FP32_MFMA_TFLOPS,
+                    "int_valu_Tlaneops": PEAK_INT_VALU_TOPS}
+    del src, dst, out, outi
+    torch.cuda.empty_cache()
+    return res
+
+
 BENCHES = {
     "dot_2p28": bench_dot,
     "matvec_16384": bench_matvec,
@@ -287,6 +361,9 @@ BENCHES = {
     "mcc_resnet": bench_mcc,
     "prl_2p16_2p18": bench_prl,
     "matmul_256": bench_matmul,
+    "mcc_resnet50_first": bench_mcc,
+    "matmul_resnet50_fc": bench_matmul_ex,
+    "matmul_vgg16_fc": bench_matmul_ex,
 }
 
 
@@ -368,6 +445,7 @@ def main() -> int:
         torch.cuda.synchronize()
         torch.cuda.empty_cache()
         line["instances"] = inst
+        line["calibration"] = calibration(torch, mdh)
 
     print(json.dumps(line))
     return 0

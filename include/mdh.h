@@ -8,10 +8,11 @@
  * which is either concatenation (++) -- the dimension indexes the output -- or a
  * point-wise reduction operator (+, or the user-defined max-with-index).
  *
- * The library evaluates four fixed instances of the paper's example table
+ * The library evaluates fixed instances of the paper's example table
  * (Figure "Data-parallel computations expressed in our high-level
- * representation"): MatMul, Jacobi-3D, multi-channel convolution (MCC) and a
- * record-linkage style custom reduction.  Each call takes the index-space sizes
+ * representation"): MatMul, Jacobi-3D, multi-channel convolution (MCC), a
+ * record-linkage style custom reduction, Dot, MatVec and the batched /
+ * transposed MatMul variants.  Each call takes the index-space sizes
  * N_1..N_D, the operand buffers the input/output views address, and one
  * configuration of the paper's tuning parameters (Table "Tuning parameters of
  * our low-level expressions"), restricted as in Section "Auto-Tuning".
@@ -307,6 +308,33 @@ mdh_status mdh_tune(mdh_instance inst, const int64_t* sizes, void* const* buffer
 int32_t mdh_num_candidates(mdh_instance inst, const int64_t* sizes);
 mdh_status mdh_candidate(mdh_instance inst, const int64_t* sizes, int32_t idx,
                          mdh_tile_params* out);
+
+/* ------------------------------------------------------------------------- */
+/* Calibration kernels (measurement support; nothing of the method)           */
+/* ------------------------------------------------------------------------- */
+/*
+ * What the chip attains on the resources the instances are bound by, with
+ * nothing else in the way: a roofline fraction quoted against the published
+ * peak (paper: Section "Experimental Results" measures against hand-tuned
+ * libraries instead) can then be read against the attainable rate as well.
+ * Every call enqueues one kernel of MDH_CALIB_BLOCKS workgroups x 256 lanes.
+ *   mdh_calib_copy : dst[0..bytes) = src[0..bytes), 16-byte non-temporal accesses;
+ *                    bytes > 0 and a multiple of 16, both pointers 16-byte aligned.
+ *   mdh_calib_read : streams src once; `out` receives one partial sum per lane
+ *                    (MDH_CALIB_BLOCKS*256 floats, device).
+ *   mdh_calib_mfma : every wavefront issues iters*16 independent
+ *                    v_mfma_f32_32x32x2_f32; *flop (host, may be NULL) receives the
+ *                    floating-point operations of the launch; `out` as above.
+ *   mdh_calib_valu : every lane issues iters*64 plain 32-bit integer VALU
+ *                    instructions; *lane_ops (host, may be NULL) receives lanes x
+ *                    instructions; `out`: MDH_CALIB_BLOCKS*256 int32 (device).
+ * Errors: MDH_ERR_NULL, MDH_ERR_SIZE, MDH_ERR_LAUNCH.
+ */
+#define MDH_CALIB_BLOCKS 2048
+mdh_status mdh_calib_copy(const void* src, void* dst, int64_t bytes, void* stream);
+mdh_status mdh_calib_read(const void* src, int64_t bytes, float* out, void* stream);
+mdh_status mdh_calib_mfma(float* out, int32_t iters, int64_t* flop, void* stream);
+mdh_status mdh_calib_valu(int32_t* out, int32_t iters, int64_t* lane_ops, void* stream);
 
 #ifdef __cplusplus
 }

@@ -17,6 +17,10 @@ from .binding import (  # noqa: F401
     MdhError,
     TileParams,
     lib,
+    mdh_calib_copy,
+    mdh_calib_mfma,
+    mdh_calib_read,
+    mdh_calib_valu,
     mdh_candidate,
     mdh_custom_reduce,
     mdh_default_params,

@@ -21,8 +21,9 @@ EXPORTS = (
     "mdh_strerror", "mdh_version", "mdh_part_offset", "mdh_default_params", "mdh_validate_params",
     "mdh_workspace_size", "mdh_matmul", "mdh_stencil", "mdh_mcc", "mdh_custom_reduce", "mdh_tune",
     "mdh_num_candidates", "mdh_candidate", "mdh_last_launch_error", "mdh_dot", "mdh_matvec",
-    "mdh_matmul_ex",
+    "mdh_matmul_ex", "mdh_calib_copy", "mdh_calib_read", "mdh_calib_mfma", "mdh_calib_valu",
 )
+MDH_CALIB_BLOCKS = 2048
 
 
 class TileParams(ctypes.Structure):
@@ -106,6 +107,10 @@ def lib() -> ctypes.CDLL:
         L.mdh_matvec.argtypes = [i64, i64, vp, vp, vp, pp, vp, sz, vp]
         L.mdh_tune.argtypes = [ctypes.c_int, p64, ctypes.POINTER(vp), ctypes.POINTER(f32), vp, sz, vp, i32, pp,
                                ctypes.POINTER(f32)]
+        L.mdh_calib_copy.argtypes = [vp, vp, i64, vp]
+        L.mdh_calib_read.argtypes = [vp, i64, vp, vp]
+        L.mdh_calib_mfma.argtypes = [vp, i32, p64, vp]
+        L.mdh_calib_valu.argtypes = [vp, i32, p64, vp]
         L.mdh_num_candidates.restype = i32
         L.mdh_num_candidates.argtypes = [ctypes.c_int, p64]
         L.mdh_candidate.argtypes = [ctypes.c_int, p64, i32, pp]
@@ -291,6 +296,45 @@ def mdh_matvec(A, x, y, params: Optional[TileParams] = None, workspace=None):
                           _pref(params), wp, wb, ctypes.c_void_p(_stream()))
     _check(st, "mdh_matvec")
     return y
+
+
+def mdh_calib_copy(src, dst):
+    """Streaming device copy of src into dst (calibration of the HBM roofline)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(lib().mdh_calib_copy(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()), nbytes,
+                                ctypes.c_void_p(_stream())), "mdh_calib_copy")
+
+
+def mdh_calib_read(src, out):
+    """Streaming read of src; out: MDH_CALIB_BLOCKS*256 float32 partial sums."""
+    import torch
+
+    assert out.numel() >= MDH_CALIB_BLOCKS * 256
+    _check(lib().mdh_calib_read(ctypes.c_void_p(src.data_ptr()), src.numel() * src.element_size(),
+                                _dev(out, torch.float32, "out"), ctypes.c_void_p(_stream())), "mdh_calib_read")
+
+
+def mdh_calib_mfma(out, iters: int) -> int:
+    """Register-resident FP32 MFMA loop; returns the floating-point operations of the launch."""
+    import torch
+
+    assert out.numel() >= MDH_CALIB_BLOCKS * 256
+    n = ctypes.c_int64()
+    _check(lib().mdh_calib_mfma(_dev(out, torch.float32, "out"), iters, ctypes.byref(n), ctypes.c_void_p(_stream())),
+           "mdh_calib_mfma")
+    return n.value
+
+
+def mdh_calib_valu(out, iters: int) -> int:
+    """Register-resident int32 VALU loop; returns lanes x operations of the launch."""
+    import torch
+
+    assert out.numel() >= MDH_CALIB_BLOCKS * 256
+    n = ctypes.c_int64()
+    _check(lib().mdh_calib_valu(_dev(out, torch.int32, "out"), iters, ctypes.byref(n), ctypes.c_void_p(_stream())),
+           "mdh_calib_valu")
+    return n.value
 
 
 def mdh_tune(inst: int, sizes: Sequence[int], buffers, scalars=None, workspace=None, reps: int = 3):

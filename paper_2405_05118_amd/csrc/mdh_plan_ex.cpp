@@ -59,7 +59,11 @@ static GemmExPlan ex_default(const int64_t* s) {
   if (M <= 64) g = GemmPlan{64, 64, 16, 32, 32, 1, 0};
   if (M <= 32) g = GemmPlan{32, 128, 16, 32, 32, 1, 0};  // small M: one block row, lanes spent on j
   if (M <= 32 && N <= 64) g = GemmPlan{32, 64, 16, 32, 32, 1, 0};
-  if (M > 64 && N > 64 && batch * M * N <= 512 * 512) g = GemmPlan{64, 64, 16, 32, 32, 1, 0};
+  // mid-sized problems: the largest tile that still gives every compute unit two workgroups
+  if (M > 64 && N > 64 && batch * cdiv(M, 128) * cdiv(N, 128) < 512) {
+    g = GemmPlan{128, 64, 16, 64, 32, 1, 0};
+    if (batch * cdiv(M, 128) * cdiv(N, 64) < 512) g = GemmPlan{64, 64, 16, 32, 32, 1, 0};
+  }
   // few output tiles: parallelise the reduction dimension over workgroups (the paper's point about
   // small-M deep-learning shapes)
   const int64_t tiles = batch * cdiv(M, g.BM) * cdiv(N, g.BN);

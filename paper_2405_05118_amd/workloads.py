@@ -128,6 +128,11 @@ CONFIGS: Dict[str, object] = {
     "matmul_ts": MatmulCfg(65536, 64, 4096, SEED_BASE + 4),
     "mcc_resnet": MccCfg(16, 230, 230, 64, 128, 7, 7, (1, 1), SEED_BASE + 5),
     "prl_2p16_2p18": PrlCfg(1 << 16, 1 << 18, 8, SEED_BASE + 6),
+    # shapes of the paper's deep-learning study (Appendix "Data Characteristics used in Deep Neural
+    # Networks"): first convolution of ResNet-50 (training, N = 16) and the small-M MatMuls
+    "mcc_resnet50_first": MccCfg(16, 230, 230, 3, 64, 7, 7, (2, 2), SEED_BASE + 9),
+    "matmul_resnet50_fc": MatmulCfg(16, 1000, 2048, SEED_BASE + 10),
+    "matmul_vgg16_fc": MatmulCfg(16, 4096, 25088, SEED_BASE + 11),
 }
 
 
