@@ -20,6 +20,7 @@ SOURCES = [
     "mdh_mcc.hip",
     "mdh_mcc_flat.hip",
     "mdh_calib.hip",
+    "mdh_matmul_skinny.hip",
     "mdh_custom_reduce.hip",
     "mdh_reduce.hip",
     "mdh_matmul_ex.hip",

@@ -72,12 +72,17 @@ struct MatVecPlan {
 struct GemmExPlan {
   GemmPlan g;
   int ta, tb, tc;
+  // skinny = 1: the small-M kernel (16 x 16 x 4 block, operands straight to registers); then
+  // g.BM = 16, g.BN = 64 * wavefronts along j, g.BK = 16 and WK = wavefronts along k
+  int skinny = 0, WK = 1;
 };
 mdh_status plan_matmul_ex(const int64_t* sizes, const mdh_tile_params* p, GemmExPlan* out);
 void params_from_plan(const int64_t* sizes, const GemmExPlan& pl, mdh_tile_params* out);
 int matmul_ex_candidates(const int64_t* sizes, GemmExPlan* out, int cap);
 mdh_status launch_matmul_ex(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, int64_t K,
                             const float* A, const float* B, float* C, void* ws, hipStream_t st);
+mdh_status launch_matmul_skinny(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, int64_t K,
+                                const float* A, const float* B, float* C, void* ws, hipStream_t st);
 // dst[i] = part_0[i] + ... + part_{S-1}[i], i < n (defined in mdh_matmul.hip)
 mdh_status launch_combine_sum(const float* ws, float* dst, int64_t n, int S, hipStream_t st);
 

@@ -248,6 +248,7 @@ mdh_status launch_trans(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t 
 
 mdh_status launch_matmul_ex(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, int64_t K,
                             const float* A, const float* B, float* C, void* ws, hipStream_t st) {
+  if (pl.skinny) return launch_matmul_skinny(pl, batch, M, N, K, A, B, C, ws, st);
 #define MDH_MX(bm, bn, bk, wm, wn)                                                                   \
   if (pl.g.BM == bm && pl.g.BN == bn && pl.g.BK == bk && pl.g.WM == wm && pl.g.WN == wn)             \
     return launch_trans<bm, bn, bk, wm, wn>(pl, batch, M, N, K, A, B, C, ws, st);

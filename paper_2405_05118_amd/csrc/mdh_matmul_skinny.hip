@@ -1,0 +1,167 @@
+// MatMul with very few rows (M <= 16 per block row): the small-M shapes of the paper's
+// deep-learning study, e.g. 16 x 1000 x 2048 and 16 x 4096 x 25088 (paper: Appendix "Data
+// Characteristics used in Deep Neural Networks"; Section "Experimental Results" on why these shapes
+// need the reduction dimension parallelised).
+//
+// With M = 16 every element of B is used 16 times: 8 FLOP per byte, far below the ridge of the
+// chip, so B streaming once from HBM is the bound and nothing is gained by staging it in LDS.
+// De-composition, dims (b, i, j, k), MFMA block = 16 x 16 x 4 (v_mfma_f32_16x16x4_f32):
+//   workgroup layer : batch x ceil(M/16) x ceil(N/(64*WAVES_N)) x S parts of k
+//   wavefront layer : WAVES_N strips of 64 columns x WAVES_K interleaved 16-row parts of k
+//   register layer  : both operands go from HBM straight to registers (memory region parameter =
+//                     register memory for A and B); per step of 16 k a lane loads 4 rows x 4
+//                     consecutive columns of B (16-byte loads, 256 contiguous bytes per 16 lanes)
+//                     and 4 consecutive k of its row of A
+// A lane's 4 columns feed 4 different MFMAs (one per column residue mod 4), so the block's 16
+// output columns are the strided set {4*l + c}; the output view un-permutes for free because a
+// lane then holds 4 consecutive columns of 4 rows.  The k parts are permuted the same way the
+// large-tile kernel does it (lane group g owns k in {4g..4g+3} of a step): + combines them.
+// Re-composition: registers (MFMA accumulators) -> LDS across the WAVES_K wavefronts of a
+// workgroup -> workspace + second kernel across the S workgroup parts.
+#include "mdh_internal.h"
+
+namespace mdh {
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));  // dword-aligned 16-byte access
+
+constexpr int SK_PF = 2;  // 16-row steps requested together by a wavefront
+
+template <int WAVES_N, int WAVES_K>
+__global__ __launch_bounds__((WAVES_N * WAVES_K * 64)) void matmul_skinny_kernel(
+    const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C,
+    float* __restrict__ ws, int M, int N, int K, int tiles_m, int tiles_n, int S, int kchunk,
+    int nbatch) {
+  __shared__ f4 part[WAVES_K > 1 ? (WAVES_K - 1) * WAVES_N * 4 * 64 : 1];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wn = wave % WAVES_N, wk = wave / WAVES_N;
+  const int g = lane >> 4, l16 = lane & 15;
+  const int batch = blockIdx.y;
+  const int tiles = tiles_m * tiles_n;
+  const int s = blockIdx.x / tiles, t = blockIdx.x % tiles;
+  const int m0 = (t % tiles_m) * 16;
+  const int n0 = ((t / tiles_m) * WAVES_N + wn) * 64;  // first column of this wavefront's strip
+  const int kbeg = s * kchunk;
+  const int kend = min(K, kbeg + kchunk);
+  const int64_t mn = (int64_t)M * N;
+  const float* Ab = A + (int64_t)batch * M * K;
+  const float* Bb = B + (int64_t)batch * K * N;
+  float* out = S > 1 ? ws + ((int64_t)s * nbatch + batch) * mn : C + (int64_t)batch * mn;
+
+  const int arow = m0 + l16;            // the row of A this lane supplies
+  const bool arow_ok = arow < M;
+  const float* ap = Ab + (int64_t)(arow_ok ? arow : 0) * K + 4 * g;
+  const int col = n0 + 4 * l16;         // the lane's 4 consecutive columns
+  const float* bp = Bb + (int64_t)(4 * g) * N + col;
+  const bool cols_full = n0 + 64 <= N;  // wavefront-uniform
+
+  f4 acc[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) acc[c] = (f4){0.f, 0.f, 0.f, 0.f};
+
+  auto mma = [&](const f4& a, const f4 (&b)[4]) {
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[tt], b[tt][c], acc[c], 0, 0, 0);
+  };
+
+  int k = kbeg + wk * 16;
+  constexpr int KSTEP = 16 * WAVES_K;
+  if (cols_full) {
+    // interior: SK_PF steps of 16 rows requested before the first is consumed
+    for (; k + (SK_PF - 1) * KSTEP + 16 <= kend; k += SK_PF * KSTEP) {
+      f4 a[SK_PF], b[SK_PF][4];
+#pragma unroll
+      for (int u = 0; u < SK_PF; ++u) {
+        const int ku = k + u * KSTEP;
+        a[u] = arow_ok ? *(const f4u*)(ap + ku) : (f4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt)
+          b[u][tt] = __builtin_nontemporal_load((const f4u*)(bp + (int64_t)(ku + tt) * N));
+      }
+#pragma unroll
+      for (int u = 0; u < SK_PF; ++u) mma(a[u], b[u]);
+    }
+  }
+  // remaining steps, ragged columns and the ragged end of k: every element predicated
+  for (; k < kend; k += KSTEP) {
+    f4 a, b[4];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+      const int kk = k + 4 * g + tt;
+      a[tt] = (arow_ok && kk < kend) ? ap[k + tt] : 0.f;
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        b[tt][c] = (kk < kend && col + c < N) ? bp[(int64_t)(k + tt) * N + c] : 0.f;
+    }
+    mma(a, b);
+  }
+
+  // wavefront -> workgroup: the wavefronts that split k add their blocks in LDS, in a fixed order
+  if (WAVES_K > 1) {
+    if (wk > 0) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) part[(((wk - 1) * WAVES_N + wn) * 4 + c) * 64 + lane] = acc[c];
+    }
+    __syncthreads();
+    if (wk > 0) return;
+#pragma unroll
+    for (int w = 1; w < WAVES_K; ++w)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[c] += part[(((w - 1) * WAVES_N + wn) * 4 + c) * 64 + lane];
+  }
+
+  // output view: register r of block c is C[m0 + 4g + r][col + c]
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = m0 + 4 * g + r;
+    if (row >= M) continue;
+    float* p = out + (int64_t)row * N + col;
+    if (cols_full) {
+      *(f4u*)p = (f4){acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
+    } else {
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (col + c < N) p[c] = acc[c][r];
+    }
+  }
+}
+
+template <int WAVES_N, int WAVES_K>
+mdh_status launch_t(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, int64_t K,
+                    const float* A, const float* B, float* C, void* ws, hipStream_t st) {
+  const int S = pl.g.S;
+  const int64_t tm = cdiv(M, 16), tn = cdiv(N, 64 * WAVES_N);
+  const int64_t kchunk = cdiv(cdiv(K, S), 16) * 16;
+  const int64_t nblocks = tm * tn * S;
+  if (nblocks > 0x7fffffff || batch > 65535) return MDH_ERR_SIZE;
+  clear_stale_error();
+  hipLaunchKernelGGL((matmul_skinny_kernel<WAVES_N, WAVES_K>), dim3((unsigned)nblocks, (unsigned)batch),
+                     dim3(WAVES_N * WAVES_K * 64), 0, st, A, B, C, (float*)ws, (int)M, (int)N, (int)K,
+                     (int)tm, (int)tn, S, (int)kchunk, (int)batch);
+  mdh_status r = launch_status();
+  if (r != MDH_OK || S <= 1) return r;
+  return launch_combine_sum((const float*)ws, C, batch * M * N, S, st);
+}
+
+}  // namespace
+
+mdh_status launch_matmul_skinny(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, int64_t K,
+                                const float* A, const float* B, float* C, void* ws, hipStream_t st) {
+  if (pl.ta || pl.tb || pl.tc) return MDH_ERR_UNSUPPORTED;
+#define MDH_SK(wn, wk) \
+  if (pl.g.BN == 64 * wn && pl.WK == wk) return launch_t<wn, wk>(pl, batch, M, N, K, A, B, C, ws, st);
+  MDH_SK(1, 4)
+  MDH_SK(1, 8)
+  MDH_SK(2, 2)
+  MDH_SK(4, 1)
+  MDH_SK(1, 1)
+#undef MDH_SK
+  return MDH_ERR_UNSUPPORTED;
+}
+
+}  // namespace mdh

@@ -18,8 +18,60 @@ static bool ex_inst(const GemmPlan& g) {
   return false;
 }
 
+// Small-M kernel: wavefronts along j x wavefronts along k
+static const int kSkinnyMenu[][2] = {{1, 4}, {1, 8}, {2, 2}, {4, 1}, {1, 1}};
+
+static bool skinny_inst(int wn, int wk) {
+  for (auto& m : kSkinnyMenu)
+    if (m[0] == wn && m[1] == wk) return true;
+  return false;
+}
+
+// Table of the small-M kernel: block 16 x 16 x 4, a wavefront owns 64 columns (4 column residues
+// in registers) and walks its k part in steps of 16 (4 k per lane group in registers); A and B are
+// read into registers directly.
+static void skinny_params(const int64_t* s, const GemmExPlan& pl, mdh_tile_params* p) {
+  const GemmPlan& g = pl.g;
+  clear_params(p, 4);
+  p->blk[1] = 16;
+  p->blk[2] = 16;
+  p->blk[3] = 4;
+  const int64_t kchunk = cdiv(cdiv(s[3], g.S), 16) * 16;
+  p->prt[MDH_L_WG][0] = (int32_t)s[0];
+  p->prt[MDH_L_WG][1] = (int32_t)cdiv(s[1], 16);
+  p->prt[MDH_L_WG][2] = (int32_t)cdiv(s[2], g.BN);
+  p->prt[MDH_L_WG][3] = g.S;
+  p->prt[MDH_L_HBM][3] = (int32_t)cdiv(kchunk, 16 * pl.WK);
+  p->prt[MDH_L_WAVE][2] = g.BN / 64;
+  p->prt[MDH_L_WAVE][3] = pl.WK;
+  p->prt[MDH_L_VGPR][2] = 4;
+  p->prt[MDH_L_VGPR][3] = 4;
+  static const int dims[4] = {0, 1, 2, 3};
+  set_order(p, dims);
+  p->strided = 1;  // the wavefronts along k interleave their 16-row parts
+  p->lane_fast_dim = 2;
+  p->in_region[0] = MDH_MR_VGPR;
+  p->in_region[1] = MDH_MR_VGPR;
+  p->out_region = MDH_MR_VGPR;
+  p->ragged = (uint8_t)g.ragged;
+}
+
+static int skinny_ragged(const int64_t* s, const GemmExPlan& pl) {
+  const int64_t kchunk = cdiv(cdiv(s[3], pl.g.S), 16) * 16;
+  return (s[1] % 16) || (s[2] % pl.g.BN) || (s[3] != (int64_t)pl.g.S * cdiv(kchunk, 16 * pl.WK) * pl.WK * 16);
+}
+
+static GemmExPlan skinny_plan(const int64_t* s, int wn, int wk, int S) {
+  GemmExPlan pl{GemmPlan{16, 64 * wn, 16, 16, 64, S, 0}, 0, 0, 0, 1, wk};
+  pl.g.ragged = skinny_ragged(s, pl);
+  return pl;
+}
+
+static bool skinny_applies(const int64_t* s) { return s[1] <= 16 && !s[4] && !s[5] && !s[6]; }
+
 // sizes: batch, M, N, K, trans_a, trans_b, trans_c
 void params_from_plan(const int64_t* s, const GemmExPlan& pl, mdh_tile_params* p) {
+  if (pl.skinny) return skinny_params(s, pl, p);
   const GemmPlan& g = pl.g;
   clear_params(p, 4);
   p->blk[1] = 32;
@@ -52,7 +104,23 @@ static int ex_ragged(const int64_t* s, const GemmPlan& g) {
   return (s[1] % g.BM) || (s[2] % g.BN) || (s[3] % ((int64_t)g.S * g.BK));
 }
 
+static GemmExPlan ex_default_tiled(const int64_t* s);
+
 static GemmExPlan ex_default(const int64_t* s) {
+  const int64_t batch = s[0], M = s[1], N = s[2], K = s[3];
+  if (skinny_applies(s)) {
+    // B streams once from HBM: 8 wavefronts along k per workgroup, and k parts over workgroups until
+    // 2048 wavefronts (two per SIMD) are in flight, each still walking at least two steps of 16 rows
+    // (measured best on 16 x 1000 x 2048, 16 x 1000 x 4096, 16 x 4096 x 4096 and 16 x 4096 x 25088)
+    const int64_t strips = batch * cdiv(M, 16) * cdiv(N, 64);
+    int S = 1;
+    while (strips * 8 * S < 2048 && S < 64 && K / (2 * S) >= 8 * 16 * 2) S *= 2;
+    return skinny_plan(s, 1, 8, S);
+  }
+  return ex_default_tiled(s);
+}
+
+static GemmExPlan ex_default_tiled(const int64_t* s) {
   const int64_t batch = s[0], M = s[1], N = s[2], K = s[3];
   GemmPlan g{128, 128, 16, 64, 64, 1, 0};
   if (N <= 64) g = GemmPlan{128, 64, 16, 64, 32, 1, 0};
@@ -60,9 +128,9 @@ static GemmExPlan ex_default(const int64_t* s) {
   if (M <= 32) g = GemmPlan{32, 128, 16, 32, 32, 1, 0};  // small M: one block row, lanes spent on j
   if (M <= 32 && N <= 64) g = GemmPlan{32, 64, 16, 32, 32, 1, 0};
   // mid-sized problems: the largest tile that still gives every compute unit two workgroups
-  if (M > 64 && N > 64 && batch * cdiv(M, 128) * cdiv(N, 128) < 512) {
+  if (M > 64 && N > 64 && batch * cdiv(M, 128) * cdiv(N, 128) < 1024) {
     g = GemmPlan{128, 64, 16, 64, 32, 1, 0};
-    if (batch * cdiv(M, 128) * cdiv(N, 64) < 512) g = GemmPlan{64, 64, 16, 32, 32, 1, 0};
+    if (batch * cdiv(M, 128) * cdiv(N, 64) < 1024) g = GemmPlan{64, 64, 16, 32, 32, 1, 0};
   }
   // few output tiles: parallelise the reduction dimension over workgroups (the paper's point about
   // small-M deep-learning shapes)
@@ -81,10 +149,23 @@ int matmul_ex_candidates(const int64_t* s, GemmExPlan* out, int cap) {
     if (g.S > 1 && s[3] / g.S < g.BK) return;
     g.ragged = ex_ragged(s, g);
     for (int i = 0; i < n; ++i)
-      if (out[i].g.BM == g.BM && out[i].g.BN == g.BN && out[i].g.S == g.S) return;
+      if (!out[i].skinny && out[i].g.BM == g.BM && out[i].g.BN == g.BN && out[i].g.S == g.S) return;
     out[n++] = GemmExPlan{g, (int)s[4], (int)s[5], (int)s[6]};
   };
-  push(ex_default(s).g);
+  if (skinny_applies(s)) {
+    const GemmExPlan d = ex_default(s);
+    out[n++] = d;
+    static const int sk_splits[] = {1, 2, 4, 8, 16, 32, 64};
+    for (auto& m : kSkinnyMenu)
+      for (int S : sk_splits) {
+        if (n >= cap / 2) break;
+        if ((m[0] == d.g.BN / 64 && m[1] == d.WK && S == d.g.S) || (S > 1 && s[3] / S < 16 * m[1])) continue;
+        const int64_t waves = s[0] * cdiv(s[1], 16) * cdiv(s[2], 64) * m[1] * S;
+        if (S > 1 && waves / 2 >= 16384) continue;
+        out[n++] = skinny_plan(s, m[0], m[1], S);
+      }
+  }
+  push(ex_default_tiled(s).g);
   static const int splits[] = {1, 2, 4, 8, 16, 32};
   for (auto& m : kExMenu)
     for (int S : splits) {
@@ -105,6 +186,16 @@ mdh_status plan_matmul_ex(const int64_t* s, const mdh_tile_params* p, GemmExPlan
   mdh_status st = check_products(p, s, &ragged);
   if (st != MDH_OK) return st;
   if ((st = check_lanes(p)) != MDH_OK) return st;
+  if (p->blk[1] == 16) {  // the small-M kernel
+    const int wn = p->prt[MDH_L_WAVE][2], wk = p->prt[MDH_L_WAVE][3];
+    if (!skinny_inst(wn, wk) || s[4] || s[5] || s[6]) return MDH_ERR_UNSUPPORTED;
+    GemmExPlan pl = skinny_plan(s, wn, wk, p->prt[MDH_L_WG][3]);
+    mdh_tile_params chk;
+    params_from_plan(s, pl, &chk);
+    if (!same_table(chk, *p)) return MDH_ERR_UNSUPPORTED;
+    *out = pl;
+    return MDH_OK;
+  }
   GemmPlan g;
   g.WM = p->prt[MDH_L_VGPR][1] * 32;
   g.WN = p->prt[MDH_L_VGPR][2] * 32;

@@ -71,6 +71,20 @@ def test_planner(sizes):
         assert p.prt[B.L_WG][3] > 1 and mdh.mdh_workspace_size(inst, sizes, p) == p.prt[B.L_WG][3] * sizes[0] * sizes[1] * sizes[2] * 4
 
 
+def test_small_m_default_streams_operands_to_registers():
+    # M <= 16 without transposed views: 16 x 16 x 4 block, no LDS staging, k parts on wavefronts
+    # and workgroups (the paper's point about parallelising the reduction of these shapes)
+    for sizes in HOST_SIZES[:3]:
+        p = mdh.mdh_default_params(mdh.MDH_BMATMUL, sizes)
+        assert list(p.blk[:4]) == [1, 16, 16, 4]
+        assert p.in_region[0] == 2 and p.in_region[1] == 2
+        assert p.prt[B.L_WAVE][3] > 1
+    # transposed views or more rows: the LDS-tiled kernel
+    for sizes in ((1, 16, 1000, 2048, 0, 1, 0), (1, 17, 1000, 2048, 0, 0, 0)):
+        p = mdh.mdh_default_params(mdh.MDH_BMATMUL, sizes)
+        assert list(p.blk[:4]) == [1, 32, 32, 2]
+
+
 torch = pytest.importorskip("torch")
 
 
@@ -106,6 +120,25 @@ def test_all_views_all_candidates(shape):
             assert np.all(np.isfinite(got))
             err = float(np.max(np.abs(got - ref) / np.where(refabs > 0, refabs, 1.0)))
             assert err <= TOL, (shape, ta, tb, tc, p and p.table())
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape", [(2, 16, 200, 300), (1, 1, 130, 257), (3, 7, 64, 48), (1, 16, 256, 1024),
+                                   (1, 12, 70, 1000), (1, 16, 1000, 2048)])
+def test_small_m_every_candidate(shape):
+    nb, M, N, K = shape
+    A = W.uniform(W.SEED_BASE + 63, 1, (nb, M, K), -1, 1)
+    Bm = W.uniform(W.SEED_BASE + 63, 2, (nb, K, N), -1, 1)
+    ref, refabs = reference(A, Bm, False, False, False)
+    sizes = (nb, M, N, K, 0, 0, 0)
+    cands = [mdh.mdh_candidate(mdh.MDH_BMATMUL, sizes, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_BMATMUL, sizes))]
+    small = [p for p in cands if p.blk[1] == 16]
+    assert len(small) >= 5
+    for p in small:
+        got, _ = run(A, Bm, False, False, False, p)
+        assert np.all(np.isfinite(got)), p.table()
+        err = float(np.max(np.abs(got - ref) / np.where(refabs > 0, refabs, 1.0)))
+        assert err <= TOL, (shape, p.table())
 
 
 @pytest.mark.gpu
