@@ -310,6 +310,99 @@ mdh_status mdh_candidate(mdh_instance inst, const int64_t* sizes, int32_t idx,
                          mdh_tile_params* out);
 
 /* ------------------------------------------------------------------------- */
+/* Generic md_hom with runtime-compiled scalar function and combine operator  */
+/* ------------------------------------------------------------------------- */
+/*
+ * The method itself rather than a fixed instance (paper: Definition "Higher-Order
+ * Function md_hom", Definitions "Input View" / "Output View"; Section
+ * "Experimental Results" on user-defined scalar types and operators, e.g. PRL):
+ *
+ *   out[out_index(i)] = op_1 ... op_D  f( in_{b_1}[idx_1(i)], ..., in_{b_A}[idx_A(i)], i )
+ *
+ * with op_d = ++ (reduce[d] = 0) or op_d = pw(op) (reduce[d] = 1), a user-defined
+ * result type T, scalar function f and operator op given as C source and compiled
+ * for gfx950 when the operation is created (hipRTC).  All point-wise dimensions of
+ * one operation share ONE operator op, which must be associative and commutative
+ * (paper: Lemma on mixes of ++ and pw); no neutral element is needed (the first
+ * value of a part overrides).  The index functions may read one buffer several
+ * times (stencils) and are arbitrary C expressions (views).
+ *
+ * Source conventions.  Every string is C/HIP device code:
+ *   prelude      type definitions and helper functions, placed first (may be NULL)
+ *   in_type[b]   element type of input buffer b (e.g. "float", or a struct of prelude)
+ *   acc_buf[a], acc_index[a]
+ *                access a reads buffer acc_buf[a] at the flat element index given by
+ *                the expression acc_index[a] over i0..i{D-1} (type long long) and
+ *                the sizes N0..N{D-1}: index function composed with the row-major
+ *                layout of the buffer
+ *   out_type     T: type of f's result, of op's operands and of the output elements
+ *   out_elem_bytes  sizeof(T), checked against the compiled code
+ *   out_index    flat element index in the output buffer; NULL = row-major over the
+ *                ++ dimensions.  Indices of reduced dimensions are 0 here.
+ *   f            statements that set `T r` from a0..a{A-1} (the accessed elements,
+ *                const references) and i0..i{D-1}
+ *   op           statements that set `T r` from `x` and `y` (const T references)
+ *   fast_dim     dimension whose consecutive indices are consecutive in memory for
+ *                the largest operand (gets the fastest lane index); -1 = D-1
+ *
+ * De-composition.  Every dimension is cut into #PRT(WG,d) workgroup parts x
+ * #PRT(LANE,d) lane parts x #PRT(HBM,d) sequential parts (blk = 1: the paper's full
+ * partitioning; no LDS staging of inputs, memory region = device memory).
+ * `strided` = 1: index = (q*WG + g)*LANE + l; 0: index = (g*Q + q)*LANE + l.
+ * Re-composition: registers -> LDS tree over the lanes of the reduced dimensions
+ * -> workspace + second kernel over their workgroup parts, every level in a fixed
+ * order (deterministic).  mdh_custom_default_params / mdh_custom_candidate supply
+ * configurations; explicit ones are validated like those of the fixed instances
+ * (MDH_ERR_TILE_NOT_DIVIDING, MDH_ERR_TILE_RESOURCES, also when a workgroup part
+ * of a reduced dimension would be empty).
+ *
+ * mdh_custom_create compiles (host only: works without a GPU) and returns an
+ * operation handle; `log` (may be NULL) receives the compiler's messages.  The
+ * first mdh_custom_run on a process loads the code object (the only allocation the
+ * runtime makes on behalf of this library); after that a run only enqueues one or
+ * two kernels.  inputs[b] / output / workspace are device pointers; the workspace
+ * needs mdh_custom_workspace_size(op) bytes (0 if no reduced dimension is split
+ * over workgroups).  Handles are not thread-safe.
+ * Errors: MDH_ERR_NULL, MDH_ERR_SIZE (D, n_in, n_acc, sizes out of range),
+ * MDH_ERR_UNSUPPORTED (source does not compile: see log), MDH_ERR_WORKSPACE,
+ * MDH_ERR_LAUNCH, and the tile errors above.
+ */
+#define MDH_CUSTOM_MAX_IN 4
+#define MDH_CUSTOM_MAX_ACC 8
+typedef struct mdh_custom_desc {
+  int32_t D;
+  int64_t sizes[MDH_MAX_D];
+  uint8_t reduce[MDH_MAX_D];
+  int32_t n_in;
+  int32_t n_acc;
+  int32_t acc_buf[MDH_CUSTOM_MAX_ACC];
+  int32_t out_elem_bytes;
+  int32_t fast_dim;
+  const char* prelude;
+  const char* in_type[MDH_CUSTOM_MAX_IN];
+  const char* acc_index[MDH_CUSTOM_MAX_ACC];
+  const char* out_type;
+  const char* out_index;
+  const char* f;
+  const char* op;
+} mdh_custom_desc;
+
+typedef struct mdh_custom_op mdh_custom_op;
+
+mdh_status mdh_custom_default_params(const mdh_custom_desc* desc, mdh_tile_params* out);
+mdh_status mdh_custom_validate_params(const mdh_custom_desc* desc, const mdh_tile_params* params);
+int32_t mdh_custom_num_candidates(const mdh_custom_desc* desc);
+mdh_status mdh_custom_candidate(const mdh_custom_desc* desc, int32_t idx, mdh_tile_params* out);
+mdh_status mdh_custom_create(const mdh_custom_desc* desc, const mdh_tile_params* params,
+                             mdh_custom_op** out, char* log, size_t log_bytes);
+/* Generated device source of the operation (owned by the handle; never NULL). */
+const char* mdh_custom_source(const mdh_custom_op* op);
+size_t mdh_custom_workspace_size(const mdh_custom_op* op);
+mdh_status mdh_custom_run(mdh_custom_op* op, const void* const* inputs, void* output,
+                          void* workspace, size_t workspace_bytes, void* stream);
+void mdh_custom_destroy(mdh_custom_op* op);
+
+/* ------------------------------------------------------------------------- */
 /* Calibration kernels (measurement support; nothing of the method)           */
 /* ------------------------------------------------------------------------- */
 /*

@@ -147,3 +147,47 @@ def custom_reduce(A, B, w_agree, w_disagree):
     ov = H.out_view([[lambda a, b: (a,)], [lambda a, b: (a,)]])
     sc, ix = ov(h(iv([A, B], [range(nA), range(nB)])))
     return [sc[(a,)] for a in range(nA)], [ix[(a,)] for a in range(nA)]
+
+
+def histo(elems, bins):
+    """Histo = md_hom(f_Histo, (++, +)) over (b, e): f_Histo(e, b) = 1 iff the element equals the
+    bin value, else 0 (Section "Examples", Subfigures 4-6: the standard histogram as the instance
+    of GenHisto with + and f_Histo); output view (b,0)->out[b]."""
+    return gen_histo(elems, bins, lambda e, b: 1 if e == b else 0, _add)
+
+
+def gen_histo(elems, bins, f, oplus):
+    """GenHisto: user-defined scalar function f(element, bin) and associative, commutative
+    operator oplus over the element dimension (same passage)."""
+    nb, ne = len(bins), len(elems)
+    iv = H.inp_view([[lambda b, e: (e,)], [lambda b, e: (b,)]])
+    h = H.md_hom(lambda t: f(t[0], t[1]), (H.concat(0), H.pointwise(1, oplus)))
+    (o,) = H.out_view([[lambda b, e: (b,)]])(h(iv([elems, bins], [range(nb), range(ne)])))
+    return [o[(b,)] for b in range(nb)]
+
+
+def jacobi1d(x, c):
+    """Jacobi1D = md_hom(J_1D, (++)) over (i), J_1D = c * (v_i + v_{i+1} + v_{i+2}): the one
+    buffer is read three times with index functions i, i+1, i+2 (Section "Introduction", running
+    stencil example; Example on input views with several accesses); output (i)->(i), N-2 cells."""
+    n = len(x) - 2
+    iv = H.inp_view([[lambda i: (i,), lambda i: (i + 1,), lambda i: (i + 2,)]])
+    h = H.md_hom(lambda t: c * (t[0] + t[1] + t[2]), (H.concat(0),))
+    (o,) = H.out_view([[lambda i: (i,)]])(h(iv([x], [range(n)])))
+    return [o[(i,)] for i in range(n)]
+
+
+def map_f(f, x):
+    """map(f) = md_hom(f, (++)) (Appendix example "map")."""
+    iv = H.inp_view([[lambda i: (i,)]])
+    h = H.md_hom(lambda t: f(t[0]), (H.concat(0),))
+    (o,) = H.out_view([[lambda i: (i,)]])(h(iv([x], [range(len(x))])))
+    return [o[(i,)] for i in range(len(x))]
+
+
+def reduce_op(oplus, x):
+    """reduce(oplus) = md_hom(id, (pw(oplus))) (Appendix example "reduce")."""
+    iv = H.inp_view([[lambda i: (i,)]])
+    h = H.md_hom(lambda t: t[0], (H.pointwise(0, oplus),))
+    (o,) = H.out_view([[lambda i: ()]])(h(iv([x], [range(len(x))])))
+    return o[()]

@@ -22,6 +22,18 @@ from .binding import (  # noqa: F401
     mdh_calib_read,
     mdh_calib_valu,
     mdh_candidate,
+    CustomDesc,
+    CustomOp,
+    custom_desc,
+    mdh_custom_candidate,
+    mdh_custom_create,
+    mdh_custom_default_params,
+    mdh_custom_destroy,
+    mdh_custom_num_candidates,
+    mdh_custom_run,
+    mdh_custom_source,
+    mdh_custom_validate_params,
+    mdh_custom_workspace_size,
     mdh_custom_reduce,
     mdh_default_params,
     mdh_dot,

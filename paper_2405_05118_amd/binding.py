@@ -22,7 +22,10 @@ EXPORTS = (
     "mdh_workspace_size", "mdh_matmul", "mdh_stencil", "mdh_mcc", "mdh_custom_reduce", "mdh_tune",
     "mdh_num_candidates", "mdh_candidate", "mdh_last_launch_error", "mdh_dot", "mdh_matvec",
     "mdh_matmul_ex", "mdh_calib_copy", "mdh_calib_read", "mdh_calib_mfma", "mdh_calib_valu",
+    "mdh_custom_default_params", "mdh_custom_validate_params", "mdh_custom_num_candidates", "mdh_custom_candidate",
+    "mdh_custom_create", "mdh_custom_source", "mdh_custom_workspace_size", "mdh_custom_run", "mdh_custom_destroy",
 )
+MDH_CUSTOM_MAX_IN, MDH_CUSTOM_MAX_ACC = 4, 8
 MDH_CALIB_BLOCKS = 2048
 
 
@@ -107,6 +110,20 @@ def lib() -> ctypes.CDLL:
         L.mdh_matvec.argtypes = [i64, i64, vp, vp, vp, pp, vp, sz, vp]
         L.mdh_tune.argtypes = [ctypes.c_int, p64, ctypes.POINTER(vp), ctypes.POINTER(f32), vp, sz, vp, i32, pp,
                                ctypes.POINTER(f32)]
+        dp = ctypes.POINTER(CustomDesc)
+        L.mdh_custom_default_params.argtypes = [dp, pp]
+        L.mdh_custom_validate_params.argtypes = [dp, pp]
+        L.mdh_custom_num_candidates.restype = i32
+        L.mdh_custom_num_candidates.argtypes = [dp]
+        L.mdh_custom_candidate.argtypes = [dp, i32, pp]
+        L.mdh_custom_create.argtypes = [dp, pp, ctypes.POINTER(vp), ctypes.c_char_p, sz]
+        L.mdh_custom_source.restype = ctypes.c_char_p
+        L.mdh_custom_source.argtypes = [vp]
+        L.mdh_custom_workspace_size.restype = sz
+        L.mdh_custom_workspace_size.argtypes = [vp]
+        L.mdh_custom_run.argtypes = [vp, ctypes.POINTER(vp), vp, vp, sz, vp]
+        L.mdh_custom_destroy.restype = None
+        L.mdh_custom_destroy.argtypes = [vp]
         L.mdh_calib_copy.argtypes = [vp, vp, i64, vp]
         L.mdh_calib_read.argtypes = [vp, i64, vp, vp]
         L.mdh_calib_mfma.argtypes = [vp, i32, p64, vp]
@@ -296,6 +313,117 @@ def mdh_matvec(A, x, y, params: Optional[TileParams] = None, workspace=None):
                           _pref(params), wp, wb, ctypes.c_void_p(_stream()))
     _check(st, "mdh_matvec")
     return y
+
+
+class CustomDesc(ctypes.Structure):
+    """Mirror of ``mdh_custom_desc`` (include/mdh.h)."""
+
+    _fields_ = [
+        ("D", ctypes.c_int32),
+        ("sizes", ctypes.c_int64 * MDH_MAX_D),
+        ("reduce", ctypes.c_uint8 * MDH_MAX_D),
+        ("n_in", ctypes.c_int32),
+        ("n_acc", ctypes.c_int32),
+        ("acc_buf", ctypes.c_int32 * MDH_CUSTOM_MAX_ACC),
+        ("out_elem_bytes", ctypes.c_int32),
+        ("fast_dim", ctypes.c_int32),
+        ("prelude", ctypes.c_char_p),
+        ("in_type", ctypes.c_char_p * MDH_CUSTOM_MAX_IN),
+        ("acc_index", ctypes.c_char_p * MDH_CUSTOM_MAX_ACC),
+        ("out_type", ctypes.c_char_p),
+        ("out_index", ctypes.c_char_p),
+        ("f", ctypes.c_char_p),
+        ("op", ctypes.c_char_p),
+    ]
+
+
+def custom_desc(sizes, reduce, in_types, accesses, out_type, out_elem_bytes, f, op=None, prelude=None,
+                out_index=None, fast_dim=-1) -> CustomDesc:
+    """Fill a ``mdh_custom_desc``: ``accesses`` is a list of (input buffer number, index expression)."""
+    d = CustomDesc()
+    d.D = len(sizes)
+    for i, (n, r) in enumerate(zip(sizes, reduce)):
+        d.sizes[i] = int(n)
+        d.reduce[i] = 1 if r else 0
+    d.n_in, d.n_acc = len(in_types), len(accesses)
+    for b, t in enumerate(in_types):
+        d.in_type[b] = t.encode()
+    for a, (buf, idx) in enumerate(accesses):
+        d.acc_buf[a] = int(buf)
+        d.acc_index[a] = idx.encode()
+    d.out_type, d.out_elem_bytes, d.fast_dim = out_type.encode(), int(out_elem_bytes), int(fast_dim)
+    d.f = f.encode()
+    d.op = op.encode() if op is not None else None
+    d.prelude = prelude.encode() if prelude is not None else None
+    d.out_index = out_index.encode() if out_index is not None else None
+    return d
+
+
+def mdh_custom_default_params(desc: CustomDesc) -> TileParams:
+    p = TileParams()
+    _check(lib().mdh_custom_default_params(ctypes.byref(desc), ctypes.byref(p)), "mdh_custom_default_params")
+    return p
+
+
+def mdh_custom_validate_params(desc: CustomDesc, params: TileParams) -> int:
+    return lib().mdh_custom_validate_params(ctypes.byref(desc), ctypes.byref(params))
+
+
+def mdh_custom_num_candidates(desc: CustomDesc) -> int:
+    return lib().mdh_custom_num_candidates(ctypes.byref(desc))
+
+
+def mdh_custom_candidate(desc: CustomDesc, idx: int) -> TileParams:
+    p = TileParams()
+    _check(lib().mdh_custom_candidate(ctypes.byref(desc), idx, ctypes.byref(p)), "mdh_custom_candidate")
+    return p
+
+
+class CustomOp:
+    """Handle of a compiled generic md_hom operation (``mdh_custom_op*``)."""
+
+    def __init__(self, handle, log):
+        self.handle, self.log = handle, log
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            mdh_custom_destroy(self)
+
+
+def mdh_custom_create(desc: CustomDesc, params: Optional[TileParams] = None) -> CustomOp:
+    """Generate and compile (hipRTC, gfx950) the kernels of one description; needs no GPU."""
+    h = ctypes.c_void_p()
+    log = ctypes.create_string_buffer(16384)
+    st = lib().mdh_custom_create(ctypes.byref(desc), _pref(params), ctypes.byref(h), log, len(log))
+    if st != 0:
+        raise MdhError(st, "mdh_custom_create: " + mdh_strerror(st) + "\n" + log.value.decode(errors="replace"))
+    return CustomOp(h, log.value.decode(errors="replace"))
+
+
+def mdh_custom_source(op: CustomOp) -> str:
+    return lib().mdh_custom_source(op.handle).decode()
+
+
+def mdh_custom_workspace_size(op: CustomOp) -> int:
+    return lib().mdh_custom_workspace_size(op.handle)
+
+
+def mdh_custom_run(op: CustomOp, inputs, output, workspace=None):
+    n = len(inputs)
+    ptrs = (ctypes.c_void_p * n)(*[ctypes.c_void_p(t.data_ptr()) for t in inputs])
+    for t in list(inputs) + [output]:
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("device-resident contiguous tensors are required")
+    wp, wb = _ws(workspace)
+    st = lib().mdh_custom_run(op.handle, ptrs, ctypes.c_void_p(output.data_ptr()), wp, wb, ctypes.c_void_p(_stream()))
+    _check(st, "mdh_custom_run")
+    return output
+
+
+def mdh_custom_destroy(op: CustomOp):
+    if op.handle:
+        lib().mdh_custom_destroy(op.handle)
+        op.handle = None
 
 
 def mdh_calib_copy(src, dst):

@@ -14,6 +14,7 @@ SOURCES = [
     "mdh_plan.cpp",
     "mdh_plan_reduce.cpp",
     "mdh_plan_ex.cpp",
+    "mdh_custom.cpp",
     "mdh_api.hip",
     "mdh_stencil.hip",
     "mdh_matmul.hip",
@@ -68,7 +69,7 @@ def build_library(verbose: bool = False, jobs: int = 6) -> str:
     if failed:
         raise RuntimeError("libmdh build failed")
     tmp = LIB + ".%d.tmp" % os.getpid()
-    subprocess.check_call(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *objs])
+    subprocess.check_call(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *objs, "-lhiprtc"])
     os.replace(tmp, LIB)
     return LIB
 

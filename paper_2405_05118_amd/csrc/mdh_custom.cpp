@@ -1,0 +1,614 @@
+// Generic md_hom with a runtime-compiled scalar function and combine operator
+// (paper: Definition "Higher-Order Function md_hom"; Definitions "Input View" / "Output View";
+// Section "Low-Level Representation": de-composition, scalar phase, re-composition).
+//
+// The kernel source is generated for ONE description and ONE tuning configuration: sizes, part
+// counts and the lane layout are compile-time constants of the generated code, the user's f, op,
+// index functions and types are pasted in, and hipRTC compiles it for gfx950.
+//
+// Per dimension d: index = (q*WG_d + g)*L_d + l  (strided)  or  (g*Q_d + q)*L_d + l  (blocked),
+// g = workgroup part, l = lane part, q = sequential part.  A lane walks its sequential parts of the
+// concatenation dimensions (outer loops) and, for each such point, its sequential parts of the
+// reduced dimensions (inner loops), combining in a register.  The lanes that share a point combine
+// in an LDS tree, workgroups that share it write to the workspace and a second kernel folds the
+// parts in ascending order.  No neutral element: a part starts with its first value, and a flag
+// says whether a lane has one.
+#include <hip/hiprtc.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "mdh_internal.h"
+
+namespace mdh {
+using namespace detail;
+
+namespace {
+
+constexpr int kMaxLanes = 1024;
+constexpr int64_t kLdsBytes = 64 * 1024;
+
+struct CustomPlan {
+  int D;
+  int64_t N[MDH_MAX_D];
+  int red[MDH_MAX_D];
+  int64_t WG[MDH_MAX_D], L[MDH_MAX_D], Q[MDH_MAX_D];
+  int strided;
+  int fast;  // dimension with the fastest lane index
+  int ragged;
+  // derived
+  int NT;          // lanes per workgroup
+  int RL, CL;      // lanes over reduced / concatenation dimensions
+  int64_t SG, CG;  // workgroup parts over reduced / concatenation dimensions
+  int64_t CCN;     // points of the concatenation dimensions
+};
+
+bool desc_ok(const mdh_custom_desc* d) {
+  if (d->D < 1 || d->D > MDH_MAX_D) return false;
+  if (d->n_in < 1 || d->n_in > MDH_CUSTOM_MAX_IN) return false;
+  if (d->n_acc < 1 || d->n_acc > MDH_CUSTOM_MAX_ACC) return false;
+  if (d->out_elem_bytes < 1 || d->out_elem_bytes > 256) return false;
+  if (d->fast_dim >= d->D) return false;
+  int64_t total = 1;
+  for (int i = 0; i < d->D; ++i) {
+    if (d->sizes[i] < 1 || d->sizes[i] > 0x7fffffff) return false;
+    if (total > (int64_t)1 << 50) return false;
+    total *= d->sizes[i];
+  }
+  for (int a = 0; a < d->n_acc; ++a)
+    if (d->acc_buf[a] < 0 || d->acc_buf[a] >= d->n_in) return false;
+  return true;
+}
+
+mdh_status desc_ptrs(const mdh_custom_desc* d) {
+  if (!d->out_type || !d->f) return MDH_ERR_NULL;
+  for (int b = 0; b < d->n_in; ++b)
+    if (!d->in_type[b]) return MDH_ERR_NULL;
+  for (int a = 0; a < d->n_acc; ++a)
+    if (!d->acc_index[a]) return MDH_ERR_NULL;
+  for (int i = 0; i < d->D; ++i)
+    if (d->reduce[i] && !d->op) return MDH_ERR_NULL;
+  return MDH_OK;
+}
+
+void derive(CustomPlan* p) {
+  p->NT = 1, p->RL = 1, p->CL = 1, p->SG = 1, p->CG = 1, p->CCN = 1;
+  for (int d = 0; d < p->D; ++d) {
+    p->NT *= (int)p->L[d];
+    if (p->red[d]) {
+      p->RL *= (int)p->L[d];
+      p->SG *= p->WG[d];
+    } else {
+      p->CL *= (int)p->L[d];
+      p->CG *= p->WG[d];
+      p->CCN *= p->N[d];
+    }
+  }
+}
+
+void params_from_custom(const CustomPlan& pl, mdh_tile_params* p) {
+  clear_params(p, pl.D);
+  int dims[MDH_MAX_D];
+  for (int d = 0; d < pl.D; ++d) {
+    p->prt[MDH_L_WG][d] = (int32_t)pl.WG[d];
+    p->prt[MDH_L_LANE][d] = (int32_t)pl.L[d];
+    p->prt[MDH_L_HBM][d] = (int32_t)pl.Q[d];
+    dims[d] = d;
+  }
+  set_order(p, dims);
+  p->strided = (uint8_t)pl.strided;
+  p->lane_fast_dim = (uint8_t)pl.fast;
+  p->out_region = MDH_MR_VGPR;  // results are combined in registers, inputs stay in device memory
+  p->ragged = (uint8_t)pl.ragged;
+}
+
+void fill_from_desc(const mdh_custom_desc* d, CustomPlan* pl) {
+  memset(pl, 0, sizeof(*pl));
+  pl->D = d->D;
+  for (int i = 0; i < d->D; ++i) {
+    pl->N[i] = d->sizes[i];
+    pl->red[i] = d->reduce[i] ? 1 : 0;
+    pl->WG[i] = pl->L[i] = pl->Q[i] = 1;
+  }
+  pl->fast = d->fast_dim < 0 ? d->D - 1 : d->fast_dim;
+  pl->strided = 1;
+}
+
+int pow2_floor(int64_t x) {
+  int p = 1;
+  while ((int64_t)p * 2 <= x) p *= 2;
+  return p;
+}
+
+// lanes: `nt` lanes, first along the fast dimension, the rest along the largest other dimension
+// (concatenation dimensions preferred); workgroup parts: all of the concatenation dimensions, and
+// the reduced dimensions `split` ways in total while every part keeps at least 8 sequential steps.
+CustomPlan make_plan(const mdh_custom_desc* d, int nt, int64_t split) {
+  CustomPlan pl;
+  fill_from_desc(d, &pl);
+  int left = nt;
+  pl.L[pl.fast] = pow2_floor(pl.N[pl.fast] < left ? pl.N[pl.fast] : left);
+  left /= (int)pl.L[pl.fast];
+  while (left > 1) {
+    int best = -1;
+    for (int pass = 0; pass < 2 && best < 0; ++pass)
+      for (int i = pl.D - 1; i >= 0; --i) {
+        if (i == pl.fast || (pass == 0 && pl.red[i])) continue;
+        if (pl.N[i] / pl.L[i] < 2) continue;
+        if (best < 0 || pl.N[i] / pl.L[i] > pl.N[best] / pl.L[best]) best = i;
+      }
+    if (best < 0) break;
+    pl.L[best] *= 2;
+    left /= 2;
+  }
+  for (int i = 0; i < pl.D; ++i)
+    if (!pl.red[i]) pl.WG[i] = cdiv(pl.N[i], pl.L[i]);
+  // sequential parts of the concatenation dimensions only when the grid would not fit
+  for (int i = 0; i < pl.D; ++i) {
+    if (pl.red[i]) continue;
+    int64_t grid = 1;
+    for (int j = 0; j < pl.D; ++j) grid *= pl.WG[j];
+    while (grid > (1 << 24) && pl.WG[i] > 1) {
+      pl.WG[i] = cdiv(pl.WG[i], 2);
+      grid = cdiv(grid, 2);
+    }
+  }
+  for (int i = 0; i < pl.D && split > 1; ++i) {
+    if (!pl.red[i]) continue;
+    while (split > 1 && cdiv(pl.N[i], pl.L[i] * pl.WG[i] * 2) >= 8) {
+      pl.WG[i] *= 2;
+      split /= 2;
+    }
+  }
+  pl.ragged = 0;
+  for (int i = 0; i < pl.D; ++i) {
+    pl.Q[i] = cdiv(pl.N[i], pl.WG[i] * pl.L[i]);
+    // no empty workgroup part: shrink WG to the parts that own at least one index
+    pl.WG[i] = cdiv(pl.N[i], pl.Q[i] * pl.L[i]);
+    if (pl.WG[i] * pl.L[i] * pl.Q[i] != pl.N[i]) pl.ragged = 1;
+  }
+  // with a blocked walk every workgroup part starts at g*Q*L; strided parts start at g*L: both
+  // are non-empty now.  Blocked is the safe choice when Q*L*WG overshoots N by more than one part.
+  pl.strided = 0;
+  derive(&pl);
+  return pl;
+}
+
+CustomPlan default_plan(const mdh_custom_desc* d) {
+  CustomPlan pl = make_plan(d, 256, 1);
+  // few workgroups: split the reduced dimensions over workgroups up to ~2048 workgroups
+  int64_t grid = pl.SG * pl.CG;
+  if (grid < 1024) {
+    int64_t split = 1;
+    while (grid * split < 2048) split *= 2;
+    pl = make_plan(d, 256, split);
+  }
+  return pl;
+}
+
+int candidates(const mdh_custom_desc* d, CustomPlan* out, int cap) {
+  int n = 0;
+  auto push = [&](const CustomPlan& c) {
+    if (n >= cap) return;
+    for (int i = 0; i < n; ++i) {
+      bool same = out[i].strided == c.strided;
+      for (int k = 0; k < c.D && same; ++k)
+        same = out[i].WG[k] == c.WG[k] && out[i].L[k] == c.L[k] && out[i].Q[k] == c.Q[k];
+      if (same) return;
+    }
+    out[n++] = c;
+  };
+  push(default_plan(d));
+  bool any_red = false;
+  for (int i = 0; i < d->D; ++i) any_red |= d->reduce[i] != 0;
+  static const int nts[] = {256, 64, 128, 512, 1024};
+  static const int64_t splits[] = {1, 4, 16, 64, 256, 1024, 4096};
+  for (int nt : nts)
+    for (int64_t s : splits) {
+      if (s > 1 && !any_red) continue;
+      push(make_plan(d, nt, s));
+    }
+  return n;
+}
+
+mdh_status plan_from_params(const mdh_custom_desc* d, const mdh_tile_params* p, CustomPlan* out) {
+  if (!p) {
+    *out = default_plan(d);
+    return MDH_OK;
+  }
+  if (p->D != d->D) return MDH_ERR_UNSUPPORTED;
+  bool ragged;
+  mdh_status st = check_products(p, d->sizes, &ragged);
+  if (st != MDH_OK) return st;
+  if ((st = check_lanes(p)) != MDH_OK) return st;
+  CustomPlan pl;
+  fill_from_desc(d, &pl);
+  for (int i = 0; i < d->D; ++i) {
+    pl.WG[i] = p->prt[MDH_L_WG][i];
+    pl.L[i] = p->prt[MDH_L_LANE][i];
+    pl.Q[i] = p->prt[MDH_L_HBM][i];
+    // a workgroup part of any dimension that owns no index would leave its partial result unset
+    const int64_t first_of_last = p->strided ? (pl.WG[i] - 1) * pl.L[i] : (pl.WG[i] - 1) * pl.Q[i] * pl.L[i];
+    if (first_of_last >= pl.N[i]) return MDH_ERR_TILE_NOT_DIVIDING;
+  }
+  if (p->lane_fast_dim >= d->D) return MDH_ERR_UNSUPPORTED;
+  pl.fast = p->lane_fast_dim;
+  pl.strided = p->strided ? 1 : 0;
+  pl.ragged = ragged;
+  derive(&pl);
+  mdh_tile_params chk;
+  params_from_custom(pl, &chk);
+  if (!same_table(chk, *p)) return MDH_ERR_UNSUPPORTED;  // e.g. parts on the LDS / register layers
+  *out = pl;
+  return MDH_OK;
+}
+
+mdh_status plan_resources(const mdh_custom_desc* d, const CustomPlan& pl) {
+  if (pl.NT > kMaxLanes) return MDH_ERR_TILE_RESOURCES;
+  if (pl.RL > 1 && (int64_t)pl.NT * (d->out_elem_bytes + 1) > kLdsBytes) return MDH_ERR_TILE_RESOURCES;
+  if (pl.SG * pl.CG > 0x7fffffff) return MDH_ERR_SIZE;
+  return MDH_OK;
+}
+
+// ------------------------------------------------------------------------------ code generation
+
+struct Src {
+  std::string s;
+  void line(const std::string& t) { s += t, s += '\n'; }
+  template <class... A>
+  void f(const char* fmt, A... a) {
+    char buf[1024];
+    snprintf(buf, sizeof buf, fmt, a...);
+    s += buf;
+    s += '\n';
+  }
+};
+
+std::string index_expr(const CustomPlan& pl, int d) {
+  char buf[160];
+  if (pl.strided)
+    snprintf(buf, sizeof buf, "((i64)q%d * %lldLL + g%d) * %lldLL + l%d", d, (long long)pl.WG[d], d, (long long)pl.L[d], d);
+  else
+    snprintf(buf, sizeof buf, "((i64)g%d * %lldLL + q%d) * %lldLL + l%d", d, (long long)pl.Q[d], d, (long long)pl.L[d], d);
+  return buf;
+}
+
+std::string generate(const mdh_custom_desc* d, const CustomPlan& pl) {
+  Src o;
+  const int D = pl.D;
+  o.line("// generated by libmdh: one md_hom description, one tuning configuration");
+  o.line("typedef long long i64;");
+  for (int i = 0; i < D; ++i) o.f("#define N%d %lldLL", i, (long long)pl.N[i]);
+  if (d->prelude) o.line(d->prelude);
+  o.line(std::string("typedef ") + d->out_type + " mdh_T;");
+  o.f("static_assert(sizeof(mdh_T) == %d, \"out_elem_bytes does not match sizeof(out_type)\");", d->out_elem_bytes);
+  for (int b = 0; b < d->n_in; ++b)
+    o.line(std::string("typedef ") + d->in_type[b] + " mdh_in" + std::to_string(b) + "_t;");
+
+  // scalar function and combine operator
+  std::string sig;
+  for (int a = 0; a < d->n_acc; ++a) {
+    char buf[96];
+    snprintf(buf, sizeof buf, "const mdh_in%d_t& a%d, ", d->acc_buf[a], a);
+    sig += buf;
+  }
+  for (int i = 0; i < D; ++i) {
+    char buf[48];
+    snprintf(buf, sizeof buf, "%si64 i%d", i ? ", " : "", i);
+    sig += buf;
+  }
+  o.line("__device__ __forceinline__ mdh_T mdh_f(" + sig + ") {");
+  o.line("  mdh_T r;");
+  for (int i = 0; i < D; ++i) o.f("  (void)i%d;", i);
+  o.line(d->f);
+  o.line("  return r;");
+  o.line("}");
+  o.line("__device__ __forceinline__ mdh_T mdh_op(const mdh_T& x, const mdh_T& y) {");
+  o.line("  mdh_T r;");
+  o.line(d->op ? d->op : "  r = x; (void)y;");
+  o.line("  return r;");
+  o.line("}");
+
+  // emission order of the lane coordinates: the group (reduced / concatenation) of the fast
+  // dimension first, the fast dimension first inside it
+  std::vector<int> order;
+  const int fast_red = pl.red[pl.fast];
+  for (int grp = 0; grp < 2; ++grp) {
+    const int want = grp == 0 ? fast_red : !fast_red;
+    if (pl.red[pl.fast] == want) order.push_back(pl.fast);
+    for (int i = D - 1; i >= 0; --i)
+      if (i != pl.fast && pl.red[i] == want) order.push_back(i);
+  }
+
+  std::string params;
+  for (int b = 0; b < d->n_in; ++b) {
+    char buf[96];
+    snprintf(buf, sizeof buf, "const mdh_in%d_t* __restrict__ in%d, ", b, b);
+    params += buf;
+  }
+  o.line("extern \"C\" __global__ __launch_bounds__(" + std::to_string(pl.NT) + ") void mdh_custom_main(" + params +
+         "mdh_T* __restrict__ out, mdh_T* __restrict__ ws) {");
+  o.line("  const int tid = (int)threadIdx.x;");
+  o.line("  int t_ = tid;");
+  for (int i : order) o.f("  const int l%d = t_ %% %lld; t_ /= %lld;", i, (long long)pl.L[i], (long long)pl.L[i]);
+  o.line("  unsigned b_ = blockIdx.x;");
+  for (int i : order) o.f("  const int g%d = (int)(b_ %% %lldu); b_ /= %lldu;", i, (long long)pl.WG[i], (long long)pl.WG[i]);
+  // flat lane index over the reduced dimensions and flat workgroup part over them
+  {
+    std::string rl = "0", sg = "0";
+    int64_t mul = 1, gm = 1;
+    for (int i : order)
+      if (pl.red[i]) {
+        char buf[96];
+        snprintf(buf, sizeof buf, " + l%d * %lld", i, (long long)mul);
+        rl += buf;
+        snprintf(buf, sizeof buf, " + (i64)g%d * %lldLL", i, (long long)gm);
+        sg += buf;
+        mul *= pl.L[i];
+        gm *= pl.WG[i];
+      }
+    o.line("  const int rl = " + rl + ";");
+    o.line("  const i64 sg = " + sg + ";");
+  }
+  o.line("  (void)rl; (void)sg; (void)ws;");
+  if (pl.RL > 1) {
+    o.f("  __shared__ mdh_T sh_val[%d];", pl.NT);
+    o.f("  __shared__ unsigned char sh_ok[%d];", pl.NT);
+  }
+  // concatenation dimensions: outer sequential loops
+  std::string ind = "  ";
+  std::string cc_ok = "true";
+  for (int i = 0; i < D; ++i)
+    if (!pl.red[i]) {
+      o.f("%sfor (int q%d = 0; q%d < %lld; ++q%d) {", ind.c_str(), i, i, (long long)pl.Q[i], i);
+      ind += "  ";
+      o.f("%sconst i64 i%d = %s;", ind.c_str(), i, index_expr(pl, i).c_str());
+      char buf[48];
+      snprintf(buf, sizeof buf, " && i%d < N%d", i, i);
+      cc_ok += buf;
+    }
+  o.line(ind + "const bool cc_ok = " + cc_ok + ";");
+  o.f("%smdh_T acc;", ind.c_str());
+  o.f("%sbool have = false;", ind.c_str());
+  std::string ind2 = ind;
+  std::string red_ok = "cc_ok";
+  for (int i = 0; i < D; ++i)
+    if (pl.red[i]) {
+      o.f("%sfor (int q%d = 0; q%d < %lld; ++q%d) {", ind2.c_str(), i, i, (long long)pl.Q[i], i);
+      ind2 += "  ";
+      o.f("%sconst i64 i%d = %s;", ind2.c_str(), i, index_expr(pl, i).c_str());
+      char buf[48];
+      snprintf(buf, sizeof buf, " && i%d < N%d", i, i);
+      red_ok += buf;
+    }
+  {
+    std::string call;
+    for (int a = 0; a < d->n_acc; ++a) {
+      call += "in" + std::to_string(d->acc_buf[a]) + "[" + d->acc_index[a] + "], ";
+    }
+    for (int i = 0; i < D; ++i) call += (i ? ", i" : "i") + std::to_string(i);
+    o.line(ind2 + "if (" + red_ok + ") {");
+    o.line(ind2 + "  const mdh_T v = mdh_f(" + call + ");");
+    o.f("%s  if (have) acc = mdh_op(acc, v); else { acc = v; have = true; }", ind2.c_str());
+    o.f("%s}", ind2.c_str());
+  }
+  for (int i = 0; i < D; ++i)
+    if (pl.red[i]) {
+      ind2.resize(ind2.size() - 2);
+      o.f("%s}", ind2.c_str());
+    }
+  // lane -> workgroup: LDS tree over the lanes of the reduced dimensions
+  if (pl.RL > 1) {
+    const int step = fast_red ? 1 : pl.CL;  // distance in tid between neighbouring reduced-lane indices
+    int p2 = 1;
+    while (p2 < pl.RL) p2 *= 2;
+    o.f("%ssh_val[tid] = acc; sh_ok[tid] = have ? 1 : 0;", ind.c_str());
+    o.f("%s__syncthreads();", ind.c_str());
+    o.f("%sfor (int s_ = %d; s_ > 0; s_ >>= 1) {", ind.c_str(), p2 / 2);
+    o.f("%s  if (rl < s_ && rl + s_ < %d) {", ind.c_str(), pl.RL);
+    o.f("%s    const int p_ = tid + s_ * %d;", ind.c_str(), step);
+    o.f("%s    if (sh_ok[p_]) { if (have) acc = mdh_op(acc, sh_val[p_]); else { acc = sh_val[p_]; have = true; } }", ind.c_str());
+    o.f("%s    sh_val[tid] = acc; sh_ok[tid] = have ? 1 : 0;", ind.c_str());
+    o.f("%s  }", ind.c_str());
+    o.f("%s  __syncthreads();", ind.c_str());
+    o.f("%s}", ind.c_str());
+  }
+  // output view / workspace
+  {
+    std::string ccflat = "0";
+    for (int i = 0; i < D; ++i)
+      if (!pl.red[i]) ccflat = "(" + ccflat + ") * N" + std::to_string(i) + " + i" + std::to_string(i);
+    o.f("%sif (rl == 0 && cc_ok && have) {", ind.c_str());
+    for (int i = 0; i < D; ++i)
+      if (pl.red[i]) o.f("%s  const i64 i%d = 0; (void)i%d;", ind.c_str(), i, i);
+    o.line(ind + "  const i64 cc_ = " + ccflat + ";");
+    if (pl.SG > 1)
+      o.f("%s  ws[sg * %lldLL + cc_] = acc;", ind.c_str(), (long long)pl.CCN);
+    else
+      o.line(ind + "  out[" + (d->out_index ? d->out_index : "cc_") + "] = acc; (void)cc_;");
+    o.f("%s}", ind.c_str());
+  }
+  for (int i = 0; i < D; ++i)
+    if (!pl.red[i]) {
+      ind.resize(ind.size() - 2);
+      o.f("%s}", ind.c_str());
+    }
+  o.line("}");
+
+  // second pass: fold the workgroup parts of the reduced dimensions in ascending order
+  o.line("extern \"C\" __global__ __launch_bounds__(256) void mdh_custom_combine(const mdh_T* __restrict__ ws, mdh_T* __restrict__ out) {");
+  o.f("  for (i64 cc_ = (i64)blockIdx.x * 256 + threadIdx.x; cc_ < %lldLL; cc_ += (i64)gridDim.x * 256) {", (long long)pl.CCN);
+  o.line("    mdh_T acc = ws[cc_];");
+  o.f("    for (i64 s_ = 1; s_ < %lldLL; ++s_) acc = mdh_op(acc, ws[s_ * %lldLL + cc_]);", (long long)pl.SG, (long long)pl.CCN);
+  o.line("    i64 c_ = cc_;");
+  for (int i = D - 1; i >= 0; --i) {
+    if (pl.red[i])
+      o.f("    const i64 i%d = 0; (void)i%d;", i, i);
+    else
+      o.f("    const i64 i%d = c_ %% N%d; c_ /= N%d; (void)i%d;", i, i, i, i);
+  }
+  o.line(std::string("    out[") + (d->out_index ? d->out_index : "cc_") + "] = acc;");
+  o.line("  }");
+  o.line("}");
+  return o.s;
+}
+
+}  // namespace
+}  // namespace mdh
+
+using namespace mdh;
+
+struct mdh_custom_op {
+  CustomPlan plan;
+  int n_in;
+  int out_bytes;
+  std::string source;
+  std::vector<char> code;
+  hipModule_t module = nullptr;
+  hipFunction_t fmain = nullptr, fcombine = nullptr;
+};
+
+extern "C" {
+
+mdh_status mdh_custom_default_params(const mdh_custom_desc* desc, mdh_tile_params* out) {
+  if (!desc || !out) return MDH_ERR_NULL;
+  if (!desc_ok(desc)) return MDH_ERR_SIZE;
+  params_from_custom(default_plan(desc), out);
+  return MDH_OK;
+}
+
+mdh_status mdh_custom_validate_params(const mdh_custom_desc* desc, const mdh_tile_params* params) {
+  if (!desc || !params) return MDH_ERR_NULL;
+  if (!desc_ok(desc)) return MDH_ERR_SIZE;
+  CustomPlan pl;
+  mdh_status st = plan_from_params(desc, params, &pl);
+  if (st != MDH_OK) return st;
+  return plan_resources(desc, pl);
+}
+
+int32_t mdh_custom_num_candidates(const mdh_custom_desc* desc) {
+  if (!desc || !desc_ok(desc)) return 0;
+  CustomPlan c[64];
+  return candidates(desc, c, 64);
+}
+
+mdh_status mdh_custom_candidate(const mdh_custom_desc* desc, int32_t idx, mdh_tile_params* out) {
+  if (!desc || !out) return MDH_ERR_NULL;
+  if (!desc_ok(desc)) return MDH_ERR_SIZE;
+  CustomPlan c[64];
+  const int n = candidates(desc, c, 64);
+  if (idx < 0 || idx >= n) return MDH_ERR_SIZE;
+  params_from_custom(c[idx], out);
+  return MDH_OK;
+}
+
+mdh_status mdh_custom_create(const mdh_custom_desc* desc, const mdh_tile_params* params,
+                             mdh_custom_op** out, char* log, size_t log_bytes) {
+  if (log && log_bytes) log[0] = 0;
+  if (!desc || !out) return MDH_ERR_NULL;
+  *out = nullptr;
+  if (!desc_ok(desc)) return MDH_ERR_SIZE;
+  mdh_status st = desc_ptrs(desc);
+  if (st != MDH_OK) return st;
+  CustomPlan pl;
+  if ((st = plan_from_params(desc, params, &pl)) != MDH_OK) return st;
+  if ((st = plan_resources(desc, pl)) != MDH_OK) return st;
+
+  mdh_custom_op* op = new mdh_custom_op;
+  op->plan = pl;
+  op->n_in = desc->n_in;
+  op->out_bytes = desc->out_elem_bytes;
+  op->source = generate(desc, pl);
+
+  hiprtcProgram prog;
+  if (hiprtcCreateProgram(&prog, op->source.c_str(), "mdh_custom.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS) {
+    delete op;
+    return MDH_ERR_LAUNCH;
+  }
+  // same code generation switches as the rest of the library
+  const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature",
+                        "-Xclang", "-packed-fp32-ops"};
+  const hiprtcResult rc = hiprtcCompileProgram(prog, (int)(sizeof opts / sizeof opts[0]), opts);
+  if (log && log_bytes) {
+    size_t n = 0;
+    if (hiprtcGetProgramLogSize(prog, &n) == HIPRTC_SUCCESS && n > 1) {
+      std::vector<char> full(n + 1, 0);
+      hiprtcGetProgramLog(prog, full.data());
+      snprintf(log, log_bytes, "%s", full.data());
+    }
+  }
+  if (rc != HIPRTC_SUCCESS) {
+    hiprtcDestroyProgram(&prog);
+    delete op;
+    return MDH_ERR_UNSUPPORTED;
+  }
+  size_t csz = 0;
+  hiprtcGetCodeSize(prog, &csz);
+  op->code.resize(csz);
+  hiprtcGetCode(prog, op->code.data());
+  hiprtcDestroyProgram(&prog);
+  *out = op;
+  return MDH_OK;
+}
+
+const char* mdh_custom_source(const mdh_custom_op* op) { return op ? op->source.c_str() : ""; }
+
+size_t mdh_custom_workspace_size(const mdh_custom_op* op) {
+  if (!op || op->plan.SG <= 1) return 0;
+  return (size_t)op->plan.SG * (size_t)op->plan.CCN * (size_t)op->out_bytes;
+}
+
+mdh_status mdh_custom_run(mdh_custom_op* op, const void* const* inputs, void* output, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  if (!op || !inputs || !output) return MDH_ERR_NULL;
+  for (int b = 0; b < op->n_in; ++b)
+    if (!inputs[b]) return MDH_ERR_NULL;
+  const CustomPlan& pl = op->plan;
+  if (pl.SG > 1 && (!workspace || workspace_bytes < mdh_custom_workspace_size(op))) return MDH_ERR_WORKSPACE;
+  clear_stale_error();
+  if (!op->module) {
+    if (hipModuleLoadData(&op->module, op->code.data()) != hipSuccess) {
+      launch_status();
+      return MDH_ERR_LAUNCH;
+    }
+    if (hipModuleGetFunction(&op->fmain, op->module, "mdh_custom_main") != hipSuccess ||
+        hipModuleGetFunction(&op->fcombine, op->module, "mdh_custom_combine") != hipSuccess) {
+      launch_status();
+      return MDH_ERR_LAUNCH;
+    }
+  }
+  const void* in[MDH_CUSTOM_MAX_IN];
+  void* args[MDH_CUSTOM_MAX_IN + 2];
+  int na = 0;
+  for (int b = 0; b < op->n_in; ++b) {
+    in[b] = inputs[b];
+    args[na++] = (void*)&in[b];
+  }
+  args[na++] = (void*)&output;
+  args[na++] = (void*)&workspace;
+  const unsigned grid = (unsigned)(pl.SG * pl.CG);
+  if (hipModuleLaunchKernel(op->fmain, grid, 1, 1, (unsigned)pl.NT, 1, 1, 0, (hipStream_t)stream, args, nullptr) != hipSuccess) {
+    launch_status();
+    return MDH_ERR_LAUNCH;
+  }
+  if (pl.SG > 1) {
+    void* cargs[2] = {(void*)&workspace, (void*)&output};
+    int64_t blocks = cdiv(pl.CCN, 256);
+    if (blocks > 4096) blocks = 4096;
+    if (hipModuleLaunchKernel(op->fcombine, (unsigned)blocks, 1, 1, 256, 1, 1, 0, (hipStream_t)stream, cargs, nullptr) != hipSuccess) {
+      launch_status();
+      return MDH_ERR_LAUNCH;
+    }
+  }
+  return MDH_OK;
+}
+
+void mdh_custom_destroy(mdh_custom_op* op) {
+  if (!op) return;
+  if (op->module) hipModuleUnload(op->module);
+  delete op;
+}
+
+}  // extern "C"

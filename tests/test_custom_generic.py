@@ -1,0 +1,270 @@
+"""Generic md_hom with runtime-compiled scalar function and combine operator (mdh_custom_*).
+
+Reference: the generic evaluator of oracle/mdhom.py (the paper's definitions of md_hom, ++, pw and
+the views, evaluated literally) on small index spaces, and the C oracle / a library routine on
+larger ones.  The instances below are those of the paper's example table that the fixed kernels
+do not cover (Histo, GenHisto, map, reduce, Jacobi1D) plus Dot, MatVec, MatMul and PRL again, this
+time through user-supplied source."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2405_05118_amd as mdh
+from oracle import instances as G
+from paper_2405_05118_amd import binding as B
+from paper_2405_05118_amd import workloads as W
+
+# ------------------------------------------------------------------ pins of the new oracle instances
+
+
+def test_histo_oracle_against_bincount():
+    rng = np.random.default_rng(11)
+    elems = rng.integers(0, 7, 40).tolist()
+    bins = list(range(7))
+    assert G.histo(elems, bins) == np.bincount(elems, minlength=7).tolist()
+    # bins need not be 0..B-1, and a value that never occurs counts 0
+    assert G.histo([5, 9, 5, 2], [9, 4, 5]) == [1, 0, 2]
+    # GenHisto with max: largest element not above the bin bound (a different f and operator)
+    got = G.gen_histo([3, 8, 1, 6], [2, 7, 9], lambda e, b: e if e <= b else -1, max)
+    assert got == [1, 6, 8]
+
+
+def test_jacobi1d_oracle_against_printed_form():
+    # w_i = c * (v_i + v_{i+1} + v_{i+2}), N-2 outputs (Section "Introduction")
+    x = [1, 4, 9, 16, 25, 36]
+    assert G.jacobi1d(x, 2) == [2 * (1 + 4 + 9), 2 * (4 + 9 + 16), 2 * (9 + 16 + 25), 2 * (16 + 25 + 36)]
+    assert G.map_f(lambda v: v * v, [1, 2, 3]) == [1, 4, 9]
+    assert G.reduce_op(min, [4, 2, 7]) == 2
+
+
+# ------------------------------------------------------------------ descriptions used below
+
+PRL_PRE = "struct rec { int f[8]; }; struct res { int score; int idx; };"
+PRL_F = ("int s = 0; for (int k = 0; k < 8; ++k) s += a0.f[k] == a1.f[k] ? a2.f[k] : a3.f[k];"
+         " r.score = s; r.idx = (int)i1;")
+PRL_OP = "if (x.score > y.score || (x.score == y.score && x.idx < y.idx)) r = x; else r = y;"
+
+
+def d_dot(K):
+    return mdh.custom_desc((K,), (1,), ["float", "float"], [(0, "i0"), (1, "i0")], "float", 4, "r = a0 * a1;", "r = x + y;")
+
+
+def d_matvec(M, K):
+    return mdh.custom_desc((M, K), (0, 1), ["float", "float"], [(0, "i0*N1+i1"), (1, "i1")], "float", 4,
+                           "r = a0 * a1;", "r = x + y;")
+
+
+def d_matmul(M, N, K, fast=1):
+    return mdh.custom_desc((M, N, K), (0, 0, 1), ["float", "float"], [(0, "i0*N2+i2"), (1, "i2*N1+i1")], "float", 4,
+                           "r = a0 * a1;", "r = x + y;", fast_dim=fast)
+
+
+def d_prl(nA, nB):
+    return mdh.custom_desc((nA, nB), (0, 1), ["rec"] * 4, [(0, "i0"), (1, "i1"), (2, "0"), (3, "0")], "res", 8,
+                           PRL_F, PRL_OP, PRL_PRE, fast_dim=0)
+
+
+def d_histo(nbins, ne):
+    return mdh.custom_desc((nbins, ne), (0, 1), ["int", "int"], [(0, "i1"), (1, "i0")], "int", 4,
+                           "r = a0 == a1 ? 1 : 0;", "r = x + y;")
+
+
+def d_jacobi1d(n, c):
+    return mdh.custom_desc((n,), (0,), ["float"], [(0, "i0"), (0, "i0+1"), (0, "i0+2")], "float", 4,
+                           "r = (float)%r * (a0 + a1 + a2);" % float(c))
+
+
+# ------------------------------------------------------------------ host side (no GPU)
+
+
+@pytest.mark.parametrize("desc", [d_dot(1 << 20), d_dot(1000), d_matvec(512, 4096), d_matvec(7, 33),
+                                  d_matmul(40, 50, 60), d_prl(1000, 3000), d_histo(256, 100000), d_jacobi1d(5000, 0.5)])
+def test_planner_tables(desc):
+    p = mdh.mdh_custom_default_params(desc)
+    assert p.D == desc.D and list(p.blk[: p.D]) == [1] * p.D  # the paper's full partitioning
+    for d in range(p.D):
+        e = p.extent(d)
+        assert e >= desc.sizes[d] if p.ragged else e == desc.sizes[d]
+    assert mdh.mdh_custom_validate_params(desc, p) == 0
+    n = mdh.mdh_custom_num_candidates(desc)
+    assert n >= 2
+    for i in range(n):
+        assert mdh.mdh_custom_validate_params(desc, mdh.mdh_custom_candidate(desc, i)) == 0
+
+
+def test_planner_rejects_bad_tables():
+    desc = d_matvec(512, 4096)
+    p = mdh.mdh_custom_default_params(desc)
+    q = p.copy()
+    q.prt[B.L_HBM][1] += 1  # product no longer N_d
+    assert mdh.mdh_custom_validate_params(desc, q) == 3
+    q = p.copy()
+    q.prt[B.L_LDS][1], q.prt[B.L_HBM][1] = q.prt[B.L_HBM][1], 1  # parts on a layer the generic kernel does not stage
+    assert mdh.mdh_custom_validate_params(desc, q) == 6
+    q = p.copy()
+    q.prt[B.L_LANE][0], q.prt[B.L_WG][0] = 2048, 1  # more than 1024 lanes
+    q.prt[B.L_HBM][0] = 1
+    q.ragged = 1
+    assert mdh.mdh_custom_validate_params(desc, q) == 4
+    # a workgroup part of the reduced dimension that owns no index
+    small = d_matvec(4, 100)
+    q = mdh.mdh_custom_default_params(small)
+    q.prt[B.L_WG][1], q.prt[B.L_LANE][1], q.prt[B.L_HBM][1], q.ragged = 4, 64, 1, 1
+    assert mdh.mdh_custom_validate_params(small, q) == 3
+
+
+def test_compiles_without_gpu_and_reports_errors():
+    op = mdh.mdh_custom_create(d_prl(100, 300))
+    src = mdh.mdh_custom_source(op)
+    assert "mdh_custom_main" in src and "struct rec" in src and "a0.f[k] == a1.f[k]" in src
+    mdh.mdh_custom_destroy(op)
+    with pytest.raises(mdh.MdhError) as e:
+        mdh.mdh_custom_create(mdh.custom_desc((8,), (1,), ["float"], [(0, "i0")], "float", 4, "r = a0 +;", "r = x + y;"))
+    assert e.value.status == 6 and "error" in str(e.value)
+    with pytest.raises(mdh.MdhError) as e:  # sizeof(out_type) disagrees with out_elem_bytes
+        mdh.mdh_custom_create(mdh.custom_desc((8,), (1,), ["float"], [(0, "i0")], "double", 4, "r = a0;", "r = x + y;"))
+    assert "out_elem_bytes" in str(e.value)
+    with pytest.raises(mdh.MdhError) as e:  # a reduced dimension needs an operator
+        mdh.mdh_custom_create(mdh.custom_desc((8,), (1,), ["float"], [(0, "i0")], "float", 4, "r = a0;"))
+    assert e.value.status == 1
+
+
+# ------------------------------------------------------------------ GPU parity
+
+torch = pytest.importorskip("torch")
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run(desc, inputs, out, params=None):
+    op = mdh.mdh_custom_create(desc, params)
+    n = mdh.mdh_custom_workspace_size(op)
+    ws = torch.empty(max(n, 4), dtype=torch.uint8, device="cuda") if n else None
+    mdh.mdh_custom_run(op, inputs, out, ws)
+    torch.cuda.synchronize()
+    mdh.mdh_custom_destroy(op)
+    return out
+
+
+def all_params(desc):
+    return [None] + [mdh.mdh_custom_candidate(desc, i) for i in range(mdh.mdh_custom_num_candidates(desc))]
+
+
+@pytest.mark.gpu
+def test_small_against_generic_evaluator():
+    rng = np.random.default_rng(3)
+    # MatMul (integers stored as float: exact)
+    M, N, K = 5, 7, 9
+    A = rng.integers(-4, 5, (M, K)).astype(np.float32)
+    Bm = rng.integers(-4, 5, (K, N)).astype(np.float32)
+    want = np.array(G.matmul(A.astype(int).tolist(), Bm.astype(int).tolist()), dtype=np.float32)
+    for p in all_params(d_matmul(M, N, K)):
+        got = run(d_matmul(M, N, K), [dev(A), dev(Bm)], torch.full((M, N), float("nan"), device="cuda"), p)
+        assert np.array_equal(got.cpu().numpy(), want)
+    # Histo and GenHisto(max)
+    elems = rng.integers(0, 6, 50).astype(np.int32)
+    bins = np.array([4, 0, 9, 5, 1], np.int32)
+    want = G.histo(elems.tolist(), bins.tolist())
+    for p in all_params(d_histo(5, 50)):
+        got = run(d_histo(5, 50), [dev(elems), dev(bins)], torch.full((5,), -7, dtype=torch.int32, device="cuda"), p)
+        assert got.cpu().tolist() == want
+    gh = mdh.custom_desc((5, 50), (0, 1), ["int", "int"], [(0, "i1"), (1, "i0")], "int", 4,
+                         "r = a0 <= a1 ? a0 : -1;", "r = x > y ? x : y;")
+    want = G.gen_histo(elems.tolist(), bins.tolist(), lambda e, b: e if e <= b else -1, max)
+    got = run(gh, [dev(elems), dev(bins)], torch.full((5,), -7, dtype=torch.int32, device="cuda"))
+    assert got.cpu().tolist() == want
+    # PRL through user-defined struct types and operator
+    nA, nB = 6, 11
+    A8 = rng.integers(0, 3, (nA, 8)).astype(np.int32)
+    B8 = rng.integers(0, 3, (nB, 8)).astype(np.int32)
+    wp = rng.integers(1, 9, 8).astype(np.int32)
+    wm = rng.integers(-9, 1, 8).astype(np.int32)
+    sc, ix = G.custom_reduce(A8.tolist(), B8.tolist(), wp.tolist(), wm.tolist())
+    for p in all_params(d_prl(nA, nB)):
+        got = run(d_prl(nA, nB), [dev(A8), dev(B8), dev(wp), dev(wm)], torch.full((nA, 2), -1, dtype=torch.int32, device="cuda"), p)
+        assert got[:, 0].cpu().tolist() == sc and got[:, 1].cpu().tolist() == ix
+    # Jacobi1D: three accesses to one buffer; map; reduce(min)
+    x = rng.integers(0, 10, 12).astype(np.float32)
+    want = G.jacobi1d(x.astype(int).tolist(), 2)
+    got = run(d_jacobi1d(10, 2.0), [dev(x)], torch.full((10,), float("nan"), device="cuda"))
+    assert got.cpu().tolist() == want
+    v = rng.integers(-50, 50, 37).astype(np.int32)
+    dm = mdh.custom_desc((37,), (1,), ["int"], [(0, "i0")], "int", 4, "r = a0;", "r = x < y ? x : y;")
+    for p in all_params(dm):
+        got = run(dm, [dev(v)], torch.full((1,), 99, dtype=torch.int32, device="cuda"), p)
+        assert got.item() == G.reduce_op(min, v.tolist())
+
+
+@pytest.mark.gpu
+def test_transposed_output_view():
+    # out_index as a view: C written transposed, (i,j,0) -> C[j,i]
+    rng = np.random.default_rng(4)
+    M, N, K = 33, 18, 70
+    A = rng.integers(-3, 4, (M, K)).astype(np.float32)
+    Bm = rng.integers(-3, 4, (K, N)).astype(np.float32)
+    d = mdh.custom_desc((M, N, K), (0, 0, 1), ["float", "float"], [(0, "i0*N2+i2"), (1, "i2*N1+i1")], "float", 4,
+                        "r = a0 * a1;", "r = x + y;", out_index="i1*N0+i0")
+    for p in all_params(d)[:6]:
+        got = run(d, [dev(A), dev(Bm)], torch.full((N, M), float("nan"), device="cuda"), p)
+        assert np.array_equal(got.cpu().numpy(), (A.astype(np.float64) @ Bm.astype(np.float64)).T.astype(np.float32))
+
+
+@pytest.mark.gpu
+def test_larger_against_c_oracle_every_candidate():
+    # Dot and MatVec: tolerance as for the fixed instances (scaled error)
+    K = 300007
+    x = W.uniform(W.SEED_BASE + 80, 1, (K,), -1, 1)
+    y = W.uniform(W.SEED_BASE + 80, 2, (K,), -1, 1)
+    ref, scale = oracle.dot(x, y)
+    for p in all_params(d_dot(K)):
+        got = run(d_dot(K), [dev(x), dev(y)], torch.full((1,), float("nan"), device="cuda"), p)
+        assert abs(got.item() - ref) / scale <= 1e-4
+    M, Kk = 301, 2050
+    A = W.uniform(W.SEED_BASE + 81, 1, (M, Kk), -1, 1)
+    xv = W.uniform(W.SEED_BASE + 81, 2, (Kk,), -1, 1)
+    ref = oracle.matvec(A, xv)
+    scale = np.abs(A.astype(np.float64)) @ np.abs(xv.astype(np.float64))
+    for p in all_params(d_matvec(M, Kk)):
+        got = run(d_matvec(M, Kk), [dev(A), dev(xv)], torch.full((M,), float("nan"), device="cuda"), p)
+        assert float(np.max(np.abs(got.cpu().numpy() - ref) / scale)) <= 1e-4
+    # PRL: bit-exact against the C oracle
+    cfg = W.PrlCfg(700, 5000, 8, W.SEED_BASE + 82)
+    A8, B8, wp, wm = W.prl_inputs(cfg)
+    sc, ix = oracle.custom_reduce(A8, B8, wp, wm)
+    for p in all_params(d_prl(cfg.nA, cfg.nB)):
+        got = run(d_prl(cfg.nA, cfg.nB), [dev(A8), dev(B8), dev(wp), dev(wm)],
+                  torch.full((cfg.nA, 2), -1, dtype=torch.int32, device="cuda"), p).cpu().numpy()
+        assert np.array_equal(got[:, 0], sc) and np.array_equal(got[:, 1], ix)
+    # Histo against the library routine it reduces to
+    elems = W.integers(W.SEED_BASE + 83, 1, (200000,), 0, 255).astype(np.int32)
+    bins = np.arange(256, dtype=np.int32)
+    want = np.bincount(elems, minlength=256)
+    for p in all_params(d_histo(256, 200000)):
+        got = run(d_histo(256, 200000), [dev(elems), dev(bins)], torch.full((256,), -1, dtype=torch.int32, device="cuda"), p)
+        assert np.array_equal(got.cpu().numpy(), want)
+
+
+@pytest.mark.gpu
+def test_handle_is_reusable_and_checks_workspace():
+    d = d_matvec(64, 100000)
+    op = mdh.mdh_custom_create(d)
+    n = mdh.mdh_custom_workspace_size(op)
+    assert n > 0  # few rows: the reduced dimension is split over workgroups
+    A = W.uniform(W.SEED_BASE + 84, 1, (64, 100000), -1, 1)
+    xv = W.uniform(W.SEED_BASE + 84, 2, (100000,), -1, 1)
+    out = torch.empty(64, device="cuda")
+    with pytest.raises(mdh.MdhError) as e:
+        mdh.mdh_custom_run(op, [dev(A), dev(xv)], out, None)
+    assert e.value.status == 5
+    ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+    first = mdh.mdh_custom_run(op, [dev(A), dev(xv)], out, ws).clone()
+    second = mdh.mdh_custom_run(op, [dev(A), dev(xv)], out, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(first, second)  # deterministic: fixed combine order on every level
+    ref = oracle.matvec(A, xv)
+    scale = np.abs(A.astype(np.float64)) @ np.abs(xv.astype(np.float64))
+    assert float(np.max(np.abs(first.cpu().numpy() - ref) / scale)) <= 1e-4
