@@ -80,6 +80,18 @@ def dot(x, y):
     return out.value, outabs.value
 
 
+def scan_rows(X, with_abs: bool = False):
+    """Row-wise inclusive prefix sums in fp64 of an fp32 matrix (rows x n)."""
+    X = _f32(X)
+    if X.ndim == 1:
+        X = X[None, :]
+    R, n = X.shape
+    out = np.empty((R, n), dtype=np.float64)
+    outabs = np.empty((R, n), dtype=np.float64) if with_abs else None
+    _load().oracle_scan_rows(_i64(R), _i64(n), _p(X), _p(out), _p(outabs) if with_abs else None)
+    return (out, outabs) if with_abs else out
+
+
 def matvec(A, x, with_abs: bool = False):
     A, x = _f32(A), _f32(x).ravel()
     M, K = A.shape

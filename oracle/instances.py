@@ -191,3 +191,35 @@ def reduce_op(oplus, x):
     h = H.md_hom(lambda t: t[0], (H.pointwise(0, oplus),))
     (o,) = H.out_view([[lambda i: ()]])(h(iv([x], [range(len(x))])))
     return o[()]
+
+
+def scan(oplus, x):
+    """scan(oplus) = md_hom(id, (prefix-sum(oplus))) over (i) (Section "Examples", Subfigure 8;
+    Appendix, Example "Prefix-Sum"); output view (i)->(i)."""
+    iv = H.inp_view([[lambda i: (i,)]])
+    h = H.md_hom(lambda t: t[0], (H.prefix_sum(0, oplus),))
+    (o,) = H.out_view([[lambda i: (i,)]])(h(iv([x], [range(len(x))])))
+    return [o[(i,)] for i in range(len(x))]
+
+
+def scan_rows(oplus, X):
+    """Row-wise scan: md_hom(id, (++, prefix-sum(oplus))) over (i, j)."""
+    R, n = len(X), len(X[0])
+    iv = H.inp_view([[lambda i, j: (i, j)]])
+    h = H.md_hom(lambda t: t[0], (H.concat(0), H.prefix_sum(1, oplus)))
+    (o,) = H.out_view([[lambda i, j: (i, j)]])(h(iv([X], [range(R), range(n)])))
+    return [[o[(i, j)] for j in range(n)] for i in range(R)]
+
+
+def bottom_box_sums(X):
+    """The md_hom of MBBS: md_hom(id, (prefix-sum(+), +)) over (i, j) with the input view reading
+    the rows bottom-up, (i,j)->X[R-1-i, j]: element i is the sum of the bottom i+1 rows (all
+    columns).  Two different operators on the two dimensions (Section "Experimental Results": the
+    remark on several reduction dimensions with different combine operators).  The maximum over i
+    that gives the Maximum Bottom Box Sum itself is a reduce(max) on this result.
+    Reading of the missing figure -- parity unpinned against the paper."""
+    R, C = len(X), len(X[0])
+    iv = H.inp_view([[lambda i, j: (R - 1 - i, j)]])
+    h = H.md_hom(lambda t: t[0], (H.prefix_sum(0, _add), H.pointwise(1, _add)))
+    (o,) = H.out_view([[lambda i, j: (i,)]])(h(iv([X], [range(R), range(C)])))
+    return [o[(i,)] for i in range(R)]

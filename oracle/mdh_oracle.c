@@ -236,3 +236,20 @@ int oracle_num_threads(void) {
   return 1;
 #endif
 }
+
+/* ---- scan(+), row-wise: md_hom(id, (++, prefix-sum(+))) over (i,j); out[i,j] = x[i,0] + ... + x[i,j]
+ * (Section "Examples", Subfigure 8; Appendix, Example "Prefix-Sum": folding the singletons of j in
+ * ascending order with that operator gives the inclusive scan).  outabs (nullable) receives the same
+ * scan of |x|, the denominator of the scaled error the tests use. */
+void oracle_scan_rows(int64_t R, int64_t n, const float* x, double* out, double* outabs) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < R; ++i) {
+    double acc = 0.0, aabs = 0.0;
+    for (int64_t j = 0; j < n; ++j) {
+      acc += (double)x[i * n + j];
+      aabs += fabs((double)x[i * n + j]);
+      out[i * n + j] = acc;
+      if (outabs) outabs[i * n + j] = aabs;
+    }
+  }
+}

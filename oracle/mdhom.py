@@ -136,6 +136,46 @@ def pointwise(d: int, oplus: Callable) -> Callable[[MDA, MDA], MDA]:
     return op
 
 
+def prefix_sum(d: int, oplus: Callable) -> Callable[[MDA, MDA], MDA]:
+    """The prefix-sum combine operator in dimension d (Appendix, Example "Prefix-Sum"): index set
+    function id; with P, Q the disjoint index sets of the operands in d,
+
+        result[.., i, ..] = a1[.., i, ..]          (+) a2[.., max_{<=i}(Q), ..]   for i in P
+        result[.., i, ..] = a1[.., max_{<=i}(P), ..] (+) a2[.., i, ..]            for i in Q
+
+    where max_{<=i}(S) is the largest index of S not above i.  Reading of the case the paper leaves
+    open: if S has no index <= i the term is absent and the other operand's value is taken alone
+    (so that folding singletons in ascending order gives the inclusive scan)."""
+
+    def below(S, i):
+        c = [s for s in S if s <= i]
+        return max(c) if c else None
+
+    def op(a1: MDA, a2: MDA) -> MDA:
+        _check_other_dims(a1, a2, d)
+        P, Q = tuple(a1.index_sets[d]), tuple(a2.index_sets[d])
+        if set(P) & set(Q):
+            raise ValueError("prefix-sum needs disjoint index sets")
+        sets = list(a1.index_sets)
+        sets[d] = tuple(sorted(set(P) | set(Q)))
+        data = {}
+        for idx in itertools.product(*sets):
+            i = idx[d]
+            if i in P:
+                j = below(Q, i)
+                left = a1.data[idx]
+                data[idx] = left if j is None else oplus(left, a2.data[idx[:d] + (j,) + idx[d + 1:]])
+            else:
+                j = below(P, i)
+                right = a2.data[idx]
+                data[idx] = right if j is None else oplus(a1.data[idx[:d] + (j,) + idx[d + 1:]], right)
+        return MDA(sets, data)
+
+    op.index_set_function = lambda I: tuple(sorted(I))  # id
+    op.is_concat = False
+    return op
+
+
 def md_hom(f: Callable, ops: Sequence[Callable], use_mda_indices: bool = False):
     """md_hom(f, (op_1..op_D)): returns the function a -> op_1_{i_1 in I_1} ...
     op_D_{i_D in I_D} f_vec(a restricted to the single point (i_1..i_D)).

@@ -1,6 +1,6 @@
 """Checks that the oracle's pins have teeth: plant one plausible mistake at a time
 in a copy of the C oracle (on the CPU), and require that at least one pin test of
-tests/test_oracle_instances.py fails for every planted mistake.  CPU only."""
+tests/test_oracle_instances.py / tests/test_oracle_scan.py fails for every planted mistake.  CPU only."""
 import ctypes
 import os
 import subprocess
@@ -9,6 +9,7 @@ import pytest
 
 import oracle
 import test_oracle_instances as pins
+import test_oracle_scan as scan_pins
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "mdh_oracle.c")
 
@@ -36,10 +37,14 @@ MUTANTS = [
     ("prl_weights_swapped", "(ra[f] == rb[f]) ? wp[f] : wm[f]", "(ra[f] == rb[f]) ? wm[f] : wp[f]"),
     ("prl_skips_last_b", "for (int64_t b = 1; b < nB; ++b)\n      maxidx(&bs, &bi, wght(nF, A + a * nF, B + b * nF", "for (int64_t b = 1; b < nB - 1; ++b)\n      maxidx(&bs, &bi, wght(nF, A + a * nF, B + b * nF"),
     ("prl_min_instead_of_max", "if (s2 > *s1) {", "if (s2 < *s1) {"),
+    ("scan_exclusive", "out[i * n + j] = acc;", "out[i * n + j] = acc - (double)x[i * n + j];"),
+    ("scan_abs_forgotten", "aabs += fabs((double)x[i * n + j]);", "aabs += (double)x[i * n + j];"),
+    ("scan_row_stride", "acc += (double)x[i * n + j];", "acc += (double)x[i * (n - 1) + j];"),
     ("prl_field_dropped", "for (int32_t f = 0; f < nF; ++f) s +=", "for (int32_t f = 0; f < nF - 1; ++f) s +="),
 ]
 
 PIN_TESTS = [getattr(pins, n) for n in dir(pins) if n.startswith("test_")]
+PIN_TESTS += [getattr(scan_pins, n) for n in dir(scan_pins) if n.startswith("test_")]
 
 
 def _any_pin_fails():
