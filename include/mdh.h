@@ -60,7 +60,8 @@ typedef enum mdh_instance {
   MDH_CUSTOM_REDUCE = 3, /* md_hom(wght, (++, max_idx)),       dims (a, b)                 */
   MDH_DOT = 4,           /* md_hom(*, (+)),                    dims (k)                    */
   MDH_MATVEC = 5,        /* md_hom(*, (++, +)),                dims (i, k)                 */
-  MDH_BMATMUL = 6        /* md_hom(*, (++, ++, ++, +)),        dims (b, i, j, k)           */
+  MDH_BMATMUL = 6,       /* md_hom(*, (++, ++, ++, +)),        dims (b, i, j, k)           */
+  MDH_SCAN = 7           /* md_hom(id, (++, prefix-sum(+))),   dims (i, j)                 */
 } mdh_instance;
 
 /*
@@ -241,6 +242,22 @@ mdh_status mdh_custom_reduce(int64_t nA, int64_t nB, int32_t nF, const int32_t* 
                              int32_t* out_score, int32_t* out_index,
                              const mdh_tile_params* params, void* workspace,
                              size_t workspace_bytes, void* stream);
+
+/*
+ * Row-wise scan: out[i,j] = in[i,0] + ... + in[i,j]  =  md_hom(id, (++, prefix-sum(+)))
+ * over (i,j) (paper: Section "Examples", Subfigure 8; combine operator: Appendix,
+ * Example "Prefix-Sum").  The prefix-sum operator keeps the dimension and a part
+ * needs ONE value of the parts before it (their last prefix); that value is
+ * passed lane -> wavefront (registers) -> workgroup (LDS) -> sequential tiles
+ * (a carry) -> and, if prt[MDH_L_WG][j] = C > 1, across workgroups: chunk
+ * totals in `workspace` (R*C doubles, 8-byte aligned), scanned by a second
+ * kernel, then applied by a third (the input is read twice in that case).
+ *   in, out: R x n fp32, row-major, device; may not overlap.  R == 0 or n == 0 is
+ *   an empty call.  `sizes` for the host helpers: (R, n).
+ */
+mdh_status mdh_scan(int64_t R, int64_t n, const float* in, float* out,
+                    const mdh_tile_params* params, void* workspace, size_t workspace_bytes,
+                    void* stream);
 
 /*
  * Dot product: out = sum_k x[k] * y[k]  =  md_hom(*, (+)) over (k) with output

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     MDH_BMATMUL,
     MDH_DOT,
     MDH_MATVEC,
+    MDH_SCAN,
     MDH_MATMUL,
     MDH_MCC,
     MDH_STENCIL,
@@ -43,6 +44,7 @@ from .binding import (  # noqa: F401
     mdh_mcc,
     mdh_num_candidates,
     mdh_part_offset,
+    mdh_scan,
     mdh_stencil,
     mdh_strerror,
     mdh_tune,

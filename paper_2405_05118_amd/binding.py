@@ -13,7 +13,7 @@ from typing import Optional, Sequence
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libmdh.so")
 
-MDH_MATMUL, MDH_STENCIL, MDH_MCC, MDH_CUSTOM_REDUCE, MDH_DOT, MDH_MATVEC, MDH_BMATMUL = 0, 1, 2, 3, 4, 5, 6
+MDH_MATMUL, MDH_STENCIL, MDH_MCC, MDH_CUSTOM_REDUCE, MDH_DOT, MDH_MATVEC, MDH_BMATMUL, MDH_SCAN = 0, 1, 2, 3, 4, 5, 6, 7
 MDH_NUM_LAYERS, MDH_MAX_D = 6, 7
 L_HBM, L_LDS, L_VGPR, L_WG, L_WAVE, L_LANE = range(6)
 
@@ -21,7 +21,7 @@ EXPORTS = (
     "mdh_strerror", "mdh_version", "mdh_part_offset", "mdh_default_params", "mdh_validate_params",
     "mdh_workspace_size", "mdh_matmul", "mdh_stencil", "mdh_mcc", "mdh_custom_reduce", "mdh_tune",
     "mdh_num_candidates", "mdh_candidate", "mdh_last_launch_error", "mdh_dot", "mdh_matvec",
-    "mdh_matmul_ex", "mdh_calib_copy", "mdh_calib_read", "mdh_calib_mfma", "mdh_calib_valu",
+    "mdh_matmul_ex", "mdh_scan", "mdh_calib_copy", "mdh_calib_read", "mdh_calib_mfma", "mdh_calib_valu",
     "mdh_custom_default_params", "mdh_custom_validate_params", "mdh_custom_num_candidates", "mdh_custom_candidate",
     "mdh_custom_create", "mdh_custom_source", "mdh_custom_workspace_size", "mdh_custom_run", "mdh_custom_destroy",
 )
@@ -107,6 +107,7 @@ def lib() -> ctypes.CDLL:
         L.mdh_custom_reduce.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, pp, vp, sz, vp]
         L.mdh_matmul_ex.argtypes = [i64, i64, i64, i64, vp, i32, vp, i32, vp, i32, pp, vp, sz, vp]
         L.mdh_dot.argtypes = [i64, vp, vp, vp, pp, vp, sz, vp]
+        L.mdh_scan.argtypes = [i64, i64, vp, vp, pp, vp, sz, vp]
         L.mdh_matvec.argtypes = [i64, i64, vp, vp, vp, pp, vp, sz, vp]
         L.mdh_tune.argtypes = [ctypes.c_int, p64, ctypes.POINTER(vp), ctypes.POINTER(f32), vp, sz, vp, i32, pp,
                                ctypes.POINTER(f32)]
@@ -300,6 +301,19 @@ def mdh_dot(x, y, out, params: Optional[TileParams] = None, workspace=None):
     st = lib().mdh_dot(K, _dev(x, torch.float32, "x"), _dev(y, torch.float32, "y"), _dev(out, torch.float32, "out"),
                        _pref(params), wp, wb, ctypes.c_void_p(_stream()))
     _check(st, "mdh_dot")
+    return out
+
+
+def mdh_scan(x, out, params: Optional[TileParams] = None, workspace=None):
+    """Row-wise inclusive prefix sums of the (R, n) matrix x (a vector counts as one row)."""
+    import torch
+
+    R, n = (1, x.numel()) if x.dim() == 1 else x.shape
+    assert out.numel() == x.numel()
+    wp, wb = _ws(workspace)
+    st = lib().mdh_scan(R, n, _dev(x, torch.float32, "x"), _dev(out, torch.float32, "out"), _pref(params), wp, wb,
+                        ctypes.c_void_p(_stream()))
+    _check(st, "mdh_scan")
     return out
 
 

@@ -14,6 +14,7 @@ SOURCES = [
     "mdh_plan.cpp",
     "mdh_plan_reduce.cpp",
     "mdh_plan_ex.cpp",
+    "mdh_plan_scan.cpp",
     "mdh_custom.cpp",
     "mdh_api.hip",
     "mdh_stencil.hip",
@@ -21,6 +22,7 @@ SOURCES = [
     "mdh_mcc.hip",
     "mdh_mcc_flat.hip",
     "mdh_calib.hip",
+    "mdh_scan.hip",
     "mdh_matmul_skinny.hip",
     "mdh_custom_reduce.hip",
     "mdh_reduce.hip",

@@ -127,6 +127,21 @@ mdh_status mdh_matmul_ex(int64_t batch, int64_t M, int64_t N, int64_t K, const f
   return launch_matmul_ex(pl, batch, M, N, K, A, B, C, workspace, (hipStream_t)stream);
 }
 
+mdh_status mdh_scan(int64_t R, int64_t n, const float* in, float* out, const mdh_tile_params* params,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  if (R < 0 || n < 0 || too_big(R) || too_big(n) || too_big(R * n)) return MDH_ERR_SIZE;
+  const int64_t sizes[2] = {R, n};
+  ScanPlan pl;
+  mdh_status st = plan_scan(sizes, params, &pl);
+  if (st != MDH_OK) return st;
+  if (R == 0 || n == 0) return MDH_OK;
+  if (!in || !out) return MDH_ERR_NULL;
+  if (pl.C > 1 && (!workspace || workspace_bytes < (size_t)pl.C * (size_t)R * sizeof(double) ||
+                   ((uintptr_t)workspace & 7)))
+    return MDH_ERR_WORKSPACE;
+  return launch_scan(pl, R, n, in, out, workspace, (hipStream_t)stream);
+}
+
 mdh_status mdh_dot(int64_t K, const float* x, const float* y, float* out,
                    const mdh_tile_params* params, void* workspace, size_t workspace_bytes,
                    void* stream) {

@@ -68,6 +68,20 @@ struct MatVecPlan {
   int ragged;
 };
 
+// Row-wise scan: a workgroup owns one chunk of one row = TPC sequential tiles of WAVES*256
+// elements; C chunks per row (C > 1: chunk totals are scanned by a second kernel).
+struct ScanPlan {
+  int WAVES;
+  int TPC;
+  int C;
+  int ragged;
+};
+mdh_status plan_scan(const int64_t* sizes, const mdh_tile_params* p, ScanPlan* out);
+void params_from_plan(const int64_t* sizes, const ScanPlan& pl, mdh_tile_params* out);
+int scan_candidates(const int64_t* sizes, ScanPlan* out, int cap);
+mdh_status launch_scan(const ScanPlan& pl, int64_t R, int64_t n, const float* in, float* out, void* ws,
+                       hipStream_t st);
+
 // bMatMul / MatMul^T: the MatMul descriptor plus the transposition of the three views
 struct GemmExPlan {
   GemmPlan g;

@@ -584,7 +584,7 @@ mdh_status mdh_part_offset(int64_t N, int32_t L, const int32_t* P, const int32_t
 
 static mdh_status check_sizes(mdh_instance inst, const int64_t* s) {
   if (!s) return MDH_ERR_NULL;
-  const int D = inst == MDH_MCC ? 9 : (inst == MDH_CUSTOM_REDUCE || inst == MDH_MATVEC) ? 2
+  const int D = inst == MDH_MCC ? 9 : (inst == MDH_CUSTOM_REDUCE || inst == MDH_MATVEC || inst == MDH_SCAN) ? 2
                                   : inst == MDH_DOT ? 1 : inst == MDH_BMATMUL ? 7 : 3;
   for (int d = 0; d < D; ++d)
     if (s[d] < 0 || s[d] > 0x7fffffff) return MDH_ERR_SIZE;
@@ -602,6 +602,7 @@ static mdh_status check_sizes(mdh_instance inst, const int64_t* s) {
       if (s[2] < 1) return MDH_ERR_SIZE;
       break;
     case MDH_STENCIL:
+    case MDH_SCAN:
       break;
     case MDH_MCC:
       if (s[4] < 1 || s[5] < 1 || s[6] < 1 || s[7] < 1 || s[8] < 1) return MDH_ERR_SIZE;
@@ -655,6 +656,11 @@ mdh_status mdh_default_params(mdh_instance inst, const int64_t* sizes, mdh_tile_
       if ((st = plan_matvec(sizes, nullptr, &pl)) == MDH_OK) params_from_plan(sizes, pl, out);
       return st;
     }
+    case MDH_SCAN: {
+      ScanPlan pl;
+      if ((st = plan_scan(sizes, nullptr, &pl)) == MDH_OK) params_from_plan(sizes, pl, out);
+      return st;
+    }
   }
   return MDH_ERR_UNSUPPORTED;
 }
@@ -692,6 +698,10 @@ mdh_status mdh_validate_params(mdh_instance inst, const int64_t* sizes, const md
       MatVecPlan pl;
       return plan_matvec(sizes, p, &pl);
     }
+    case MDH_SCAN: {
+      ScanPlan pl;
+      return plan_scan(sizes, p, &pl);
+    }
   }
   return MDH_ERR_UNSUPPORTED;
 }
@@ -723,6 +733,11 @@ size_t mdh_workspace_size(mdh_instance inst, const int64_t* sizes, const mdh_til
       MatVecPlan pl;
       if (plan_matvec(sizes, params, &pl) != MDH_OK || pl.S <= 1) return 0;
       return (size_t)pl.S * (size_t)sizes[0] * sizeof(float);
+    }
+    case MDH_SCAN: {
+      ScanPlan pl;
+      if (plan_scan(sizes, params, &pl) != MDH_OK || pl.C <= 1) return 0;
+      return (size_t)pl.C * (size_t)sizes[0] * sizeof(double);
     }
     default:
       return 0;
@@ -760,6 +775,10 @@ int32_t mdh_num_candidates(mdh_instance inst, const int64_t* sizes) {
     case MDH_MATVEC: {
       MatVecPlan c[CAP];
       return matvec_candidates(sizes, c, CAP);
+    }
+    case MDH_SCAN: {
+      ScanPlan c[CAP];
+      return scan_candidates(sizes, c, CAP);
     }
   }
   return 0;
@@ -816,6 +835,13 @@ mdh_status mdh_candidate(mdh_instance inst, const int64_t* sizes, int32_t idx, m
     case MDH_MATVEC: {
       MatVecPlan c[CAP];
       int n = matvec_candidates(sizes, c, CAP);
+      if (idx < 0 || idx >= n) return MDH_ERR_SIZE;
+      params_from_plan(sizes, c[idx], out);
+      return MDH_OK;
+    }
+    case MDH_SCAN: {
+      ScanPlan c[CAP];
+      int n = scan_candidates(sizes, c, CAP);
       if (idx < 0 || idx >= n) return MDH_ERR_SIZE;
       params_from_plan(sizes, c[idx], out);
       return MDH_OK;

@@ -1,0 +1,95 @@
+// Planner for the row-wise scan: md_hom(id, (++, prefix-sum(+))) over (i, j)
+// (paper: Section "Examples", Subfigure 8; Appendix, Example "Prefix-Sum").
+// Table: a workgroup owns one row i and one chunk of j; the chunk is TPC sequential tiles
+// (HBM-layer parts) of WAVES wavefronts x 64 lanes x 4 consecutive elements; blocked assignment
+// (a part of j is a contiguous range, so that a part's result only needs ONE value of the parts
+// before it: their last prefix).
+#include <string.h>
+
+#include "mdh_internal.h"
+
+namespace mdh {
+using namespace detail;
+
+static const int kScanWaves[] = {4, 8, 16};
+
+void params_from_plan(const int64_t* s, const ScanPlan& pl, mdh_tile_params* p) {
+  clear_params(p, 2);
+  p->prt[MDH_L_WG][0] = (int32_t)(s[0] > 0 ? s[0] : 1);  // an empty call still has a valid table
+  p->prt[MDH_L_WG][1] = pl.C;
+  p->prt[MDH_L_HBM][1] = pl.TPC;
+  p->prt[MDH_L_WAVE][1] = pl.WAVES;
+  p->prt[MDH_L_LANE][1] = 64;
+  p->prt[MDH_L_VGPR][1] = 4;
+  static const int dims[2] = {0, 1};
+  set_order(p, dims);
+  p->strided = 0;
+  p->lane_fast_dim = 1;
+  p->in_region[0] = MDH_MR_VGPR;
+  p->out_region = MDH_MR_VGPR;
+  p->ragged = (uint8_t)pl.ragged;
+}
+
+static int scan_ragged(const int64_t* s, const ScanPlan& pl) {
+  return s[0] == 0 || s[1] != (int64_t)pl.C * pl.TPC * pl.WAVES * 256;
+}
+
+static ScanPlan scan_plan(const int64_t* s, int waves, int64_t chunks) {
+  ScanPlan pl{waves, 1, 1, 0};
+  const int64_t tile = (int64_t)waves * 256;
+  const int64_t tiles = cdiv(s[1] > 0 ? s[1] : 1, tile);
+  if (chunks < 1) chunks = 1;
+  if (chunks > tiles) chunks = tiles;
+  pl.TPC = (int)cdiv(tiles, chunks);
+  pl.C = (int)cdiv(tiles, pl.TPC);  // no empty chunk
+  pl.ragged = scan_ragged(s, pl);
+  return pl;
+}
+
+static ScanPlan scan_default(const int64_t* s) {
+  // enough rows: one workgroup per row walks the whole row (one pass over the data); few rows:
+  // chunks of j over workgroups until ~2048 workgroups, chunk totals scanned by a second kernel
+  const int64_t rows = s[0] > 0 ? s[0] : 1;
+  int64_t chunks = 1;
+  while (rows * chunks < 2048 && cdiv(s[1], 1024 * chunks * 2) >= 4) chunks *= 2;
+  return scan_plan(s, 4, chunks);
+}
+
+int scan_candidates(const int64_t* s, ScanPlan* out, int cap) {
+  int n = 0;
+  auto push = [&](const ScanPlan& pl) {
+    if (n >= cap) return;
+    for (int i = 0; i < n; ++i)
+      if (out[i].WAVES == pl.WAVES && out[i].C == pl.C && out[i].TPC == pl.TPC) return;
+    out[n++] = pl;
+  };
+  const ScanPlan d = scan_default(s);
+  push(d);
+  for (int w : kScanWaves)
+    for (int64_t c = d.C / 4 > 0 ? d.C / 4 : 1; c <= (int64_t)d.C * 8; c *= 2) push(scan_plan(s, w, c));
+  return n;
+}
+
+mdh_status plan_scan(const int64_t* s, const mdh_tile_params* p, ScanPlan* out) {
+  if (!p) {
+    *out = scan_default(s);
+    return MDH_OK;
+  }
+  if (p->D != 2) return MDH_ERR_UNSUPPORTED;
+  bool ragged;
+  mdh_status st = check_products(p, s, &ragged);
+  if (st != MDH_OK) return st;
+  if ((st = check_lanes(p)) != MDH_OK) return st;
+  ScanPlan pl{p->prt[MDH_L_WAVE][1], p->prt[MDH_L_HBM][1], p->prt[MDH_L_WG][1], ragged};
+  bool inst = false;
+  for (int w : kScanWaves) inst = inst || (w == pl.WAVES);
+  // a chunk that owns no index would leave its total unset
+  if ((int64_t)(pl.C - 1) * pl.TPC * pl.WAVES * 256 >= (s[1] > 0 ? s[1] : 1)) return MDH_ERR_TILE_NOT_DIVIDING;
+  mdh_tile_params chk;
+  params_from_plan(s, pl, &chk);
+  if (!same_table(chk, *p) || !inst) return MDH_ERR_UNSUPPORTED;
+  *out = pl;
+  return MDH_OK;
+}
+
+}  // namespace mdh

@@ -1,0 +1,101 @@
+"""Row-wise scan(+) = md_hom(id, (++, prefix-sum(+))): host planner and GPU parity against the
+oracle (fp64 inclusive prefix sums of the same fp32 inputs)."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2405_05118_amd as mdh
+from paper_2405_05118_amd import binding as B
+from paper_2405_05118_amd import workloads as W
+
+TOL = 1e-5  # |gpu - ref| / prefix sum of |x|; fp32 tree inside a tile, fp64 carries between tiles
+
+
+@pytest.mark.parametrize("sizes", [(1, 1 << 24), (4096, 4096), (3, 1000), (1, 1), (70000, 17), (0, 5), (5, 0)])
+def test_planner(sizes):
+    inst = mdh.MDH_SCAN
+    p = mdh.mdh_default_params(inst, sizes)
+    assert p.D == 2 and list(p.blk[:2]) == [1, 1] and p.strided == 0
+    for d in range(2):
+        e = p.extent(d)
+        assert e >= sizes[d] if p.ragged else e == sizes[d]
+    assert mdh.mdh_validate_params(inst, sizes, p) == 0
+    for i in range(mdh.mdh_num_candidates(inst, sizes)):
+        c = mdh.mdh_candidate(inst, sizes, i)
+        assert mdh.mdh_validate_params(inst, sizes, c) == 0
+    C = p.prt[B.L_WG][1]
+    assert mdh.mdh_workspace_size(inst, sizes, p) == (8 * C * sizes[0] if C > 1 else 0)
+    # a long single row is cut into chunks over workgroups, many rows are not
+    if sizes == (1, 1 << 24):
+        assert C > 1
+    if sizes == (4096, 4096):
+        assert C == 1
+
+
+def test_planner_rejects_empty_chunk():
+    sizes = (2, 5000)
+    p = mdh.mdh_default_params(mdh.MDH_SCAN, sizes)
+    q = p.copy()
+    q.prt[B.L_WG][1], q.prt[B.L_HBM][1], q.ragged = 8, 1, 1  # chunks 5..7 start beyond the row
+    assert mdh.mdh_validate_params(mdh.MDH_SCAN, sizes, q) == 3
+    q = p.copy()
+    q.prt[B.L_WAVE][1] = 5  # no such instantiation (and the product changes)
+    assert mdh.mdh_validate_params(mdh.MDH_SCAN, sizes, q) != 0
+
+
+torch = pytest.importorskip("torch")
+
+
+def run(x, p):
+    xs = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    out = torch.full_like(xs, float("nan"))
+    sizes = x.shape if x.ndim == 2 else (1, x.size)
+    n = mdh.mdh_workspace_size(mdh.MDH_SCAN, sizes, p)
+    ws = torch.empty(max(n, 8) // 8, dtype=torch.float64, device="cuda") if n else None
+    mdh.mdh_scan(xs, out, p, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64)
+
+
+def cands(sizes):
+    return [None] + [mdh.mdh_candidate(mdh.MDH_SCAN, sizes, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_SCAN, sizes))]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape", [(1, 1), (1, 5), (3, 1000), (7, 1024), (2, 1025), (5, 4099), (1, 300007), (33, 20000), (600, 257)])
+def test_every_candidate(shape):
+    x = W.uniform(W.SEED_BASE + 95, 1, shape, -1, 1)
+    ref, refabs = oracle.scan_rows(x, with_abs=True)
+    for p in cands(shape):
+        got = run(x, p)
+        assert np.all(np.isfinite(got)), "output not fully overwritten"
+        err = float(np.max(np.abs(got - ref) / refabs))
+        assert err <= TOL, (shape, p and p.table(), err)
+
+
+@pytest.mark.gpu
+def test_exact_on_small_integers_and_ones():
+    ones = np.ones((2, 70001), np.float32)
+    for p in cands(ones.shape):
+        got = run(ones, p)
+        assert np.array_equal(got[0], np.arange(1, 70002)) and np.array_equal(got[1], got[0])
+    rng = np.random.default_rng(9)
+    x = rng.integers(-3, 4, (4, 9000)).astype(np.float32)  # partial sums stay far below 2^24: exact
+    assert np.array_equal(run(x, None), np.cumsum(x.astype(np.float64), axis=1))
+
+
+@pytest.mark.gpu
+def test_long_row_and_explicit_chunks():
+    n = (1 << 24) + 12345
+    x = W.uniform(W.SEED_BASE + 96, 1, (1, n), 0, 1)  # non-negative: the prefix itself is the scale
+    ref = oracle.scan_rows(x)
+    got = run(x, None)
+    assert float(np.max(np.abs(got - ref) / np.maximum(ref, 1e-30))) <= TOL
+    # one workgroup walking the whole row (C = 1) must agree with the chunked evaluation
+    sizes = (1, n)
+    one = [p for p in cands(sizes)[1:] if p.prt[B.L_WG][1] == 1]
+    if one:
+        assert float(np.max(np.abs(run(x, one[0]) - ref) / np.maximum(ref, 1e-30))) <= TOL
+    with pytest.raises(mdh.MdhError) as e:  # chunked configuration without workspace
+        mdh.mdh_scan(torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda"))
+    assert e.value.status == 5
