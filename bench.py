@@ -316,6 +316,82 @@ def bench_matmul_ex(torch, mdh, W, name, steps, warmup, cpu):
     return res
 
 
+def bench_scan(torch, mdh, W, name, steps, warmup, cpu):
+    """Row-wise scan(+): one long row (chunks over workgroups, three kernels) or many rows (one pass)."""
+    R, n = (1, 1 << 28) if name == "scan_2p28" else (65536, 4096)
+    seed = W.SEED_BASE + 12
+    x = W.device_uniform(seed, 1, (R, n), -1.0, 1.0)
+    out = torch.empty_like(x)
+    ws = _ws(torch, mdh, mdh.MDH_SCAN, (R, n))
+    p = mdh.mdh_default_params(mdh.MDH_SCAN, (R, n))
+    ms, wall = _events_ms(torch, lambda: mdh.mdh_scan(x, out, None, ws), steps, warmup)
+    nbytes = 8 * R * n  # every element read once and written once
+    gbs = nbytes / ms / 1e6
+    chunks = int(p.prt[3][1])
+    res = {
+        "value": nbytes / wall / 1e6, "unit": "GB/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "f32",
+        "kernel": "scan_apply_kernel" + (" + scan_totals_kernel + scan_offsets_kernel" if chunks > 1 else ""),
+        "rows": R, "n": n, "chunks_per_row": chunks,
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES.get(name)},
+        "algorithmic_bytes": nbytes,
+        "kernel_bytes": nbytes + (4 * R * n if chunks > 1 else 0),  # chunked rows read the input twice
+    }
+    if cpu:
+        import oracle
+
+        rows = max(1, min(R, (1 << 26) // n))
+        cols = min(n, 1 << 26)
+        xh = x[:rows, :cols].contiguous().cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.scan_rows(xh)
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": 8 * rows * cols / dt / 1e9, "unit": "GB/s", "cores": min(rows, oracle.num_threads()),
+                               "kind": "oracle", "sample": "first %d row(s) x %d columns (%.2f s)" % (rows, cols, dt)}
+    return res
+
+
+def bench_histo_generic(torch, mdh, W, name, steps, warmup, cpu):
+    """Histo through the generic runtime-compiled path: md_hom(f_Histo, (++, +)) over (bins, elements)."""
+    nb, ne = 256, 1 << 24
+    seed = W.SEED_BASE + 13
+    elems = W.device_integers(seed, 1, (ne,), 0, nb - 1)
+    bins = torch.arange(nb, dtype=torch.int32, device="cuda")
+    out = torch.empty(nb, dtype=torch.int32, device="cuda")
+    desc = mdh.custom_desc((nb, ne), (0, 1), ["int", "int"], [(0, "i1"), (1, "i0")], "int", 4,
+                           "r = a0 == a1 ? 1 : 0;", "r = x + y;")
+    op = mdh.mdh_custom_create(desc)
+    n = mdh.mdh_custom_workspace_size(op)
+    ws = torch.empty(max(n, 4), dtype=torch.uint8, device="cuda") if n else None
+    ms, wall = _events_ms(torch, lambda: mdh.mdh_custom_run(op, [elems, bins], out, ws), steps, warmup)
+    pairs = float(nb) * ne
+    # per (bin, element) pair at least a compare and a conditional add: 2 lane-ops
+    tops = pairs * 2.0 / ms / 1e9
+    res = {
+        "value": pairs / wall / 1e6, "unit": "Gpairs/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "i32",
+        "kernel": "mdh_custom_main + mdh_custom_combine (hipRTC)", "bins": nb, "elements": ne,
+        "roofline": {"bound": "alu", "achieved": tops, "peak": PEAK_INT_VALU_TOPS, "unit": "Tlane-op/s",
+                     "frac": tops / PEAK_INT_VALU_TOPS, "traffic": None},
+        "lane_ops_per_pair": 2.0,
+        "algorithmic_bytes": 4 * (ne + 2 * nb),
+    }
+    if cpu:
+        import numpy as np
+
+        from oracle import instances as G
+
+        m = 4096
+        eh = elems[:m].cpu().numpy().tolist()
+        t0 = time.perf_counter()
+        G.histo(eh, list(range(16)))
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": 16 * m / dt / 1e9, "unit": "Gpairs/s", "cores": 1, "kind": "oracle",
+                               "sample": "generic evaluator, 16 bins x %d elements (%.2f s)" % (m, dt)}
+        del np
+    mdh.mdh_custom_destroy(op)
+    return res
+
+
 def calibration(torch, mdh):
     """Attainable rates of this chip on the resources that bound the instances, from the library's
     calibration kernels (HIP events on the launch stream, 20 launches each)."""
@@ -364,6 +440,9 @@ BENCHES = {
     "mcc_resnet50_first": bench_mcc,
     "matmul_resnet50_fc": bench_matmul_ex,
     "matmul_vgg16_fc": bench_matmul_ex,
+    "scan_2p28": bench_scan,
+    "scan_rows_65536x4096": bench_scan,
+    "histo_generic_256x2p24": bench_histo_generic,
 }
 
 

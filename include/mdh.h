@@ -11,8 +11,9 @@
  * The library evaluates fixed instances of the paper's example table
  * (Figure "Data-parallel computations expressed in our high-level
  * representation"): MatMul, Jacobi-3D, multi-channel convolution (MCC), a
- * record-linkage style custom reduction, Dot, MatVec and the batched /
- * transposed MatMul variants.  Each call takes the index-space sizes
+ * record-linkage style custom reduction, Dot, MatVec, the batched /
+ * transposed MatMul variants and the row-wise scan; mdh_custom_* evaluates a
+ * user-defined md_hom compiled at run time.  Each call takes the index-space sizes
  * N_1..N_D, the operand buffers the input/output views address, and one
  * configuration of the paper's tuning parameters (Table "Tuning parameters of
  * our low-level expressions"), restricted as in Section "Auto-Tuning".
