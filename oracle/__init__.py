@@ -159,6 +159,35 @@ def mcc_at(x, filt, idx, stride=(1, 1)):
     return out, outabs
 
 
+def mcc_capsule(x, filt, stride=(1, 1), with_abs: bool = False):
+    """x: (N,H,W,C,MI,MK), filt: (K,R,S,C,MK,MJ) -> (N,P,Q,K,MI,MJ)."""
+    x, filt = _f32(x), _f32(filt)
+    N, H, W, C, MI, MK = x.shape
+    K, R, S, C2, MK2, MJ = filt.shape
+    assert C == C2 and MK == MK2
+    sh, sw = stride
+    P, Q = (H - R) // sh + 1, (W - S) // sw + 1
+    out = np.empty((N, P, Q, K, MI, MJ), dtype=np.float64)
+    outabs = np.empty(out.shape, dtype=np.float64) if with_abs else None
+    _load().oracle_mcc_capsule(_i64(N), _i64(H), _i64(W), _i64(C), _i64(K), _i64(R), _i64(S), _i64(sh), _i64(sw),
+                               _i64(MI), _i64(MJ), _i64(MK), _p(x), _p(filt), _p(out), _p(outabs) if with_abs else None)
+    return (out, outabs) if with_abs else out
+
+
+def mcc_capsule_at(x, filt, idx, stride=(1, 1)):
+    """The same definition at chosen output positions idx = (n,p,q,k,mi,mj) rows."""
+    x, filt = _f32(x), _f32(filt)
+    N, H, W, C, MI, MK = x.shape
+    K, R, S, _, _, MJ = filt.shape
+    sh, sw = stride
+    idx = _i64a(idx).reshape(-1, 6)
+    out = np.empty(len(idx), dtype=np.float64)
+    outabs = np.empty(len(idx), dtype=np.float64)
+    _load().oracle_mcc_capsule_at(_i64(H), _i64(W), _i64(C), _i64(R), _i64(S), _i64(sh), _i64(sw), _i64(MI), _i64(MJ),
+                                  _i64(MK), _p(x), _p(filt), _i64(len(idx)), _p(idx), _p(out), _p(outabs))
+    return out, outabs
+
+
 def custom_reduce(A, B, w_agree, w_disagree):
     A, B, wp, wm = _i32a(A), _i32a(B), _i32a(w_agree), _i32a(w_disagree)
     nA, nF = A.shape

@@ -223,3 +223,26 @@ def bottom_box_sums(X):
     h = H.md_hom(lambda t: t[0], (H.prefix_sum(0, _add), H.pointwise(1, _add)))
     (o,) = H.out_view([[lambda i, j: (i,)]])(h(iv([X], [range(R), range(C)])))
     return [o[(i,)] for i in range(R)]
+
+
+def mcc_capsule(x, filt, stride=(1, 1)):
+    """MCC_Capsule as a 10-dimensional md_hom(*, (++ x6, + x4)) over (n,p,q,k,mi,mj,c,r,s,mk) with
+    views in[n,p*sh+r,q*sw+s,c,mi,mk] and filt[k,r,s,c,mk,mj] (Section "Examples", Subfigure 2;
+    reading of the missing figure: MCC on MI x MK / MK x MJ matrices)."""
+    N, Hh, W, C, MI, MK = len(x), len(x[0]), len(x[0][0]), len(x[0][0][0]), len(x[0][0][0][0]), len(x[0][0][0][0][0])
+    K, R, S, MJ = len(filt), len(filt[0]), len(filt[0][0]), len(filt[0][0][0][0][0])
+    sh, sw = stride
+    P, Q = (Hh - R) // sh + 1, (W - S) // sw + 1
+    iv = H.inp_view(
+        [
+            [lambda n, p, q, k, mi, mj, c, r, s, mk: (n, p * sh + r, q * sw + s, c, mi, mk)],
+            [lambda n, p, q, k, mi, mj, c, r, s, mk: (k, r, s, c, mk, mj)],
+        ]
+    )
+    ops = tuple(H.concat(d) for d in range(6)) + tuple(H.pointwise(d, _add) for d in range(6, 10))
+    h = H.md_hom(lambda t: t[0] * t[1], ops)
+    ov = H.out_view([[lambda n, p, q, k, mi, mj, c, r, s, mk: (n, p, q, k, mi, mj)]])
+    sets = [range(N), range(P), range(Q), range(K), range(MI), range(MJ), range(C), range(R), range(S), range(MK)]
+    (o,) = ov(h(iv([x, filt], sets)))
+    return [[[[[[o[(n, p, q, k, a, b)] for b in range(MJ)] for a in range(MI)] for k in range(K)] for q in range(Q)]
+             for p in range(P)] for n in range(N)]

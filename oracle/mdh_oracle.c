@@ -253,3 +253,60 @@ void oracle_scan_rows(int64_t R, int64_t n, const float* x, double* out, double*
     }
   }
 }
+
+/* ---- MCC_Capsule: the 10-dimensional generalisation of MCC that operates on MI x MK and MK x MJ
+ * matrices instead of scalars (Section "Examples", Subfigure 2; Appendix "Data Characteristics
+ * used in Deep Neural Networks": three more dimensions MI, MJ, MK).  Reading of the missing figure:
+ * md_hom(*, (++ n,p,q,k,mi,mj ; + c,r,s,mk)) with views
+ *   (..)->in[n, p*sh+r, q*sw+s, c, mi, mk],  (..)->filt[k, r, s, c, mk, mj],  out[n,p,q,k,mi,mj]:
+ * every scalar product of MCC becomes a matrix product.  One output position per call; idx =
+ * (n,p,q,k,mi,mj). */
+static void capsule_point(int64_t H, int64_t W, int64_t C, int64_t R, int64_t S, int64_t sh, int64_t sw,
+                          int64_t MI, int64_t MJ, int64_t MK, const float* in, const float* filt,
+                          int64_t n, int64_t p, int64_t q, int64_t k, int64_t mi, int64_t mj,
+                          double* acc_out, double* abs_out) {
+  double acc = 0.0, aabs = 0.0;
+  for (int64_t c = 0; c < C; ++c)
+    for (int64_t r = 0; r < R; ++r)
+      for (int64_t s = 0; s < S; ++s)
+        for (int64_t mk = 0; mk < MK; ++mk) {
+          double a = (double)in[((((n * H + (p * sh + r)) * W + (q * sw + s)) * C + c) * MI + mi) * MK + mk];
+          double b = (double)filt[((((k * R + r) * S + s) * C + c) * MK + mk) * MJ + mj];
+          acc += a * b;
+          aabs += fabs(a * b);
+        }
+  *acc_out = acc;
+  *abs_out = aabs;
+}
+
+void oracle_mcc_capsule(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                        int64_t sh, int64_t sw, int64_t MI, int64_t MJ, int64_t MK, const float* in,
+                        const float* filt, double* out, double* outabs) {
+  const int64_t P = (H - R) / sh + 1, Q = (W - S) / sw + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t p = 0; p < P; ++p)
+      for (int64_t q = 0; q < Q; ++q)
+        for (int64_t k = 0; k < K; ++k)
+          for (int64_t mi = 0; mi < MI; ++mi)
+            for (int64_t mj = 0; mj < MJ; ++mj) {
+              double acc, aabs;
+              capsule_point(H, W, C, R, S, sh, sw, MI, MJ, MK, in, filt, n, p, q, k, mi, mj, &acc, &aabs);
+              int64_t o = ((((n * P + p) * Q + q) * K + k) * MI + mi) * MJ + mj;
+              out[o] = acc;
+              if (outabs) outabs[o] = aabs;
+            }
+}
+
+void oracle_mcc_capsule_at(int64_t H, int64_t W, int64_t C, int64_t R, int64_t S, int64_t sh, int64_t sw,
+                           int64_t MI, int64_t MJ, int64_t MK, const float* in, const float* filt,
+                           int64_t nS, const int64_t* idx, double* out, double* outabs) {
+#pragma omp parallel for schedule(static)
+  for (int64_t t = 0; t < nS; ++t) {
+    double acc, aabs;
+    capsule_point(H, W, C, R, S, sh, sw, MI, MJ, MK, in, filt, idx[6 * t], idx[6 * t + 1], idx[6 * t + 2],
+                  idx[6 * t + 3], idx[6 * t + 4], idx[6 * t + 5], &acc, &aabs);
+    out[t] = acc;
+    outabs[t] = aabs;
+  }
+}

@@ -1,6 +1,6 @@
 """Checks that the oracle's pins have teeth: plant one plausible mistake at a time
 in a copy of the C oracle (on the CPU), and require that at least one pin test of
-tests/test_oracle_instances.py / tests/test_oracle_scan.py fails for every planted mistake.  CPU only."""
+tests/test_oracle_instances.py / test_oracle_scan.py / test_oracle_capsule.py fails for every planted mistake.  CPU only."""
 import ctypes
 import os
 import subprocess
@@ -9,6 +9,7 @@ import pytest
 
 import oracle
 import test_oracle_instances as pins
+import test_oracle_capsule as capsule_pins
 import test_oracle_scan as scan_pins
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "mdh_oracle.c")
@@ -40,11 +41,16 @@ MUTANTS = [
     ("scan_exclusive", "out[i * n + j] = acc;", "out[i * n + j] = acc - (double)x[i * n + j];"),
     ("scan_abs_forgotten", "aabs += fabs((double)x[i * n + j]);", "aabs += (double)x[i * n + j];"),
     ("scan_row_stride", "acc += (double)x[i * n + j];", "acc += (double)x[i * (n - 1) + j];"),
+    ("capsule_filter_matrix_transposed", "* MK + mk) * MJ + mj];", "* MK + mj % MK) * MJ + mk % MJ];"),
+    ("capsule_drops_first_mk", "for (int64_t mk = 0; mk < MK; ++mk) {", "for (int64_t mk = 1; mk < MK; ++mk) {"),
+    ("capsule_input_matrix_transposed", "* MI + mi) * MK + mk];", "* MI + mk % MI) * MK + mi % MK];"),
+    ("capsule_stride_on_tap", "(n * H + (p * sh + r)) * W + (q * sw + s)) * C + c) * MI", "(n * H + (p + r * sh)) * W + (q * sw + s)) * C + c) * MI"),
     ("prl_field_dropped", "for (int32_t f = 0; f < nF; ++f) s +=", "for (int32_t f = 0; f < nF - 1; ++f) s +="),
 ]
 
 PIN_TESTS = [getattr(pins, n) for n in dir(pins) if n.startswith("test_")]
 PIN_TESTS += [getattr(scan_pins, n) for n in dir(scan_pins) if n.startswith("test_")]
+PIN_TESTS += [getattr(capsule_pins, n) for n in dir(capsule_pins) if n.startswith("test_")]
 
 
 def _any_pin_fails():
