@@ -62,7 +62,8 @@ typedef enum mdh_instance {
   MDH_DOT = 4,           /* md_hom(*, (+)),                    dims (k)                    */
   MDH_MATVEC = 5,        /* md_hom(*, (++, +)),                dims (i, k)                 */
   MDH_BMATMUL = 6,       /* md_hom(*, (++, ++, ++, +)),        dims (b, i, j, k)           */
-  MDH_SCAN = 7           /* md_hom(id, (++, prefix-sum(+))),   dims (i, j)                 */
+  MDH_SCAN = 7,          /* md_hom(id, (++, prefix-sum(+))),   dims (i, j)                 */
+  MDH_MCC_CAPSULE = 8    /* md_hom(*, (++ x6, + x4)),  dims (n,p,q,k,mi,mj, c,r,s,mk)      */
 } mdh_instance;
 
 /*
@@ -79,7 +80,7 @@ enum {
   MDH_L_WAVE = 4, /* core layer: wavefronts (64 lanes) of a workgroup            */
   MDH_L_LANE = 5, /* core layer: lanes of a wavefront                            */
   MDH_NUM_LAYERS = 6,
-  MDH_MAX_D = 7
+  MDH_MAX_D = 10
 };
 
 /* Memory regions (parameters D3/S3/S5/R3). */
@@ -243,6 +244,25 @@ mdh_status mdh_custom_reduce(int64_t nA, int64_t nB, int32_t nF, const int32_t* 
                              int32_t* out_score, int32_t* out_index,
                              const mdh_tile_params* params, void* workspace,
                              size_t workspace_bytes, void* stream);
+
+/*
+ * MCC_Capsule: MCC on 4 x 4 matrices instead of scalars,
+ *   out[n,p,q,k,mi,mj] = sum_{c,r,s,mk} in[n, p*stride_h+r, q*stride_w+s, c, mi, mk]
+ *                                        * filt[k, r, s, c, mk, mj]
+ * = md_hom(*, (++,++,++,++,++,++, +,+,+,+)) over (n,p,q,k,mi,mj,c,r,s,mk) (paper:
+ * Section "Examples", Subfigure 2; Appendix "Data Characteristics used in Deep
+ * Neural Networks": MCC with three more dimensions MI = MJ = MK = 4).
+ *   in:   N x H x W x C x 4 x 4        filt: K x R x S x C x 4 x 4
+ *   out:  N x P x Q x K x 4 x 4,  P, Q as for mdh_mcc; all fp32, dense, device.
+ * The whole filter slice of a workgroup is staged in LDS: shapes whose slice
+ * (8 channels x R x S x C x 16 floats) plus input patch exceed 160 KB are refused
+ * with MDH_ERR_TILE_RESOURCES (few input channels, as in the paper's study).
+ * `sizes` for the host helpers: (N, P, Q, K, C, R, S, stride_h, stride_w).
+ */
+mdh_status mdh_mcc_capsule(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R,
+                           int64_t S, int64_t stride_h, int64_t stride_w, const float* in,
+                           const float* filt, float* out, const mdh_tile_params* params,
+                           void* stream);
 
 /*
  * Row-wise scan: out[i,j] = in[i,0] + ... + in[i,j]  =  md_hom(id, (++, prefix-sum(+)))

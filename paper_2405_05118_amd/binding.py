@@ -13,15 +13,15 @@ from typing import Optional, Sequence
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libmdh.so")
 
-MDH_MATMUL, MDH_STENCIL, MDH_MCC, MDH_CUSTOM_REDUCE, MDH_DOT, MDH_MATVEC, MDH_BMATMUL, MDH_SCAN = 0, 1, 2, 3, 4, 5, 6, 7
-MDH_NUM_LAYERS, MDH_MAX_D = 6, 7
+MDH_MATMUL, MDH_STENCIL, MDH_MCC, MDH_CUSTOM_REDUCE, MDH_DOT, MDH_MATVEC, MDH_BMATMUL, MDH_SCAN, MDH_MCC_CAPSULE = 0, 1, 2, 3, 4, 5, 6, 7, 8
+MDH_NUM_LAYERS, MDH_MAX_D = 6, 10
 L_HBM, L_LDS, L_VGPR, L_WG, L_WAVE, L_LANE = range(6)
 
 EXPORTS = (
     "mdh_strerror", "mdh_version", "mdh_part_offset", "mdh_default_params", "mdh_validate_params",
     "mdh_workspace_size", "mdh_matmul", "mdh_stencil", "mdh_mcc", "mdh_custom_reduce", "mdh_tune",
     "mdh_num_candidates", "mdh_candidate", "mdh_last_launch_error", "mdh_dot", "mdh_matvec",
-    "mdh_matmul_ex", "mdh_scan", "mdh_calib_copy", "mdh_calib_read", "mdh_calib_mfma", "mdh_calib_valu",
+    "mdh_matmul_ex", "mdh_scan", "mdh_mcc_capsule", "mdh_calib_copy", "mdh_calib_read", "mdh_calib_mfma", "mdh_calib_valu",
     "mdh_custom_default_params", "mdh_custom_validate_params", "mdh_custom_num_candidates", "mdh_custom_candidate",
     "mdh_custom_create", "mdh_custom_source", "mdh_custom_workspace_size", "mdh_custom_run", "mdh_custom_destroy",
 )
@@ -108,6 +108,7 @@ def lib() -> ctypes.CDLL:
         L.mdh_matmul_ex.argtypes = [i64, i64, i64, i64, vp, i32, vp, i32, vp, i32, pp, vp, sz, vp]
         L.mdh_dot.argtypes = [i64, vp, vp, vp, pp, vp, sz, vp]
         L.mdh_scan.argtypes = [i64, i64, vp, vp, pp, vp, sz, vp]
+        L.mdh_mcc_capsule.argtypes = [i64] * 9 + [vp, vp, vp, pp, vp]
         L.mdh_matvec.argtypes = [i64, i64, vp, vp, vp, pp, vp, sz, vp]
         L.mdh_tune.argtypes = [ctypes.c_int, p64, ctypes.POINTER(vp), ctypes.POINTER(f32), vp, sz, vp, i32, pp,
                                ctypes.POINTER(f32)]
@@ -301,6 +302,22 @@ def mdh_dot(x, y, out, params: Optional[TileParams] = None, workspace=None):
     st = lib().mdh_dot(K, _dev(x, torch.float32, "x"), _dev(y, torch.float32, "y"), _dev(out, torch.float32, "out"),
                        _pref(params), wp, wb, ctypes.c_void_p(_stream()))
     _check(st, "mdh_dot")
+    return out
+
+
+def mdh_mcc_capsule(x, filt, out, stride=(1, 1), params: Optional[TileParams] = None):
+    """x: (N,H,W,C,4,4), filt: (K,R,S,C,4,4), out: (N,P,Q,K,4,4)."""
+    import torch
+
+    N, H, W, C, MI, MK = x.shape
+    K, R, S, C2, MK2, MJ = filt.shape
+    assert (MI, MK, MJ, MK2) == (4, 4, 4, 4) and C == C2
+    sh, sw = stride
+    P, Q = (H - R) // sh + 1, (W - S) // sw + 1
+    assert tuple(out.shape) == (N, P, Q, K, 4, 4)
+    st = lib().mdh_mcc_capsule(N, H, W, C, K, R, S, sh, sw, _dev(x, torch.float32, "x"), _dev(filt, torch.float32, "filt"),
+                               _dev(out, torch.float32, "out"), _pref(params), ctypes.c_void_p(_stream()))
+    _check(st, "mdh_mcc_capsule")
     return out
 
 

@@ -15,6 +15,7 @@ SOURCES = [
     "mdh_plan_reduce.cpp",
     "mdh_plan_ex.cpp",
     "mdh_plan_scan.cpp",
+    "mdh_plan_capsule.cpp",
     "mdh_custom.cpp",
     "mdh_api.hip",
     "mdh_stencil.hip",
@@ -23,6 +24,7 @@ SOURCES = [
     "mdh_mcc_flat.hip",
     "mdh_calib.hip",
     "mdh_scan.hip",
+    "mdh_capsule.hip",
     "mdh_matmul_skinny.hip",
     "mdh_custom_reduce.hip",
     "mdh_reduce.hip",

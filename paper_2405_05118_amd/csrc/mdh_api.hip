@@ -83,6 +83,26 @@ mdh_status mdh_mcc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_
   return launch_mcc(pl, N, H, W, C, K, R, S, stride_h, stride_w, in, filt, out, (hipStream_t)stream);
 }
 
+mdh_status mdh_mcc_capsule(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                           int64_t stride_h, int64_t stride_w, const float* in, const float* filt,
+                           float* out, const mdh_tile_params* params, void* stream) {
+  if (N < 0 || K < 0 || C < 1 || R < 1 || S < 1 || stride_h < 1 || stride_w < 1) return MDH_ERR_SIZE;
+  if (H < R || W < S) return MDH_ERR_SIZE;
+  if (too_big(N) || too_big(H) || too_big(W) || too_big(C) || too_big(K) || too_big(R) || too_big(S))
+    return MDH_ERR_SIZE;
+  const int64_t P = (H - R) / stride_h + 1, Q = (W - S) / stride_w + 1;
+  if (too_big(H * W) || too_big(N * H * W) || too_big(N * H * W * C) || too_big(N * H * W * C * 16)) return MDH_ERR_SIZE;
+  if (too_big(R * S * C) || too_big(K * R * S * C) || too_big(K * R * S * C * 16)) return MDH_ERR_SIZE;
+  if (too_big(N * P * Q) || too_big(N * P * Q * K) || too_big(N * P * Q * K * 16)) return MDH_ERR_SIZE;
+  const int64_t sizes[9] = {N, P, Q, K, C, R, S, stride_h, stride_w};
+  CapsulePlan pl;
+  mdh_status st = plan_capsule(sizes, params, &pl);
+  if (st != MDH_OK) return st;
+  if (N == 0 || K == 0) return MDH_OK;
+  if (!in || !filt || !out) return MDH_ERR_NULL;
+  return launch_capsule(pl, N, H, W, C, K, R, S, stride_h, stride_w, in, filt, out, (hipStream_t)stream);
+}
+
 mdh_status mdh_custom_reduce(int64_t nA, int64_t nB, int32_t nF, const int32_t* A,
                              const int32_t* B, const int32_t* w_agree, const int32_t* w_disagree,
                              int32_t* out_score, int32_t* out_index,

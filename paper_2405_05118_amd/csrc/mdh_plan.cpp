@@ -584,7 +584,7 @@ mdh_status mdh_part_offset(int64_t N, int32_t L, const int32_t* P, const int32_t
 
 static mdh_status check_sizes(mdh_instance inst, const int64_t* s) {
   if (!s) return MDH_ERR_NULL;
-  const int D = inst == MDH_MCC ? 9 : (inst == MDH_CUSTOM_REDUCE || inst == MDH_MATVEC || inst == MDH_SCAN) ? 2
+  const int D = (inst == MDH_MCC || inst == MDH_MCC_CAPSULE) ? 9 : (inst == MDH_CUSTOM_REDUCE || inst == MDH_MATVEC || inst == MDH_SCAN) ? 2
                                   : inst == MDH_DOT ? 1 : inst == MDH_BMATMUL ? 7 : 3;
   for (int d = 0; d < D; ++d)
     if (s[d] < 0 || s[d] > 0x7fffffff) return MDH_ERR_SIZE;
@@ -605,6 +605,7 @@ static mdh_status check_sizes(mdh_instance inst, const int64_t* s) {
     case MDH_SCAN:
       break;
     case MDH_MCC:
+    case MDH_MCC_CAPSULE:
       if (s[4] < 1 || s[5] < 1 || s[6] < 1 || s[7] < 1 || s[8] < 1) return MDH_ERR_SIZE;
       break;
     case MDH_CUSTOM_REDUCE:
@@ -661,6 +662,11 @@ mdh_status mdh_default_params(mdh_instance inst, const int64_t* sizes, mdh_tile_
       if ((st = plan_scan(sizes, nullptr, &pl)) == MDH_OK) params_from_plan(sizes, pl, out);
       return st;
     }
+    case MDH_MCC_CAPSULE: {
+      CapsulePlan pl;
+      if ((st = plan_capsule(sizes, nullptr, &pl)) == MDH_OK) params_from_plan(sizes, pl, out);
+      return st;
+    }
   }
   return MDH_ERR_UNSUPPORTED;
 }
@@ -701,6 +707,10 @@ mdh_status mdh_validate_params(mdh_instance inst, const int64_t* sizes, const md
     case MDH_SCAN: {
       ScanPlan pl;
       return plan_scan(sizes, p, &pl);
+    }
+    case MDH_MCC_CAPSULE: {
+      CapsulePlan pl;
+      return plan_capsule(sizes, p, &pl);
     }
   }
   return MDH_ERR_UNSUPPORTED;
@@ -780,6 +790,10 @@ int32_t mdh_num_candidates(mdh_instance inst, const int64_t* sizes) {
       ScanPlan c[CAP];
       return scan_candidates(sizes, c, CAP);
     }
+    case MDH_MCC_CAPSULE: {
+      CapsulePlan c[CAP];
+      return capsule_candidates(sizes, c, CAP);
+    }
   }
   return 0;
 }
@@ -842,6 +856,13 @@ mdh_status mdh_candidate(mdh_instance inst, const int64_t* sizes, int32_t idx, m
     case MDH_SCAN: {
       ScanPlan c[CAP];
       int n = scan_candidates(sizes, c, CAP);
+      if (idx < 0 || idx >= n) return MDH_ERR_SIZE;
+      params_from_plan(sizes, c[idx], out);
+      return MDH_OK;
+    }
+    case MDH_MCC_CAPSULE: {
+      CapsulePlan c[CAP];
+      int n = capsule_candidates(sizes, c, CAP);
       if (idx < 0 || idx >= n) return MDH_ERR_SIZE;
       params_from_plan(sizes, c[idx], out);
       return MDH_OK;

@@ -39,8 +39,8 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_struct_layout_matches_header():
-    # 4 + 6*7*4 + 7*4 + 42 + 3 + 4 + 1 + 4 + 1 + 3 = 258 -> padded to 260 (int32 alignment)
-    assert ctypes.sizeof(mdh.TileParams) == 260
+    # 4 + 6*10*4 + 10*4 + 60 + 3 + 4 + 1 + 4 + 1 + 3 = 360
+    assert ctypes.sizeof(mdh.TileParams) == 360
     assert mdh.mdh_version() == "0.1"
     assert "NULL" in mdh.mdh_strerror(E_NULL)
 
@@ -91,7 +91,7 @@ def test_default_params_satisfy_the_constraints(inst, sizes):
     assert lanes <= 1024  # model constraint: lanes per workgroup
     # the order is a permutation of all (layer, dim) pairs
     used = sorted(p.order[i] for i in range(6 * D))
-    assert used == sorted(l * 7 + d for l in range(6) for d in range(D))
+    assert used == sorted(l * B.MDH_MAX_D + d for l in range(6) for d in range(D))
     assert mdh.mdh_validate_params(inst, sizes, p) == OK
 
 
