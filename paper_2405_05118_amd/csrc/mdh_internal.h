@@ -82,15 +82,18 @@ int scan_candidates(const int64_t* sizes, ScanPlan* out, int cap);
 mdh_status launch_scan(const ScanPlan& pl, int64_t R, int64_t n, const float* in, float* out, void* ws,
                        hipStream_t st);
 
-// MCC_Capsule: NI blocks of 8 output channels per wavefront (workgroup = 4 rows x 8 columns of pixels)
+// MCC_Capsule: NI blocks of 8 output channels per wavefront; a workgroup owns 4 output rows and walks
+// QT tiles of 8 columns
 struct CapsulePlan {
   int NI;
+  int QT;
+  int RW;  // wavefront-layer parts of the fused (r, s, c) reduction walk
   int ragged;
 };
 mdh_status plan_capsule(const int64_t* sizes, const mdh_tile_params* p, CapsulePlan* out);
 void params_from_plan(const int64_t* sizes, const CapsulePlan& pl, mdh_tile_params* out);
 int capsule_candidates(const int64_t* sizes, CapsulePlan* out, int cap);
-int64_t capsule_lds_bytes(int NI, int64_t C, int64_t R, int64_t S, int64_t sh, int64_t sw);
+int64_t capsule_lds_bytes(int NI, int RW, int64_t C, int64_t R, int64_t S, int64_t sh, int64_t sw);
 mdh_status launch_capsule(const CapsulePlan& pl, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
                           int64_t R, int64_t S, int64_t sh, int64_t sw, const float* in,
                           const float* filt, float* out, hipStream_t st);
