@@ -316,6 +316,40 @@ def bench_matmul_ex(torch, mdh, W, name, steps, warmup, cpu):
     return res
 
 
+def bench_capsule(torch, mdh, W, name, steps, warmup, cpu):
+    """MCC_Capsule at the first-layer shape of ResNet-50 (training): MCC on 4 x 4 matrices."""
+    cfg = W.CONFIGS["mcc_resnet50_first"]
+    P = (cfg.H - cfg.R) // cfg.stride[0] + 1
+    Q = (cfg.W - cfg.S) // cfg.stride[1] + 1
+    x = W.device_normal(cfg.seed + 100, 1, (cfg.N, cfg.H, cfg.W, cfg.C, 4, 4))
+    f = W.device_normal(cfg.seed + 100, 2, (cfg.K, cfg.R, cfg.S, cfg.C, 4, 4))
+    o = torch.empty((cfg.N, P, Q, cfg.K, 4, 4), dtype=torch.float32, device="cuda")
+    ms, wall = _events_ms(torch, lambda: mdh.mdh_mcc_capsule(x, f, o, cfg.stride), steps, warmup)
+    flop = 2.0 * cfg.N * P * Q * cfg.K * cfg.C * cfg.R * cfg.S * 64
+    tf = flop / ms / 1e9
+    res = {
+        "value": flop / wall / 1e6, "unit": "GFLOP/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "f32",
+        "kernel": "capsule_kernel",
+        "roofline": {"bound": "mfma", "achieved": tf, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tf / PEAK_FP32_MFMA_TFLOPS, "traffic": TRAFFIC_BYTES.get(name)},
+        "algorithmic_flop": flop,
+        "algorithmic_bytes": 4 * (x.numel() + f.numel() + o.numel()),
+    }
+    if cpu:
+        import numpy as np
+
+        import oracle
+
+        xh, fh = x[:1, : cfg.R + 2 * 7].cpu().numpy(), f.cpu().numpy()  # 8 output rows of image 0
+        t0 = time.perf_counter()
+        r = oracle.mcc_capsule(np.ascontiguousarray(xh), fh, cfg.stride)
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": 2.0 * r.size * cfg.C * cfg.R * cfg.S * 4 / dt / 1e9, "unit": "GFLOP/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "output rows p<%d of image 0 (%.2f s)" % (r.shape[1], dt)}
+    return res
+
+
 def bench_scan(torch, mdh, W, name, steps, warmup, cpu):
     """Row-wise scan(+): one long row (chunks over workgroups, three kernels) or many rows (one pass)."""
     R, n = (1, 1 << 28) if name == "scan_2p28" else (65536, 4096)
@@ -440,6 +474,7 @@ BENCHES = {
     "mcc_resnet50_first": bench_mcc,
     "matmul_resnet50_fc": bench_matmul_ex,
     "matmul_vgg16_fc": bench_matmul_ex,
+    "mcc_capsule_resnet50_first": bench_capsule,
     "scan_2p28": bench_scan,
     "scan_rows_65536x4096": bench_scan,
     "histo_generic_256x2p24": bench_histo_generic,
@@ -514,7 +549,7 @@ def main() -> int:
         for name, fn in BENCHES.items():
             if name == args.workload:
                 continue
-            steps = max(5, min(args.steps, 30 if name in ("mcc_resnet", "prl_2p16_2p18") else 100))
+            steps = max(5, min(args.steps, 30 if name in ("mcc_resnet", "prl_2p16_2p18", "mcc_capsule_resnet50_first") else 100))
             inst[name] = fn(torch, mdh, W, name, steps, max(2, min(args.warmup, 5)), not args.no_cpu)
             torch.cuda.synchronize()
             torch.cuda.empty_cache()
