@@ -36,15 +36,22 @@ PRL_LANE_OPS_PER_PAIR = 24.0
 # HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/);
 # None until measured for that workload
 TRAFFIC_BYTES = {
-    # profiles/all_kernels_hbm_traffic_pmc.md (main kernel of each workload)
-    "jacobi3d_512": 1109672283,
-    "dot_2p28": 2147433877,
-    "matvec_16384": 1074504826,
-    "matmul_4096": 604096517,
-    "matmul_ts": None,  # only measured mixed with the split-k run (same kernel name)
-    "mcc_resnet": 851363442,
-    "prl_2p16_2p18": 138923866,
-    "matmul_256": 4809399,
+    # profiles/all_kernels_hbm_traffic_pmc.md (all kernels of a step)
+    "jacobi3d_512": 1110236372,
+    "dot_2p28": 2147373315,
+    "matvec_16384": 1074466926,
+    "matmul_4096": 604073920,
+    "matmul_ts": 1102209479,
+    "mcc_resnet": 851128217,
+    "prl_2p16_2p18": 141525914,
+    "matmul_256": 5403072,
+    "mcc_resnet50_first": 61878429,
+    "matmul_resnet50_fc": 14433971,
+    "matmul_vgg16_fc": 426435447,
+    "mcc_capsule_resnet50_first": 1072570351,
+    "scan_2p28": 3221513028,
+    "scan_rows_65536x4096": 2147467414,
+    "histo_generic_256x2p24": 320573908,
 }
 
 
