@@ -230,6 +230,20 @@ mdh_status mdh_tune(mdh_instance inst, const int64_t* sizes, void* const* buffer
                                    (const int32_t*)buffers[1], (const int32_t*)buffers[2],
                                    (const int32_t*)buffers[3], (int32_t*)buffers[4],
                                    (int32_t*)buffers[5], &p, workspace, workspace_bytes, stream);
+        case MDH_BMATMUL:
+          return mdh_matmul_ex(sizes[0], sizes[1], sizes[2], sizes[3], (const float*)buffers[0], (int32_t)sizes[4],
+                               (const float*)buffers[1], (int32_t)sizes[5], (float*)buffers[2], (int32_t)sizes[6],
+                               &p, workspace, workspace_bytes, stream);
+        case MDH_SCAN:
+          return mdh_scan(sizes[0], sizes[1], (const float*)buffers[0], (float*)buffers[1], &p, workspace,
+                          workspace_bytes, stream);
+        case MDH_MCC_CAPSULE: {
+          const int64_t H = (sizes[1] - 1) * sizes[7] + sizes[5], W = (sizes[2] - 1) * sizes[8] + sizes[6];
+          return mdh_mcc_capsule(sizes[0], H, W, sizes[4], sizes[3], sizes[5], sizes[6], sizes[7], sizes[8],
+                                 (const float*)buffers[0], (const float*)buffers[1], (float*)buffers[2], &p, stream);
+        }
+        default:
+          break;
       }
       return MDH_ERR_UNSUPPORTED;
     };

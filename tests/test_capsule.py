@@ -116,3 +116,15 @@ def test_paper_shapes_sampled(net, N):
     ref, refabs = oracle.mcc_capsule_at(x, f, pos, net["stride"])
     err = np.abs(got[tuple(pos.T)] - ref) / refabs
     assert float(err.max()) <= TOL
+
+
+@pytest.mark.gpu
+def test_tune_picks_a_valid_configuration():
+    N, H, Wd, C, K, R, S, stride = 1, 21, 40, 3, 16, 3, 3, (2, 2)
+    x, f = inputs(N, H, Wd, C, K, R, S, W.SEED_BASE + 96)
+    s = sizes_of(N, H, Wd, C, K, R, S, stride)
+    out = torch.empty((N, s[1], s[2], K, 4, 4), dtype=torch.float32, device="cuda")
+    best, ms = mdh.mdh_tune(mdh.MDH_MCC_CAPSULE, s, [dev(x), dev(f), out], reps=2)
+    assert ms > 0 and mdh.mdh_validate_params(mdh.MDH_MCC_CAPSULE, s, best) == 0
+    ref, refabs = oracle.mcc_capsule(x, f, stride, with_abs=True)
+    assert float(np.max(np.abs(run(x, f, stride, best) - ref) / refabs)) <= TOL

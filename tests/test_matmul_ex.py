@@ -155,3 +155,17 @@ def test_paper_shapes_small_m():
         ones_b = np.ones((1, 1000, 2048), np.float32)
         got, _ = run(ones_a, ones_b, True, True, True, None)
         assert got.shape == (1, 1000, M) and np.all(got == 2048)
+
+
+@pytest.mark.gpu
+def test_tune_picks_a_valid_configuration():
+    sizes = (2, 16, 300, 700, 0, 0, 0)
+    A = W.uniform(W.SEED_BASE + 64, 1, (2, 16, 700), -1, 1)
+    Bm = W.uniform(W.SEED_BASE + 64, 2, (2, 700, 300), -1, 1)
+    C = torch.empty((2, 16, 300), dtype=torch.float32, device="cuda")
+    ws = torch.empty(64 * 2 * 16 * 300, dtype=torch.float32, device="cuda")
+    best, ms = mdh.mdh_tune(mdh.MDH_BMATMUL, sizes, [dev(A), dev(Bm), C], workspace=ws, reps=2)
+    assert ms > 0 and mdh.mdh_validate_params(mdh.MDH_BMATMUL, sizes, best) == 0
+    ref, refabs = reference(A, Bm, False, False, False)
+    got, _ = run(A, Bm, False, False, False, best)
+    assert float(np.max(np.abs(got - ref) / refabs)) <= TOL

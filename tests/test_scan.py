@@ -99,3 +99,16 @@ def test_long_row_and_explicit_chunks():
     with pytest.raises(mdh.MdhError) as e:  # chunked configuration without workspace
         mdh.mdh_scan(torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda"))
     assert e.value.status == 5
+
+
+@pytest.mark.gpu
+def test_tune_picks_a_valid_configuration():
+    shape = (4, 200000)
+    x = W.uniform(W.SEED_BASE + 97, 1, shape, -1, 1)
+    xs = torch.from_numpy(x).cuda()
+    out = torch.empty_like(xs)
+    ws = torch.empty(1 << 16, dtype=torch.float64, device="cuda")
+    best, ms = mdh.mdh_tune(mdh.MDH_SCAN, shape, [xs, out], workspace=ws, reps=2)
+    assert ms > 0 and mdh.mdh_validate_params(mdh.MDH_SCAN, shape, best) == 0
+    ref, refabs = oracle.scan_rows(x, with_abs=True)
+    assert float(np.max(np.abs(run(x, best) - ref) / refabs)) <= TOL
