@@ -20,6 +20,7 @@ namespace mdh {
 namespace {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));  // dword-aligned 16-byte access
 typedef float f16 __attribute__((ext_vector_type(16)));
 
 template <int QB, int MI, int NI, int WAVES_M, int WAVES_N>
@@ -54,22 +55,61 @@ __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
   float* fs = lds;                    // filter slice [BN][PFR]: row k holds R groups of SCP floats
   float* ps = lds + Cf::BN * PFR;     // input patch [PH][PWF]
 
-  // stage the filter slice, zero in the padding of sc and in absent output channels
-  for (int idx = tid; idx < Cf::BN * R * SCP; idx += Cf::NT) {
-    const int k = idx / (R * SCP), rem = idx - k * (R * SCP);
-    const int r = rem / SCP, x = rem - r * SCP;
-    float v = 0.f;
-    if (k0 + k < K && x < SC) v = filt[((int64_t)(k0 + k) * R + r) * SC + x];
-    fs[k * PFR + r * SCP + x] = v;
-  }
-  // stage the input patch; cells outside the image read as 0 (they only meet zero filter entries
-  // or outputs that are not stored)
-  for (int idx = tid; idx < PH * PWF; idx += Cf::NT) {
-    const int ph = idx / PWF, x = idx - ph * PWF;
-    const int hy = p0 * sh + ph, gx = q0 * sw * C + x;
-    float v = 0.f;
-    if (hy < H && gx < WC) v = in[((int64_t)n * H + hy) * WC + gx];
-    ps[idx] = v;
+  // Staging without integer divisions in the loops: a filter row k is R*SC contiguous floats in
+  // memory, so a lane's elements e = lane, lane+64, ... have the same (r, x) for every k and that
+  // split is computed once; wavefronts take the rows k (filter) and ph (patch) in turn.
+  {
+    constexpr int NW = Cf::NT / 64;
+    const int RSC = R * SC;
+    for (int e0 = 0; e0 < RSC; e0 += 256) {
+      int off[4];  // LDS offset inside a filter row, -1: beyond the row
+      int ge[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int e = e0 + u * 64 + lane;
+        const int r = e / SC;
+        ge[u] = e;
+        off[u] = e < RSC ? r * SCP + (e - r * SC) : -1;
+      }
+      for (int k = wave; k < Cf::BN; k += NW) {
+        const bool kin = k0 + k < K;
+        const float* src = filt + (int64_t)(k0 + k) * RSC;
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = (kin && off[u] >= 0) ? src[ge[u]] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (off[u] >= 0) fs[k * PFR + off[u]] = v[u];
+      }
+    }
+    // zero the padding of every filter row (x in [SC, SCP)): it meets patch values in the MFMAs
+    const int padn = SCP - SC;
+    for (int i = tid; i < Cf::BN * R * padn; i += Cf::NT) {
+      const int row = i / padn, x = SC + (i - row * padn);
+      const int k = row / R, r = row - k * R;
+      fs[k * PFR + r * SCP + x] = 0.f;
+    }
+    // Input patch, 16 bytes at a time (rows are only dword aligned); cells outside the image read
+    // as 0 (they only meet zero filter entries or outputs that are not stored).
+    const int pw4 = PWF >> 2;
+    for (int ph = wave; ph < PH; ph += NW) {
+      const int hy = p0 * sh + ph;
+      const float* src = in + ((int64_t)n * H + hy) * WC + q0 * sw * C;
+      for (int x4 = lane; x4 < pw4; x4 += 64) {
+        const int x = x4 << 2, gx = q0 * sw * C + x;
+        f4 v = {0.f, 0.f, 0.f, 0.f};
+        if (hy < H) {
+          if (gx + 3 < WC) {
+            v = *(const f4u*)(src + x);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (gx + e < WC) v[e] = src[x + e];
+          }
+        }
+        *(f4*)(ps + ph * PWF + x) = v;
+      }
+    }
   }
   __syncthreads();
 
@@ -106,19 +146,24 @@ __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
     }
   }
 
-  // output view (n,p,q,k,0,0,0) -> out[n,p,q,k]
+  // output view (n,p,q,k,0,0,0) -> out[n,p,q,k]; the buffer has fewer than 2^31 elements (checked
+  // by the caller), so 32-bit offsets are exact
+  float* obase = out + (int64_t)n * P * Q * K;
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
+  for (int mi = 0; mi < MI; ++mi) {
+    const int prow = p0 + (wm * MI + mi) * Cf::RB;
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
       const int k = k0 + (wn * NI + ni) * 32 + l32;
+      if (k >= K) continue;
 #pragma unroll
       for (int rg = 0; rg < 16; ++rg) {
         const int m = 8 * (rg / 4) + 4 * lh + (rg % 4);  // pixel of the block this register holds
-        const int p = p0 + (wm * MI + mi) * Cf::RB + m / QB, q = q0 + m % QB;
-        if (p < P && q < Q && k < K) out[(((int64_t)n * P + p) * Q + q) * K + k] = acc[mi][ni][rg];
+        const int p = prow + m / QB, q = q0 + m % QB;
+        if (p < P && q < Q) obase[(p * Q + q) * K + k] = acc[mi][ni][rg];
       }
     }
+  }
 }
 
 template <int QB, int MI, int NI, int WAVES_M, int WAVES_N>
