@@ -62,17 +62,46 @@ __global__ __launch_bounds__(256 * RW) void capsule_kernel(const float* __restri
   const int steps = R * J2;
   const int t0 = (steps * rw) / RW, t1 = (steps * (rw + 1)) / RW;
 
-  // filter slice: global order [mk][mj] -> LDS order [mj][mk]; zeros beyond S*C and beyond K.
-  // One 16-byte global read (mj = 0..3 of one mk) per step.
-  for (int idx = tid; idx < 8 * NI * R * JP * 4; idx += CAP_NT) {
-    const int mk = idx & 3, t = idx >> 2;
-    const int j = t % JP, t2 = t / JP;
-    const int r = t2 % R, k = t2 / R;
-    f4 v = {0.f, 0.f, 0.f, 0.f};
-    if (k0 + k < K && j < SCJ) v = *(const f4u*)(filt + ((((int64_t)(k0 + k) * R + r) * SCJ + j) << 4) + mk * 4);
-    float* d = fs + k * PFR + ((r * JP + j) << 4) + mk;
+  // filter slice: global order [mk][mj] -> LDS order [mj][mk].  A filter row k is R*S*C*16 contiguous
+  // floats, so the split of a lane's 16-byte pieces into (r, j, mk) is the same for every k and is
+  // computed once; the wavefronts take the rows k in turn (no integer division per element).
+  {
+    constexpr int NW = CAP_NT / 64;
+    const int wid = tid >> 6;
+    const int row4 = R * SCJ * 4;  // 16-byte pieces of a filter row
+    for (int e0 = 0; e0 < row4; e0 += 256) {
+      int off[4], ge[4];
 #pragma unroll
-    for (int mj = 0; mj < 4; ++mj) d[mj * 4] = v[mj];
+      for (int u = 0; u < 4; ++u) {
+        const int e = e0 + u * 64 + lane;  // piece (r, j, mk): mj = 0..3 of one mk
+        const int rj = e >> 2, mk = e & 3;
+        const int r = rj / SCJ, j = rj - r * SCJ;
+        ge[u] = e << 2;
+        off[u] = e < row4 ? ((r * JP + j) << 4) + mk : -1;
+      }
+      for (int k = wid; k < 8 * NI; k += NW) {
+        const bool kin = k0 + k < K;
+        const float* src = filt + (int64_t)(k0 + k) * row4 * 4;
+        f4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          v[u] = (kin && off[u] >= 0) ? *(const f4u*)(src + ge[u]) : (f4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (off[u] >= 0) {
+            float* d = fs + k * PFR + off[u];
+#pragma unroll
+            for (int mj = 0; mj < 4; ++mj) d[mj * 4] = v[u][mj];
+          }
+      }
+    }
+    // zero the padding pair of every filter row r (j in [S*C, JP)): it meets patch values
+    if (JP > SCJ)
+      for (int i = tid; i < 8 * NI * R * 16; i += CAP_NT) {
+        const int e = i & 15, row = i >> 4;
+        const int k = row / R, r = row - k * R;
+        fs[k * PFR + ((r * JP + SCJ) << 4) + e] = 0.f;
+      }
   }
 
   // A: row (dq, mi) of the block; B: column (dk, mj); the lane half h takes the odd (s,c) pair
@@ -159,7 +188,7 @@ __global__ __launch_bounds__(256 * RW) void capsule_kernel(const float* __restri
         for (int g = 0; g < 4; ++g) {
           const int q = q0 + 2 * g + h;  // registers 4g..4g+3 hold mi = 0..3 of this pixel
           if (q >= Q) continue;
-          float* o = out + (((((int64_t)n * P + p) * Q + q) * K + k) << 4) + m4;
+          float* o = out + ((((int64_t)n * P + p) * Q * K) << 4) + (((q * K + k) << 4) + m4);
 #pragma unroll
           for (int mi = 0; mi < 4; ++mi) o[mi * 4] = acc[ni][4 * g + mi];
         }

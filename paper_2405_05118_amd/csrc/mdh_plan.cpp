@@ -378,13 +378,14 @@ static int mcc_ragged(const int64_t* s, const MccPlan& pl) {
 }
 
 static MccPlan mcc_flat_plan(const int64_t* s) {
-  // block width 16 when it divides Q and 32 does not (e.g. Q = 112); channels per workgroup by K
-  const int qb = (s[2] % 32 != 0 && s[2] % 16 == 0) ? 16 : 32;
-  const int tp = qb == 16 ? 8 : 4;
-  // 32 channels per workgroup measured fastest up to K = 64 (ResNet-50 first layer: 80 us against
-  // 106 us with 64): more workgroups, and each stages half the filter
+  // Measured on the first-layer shapes of ResNet-50, VGG-16 and MobileNet: blocks of 4 x 32 pixels are
+  // fastest even where 32 does not divide Q (112 = 3.5 blocks: the last one is predicated).  Many
+  // taps (7 x 7 x 3): 32 channels per workgroup -- more workgroups, each stages half the filter
+  // (64 us against 78 us with 64).  Few taps (3 x 3 x 3): the output write dominates and 64
+  // channels per workgroup write whole 256-byte pixels (78 us against 93 us).
+  const int qb = 32, tp = 4;
   MccPlan pl{tp, qb, 32, 0, 32, 32, 0, 1};
-  if (s[3] > 64) pl = MccPlan{tp, qb, 64, 0, 32, 64, 0, 1};
+  if (s[3] > 64 || (s[3] > 32 && s[4] * s[5] * s[6] <= 48)) pl = MccPlan{tp, qb, 64, 0, 32, 64, 0, 1};
   pl.ragged = mcc_ragged(s, pl);
   return pl;
 }

@@ -29,10 +29,13 @@ def test_default_fuses_s_and_c_for_few_channels():
         assert mdh.mdh_validate_params(mdh.MDH_MCC, s, p) == 0
         for d in range(7):
             assert p.extent(d) >= s[d] if p.ragged else p.extent(d) == s[d]
-    # ResNet's 112 output columns are 7 blocks of 16, not a multiple of 32: no ragged columns
+    # ResNet's 112 output columns are walked in blocks of 32 (the last one predicated); a table with
+    # blocks of 16, which divide 112, is among the candidates
     s = sizes_of(1, 230, 230, 3, 64, 7, 7, (2, 2))
     p = mdh.mdh_default_params(mdh.MDH_MCC, s)
-    assert p.blk[2] == 16 and p.extent(2) == 112
+    assert p.blk[2] == 32 and p.extent(2) == 128 and p.ragged
+    cands = [mdh.mdh_candidate(mdh.MDH_MCC, s, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_MCC, s))]
+    assert any(c.blk[2] == 16 and c.extent(2) == 112 for c in cands)
     # many channels keep the channel-chunked kernel
     p = mdh.mdh_default_params(mdh.MDH_MCC, (16, 224, 224, 128, 64, 7, 7, 1, 1))
     assert p.blk[4] == 2
