@@ -2,7 +2,8 @@
 on seeded inputs.  Sizes span several tiles and ragged tails; every candidate tile
 configuration is a valid (de/re)-composition and must give the same result.
 
-Tolerances (the design doc derives them):
+Tolerances (fp32 products are exact in fp64 and every fp32 accumulation step adds at most 2^-24
+relative to the running |sum| <= sum |a*b|: worst case K * 2^-24, typically ~sqrt(K) * 2^-24):
   MatMul / MCC : max |gpu - ref| / sum_k |a*b|  <= 1e-4   (componentwise-scaled error)
   Jacobi-3D    : max |gpu - ref| / ref          <= 1e-6   (all terms non-negative)
   custom reduce: bit-exact (int32)
