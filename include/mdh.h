@@ -357,7 +357,10 @@ mdh_status mdh_candidate(mdh_instance inst, const int64_t* sizes, int32_t idx,
  *
  *   out[out_index(i)] = op_1 ... op_D  f( in_{b_1}[idx_1(i)], ..., in_{b_A}[idx_A(i)], i )
  *
- * with op_d = ++ (reduce[d] = 0) or op_d = pw(op) (reduce[d] = 1), a user-defined
+ * with op_d = ++ (reduce[d] = 0), op_d = pw(op) (reduce[d] = 1) or, for at most
+ * one dimension, op_d = prefix-sum(op) (reduce[d] = 2; paper: Appendix, Example
+ * "Prefix-Sum": the dimension is kept and index i holds the combination of all
+ * indices <= i; this kernel walks it sequentially per lane), a user-defined
  * result type T, scalar function f and operator op given as C source and compiled
  * for gfx950 when the operation is created (hipRTC).  All point-wise dimensions of
  * one operation share ONE operator op, which must be associative and commutative
@@ -376,7 +379,7 @@ mdh_status mdh_candidate(mdh_instance inst, const int64_t* sizes, int32_t idx,
  *   out_type     T: type of f's result, of op's operands and of the output elements
  *   out_elem_bytes  sizeof(T), checked against the compiled code
  *   out_index    flat element index in the output buffer; NULL = row-major over the
- *                ++ dimensions.  Indices of reduced dimensions are 0 here.
+ *                ++ (and prefix-sum) dimensions.  Indices of reduced dimensions are 0.
  *   f            statements that set `T r` from a0..a{A-1} (the accessed elements,
  *                const references) and i0..i{D-1}
  *   op           statements that set `T r` from `x` and `y` (const T references)

@@ -370,12 +370,13 @@ class CustomDesc(ctypes.Structure):
 
 def custom_desc(sizes, reduce, in_types, accesses, out_type, out_elem_bytes, f, op=None, prelude=None,
                 out_index=None, fast_dim=-1) -> CustomDesc:
-    """Fill a ``mdh_custom_desc``: ``accesses`` is a list of (input buffer number, index expression)."""
+    """Fill a ``mdh_custom_desc``: ``reduce[d]`` is 0 (++), 1 (pw(op)) or 2 (prefix-sum(op));
+    ``accesses`` is a list of (input buffer number, index expression)."""
     d = CustomDesc()
     d.D = len(sizes)
     for i, (n, r) in enumerate(zip(sizes, reduce)):
         d.sizes[i] = int(n)
-        d.reduce[i] = 1 if r else 0
+        d.reduce[i] = int(r)  # 0: ++, 1: pw(op), 2: prefix-sum(op)
     d.n_in, d.n_acc = len(in_types), len(accesses)
     for b, t in enumerate(in_types):
         d.in_type[b] = t.encode()

@@ -35,6 +35,7 @@ struct CustomPlan {
   int64_t N[MDH_MAX_D];
   int red[MDH_MAX_D];
   int64_t WG[MDH_MAX_D], L[MDH_MAX_D], Q[MDH_MAX_D];
+  int scan;  // the prefix-sum dimension (at most one), -1: none
   int strided;
   int fast;  // dimension with the fastest lane index
   int ragged;
@@ -51,6 +52,12 @@ bool desc_ok(const mdh_custom_desc* d) {
   if (d->n_acc < 1 || d->n_acc > MDH_CUSTOM_MAX_ACC) return false;
   if (d->out_elem_bytes < 1 || d->out_elem_bytes > 256) return false;
   if (d->fast_dim >= d->D) return false;
+  int scans = 0;
+  for (int i = 0; i < d->D; ++i) {
+    if (d->reduce[i] > 2) return false;
+    scans += d->reduce[i] == 2;
+  }
+  if (scans > 1) return false;
   int64_t total = 1;
   for (int i = 0; i < d->D; ++i) {
     if (d->sizes[i] < 1 || d->sizes[i] > 0x7fffffff) return false;
@@ -109,10 +116,17 @@ void fill_from_desc(const mdh_custom_desc* d, CustomPlan* pl) {
   pl->D = d->D;
   for (int i = 0; i < d->D; ++i) {
     pl->N[i] = d->sizes[i];
-    pl->red[i] = d->reduce[i] ? 1 : 0;
+    pl->red[i] = d->reduce[i] == 1 ? 1 : 0;
     pl->WG[i] = pl->L[i] = pl->Q[i] = 1;
   }
+  pl->scan = -1;
+  for (int i = 0; i < d->D; ++i)
+    if (d->reduce[i] == 2) pl->scan = i;
   pl->fast = d->fast_dim < 0 ? d->D - 1 : d->fast_dim;
+  // the prefix-sum dimension is walked sequentially by a lane: the lanes go to another dimension
+  if (pl->fast == pl->scan)
+    for (int i = 0; i < d->D; ++i)
+      if (i != pl->scan) pl->fast = i;
   pl->strided = 1;
 }
 
@@ -129,13 +143,14 @@ CustomPlan make_plan(const mdh_custom_desc* d, int nt, int64_t split) {
   CustomPlan pl;
   fill_from_desc(d, &pl);
   int left = nt;
-  pl.L[pl.fast] = pow2_floor(pl.N[pl.fast] < left ? pl.N[pl.fast] : left);
+  if (pl.scan >= 0) split = 1;  // the parts of the other reduced dimensions meet inside the workgroup
+  if (pl.fast != pl.scan) pl.L[pl.fast] = pow2_floor(pl.N[pl.fast] < left ? pl.N[pl.fast] : left);
   left /= (int)pl.L[pl.fast];
   while (left > 1) {
     int best = -1;
     for (int pass = 0; pass < 2 && best < 0; ++pass)
       for (int i = pl.D - 1; i >= 0; --i) {
-        if (i == pl.fast || (pass == 0 && pl.red[i])) continue;
+        if (i == pl.fast || i == pl.scan || (pass == 0 && pl.red[i])) continue;
         if (pl.N[i] / pl.L[i] < 2) continue;
         if (best < 0 || pl.N[i] / pl.L[i] > pl.N[best] / pl.L[best]) best = i;
       }
@@ -144,7 +159,7 @@ CustomPlan make_plan(const mdh_custom_desc* d, int nt, int64_t split) {
     left /= 2;
   }
   for (int i = 0; i < pl.D; ++i)
-    if (!pl.red[i]) pl.WG[i] = cdiv(pl.N[i], pl.L[i]);
+    if (!pl.red[i] && i != pl.scan) pl.WG[i] = cdiv(pl.N[i], pl.L[i]);
   // sequential parts of the concatenation dimensions only when the grid would not fit
   for (int i = 0; i < pl.D; ++i) {
     if (pl.red[i]) continue;
@@ -238,6 +253,9 @@ mdh_status plan_from_params(const mdh_custom_desc* d, const mdh_tile_params* p, 
   pl.strided = p->strided ? 1 : 0;
   pl.ragged = ragged;
   derive(&pl);
+  // a prefix-sum dimension is sequential in this kernel, and the other reduced dimensions may then
+  // not be split over workgroups
+  if (pl.scan >= 0 && (pl.WG[pl.scan] != 1 || pl.L[pl.scan] != 1 || pl.SG != 1)) return MDH_ERR_UNSUPPORTED;
   mdh_tile_params chk;
   params_from_custom(pl, &chk);
   if (!same_table(chk, *p)) return MDH_ERR_UNSUPPORTED;  // e.g. parts on the LDS / register layers
@@ -357,18 +375,26 @@ std::string generate(const mdh_custom_desc* d, const CustomPlan& pl) {
     o.f("  __shared__ mdh_T sh_val[%d];", pl.NT);
     o.f("  __shared__ unsigned char sh_ok[%d];", pl.NT);
   }
-  // concatenation dimensions: outer sequential loops
+  // concatenation dimensions: outer sequential loops; the prefix-sum dimension (which keeps its
+  // index set like a concatenation dimension) innermost of them, with a running value across it
   std::string ind = "  ";
   std::string cc_ok = "true";
+  std::vector<int> outer;
   for (int i = 0; i < D; ++i)
-    if (!pl.red[i]) {
-      o.f("%sfor (int q%d = 0; q%d < %lld; ++q%d) {", ind.c_str(), i, i, (long long)pl.Q[i], i);
-      ind += "  ";
-      o.f("%sconst i64 i%d = %s;", ind.c_str(), i, index_expr(pl, i).c_str());
-      char buf[48];
-      snprintf(buf, sizeof buf, " && i%d < N%d", i, i);
-      cc_ok += buf;
+    if (!pl.red[i] && i != pl.scan) outer.push_back(i);
+  if (pl.scan >= 0) outer.push_back(pl.scan);
+  for (int i : outer) {
+    if (i == pl.scan) {
+      o.f("%smdh_T run;", ind.c_str());
+      o.f("%sbool have_run = false;", ind.c_str());
     }
+    o.f("%sfor (int q%d = 0; q%d < %lld; ++q%d) {", ind.c_str(), i, i, (long long)pl.Q[i], i);
+    ind += "  ";
+    o.f("%sconst i64 i%d = %s;", ind.c_str(), i, index_expr(pl, i).c_str());
+    char buf[48];
+    snprintf(buf, sizeof buf, " && i%d < N%d", i, i);
+    cc_ok += buf;
+  }
   o.line(ind + "const bool cc_ok = " + cc_ok + ";");
   o.f("%smdh_T acc;", ind.c_str());
   o.f("%sbool have = false;", ind.c_str());
@@ -420,21 +446,27 @@ std::string generate(const mdh_custom_desc* d, const CustomPlan& pl) {
     std::string ccflat = "0";
     for (int i = 0; i < D; ++i)
       if (!pl.red[i]) ccflat = "(" + ccflat + ") * N" + std::to_string(i) + " + i" + std::to_string(i);
-    o.f("%sif (rl == 0 && cc_ok && have) {", ind.c_str());
+    if (pl.scan >= 0) {
+      // prefix-sum: the value of this index is the running combination of everything up to it
+      o.f("%sif (have) { if (have_run) run = mdh_op(run, acc); else { run = acc; have_run = true; } }", ind.c_str());
+      o.f("%sif (rl == 0 && cc_ok && have_run) {", ind.c_str());
+    } else {
+      o.f("%sif (rl == 0 && cc_ok && have) {", ind.c_str());
+    }
     for (int i = 0; i < D; ++i)
       if (pl.red[i]) o.f("%s  const i64 i%d = 0; (void)i%d;", ind.c_str(), i, i);
     o.line(ind + "  const i64 cc_ = " + ccflat + ";");
+    const char* val = pl.scan >= 0 ? "run" : "acc";
     if (pl.SG > 1)
-      o.f("%s  ws[sg * %lldLL + cc_] = acc;", ind.c_str(), (long long)pl.CCN);
+      o.f("%s  ws[sg * %lldLL + cc_] = %s;", ind.c_str(), (long long)pl.CCN, val);
     else
-      o.line(ind + "  out[" + (d->out_index ? d->out_index : "cc_") + "] = acc; (void)cc_;");
+      o.line(ind + "  out[" + (d->out_index ? d->out_index : "cc_") + "] = " + val + "; (void)cc_;");
     o.f("%s}", ind.c_str());
   }
-  for (int i = 0; i < D; ++i)
-    if (!pl.red[i]) {
-      ind.resize(ind.size() - 2);
-      o.f("%s}", ind.c_str());
-    }
+  for (size_t i = 0; i < outer.size(); ++i) {
+    ind.resize(ind.size() - 2);
+    o.f("%s}", ind.c_str());
+  }
   o.line("}");
 
   // second pass: fold the workgroup parts of the reduced dimensions in ascending order

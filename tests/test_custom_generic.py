@@ -268,3 +268,59 @@ def test_handle_is_reusable_and_checks_workspace():
     ref = oracle.matvec(A, xv)
     scale = np.abs(A.astype(np.float64)) @ np.abs(xv.astype(np.float64))
     assert float(np.max(np.abs(first.cpu().numpy() - ref) / scale)) <= 1e-4
+
+
+# ------------------------------------------------------------------ prefix-sum dimension (reduce = 2)
+
+
+def d_scan_rows(R, n, op="r = x + y;", ty="float"):
+    return mdh.custom_desc((R, n), (0, 2), [ty], [(0, "i0*N1+i1")], ty, 4, "r = a0;", op)
+
+
+def d_bottom_box_sums(R, C):
+    # md_hom(id, (prefix-sum(+), +)) with the rows read bottom-up through the index function
+    return mdh.custom_desc((R, C), (2, 1), ["float"], [(0, "(N0-1-i0)*N1+i1")], "float", 4, "r = a0;", "r = x + y;")
+
+
+def test_prefix_sum_dimension_is_sequential_in_the_table():
+    d = d_scan_rows(64, 3000)
+    p = mdh.mdh_custom_default_params(d)
+    assert p.prt[B.L_WG][1] == 1 and p.prt[B.L_LANE][1] == 1 and p.prt[B.L_HBM][1] == 3000
+    assert mdh.mdh_custom_validate_params(d, p) == 0
+    q = p.copy()
+    q.prt[B.L_LANE][1], q.prt[B.L_HBM][1] = 4, 750  # lanes on the prefix-sum dimension: not this kernel
+    assert mdh.mdh_custom_validate_params(d, q) == 6
+    # two prefix-sum dimensions are refused
+    with pytest.raises(mdh.MdhError):
+        mdh.mdh_custom_default_params(mdh.custom_desc((4, 4), (2, 2), ["int"], [(0, "i0*N1+i1")], "int", 4, "r = a0;", "r = x + y;"))
+    assert "have_run" in mdh.mdh_custom_source(mdh.mdh_custom_create(d))
+
+
+@pytest.mark.gpu
+def test_scan_and_mbbs_through_the_generic_path():
+    rng = np.random.default_rng(6)
+    # scan(+) and scan(max) on integers against the generic evaluator
+    v = rng.integers(-9, 10, 41).astype(np.int32)
+    for op, f in (("r = x + y;", lambda a, b: a + b), ("r = x > y ? x : y;", max)):
+        d = mdh.custom_desc((41,), (2,), ["int"], [(0, "i0")], "int", 4, "r = a0;", op)
+        got = run(d, [dev(v)], torch.full((41,), -99, dtype=torch.int32, device="cuda"))
+        assert got.cpu().tolist() == G.scan(f, v.tolist())
+    # row-wise scan against the generic evaluator (small) and the C oracle (larger), every candidate
+    X = rng.integers(-4, 5, (3, 7)).astype(np.float32)
+    got = run(d_scan_rows(3, 7), [dev(X)], torch.full((3, 7), float("nan"), device="cuda"))
+    assert got.cpu().numpy().tolist() == G.scan_rows(lambda a, b: a + b, X.astype(int).tolist())
+    Xl = W.uniform(W.SEED_BASE + 85, 1, (70, 1500), -1, 1)
+    ref, refabs = oracle.scan_rows(Xl, with_abs=True)
+    for p in all_params(d_scan_rows(70, 1500)):
+        got = run(d_scan_rows(70, 1500), [dev(Xl)], torch.full((70, 1500), float("nan"), device="cuda"), p)
+        assert float(np.max(np.abs(got.cpu().numpy() - ref) / refabs)) <= 1e-4
+    # the md_hom of MBBS: two dimensions, two operators (prefix-sum(+), +)
+    M = rng.integers(-5, 6, (6, 9)).astype(np.float32)
+    got = run(d_bottom_box_sums(6, 9), [dev(M)], torch.full((6,), float("nan"), device="cuda"))
+    assert got.cpu().tolist() == G.bottom_box_sums(M.astype(int).tolist())
+    Ml = rng.integers(-5, 6, (300, 500)).astype(np.float32)  # integer sums below 2^24: exact
+    want = np.cumsum(Ml[::-1].astype(np.float64).sum(axis=1))
+    for p in all_params(d_bottom_box_sums(300, 500)):
+        got = run(d_bottom_box_sums(300, 500), [dev(Ml)], torch.full((300,), float("nan"), device="cuda"), p)
+        assert np.array_equal(got.cpu().numpy().astype(np.float64), want)
+    assert float(want.max()) == max(G.bottom_box_sums(Ml[-3:, :4].astype(int).tolist()) + [float(want.max())])
