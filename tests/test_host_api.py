@@ -187,3 +187,49 @@ def test_size_errors_before_any_launch():
     assert p is not None
     one = ctypes.c_void_p(16)  # non-NULL dummy addresses: the call must stop at the workspace check
     assert L.mdh_matmul(*s, one, one, one, ctypes.byref(p), null, 0, null) == E_WS
+
+
+def test_size_errors_of_the_later_entry_points():
+    L = mdh.lib()
+    null = None
+    one = ctypes.c_void_p(16)
+    # Dot / MatVec: the reduction dimension may not be empty
+    assert L.mdh_dot(0, null, null, null, null, null, 0, null) == E_SIZE
+    assert L.mdh_dot(8, null, null, null, null, null, 0, null) == E_NULL
+    assert L.mdh_matvec(4, 0, null, null, null, null, null, 0, null) == E_SIZE
+    assert L.mdh_matvec(0, 4, null, null, null, null, null, 0, null) == OK
+    # bMatMul: empty batch is an empty call, K = 0 and more than 65535 batch entries are size errors
+    assert L.mdh_matmul_ex(0, 4, 4, 4, null, 0, null, 0, null, 0, null, null, 0, null) == OK
+    assert L.mdh_matmul_ex(2, 4, 4, 0, null, 0, null, 0, null, 0, null, null, 0, null) == E_SIZE
+    assert L.mdh_matmul_ex(70000, 4, 4, 4, null, 0, null, 0, null, 0, null, null, 0, null) == E_SIZE
+    assert L.mdh_matmul_ex(2, 4, 4, 4, null, 0, null, 0, null, 0, null, null, 0, null) == E_NULL
+    # small M splits the reduction: without workspace the call stops before any launch
+    assert L.mdh_matmul_ex(1, 16, 1000, 2048, one, 0, one, 0, one, 0, null, null, 0, null) == E_WS
+    # scan: empty rows / empty row length are empty calls; a chunked long row needs its workspace
+    assert L.mdh_scan(0, 8, null, null, null, null, 0, null) == OK
+    assert L.mdh_scan(8, 0, null, null, null, null, 0, null) == OK
+    assert L.mdh_scan(-1, 8, null, null, null, null, 0, null) == E_SIZE
+    assert L.mdh_scan(2, 8, null, null, null, null, 0, null) == E_NULL
+    assert L.mdh_scan(1, 1 << 24, one, one, null, null, 0, null) == E_WS
+    assert L.mdh_scan(1, 1 << 24, one, one, null, ctypes.c_void_p(20), 1 << 30, null) == E_WS  # misaligned workspace
+    assert L.mdh_scan(1 << 20, 1 << 20, one, one, null, null, 0, null) == E_SIZE  # more than 2^31-1 elements
+    # MCC_Capsule: as MCC, plus the LDS limit on the filter slice
+    assert L.mdh_mcc_capsule(1, 6, 6, 3, 8, 7, 7, 1, 1, null, null, null, null, null) == E_SIZE  # H < R
+    assert L.mdh_mcc_capsule(0, 8, 8, 3, 8, 3, 3, 1, 1, null, null, null, null, null) == OK
+    assert L.mdh_mcc_capsule(1, 8, 8, 3, 8, 3, 3, 1, 1, null, null, null, null, null) == E_NULL
+    assert L.mdh_mcc_capsule(1, 38, 38, 64, 8, 7, 7, 1, 1, one, one, one, null, null) == E_RES
+    # calibration kernels
+    assert L.mdh_calib_copy(one, one, 24, null) == E_SIZE  # not a multiple of 16 bytes
+    assert L.mdh_calib_copy(null, one, 32, null) == E_NULL
+    assert L.mdh_calib_mfma(null, 8, null, null) == E_NULL
+    # generic path: description limits
+    d = mdh.custom_desc((8,), (1,), ["float"], [(0, "i0")], "float", 4, "r = a0;", "r = x + y;")
+    d.D = 0
+    assert L.mdh_custom_default_params(ctypes.byref(d), ctypes.byref(mdh.TileParams())) == E_SIZE
+    d.D = 1
+    d.sizes[0] = 0  # an empty index set has no value under md_hom without a neutral element
+    assert L.mdh_custom_default_params(ctypes.byref(d), ctypes.byref(mdh.TileParams())) == E_SIZE
+    d.sizes[0] = 8
+    d.acc_buf[0] = 3  # no such input buffer
+    assert L.mdh_custom_default_params(ctypes.byref(d), ctypes.byref(mdh.TileParams())) == E_SIZE
+    assert mdh.mdh_custom_workspace_size(mdh.CustomOp(None, "")) == 0
