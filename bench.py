@@ -55,22 +55,42 @@ TRAFFIC_BYTES = {
 }
 
 
+LAST_SPREAD = {}
+
+
 def _events_ms(torch, fn, steps, warmup):
     """(events ms, wall ms) per step: `steps` launches bracketed by synchronize on both sides;
-    HIP events on the launch stream give the device time, the host clock the whole-job time."""
+    HIP events on the launch stream give the device time, the host clock the whole-job time.
+    Events recorded every steps/10 launches inside the same timed region give the spread of the
+    per-step time (half-width of the 99 % confidence interval of the mean, relative), kept in
+    LAST_SPREAD for the caller."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
+    groups = 10 if steps >= 20 else 1
+    per = steps // groups
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(groups + 1)]
     t0 = time.perf_counter()
-    e0.record()
-    for _ in range(steps):
-        fn()
-    e1.record()
+    marks[0].record()
+    done = 0
+    for g in range(groups):
+        n = per if g < groups - 1 else steps - done
+        for _ in range(n):
+            fn()
+        done += n
+        marks[g + 1].record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    return e0.elapsed_time(e1) / steps, wall_ms / steps
+    LAST_SPREAD.clear()
+    if groups > 1:
+        sizes = [per] * (groups - 1) + [steps - per * (groups - 1)]
+        t = [marks[g].elapsed_time(marks[g + 1]) / sizes[g] for g in range(groups)]
+        mean = sum(t) / groups
+        var = sum((x - mean) ** 2 for x in t) / (groups - 1)
+        # Student t, 9 degrees of freedom, 99 % two-sided: 3.25
+        LAST_SPREAD.update({"groups": groups, "ci99_rel": 3.25 * (var / groups) ** 0.5 / mean,
+                            "min_ms": min(t), "max_ms": max(t)})
+    return marks[0].elapsed_time(marks[groups]) / steps, wall_ms / steps
 
 
 def _ws(torch, mdh, inst, sizes):
@@ -528,6 +548,7 @@ def main() -> int:
 
     torch.cuda.synchronize()
     head = BENCHES[args.workload](torch, mdh, W, args.workload, args.steps, args.warmup, not args.no_cpu)
+    head["spread"] = dict(LAST_SPREAD)
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
 
@@ -558,11 +579,13 @@ def main() -> int:
                 continue
             steps = max(5, min(args.steps, 30 if name in ("mcc_resnet", "prl_2p16_2p18", "mcc_capsule_resnet50_first") else 100))
             inst[name] = fn(torch, mdh, W, name, steps, max(2, min(args.warmup, 5)), not args.no_cpu)
+            inst[name]["spread"] = dict(LAST_SPREAD)
             torch.cuda.synchronize()
             torch.cuda.empty_cache()
         # the tall-skinny MatMul again with the reduction dimension split over workgroups
         # (partial results in a device-memory workspace + second-pass combine)
         inst["matmul_ts_split_k4"] = bench_matmul(torch, mdh, W, "matmul_ts", 100, 5, False, split=4)
+        inst["matmul_ts_split_k4"]["spread"] = dict(LAST_SPREAD)
         torch.cuda.synchronize()
         torch.cuda.empty_cache()
         line["instances"] = inst
