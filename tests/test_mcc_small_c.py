@@ -106,3 +106,25 @@ def test_paper_shapes_sampled(net, N):
     ref, refabs = oracle.mcc_at(x, f, pos, cfg.stride)
     err = np.abs(got[tuple(pos.T)] - ref) / refabs
     assert float(err.max()) <= TOL
+
+
+@pytest.mark.gpu
+def test_conv2d_is_the_single_channel_special_case():
+    # Conv2D = md_hom(*, (++,++,+,+)) over (p,q,r,s): MCC with N = K = C = 1 (the classical variant the
+    # paper contrasts MCC with); checked through mdh_mcc and through the generic runtime-compiled path
+    Hh, Wd, R, S = 45, 70, 5, 3
+    x, f = W.mcc_inputs(W.MccCfg(1, Hh, Wd, 1, 1, R, S, (1, 1), W.SEED_BASE + 73))
+    ref, refabs = oracle.mcc(x, f, (1, 1), with_abs=True)
+    got = run(x, f, (1, 1), None)
+    assert float(np.max(np.abs(got - ref) / refabs)) <= TOL
+    P, Q = Hh - R + 1, Wd - S + 1
+    d = mdh.custom_desc((P, Q, R, S), (0, 0, 1, 1), ["float", "float"],
+                        [(0, "(i0+i2)*%d+(i1+i3)" % Wd), (1, "i2*N3+i3")], "float", 4, "r = a0 * a1;", "r = x + y;", fast_dim=1)
+    op = mdh.mdh_custom_create(d)
+    out = torch.full((P, Q), float("nan"), dtype=torch.float32, device="cuda")
+    n = mdh.mdh_custom_workspace_size(op)
+    ws = torch.empty(max(n, 4), dtype=torch.uint8, device="cuda") if n else None
+    mdh.mdh_custom_run(op, [dev(x), dev(f)], out, ws)
+    torch.cuda.synchronize()
+    g2 = out.cpu().numpy().astype(np.float64)
+    assert float(np.max(np.abs(g2 - ref[0, :, :, 0]) / refabs[0, :, :, 0])) <= TOL
