@@ -154,6 +154,39 @@ __global__ __launch_bounds__(WAVES * 64) void scan_apply_kernel(const float* __r
   }
 }
 
+// Short rows: one wavefront per row, 4 rows per workgroup, no LDS and no barrier; the row is walked
+// in tiles of 256 elements with the carry in a register.
+__global__ __launch_bounds__(256) void scan_rows_wave_kernel(const float* __restrict__ in,
+                                                             float* __restrict__ out, int64_t R,
+                                                             int64_t n, int TPC) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= R) return;  // whole wavefront; the kernel has no barrier
+  const float* src = in + row * n;
+  float* dst = out + row * n;
+  double carry = 0.0;
+  f4 nxt = load4(src, (int64_t)lane * 4, n);
+  for (int t = 0; t < TPC; ++t) {
+    const int64_t j = ((int64_t)t * 64 + lane) * 4;
+    f4 v = nxt;
+    if (t + 1 < TPC) nxt = load4(src, j + 256, n);
+    v[1] += v[0];
+    v[2] += v[1];
+    v[3] += v[2];
+    const float incl = wave_scan(v[3], lane);
+    const float all = __shfl(incl, 63, 64);
+    v += (float)(carry + (double)(incl - v[3]));
+    if (j + 3 < n) {
+      __builtin_nontemporal_store(v, (f4u*)(dst + j));
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (j + e < n) dst[j + e] = v[e];
+    }
+    carry += (double)all;
+  }
+}
+
 template <int WAVES>
 mdh_status launch_t(const ScanPlan& pl, int64_t R, int64_t n, const float* in, float* out, void* ws,
                     hipStream_t st) {
@@ -179,6 +212,14 @@ mdh_status launch_t(const ScanPlan& pl, int64_t R, int64_t n, const float* in, f
 
 mdh_status launch_scan(const ScanPlan& pl, int64_t R, int64_t n, const float* in, float* out, void* ws,
                        hipStream_t st) {
+  if (pl.WAVES == 1) {
+    if (pl.C != 1) return MDH_ERR_UNSUPPORTED;
+    const int64_t blocks = cdiv(R, 4);
+    if (blocks > 0x7fffffff) return MDH_ERR_SIZE;
+    clear_stale_error();
+    hipLaunchKernelGGL(scan_rows_wave_kernel, dim3((unsigned)blocks), dim3(256), 0, st, in, out, R, n, pl.TPC);
+    return launch_status();
+  }
   switch (pl.WAVES) {
     case 4: return launch_t<4>(pl, R, n, in, out, ws, st);
     case 8: return launch_t<8>(pl, R, n, in, out, ws, st);
