@@ -470,18 +470,41 @@ std::string generate(const mdh_custom_desc* d, const CustomPlan& pl) {
   o.line("}");
 
   // second pass: fold the workgroup parts of the reduced dimensions in ascending order
+  // Few output points and many parts (e.g. Dot): one workgroup per point, the 256 lanes fold strided
+  // shares of the parts and meet in an LDS tree (fixed order).  Otherwise one lane per point.
+  const bool wide = pl.CCN < 256 && pl.SG > 64;
   o.line("extern \"C\" __global__ __launch_bounds__(256) void mdh_custom_combine(const mdh_T* __restrict__ ws, mdh_T* __restrict__ out) {");
-  o.f("  for (i64 cc_ = (i64)blockIdx.x * 256 + threadIdx.x; cc_ < %lldLL; cc_ += (i64)gridDim.x * 256) {", (long long)pl.CCN);
-  o.line("    mdh_T acc = ws[cc_];");
-  o.f("    for (i64 s_ = 1; s_ < %lldLL; ++s_) acc = mdh_op(acc, ws[s_ * %lldLL + cc_]);", (long long)pl.SG, (long long)pl.CCN);
-  o.line("    i64 c_ = cc_;");
+  if (wide) {
+    o.line("  __shared__ mdh_T sh_val[256];");
+    o.line("  const int tid = (int)threadIdx.x;");
+    o.f("  for (i64 cc_ = blockIdx.x; cc_ < %lldLL; cc_ += gridDim.x) {", (long long)pl.CCN);
+    o.f("    const i64 parts = %lldLL;", (long long)pl.SG);
+    o.line("    mdh_T acc;");
+    o.line("    const bool have = tid < parts;");
+    o.f("    if (have) { acc = ws[(i64)tid * %lldLL + cc_];", (long long)pl.CCN);
+    o.f("      for (i64 s_ = tid + 256; s_ < parts; s_ += 256) acc = mdh_op(acc, ws[s_ * %lldLL + cc_]); }", (long long)pl.CCN);
+    o.line("    if (have) sh_val[tid] = acc;");
+    o.line("    __syncthreads();");
+    o.line("    for (int s_ = 128; s_ > 0; s_ >>= 1) {");
+    o.line("      if (tid < s_ && tid + s_ < parts) { acc = mdh_op(acc, sh_val[tid + s_]); sh_val[tid] = acc; }");
+    o.line("      __syncthreads();");
+    o.line("    }");
+    o.line("    if (tid == 0) {");
+  } else {
+    o.f("  for (i64 cc_ = (i64)blockIdx.x * 256 + threadIdx.x; cc_ < %lldLL; cc_ += (i64)gridDim.x * 256) {", (long long)pl.CCN);
+    o.line("    mdh_T acc = ws[cc_];");
+    o.f("    for (i64 s_ = 1; s_ < %lldLL; ++s_) acc = mdh_op(acc, ws[s_ * %lldLL + cc_]);", (long long)pl.SG, (long long)pl.CCN);
+    o.line("    {");
+  }
+  o.line("      i64 c_ = cc_;");
   for (int i = D - 1; i >= 0; --i) {
     if (pl.red[i])
-      o.f("    const i64 i%d = 0; (void)i%d;", i, i);
+      o.f("      const i64 i%d = 0; (void)i%d;", i, i);
     else
-      o.f("    const i64 i%d = c_ %% N%d; c_ /= N%d; (void)i%d;", i, i, i, i);
+      o.f("      const i64 i%d = c_ %% N%d; c_ /= N%d; (void)i%d;", i, i, i, i);
   }
-  o.line(std::string("    out[") + (d->out_index ? d->out_index : "cc_") + "] = acc;");
+  o.line(std::string("      out[") + (d->out_index ? d->out_index : "cc_") + "] = acc;");
+  o.line("    }");
   o.line("  }");
   o.line("}");
   return o.s;
@@ -627,7 +650,7 @@ mdh_status mdh_custom_run(mdh_custom_op* op, const void* const* inputs, void* ou
   }
   if (pl.SG > 1) {
     void* cargs[2] = {(void*)&workspace, (void*)&output};
-    int64_t blocks = cdiv(pl.CCN, 256);
+    int64_t blocks = (pl.CCN < 256 && pl.SG > 64) ? pl.CCN : cdiv(pl.CCN, 256);  // as in the generator
     if (blocks > 4096) blocks = 4096;
     if (hipModuleLaunchKernel(op->fcombine, (unsigned)blocks, 1, 1, 256, 1, 1, 0, (hipStream_t)stream, cargs, nullptr) != hipSuccess) {
       launch_status();
