@@ -453,6 +453,39 @@ def bench_histo_generic(torch, mdh, W, name, steps, warmup, cpu):
     return res
 
 
+def bench_prl_generic(torch, mdh, W, name, steps, warmup, cpu):
+    """The custom reduce again, this time through the generic path: record and result types, wght and
+    max_idx given as source and compiled at run time (same inputs and sizes as prl_2p16_2p18)."""
+    cfg = W.CONFIGS["prl_2p16_2p18"]
+    alph = W.prl_alphabets(cfg.nF)
+    A = torch.stack([W.device_integers(cfg.seed, 1 + 2 * f, (cfg.nA,), 0, a - 1) for f, a in enumerate(alph)], 1).contiguous()
+    B = torch.stack([W.device_integers(cfg.seed, 2 + 2 * f, (cfg.nB,), 0, a - 1) for f, a in enumerate(alph)], 1).contiguous()
+    wp = W.device_integers(cfg.seed, 40, (cfg.nF,), 1, W.PRL_WEIGHT_MAX)
+    wm = W.device_integers(cfg.seed, 41, (cfg.nF,), -W.PRL_WEIGHT_MAX, 0)
+    out = torch.empty((cfg.nA, 2), dtype=torch.int32, device="cuda")
+    pre = "struct rec { int f[8]; }; struct res { int score; int idx; };"
+    fsrc = ("int s = 0; for (int k = 0; k < 8; ++k) s += a0.f[k] == a1.f[k] ? a2.f[k] : a3.f[k];"
+            " r.score = s; r.idx = (int)i1;")
+    osrc = "if (x.score > y.score || (x.score == y.score && x.idx < y.idx)) r = x; else r = y;"
+    desc = mdh.custom_desc((cfg.nA, cfg.nB), (0, 1), ["rec"] * 4, [(0, "i0"), (1, "i1"), (2, "0"), (3, "0")], "res", 8,
+                           fsrc, osrc, pre, fast_dim=0)
+    op = mdh.mdh_custom_create(desc)
+    n = mdh.mdh_custom_workspace_size(op)
+    ws = torch.empty(max(n, 4), dtype=torch.uint8, device="cuda") if n else None
+    ms, wall = _events_ms(torch, lambda: mdh.mdh_custom_run(op, [A, B, wp, wm], out, ws), steps, warmup)
+    pairs = float(cfg.nA) * cfg.nB
+    tops = pairs * PRL_LANE_OPS_PER_PAIR / ms / 1e9  # priced with the hand-written kernel's instruction count
+    res = {
+        "value": pairs / wall / 1e6, "unit": "Gpairs/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "i32",
+        "kernel": "mdh_custom_main + mdh_custom_combine (hipRTC)",
+        "roofline": {"bound": "alu", "achieved": tops, "peak": PEAK_INT_VALU_TOPS, "unit": "Tlane-op/s",
+                     "frac": tops / PEAK_INT_VALU_TOPS, "traffic": None},
+        "lane_ops_per_pair": PRL_LANE_OPS_PER_PAIR,
+    }
+    mdh.mdh_custom_destroy(op)
+    return res
+
+
 def calibration(torch, mdh):
     """Attainable rates of this chip on the resources that bound the instances, from the library's
     calibration kernels (HIP events on the launch stream, 20 launches each)."""
@@ -505,6 +538,7 @@ BENCHES = {
     "scan_2p28": bench_scan,
     "scan_rows_65536x4096": bench_scan,
     "histo_generic_256x2p24": bench_histo_generic,
+    "prl_generic_2p16_2p18": bench_prl_generic,
 }
 
 
@@ -577,7 +611,7 @@ def main() -> int:
         for name, fn in BENCHES.items():
             if name == args.workload:
                 continue
-            steps = max(5, min(args.steps, 30 if name in ("mcc_resnet", "prl_2p16_2p18", "mcc_capsule_resnet50_first") else 100))
+            steps = max(5, min(args.steps, 30 if name in ("mcc_resnet", "prl_2p16_2p18", "mcc_capsule_resnet50_first", "prl_generic_2p16_2p18") else 100))
             inst[name] = fn(torch, mdh, W, name, steps, max(2, min(args.warmup, 5)), not args.no_cpu)
             inst[name]["spread"] = dict(LAST_SPREAD)
             torch.cuda.synchronize()

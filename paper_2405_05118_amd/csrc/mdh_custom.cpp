@@ -410,12 +410,16 @@ std::string generate(const mdh_custom_desc* d, const CustomPlan& pl) {
       red_ok += buf;
     }
   {
+    // the accessed elements are copied to registers first: f then works on values, and a
+    // conditional between two of them is a register select, not a load through a selected address
     std::string call;
+    o.line(ind2 + "if (" + red_ok + ") {");
     for (int a = 0; a < d->n_acc; ++a) {
-      call += "in" + std::to_string(d->acc_buf[a]) + "[" + d->acc_index[a] + "], ";
+      const std::string b = std::to_string(d->acc_buf[a]), n = std::to_string(a);
+      o.line(ind2 + "  const mdh_in" + b + "_t e" + n + "_ = in" + b + "[" + d->acc_index[a] + "];");
+      call += "e" + n + "_, ";
     }
     for (int i = 0; i < D; ++i) call += (i ? ", i" : "i") + std::to_string(i);
-    o.line(ind2 + "if (" + red_ok + ") {");
     o.line(ind2 + "  const mdh_T v = mdh_f(" + call + ");");
     o.f("%s  if (have) acc = mdh_op(acc, v); else { acc = v; have = true; }", ind2.c_str());
     o.f("%s}", ind2.c_str());
