@@ -6,10 +6,13 @@
 // counts and the lane layout are compile-time constants of the generated code, the user's f, op,
 // index functions and types are pasted in, and hipRTC compiles it for gfx950.
 //
-// Per dimension d: index = (q*WG_d + g)*L_d + l  (strided)  or  (g*Q_d + q)*L_d + l  (blocked),
-// g = workgroup part, l = lane part, q = sequential part.  A lane walks its sequential parts of the
-// concatenation dimensions (outer loops) and, for each such point, its sequential parts of the
-// reduced dimensions (inner loops), combining in a register.  The lanes that share a point combine
+// Per dimension d: index = ((q*WG_d + g)*L_d + l)*V_d + v  (strided)  or  ((g*Q_d + q)*L_d + l)*V_d + v
+// (blocked), g = workgroup part, l = lane part, q = sequential part on the device-memory layer, v =
+// part on the register layer (concatenation dimensions only).  A lane walks its sequential parts of
+// the concatenation dimensions (outer loops) and, for each, its sequential parts of the reduced
+// dimensions (inner loops); innermost, unrolled, are the V = prod V_d register parts: V results are
+// combined in registers at once, and an input element whose index function does not depend on a
+// register-blocked dimension is loaded once for all of its parts (register tiling).  The lanes that share a point combine
 // in an LDS tree, workgroups that share it write to the workspace and a second kernel folds the
 // parts in ascending order.  No neutral element: a part starts with its first value, and a flag
 // says whether a lane has one.
@@ -35,11 +38,13 @@ struct CustomPlan {
   int64_t N[MDH_MAX_D];
   int red[MDH_MAX_D];
   int64_t WG[MDH_MAX_D], L[MDH_MAX_D], Q[MDH_MAX_D];
+  int64_t V[MDH_MAX_D];  // register-layer parts (concatenation dimensions; 1 elsewhere)
   int scan;  // the prefix-sum dimension (at most one), -1: none
   int strided;
   int fast;  // dimension with the fastest lane index
   int ragged;
   // derived
+  int VT;          // register parts per lane (product of V)
   int NT;          // lanes per workgroup
   int RL, CL;      // lanes over reduced / concatenation dimensions
   int64_t SG, CG;  // workgroup parts over reduced / concatenation dimensions
@@ -81,9 +86,10 @@ mdh_status desc_ptrs(const mdh_custom_desc* d) {
 }
 
 void derive(CustomPlan* p) {
-  p->NT = 1, p->RL = 1, p->CL = 1, p->SG = 1, p->CG = 1, p->CCN = 1;
+  p->NT = 1, p->RL = 1, p->CL = 1, p->SG = 1, p->CG = 1, p->CCN = 1, p->VT = 1;
   for (int d = 0; d < p->D; ++d) {
     p->NT *= (int)p->L[d];
+    p->VT *= (int)p->V[d];
     if (p->red[d]) {
       p->RL *= (int)p->L[d];
       p->SG *= p->WG[d];
@@ -102,6 +108,7 @@ void params_from_custom(const CustomPlan& pl, mdh_tile_params* p) {
     p->prt[MDH_L_WG][d] = (int32_t)pl.WG[d];
     p->prt[MDH_L_LANE][d] = (int32_t)pl.L[d];
     p->prt[MDH_L_HBM][d] = (int32_t)pl.Q[d];
+    p->prt[MDH_L_VGPR][d] = (int32_t)pl.V[d];
     dims[d] = d;
   }
   set_order(p, dims);
@@ -117,7 +124,7 @@ void fill_from_desc(const mdh_custom_desc* d, CustomPlan* pl) {
   for (int i = 0; i < d->D; ++i) {
     pl->N[i] = d->sizes[i];
     pl->red[i] = d->reduce[i] == 1 ? 1 : 0;
-    pl->WG[i] = pl->L[i] = pl->Q[i] = 1;
+    pl->WG[i] = pl->L[i] = pl->Q[i] = pl->V[i] = 1;
   }
   pl->scan = -1;
   for (int i = 0; i < d->D; ++i)
@@ -130,6 +137,25 @@ void fill_from_desc(const mdh_custom_desc* d, CustomPlan* pl) {
   pl->strided = 1;
 }
 
+// Does the C expression `e` use the identifier `id` (e.g. "i2")?
+bool uses_identifier(const char* e, const char* id) {
+  const size_t n = strlen(id);
+  auto word = [](char c) { return (c >= '0' && c <= '9') || (c >= 'a' && c <= 'z') || (c >= 'A' && c <= 'Z') || c == '_'; };
+  for (const char* p = strstr(e, id); p; p = strstr(p + 1, id))
+    if ((p == e || !word(p[-1])) && !word(p[n])) return true;
+  return false;
+}
+
+// A concatenation dimension is worth blocking in registers if some input access does not depend on
+// it: that element is then loaded once for all register parts of the dimension.
+bool reused_across(const mdh_custom_desc* d, int dim) {
+  char id[8];
+  snprintf(id, sizeof id, "i%d", dim);
+  for (int a = 0; a < d->n_acc; ++a)
+    if (!uses_identifier(d->acc_index[a], id)) return true;
+  return false;
+}
+
 int pow2_floor(int64_t x) {
   int p = 1;
   while ((int64_t)p * 2 <= x) p *= 2;
@@ -139,7 +165,7 @@ int pow2_floor(int64_t x) {
 // lanes: `nt` lanes, first along the fast dimension, the rest along the largest other dimension
 // (concatenation dimensions preferred); workgroup parts: all of the concatenation dimensions, and
 // the reduced dimensions `split` ways in total while every part keeps at least 8 sequential steps.
-CustomPlan make_plan(const mdh_custom_desc* d, int nt, int64_t split) {
+CustomPlan make_plan(const mdh_custom_desc* d, int nt, int64_t split, int vreg = 1) {
   CustomPlan pl;
   fill_from_desc(d, &pl);
   int left = nt;
@@ -158,8 +184,18 @@ CustomPlan make_plan(const mdh_custom_desc* d, int nt, int64_t split) {
     pl.L[best] *= 2;
     left /= 2;
   }
+  // register parts: `vreg` per reusable concatenation dimension, at most 16 results per lane
+  if (vreg > 1 && pl.scan < 0) {
+    int vt = 1;
+    for (int i = pl.D - 1; i >= 0; --i) {
+      if (pl.red[i] || !d->acc_index[0] || !reused_across(d, i)) continue;
+      if (pl.N[i] < 2 * pl.L[i] * vreg || vt * vreg > 16) continue;
+      pl.V[i] = vreg;
+      vt *= vreg;
+    }
+  }
   for (int i = 0; i < pl.D; ++i)
-    if (!pl.red[i] && i != pl.scan) pl.WG[i] = cdiv(pl.N[i], pl.L[i]);
+    if (!pl.red[i] && i != pl.scan) pl.WG[i] = cdiv(pl.N[i], pl.L[i] * pl.V[i]);
   // sequential parts of the concatenation dimensions only when the grid would not fit
   for (int i = 0; i < pl.D; ++i) {
     if (pl.red[i]) continue;
@@ -172,17 +208,17 @@ CustomPlan make_plan(const mdh_custom_desc* d, int nt, int64_t split) {
   }
   for (int i = 0; i < pl.D && split > 1; ++i) {
     if (!pl.red[i]) continue;
-    while (split > 1 && cdiv(pl.N[i], pl.L[i] * pl.WG[i] * 2) >= 8) {
+    while (split > 1 && cdiv(pl.N[i], pl.L[i] * pl.WG[i] * 2) >= 8) {  // reduced dimensions: V = 1
       pl.WG[i] *= 2;
       split /= 2;
     }
   }
   pl.ragged = 0;
   for (int i = 0; i < pl.D; ++i) {
-    pl.Q[i] = cdiv(pl.N[i], pl.WG[i] * pl.L[i]);
+    pl.Q[i] = cdiv(pl.N[i], pl.WG[i] * pl.L[i] * pl.V[i]);
     // no empty workgroup part: shrink WG to the parts that own at least one index
-    pl.WG[i] = cdiv(pl.N[i], pl.Q[i] * pl.L[i]);
-    if (pl.WG[i] * pl.L[i] * pl.Q[i] != pl.N[i]) pl.ragged = 1;
+    pl.WG[i] = cdiv(pl.N[i], pl.Q[i] * pl.L[i] * pl.V[i]);
+    if (pl.WG[i] * pl.L[i] * pl.Q[i] * pl.V[i] != pl.N[i]) pl.ragged = 1;
   }
   // with a blocked walk every workgroup part starts at g*Q*L; strided parts start at g*L: both
   // are non-empty now.  Blocked is the safe choice when Q*L*WG overshoots N by more than one part.
@@ -192,13 +228,20 @@ CustomPlan make_plan(const mdh_custom_desc* d, int nt, int64_t split) {
 }
 
 CustomPlan default_plan(const mdh_custom_desc* d) {
-  CustomPlan pl = make_plan(d, 256, 1);
+  // 4 register parts per reusable concatenation dimension, unless the grid gets too small for it;
   // few workgroups: split the reduced dimensions over workgroups up to ~2048 workgroups
-  int64_t grid = pl.SG * pl.CG;
-  if (grid < 1024) {
-    int64_t split = 1;
-    while (grid * split < 2048) split *= 2;
-    pl = make_plan(d, 256, split);
+  // (results wider than 4 bytes -- user-defined structs -- are not blocked by default: measured
+  // slower on the record-linkage example; such configurations are among the candidates)
+  CustomPlan pl;
+  for (int vreg : {d->out_elem_bytes <= 4 ? 4 : 1, 1}) {
+    pl = make_plan(d, 256, 1, vreg);
+    const int64_t grid = pl.SG * pl.CG;
+    if (grid < 1024) {
+      int64_t split = 1;
+      while (grid * split < 2048) split *= 2;
+      pl = make_plan(d, 256, split, vreg);
+    }
+    if (pl.SG * pl.CG >= 512) break;
   }
   return pl;
 }
@@ -210,7 +253,7 @@ int candidates(const mdh_custom_desc* d, CustomPlan* out, int cap) {
     for (int i = 0; i < n; ++i) {
       bool same = out[i].strided == c.strided;
       for (int k = 0; k < c.D && same; ++k)
-        same = out[i].WG[k] == c.WG[k] && out[i].L[k] == c.L[k] && out[i].Q[k] == c.Q[k];
+        same = out[i].WG[k] == c.WG[k] && out[i].L[k] == c.L[k] && out[i].Q[k] == c.Q[k] && out[i].V[k] == c.V[k];
       if (same) return;
     }
     out[n++] = c;
@@ -225,6 +268,13 @@ int candidates(const mdh_custom_desc* d, CustomPlan* out, int cap) {
       if (s > 1 && !any_red) continue;
       push(make_plan(d, nt, s));
     }
+  static const int vregs[] = {2, 4, 8};
+  for (int v : vregs)
+    for (int nt : {256, 64})
+      for (int64_t s : {(int64_t)1, (int64_t)16, (int64_t)256}) {
+        if (s > 1 && !any_red) continue;
+        push(make_plan(d, nt, s, v));
+      }
   return n;
 }
 
@@ -244,8 +294,13 @@ mdh_status plan_from_params(const mdh_custom_desc* d, const mdh_tile_params* p, 
     pl.WG[i] = p->prt[MDH_L_WG][i];
     pl.L[i] = p->prt[MDH_L_LANE][i];
     pl.Q[i] = p->prt[MDH_L_HBM][i];
+    pl.V[i] = p->prt[MDH_L_VGPR][i];
+    // register parts only on concatenation dimensions (a lane's parts of a reduced dimension are
+    // the sequential parts)
+    if (pl.V[i] > 1 && (pl.red[i] || pl.scan >= 0)) return MDH_ERR_UNSUPPORTED;
     // a workgroup part of any dimension that owns no index would leave its partial result unset
-    const int64_t first_of_last = p->strided ? (pl.WG[i] - 1) * pl.L[i] : (pl.WG[i] - 1) * pl.Q[i] * pl.L[i];
+    const int64_t first_of_last =
+        (p->strided ? (pl.WG[i] - 1) * pl.L[i] : (pl.WG[i] - 1) * pl.Q[i] * pl.L[i]) * pl.V[i];
     if (first_of_last >= pl.N[i]) return MDH_ERR_TILE_NOT_DIVIDING;
   }
   if (p->lane_fast_dim >= d->D) return MDH_ERR_UNSUPPORTED;
@@ -265,6 +320,7 @@ mdh_status plan_from_params(const mdh_custom_desc* d, const mdh_tile_params* p, 
 
 mdh_status plan_resources(const mdh_custom_desc* d, const CustomPlan& pl) {
   if (pl.NT > kMaxLanes) return MDH_ERR_TILE_RESOURCES;
+  if ((int64_t)pl.VT * d->out_elem_bytes > 1024) return MDH_ERR_TILE_RESOURCES;  // results held in registers
   if (pl.RL > 1 && (int64_t)pl.NT * (d->out_elem_bytes + 1) > kLdsBytes) return MDH_ERR_TILE_RESOURCES;
   if (pl.SG * pl.CG > 0x7fffffff) return MDH_ERR_SIZE;
   return MDH_OK;
@@ -287,9 +343,11 @@ struct Src {
 std::string index_expr(const CustomPlan& pl, int d) {
   char buf[160];
   if (pl.strided)
-    snprintf(buf, sizeof buf, "((i64)q%d * %lldLL + g%d) * %lldLL + l%d", d, (long long)pl.WG[d], d, (long long)pl.L[d], d);
+    snprintf(buf, sizeof buf, "(((i64)q%d * %lldLL + g%d) * %lldLL + l%d) * %lldLL", d, (long long)pl.WG[d], d,
+             (long long)pl.L[d], d, (long long)pl.V[d]);
   else
-    snprintf(buf, sizeof buf, "((i64)g%d * %lldLL + q%d) * %lldLL + l%d", d, (long long)pl.Q[d], d, (long long)pl.L[d], d);
+    snprintf(buf, sizeof buf, "(((i64)g%d * %lldLL + q%d) * %lldLL + l%d) * %lldLL", d, (long long)pl.Q[d], d,
+             (long long)pl.L[d], d, (long long)pl.V[d]);
   return buf;
 }
 
@@ -378,7 +436,6 @@ std::string generate(const mdh_custom_desc* d, const CustomPlan& pl) {
   // concatenation dimensions: outer sequential loops; the prefix-sum dimension (which keeps its
   // index set like a concatenation dimension) innermost of them, with a running value across it
   std::string ind = "  ";
-  std::string cc_ok = "true";
   std::vector<int> outer;
   for (int i = 0; i < D; ++i)
     if (!pl.red[i] && i != pl.scan) outer.push_back(i);
@@ -390,82 +447,151 @@ std::string generate(const mdh_custom_desc* d, const CustomPlan& pl) {
     }
     o.f("%sfor (int q%d = 0; q%d < %lld; ++q%d) {", ind.c_str(), i, i, (long long)pl.Q[i], i);
     ind += "  ";
-    o.f("%sconst i64 i%d = %s;", ind.c_str(), i, index_expr(pl, i).c_str());
-    char buf[48];
-    snprintf(buf, sizeof buf, " && i%d < N%d", i, i);
-    cc_ok += buf;
+    o.f("%sconst i64 b%d = %s;", ind.c_str(), i, index_expr(pl, i).c_str());
   }
-  o.line(ind + "const bool cc_ok = " + cc_ok + ";");
-  o.f("%smdh_T acc;", ind.c_str());
-  o.f("%sbool have = false;", ind.c_str());
-  std::string ind2 = ind;
-  std::string red_ok = "cc_ok";
-  for (int i = 0; i < D; ++i)
-    if (pl.red[i]) {
-      o.f("%sfor (int q%d = 0; q%d < %lld; ++q%d) {", ind2.c_str(), i, i, (long long)pl.Q[i], i);
-      ind2 += "  ";
-      o.f("%sconst i64 i%d = %s;", ind2.c_str(), i, index_expr(pl, i).c_str());
-      char buf[48];
-      snprintf(buf, sizeof buf, " && i%d < N%d", i, i);
-      red_ok += buf;
+  // the V register parts of the concatenation dimensions: unrolled loops v<d>, flat index vf.
+  // In the scalar phase the indices are clamped to the index space (a ragged edge then computes a
+  // duplicate that is never stored), so that validity does not enter the inner loops.
+  auto open_v = [&](std::string& in, bool clamp) {
+    std::string vf = "0", ok = "true";
+    for (int i : outer) {
+      o.f("%s_Pragma(\"unroll\") for (int v%d = 0; v%d < %lld; ++v%d) {", in.c_str(), i, i, (long long)pl.V[i], i);
+      in += "  ";
+      if (clamp)
+        o.f("%sconst i64 i%d = b%d + v%d < N%d ? b%d + v%d : N%d - 1;", in.c_str(), i, i, i, i, i, i, i);
+      else
+        o.f("%sconst i64 i%d = b%d + v%d;", in.c_str(), i, i, i);
+      vf = "(" + vf + ") * " + std::to_string(pl.V[i]) + " + v" + std::to_string(i);
+      ok += " && i" + std::to_string(i) + " < N" + std::to_string(i);
     }
-  {
+    o.line(in + "const int vf = " + vf + ";");
+    if (!clamp) o.line(in + "const bool cc_ok = " + ok + "; (void)cc_ok;");
+    o.line(in + "(void)vf;");
+  };
+  auto close_v = [&](std::string& in) {
+    for (size_t i = 0; i < outer.size(); ++i) {
+      in.resize(in.size() - 2);
+      o.f("%s}", in.c_str());
+    }
+  };
+  // one evaluation of f for every register part; `first`: the part may still be empty (had == false)
+  auto emit_body = [&](std::string in, bool first) {
+    open_v(in, true);
     // the accessed elements are copied to registers first: f then works on values, and a
     // conditional between two of them is a register select, not a load through a selected address
     std::string call;
-    o.line(ind2 + "if (" + red_ok + ") {");
     for (int a = 0; a < d->n_acc; ++a) {
       const std::string b = std::to_string(d->acc_buf[a]), n = std::to_string(a);
-      o.line(ind2 + "  const mdh_in" + b + "_t e" + n + "_ = in" + b + "[" + d->acc_index[a] + "];");
+      o.line(in + "const mdh_in" + b + "_t e" + n + "_ = in" + b + "[" + d->acc_index[a] + "];");
       call += "e" + n + "_, ";
     }
     for (int i = 0; i < D; ++i) call += (i ? ", i" : "i") + std::to_string(i);
-    o.line(ind2 + "  const mdh_T v = mdh_f(" + call + ");");
-    o.f("%s  if (have) acc = mdh_op(acc, v); else { acc = v; have = true; }", ind2.c_str());
-    o.f("%s}", ind2.c_str());
-  }
+    o.line(in + "const mdh_T v = mdh_f(" + call + ");");
+    if (first)
+      o.line(in + "if (had) acc[vf] = mdh_op(acc[vf], v); else acc[vf] = v;");
+    else
+      o.line(in + "acc[vf] = mdh_op(acc[vf], v);");
+    close_v(in);
+  };
+  o.f("%smdh_T acc[%d];", ind.c_str(), pl.VT);
+  o.f("%sbool have = false;", ind.c_str());
+  std::vector<int> reds;
   for (int i = 0; i < D; ++i)
-    if (pl.red[i]) {
+    if (pl.red[i]) reds.push_back(i);
+  if (reds.empty()) {
+    o.line(ind + "{");
+    o.line(ind + "  const bool had = false;");
+    emit_body(ind + "  ", true);
+    o.line(ind + "  have = true;");
+    o.line(ind + "}");
+  } else {
+    // outer reduced dimensions: plain loops that skip indices beyond the index space
+    std::string ind2 = ind;
+    for (size_t k = 0; k + 1 < reds.size(); ++k) {
+      const int i = reds[k];
+      o.f("%sfor (int q%d = 0; q%d < %lld; ++q%d) {", ind2.c_str(), i, i, (long long)pl.Q[i], i);
+      ind2 += "  ";
+      o.f("%sconst i64 i%d = %s + 0;", ind2.c_str(), i, index_expr(pl, i).c_str());
+      o.f("%sif (i%d >= N%d) continue;", ind2.c_str(), i, i);
+    }
+    // innermost reduced dimension: the first step may start the part (no neutral element); after it
+    // a lane either has a value or has no index at all in this row, so the remaining steps combine
+    // unconditionally; rows that lie completely inside the index space run without bounds checks
+    const int r = reds.back();
+    const long long step = pl.strided ? (long long)(pl.WG[r] * pl.L[r]) : (long long)pl.L[r];
+    o.f("%s{", ind2.c_str());
+    ind2 += "  ";
+    o.f("%sconst int q%d = 0; (void)q%d;", ind2.c_str(), r, r);
+    o.f("%sconst i64 r0_ = %s + 0;", ind2.c_str(), index_expr(pl, r).c_str());
+    o.f("%sif (r0_ < N%d) {", ind2.c_str(), r);
+    o.f("%s  const bool had = have;", ind2.c_str());
+    o.f("%s  const i64 i%d = r0_;", ind2.c_str(), r);
+    emit_body(ind2 + "  ", true);
+    o.f("%s  have = true;", ind2.c_str());
+    o.f("%s}", ind2.c_str());
+    if (pl.Q[r] > 1) {
+      o.f("%sif (r0_ + %lldLL < N%d) {", ind2.c_str(), (long long)(pl.Q[r] - 1) * step, r);
+      o.f("%s  _Pragma(\"unroll 4\") for (int s_ = 1; s_ < %lld; ++s_) {", ind2.c_str(), (long long)pl.Q[r]);
+      o.f("%s    const i64 i%d = r0_ + s_ * %lldLL;", ind2.c_str(), r, step);
+      emit_body(ind2 + "    ", false);
+      o.f("%s  }", ind2.c_str());
+      o.f("%s} else {", ind2.c_str());
+      o.f("%s  for (int s_ = 1; s_ < %lld; ++s_) {", ind2.c_str(), (long long)pl.Q[r]);
+      o.f("%s    const i64 i%d = r0_ + s_ * %lldLL;", ind2.c_str(), r, step);
+      o.f("%s    if (i%d >= N%d) break;", ind2.c_str(), r, r);
+      emit_body(ind2 + "    ", false);
+      o.f("%s  }", ind2.c_str());
+      o.f("%s}", ind2.c_str());
+    }
+    ind2.resize(ind2.size() - 2);
+    o.f("%s}", ind2.c_str());
+    for (size_t k = 0; k + 1 < reds.size(); ++k) {
       ind2.resize(ind2.size() - 2);
       o.f("%s}", ind2.c_str());
     }
-  // lane -> workgroup: LDS tree over the lanes of the reduced dimensions
-  if (pl.RL > 1) {
-    const int step = fast_red ? 1 : pl.CL;  // distance in tid between neighbouring reduced-lane indices
-    int p2 = 1;
-    while (p2 < pl.RL) p2 *= 2;
-    o.f("%ssh_val[tid] = acc; sh_ok[tid] = have ? 1 : 0;", ind.c_str());
-    o.f("%s__syncthreads();", ind.c_str());
-    o.f("%sfor (int s_ = %d; s_ > 0; s_ >>= 1) {", ind.c_str(), p2 / 2);
-    o.f("%s  if (rl < s_ && rl + s_ < %d) {", ind.c_str(), pl.RL);
-    o.f("%s    const int p_ = tid + s_ * %d;", ind.c_str(), step);
-    o.f("%s    if (sh_ok[p_]) { if (have) acc = mdh_op(acc, sh_val[p_]); else { acc = sh_val[p_]; have = true; } }", ind.c_str());
-    o.f("%s    sh_val[tid] = acc; sh_ok[tid] = have ? 1 : 0;", ind.c_str());
-    o.f("%s  }", ind.c_str());
-    o.f("%s  __syncthreads();", ind.c_str());
-    o.f("%s}", ind.c_str());
   }
-  // output view / workspace
+  // re-composition of every register part: lane -> workgroup in an LDS tree over the lanes of the
+  // reduced dimensions, then the output view or the workspace
   {
+    std::string in3 = ind;
+    open_v(in3, false);
+    o.line(in3 + "mdh_T a_ = acc[vf];");
+    o.line(in3 + "bool h_ = have;");
+    if (pl.RL > 1) {
+      const int step = fast_red ? 1 : pl.CL;  // distance in tid between neighbouring reduced-lane indices
+      int p2 = 1;
+      while (p2 < pl.RL) p2 *= 2;
+      o.f("%ssh_val[tid] = a_; sh_ok[tid] = h_ ? 1 : 0;", in3.c_str());
+      o.f("%s__syncthreads();", in3.c_str());
+      o.f("%sfor (int s_ = %d; s_ > 0; s_ >>= 1) {", in3.c_str(), p2 / 2);
+      o.f("%s  if (rl < s_ && rl + s_ < %d) {", in3.c_str(), pl.RL);
+      o.f("%s    const int p_ = tid + s_ * %d;", in3.c_str(), step);
+      o.f("%s    if (sh_ok[p_]) { if (h_) a_ = mdh_op(a_, sh_val[p_]); else { a_ = sh_val[p_]; h_ = true; } }", in3.c_str());
+      o.f("%s    sh_val[tid] = a_; sh_ok[tid] = h_ ? 1 : 0;", in3.c_str());
+      o.f("%s  }", in3.c_str());
+      o.f("%s  __syncthreads();", in3.c_str());
+      o.f("%s}", in3.c_str());
+    }
     std::string ccflat = "0";
     for (int i = 0; i < D; ++i)
       if (!pl.red[i]) ccflat = "(" + ccflat + ") * N" + std::to_string(i) + " + i" + std::to_string(i);
     if (pl.scan >= 0) {
       // prefix-sum: the value of this index is the running combination of everything up to it
-      o.f("%sif (have) { if (have_run) run = mdh_op(run, acc); else { run = acc; have_run = true; } }", ind.c_str());
-      o.f("%sif (rl == 0 && cc_ok && have_run) {", ind.c_str());
+      o.f("%sif (h_) { if (have_run) run = mdh_op(run, a_); else { run = a_; have_run = true; } }", in3.c_str());
+      o.f("%sif (rl == 0 && cc_ok && have_run) {", in3.c_str());
     } else {
-      o.f("%sif (rl == 0 && cc_ok && have) {", ind.c_str());
+      o.f("%sif (rl == 0 && cc_ok && h_) {", in3.c_str());
     }
     for (int i = 0; i < D; ++i)
-      if (pl.red[i]) o.f("%s  const i64 i%d = 0; (void)i%d;", ind.c_str(), i, i);
-    o.line(ind + "  const i64 cc_ = " + ccflat + ";");
-    const char* val = pl.scan >= 0 ? "run" : "acc";
+      if (pl.red[i]) o.f("%s  const i64 i%d = 0; (void)i%d;", in3.c_str(), i, i);
+    o.line(in3 + "  const i64 cc_ = " + ccflat + ";");
+    const char* val = pl.scan >= 0 ? "run" : "a_";
     if (pl.SG > 1)
-      o.f("%s  ws[sg * %lldLL + cc_] = %s;", ind.c_str(), (long long)pl.CCN, val);
+      o.f("%s  ws[sg * %lldLL + cc_] = %s;", in3.c_str(), (long long)pl.CCN, val);
     else
-      o.line(ind + "  out[" + (d->out_index ? d->out_index : "cc_") + "] = " + val + "; (void)cc_;");
-    o.f("%s}", ind.c_str());
+      o.line(in3 + "  out[" + (d->out_index ? d->out_index : "cc_") + "] = " + val + "; (void)cc_;");
+    o.f("%s}", in3.c_str());
+    close_v(in3);
   }
   for (size_t i = 0; i < outer.size(); ++i) {
     ind.resize(ind.size() - 2);

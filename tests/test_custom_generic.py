@@ -94,6 +94,24 @@ def test_planner_tables(desc):
         assert mdh.mdh_custom_validate_params(desc, mdh.mdh_custom_candidate(desc, i)) == 0
 
 
+def test_register_parts_of_concatenation_dimensions():
+    # MatMul: A does not depend on j, B not on i: blocking a concatenation dimension in registers
+    # re-uses the loaded element; the default blocks, candidates cover 1, 2, 4 and 8 parts
+    d = d_matmul(1024, 1024, 1024)
+    p = mdh.mdh_custom_default_params(d)
+    assert max(p.prt[B.L_VGPR][0], p.prt[B.L_VGPR][1]) == 4 and p.prt[B.L_VGPR][2] == 1
+    vs = {max(c.prt[B.L_VGPR][:3]) for c in (mdh.mdh_custom_candidate(d, i) for i in range(mdh.mdh_custom_num_candidates(d)))}
+    assert {1, 2, 4, 8} <= vs
+    src = mdh.mdh_custom_source(mdh.mdh_custom_create(d, p))
+    assert "mdh_T acc[4];" in src
+    # register parts on a reduced dimension are not a configuration of this kernel
+    q = p.copy()
+    q.prt[B.L_VGPR][2], q.prt[B.L_HBM][2] = 2, q.prt[B.L_HBM][2] // 2
+    assert mdh.mdh_custom_validate_params(d, q) == 6
+    # Jacobi1D: every access depends on the only dimension: nothing to re-use, no blocking
+    assert mdh.mdh_custom_default_params(d_jacobi1d(1 << 20, 0.5)).prt[B.L_VGPR][0] == 1
+
+
 def test_planner_rejects_bad_tables():
     desc = d_matvec(512, 4096)
     p = mdh.mdh_custom_default_params(desc)
