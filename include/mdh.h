@@ -387,9 +387,12 @@ mdh_status mdh_candidate(mdh_instance inst, const int64_t* sizes, int32_t idx,
  *                the largest operand (gets the fastest lane index); -1 = D-1
  *
  * De-composition.  Every dimension is cut into #PRT(WG,d) workgroup parts x
- * #PRT(LANE,d) lane parts x #PRT(HBM,d) sequential parts (blk = 1: the paper's full
- * partitioning; no LDS staging of inputs, memory region = device memory).
- * `strided` = 1: index = (q*WG + g)*LANE + l; 0: index = (g*Q + q)*LANE + l.
+ * #PRT(LANE,d) lane parts x #PRT(HBM,d) sequential parts x #PRT(VGPR,d) register
+ * parts (blk = 1: the paper's full partitioning; inputs stay in device memory).
+ * Register parts exist for ++ dimensions only: a lane then holds
+ * prod #PRT(VGPR,d) results at once, and an input element whose index function does
+ * not use a register-blocked dimension is loaded once for all of its parts.
+ * `strided` = 1: index = ((q*WG + g)*LANE + l)*VGPR + v; 0: ((g*Q + q)*LANE + l)*VGPR + v.
  * Re-composition: registers -> LDS tree over the lanes of the reduced dimensions
  * -> workspace + second kernel over their workgroup parts, every level in a fixed
  * order (deterministic).  mdh_custom_default_params / mdh_custom_candidate supply
