@@ -445,6 +445,16 @@ size_t mdh_custom_workspace_size(const mdh_custom_op* op);
 mdh_status mdh_custom_run(mdh_custom_op* op, const void* const* inputs, void* output,
                           void* workspace, size_t workspace_bytes, void* stream);
 void mdh_custom_destroy(mdh_custom_op* op);
+/*
+ * The small search for the generic path: compiles the first `max_candidates`
+ * candidate configurations of `desc` (<= 0: all of them, a second or so each),
+ * runs each `reps` times on the given device buffers (the output is overwritten)
+ * and returns the fastest and its milliseconds per run.  Candidates that need
+ * more workspace than given are skipped.  Synchronises `stream`.
+ */
+mdh_status mdh_custom_tune(const mdh_custom_desc* desc, const void* const* inputs, void* output,
+                           void* workspace, size_t workspace_bytes, void* stream, int32_t reps,
+                           int32_t max_candidates, mdh_tile_params* best, float* best_ms);
 
 /* ------------------------------------------------------------------------- */
 /* Calibration kernels (measurement support; nothing of the method)           */

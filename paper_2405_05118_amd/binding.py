@@ -24,6 +24,7 @@ EXPORTS = (
     "mdh_matmul_ex", "mdh_scan", "mdh_mcc_capsule", "mdh_calib_copy", "mdh_calib_read", "mdh_calib_mfma", "mdh_calib_valu",
     "mdh_custom_default_params", "mdh_custom_validate_params", "mdh_custom_num_candidates", "mdh_custom_candidate",
     "mdh_custom_create", "mdh_custom_source", "mdh_custom_workspace_size", "mdh_custom_run", "mdh_custom_destroy",
+    "mdh_custom_tune",
 )
 MDH_CUSTOM_MAX_IN, MDH_CUSTOM_MAX_ACC = 4, 8
 MDH_CALIB_BLOCKS = 2048
@@ -124,6 +125,7 @@ def lib() -> ctypes.CDLL:
         L.mdh_custom_workspace_size.restype = sz
         L.mdh_custom_workspace_size.argtypes = [vp]
         L.mdh_custom_run.argtypes = [vp, ctypes.POINTER(vp), vp, vp, sz, vp]
+        L.mdh_custom_tune.argtypes = [dp, ctypes.POINTER(vp), vp, vp, sz, vp, i32, i32, pp, ctypes.POINTER(f32)]
         L.mdh_custom_destroy.restype = None
         L.mdh_custom_destroy.argtypes = [vp]
         L.mdh_calib_copy.argtypes = [vp, vp, i64, vp]
@@ -450,6 +452,18 @@ def mdh_custom_run(op: CustomOp, inputs, output, workspace=None):
     st = lib().mdh_custom_run(op.handle, ptrs, ctypes.c_void_p(output.data_ptr()), wp, wb, ctypes.c_void_p(_stream()))
     _check(st, "mdh_custom_run")
     return output
+
+
+def mdh_custom_tune(desc: CustomDesc, inputs, output, workspace=None, reps: int = 3, max_candidates: int = 0):
+    """Compile and time the candidate configurations of desc; returns (best params, ms)."""
+    n = len(inputs)
+    ptrs = (ctypes.c_void_p * n)(*[ctypes.c_void_p(t.data_ptr()) for t in inputs])
+    wp, wb = _ws(workspace)
+    best, ms = TileParams(), ctypes.c_float()
+    st = lib().mdh_custom_tune(ctypes.byref(desc), ptrs, ctypes.c_void_p(output.data_ptr()), wp, wb,
+                               ctypes.c_void_p(_stream()), reps, max_candidates, ctypes.byref(best), ctypes.byref(ms))
+    _check(st, "mdh_custom_tune")
+    return best, ms.value
 
 
 def mdh_custom_destroy(op: CustomOp):

@@ -790,6 +790,56 @@ mdh_status mdh_custom_run(mdh_custom_op* op, const void* const* inputs, void* ou
   return MDH_OK;
 }
 
+mdh_status mdh_custom_tune(const mdh_custom_desc* desc, const void* const* inputs, void* output,
+                           void* workspace, size_t workspace_bytes, void* stream, int32_t reps,
+                           int32_t max_candidates, mdh_tile_params* best, float* best_ms) {
+  if (!desc || !inputs || !output || !best) return MDH_ERR_NULL;
+  if (!desc_ok(desc)) return MDH_ERR_SIZE;
+  if (reps < 1) reps = 3;
+  CustomPlan c[64];
+  int n = candidates(desc, c, 64);
+  if (max_candidates > 0 && n > max_candidates) n = max_candidates;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return MDH_ERR_LAUNCH;
+  float best_t = -1.f;
+  mdh_status last = MDH_ERR_UNSUPPORTED;
+  for (int i = 0; i < n; ++i) {
+    mdh_tile_params p;
+    params_from_custom(c[i], &p);
+    mdh_custom_op* op = nullptr;
+    mdh_status st = mdh_custom_create(desc, &p, &op, nullptr, 0);
+    if (st != MDH_OK) {
+      last = st;
+      continue;
+    }
+    st = mdh_custom_run(op, inputs, output, workspace, workspace_bytes, stream);  // warm-up, loads the code
+    if (st == MDH_OK) {
+      hipEventRecord(e0, (hipStream_t)stream);
+      for (int r = 0; r < reps && st == MDH_OK; ++r)
+        st = mdh_custom_run(op, inputs, output, workspace, workspace_bytes, stream);
+      hipEventRecord(e1, (hipStream_t)stream);
+      if (hipEventSynchronize(e1) != hipSuccess) st = MDH_ERR_LAUNCH;
+    }
+    if (st == MDH_OK) {
+      float ms = 0.f;
+      hipEventElapsedTime(&ms, e0, e1);
+      ms /= reps;
+      if (best_t < 0.f || ms < best_t) {
+        best_t = ms;
+        *best = p;
+      }
+    } else {
+      last = st;  // e.g. a candidate that needs more workspace than was given
+    }
+    mdh_custom_destroy(op);
+  }
+  hipEventDestroy(e0);
+  hipEventDestroy(e1);
+  if (best_t < 0.f) return last;
+  if (best_ms) *best_ms = best_t;
+  return MDH_OK;
+}
+
 void mdh_custom_destroy(mdh_custom_op* op) {
   if (!op) return;
   if (op->module) hipModuleUnload(op->module);

@@ -342,3 +342,16 @@ def test_scan_and_mbbs_through_the_generic_path():
         got = run(d_bottom_box_sums(300, 500), [dev(Ml)], torch.full((300,), float("nan"), device="cuda"), p)
         assert np.array_equal(got.cpu().numpy().astype(np.float64), want)
     assert float(want.max()) == max(G.bottom_box_sums(Ml[-3:, :4].astype(int).tolist()) + [float(want.max())])
+
+
+@pytest.mark.gpu
+def test_custom_tune_returns_a_valid_configuration():
+    d = d_histo(64, 50000)
+    elems = W.integers(W.SEED_BASE + 86, 1, (50000,), 0, 63).astype(np.int32)
+    bins = np.arange(64, dtype=np.int32)
+    out = torch.empty(64, dtype=torch.int32, device="cuda")
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    best, ms = mdh.mdh_custom_tune(d, [dev(elems), dev(bins)], out, ws, reps=2, max_candidates=6)
+    assert ms > 0 and mdh.mdh_custom_validate_params(d, best) == 0
+    got = run(d, [dev(elems), dev(bins)], torch.full((64,), -1, dtype=torch.int32, device="cuda"), best)
+    assert np.array_equal(got.cpu().numpy(), np.bincount(elems, minlength=64))
