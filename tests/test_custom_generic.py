@@ -355,3 +355,35 @@ def test_custom_tune_returns_a_valid_configuration():
     assert ms > 0 and mdh.mdh_custom_validate_params(d, best) == 0
     got = run(d, [dev(elems), dev(bins)], torch.full((64,), -1, dtype=torch.int32, device="cuda"), best)
     assert np.array_equal(got.cpu().numpy(), np.bincount(elems, minlength=64))
+
+
+@pytest.mark.gpu
+def test_high_dimensional_instances_through_the_generic_path():
+    # MCC itself, all seven dimensions (n,p,q,k | c,r,s), strided index functions p*sh+r, q*sw+s
+    N, Hh, Wd, C, K, R, S, sh, sw = 2, 11, 13, 3, 5, 3, 2, 2, 1
+    x, f = W.mcc_inputs(W.MccCfg(N, Hh, Wd, C, K, R, S, (sh, sw), W.SEED_BASE + 87))
+    P, Q = (Hh - R) // sh + 1, (Wd - S) // sw + 1
+    ref, refabs = oracle.mcc(x, f, (sh, sw), with_abs=True)
+    d = mdh.custom_desc((N, P, Q, K, C, R, S), (0, 0, 0, 0, 1, 1, 1), ["float", "float"],
+                        [(0, "((i0*%d + (i1*%d+i5))*%d + (i2*%d+i6))*N4 + i4" % (Hh, sh, Wd, sw)),
+                         (1, "((i3*N5 + i5)*N6 + i6)*N4 + i4")], "float", 4, "r = a0 * a1;", "r = x + y;", fast_dim=3)
+    for p in all_params(d)[:8]:
+        got = run(d, [dev(x), dev(f)], torch.full((N, P, Q, K), float("nan"), device="cuda"), p)
+        assert float(np.max(np.abs(got.cpu().numpy() - ref) / refabs)) <= 1e-4
+    # a tensor contraction with transposed accesses, C[a,b,c] = sum_d A[d,b,a] * B[c,d]
+    # (the kind of view the coupled-cluster examples of the paper use)
+    na, nb, nc, nd = 6, 5, 7, 9
+    rng = np.random.default_rng(12)
+    A = rng.integers(-3, 4, (nd, nb, na)).astype(np.float32)
+    Bm = rng.integers(-3, 4, (nc, nd)).astype(np.float32)
+    want = np.einsum("dba,cd->abc", A.astype(np.float64), Bm.astype(np.float64))
+    d = mdh.custom_desc((na, nb, nc, nd), (0, 0, 0, 1), ["float", "float"],
+                        [(0, "(i3*N1 + i1)*N0 + i0"), (1, "i2*N3 + i3")], "float", 4, "r = a0 * a1;", "r = x + y;")
+    got = run(d, [dev(A), dev(Bm)], torch.full((na, nb, nc), float("nan"), device="cuda"))
+    assert np.array_equal(got.cpu().numpy().astype(np.float64), want)
+    # reduce with two operators at once: one pass, a pair (sum, max) as the result type
+    v = rng.integers(-100, 100, 5000).astype(np.int32)
+    d = mdh.custom_desc((5000,), (1,), ["int"], [(0, "i0")], "pr", 8, "r.s = a0; r.m = a0;",
+                        "r.s = x.s + y.s; r.m = x.m > y.m ? x.m : y.m;", "struct pr { int s; int m; };")
+    got = run(d, [dev(v)], torch.zeros(2, dtype=torch.int32, device="cuda"))
+    assert got.cpu().tolist() == [int(v.sum()), int(v.max())]
