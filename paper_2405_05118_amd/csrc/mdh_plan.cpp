@@ -226,15 +226,23 @@ static int gemm_ragged(const int64_t* s, const GemmPlan& pl) {
 
 static GemmPlan gemm_default(const int64_t* s) {
   const int64_t M = s[0], N = s[1], K = s[2];
+  // Tile: the largest of 128x128, 128x64, 64x64 that still gives two workgroups per compute unit
+  // (measured best at 4096^3, 2048^3 and 1024^3 respectively); narrow problems keep 128x64 / 64x64.
   GemmPlan pl{128, 128, 32, 64, 64, 1, 0};
-  if (N <= 64 || M <= 64) pl = GemmPlan{128, 64, 32, 64, 32, 1, 0};
-  if (M <= 64 && N <= 64) pl = GemmPlan{64, 64, 16, 32, 32, 1, 0};
-  if (M > 64 && N > 64 && M * N <= 512 * 512) pl = GemmPlan{64, 64, 16, 32, 32, 1, 0};
-  // split the reduction dimension over workgroups until every compute unit (256) has two
-  // workgroups; beyond that the extra pass over the partial results costs more than it hides
+  if (N <= 64 || M <= 64) {
+    pl = GemmPlan{128, 64, 32, 64, 32, 1, 0};
+  } else if (cdiv(M, 128) * cdiv(N, 128) < 512) {
+    pl = GemmPlan{128, 64, 32, 64, 32, 1, 0};
+    if (cdiv(M, 128) * cdiv(N, 64) < 512) pl = GemmPlan{64, 64, 32, 32, 32, 1, 0};
+  }
+  if (M <= 64 && N <= 64) pl = GemmPlan{64, 64, 32, 32, 32, 1, 0};
+  // Split the reduction dimension over workgroups only while there is less than one workgroup per
+  // compute unit AND every part keeps at least 8 k-tiles: below that the second pass and the
+  // shortened pipelines cost more than the parallelism gains (256^3 is fastest unsplit, 8.7 us
+  // against 14.6 us with 16 parts; 256 x 256 x 4096 is fastest with 16 parts).
   const int64_t tiles = cdiv(M, pl.BM) * cdiv(N, pl.BN);
   int S = 1;
-  while (tiles * S < 512 && S < 64 && K / (S * 2) >= pl.BK) S *= 2;
+  while (tiles * S < 256 && S < 64 && K / (S * 2) >= 8 * pl.BK) S *= 2;
   pl.S = S;
   pl.ragged = gemm_ragged(s, pl);
   return pl;
