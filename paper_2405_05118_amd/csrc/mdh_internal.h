@@ -32,7 +32,8 @@ struct GemmPlan {
 struct MccPlan {
   int TP, TQ, BN, CK, WM, WN;
   int ragged;
-  int flat;  // 1: few-channel kernel that walks s and c as one fused dimension (TQ = block width)
+  int flat;    // 1: few-channel kernel that walks s and c as one fused dimension (TQ = block width)
+  int QT = 1;  // few-channel kernel: column tiles a workgroup walks with its filter slice resident
 };
 
 // Custom reduce: RA records of A per lane, WB wavefronts of a workgroup split B,

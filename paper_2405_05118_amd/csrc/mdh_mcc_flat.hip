@@ -9,9 +9,11 @@
 // parts is a valid evaluation).  sc is padded to a multiple of 8 with zero filter entries.
 //
 // De-composition, dims (n,p,q,k,c,r,s):
-//   workgroup layer : N x (P/TP) x (Q/QB) x (K/BN)
-//   LDS             : the whole input patch ((TP-1)*sh + R rows of (QB-1)*sw*C + S*C floats) and the
-//                     BN x R x S*C filter slice are staged once per workgroup
+//   workgroup layer : N x (P/TP) x (Q/(QB*QT)) x (K/BN)
+//   HBM layer       : QT tiles of QB columns q walked sequentially by a workgroup: the BN x R x S*C
+//                     filter slice stays in LDS; the input patch ((TP-1)*sh + R rows of
+//                     (QB-1)*sw*C + S*C floats) of the NEXT tile is requested from memory before the
+//                     current one is computed and written to the other of two LDS buffers after it
 //   wavefront layer : WAVES_M along p  x  WAVES_N along k
 //   block           : (32/QB rows of p) x (QB consecutive q) x 32 output channels x 2 of sc
 #include "mdh_internal.h"
@@ -35,7 +37,7 @@ template <int QB, int MI, int NI, int WAVES_M, int WAVES_N>
 __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
     const float* __restrict__ in, const float* __restrict__ filt, float* __restrict__ out, int H,
     int W, int C, int K, int R, int S, int sh, int sw, int P, int Q, int tp_n, int tq_n, int tk_n,
-    int SCP, int PWF, int PFR) {
+    int SCP, int PWF, int PFR, int QT, int pstep_rows, int pstep_x4) {
   using Cf = FlatCfg<QB, MI, NI, WAVES_M, WAVES_N>;
   extern __shared__ __attribute__((aligned(16))) float lds[];
   const int tid = threadIdx.x;
@@ -49,11 +51,11 @@ __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
   const int tq = (b / tk_n) % tq_n;
   const int tp = (b / (tk_n * tq_n)) % tp_n;
   const int n = b / (tk_n * tq_n * tp_n);
-  const int p0 = tp * Cf::TP, q0 = tq * Cf::TQ, k0 = tk * Cf::BN;
+  const int p0 = tp * Cf::TP, k0 = tk * Cf::BN;
   const int SC = S * C, WC = W * C;
   const int PH = (Cf::TP - 1) * sh + R;
   float* fs = lds;                    // filter slice [BN][PFR]: row k holds R groups of SCP floats
-  float* ps = lds + Cf::BN * PFR;     // input patch [PH][PWF]
+  float* ps0 = lds + Cf::BN * PFR;    // input patch [2][PH][PWF]: two buffers
 
   // Staging without integer divisions in the loops: a filter row k is R*SC contiguous floats in
   // memory, so a lane's elements e = lane, lane+64, ... have the same (r, x) for every k and that
@@ -71,15 +73,28 @@ __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
         ge[u] = e;
         off[u] = e < RSC ? r * SCP + (e - r * SC) : -1;
       }
-      for (int k = wave; k < Cf::BN; k += NW) {
-        const bool kin = k0 + k < K;
-        const float* src = filt + (int64_t)(k0 + k) * RSC;
-        float v[4];
+      // all loads of a group of 8 rows are issued before the first LDS write: one round trip to
+      // memory per group instead of one per row
+      constexpr int KI = Cf::BN / NW;  // rows k per wavefront
+      constexpr int KG = KI < 8 ? KI : 8;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = (kin && off[u] >= 0) ? src[ge[u]] : 0.f;
+      for (int kb = 0; kb < KI; kb += KG) {
+        float v[KG][4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-          if (off[u] >= 0) fs[k * PFR + off[u]] = v[u];
+        for (int ki = 0; ki < KG; ++ki) {
+          const int k = wave + (kb + ki) * NW;
+          const bool kin = k0 + k < K;
+          const float* src = filt + (int64_t)(k0 + k) * RSC;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) v[ki][u] = (kin && off[u] >= 0) ? src[ge[u]] : 0.f;
+        }
+#pragma unroll
+        for (int ki = 0; ki < KG; ++ki) {
+          const int k = wave + (kb + ki) * NW;
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            if (off[u] >= 0) fs[k * PFR + off[u]] = v[ki][u];
+        }
       }
     }
     // zero the padding of every filter row (x in [SC, SCP)): it meets patch values in the MFMAs
@@ -89,95 +104,145 @@ __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
       const int k = row / R, r = row - k * R;
       fs[k * PFR + r * SCP + x] = 0.f;
     }
-    // Input patch, 16 bytes at a time (rows are only dword aligned); cells outside the image read
-    // as 0 (they only meet zero filter entries or outputs that are not stored).
-    const int pw4 = PWF >> 2;
-    for (int ph = wave; ph < PH; ph += NW) {
-      const int hy = p0 * sh + ph;
-      const float* src = in + ((int64_t)n * H + hy) * WC + q0 * sw * C;
-      for (int x4 = lane; x4 < pw4; x4 += 64) {
-        const int x = x4 << 2, gx = q0 * sw * C + x;
-        f4 v = {0.f, 0.f, 0.f, 0.f};
-        if (hy < H) {
-          if (gx + 3 < WC) {
-            v = *(const f4u*)(src + x);
-          } else {
+  }
+
+  // Input patch, 16 bytes at a time (rows are only dword aligned); cells outside the image read as
+  // 0 (they only meet zero filter entries or outputs that are not stored).  A lane's pieces
+  // (row ph, offset x) are the same for every tile; only the column origin moves.
+  constexpr int PV = 8;  // 16-byte pieces per lane the prefetch can hold (checked by the launcher)
+  const int pw4 = PWF >> 2;
+  const int npiece = PH * pw4;
+  int poff[PV];   // LDS offset of piece i, -1: none
+  int pgx[PV];    // offset inside the image row, relative to the tile's first column
+  int phy[PV];    // image row
+  {
+    // piece i of a lane is piece tid + i*NT of the patch: one division for i = 0, then steps of
+    // (NT / pw4 rows, NT % pw4 pieces) -- both uniform, passed in by the launcher
+    int ph = tid / pw4, x4 = tid - ph * pw4;
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (gx + e < WC) v[e] = src[x + e];
-          }
-        }
-        *(f4*)(ps + ph * PWF + x) = v;
+    for (int i = 0; i < PV; ++i) {
+      poff[i] = (tid + i * Cf::NT) < npiece ? ph * PWF + (x4 << 2) : -1;
+      pgx[i] = x4 << 2;
+      phy[i] = p0 * sh + ph;
+      ph += pstep_rows;
+      x4 += pstep_x4;
+      if (x4 >= pw4) {
+        x4 -= pw4;
+        ++ph;
       }
     }
   }
-  __syncthreads();
-
-  f16 acc[MI][NI];
+  auto load_patch = [&](int q0, f4 (&v)[PV]) {
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
+    for (int i = 0; i < PV; ++i) {
+      v[i] = (f4){0.f, 0.f, 0.f, 0.f};
+      if (poff[i] >= 0 && phy[i] < H) {
+        const int gx = q0 * sw * C + pgx[i];
+        const float* src = in + ((int64_t)n * H + phy[i]) * WC + gx;
+        if (gx + 3 < WC) {
+          v[i] = *(const f4u*)src;
+        } else {
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
+          for (int e = 0; e < 4; ++e)
+            if (gx + e < WC) v[i][e] = src[e];
+        }
+      }
+    }
+  };
+  auto store_patch = [&](float* ps, const f4 (&v)[PV]) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+    for (int i = 0; i < PV; ++i)
+      if (poff[i] >= 0) *(f4*)(ps + poff[i]) = v[i];
+  };
 
   // the lane's pixel inside a block: dp rows down, dq columns right
   const int dp = l32 / QB, dq = l32 % QB;
-  const float* arow = ps + ((wm * MI * Cf::RB + dp) * sh) * PWF + dq * sw * C + lh * 4;
+  const int aoff = ((wm * MI * Cf::RB + dp) * sh) * PWF + dq * sw * C + lh * 4;
   const float* brow = fs + (wn * NI * 32 + l32) * PFR + lh * 4;
-  for (int r = 0; r < R; ++r) {
-    for (int sc0 = 0; sc0 < SCP; sc0 += 8) {
-      f4 af[MI], bf[NI];
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi) {
-        const float* a = arow + (mi * Cf::RB * sh + r) * PWF + sc0;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) af[mi][t] = a[t];
-      }
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni) bf[ni] = *(const f4*)(brow + ni * 32 * PFR + r * SCP + sc0);
-#pragma unroll
-      for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-          for (int ni = 0; ni < NI; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi][t], bf[ni][t], acc[mi][ni], 0, 0, 0);
-    }
-  }
-
-  // output view (n,p,q,k,0,0,0) -> out[n,p,q,k]; the buffer has fewer than 2^31 elements (checked
-  // by the caller), so 32-bit offsets are exact
   float* obase = out + (int64_t)n * P * Q * K;
+
+  const int tile0 = tq * QT;
+  f4 pv[PV];
+  load_patch(tile0 * Cf::TQ, pv);
+  store_patch(ps0, pv);
+  __syncthreads();
+
+  for (int t = 0; t < QT; ++t) {
+    const int q0 = (tile0 + t) * Cf::TQ;
+    if (q0 >= Q) break;  // workgroup-uniform
+    const float* ps = ps0 + (t & 1) * PH * PWF;
+    const bool more = t + 1 < QT && q0 + Cf::TQ < Q;
+    if (more) load_patch(q0 + Cf::TQ, pv);  // in flight while this tile is computed
+
+    f16 acc[MI][NI];
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi) {
-    const int prow = p0 + (wm * MI + mi) * Cf::RB;
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
-      const int k = k0 + (wn * NI + ni) * 32 + l32;
-      if (k >= K) continue;
+      for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-      for (int rg = 0; rg < 16; ++rg) {
-        const int m = 8 * (rg / 4) + 4 * lh + (rg % 4);  // pixel of the block this register holds
-        const int p = prow + m / QB, q = q0 + m % QB;
-        if (p < P && q < Q) obase[(p * Q + q) * K + k] = acc[mi][ni][rg];
+        for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+    const float* arow = ps + aoff;
+    for (int r = 0; r < R; ++r) {
+      for (int sc0 = 0; sc0 < SCP; sc0 += 8) {
+        f4 af[MI], bf[NI];
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+          const float* a = arow + (mi * Cf::RB * sh + r) * PWF + sc0;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) af[mi][e] = a[e];
+        }
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) bf[ni] = *(const f4*)(brow + ni * 32 * PFR + r * SCP + sc0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+              acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi][e], bf[ni][e], acc[mi][ni], 0, 0, 0);
       }
     }
+
+    // output view (n,p,q,k,0,0,0) -> out[n,p,q,k]; the buffer has fewer than 2^31 elements (checked
+    // by the caller), so 32-bit offsets are exact
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      const int prow = p0 + (wm * MI + mi) * Cf::RB;
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) {
+        const int k = k0 + (wn * NI + ni) * 32 + l32;
+        if (k >= K) continue;
+#pragma unroll
+        for (int rg = 0; rg < 16; ++rg) {
+          const int m = 8 * (rg / 4) + 4 * lh + (rg % 4);  // pixel of the block this register holds
+          const int p = prow + m / QB, q = q0 + m % QB;
+          if (p < P && q < Q) obase[(p * Q + q) * K + k] = acc[mi][ni][rg];
+        }
+      }
+    }
+
+    // the next tile's patch goes to the other buffer (its last readers passed the barrier of the
+    // previous iteration)
+    if (more) store_patch(ps0 + ((t + 1) & 1) * PH * PWF, pv);
+    __syncthreads();
   }
 }
 
 template <int QB, int MI, int NI, int WAVES_M, int WAVES_N>
-mdh_status launch_t(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+mdh_status launch_t(int QT, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
                     int64_t sh, int64_t sw, const float* in, const float* filt, float* out,
                     hipStream_t st) {
   using Cf = FlatCfg<QB, MI, NI, WAVES_M, WAVES_N>;
+  if (QT < 1) return MDH_ERR_UNSUPPORTED;
   const int64_t P = (H - R) / sh + 1, Q = (W - S) / sw + 1;
   const int64_t SCP = cdiv(S * C, 8) * 8;
   const int64_t PWF = cdiv((Cf::TQ - 1) * sw * C + SCP + 4, 4) * 4;
   const int64_t PFR = R * SCP + 4;
   const int64_t PH = (Cf::TP - 1) * sh + R;
-  const int64_t lds_bytes = (Cf::BN * PFR + PH * PWF) * 4;
+  const int64_t lds_bytes = (Cf::BN * PFR + 2 * PH * PWF) * 4;
   if (lds_bytes > 160 * 1024) return MDH_ERR_TILE_RESOURCES;
+  if (PH * (PWF / 4) > 8 * Cf::NT) return MDH_ERR_TILE_RESOURCES;  // prefetch registers per lane
   auto kern = mcc_flat_kernel<QB, MI, NI, WAVES_M, WAVES_N>;
   static int64_t attr_bytes = 0;
   if (lds_bytes > attr_bytes) {
@@ -185,13 +250,14 @@ mdh_status launch_t(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64
       return MDH_ERR_LAUNCH;
     attr_bytes = lds_bytes;
   }
-  const int64_t tp_n = cdiv(P, Cf::TP), tq_n = cdiv(Q, Cf::TQ), tk_n = cdiv(K, Cf::BN);
+  const int64_t tp_n = cdiv(P, Cf::TP), tq_n = cdiv(cdiv(Q, Cf::TQ), QT), tk_n = cdiv(K, Cf::BN);
   const int64_t nblocks = N * tp_n * tq_n * tk_n;
   if (nblocks > 0x7fffffff) return MDH_ERR_SIZE;
   clear_stale_error();
   hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cf::NT), (size_t)lds_bytes, st, in, filt, out,
                      (int)H, (int)W, (int)C, (int)K, (int)R, (int)S, (int)sh, (int)sw, (int)P, (int)Q,
-                     (int)tp_n, (int)tq_n, (int)tk_n, (int)SCP, (int)PWF, (int)PFR);
+                     (int)tp_n, (int)tq_n, (int)tk_n, (int)SCP, (int)PWF, (int)PFR, QT,
+                     (int)(Cf::NT / (PWF / 4)), (int)(Cf::NT % (PWF / 4)));
   return launch_status();
 }
 
@@ -201,7 +267,9 @@ mdh_status launch_t(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64
 int64_t mcc_flat_lds_bytes(int QB, int TP, int BN, int64_t C, int64_t R, int64_t S, int64_t sh, int64_t sw) {
   const int64_t SCP = cdiv(S * C, 8) * 8;
   const int64_t PWF = cdiv((QB - 1) * sw * C + SCP + 4, 4) * 4;
-  return ((int64_t)BN * (R * SCP + 4) + ((TP - 1) * sh + R) * PWF) * 4;
+  const int64_t PH = (TP - 1) * sh + R;
+  if (PH * (PWF / 4) > 8 * 256) return (int64_t)1 << 40;  // the patch prefetch would not fit in registers
+  return ((int64_t)BN * (R * SCP + 4) + 2 * PH * PWF) * 4;
 }
 
 mdh_status launch_mcc_flat(const MccPlan& pl, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
@@ -211,7 +279,7 @@ mdh_status launch_mcc_flat(const MccPlan& pl, int64_t N, int64_t H, int64_t W, i
 #define MDH_FL(qb, mi, ni, wm, wn)                                                              \
   if (pl.TQ == qb && pl.TP == wm * mi * (32 / qb) && pl.BN == wn * ni * 32 && pl.WM == mi * 32 && \
       pl.WN == ni * 32)                                                                         \
-    return launch_t<qb, mi, ni, wm, wn>(N, H, W, C, K, R, S, sh, sw, in, filt, out, st);
+    return launch_t<qb, mi, ni, wm, wn>(pl.QT, N, H, W, C, K, R, S, sh, sw, in, filt, out, st);
   MDH_FL(16, 1, 2, 4, 1)  // 8 x 16 pixels x 64 channels
   MDH_FL(32, 1, 2, 4, 1)  // 4 x 32 pixels x 64 channels
   MDH_FL(16, 1, 1, 4, 1)  // 8 x 16 pixels x 32 channels

@@ -343,8 +343,9 @@ void params_from_plan(const int64_t* s, const MccPlan& pl, mdh_tile_params* p) {
   clear_params(p, 7);
   p->prt[MDH_L_WG][0] = (int32_t)s[0];
   p->prt[MDH_L_WG][1] = (int32_t)cdiv(s[1], pl.TP);
-  p->prt[MDH_L_WG][2] = (int32_t)cdiv(s[2], pl.TQ);
+  p->prt[MDH_L_WG][2] = (int32_t)cdiv(cdiv(s[2], pl.TQ), pl.flat ? pl.QT : 1);
   p->prt[MDH_L_WG][3] = (int32_t)cdiv(s[3], pl.BN);
+  if (pl.flat) p->prt[MDH_L_HBM][2] = pl.QT;  // column tiles walked with the filter slice resident
   p->prt[MDH_L_LDS][5] = (int32_t)s[5];
   p->prt[MDH_L_LDS][6] = (int32_t)s[6];
   p->prt[MDH_L_WAVE][3] = pl.BN / pl.WN;
@@ -381,19 +382,35 @@ void params_from_plan(const int64_t* s, const MccPlan& pl, mdh_tile_params* p) {
 }
 
 static int mcc_ragged(const int64_t* s, const MccPlan& pl) {
-  if (pl.flat) return (s[1] % pl.TP) || (s[2] % pl.TQ) || (s[3] % pl.BN);
+  if (pl.flat) return (s[1] % pl.TP) || (s[2] % ((int64_t)pl.TQ * pl.QT)) || (s[3] % pl.BN);
   return (s[1] % pl.TP) || (s[2] % pl.TQ) || (s[3] % pl.BN) || (s[4] % pl.CK);
 }
 
+// Column tiles per workgroup of the few-channel kernel: at most `want`, fewer while the grid would
+// drop below one workgroup per compute unit; normalised so that no workgroup is without a tile.
+static int flat_qt(const int64_t* s, const MccPlan& pl, int want) {
+  const int64_t tiles = cdiv(s[2] > 0 ? s[2] : 1, pl.TQ);
+  const int64_t other = (s[0] > 0 ? s[0] : 1) * cdiv(s[1] > 0 ? s[1] : 1, pl.TP) * cdiv(s[3] > 0 ? s[3] : 1, pl.BN);
+  int64_t qt = want < tiles ? want : tiles;
+  while (qt > 1 && other * cdiv(tiles, qt) < 256) qt = cdiv(qt, 2);
+  return (int)cdiv(tiles, cdiv(tiles, qt));
+}
+
 static MccPlan mcc_flat_plan(const int64_t* s) {
-  // Measured on the first-layer shapes of ResNet-50, VGG-16 and MobileNet: blocks of 4 x 32 pixels are
-  // fastest even where 32 does not divide Q (112 = 3.5 blocks: the last one is predicated).  Many
-  // taps (7 x 7 x 3): 32 channels per workgroup -- more workgroups, each stages half the filter
-  // (64 us against 78 us with 64).  Few taps (3 x 3 x 3): the output write dominates and 64
-  // channels per workgroup write whole 256-byte pixels (78 us against 93 us).
-  const int qb = 32, tp = 4;
+  // Measured on the first-layer shapes of ResNet-50, VGG-16 and MobileNet.
+  // Many taps (7 x 7 x 3): the filter slice is the larger part of what a workgroup stages, so a
+  // workgroup keeps it and walks a whole row of column tiles (56 us against 64 us); 32 channels per
+  // workgroup (more workgroups, each stages half the filter); blocks of 8 x 16 pixels where 16
+  // divides Q and 32 does not (Q = 112).
+  // Few taps (3 x 3 x 3): the output write dominates; blocks of 4 x 32 pixels, one tile per
+  // workgroup, and 64 channels per workgroup so that whole 256-byte pixels are written (78 us
+  // against 93 us).
+  const bool many_taps = s[4] * s[5] * s[6] >= 64;
+  const int qb = (s[2] % 32 != 0 && s[2] % 16 == 0) ? 16 : 32;
+  const int tp = qb == 16 ? 8 : 4;
   MccPlan pl{tp, qb, 32, 0, 32, 32, 0, 1};
-  if (s[3] > 64 || (s[3] > 32 && s[4] * s[5] * s[6] <= 48)) pl = MccPlan{tp, qb, 64, 0, 32, 64, 0, 1};
+  if (s[3] > 64 || (s[3] > 32 && !many_taps)) pl = MccPlan{tp, qb, 64, 0, 32, 64, 0, 1};
+  pl.QT = flat_qt(s, pl, 8);
   pl.ragged = mcc_ragged(s, pl);
   return pl;
 }
@@ -417,14 +434,21 @@ int mcc_candidates(const int64_t* s, MccPlan* out, int cap) {
     pl.ragged = mcc_ragged(s, pl);
     for (int i = 0; i < n; ++i)
       if (out[i].flat == pl.flat && out[i].TP == pl.TP && out[i].TQ == pl.TQ && out[i].BN == pl.BN &&
-          out[i].WM == pl.WM)
+          out[i].WM == pl.WM && out[i].QT == pl.QT)
         return;
     out[n++] = pl;
   };
   push(mcc_default(s));
   for (auto& m : kMccMenu) push(MccPlan{m.TP, m.TQ, m.BN, m.CK, m.WM, m.WN, 0, 0});
   if (s[4] <= 16)
-    for (auto& m : kMccFlatMenu) push(MccPlan{m.TP, m.TQ, m.BN, m.CK, m.WM, m.WN, 0, 1});
+    for (int want : {1, 2, 4, 8, 16})
+      for (auto& m : kMccFlatMenu) {
+        MccPlan pl{m.TP, m.TQ, m.BN, m.CK, m.WM, m.WN, 0, 1};
+        const int64_t tiles = cdiv(s[2] > 0 ? s[2] : 1, pl.TQ);
+        const int64_t qt = want < tiles ? want : tiles;
+        pl.QT = (int)cdiv(tiles, cdiv(tiles, qt));
+        push(pl);
+      }
   return n;
 }
 
@@ -449,6 +473,9 @@ mdh_status plan_mcc(const int64_t* s, const mdh_tile_params* p, MccPlan* out) {
     pl.WM = p->prt[MDH_L_VGPR][1] * 32;
     pl.TP = p->prt[MDH_L_WAVE][1] * p->prt[MDH_L_VGPR][1] * (32 / pl.TQ);
     pl.CK = 0;
+    pl.QT = p->prt[MDH_L_HBM][2];
+    // a workgroup part of q that owns no tile is not a partition of the columns
+    if ((int64_t)(p->prt[MDH_L_WG][2] - 1) * pl.QT * pl.TQ >= (s[2] > 0 ? s[2] : 1)) return MDH_ERR_TILE_NOT_DIVIDING;
   } else {
     pl.TQ = p->prt[MDH_L_VGPR][2] * 32;
     pl.TP = p->prt[MDH_L_WAVE][1] * p->prt[MDH_L_VGPR][1];

@@ -7,6 +7,7 @@ import pytest
 
 import oracle
 import paper_2405_05118_amd as mdh
+from paper_2405_05118_amd import binding as B
 from paper_2405_05118_amd import workloads as W
 
 TOL = 1e-4
@@ -29,13 +30,16 @@ def test_default_fuses_s_and_c_for_few_channels():
         assert mdh.mdh_validate_params(mdh.MDH_MCC, s, p) == 0
         for d in range(7):
             assert p.extent(d) >= s[d] if p.ragged else p.extent(d) == s[d]
-    # ResNet's 112 output columns are walked in blocks of 32 (the last one predicated); a table with
-    # blocks of 16, which divide 112, is among the candidates
+    # ResNet's 112 output columns are 7 blocks of 16, not a multiple of 32: no ragged columns; with a
+    # batch of 16 a workgroup walks the whole row of tiles with its filter slice resident
     s = sizes_of(1, 230, 230, 3, 64, 7, 7, (2, 2))
     p = mdh.mdh_default_params(mdh.MDH_MCC, s)
-    assert p.blk[2] == 32 and p.extent(2) == 128 and p.ragged
+    assert p.blk[2] == 16 and p.extent(2) == 112 and p.prt[B.L_HBM][2] == 1
+    s = sizes_of(16, 230, 230, 3, 64, 7, 7, (2, 2))
+    p = mdh.mdh_default_params(mdh.MDH_MCC, s)
+    assert p.blk[2] == 16 and p.extent(2) == 112 and p.prt[B.L_HBM][2] == 7 and p.prt[B.L_WG][2] == 1
     cands = [mdh.mdh_candidate(mdh.MDH_MCC, s, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_MCC, s))]
-    assert any(c.blk[2] == 16 and c.extent(2) == 112 for c in cands)
+    assert any(c.blk[2] == 32 and c.extent(2) == 128 for c in cands)
     # many channels keep the channel-chunked kernel
     p = mdh.mdh_default_params(mdh.MDH_MCC, (16, 224, 224, 128, 64, 7, 7, 1, 1))
     assert p.blk[4] == 2
