@@ -37,21 +37,22 @@ PRL_LANE_OPS_PER_PAIR = 24.0
 # None until measured for that workload
 TRAFFIC_BYTES = {
     # profiles/all_kernels_hbm_traffic_pmc.md (all kernels of a step)
-    "jacobi3d_512": 1110236372,
-    "dot_2p28": 2147373315,
-    "matvec_16384": 1074466926,
-    "matmul_4096": 604073920,
-    "matmul_ts": 1102209479,
-    "mcc_resnet": 851128217,
-    "prl_2p16_2p18": 141525914,
-    "matmul_256": 5403072,
-    "mcc_resnet50_first": 61878429,
-    "matmul_resnet50_fc": 14433971,
-    "matmul_vgg16_fc": 426435447,
-    "mcc_capsule_resnet50_first": 1072570351,
-    "scan_2p28": 3221513028,
-    "scan_rows_65536x4096": 2147467414,
-    "histo_generic_256x2p24": 320573908,
+    "jacobi3d_512": 1109916130,
+    "dot_2p28": 2147368726,
+    "matvec_16384": 1074464904,
+    "matmul_4096": 604074231,
+    "matmul_ts": 1102106332,
+    "mcc_resnet": 850741972,
+    "prl_2p16_2p18": 141555895,
+    "matmul_256": 1927895,
+    "mcc_resnet50_first": 62421828,
+    "matmul_resnet50_fc": 13577143,
+    "matmul_vgg16_fc": 426312390,
+    "mcc_capsule_resnet50_first": 1072581881,
+    "scan_2p28": 3221501235,
+    "scan_rows_65536x4096": 2147448415,
+    "histo_generic_256x2p24": 67263624,
+    "prl_generic_2p16_2p18": 145818385,
 }
 
 
@@ -432,7 +433,7 @@ def bench_histo_generic(torch, mdh, W, name, steps, warmup, cpu):
         "value": pairs / wall / 1e6, "unit": "Gpairs/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "i32",
         "kernel": "mdh_custom_main + mdh_custom_combine (hipRTC)", "bins": nb, "elements": ne,
         "roofline": {"bound": "alu", "achieved": tops, "peak": PEAK_INT_VALU_TOPS, "unit": "Tlane-op/s",
-                     "frac": tops / PEAK_INT_VALU_TOPS, "traffic": None},
+                     "frac": tops / PEAK_INT_VALU_TOPS, "traffic": TRAFFIC_BYTES.get(name)},
         "lane_ops_per_pair": 2.0,
         "algorithmic_bytes": 4 * (ne + 2 * nb),
     }
@@ -479,7 +480,7 @@ def bench_prl_generic(torch, mdh, W, name, steps, warmup, cpu):
         "value": pairs / wall / 1e6, "unit": "Gpairs/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "i32",
         "kernel": "mdh_custom_main + mdh_custom_combine (hipRTC)",
         "roofline": {"bound": "alu", "achieved": tops, "peak": PEAK_INT_VALU_TOPS, "unit": "Tlane-op/s",
-                     "frac": tops / PEAK_INT_VALU_TOPS, "traffic": None},
+                     "frac": tops / PEAK_INT_VALU_TOPS, "traffic": TRAFFIC_BYTES.get(name)},
         "lane_ops_per_pair": PRL_LANE_OPS_PER_PAIR,
     }
     mdh.mdh_custom_destroy(op)
