@@ -14,11 +14,12 @@
 // De-composition:
 //   workgroup layer : N x (P/4) x (Q/(8*QT)) x (K/(8*NI))
 //   HBM layer       : QT tiles of 8 columns q, walked sequentially: the filter slice is staged once
-//                     per workgroup, the input patch (3*sh+R rows) once per tile
+//                     per workgroup, the input patch (3*sh+R rows) once per tile; the patch of the
+//                     next tile is requested into registers before the walk of the current one
 //   wavefront layer : 4 output rows p x RW parts of the fused (r, s, c) walk; the RW partial
 //                     blocks of a row are added in LDS (two wavefronts per SIMD hide the LDS
 //                     latency of the operand reads; the LDS footprint allows one workgroup per CU)
-//   block           : (8 q x 4 mi) x (8 k x 4 mj) x 2 of mk; NI blocks along k per wavefront
+//   block           : (8 k x 4 mj) x (8 q x 4 mi) x 2 of mk; NI blocks along k per wavefront
 #include "mdh_internal.h"
 
 namespace mdh {
@@ -36,13 +37,16 @@ __global__ __launch_bounds__(256 * RW) void capsule_kernel(const float* __restri
                                                          float* __restrict__ out, int H, int W, int C,
                                                          int K, int R, int S, int sh, int sw, int P,
                                                          int Q, int tp_n, int tq_n, int tk_n, int J2,
-                                                         int PWF, int PFR, int QT) {
+                                                         int PWF, int PFR, int QT, int pstep_rows,
+                                                         int pstep_x) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   constexpr int CAP_NT = 256 * RW;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = (tid >> 6) & 3;  // output row of the workgroup
-  const int rw = tid >> 8;          // part of the reduction walk
+  // wavefront-uniform values are made scalar explicitly: the walk below then runs on scalar
+  // loop counters instead of per-lane masks
+  const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);  // output row of the workgroup
+  const int rw = __builtin_amdgcn_readfirstlane(tid >> 8);          // part of the reduction walk
   const int l32 = lane & 31, h = lane >> 5;
   int b = blockIdx.x;
   const int nb = gridDim.x;
@@ -61,6 +65,54 @@ __global__ __launch_bounds__(256 * RW) void capsule_kernel(const float* __restri
   // this wavefront's share [t0, t1) of the R*J2 steps of the walk (a step = two (s,c) pairs)
   const int steps = R * J2;
   const int t0 = (steps * rw) / RW, t1 = (steps * (rw + 1)) / RW;
+
+  // The input patch of a column tile travels HBM -> registers -> LDS in 16-byte pieces; piece
+  // u*CAP_NT + tid sits in patch row ph at 16-byte column x, and stepping u advances (ph, x) by a
+  // fixed amount (CAP_NT = pstep_rows*pw4 + pstep_x, from the host), so only one division is needed.
+  // The pieces of the NEXT tile are requested before the MFMA walk of the current one and are
+  // written to LDS after it: the HBM/L2 latency hides behind the walk.  Pieces beyond CAP_PV per
+  // lane (very wide patches) are staged directly.
+  constexpr int CAP_PV = 16;
+  const int pw4 = PWF >> 2;
+  const int npieces = PH * pw4;
+  const int pv_n = (npieces + CAP_NT - 1) / CAP_NT;  // pieces per lane (workgroup-uniform)
+  const int ph_first = tid / pw4, x_first = tid - ph_first * pw4;
+  const float* img = in + (int64_t)n * H * WC16;
+  f4 pre[CAP_PV];
+  auto fetch = [&](int q0) {
+    int ph = ph_first, x = x_first;
+    const int64_t gq = (int64_t)q0 * sw * C * 16;
+#pragma unroll
+    for (int u = 0; u < CAP_PV; ++u) {
+      if (u >= pv_n) break;
+      f4 v = {0.f, 0.f, 0.f, 0.f};
+      const int hy = p0 * sh + ph;
+      const int64_t gx = gq + (x << 2);
+      if (u * CAP_NT + tid < npieces && hy < H && gx < WC16) v = *(const f4u*)(img + hy * WC16 + gx);
+      pre[u] = v;
+      x += pstep_x;
+      ph += pstep_rows;
+      if (x >= pw4) {
+        x -= pw4;
+        ++ph;
+      }
+    }
+  };
+  auto stash = [&]() {
+    int ph = ph_first, x = x_first;
+#pragma unroll
+    for (int u = 0; u < CAP_PV; ++u) {
+      if (u >= pv_n) break;
+      if (u * CAP_NT + tid < npieces) *(f4*)(ps + ph * PWF + (x << 2)) = pre[u];
+      x += pstep_x;
+      ph += pstep_rows;
+      if (x >= pw4) {
+        x -= pw4;
+        ++ph;
+      }
+    }
+  };
+  if (tq * QT * CAP_TQ < Q) fetch(tq * QT * CAP_TQ);
 
   // filter slice: global order [mk][mj] -> LDS order [mj][mk].  A filter row k is R*S*C*16 contiguous
   // floats, so the split of a lane's 16-byte pieces into (r, j, mk) is the same for every k and is
@@ -104,27 +156,29 @@ __global__ __launch_bounds__(256 * RW) void capsule_kernel(const float* __restri
       }
   }
 
-  // A: row (dq, mi) of the block; B: column (dk, mj); the lane half h takes the odd (s,c) pair
+  // patch operand: (dq, mi) of the block; filter operand: (dk, mj); the lane half h takes the odd
+  // (s,c) pair
   const int d4 = l32 >> 2, m4 = l32 & 3;
   const float* arow = ps + (wave * sh) * PWF + d4 * sw * C * 16 + h * 16 + m4 * 4;
   const float* brow = fs + d4 * PFR + h * 16 + m4 * 4;
   const int p = p0 + wave;
-  const int pw4 = PWF >> 2;
 
   for (int qt = 0; qt < QT; ++qt) {
     const int q0 = (tq * QT + qt) * CAP_TQ;
     if (q0 >= Q) break;  // workgroup-uniform
-    // input patch of this tile, 16 bytes at a time; cells outside the image read as 0
+    // input patch of this tile (cells outside the image read as 0), then the request for the next
     if (qt) __syncthreads();  // the previous tile's reads are done
-    for (int idx = tid; idx < PH * pw4; idx += CAP_NT) {
+    stash();
+    for (int idx = CAP_PV * CAP_NT + tid; idx < npieces; idx += CAP_NT) {
       const int ph = idx / pw4, x = (idx - ph * pw4) << 2;
       const int hy = p0 * sh + ph;
       const int64_t gx = (int64_t)q0 * sw * C * 16 + x;
       f4 v = {0.f, 0.f, 0.f, 0.f};
-      if (hy < H && gx < WC16) v = *(const f4u*)(in + ((int64_t)n * H + hy) * WC16 + gx);
+      if (hy < H && gx < WC16) v = *(const f4u*)(img + hy * WC16 + gx);
       *(f4*)(ps + ph * PWF + x) = v;
     }
     __syncthreads();
+    if (qt + 1 < QT && q0 + CAP_TQ < Q) fetch(q0 + CAP_TQ);
 
     f16 acc[NI];
 #pragma unroll
@@ -133,26 +187,61 @@ __global__ __launch_bounds__(256 * RW) void capsule_kernel(const float* __restri
       for (int r = 0; r < 16; ++r) acc[ni][r] = 0.f;
 
     {
+      // Software pipeline over two operand sets: the LDS reads of step t+1 are issued before the
+      // MFMAs of step t, so their latency hides behind 4*NI MFMAs.  The scheduling barriers keep the
+      // compiler from sinking the reads below the MFMAs (it would then wait for them at once).
+      // sa/sb: wavefront-uniform offsets of the step in the patch row / the filter row.
       int r = t0 / J2, jj = t0 - r * J2;
-      const float* a = arow + r * PWF + jj * 32;
-      const float* bb = brow + t0 * 32;  // the filter rows are contiguous over (r, j)
-#pragma unroll 2
-      for (int t = t0; t < t1; ++t) {
-        const f4 af = *(const f4*)a;
-        f4 bf[NI];
+      int sa = r * PWF + jj * 32, sb = t0 * 32;  // the filter rows are contiguous over (r, j)
+      f4 a0 = *(const f4*)(arow + sa), a1;
+      f4 b0[NI], b1[NI];
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) bf[ni] = *(const f4*)(bb + ni * 8 * PFR);
+      for (int ni = 0; ni < NI; ++ni) b0[ni] = *(const f4*)(brow + sb + ni * 8 * PFR);
+      int t = t0;
+      for (; t + 2 <= t1; t += 2) {
+        sb += 32;
+        sa += 32;
+        if (++jj == J2) {  // next filter row r: next patch row
+          jj = 0;
+          sa += PWF - J2 * 32;
+        }
+        a1 = *(const f4*)(arow + sa);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) b1[ni] = *(const f4*)(brow + sb + ni * 8 * PFR);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int e = 0; e < 4; ++e)
 #pragma unroll
           for (int ni = 0; ni < NI; ++ni)
-            acc[ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[e], bf[ni][e], acc[ni], 0, 0, 0);
-        bb += 32;
-        a += 32;
-        if (++jj == J2) {  // next filter row r: next patch row
-          jj = 0;
-          a += PWF - J2 * 32;
+            acc[ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(b0[ni][e], a0[e], acc[ni], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        // operands of step t+2; past the end of the walk the reads repeat step t+1 and are unused
+        int na = sa + 32, nj = jj + 1;
+        if (nj == J2) {
+          nj = 0;
+          na += PWF - J2 * 32;
         }
+        const bool more = t + 2 < t1;
+        sa = more ? na : sa;
+        sb = more ? sb + 32 : sb;
+        jj = more ? nj : jj;
+        a0 = *(const f4*)(arow + sa);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) b0[ni] = *(const f4*)(brow + sb + ni * 8 * PFR);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int ni = 0; ni < NI; ++ni)
+            acc[ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(b1[ni][e], a1[e], acc[ni], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (t < t1) {  // odd number of steps
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int ni = 0; ni < NI; ++ni)
+            acc[ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(b0[ni][e], a0[e], acc[ni], 0, 0, 0);
       }
     }
 
@@ -178,21 +267,21 @@ __global__ __launch_bounds__(256 * RW) void capsule_kernel(const float* __restri
       }
     }
 
-    // output view (n,p,q,k,mi,mj,0,0,0,0) -> out[n,p,q,k,mi,mj]
+    // output view (n,p,q,k,mi,mj,0,0,0,0) -> out[n,p,q,k,mi,mj].  The filter is the row operand of
+    // the MFMA, so registers 4g..4g+3 of a lane hold mj = 0..3 of filter k = 2g + h for the lane's
+    // (pixel, mi) column: one 16-byte store, and a store instruction writes 128-byte runs.
     if (rw == 0 && p < P) {
+      const int q = q0 + d4;
+      float* o = out + ((((int64_t)n * P + p) * Q * K) << 4) + m4 * 4;
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni) {
-        const int k = k0 + ni * 8 + d4;
-        if (k >= K) continue;
+      for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int q = q0 + 2 * g + h;  // registers 4g..4g+3 hold mi = 0..3 of this pixel
-          if (q >= Q) continue;
-          float* o = out + ((((int64_t)n * P + p) * Q * K) << 4) + (((q * K + k) << 4) + m4);
-#pragma unroll
-          for (int mi = 0; mi < 4; ++mi) o[mi * 4] = acc[ni][4 * g + mi];
+          const int k = k0 + ni * 8 + 2 * g + h;
+          if (q < Q && k < K)
+            *(f4u*)(o + ((q * K + k) << 4)) =
+                (f4){acc[ni][4 * g], acc[ni][4 * g + 1], acc[ni][4 * g + 2], acc[ni][4 * g + 3]};
         }
-      }
     }
   }
 }
@@ -234,7 +323,8 @@ mdh_status launch_t(int QT, int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
   clear_stale_error();
   hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(256 * RW), (size_t)g.lds_bytes, st, in, filt, out,
                      (int)H, (int)W, (int)C, (int)K, (int)R, (int)S, (int)sh, (int)sw, (int)P, (int)Q,
-                     (int)tp_n, (int)tq_n, (int)tk_n, (int)g.J2, (int)g.PWF, (int)g.PFR, QT);
+                     (int)tp_n, (int)tq_n, (int)tk_n, (int)g.J2, (int)g.PWF, (int)g.PFR, QT,
+                     (int)((256 * RW) / (g.PWF / 4)), (int)((256 * RW) % (g.PWF / 4)));
   return launch_status();
 }
 

@@ -182,26 +182,64 @@ __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
+    // The walk over (r, s*c) in steps of 8, software-pipelined over two operand sets: the LDS reads
+    // of step t+1 are issued before the MFMAs of step t.  The scheduling barriers keep the compiler
+    // from sinking the reads below the MFMAs (it would then wait for them at once).  sa/sb are the
+    // wavefront-uniform offsets of a step in the patch / in the filter row (contiguous over r).
     const float* arow = ps + aoff;
-    for (int r = 0; r < R; ++r) {
-      for (int sc0 = 0; sc0 < SCP; sc0 += 8) {
-        f4 af[MI], bf[NI];
+    auto ld = [&](f4 (&af)[MI], f4 (&bf)[NI], int sa, int sb) {
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-          const float* a = arow + (mi * Cf::RB * sh + r) * PWF + sc0;
+      for (int mi = 0; mi < MI; ++mi) {
+        const float* a = arow + mi * Cf::RB * sh * PWF + sa;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) af[mi][e] = a[e];
-        }
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) bf[ni] = *(const f4*)(brow + ni * 32 * PFR + r * SCP + sc0);
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-#pragma unroll
-          for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-              acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi][e], bf[ni][e], acc[mi][ni], 0, 0, 0);
+        for (int e = 0; e < 4; ++e) af[mi][e] = a[e];
       }
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) bf[ni] = *(const f4*)(brow + ni * 32 * PFR + sb);
+    };
+    auto mma = [&](const f4 (&af)[MI], const f4 (&bf)[NI]) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < NI; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi][e], bf[ni][e], acc[mi][ni], 0, 0, 0);
+    };
+    {
+      const int nsteps = R * (SCP >> 3);
+      f4 a0[MI], b0[NI], a1[MI], b1[NI];
+      int sa = 0, sb = 0, sc0 = 0;
+      ld(a0, b0, 0, 0);
+      int st = 0;
+      for (; st + 2 <= nsteps; st += 2) {
+        sb += 8;
+        sa += 8;
+        sc0 += 8;
+        if (sc0 == SCP) {  // next filter row r: next patch row
+          sc0 = 0;
+          sa += PWF - SCP;
+        }
+        ld(a1, b1, sa, sb);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        // operands of step st+2; past the end of the walk the reads repeat step st+1 and are unused
+        int na = sa + 8, nc = sc0 + 8;
+        if (nc == SCP) {
+          nc = 0;
+          na += PWF - SCP;
+        }
+        const bool nxt = st + 2 < nsteps;
+        sa = nxt ? na : sa;
+        sb = nxt ? sb + 8 : sb;
+        sc0 = nxt ? nc : sc0;
+        ld(a0, b0, sa, sb);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (st < nsteps) mma(a0, b0);  // odd number of steps
     }
 
     // output view (n,p,q,k,0,0,0) -> out[n,p,q,k]; the buffer has fewer than 2^31 elements (checked
