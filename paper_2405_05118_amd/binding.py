@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(HERE, "libmdh.so")
 MDH_MATMUL, MDH_STENCIL, MDH_MCC, MDH_CUSTOM_REDUCE, MDH_DOT, MDH_MATVEC, MDH_BMATMUL, MDH_SCAN, MDH_MCC_CAPSULE = 0, 1, 2, 3, 4, 5, 6, 7, 8
 MDH_NUM_LAYERS, MDH_MAX_D = 6, 10
 L_HBM, L_LDS, L_VGPR, L_WG, L_WAVE, L_LANE = range(6)
+MR_HBM, MR_LDS, MR_VGPR = range(3)  # memory regions of in_region / out_region
 
 EXPORTS = (
     "mdh_strerror", "mdh_version", "mdh_part_offset", "mdh_default_params", "mdh_validate_params",

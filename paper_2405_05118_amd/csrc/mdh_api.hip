@@ -156,8 +156,7 @@ mdh_status mdh_scan(int64_t R, int64_t n, const float* in, float* out, const mdh
   if (st != MDH_OK) return st;
   if (R == 0 || n == 0) return MDH_OK;
   if (!in || !out) return MDH_ERR_NULL;
-  if (pl.C > 1 && (!workspace || workspace_bytes < (size_t)pl.C * (size_t)R * sizeof(double) ||
-                   ((uintptr_t)workspace & 7)))
+  if (pl.C > 1 && (!workspace || workspace_bytes < scan_workspace_bytes(pl, R) || ((uintptr_t)workspace & 7)))
     return MDH_ERR_WORKSPACE;
   return launch_scan(pl, R, n, in, out, workspace, (hipStream_t)stream);
 }

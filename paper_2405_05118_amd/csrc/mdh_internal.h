@@ -76,7 +76,10 @@ struct ScanPlan {
   int TPC;
   int C;
   int ragged;
+  int onepass;  // C > 1 only: a chunk stays in registers while the workgroups exchange chunk totals
 };
+// bytes of workspace a scan plan needs for R rows (0: none)
+size_t scan_workspace_bytes(const ScanPlan& pl, int64_t R);
 mdh_status plan_scan(const int64_t* sizes, const mdh_tile_params* p, ScanPlan* out);
 void params_from_plan(const int64_t* sizes, const ScanPlan& pl, mdh_tile_params* out);
 int scan_candidates(const int64_t* sizes, ScanPlan* out, int cap);

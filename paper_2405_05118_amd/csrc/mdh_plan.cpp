@@ -782,8 +782,8 @@ size_t mdh_workspace_size(mdh_instance inst, const int64_t* sizes, const mdh_til
     }
     case MDH_SCAN: {
       ScanPlan pl;
-      if (plan_scan(sizes, params, &pl) != MDH_OK || pl.C <= 1) return 0;
-      return (size_t)pl.C * (size_t)sizes[0] * sizeof(double);
+      if (plan_scan(sizes, params, &pl) != MDH_OK) return 0;
+      return scan_workspace_bytes(pl, sizes[0]);
     }
     default:
       return 0;

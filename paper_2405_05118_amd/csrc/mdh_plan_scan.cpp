@@ -12,6 +12,9 @@ namespace mdh {
 using namespace detail;
 
 static const int kScanWaves[] = {4, 8, 16};
+// single-pass variant (the chunk stays in registers): tiles per chunk are a template parameter
+static const int kOnePassWaves[] = {8, 16};
+static const int kOnePassTpc[] = {2, 4, 8};  // 5 registers per tile and lane
 
 void params_from_plan(const int64_t* s, const ScanPlan& pl, mdh_tile_params* p) {
   clear_params(p, 2);
@@ -29,7 +32,9 @@ void params_from_plan(const int64_t* s, const ScanPlan& pl, mdh_tile_params* p) 
   set_order(p, dims);
   p->strided = 0;
   p->lane_fast_dim = 1;
-  p->in_region[0] = MDH_MR_VGPR;
+  // where a chunk waits while the workgroups exchange their totals: in registers (one pass over
+  // the input), or not at all (it is read from HBM a second time)
+  p->in_region[0] = (pl.C > 1 && !pl.onepass) ? MDH_MR_HBM : MDH_MR_VGPR;
   p->out_region = MDH_MR_VGPR;
   p->ragged = (uint8_t)pl.ragged;
 }
@@ -39,7 +44,7 @@ static int scan_ragged(const int64_t* s, const ScanPlan& pl) {
 }
 
 static ScanPlan scan_plan(const int64_t* s, int waves, int64_t chunks) {
-  ScanPlan pl{waves, 1, 1, 0};
+  ScanPlan pl{waves, 1, 1, 0, 0};
   const int64_t tile = (int64_t)waves * 256;
   const int64_t tiles = cdiv(s[1] > 0 ? s[1] : 1, tile);
   if (chunks < 1) chunks = 1;
@@ -50,8 +55,17 @@ static ScanPlan scan_plan(const int64_t* s, int waves, int64_t chunks) {
   return pl;
 }
 
+static ScanPlan scan_onepass_plan(const int64_t* s, int waves, int tpc) {
+  ScanPlan pl{waves, tpc, 1, 0, 1};
+  const int64_t tiles = cdiv(s[1] > 0 ? s[1] : 1, (int64_t)waves * 256);
+  pl.C = (int)cdiv(tiles, tpc);
+  if (pl.C <= 1) pl.onepass = 0;  // a single chunk needs no exchange
+  pl.ragged = scan_ragged(s, pl);
+  return pl;
+}
+
 static ScanPlan scan_wave_plan(const int64_t* s) {
-  ScanPlan pl{1, (int)cdiv(s[1] > 0 ? s[1] : 1, 256), 1, 0};
+  ScanPlan pl{1, (int)cdiv(s[1] > 0 ? s[1] : 1, 256), 1, 0, 0};
   pl.ragged = scan_ragged(s, pl);
   return pl;
 }
@@ -64,7 +78,12 @@ static ScanPlan scan_default(const int64_t* s) {
   const int64_t rows = s[0] > 0 ? s[0] : 1;
   int64_t chunks = 1;
   while (rows * chunks < 2048 && cdiv(s[1], 2048 * chunks * 2) >= 4) chunks *= 2;
-  return scan_plan(s, 8, chunks);  // 8 wavefronts per workgroup measured fastest (4 and 16 within 7 %)
+  if (chunks == 1) return scan_plan(s, 8, 1);  // 8 wavefronts per workgroup measured fastest (4 and 16 within 7 %)
+  // few long rows: chunks of j over workgroups, a chunk resident in registers (one pass over the
+  // input); as many tiles per chunk as still give a workgroup per compute unit
+  int tpc = 8;
+  while (tpc > 2 && rows * cdiv(s[1], (int64_t)4096 * tpc) < 256) tpc /= 2;
+  return scan_onepass_plan(s, 16, tpc);  // 16 wavefronts measured fastest (8: +8 %)
 }
 
 int scan_candidates(const int64_t* s, ScanPlan* out, int cap) {
@@ -72,7 +91,7 @@ int scan_candidates(const int64_t* s, ScanPlan* out, int cap) {
   auto push = [&](const ScanPlan& pl) {
     if (n >= cap) return;
     for (int i = 0; i < n; ++i)
-      if (out[i].WAVES == pl.WAVES && out[i].C == pl.C && out[i].TPC == pl.TPC) return;
+      if (out[i].WAVES == pl.WAVES && out[i].C == pl.C && out[i].TPC == pl.TPC && out[i].onepass == pl.onepass) return;
     out[n++] = pl;
   };
   const ScanPlan d0 = scan_default(s);
@@ -85,6 +104,12 @@ int scan_candidates(const int64_t* s, ScanPlan* out, int cap) {
   push(d);
   for (int w : kScanWaves)
     for (int64_t c = d.C / 4 > 0 ? d.C / 4 : 1; c <= (int64_t)d.C * 8; c *= 2) push(scan_plan(s, w, c));
+  if (d.C > 1)
+    for (int w : kOnePassWaves)
+      for (int t : kOnePassTpc) {
+        const ScanPlan pl = scan_onepass_plan(s, w, t);
+        if (pl.onepass) push(pl);
+      }
   return n;
 }
 
@@ -98,9 +123,17 @@ mdh_status plan_scan(const int64_t* s, const mdh_tile_params* p, ScanPlan* out) 
   mdh_status st = check_products(p, s, &ragged);
   if (st != MDH_OK) return st;
   if ((st = check_lanes(p)) != MDH_OK) return st;
-  ScanPlan pl{p->prt[MDH_L_WAVE][1], p->prt[MDH_L_HBM][1], p->prt[MDH_L_WG][1], ragged};
+  ScanPlan pl{p->prt[MDH_L_WAVE][1], p->prt[MDH_L_HBM][1], p->prt[MDH_L_WG][1], ragged, 0};
+  pl.onepass = pl.C > 1 && p->in_region[0] == MDH_MR_VGPR;
   bool inst = pl.WAVES == 1 && pl.C == 1;
-  for (int w : kScanWaves) inst = inst || (w == pl.WAVES);
+  if (pl.onepass) {
+    bool w_ok = false, t_ok = false;
+    for (int w : kOnePassWaves) w_ok = w_ok || (w == pl.WAVES);
+    for (int t : kOnePassTpc) t_ok = t_ok || (t == pl.TPC);
+    inst = w_ok && t_ok;
+  } else {
+    for (int w : kScanWaves) inst = inst || (w == pl.WAVES);
+  }
   // a chunk that owns no index would leave its total unset
   if ((int64_t)(pl.C - 1) * pl.TPC * pl.WAVES * 256 >= (s[1] > 0 ? s[1] : 1)) return MDH_ERR_TILE_NOT_DIVIDING;
   mdh_tile_params chk;
@@ -108,6 +141,14 @@ mdh_status plan_scan(const int64_t* s, const mdh_tile_params* p, ScanPlan* out) 
   if (!same_table(chk, *p) || !inst) return MDH_ERR_UNSUPPORTED;
   *out = pl;
   return MDH_OK;
+}
+
+// Three-kernel variant: R*C chunk totals (fp64).  Single-pass variant: a ticket counter and a
+// time-out flag (2 words), R*C chunk totals and R*ceil(C/64) group sums, 8 bytes each.
+size_t scan_workspace_bytes(const ScanPlan& pl, int64_t R) {
+  if (pl.C <= 1) return 0;
+  if (!pl.onepass) return (size_t)pl.C * (size_t)R * sizeof(double);
+  return (2 + (size_t)R * (size_t)pl.C + (size_t)R * (size_t)cdiv(pl.C, 64)) * 8;
 }
 
 }  // namespace mdh

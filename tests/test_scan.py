@@ -24,7 +24,25 @@ def test_planner(sizes):
         c = mdh.mdh_candidate(inst, sizes, i)
         assert mdh.mdh_validate_params(inst, sizes, c) == 0
     C = p.prt[B.L_WG][1]
-    assert mdh.mdh_workspace_size(inst, sizes, p) == (8 * C * sizes[0] if C > 1 else 0)
+
+    def want_ws(q):
+        c = q.prt[B.L_WG][1]
+        if c <= 1:
+            return 0
+        if q.in_region[0] == B.MR_VGPR:  # single pass: ticket, time-out flag, totals, group sums
+            return 8 * (2 + sizes[0] * c + sizes[0] * ((c + 63) // 64))
+        return 8 * c * sizes[0]  # three kernels: chunk totals
+
+    assert mdh.mdh_workspace_size(inst, sizes, p) == want_ws(p)
+    kinds = set()
+    for i in range(mdh.mdh_num_candidates(inst, sizes)):
+        c = mdh.mdh_candidate(inst, sizes, i)
+        assert mdh.mdh_workspace_size(inst, sizes, c) == want_ws(c)
+        if c.prt[B.L_WG][1] > 1:
+            kinds.add(int(c.in_region[0]))
+    if C > 1:  # both ways of exchanging the chunk totals are in the search space
+        assert kinds == {B.MR_HBM, B.MR_VGPR}
+        assert p.in_region[0] == B.MR_VGPR and p.prt[B.L_HBM][1] in (2, 4, 8)
     # a long single row is cut into chunks over workgroups, many rows are not
     if sizes == (1, 1 << 24):
         assert C > 1
@@ -40,6 +58,15 @@ def test_planner_rejects_empty_chunk():
     assert mdh.mdh_validate_params(mdh.MDH_SCAN, sizes, q) == 3
     q = p.copy()
     q.prt[B.L_WAVE][1] = 5  # no such instantiation (and the product changes)
+    assert mdh.mdh_validate_params(mdh.MDH_SCAN, sizes, q) != 0
+    # the single-pass variant holds a chunk in registers: only 2, 4 or 8 tiles per chunk
+    sizes = (1, 1 << 24)
+    three = [c for c in cands(sizes)[1:] if c.prt[B.L_WG][1] > 1 and c.in_region[0] == B.MR_HBM and c.prt[B.L_HBM][1] > 8]
+    assert three
+    q = three[0].copy()
+    q.in_region[0] = B.MR_VGPR
+    assert mdh.mdh_validate_params(mdh.MDH_SCAN, sizes, q) != 0
+    q.in_region[0] = B.MR_LDS  # no such variant
     assert mdh.mdh_validate_params(mdh.MDH_SCAN, sizes, q) != 0
 
 
@@ -71,6 +98,25 @@ def test_every_candidate(shape):
         assert np.all(np.isfinite(got)), "output not fully overwritten"
         err = float(np.max(np.abs(got - ref) / refabs))
         assert err <= TOL, (shape, p and p.table(), err)
+
+
+@pytest.mark.gpu
+def test_single_pass_many_chunks():
+    """Rows of several hundred chunks: totals travel through groups of 64 chunks and their sums."""
+    shape = (2, 2100003)
+    x = W.uniform(W.SEED_BASE + 96, 1, shape, -1, 1)
+    ref, refabs = oracle.scan_rows(x, with_abs=True)
+    seen = 0
+    for p in cands(shape):
+        if p is None or p.prt[B.L_WG][1] <= 1 or p.in_region[0] != B.MR_VGPR:
+            continue
+        seen += 1
+        first = run(x, p)
+        err = float(np.max(np.abs(first - ref) / refabs))
+        assert err <= TOL, (p.table(), err)
+        assert np.array_equal(first, run(x, p)), "not bit-identical run to run"
+    assert seen >= 4
+    assert max(p.prt[B.L_WG][1] for p in cands(shape)[1:]) > 128  # more than two groups
 
 
 @pytest.mark.gpu
