@@ -270,9 +270,23 @@ mdh_status mdh_mcc_capsule(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K
  * Example "Prefix-Sum").  The prefix-sum operator keeps the dimension and a part
  * needs ONE value of the parts before it (their last prefix); that value is
  * passed lane -> wavefront (registers) -> workgroup (LDS) -> sequential tiles
- * (a carry) -> and, if prt[MDH_L_WG][j] = C > 1, across workgroups: chunk
- * totals in `workspace` (R*C doubles, 8-byte aligned), scanned by a second
- * kernel, then applied by a third (the input is read twice in that case).
+ * (a carry) -> and, if prt[MDH_L_WG][j] = C > 1, across workgroups, in one of
+ * two ways that the table tells apart by in_region[0]:
+ *   MDH_MR_VGPR  single pass: a chunk (2, 4 or 8 tiles) waits in registers while
+ *                the workgroups exchange chunk totals, and sums of 64 totals,
+ *                through `workspace`; 8 bytes of HBM traffic per element.  Chunk
+ *                numbers are handed out in the order in which workgroups start,
+ *                so a workgroup only waits for workgroups that already run; each
+ *                wait is bounded, and should a bound ever be hit the kernel stops
+ *                waiting, finishes with wrong values in that chunk and sets the
+ *                second 8-byte word of `workspace` to 1 (0 otherwise).
+ *   MDH_MR_HBM   three kernels: chunk totals, their exclusive scan per row, then
+ *                every chunk scanned from its offset; the input is read twice
+ *                (12 bytes per element).
+ * Both add in a fixed order (bit-identical run to run).  `workspace`: 8-byte
+ * aligned, mdh_workspace_size() bytes (R*C doubles for three kernels;
+ * 2 + R*C + R*ceil(C/64) 8-byte words for the single pass); its contents need no
+ * initialisation and calls that share it must be ordered on one stream.
  *   in, out: R x n fp32, row-major, device; may not overlap.  R == 0 or n == 0 is
  *   an empty call.  `sizes` for the host helpers: (R, n).
  */
