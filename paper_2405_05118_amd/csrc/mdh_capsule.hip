@@ -311,12 +311,8 @@ mdh_status launch_t(int QT, int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
   if (QT < 1) return MDH_ERR_UNSUPPORTED;
   if (g.lds_bytes > 160 * 1024) return MDH_ERR_TILE_RESOURCES;
   auto kern = capsule_kernel<NI, RW>;
-  static int64_t attr_bytes = 0;
-  if (g.lds_bytes > attr_bytes) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes) != hipSuccess)
-      return MDH_ERR_LAUNCH;
-    attr_bytes = g.lds_bytes;
-  }
+  static int64_t lds_allowed[kMaxDevices] = {};
+  if (allow_dynamic_lds((const void*)kern, g.lds_bytes, lds_allowed) != MDH_OK) return MDH_ERR_LAUNCH;
   const int64_t tp_n = cdiv(P, CAP_TP), tq_n = cdiv(cdiv(Q, CAP_TQ), QT), tk_n = cdiv(K, 8 * NI);
   const int64_t nblocks = N * tp_n * tq_n * tk_n;
   if (nblocks > 0x7fffffff) return MDH_ERR_SIZE;

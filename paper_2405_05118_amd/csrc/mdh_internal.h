@@ -175,4 +175,22 @@ inline mdh_status launch_status() {
   return MDH_ERR_LAUNCH;
 }
 
+
+// A kernel may use more than 64 KB of dynamic LDS only after that has been allowed, per kernel and per
+// device.  `done[dev]` remembers the largest size allowed so far on each device (one array per kernel
+// instantiation, kept by the caller); two threads racing here both set the same attribute.
+constexpr int kMaxDevices = 64;
+inline mdh_status allow_dynamic_lds(const void* kern, int64_t bytes, int64_t (&done)[kMaxDevices]) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MDH_ERR_LAUNCH;
+  if (bytes <= done[dev]) return MDH_OK;
+  const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e != hipSuccess) {
+    g_last_launch_error = e;
+    return MDH_ERR_LAUNCH;
+  }
+  done[dev] = bytes;
+  return MDH_OK;
+}
+
 }  // namespace mdh

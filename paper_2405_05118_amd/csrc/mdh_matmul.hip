@@ -262,14 +262,9 @@ template <int BM, int BN, int BK, int WM, int WN>
 mdh_status launch_t(const GemmPlan& pl, int64_t M, int64_t N, int64_t K, const float* A,
                     const float* B, float* C, void* ws, hipStream_t st) {
   using Cfg = GemmCfg<BM, BN, BK, WM, WN>;
-  static bool attr_done = false;
   auto kern = matmul_kernel<BM, BN, BK, WM, WN>;
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            Cfg::LDS_BYTES) != hipSuccess)
-      return MDH_ERR_LAUNCH;
-    attr_done = true;
-  }
+  static int64_t lds_allowed[kMaxDevices] = {};
+  if (allow_dynamic_lds((const void*)kern, Cfg::LDS_BYTES, lds_allowed) != MDH_OK) return MDH_ERR_LAUNCH;
   const int64_t tm = cdiv(M, BM), tn = cdiv(N, BN);
   const int64_t kchunk = cdiv(cdiv(K, pl.S), BK) * BK;
   const int64_t nblocks = tm * tn * pl.S;

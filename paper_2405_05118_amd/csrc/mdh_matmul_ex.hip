@@ -205,12 +205,8 @@ mdh_status launch_t(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, i
   using OpB = Operand<BN, BK, TB, NT>;
   constexpr int LDS_BYTES = 2 * (OpA::SIZE + OpB::SIZE) * 4;
   auto kern = matmul_ex_kernel<BM, BN, BK, WM, WN, TA, TB, TC>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
-      return MDH_ERR_LAUNCH;
-    attr_done = true;
-  }
+  static int64_t lds_allowed[kMaxDevices] = {};
+  if (allow_dynamic_lds((const void*)kern, LDS_BYTES, lds_allowed) != MDH_OK) return MDH_ERR_LAUNCH;
   const int S = pl.g.S;
   const int64_t tm = cdiv(M, BM), tn = cdiv(N, BN);
   const int64_t kchunk = cdiv(cdiv(K, S), BK) * BK;

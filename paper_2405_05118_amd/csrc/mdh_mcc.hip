@@ -210,13 +210,8 @@ mdh_status launch_t(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64
   const int64_t lds_bytes = (2ll * Cf::F_STAGE + PH * PW * Cf::PC) * 4;
   if (lds_bytes > 160 * 1024) return MDH_ERR_TILE_RESOURCES;
   auto kern = mcc_kernel<TP, TQ, BN, CK, WM, WN>;
-  static int64_t attr_bytes = 0;
-  if (lds_bytes > attr_bytes) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds_bytes) != hipSuccess)
-      return MDH_ERR_LAUNCH;
-    attr_bytes = lds_bytes;
-  }
+  static int64_t lds_allowed[kMaxDevices] = {};
+  if (allow_dynamic_lds((const void*)kern, lds_bytes, lds_allowed) != MDH_OK) return MDH_ERR_LAUNCH;
   const int64_t tp_n = cdiv(P, TP), tq_n = cdiv(Q, TQ), tk_n = cdiv(K, BN);
   const int64_t nblocks = N * tp_n * tq_n * tk_n;
   if (nblocks > 0x7fffffff) return MDH_ERR_SIZE;

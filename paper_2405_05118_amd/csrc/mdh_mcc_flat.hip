@@ -282,12 +282,8 @@ mdh_status launch_t(int QT, int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
   if (lds_bytes > 160 * 1024) return MDH_ERR_TILE_RESOURCES;
   if (PH * (PWF / 4) > 8 * Cf::NT) return MDH_ERR_TILE_RESOURCES;  // prefetch registers per lane
   auto kern = mcc_flat_kernel<QB, MI, NI, WAVES_M, WAVES_N>;
-  static int64_t attr_bytes = 0;
-  if (lds_bytes > attr_bytes) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
-      return MDH_ERR_LAUNCH;
-    attr_bytes = lds_bytes;
-  }
+  static int64_t lds_allowed[kMaxDevices] = {};
+  if (allow_dynamic_lds((const void*)kern, lds_bytes, lds_allowed) != MDH_OK) return MDH_ERR_LAUNCH;
   const int64_t tp_n = cdiv(P, Cf::TP), tq_n = cdiv(cdiv(Q, Cf::TQ), QT), tk_n = cdiv(K, Cf::BN);
   const int64_t nblocks = N * tp_n * tq_n * tk_n;
   if (nblocks > 0x7fffffff) return MDH_ERR_SIZE;
