@@ -37,7 +37,7 @@ template <int QB, int MI, int NI, int WAVES_M, int WAVES_N>
 __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
     const float* __restrict__ in, const float* __restrict__ filt, float* __restrict__ out, int H,
     int W, int C, int K, int R, int S, int sh, int sw, int P, int Q, int tp_n, int tq_n, int tk_n,
-    int SCP, int PWF, int PFR, int QT, int pstep_rows, int pstep_x4) {
+    int SCP, int PWF, int PFR, int QT, int pstep_rows, int pstep_x4, int64_t in_elems) {
   using Cf = FlatCfg<QB, MI, NI, WAVES_M, WAVES_N>;
   extern __shared__ __attribute__((aligned(16))) float lds[];
   const int tid = threadIdx.x;
@@ -138,13 +138,19 @@ __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
       v[i] = (f4){0.f, 0.f, 0.f, 0.f};
       if (poff[i] >= 0 && phy[i] < H) {
         const int gx = q0 * sw * C + pgx[i];
-        const float* src = in + ((int64_t)n * H + phy[i]) * WC + gx;
-        if (gx + 3 < WC) {
-          v[i] = *(const f4u*)src;
-        } else {
+        const int64_t off = ((int64_t)n * H + phy[i]) * WC + gx;
+        if (gx < WC) {
+          if (off + 3 < in_elems) {
+            // a piece that straddles the end of an image row is still one 16-byte load (the next
+            // row follows in memory); the elements beyond the row read as 0
+            const f4 t = *(const f4u*)(in + off);
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (gx + e < WC) v[i][e] = src[e];
+            for (int e = 0; e < 4; ++e) v[i][e] = gx + e < WC ? t[e] : 0.f;
+          } else {  // the last few elements of the whole buffer
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (gx + e < WC) v[i][e] = in[off + e];
+          }
         }
       }
     }
@@ -204,7 +210,7 @@ __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
           for (int ni = 0; ni < NI; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi][e], bf[ni][e], acc[mi][ni], 0, 0, 0);
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(bf[ni][e], af[mi][e], acc[mi][ni], 0, 0, 0);
     };
     {
       const int nsteps = R * (SCP >> 3);
@@ -243,21 +249,28 @@ __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
     }
 
     // output view (n,p,q,k,0,0,0) -> out[n,p,q,k]; the buffer has fewer than 2^31 elements (checked
-    // by the caller), so 32-bit offsets are exact
+    // by the caller), so 32-bit offsets are exact.  The filter is the row operand of the MFMA: the
+    // lane's pixel is l32 and registers 4g..4g+3 hold channels 8g + 4*lh + (0..3) of the block, one
+    // 16-byte store (four times fewer store instructions than with one channel per lane).
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
-      const int prow = p0 + (wm * MI + mi) * Cf::RB;
+      const int p = p0 + (wm * MI + mi) * Cf::RB + dp, q = q0 + dq;
+      if (p >= P || q >= Q) continue;
+      float* o = obase + (p * Q + q) * K;
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni) {
-        const int k = k0 + (wn * NI + ni) * 32 + l32;
-        if (k >= K) continue;
+      for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-        for (int rg = 0; rg < 16; ++rg) {
-          const int m = 8 * (rg / 4) + 4 * lh + (rg % 4);  // pixel of the block this register holds
-          const int p = prow + m / QB, q = q0 + m % QB;
-          if (p < P && q < Q) obase[(p * Q + q) * K + k] = acc[mi][ni][rg];
+        for (int g = 0; g < 4; ++g) {
+          const int k = k0 + (wn * NI + ni) * 32 + 8 * g + 4 * lh;
+          if (k + 3 < K) {
+            *(f4u*)(o + k) = (f4){acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1], acc[mi][ni][4 * g + 2],
+                                  acc[mi][ni][4 * g + 3]};
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (k + e < K) o[k + e] = acc[mi][ni][4 * g + e];
+          }
         }
-      }
     }
 
     // the next tile's patch goes to the other buffer (its last readers passed the barrier of the
@@ -291,7 +304,7 @@ mdh_status launch_t(int QT, int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
   hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cf::NT), (size_t)lds_bytes, st, in, filt, out,
                      (int)H, (int)W, (int)C, (int)K, (int)R, (int)S, (int)sh, (int)sw, (int)P, (int)Q,
                      (int)tp_n, (int)tq_n, (int)tk_n, (int)SCP, (int)PWF, (int)PFR, QT,
-                     (int)(Cf::NT / (PWF / 4)), (int)(Cf::NT % (PWF / 4)));
+                     (int)(Cf::NT / (PWF / 4)), (int)(Cf::NT % (PWF / 4)), N * H * W * C);
   return launch_status();
 }
 

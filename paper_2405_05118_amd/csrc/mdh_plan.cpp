@@ -397,19 +397,16 @@ static int flat_qt(const int64_t* s, const MccPlan& pl, int want) {
 }
 
 static MccPlan mcc_flat_plan(const int64_t* s) {
-  // Measured on the first-layer shapes of ResNet-50, VGG-16 and MobileNet.
-  // Many taps (7 x 7 x 3): the filter slice is the larger part of what a workgroup stages, so a
-  // workgroup keeps it and walks a whole row of column tiles (56 us against 64 us); 32 channels per
-  // workgroup (more workgroups, each stages half the filter); blocks of 8 x 16 pixels where 16
-  // divides Q and 32 does not (Q = 112).
-  // Few taps (3 x 3 x 3): the output write dominates; blocks of 4 x 32 pixels, one tile per
-  // workgroup, and 64 channels per workgroup so that whole 256-byte pixels are written (78 us
-  // against 93 us).
-  const bool many_taps = s[4] * s[5] * s[6] >= 64;
+  // Measured on the first-layer shapes of ResNet-50, VGG-16 and MobileNet: 32 channels per
+  // workgroup up to K = 64 (more workgroups, each stages a smaller filter slice; a lane stores 16
+  // bytes of a pixel, so narrow channel slices still write whole 128-byte lines), a workgroup keeps
+  // its filter slice and walks up to 8 column tiles (ResNet-50: 56 us against 64 us with one tile;
+  // VGG-16: 66 us against 80 us with 64 channels), blocks of 8 x 16 pixels where 16 divides Q and
+  // 32 does not (Q = 112), of 4 x 32 pixels otherwise.
   const int qb = (s[2] % 32 != 0 && s[2] % 16 == 0) ? 16 : 32;
   const int tp = qb == 16 ? 8 : 4;
   MccPlan pl{tp, qb, 32, 0, 32, 32, 0, 1};
-  if (s[3] > 64 || (s[3] > 32 && !many_taps)) pl = MccPlan{tp, qb, 64, 0, 32, 64, 0, 1};
+  if (s[3] > 64) pl = MccPlan{tp, qb, 64, 0, 32, 64, 0, 1};
   pl.QT = flat_qt(s, pl, 8);
   pl.ragged = mcc_ragged(s, pl);
   return pl;
