@@ -229,20 +229,27 @@ static GemmPlan gemm_default(const int64_t* s) {
   // Tile: the largest of 128x128, 128x64, 64x64 that still gives two workgroups per compute unit
   // (measured best at 4096^3, 2048^3 and 1024^3 respectively); narrow problems keep 128x64 / 64x64.
   GemmPlan pl{128, 128, 32, 64, 64, 1, 0};
-  if (N <= 64 || M <= 64) {
-    pl = GemmPlan{128, 64, 32, 64, 32, 1, 0};
+  const bool narrow = N <= 64 || M <= 64;
+  if (narrow) {
+    // one tile spans the short dimension.  Measured (65536 x 64 x 4096 / 16384 x 64 x 4096 /
+    // 64 x 65536 x 1024): 128x64 tiles only where they still give two workgroups per compute unit
+    // (0.312 against 0.327 ms), 64x64 tiles otherwise (0.085 against 0.088 ms; 0.087 against 0.19 ms
+    // when M = 64 would leave half of a 128-row tile empty)
+    pl = GemmPlan{64, 64, 32, 32, 32, 1, 0};
+    if (M > 64 && cdiv(M, 128) * cdiv(N, 64) >= 512) pl = GemmPlan{128, 64, 32, 64, 32, 1, 0};
   } else if (cdiv(M, 128) * cdiv(N, 128) < 512) {
     pl = GemmPlan{128, 64, 32, 64, 32, 1, 0};
     if (cdiv(M, 128) * cdiv(N, 64) < 512) pl = GemmPlan{64, 64, 32, 32, 32, 1, 0};
   }
-  if (M <= 64 && N <= 64) pl = GemmPlan{64, 64, 32, 32, 32, 1, 0};
   // Split the reduction dimension over workgroups only while there is less than one workgroup per
-  // compute unit AND every part keeps at least 8 k-tiles: below that the second pass and the
-  // shortened pipelines cost more than the parallelism gains (256^3 is fastest unsplit, 8.7 us
-  // against 14.6 us with 16 parts; 256 x 256 x 4096 is fastest with 16 parts).
+  // compute unit (two for the narrow shapes, whose tiles are small) AND every part keeps at least 8
+  // k-tiles: below that the second pass and the shortened pipelines cost more than the parallelism
+  // gains (256^3 is fastest unsplit, 8.7 us against 14.6 us with 16 parts; 256 x 256 x 4096 is
+  // fastest with 16 parts; 8192 x 64 x 4096 with 4 parts: 0.046 against 0.089 ms unsplit).
   const int64_t tiles = cdiv(M, pl.BM) * cdiv(N, pl.BN);
+  const int64_t want = narrow ? 512 : 256;
   int S = 1;
-  while (tiles * S < 256 && S < 64 && K / (S * 2) >= 8 * pl.BK) S *= 2;
+  while (tiles * S < want && S < 64 && K / (S * 2) >= 8 * pl.BK) S *= 2;
   pl.S = S;
   pl.ragged = gemm_ragged(s, pl);
   return pl;
