@@ -31,7 +31,7 @@ typedef float f16 __attribute__((ext_vector_type(16)));
 
 constexpr int CAP_TP = 4, CAP_TQ = 8;
 
-template <int NI, int RW>
+template <int NI, int RW, int CAP_PV>
 __global__ __launch_bounds__(256 * RW) void capsule_kernel(const float* __restrict__ in,
                                                          const float* __restrict__ filt,
                                                          float* __restrict__ out, int H, int W, int C,
@@ -71,8 +71,8 @@ __global__ __launch_bounds__(256 * RW) void capsule_kernel(const float* __restri
   // fixed amount (CAP_NT = pstep_rows*pw4 + pstep_x, from the host), so only one division is needed.
   // The pieces of the NEXT tile are requested before the MFMA walk of the current one and are
   // written to LDS after it: the HBM/L2 latency hides behind the walk.  Pieces beyond CAP_PV per
-  // lane (very wide patches) are staged directly.
-  constexpr int CAP_PV = 16;
+  // lane (very wide patches) are staged directly.  CAP_PV is 8 or 16: the smaller one saves registers
+  // (a second workgroup per compute unit for short walks).
   const int pw4 = PWF >> 2;
   const int npieces = PH * pw4;
   const int pv_n = (npieces + CAP_NT - 1) / CAP_NT;  // pieces per lane (workgroup-uniform)
@@ -302,15 +302,15 @@ CapGeom geom(int NI, int RW, int64_t C, int64_t R, int64_t S, int64_t sh, int64_
   return g;
 }
 
-template <int NI, int RW>
-mdh_status launch_t(int QT, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+template <int NI, int RW, int PV>
+mdh_status launch_pv(int QT, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
                     int64_t sh, int64_t sw, const float* in, const float* filt, float* out,
                     hipStream_t st) {
   const int64_t P = (H - R) / sh + 1, Q = (W - S) / sw + 1;
   const CapGeom g = geom(NI, RW, C, R, S, sh, sw);
   if (QT < 1) return MDH_ERR_UNSUPPORTED;
   if (g.lds_bytes > 160 * 1024) return MDH_ERR_TILE_RESOURCES;
-  auto kern = capsule_kernel<NI, RW>;
+  auto kern = capsule_kernel<NI, RW, PV>;
   static int64_t lds_allowed[kMaxDevices] = {};
   if (allow_dynamic_lds((const void*)kern, g.lds_bytes, lds_allowed) != MDH_OK) return MDH_ERR_LAUNCH;
   const int64_t tp_n = cdiv(P, CAP_TP), tq_n = cdiv(cdiv(Q, CAP_TQ), QT), tk_n = cdiv(K, 8 * NI);
@@ -322,6 +322,17 @@ mdh_status launch_t(int QT, int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
                      (int)tp_n, (int)tq_n, (int)tk_n, (int)g.J2, (int)g.PWF, (int)g.PFR, QT,
                      (int)((256 * RW) / (g.PWF / 4)), (int)((256 * RW) % (g.PWF / 4)));
   return launch_status();
+}
+
+template <int NI, int RW>
+mdh_status launch_t(int QT, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                    int64_t sh, int64_t sw, const float* in, const float* filt, float* out,
+                    hipStream_t st) {
+  // 16-byte pieces of the input patch per lane: up to 8 take the instantiation with fewer registers
+  const CapGeom g = geom(NI, RW, C, R, S, sh, sw);
+  const int64_t pieces = ((CAP_TP - 1) * sh + R) * (g.PWF / 4);
+  if (pieces <= 8 * 256 * RW) return launch_pv<NI, RW, 8>(QT, N, H, W, C, K, R, S, sh, sw, in, filt, out, st);
+  return launch_pv<NI, RW, 16>(QT, N, H, W, C, K, R, S, sh, sw, in, filt, out, st);
 }
 
 }  // namespace

@@ -68,14 +68,15 @@ static CapsulePlan cap_plan(const int64_t* s, int ni, int qt, int rw) {
 }
 
 static CapsulePlan cap_default(const int64_t* s) {
-  // Measured: one block of 8 channels per wavefront is fastest throughout (more workgroups, and
-  // short walks then fit two workgroups per compute unit); long walks (7x7x3 taps: 77 steps) gain
-  // from splitting the walk over two wavefronts, short ones (3x3x3: 15 steps) do not.  Column tiles
-  // per workgroup: as many as leave one workgroup per compute unit (the filter slice is staged once
-  // per workgroup).
+  // Measured: long walks (7x7x3 taps: 77 steps) are fastest with one block of 8 channels per
+  // wavefront and the walk split over two wavefronts (2.09 ms against 2.31 ms unsplit); short ones
+  // (3x3x3: 15 steps) unsplit, with four blocks per wavefront where K gives every workgroup 32
+  // channels (VGG-16 shape: 1.52 ms against 1.61 ms with one block), else one block (MobileNet
+  // shape, K = 32: 0.24 ms against 0.26 ms with four).  Column tiles per workgroup: as many as leave
+  // one workgroup per compute unit (the filter slice is staged once per workgroup).
   const bool long_walk = s[5] * cdiv(s[6] * s[4], 2) >= 32;
   const int rw = long_walk && cap_fits(s, 1, 2) ? 2 : 1;
-  const int ni = 1;
+  const int ni = !long_walk && s[3] >= 64 && cap_fits(s, 4, 1) ? 4 : 1;
   const int64_t tiles = cdiv(s[2] > 0 ? s[2] : 1, 8);
   const int64_t other = (s[0] > 0 ? s[0] : 1) * cdiv(s[1] > 0 ? s[1] : 1, 4) * cdiv(s[3] > 0 ? s[3] : 1, 8 * ni);
   int qt = 1;
