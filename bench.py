@@ -37,22 +37,22 @@ PRL_LANE_OPS_PER_PAIR = 24.0
 # None until measured for that workload
 TRAFFIC_BYTES = {
     # profiles/all_kernels_hbm_traffic_pmc.md (all kernels of a step)
-    "jacobi3d_512": 1110163269,
-    "dot_2p28": 2147375902,
-    "matvec_16384": 1074468403,
-    "matmul_4096": 604071873,
-    "matmul_ts": 1102124984,
-    "mcc_resnet": 851149055,
-    "prl_2p16_2p18": 141568317,
-    "matmul_256": 1927901,
-    "mcc_resnet50_first": 62419780,
-    "matmul_resnet50_fc": 13577187,
-    "matmul_vgg16_fc": 426313864,
-    "mcc_capsule_resnet50_first": 1072686443,
-    "scan_2p28": 2152163098,
-    "scan_rows_65536x4096": 2147463171,
-    "histo_generic_256x2p24": 67263830,
-    "prl_generic_2p16_2p18": 145818854,
+    "jacobi3d_512": 1109526921,
+    "dot_2p28": 2147370376,
+    "matvec_16384": 1074464598,
+    "matmul_4096": 604064760,
+    "matmul_ts": 1102176441,
+    "mcc_resnet": 851257770,
+    "prl_2p16_2p18": 141517981,
+    "matmul_256": 1939160,
+    "mcc_resnet50_first": 62431965,
+    "matmul_resnet50_fc": 13577153,
+    "matmul_vgg16_fc": 426312877,
+    "mcc_capsule_resnet50_first": 1072647463,
+    "scan_2p28": 2153124757,
+    "scan_rows_65536x4096": 2147466353,
+    "histo_generic_256x2p24": 67263654,
+    "prl_generic_2p16_2p18": 145818449,
 }
 
 

@@ -80,7 +80,7 @@ static CapsulePlan cap_default(const int64_t* s) {
   const int64_t tiles = cdiv(s[2] > 0 ? s[2] : 1, 8);
   const int64_t other = (s[0] > 0 ? s[0] : 1) * cdiv(s[1] > 0 ? s[1] : 1, 4) * cdiv(s[3] > 0 ? s[3] : 1, 8 * ni);
   int qt = 1;
-  while (qt < tiles && other * cdiv(tiles, qt * 2) >= 256) qt *= 2;
+  while (qt < tiles && qt < 16 && other * cdiv(tiles, qt * 2) >= 256) qt *= 2;  // beyond ~16 tiles nothing is gained
   return cap_plan(s, ni, qt, rw);
 }
 
