@@ -158,6 +158,27 @@ def test_long_row_and_explicit_chunks():
 
 
 @pytest.mark.gpu
+def test_full_size_row_exact():
+    """One row of 2^28 elements, the configuration bench.py times: a 1 at every 16th position keeps
+    every partial sum an integer below 2^24, so each order of additions gives the same exact result."""
+    n = 1 << 28
+    shape = (1, n)
+    x = torch.zeros(n, dtype=torch.float32, device="cuda")
+    x[::16] = 1.0
+    out = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+    p = mdh.mdh_default_params(mdh.MDH_SCAN, shape)
+    assert p.prt[B.L_WG][1] > 1 and p.in_region[0] == B.MR_VGPR  # chunks over workgroups, single pass
+    ws = torch.empty(mdh.mdh_workspace_size(mdh.MDH_SCAN, shape, p) // 8, dtype=torch.int64, device="cuda")
+    mdh.mdh_scan(x, out, None, ws)
+    torch.cuda.synchronize()
+    step = 1 << 24
+    for j0 in range(0, n, step):  # expected values chunk by chunk (device memory)
+        want = (torch.arange(j0, j0 + step, device="cuda", dtype=torch.int64) // 16 + 1).to(torch.float32)
+        assert torch.equal(out[j0:j0 + step], want), j0
+    assert int(ws[1].item()) == 0  # no wait ran into its bound
+
+
+@pytest.mark.gpu
 def test_tune_picks_a_valid_configuration():
     shape = (4, 200000)
     x = W.uniform(W.SEED_BASE + 97, 1, shape, -1, 1)
