@@ -379,7 +379,7 @@ def bench_capsule(torch, mdh, W, name, steps, warmup, cpu):
 
 
 def bench_scan(torch, mdh, W, name, steps, warmup, cpu):
-    """Row-wise scan(+): one long row (chunks over workgroups, three kernels) or many rows (one pass)."""
+    """Row-wise scan(+): one long row (chunks over workgroups) or many rows (a workgroup per row)."""
     R, n = (1, 1 << 28) if name == "scan_2p28" else (65536, 4096)
     seed = W.SEED_BASE + 12
     x = W.device_uniform(seed, 1, (R, n), -1.0, 1.0)
@@ -390,14 +390,17 @@ def bench_scan(torch, mdh, W, name, steps, warmup, cpu):
     nbytes = 8 * R * n  # every element read once and written once
     gbs = nbytes / ms / 1e6
     chunks = int(p.prt[3][1])
+    single_pass = chunks > 1 and int(p.in_region[0]) == 2  # the chunk waits in registers (MDH_MR_VGPR)
     res = {
         "value": nbytes / wall / 1e6, "unit": "GB/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "f32",
-        "kernel": "scan_apply_kernel" + (" + scan_totals_kernel + scan_offsets_kernel" if chunks > 1 else ""),
+        "kernel": ("scan_apply_kernel" if chunks == 1 else
+                   "scan_onepass_init_kernel + scan_onepass_kernel (single pass)" if single_pass else
+                   "scan_totals_kernel + scan_offsets_kernel + scan_apply_kernel"),
         "rows": R, "n": n, "chunks_per_row": chunks,
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES.get(name)},
         "algorithmic_bytes": nbytes,
-        "kernel_bytes": nbytes + (4 * R * n if chunks > 1 else 0),  # chunked rows read the input twice
+        "kernel_bytes": nbytes + (4 * R * n if chunks > 1 and not single_pass else 0),  # three kernels read the input twice
     }
     if cpu:
         import oracle

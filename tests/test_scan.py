@@ -179,6 +179,29 @@ def test_full_size_row_exact():
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("shape", [(1, 1 << 28), (65536, 4096)])
+def test_full_size_random(shape):
+    """The two shapes bench.py times, its inputs, library defaults; the oracle scans a copy of the
+    device data and every element is compared (scaled by the prefix sum of |x|)."""
+    x = W.device_uniform(W.SEED_BASE + 12, 1, shape, -1.0, 1.0)
+    out = torch.full_like(x, float("nan"))
+    n = mdh.mdh_workspace_size(mdh.MDH_SCAN, shape)
+    ws = torch.empty(max(n, 8) // 8, dtype=torch.float64, device="cuda") if n else None
+    mdh.mdh_scan(x, out, None, ws)
+    torch.cuda.synchronize()
+    ref, refabs = oracle.scan_rows(x.cpu().numpy(), with_abs=True)
+    got = out.cpu().numpy()
+    del x, out
+    worst = 0.0
+    rows = ref.shape[0]
+    for r0 in range(0, rows, 4096):  # in slabs: the whole difference would double the memory
+        for c0 in range(0, ref.shape[1], 1 << 24):
+            sl = (slice(r0, r0 + 4096), slice(c0, c0 + (1 << 24)))
+            worst = max(worst, float(np.max(np.abs(got[sl] - ref[sl]) / refabs[sl])))
+    assert worst <= TOL, worst
+
+
+@pytest.mark.gpu
 def test_tune_picks_a_valid_configuration():
     shape = (4, 200000)
     x = W.uniform(W.SEED_BASE + 97, 1, shape, -1, 1)
