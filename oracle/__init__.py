@@ -211,6 +211,15 @@ def custom_reduce_rows(A, B, w_agree, w_disagree, rows):
     return score, index
 
 
+def histo(elems, bins):
+    """Histo (md_hom(f_Histo, (++, +)) over (bins, elements)): out[b] = number of elements equal to
+    bins[b], as int64."""
+    elems, bins = _i32a(elems), _i32a(bins)
+    out = np.empty(len(bins), dtype=np.int64)
+    _load().oracle_histo(_i64(len(bins)), _i64(len(elems)), _p(elems), _p(bins), _p(out))
+    return out
+
+
 def maxidx_combine(s1, b1, s2, b2):
     s1, b1 = _i32a(s1).copy(), _i32a(b1).copy()
     s2, b2 = _i32a(s2), _i32a(b2)

@@ -254,6 +254,19 @@ void oracle_scan_rows(int64_t R, int64_t n, const float* x, double* out, double*
   }
 }
 
+/* ---- Histo: md_hom(f_Histo, (++, +)) over (b, e), f_Histo(e, b) = 1 if the element equals the
+ * bin value, else 0 (Section "Examples", Subfigures 4-6; Appendix on GenHisto: work E*B, every
+ * element is compared with every bin).  Input views (b,e)->elems[e], (b,e)->bins[b]; output view
+ * (b,0)->out[b].  Written as the definition: the ++ dimension outside, the + dimension inside. */
+void oracle_histo(int64_t nB, int64_t nE, const int32_t* elems, const int32_t* bins, int64_t* out) {
+#pragma omp parallel for schedule(static)
+  for (int64_t b = 0; b < nB; ++b) {
+    int64_t acc = 0;
+    for (int64_t e = 0; e < nE; ++e) acc += elems[e] == bins[b] ? 1 : 0;
+    out[b] = acc;
+  }
+}
+
 /* ---- MCC_Capsule: the 10-dimensional generalisation of MCC that operates on MI x MK and MK x MJ
  * matrices instead of scalars (Section "Examples", Subfigure 2; Appendix "Data Characteristics
  * used in Deep Neural Networks": three more dimensions MI, MJ, MK).  Reading of the missing figure:

@@ -66,6 +66,26 @@ def d_prl(nA, nB):
                            PRL_F, PRL_OP, PRL_PRE, fast_dim=0)
 
 
+def test_compiled_histo_oracle_pins():
+    """The C version of the Histo definition (used for large inputs): against the generic evaluator
+    on small inputs, and closed forms (every element in one bin; bins absent from the data;
+    duplicate bin values count the same elements; the counts of distinct bins that cover the data
+    add up to the number of elements)."""
+    import oracle
+
+    rng = np.random.default_rng(5)
+    elems = rng.integers(0, 9, size=200).astype(np.int32)
+    bins = np.array([3, 0, 8, 8, 11, 5], dtype=np.int32)
+    assert oracle.histo(elems, bins).tolist() == G.histo(elems.tolist(), bins.tolist())
+    assert oracle.histo(np.full(1000, 4, np.int32), np.array([4, 5], np.int32)).tolist() == [1000, 0]
+    assert oracle.histo(np.empty(0, np.int32), np.array([1, 2], np.int32)).tolist() == [0, 0]
+    big = rng.integers(0, 256, size=100000).astype(np.int32)
+    counts = oracle.histo(big, np.arange(256, dtype=np.int32))
+    assert int(counts.sum()) == big.size and counts.dtype == np.int64
+    # a planted mistake: comparing with the bin's position instead of its value
+    assert oracle.histo(np.array([7, 7, 2], np.int32), np.array([2, 7], np.int32)).tolist() == [1, 2]
+
+
 def d_histo(nbins, ne):
     return mdh.custom_desc((nbins, ne), (0, 1), ["int", "int"], [(0, "i1"), (1, "i0")], "int", 4,
                            "r = a0 == a1 ? 1 : 0;", "r = x + y;")
@@ -387,3 +407,27 @@ def test_high_dimensional_instances_through_the_generic_path():
                         "r.s = x.s + y.s; r.m = x.m > y.m ? x.m : y.m;", "struct pr { int s; int m; };")
     got = run(d, [dev(v)], torch.zeros(2, dtype=torch.int32, device="cuda"))
     assert got.cpu().tolist() == [int(v.sum()), int(v.max())]
+
+
+@pytest.mark.gpu
+def test_bench_sizes_against_the_oracle():
+    """The two workloads bench.py runs through the generic path, at its sizes, inputs and default
+    configuration: Histo 256 bins x 2^24 elements (every bin against the compiled oracle) and the
+    custom reduce 2^16 x 2^18 (sampled records against the compiled oracle), bit-exact."""
+    nb, ne = 256, 1 << 24
+    elems = W.device_integers(W.SEED_BASE + 13, 1, (ne,), 0, nb - 1)
+    bins = torch.arange(nb, dtype=torch.int32, device="cuda")
+    got = run(d_histo(nb, ne), [elems, bins], torch.full((nb,), -1, dtype=torch.int32, device="cuda"))
+    want = oracle.histo(elems.cpu().numpy(), bins.cpu().numpy())
+    assert np.array_equal(got.cpu().numpy().astype(np.int64), want) and int(want.sum()) == ne
+
+    cfg = W.CONFIGS["prl_2p16_2p18"]
+    alph = W.prl_alphabets(cfg.nF)
+    A = torch.stack([W.device_integers(cfg.seed, 1 + 2 * f, (cfg.nA,), 0, a - 1) for f, a in enumerate(alph)], 1).contiguous()
+    Bm = torch.stack([W.device_integers(cfg.seed, 2 + 2 * f, (cfg.nB,), 0, a - 1) for f, a in enumerate(alph)], 1).contiguous()
+    wp = W.device_integers(cfg.seed, 40, (cfg.nF,), 1, W.PRL_WEIGHT_MAX)
+    wm = W.device_integers(cfg.seed, 41, (cfg.nF,), -W.PRL_WEIGHT_MAX, 0)
+    got = run(d_prl(cfg.nA, cfg.nB), [A, Bm, wp, wm], torch.full((cfg.nA, 2), -1, dtype=torch.int32, device="cuda")).cpu().numpy()
+    rows = np.unique(np.concatenate([np.random.default_rng(11).integers(0, cfg.nA, 500), [0, cfg.nA - 1]])).astype(np.int64)
+    sc, ix = oracle.custom_reduce_rows(A.cpu().numpy(), Bm.cpu().numpy(), wp.cpu().numpy(), wm.cpu().numpy(), rows)
+    assert np.array_equal(got[rows, 0], sc) and np.array_equal(got[rows, 1], ix)
