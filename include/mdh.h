@@ -416,11 +416,12 @@ mdh_status mdh_candidate(mdh_instance inst, const int64_t* sizes, int32_t idx,
  *
  * mdh_custom_create compiles (host only: works without a GPU) and returns an
  * operation handle; `log` (may be NULL) receives the compiler's messages.  The
- * first mdh_custom_run on a process loads the code object (the only allocation the
- * runtime makes on behalf of this library); after that a run only enqueues one or
- * two kernels.  inputs[b] / output / workspace are device pointers; the workspace
+ * first mdh_custom_run of a handle loads the code object on the current device (the
+ * only allocation the runtime makes on behalf of this library; a handle stays with
+ * that device); after that a run only enqueues one or two kernels.  inputs[b] / output / workspace are device pointers; the workspace
  * needs mdh_custom_workspace_size(op) bytes (0 if no reduced dimension is split
- * over workgroups).  Handles are not thread-safe.
+ * over workgroups).  Runs of one handle may be issued from several threads; create
+ * and destroy are the caller's to order.
  * Errors: MDH_ERR_NULL, MDH_ERR_SIZE (D, n_in, n_acc, sizes out of range),
  * MDH_ERR_UNSUPPORTED (source does not compile: see log), MDH_ERR_WORKSPACE,
  * MDH_ERR_LAUNCH, and the tile errors above.

@@ -20,6 +20,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -651,6 +652,7 @@ struct mdh_custom_op {
   int out_bytes;
   std::string source;
   std::vector<char> code;
+  std::mutex load_mutex;  // the first run loads the code object; concurrent first runs wait here
   hipModule_t module = nullptr;
   hipFunction_t fmain = nullptr, fcombine = nullptr;
 };
@@ -753,15 +755,25 @@ mdh_status mdh_custom_run(mdh_custom_op* op, const void* const* inputs, void* ou
   const CustomPlan& pl = op->plan;
   if (pl.SG > 1 && (!workspace || workspace_bytes < mdh_custom_workspace_size(op))) return MDH_ERR_WORKSPACE;
   clear_stale_error();
-  if (!op->module) {
-    if (hipModuleLoadData(&op->module, op->code.data()) != hipSuccess) {
-      launch_status();
-      return MDH_ERR_LAUNCH;
-    }
-    if (hipModuleGetFunction(&op->fmain, op->module, "mdh_custom_main") != hipSuccess ||
-        hipModuleGetFunction(&op->fcombine, op->module, "mdh_custom_combine") != hipSuccess) {
-      launch_status();
-      return MDH_ERR_LAUNCH;
+  {
+    std::lock_guard<std::mutex> lock(op->load_mutex);
+    if (!op->module) {
+      // the handle only becomes "loaded" once both kernels have been found
+      hipModule_t mod = nullptr;
+      hipFunction_t fm = nullptr, fc = nullptr;
+      if (hipModuleLoadData(&mod, op->code.data()) != hipSuccess) {
+        launch_status();
+        return MDH_ERR_LAUNCH;
+      }
+      if (hipModuleGetFunction(&fm, mod, "mdh_custom_main") != hipSuccess ||
+          hipModuleGetFunction(&fc, mod, "mdh_custom_combine") != hipSuccess) {
+        launch_status();
+        hipModuleUnload(mod);
+        return MDH_ERR_LAUNCH;
+      }
+      op->fmain = fm;
+      op->fcombine = fc;
+      op->module = mod;
     }
   }
   const void* in[MDH_CUSTOM_MAX_IN];
