@@ -202,7 +202,11 @@ mdh_status mdh_tune(mdh_instance inst, const int64_t* sizes, void* const* buffer
   const int n = mdh_num_candidates(inst, sizes);
   if (n <= 0) return MDH_ERR_UNSUPPORTED;
   hipEvent_t e0, e1;
-  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return MDH_ERR_LAUNCH;
+  if (hipEventCreate(&e0) != hipSuccess) return MDH_ERR_LAUNCH;
+  if (hipEventCreate(&e1) != hipSuccess) {
+    hipEventDestroy(e0);
+    return MDH_ERR_LAUNCH;
+  }
   float best_t = -1.f;
   mdh_status last = MDH_ERR_UNSUPPORTED;
   for (int c = 0; c < n; ++c) {

@@ -812,7 +812,11 @@ mdh_status mdh_custom_tune(const mdh_custom_desc* desc, const void* const* input
   int n = candidates(desc, c, 64);
   if (max_candidates > 0 && n > max_candidates) n = max_candidates;
   hipEvent_t e0, e1;
-  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return MDH_ERR_LAUNCH;
+  if (hipEventCreate(&e0) != hipSuccess) return MDH_ERR_LAUNCH;
+  if (hipEventCreate(&e1) != hipSuccess) {
+    hipEventDestroy(e0);
+    return MDH_ERR_LAUNCH;
+  }
   float best_t = -1.f;
   mdh_status last = MDH_ERR_UNSUPPORTED;
   for (int i = 0; i < n; ++i) {
