@@ -270,9 +270,11 @@ mdh_status mdh_mcc_capsule(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K
  * Example "Prefix-Sum").  The prefix-sum operator keeps the dimension and a part
  * needs ONE value of the parts before it (their last prefix); that value is
  * passed lane -> wavefront (registers) -> workgroup (LDS) -> sequential tiles
- * (a carry) -> and, if prt[MDH_L_WG][j] = C > 1, across workgroups, in one of
+ * (a carry; rows of up to 8 tiles can instead stay in registers as register-layer
+ * parts) -> and, if prt[MDH_L_WG][j] = C > 1, across workgroups, in one of
  * two ways that the table tells apart by in_region[0]:
- *   MDH_MR_VGPR  single pass: a chunk (2, 4 or 8 tiles) waits in registers while
+ *   MDH_MR_VGPR  single pass: a chunk (1, 2, 4 or 8 tiles, register-layer parts:
+ *                prt[MDH_L_VGPR][j] = 4 * tiles, prt[MDH_L_HBM][j] = 1) waits in registers while
  *                the workgroups exchange chunk totals, and sums of 64 totals,
  *                through `workspace`; 8 bytes of HBM traffic per element.  Chunk
  *                numbers are handed out in the order in which workgroups start,

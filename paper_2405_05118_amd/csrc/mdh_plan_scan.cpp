@@ -1,7 +1,8 @@
 // Planner for the row-wise scan: md_hom(id, (++, prefix-sum(+))) over (i, j)
 // (paper: Section "Examples", Subfigure 8; Appendix, Example "Prefix-Sum").
-// Table: a workgroup owns one row i and one chunk of j; the chunk is TPC sequential tiles
-// (HBM-layer parts) of WAVES wavefronts x 64 lanes x 4 consecutive elements; blocked assignment
+// Table: a workgroup owns one row i and one chunk of j; the chunk is TPC tiles of WAVES wavefronts
+// x 64 lanes x 4 consecutive elements, walked one after the other with a carry (HBM-layer parts) or
+// all held in registers (register-layer parts: single pass over long rows, short rows); blocked assignment
 // (a part of j is a contiguous range, so that a part's result only needs ONE value of the parts
 // before it: their last prefix).
 #include <string.h>
@@ -14,7 +15,7 @@ using namespace detail;
 static const int kScanWaves[] = {4, 8, 16};
 // single-pass variant (the chunk stays in registers): tiles per chunk are a template parameter
 static const int kOnePassWaves[] = {8, 16};
-static const int kOnePassTpc[] = {2, 4, 8};  // 5 registers per tile and lane
+static const int kOnePassTpc[] = {1, 2, 4, 8};  // 5 registers per tile and lane
 
 void params_from_plan(const int64_t* s, const ScanPlan& pl, mdh_tile_params* p) {
   clear_params(p, 2);
@@ -24,10 +25,15 @@ void params_from_plan(const int64_t* s, const ScanPlan& pl, mdh_tile_params* p) 
     p->prt[MDH_L_WAVE][0] = 4;
   }
   p->prt[MDH_L_WG][1] = pl.C;
-  p->prt[MDH_L_HBM][1] = pl.TPC;
   p->prt[MDH_L_WAVE][1] = pl.WAVES;
   p->prt[MDH_L_LANE][1] = 64;
-  p->prt[MDH_L_VGPR][1] = 4;
+  if (pl.onepass) {  // the TPC tiles of a chunk are register-layer parts: a lane holds 4 * TPC elements
+    p->prt[MDH_L_HBM][1] = 1;
+    p->prt[MDH_L_VGPR][1] = 4 * pl.TPC;
+  } else {  // sequential tiles with a carry, 4 elements of a lane in registers at a time
+    p->prt[MDH_L_HBM][1] = pl.TPC;
+    p->prt[MDH_L_VGPR][1] = 4;
+  }
   static const int dims[2] = {0, 1};
   set_order(p, dims);
   p->strided = 0;
@@ -59,7 +65,11 @@ static ScanPlan scan_onepass_plan(const int64_t* s, int waves, int tpc) {
   ScanPlan pl{waves, tpc, 1, 0, 1};
   const int64_t tiles = cdiv(s[1] > 0 ? s[1] : 1, (int64_t)waves * 256);
   pl.C = (int)cdiv(tiles, tpc);
-  if (pl.C <= 1) pl.onepass = 0;  // a single chunk needs no exchange
+  if (pl.C <= 1) {  // the whole row in one workgroup's registers: as few tiles as cover it
+    pl.C = 1;
+    while (pl.TPC > 1 && pl.TPC / 2 >= tiles) pl.TPC /= 2;
+    if (pl.TPC == 1) pl.onepass = 0;  // one tile: the same as the sequential kernel
+  }
   pl.ragged = scan_ragged(s, pl);
   return pl;
 }
@@ -78,7 +88,15 @@ static ScanPlan scan_default(const int64_t* s) {
   const int64_t rows = s[0] > 0 ? s[0] : 1;
   int64_t chunks = 1;
   while (rows * chunks < 2048 && cdiv(s[1], 2048 * chunks * 2) >= 4) chunks *= 2;
-  if (chunks == 1) return scan_plan(s, 8, 1);  // 8 wavefronts per workgroup measured fastest (4 and 16 within 7 %)
+  if (chunks == 1) {
+    // a row of up to 8 tiles stays in registers (two barriers per row); longer rows are walked tile
+    // by tile with a carry; 8 wavefronts per workgroup measured fastest (4 and 16 within 7 %)
+    // (65536 x 4096: 0.330 ms resident against 0.349 ms; 8192 x 32768: 0.364 against 0.403 ms; rows
+    // beyond 4096 elements with 16 wavefronts, which keeps the tiles per lane few)
+    const ScanPlan res = s[1] <= 4096 ? scan_onepass_plan(s, 8, 8) : scan_onepass_plan(s, 16, 8);
+    if (res.C == 1 && res.onepass) return res;
+    return scan_plan(s, 8, 1);
+  }
   // few long rows: chunks of j over workgroups, a chunk resident in registers (one pass over the
   // input); as many tiles per chunk as still give a workgroup per compute unit
   int tpc = 8;
@@ -104,12 +122,11 @@ int scan_candidates(const int64_t* s, ScanPlan* out, int cap) {
   push(d);
   for (int w : kScanWaves)
     for (int64_t c = d.C / 4 > 0 ? d.C / 4 : 1; c <= (int64_t)d.C * 8; c *= 2) push(scan_plan(s, w, c));
-  if (d.C > 1)
-    for (int w : kOnePassWaves)
-      for (int t : kOnePassTpc) {
-        const ScanPlan pl = scan_onepass_plan(s, w, t);
-        if (pl.onepass) push(pl);
-      }
+  for (int w : kOnePassWaves)
+    for (int t : kOnePassTpc) {
+      const ScanPlan pl = scan_onepass_plan(s, w, t);
+      if (pl.onepass && (d.C > 1 || pl.C == 1)) push(pl);
+    }
   return n;
 }
 
@@ -124,13 +141,18 @@ mdh_status plan_scan(const int64_t* s, const mdh_tile_params* p, ScanPlan* out) 
   if (st != MDH_OK) return st;
   if ((st = check_lanes(p)) != MDH_OK) return st;
   ScanPlan pl{p->prt[MDH_L_WAVE][1], p->prt[MDH_L_HBM][1], p->prt[MDH_L_WG][1], ragged, 0};
-  pl.onepass = pl.C > 1 && p->in_region[0] == MDH_MR_VGPR;
+  const int vg = p->prt[MDH_L_VGPR][1];
+  pl.onepass = (pl.C > 1 && p->in_region[0] == MDH_MR_VGPR) || (pl.C == 1 && vg > 4);
+  if (pl.onepass) {
+    if (vg % 4 || pl.TPC != 1) return MDH_ERR_UNSUPPORTED;  // register-layer tiles, no sequential ones
+    pl.TPC = vg / 4;
+  }
   bool inst = pl.WAVES == 1 && pl.C == 1;
   if (pl.onepass) {
     bool w_ok = false, t_ok = false;
     for (int w : kOnePassWaves) w_ok = w_ok || (w == pl.WAVES);
     for (int t : kOnePassTpc) t_ok = t_ok || (t == pl.TPC);
-    inst = w_ok && t_ok;
+    inst = w_ok && t_ok && (pl.C > 1 || pl.TPC > 1);
   } else {
     for (int w : kScanWaves) inst = inst || (w == pl.WAVES);
   }

@@ -202,8 +202,9 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
-// FULL: the whole chunk lies inside the row (no bounds checks on loads and stores)
-template <int WAVES, int TPC, bool FULL>
+// FULL: the whole chunk lies inside the row (no bounds checks on loads and stores).  SOLO: the
+// chunk is the whole row, nothing is exchanged with other workgroups.
+template <int WAVES, int TPC, bool FULL, bool SOLO = false>
 __device__ __forceinline__ void onepass_body(const float* __restrict__ src, float* __restrict__ dst,
                                              unsigned long long* __restrict__ my_totals,
                                              unsigned long long* __restrict__ my_gsums,
@@ -250,26 +251,33 @@ __device__ __forceinline__ void onepass_body(const float* __restrict__ src, floa
     const double excl = incl - (a0 + a1);
     if (e0 < NE) wex[e0] = excl;
     if (e0 + 1 < NE) wex[e0 + 1] = excl + a0;
-    const double total = __shfl(incl, 63, 64);
-    if (lane == 0) {
-      wex[NE] = total;
-      __hip_atomic_store(my_totals + chunk, (unsigned long long)__double_as_longlong(total), __ATOMIC_RELAXED,
-                         __HIP_MEMORY_SCOPE_AGENT);
+    if (!SOLO) {
+      const double total = __shfl(incl, 63, 64);
+      if (lane == 0) {
+        wex[NE] = total;
+        __hip_atomic_store(my_totals + chunk, (unsigned long long)__double_as_longlong(total), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+      }
+      if (lane < m) part = wait_for(my_totals + (g << 6) + lane, spin_limit, err);
     }
-    if (lane < m) part = wait_for(my_totals + (g << 6) + lane, spin_limit, err);
-  } else {
+  } else if (!SOLO) {
     for (int k = tid - 64; k < g; k += NT - 64) part += wait_for(my_gsums + k, spin_limit, err);
   }
-  part = wave_sum(part);
-  if (lane == 0) dpart[wave] = part;
-  __syncthreads();
-  const double in_group = dpart[0];
-  if (tid == 0 && m == 63)  // the group is complete with this chunk
-    __hip_atomic_store(my_gsums + g, (unsigned long long)__double_as_longlong(in_group + wex[NE]), __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-  double off = in_group;
+  double off = 0.0;
+  if (SOLO) {
+    __syncthreads();
+  } else {
+    part = wave_sum(part);
+    if (lane == 0) dpart[wave] = part;
+    __syncthreads();
+    const double in_group = dpart[0];
+    if (tid == 0 && m == 63)  // the group is complete with this chunk
+      __hip_atomic_store(my_gsums + g, (unsigned long long)__double_as_longlong(in_group + wex[NE]), __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+    off = in_group;
 #pragma unroll
-  for (int w = 1; w < WAVES; ++w) off += dpart[w];
+    for (int w = 1; w < WAVES; ++w) off += dpart[w];
+  }
 
 #pragma unroll
   for (int t = 0; t < TPC; ++t) {
@@ -316,6 +324,22 @@ __global__ __launch_bounds__(WAVES * 64, 4) void scan_onepass_kernel(const float
   else
     onepass_body<WAVES, TPC, false>(in + row * n, out + row * n, my_totals, my_gsums, ws + 1, j0, n, chunk,
                                     spin_limit, wex, dpart);
+}
+
+// A whole row per workgroup, resident in registers (rows of up to 8 tiles): the wavefront scans
+// need no barrier, one wavefront turns the wavefront totals into exclusive prefixes, two barriers
+// per row instead of one per tile.
+template <int WAVES, int TPC>
+__global__ __launch_bounds__(WAVES * 64, 4) void scan_row_resident_kernel(const float* __restrict__ in,
+                                                                          float* __restrict__ out, int64_t n) {
+  constexpr int NT = WAVES * 64;
+  __shared__ double wex[TPC * WAVES + 1];
+  static_assert(TPC * WAVES <= 128, "two entries per lane of wavefront 0");
+  const int64_t row = blockIdx.x;
+  if ((int64_t)TPC * NT * 4 <= n)
+    onepass_body<WAVES, TPC, true, true>(in + row * n, out + row * n, nullptr, nullptr, nullptr, 0, n, 0, 0, wex, nullptr);
+  else
+    onepass_body<WAVES, TPC, false, true>(in + row * n, out + row * n, nullptr, nullptr, nullptr, 0, n, 0, 0, wex, nullptr);
 }
 
 // Short rows: one wavefront per row, 4 rows per workgroup, no LDS and no barrier; the row is walked
@@ -391,13 +415,24 @@ mdh_status launch_onepass_t(const ScanPlan& pl, int64_t R, int64_t n, const floa
   return launch_status();
 }
 
+template <int WAVES, int TPC>
+mdh_status launch_resident_t(int64_t R, int64_t n, const float* in, float* out, hipStream_t st) {
+  if (R > 0x7fffffff) return MDH_ERR_SIZE;
+  clear_stale_error();
+  hipLaunchKernelGGL((scan_row_resident_kernel<WAVES, TPC>), dim3((unsigned)R), dim3(WAVES * 64), 0, st, in, out, n);
+  return launch_status();
+}
+
 mdh_status launch_onepass(const ScanPlan& pl, int64_t R, int64_t n, const float* in, float* out, void* ws,
                           hipStream_t st) {
-#define MDH_OP(w, t) \
-  if (pl.WAVES == w && pl.TPC == t) return launch_onepass_t<w, t>(pl, R, n, in, out, ws, st);
+#define MDH_OP(w, t)                                                                       \
+  if (pl.WAVES == w && pl.TPC == t)                                                        \
+    return pl.C == 1 ? launch_resident_t<w, t>(R, n, in, out, st) : launch_onepass_t<w, t>(pl, R, n, in, out, ws, st);
+  MDH_OP(8, 1)
   MDH_OP(8, 2)
   MDH_OP(8, 4)
   MDH_OP(8, 8)
+  MDH_OP(16, 1)
   MDH_OP(16, 2)
   MDH_OP(16, 4)
   MDH_OP(16, 8)
@@ -417,7 +452,7 @@ mdh_status launch_scan(const ScanPlan& pl, int64_t R, int64_t n, const float* in
     hipLaunchKernelGGL(scan_rows_wave_kernel, dim3((unsigned)blocks), dim3(256), 0, st, in, out, R, n, pl.TPC);
     return launch_status();
   }
-  if (pl.onepass && pl.C > 1) return launch_onepass(pl, R, n, in, out, ws, st);
+  if (pl.onepass) return launch_onepass(pl, R, n, in, out, ws, st);  // chunks, or a whole row, resident in registers
   switch (pl.WAVES) {
     case 4: return launch_t<4>(pl, R, n, in, out, ws, st);
     case 8: return launch_t<8>(pl, R, n, in, out, ws, st);

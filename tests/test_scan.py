@@ -42,12 +42,12 @@ def test_planner(sizes):
             kinds.add(int(c.in_region[0]))
     if C > 1:  # both ways of exchanging the chunk totals are in the search space
         assert kinds == {B.MR_HBM, B.MR_VGPR}
-        assert p.in_region[0] == B.MR_VGPR and p.prt[B.L_HBM][1] in (2, 4, 8)
+        assert p.in_region[0] == B.MR_VGPR and p.prt[B.L_HBM][1] == 1 and p.prt[B.L_VGPR][1] in (4, 8, 16, 32)
     # a long single row is cut into chunks over workgroups, many rows are not
     if sizes == (1, 1 << 24):
         assert C > 1
-    if sizes == (4096, 4096):
-        assert C == 1
+    if sizes == (4096, 4096):  # a row of two tiles stays in the workgroup's registers
+        assert C == 1 and p.prt[B.L_HBM][1] == 1 and p.prt[B.L_VGPR][1] == 8
 
 
 def test_planner_rejects_empty_chunk():
