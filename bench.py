@@ -393,7 +393,8 @@ def bench_scan(torch, mdh, W, name, steps, warmup, cpu):
     single_pass = chunks > 1 and int(p.in_region[0]) == 2  # the chunk waits in registers (MDH_MR_VGPR)
     res = {
         "value": nbytes / wall / 1e6, "unit": "GB/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "f32",
-        "kernel": ("scan_apply_kernel" if chunks == 1 else
+        "kernel": ("scan_row_resident_kernel (the row stays in registers)" if chunks == 1 and int(p.prt[2][1]) > 4 else
+                   "scan_apply_kernel" if chunks == 1 else
                    "scan_onepass_init_kernel + scan_onepass_kernel (single pass)" if single_pass else
                    "scan_totals_kernel + scan_offsets_kernel + scan_apply_kernel"),
         "rows": R, "n": n, "chunks_per_row": chunks,
