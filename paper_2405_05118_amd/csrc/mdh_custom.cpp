@@ -229,24 +229,25 @@ CustomPlan make_plan(const mdh_custom_desc* d, int nt, int64_t split, int vreg =
 }
 
 CustomPlan default_plan(const mdh_custom_desc* d) {
-  // 4 register parts per reusable concatenation dimension, unless the grid gets too small for it;
+  // register parts on the reusable concatenation dimensions, unless the grid gets too small for it;
   // few workgroups: split the reduced dimensions over workgroups up to ~2048 workgroups
   // (results wider than 4 bytes -- user-defined structs -- are not blocked by default: measured
   // slower on the record-linkage example; such configurations are among the candidates)
-  // one reusable dimension alone takes 8 parts (Histo, 256 bins x 2^24 elements: 0.32 ms against
-  // 0.37 ms with 4), several take 4 each
-  int reusable = 0;
-  for (int i = 0; i < d->D; ++i)
-    if (d->reduce[i] == 0 && d->acc_index[0] && reused_across(d, i)) ++reusable;
+  // eight parts on one reusable dimension first (Histo, 256 bins x 2^24 elements: 0.32 ms against
+  // 0.37 ms with four; MatMul 1024^3: 25 TFLOP/s against 18 with four parts on each of i and j)
   CustomPlan pl;
-  for (int vreg : {d->out_elem_bytes <= 4 ? (reusable == 1 ? 8 : 4) : 1, d->out_elem_bytes <= 4 ? 4 : 1, 1}) {
+  for (int vreg : {d->out_elem_bytes <= 4 ? 8 : 1, d->out_elem_bytes <= 4 ? 4 : 1, 1}) {
     pl = make_plan(d, 256, 1, vreg);
     const int64_t grid = pl.SG * pl.CG;
-    if (grid < 1024) {
-      int64_t split = 1;
-      while (grid * split < 2048) split *= 2;
-      pl = make_plan(d, 256, split, vreg);
-    }
+    int64_t steps = 1;  // sequential steps of a lane over the reduced dimensions
+    for (int i = 0; i < pl.D; ++i)
+      if (pl.red[i]) steps *= pl.Q[i];
+    // split up to ~2048 workgroups, and further while a lane would walk more than ~1024 steps
+    // (custom reduce 2^16 x 2^18: 10.0 ms with 1024 steps per lane, 13.9 ms with 32768)
+    int64_t split = 1;
+    while (grid * split < 2048 && grid < 1024) split *= 2;
+    while (steps / split > 1024 && grid * split < 32768) split *= 2;
+    if (split > 1) pl = make_plan(d, 256, split, vreg);
     if (pl.SG * pl.CG >= 512) break;
   }
   return pl;

@@ -119,11 +119,11 @@ def test_register_parts_of_concatenation_dimensions():
     # re-uses the loaded element; the default blocks, candidates cover 1, 2, 4 and 8 parts
     d = d_matmul(1024, 1024, 1024)
     p = mdh.mdh_custom_default_params(d)
-    assert max(p.prt[B.L_VGPR][0], p.prt[B.L_VGPR][1]) == 4 and p.prt[B.L_VGPR][2] == 1
+    assert max(p.prt[B.L_VGPR][0], p.prt[B.L_VGPR][1]) == 8 and p.prt[B.L_VGPR][2] == 1  # eight parts on one dimension
     vs = {max(c.prt[B.L_VGPR][:3]) for c in (mdh.mdh_custom_candidate(d, i) for i in range(mdh.mdh_custom_num_candidates(d)))}
     assert {1, 2, 4, 8} <= vs
     src = mdh.mdh_custom_source(mdh.mdh_custom_create(d, p))
-    assert "mdh_T acc[4];" in src
+    assert "mdh_T acc[8];" in src
     # register parts on a reduced dimension are not a configuration of this kernel
     q = p.copy()
     q.prt[B.L_VGPR][2], q.prt[B.L_HBM][2] = 2, q.prt[B.L_HBM][2] // 2
