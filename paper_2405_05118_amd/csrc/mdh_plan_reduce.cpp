@@ -36,10 +36,11 @@ static int dot_ragged(const int64_t* s, const DotPlan& pl) {
 }
 
 static DotPlan dot_default(const int64_t* s) {
-  DotPlan pl{4, 1, 0};
-  // four workgroups per compute unit, as long as each still streams a few KiB
+  // workgroups of 8 wavefronts, one per compute unit, as long as each still streams a few KiB
+  // (2^28 elements: 0.300 ms with 256 such workgroups, 0.314 ms with 1024 of 4 wavefronts)
+  DotPlan pl{8, 1, 0};
   int S = 1;
-  while (S < 1024 && s[0] / (2ll * S) >= (int64_t)pl.WAVES * 256 * 8) S *= 2;
+  while (S < 256 && s[0] / (2ll * S) >= (int64_t)pl.WAVES * 256 * 8) S *= 2;
   pl.S = S;
   pl.ragged = dot_ragged(s, pl);
   return pl;
