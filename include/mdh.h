@@ -481,11 +481,13 @@ mdh_status mdh_custom_tune(const mdh_custom_desc* desc, const void* const* input
  * nothing else in the way: a roofline fraction quoted against the published
  * peak (paper: Section "Experimental Results" measures against hand-tuned
  * libraries instead) can then be read against the attainable rate as well.
- * Every call enqueues one kernel of MDH_CALIB_BLOCKS workgroups x 256 lanes.
+ * Every call enqueues one kernel (the arithmetic ones MDH_CALIB_BLOCKS workgroups x
+ * 256 lanes; the streaming ones one workgroup of 512 lanes per compute unit, the
+ * launch shape measured fastest).
  *   mdh_calib_copy : dst[0..bytes) = src[0..bytes), 16-byte non-temporal accesses;
  *                    bytes > 0 and a multiple of 16, both pointers 16-byte aligned.
- *   mdh_calib_read : streams src once; `out` receives one partial sum per lane
- *                    (MDH_CALIB_BLOCKS*256 floats, device).
+ *   mdh_calib_read : streams src once; the first MDH_CALIB_STREAM_LANES floats of
+ *                    `out` (device) receive one partial sum per lane.
  *   mdh_calib_mfma : every wavefront issues iters*16 independent
  *                    v_mfma_f32_32x32x2_f32; *flop (host, may be NULL) receives the
  *                    floating-point operations of the launch; `out` as above.
@@ -495,6 +497,7 @@ mdh_status mdh_custom_tune(const mdh_custom_desc* desc, const void* const* input
  * Errors: MDH_ERR_NULL, MDH_ERR_SIZE, MDH_ERR_LAUNCH.
  */
 #define MDH_CALIB_BLOCKS 2048
+#define MDH_CALIB_STREAM_LANES (256 * 512)
 mdh_status mdh_calib_copy(const void* src, void* dst, int64_t bytes, void* stream);
 mdh_status mdh_calib_read(const void* src, int64_t bytes, float* out, void* stream);
 mdh_status mdh_calib_mfma(float* out, int32_t iters, int64_t* flop, void* stream);

@@ -29,6 +29,7 @@ EXPORTS = (
 )
 MDH_CUSTOM_MAX_IN, MDH_CUSTOM_MAX_ACC = 4, 8
 MDH_CALIB_BLOCKS = 2048
+MDH_CALIB_STREAM_LANES = 256 * 512
 
 
 class TileParams(ctypes.Structure):
@@ -482,10 +483,10 @@ def mdh_calib_copy(src, dst):
 
 
 def mdh_calib_read(src, out):
-    """Streaming read of src; out: MDH_CALIB_BLOCKS*256 float32 partial sums."""
+    """Streaming read of src; out: MDH_CALIB_STREAM_LANES float32 partial sums."""
     import torch
 
-    assert out.numel() >= MDH_CALIB_BLOCKS * 256
+    assert out.numel() >= MDH_CALIB_STREAM_LANES
     _check(lib().mdh_calib_read(ctypes.c_void_p(src.data_ptr()), src.numel() * src.element_size(),
                                 _dev(out, torch.float32, "out"), ctypes.c_void_p(_stream())), "mdh_calib_read")
 

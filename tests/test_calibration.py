@@ -14,13 +14,14 @@ def test_copy_and_read():
     src = W.device_uniform(W.SEED_BASE + 90, 1, (n,), 0.0, 1.0)
     dst = torch.zeros_like(src)
     mdh.mdh_calib_copy(src, dst)
-    out = torch.empty(B.MDH_CALIB_BLOCKS * 256, dtype=torch.float32, device="cuda")
+    out = torch.full((B.MDH_CALIB_STREAM_LANES + 64,), float("nan"), dtype=torch.float32, device="cuda")
     mdh.mdh_calib_read(src, out)
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
     # every element is read exactly once: the partial sums add up to the sum of the buffer
     want = float(src.double().sum())
-    assert abs(float(out.double().sum()) - want) <= 1e-6 * want
+    assert abs(float(out[: B.MDH_CALIB_STREAM_LANES].double().sum()) - want) <= 1e-6 * want
+    assert torch.isnan(out[B.MDH_CALIB_STREAM_LANES:]).all()  # nothing written beyond the documented size
 
 
 @pytest.mark.gpu
