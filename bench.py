@@ -37,22 +37,22 @@ PRL_LANE_OPS_PER_PAIR = 24.0
 # None until measured for that workload
 TRAFFIC_BYTES = {
     # profiles/all_kernels_hbm_traffic_pmc.md (all kernels of a step)
-    "jacobi3d_512": 1110261530,
-    "dot_2p28": 2147373895,
-    "matvec_16384": 1074467360,
-    "matmul_4096": 604065546,
-    "matmul_ts": 1101994899,
-    "mcc_resnet": 850781618,
-    "prl_2p16_2p18": 141620111,
-    "matmul_256": 1939181,
-    "mcc_resnet50_first": 62430927,
-    "matmul_resnet50_fc": 13577175,
-    "matmul_vgg16_fc": 426313404,
-    "mcc_capsule_resnet50_first": 1072648064,
-    "scan_2p28": 2152029755,
-    "scan_rows_65536x4096": 2147499120,
-    "histo_generic_256x2p24": 204518681,
-    "prl_generic_2p16_2p18": 145818684,
+    "jacobi3d_512": 1109913792,
+    "dot_2p28": 2147343642,
+    "matvec_16384": 1074466336,
+    "matmul_4096": 604065034,
+    "matmul_ts": 1102001855,
+    "mcc_resnet": 850240045,
+    "prl_2p16_2p18": 154090581,
+    "matmul_256": 1939161,
+    "mcc_resnet50_first": 62430912,
+    "matmul_resnet50_fc": 13577162,
+    "matmul_vgg16_fc": 426313090,
+    "mcc_capsule_resnet50_first": 1072647788,
+    "scan_2p28": 2152690234,
+    "scan_rows_65536x4096": 2147508611,
+    "histo_generic_256x2p24": 205063027,
+    "prl_generic_2p16_2p18": 271647975,
 }
 
 
