@@ -235,9 +235,21 @@ CustomPlan default_plan(const mdh_custom_desc* d) {
   // slower on the record-linkage example; such configurations are among the candidates)
   // eight parts on one reusable dimension first (Histo, 256 bins x 2^24 elements: 0.32 ms against
   // 0.37 ms with four; MatMul 1024^3: 25 TFLOP/s against 18 with four parts on each of i and j)
+  // lanes: a workgroup of 256, but a single wavefront when the lanes run along a reduced dimension
+  // and the concatenation dimensions alone fill the chip (MatVec 8192^2: 6.7 TB/s against 5.0 TB/s --
+  // the wavefront's partial results meet in registers, no LDS tree)
+  int nt = 256;
+  {
+    CustomPlan probe;
+    fill_from_desc(d, &probe);
+    int64_t cc = 1;
+    for (int i = 0; i < probe.D; ++i)
+      if (!probe.red[i] && i != probe.scan) cc *= probe.N[i];
+    if (probe.scan < 0 && probe.red[probe.fast] && cc >= 2048 && probe.N[probe.fast] >= 1024) nt = 64;
+  }
   CustomPlan pl;
   for (int vreg : {d->out_elem_bytes <= 4 ? 8 : 1, d->out_elem_bytes <= 4 ? 4 : 1, 1}) {
-    pl = make_plan(d, 256, 1, vreg);
+    pl = make_plan(d, nt, 1, vreg);
     const int64_t grid = pl.SG * pl.CG;
     int64_t steps = 1;  // sequential steps of a lane over the reduced dimensions
     for (int i = 0; i < pl.D; ++i)
@@ -247,7 +259,7 @@ CustomPlan default_plan(const mdh_custom_desc* d) {
     int64_t split = 1;
     while (grid * split < 2048 && grid < 1024) split *= 2;
     while (steps / split > 1024 && grid * split < 32768) split *= 2;
-    if (split > 1) pl = make_plan(d, 256, split, vreg);
+    if (split > 1) pl = make_plan(d, nt, split, vreg);
     if (pl.SG * pl.CG >= 512) break;
   }
   return pl;
