@@ -169,8 +169,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan_apply_kernel(const float* __r
 // published too, by the workgroup of the group's last chunk, so that a workgroup reads at most
 // 63 totals and C/64 group sums.  Every sum is taken in a fixed order: bit-identical run to run.
 //
-// Progress: chunk numbers are handed out by a ticket counter in the order in which workgroups
-// start, so every chunk a workgroup waits for belongs to a workgroup that is already running; a
+// Progress: chunk numbers are handed out by a ticket counter to running workgroups, so every chunk a
+// workgroup waits for has been drawn by a workgroup that is running it or has finished it; a
 // total depends on the chunk alone and a group sum on totals alone, so there is no chain of waits.
 // Each wait is also bounded (spin_limit polls); on a time-out the kernel stops waiting, sets word
 // 1 of the workspace and finishes with wrong values in that chunk.
@@ -310,20 +310,27 @@ __global__ __launch_bounds__(WAVES * 64, 4) void scan_onepass_kernel(const float
   __shared__ double dpart[WAVES];
   __shared__ unsigned ticket;
   static_assert(TPC * WAVES <= 128, "two entries per lane of wavefront 0");
-  if (threadIdx.x == 0) ticket = atomicAdd((unsigned*)ws, 1u);
-  __syncthreads();
-  const unsigned bid = ticket;
-  const int64_t row = bid / C;
-  const int chunk = bid % C;
-  const int64_t j0 = (int64_t)chunk * TPC * NT * 4;
-  unsigned long long* my_totals = ws + 2 + row * C;
-  unsigned long long* my_gsums = ws + 2 + RC + row * G;
-  if (j0 + (int64_t)TPC * NT * 4 <= n)
-    onepass_body<WAVES, TPC, true>(in + row * n, out + row * n, my_totals, my_gsums, ws + 1, j0, n, chunk,
-                                   spin_limit, wex, dpart);
-  else
-    onepass_body<WAVES, TPC, false>(in + row * n, out + row * n, my_totals, my_gsums, ws + 1, j0, n, chunk,
-                                    spin_limit, wex, dpart);
+  // persistent workgroups: one launch of as many workgroups as the chip holds at once, each drawing
+  // chunk numbers until none is left -- the loads of a workgroup's next chunk go out while the
+  // stores of its last one drain, instead of a new workgroup starting from an empty compute unit
+  for (;;) {
+    __syncthreads();  // every lane is done with the previous chunk's LDS values and its number
+    if (threadIdx.x == 0) ticket = atomicAdd((unsigned*)ws, 1u);
+    __syncthreads();
+    const unsigned bid = ticket;
+    if ((int64_t)bid >= RC) break;  // workgroup-uniform
+    const int64_t row = bid / C;
+    const int chunk = bid % C;
+    const int64_t j0 = (int64_t)chunk * TPC * NT * 4;
+    unsigned long long* my_totals = ws + 2 + row * C;
+    unsigned long long* my_gsums = ws + 2 + RC + row * G;
+    if (j0 + (int64_t)TPC * NT * 4 <= n)
+      onepass_body<WAVES, TPC, true>(in + row * n, out + row * n, my_totals, my_gsums, ws + 1, j0, n, chunk,
+                                     spin_limit, wex, dpart);
+    else
+      onepass_body<WAVES, TPC, false>(in + row * n, out + row * n, my_totals, my_gsums, ws + 1, j0, n, chunk,
+                                      spin_limit, wex, dpart);
+  }
 }
 
 // A whole row per workgroup, resident in registers (rows of up to 8 tiles): the wavefront scans
@@ -410,7 +417,18 @@ mdh_status launch_onepass_t(const ScanPlan& pl, int64_t R, int64_t n, const floa
   if (r != MDH_OK) return r;
   clear_stale_error();
   // a poll sleeps ~64 cycles plus a trip to memory: 2^22 polls are seconds, far beyond any real wait
-  hipLaunchKernelGGL((scan_onepass_kernel<WAVES, TPC>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, st, in, out,
+  // as many workgroups as run at once (16 wavefronts per compute unit by the kernel's register bound)
+  static int cus[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MDH_ERR_LAUNCH;
+  if (cus[dev] == 0) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) return MDH_ERR_LAUNCH;
+    cus[dev] = v;
+  }
+  int64_t grid = (int64_t)cus[dev] * (16 / WAVES);
+  if (grid > blocks) grid = blocks;
+  hipLaunchKernelGGL((scan_onepass_kernel<WAVES, TPC>), dim3((unsigned)grid), dim3(WAVES * 64), 0, st, in, out,
                      (unsigned long long*)ws, n, pl.C, (int)G, blocks, 1 << 22);
   return launch_status();
 }

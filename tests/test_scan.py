@@ -117,7 +117,8 @@ def test_single_pass_many_chunks():
         assert np.array_equal(first, run(x, p)), "not bit-identical run to run"
     assert seen >= 4
     assert max(p.prt[B.L_WG][1] for p in cands(shape)[1:]) > 128  # more than two groups
-    # the workspace afterwards: every workgroup drew a ticket, no wait ran into its bound
+    # the workspace afterwards: every chunk was drawn (and every workgroup drew one number past the
+    # end), no wait ran into its bound
     p = mdh.mdh_default_params(mdh.MDH_SCAN, shape)
     assert p.in_region[0] == B.MR_VGPR
     xs = torch.from_numpy(x).cuda()
@@ -126,7 +127,8 @@ def test_single_pass_many_chunks():
     mdh.mdh_scan(xs, out, p, ws)
     torch.cuda.synchronize()
     words = ws.cpu().numpy()
-    assert words[0] == shape[0] * p.prt[B.L_WG][1] and words[1] == 0
+    chunks = shape[0] * p.prt[B.L_WG][1]
+    assert chunks < words[0] <= 2 * chunks and words[1] == 0
 
 
 @pytest.mark.gpu
