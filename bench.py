@@ -37,22 +37,22 @@ PRL_LANE_OPS_PER_PAIR = 24.0
 # None until measured for that workload
 TRAFFIC_BYTES = {
     # profiles/all_kernels_hbm_traffic_pmc.md (all kernels of a step)
-    "jacobi3d_512": 1109913792,
-    "dot_2p28": 2147343642,
-    "matvec_16384": 1074466336,
-    "matmul_4096": 604065034,
-    "matmul_ts": 1102001855,
-    "mcc_resnet": 850240045,
-    "prl_2p16_2p18": 154090581,
-    "matmul_256": 1939161,
-    "mcc_resnet50_first": 62430912,
-    "matmul_resnet50_fc": 13577162,
-    "matmul_vgg16_fc": 426313090,
-    "mcc_capsule_resnet50_first": 1072647788,
-    "scan_2p28": 2152690234,
-    "scan_rows_65536x4096": 2147508611,
-    "histo_generic_256x2p24": 205063027,
-    "prl_generic_2p16_2p18": 271647975,
+    "jacobi3d_512": 1110138640,
+    "dot_2p28": 2147348249,
+    "matvec_16384": 1074468558,
+    "matmul_4096": 604066186,
+    "matmul_ts": 1102097670,
+    "mcc_resnet": 891753253,
+    "prl_2p16_2p18": 154105210,
+    "matmul_256": 1939164,
+    "mcc_resnet50_first": 62430680,
+    "matmul_resnet50_fc": 13577190,
+    "matmul_vgg16_fc": 426313928,
+    "mcc_capsule_resnet50_first": 1072648289,
+    "scan_2p28": 2151803943,
+    "scan_rows_65536x4096": 2147503399,
+    "histo_generic_256x2p24": 204977349,
+    "prl_generic_2p16_2p18": 271641353,
 }
 
 
