@@ -235,7 +235,8 @@ CustomPlan default_plan(const mdh_custom_desc* d) {
   // slower on the record-linkage example; such configurations are among the candidates)
   // eight parts on one reusable dimension first (Histo, 256 bins x 2^24 elements: 0.32 ms against
   // 0.37 ms with four; MatMul 1024^3: 25 TFLOP/s against 18 with four parts on each of i and j)
-  // lanes: a workgroup of 256, but a single wavefront when the lanes run along a reduced dimension
+  // lanes: a workgroup of 256 (1024 when every dimension is a concatenation dimension), but a single
+  // wavefront when the lanes run along a reduced dimension
   // and the concatenation dimensions alone fill the chip (MatVec 8192^2: 6.7 TB/s against 5.0 TB/s --
   // the wavefront's partial results meet in registers, no LDS tree)
   int nt = 256;
@@ -246,9 +247,26 @@ CustomPlan default_plan(const mdh_custom_desc* d) {
     for (int i = 0; i < probe.D; ++i)
       if (!probe.red[i] && i != probe.scan) cc *= probe.N[i];
     if (probe.scan < 0 && probe.red[probe.fast] && cc >= 2048 && probe.N[probe.fast] >= 1024) nt = 64;
+    bool any_red = false;
+    for (int i = 0; i < probe.D; ++i) any_red = any_red || probe.red[i] || i == probe.scan;
+    if (!any_red && cc >= (1 << 20)) nt = 1024;  // nothing but concatenation: Jacobi1D 2^26 4.0 against 3.5 TB/s
   }
+  // an access that depends on every dimension streams its buffer once whatever the blocking
+  // (MatVec's matrix): register parts then only cost lanes (MatVec 8192^2: 6.4 TB/s without them,
+  // 5.6 TB/s with eight)
+  bool streams = false;
+  for (int a = 0; a < d->n_acc && d->D > 1; ++a) {
+    bool all = true;
+    for (int i = 0; i < d->D && all; ++i) {
+      char id[8];
+      snprintf(id, sizeof id, "i%d", i);
+      all = uses_identifier(d->acc_index[a], id);
+    }
+    streams = streams || all;
+  }
+  const int v8 = (d->out_elem_bytes <= 4 && !streams) ? 8 : 1, v4 = (d->out_elem_bytes <= 4 && !streams) ? 4 : 1;
   CustomPlan pl;
-  for (int vreg : {d->out_elem_bytes <= 4 ? 8 : 1, d->out_elem_bytes <= 4 ? 4 : 1, 1}) {
+  for (int vreg : {v8, v4, 1}) {
     pl = make_plan(d, nt, 1, vreg);
     const int64_t grid = pl.SG * pl.CG;
     int64_t steps = 1;  // sequential steps of a lane over the reduced dimensions
