@@ -69,13 +69,19 @@ struct Operand {
       if (F4 % NT == 0 || f < F4) *(f4*)(st + row * P + c4 * 4) = r[x];
     }
   }
-  // the four values lane (l32, lh) contributes to the MFMAs of k-step group kk for the 32-wide
-  // block that starts at free offset foff: k = kk + 4*lh + t, t = 0..3
-  static __device__ __forceinline__ f4 frag(const float* st, int foff, int l32, int lh, int kk) {
-    if (KC) return *(const f4*)(st + (foff + l32) * P + kk + 4 * lh);
+  // A lane's view of the staged tile: lane (l32, lh) of the wavefront whose blocks start at free
+  // offset woff contributes, to the MFMAs of k-step group kk and block blk, the four values
+  // k = kk + 4*lh + t, t = 0..3, of free index woff + 32*blk + l32.  The lane-dependent part of the
+  // address is folded into one pointer so that the reads of a step differ by constants only (the
+  // 4-byte reads then pair up into two-address LDS instructions).
+  static __device__ __forceinline__ const float* lane_base(const float* st, int woff, int l32, int lh) {
+    return KC ? st + (woff + l32) * P + 4 * lh : st + (4 * lh) * P + woff + l32;
+  }
+  static __device__ __forceinline__ f4 frag(const float* lb, int blk, int kk) {
+    if (KC) return *(const f4*)(lb + blk * 32 * P + kk);
     f4 v;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) v[t] = st[(kk + 4 * lh + t) * P + foff + l32];
+    for (int t = 0; t < 4; ++t) v[t] = lb[(kk + t) * P + blk * 32];
     return v;
   }
 };
@@ -102,45 +108,91 @@ __device__ __forceinline__ void gemm_ex_tile(const float* __restrict__ A, const 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
+  struct Frag {
+    f4 a[MI], b[NI];
+  };
+  auto load_frag = [&](Frag& f, const float* as, const float* bs, int kk) {
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) f.a[mi] = OpA::frag(as, mi, kk);
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) f.b[ni] = OpB::frag(bs, ni, kk);
+  };
+  auto mma = [&](const Frag& f) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[mi][t], f.b[ni][t], acc[mi][ni], 0, 0, 0);
+  };
   auto compute = [&](const float* st) {
+    const float* as = OpA::lane_base(st, wm * WM, l32, lh);
+    const float* bs = OpB::lane_base(st + OpA::SIZE, wn * WN, l32, lh);
+    if (MI * NI >= 4) {
+      // as in the MatMul kernel: the fragments of k-step kk+8 are read while the MFMAs of step kk
+      // run, one LDS read instruction per few MFMAs.  A k-contiguous operand block is one 16-byte
+      // read, the other layout four 4-byte reads that pair up into two instructions.
+      constexpr int NR = (TA ? 2 : 1) * MI + (TB ? 1 : 2) * NI, NM = 4 * MI * NI, PER = NM / NR;
+      Frag f[2];
+      load_frag(f[0], as, bs, 0);
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 8) {
-      f4 af[MI], bf[NI];
+      for (int kk = 0; kk < BK; kk += 8) {
+        const int cur = (kk >> 3) & 1;
+        if (kk + 8 < BK) load_frag(f[cur ^ 1], as, bs, kk + 8);
+        mma(f[cur]);
+        if (kk + 8 < BK) {
 #pragma unroll
-      for (int mi = 0; mi < MI; ++mi) af[mi] = OpA::frag(st, wm * WM + mi * 32, l32, lh, kk);
+          for (int i = 0; i < NR; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, NM - NR * PER, 0);
+        }
+      }
+    } else {
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni) bf[ni] = OpB::frag(st + OpA::SIZE, wn * WN + ni * 32, l32, lh, kk);
-#pragma unroll
-      for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-          for (int ni = 0; ni < NI; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi][t], bf[ni][t], acc[mi][ni], 0, 0, 0);
+      for (int kk = 0; kk < BK; kk += 8) {
+        Frag f;
+        load_frag(f, as, bs, kk);
+        mma(f);
+      }
     }
   };
 
-  OpA ga;
-  OpB gb;
+  // two k-tiles in flight (tile kt+2 is requested while tile kt is computed and tile kt+1 waits in
+  // registers), the pipeline of the MatMul kernel
+  struct Staged {
+    OpA a;
+    OpB b;
+  };
+  auto load_global = [&](Staged& g, int k0) {
+    g.a.template load<GUARD>(A, lda, m0, M, k0, kend);
+    g.b.template load<GUARD>(B, ldb, n0, N, k0, kend);
+  };
+  auto store_lds = [&](const Staged& g, float* st) {
+    g.a.store(st);
+    g.b.store(st + OpA::SIZE);
+  };
   const int nk = (kend - kbeg + BK - 1) / BK;
-  ga.template load<GUARD>(A, lda, m0, M, kbeg, kend);
-  gb.template load<GUARD>(B, ldb, n0, N, kbeg, kend);
-  ga.store(lds);
-  gb.store(lds + OpA::SIZE);
+  float* const st0 = lds;
+  float* const st1 = lds + STAGE;
+  Staged g0, g1;  // g0 carries even tiles, g1 odd tiles
+  load_global(g0, kbeg);
+  if (nk > 1) load_global(g1, kbeg + BK);
+  store_lds(g0, st0);
   __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    float* cur = lds + (kt & 1) * STAGE;
-    float* nxt = lds + ((kt + 1) & 1) * STAGE;
-    if (kt + 1 < nk) {
-      ga.template load<GUARD>(A, lda, m0, M, kbeg + (kt + 1) * BK, kend);
-      gb.template load<GUARD>(B, ldb, n0, N, kbeg + (kt + 1) * BK, kend);
-    }
-    compute(cur);
-    if (kt + 1 < nk) {
-      ga.store(nxt);
-      gb.store(nxt + OpA::SIZE);
-    }
+  for (int kt = 0; kt < nk; kt += 2) {
+    if (kt + 2 < nk) load_global(g0, kbeg + (kt + 2) * BK);
+    compute(st0);
+    if (kt + 1 < nk) store_lds(g1, st1);
     __syncthreads();
+    if (kt + 1 < nk) {
+      if (kt + 3 < nk) load_global(g1, kbeg + (kt + 3) * BK);
+      compute(st1);
+      if (kt + 2 < nk) store_lds(g0, st0);
+      __syncthreads();
+    }
   }
 
   // output view: (i,j,0) -> C[i,j], or C[j,i] for the transposed view
@@ -176,13 +228,24 @@ __global__ __launch_bounds__(((BM / WM) * (BN / WN) * 64)) void matmul_ex_kernel
     float* __restrict__ ws, int M, int N, int K, int tiles_m, int tiles_n, int S, int kchunk,
     int nbatch) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
-  // one more ++ dimension on the workgroup layer: blockIdx.y is the batch index b
-  const int batch = blockIdx.y;
+  // one more ++ dimension on the workgroup layer: the grid is batch x S x tiles, flattened.
+  // XCD-aware order: workgroup ids are dealt round-robin to the 8 XCDs; each XCD gets a contiguous
+  // run (whole batches when there are at least 8), walked in bands of 8 tile-rows so that the tiles
+  // resident on one XCD at a time share few panels of A and B in that XCD's L2.
+  int b = blockIdx.x;
+  const int nb = gridDim.x;
+  if ((nb & 7) == 0) b = (b & 7) * (nb >> 3) + (b >> 3);
   const int tiles = tiles_m * tiles_n;
-  const int b = blockIdx.x;
+  const int batch = b / (tiles * S);
+  b -= batch * tiles * S;
   const int s = b / tiles;
   const int t = b % tiles;
-  const int tm = t % tiles_m, tn = t / tiles_m;
+  constexpr int GM = 8;
+  const int band = t / (GM * tiles_n);
+  const int band_rows = min(GM, tiles_m - band * GM);
+  const int in_band = t - band * GM * tiles_n;
+  const int tm = band * GM + in_band % band_rows;
+  const int tn = in_band / band_rows;
   const int m0 = tm * BM, n0 = tn * BN;
   const int kbeg = s * kchunk;
   const int kend = min(K, kbeg + kchunk);
@@ -210,10 +273,10 @@ mdh_status launch_t(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, i
   const int S = pl.g.S;
   const int64_t tm = cdiv(M, BM), tn = cdiv(N, BN);
   const int64_t kchunk = cdiv(cdiv(K, S), BK) * BK;
-  const int64_t nblocks = tm * tn * S;
-  if (nblocks > 0x7fffffff || batch > 65535) return MDH_ERR_SIZE;
+  const int64_t nblocks = tm * tn * S * batch;
+  if (nblocks > 0x7fffffff) return MDH_ERR_SIZE;
   clear_stale_error();
-  hipLaunchKernelGGL(kern, dim3((unsigned)nblocks, (unsigned)batch), dim3(NT), LDS_BYTES, st, A, B, C,
+  hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(NT), LDS_BYTES, st, A, B, C,
                      (float*)ws, (int)M, (int)N, (int)K, (int)tm, (int)tn, S, (int)kchunk, (int)batch);
   mdh_status r = launch_status();
   if (r != MDH_OK || S <= 1) return r;
@@ -248,6 +311,9 @@ mdh_status launch_matmul_ex(const GemmExPlan& pl, int64_t batch, int64_t M, int6
 #define MDH_MX(bm, bn, bk, wm, wn)                                                                   \
   if (pl.g.BM == bm && pl.g.BN == bn && pl.g.BK == bk && pl.g.WM == wm && pl.g.WN == wn)             \
     return launch_trans<bm, bn, bk, wm, wn>(pl, batch, M, N, K, A, B, C, ws, st);
+  MDH_MX(128, 128, 32, 64, 64)
+  MDH_MX(128, 64, 32, 64, 32)
+  MDH_MX(64, 64, 32, 32, 32)
   MDH_MX(128, 128, 16, 64, 64)
   MDH_MX(128, 64, 16, 64, 32)
   MDH_MX(64, 64, 16, 32, 32)
