@@ -344,6 +344,43 @@ def bench_matmul_ex(torch, mdh, W, name, steps, warmup, cpu):
     return res
 
 
+def bench_bmatmul(torch, mdh, W, name, steps, warmup, cpu):
+    """bMatMul / MatMul^T on the LDS-tiled MFMA kernel of the batched / transposed entry point."""
+    cfg = W.CONFIGS[name]
+    ta, tb, tc = cfg.trans
+    sizes = (cfg.batch, cfg.M, cfg.N, cfg.K, ta, tb, tc)
+    a = W.device_uniform(cfg.seed, 1, (cfg.batch, cfg.K, cfg.M) if ta else (cfg.batch, cfg.M, cfg.K), -1.0, 1.0)
+    b = W.device_uniform(cfg.seed, 2, (cfg.batch, cfg.N, cfg.K) if tb else (cfg.batch, cfg.K, cfg.N), -1.0, 1.0)
+    c = torch.empty((cfg.batch, cfg.N, cfg.M) if tc else (cfg.batch, cfg.M, cfg.N), dtype=torch.float32, device="cuda")
+    p = mdh.mdh_default_params(mdh.MDH_BMATMUL, sizes)
+    ws = _ws(torch, mdh, mdh.MDH_BMATMUL, sizes)
+    ms, wall = _events_ms(torch, lambda: mdh.mdh_matmul_ex(a, b, c, bool(ta), bool(tb), bool(tc), None, ws), steps, warmup)
+    flop = 2.0 * cfg.batch * cfg.M * cfg.N * cfg.K
+    tf = flop / ms / 1e9
+    res = {
+        "value": flop / wall / 1e6, "unit": "GFLOP/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "f32",
+        "kernel": "matmul_ex_kernel", "split_k": int(p.prt[3][3]),
+        "roofline": {"bound": "mfma", "achieved": tf, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tf / PEAK_FP32_MFMA_TFLOPS, "traffic": TRAFFIC_BYTES.get(name)},
+        "algorithmic_flop": flop,
+        "algorithmic_bytes": 4 * cfg.batch * (cfg.M * cfg.K + cfg.K * cfg.N + cfg.M * cfg.N),
+    }
+    if cpu:
+        import oracle
+
+        # batch 0, the first rows of C: the views are undone on the host, the oracle sees plain A and B
+        rows = max(1, min(cfg.M, int(4e8 // (cfg.N * cfg.K))))
+        a0 = a[0].t() if ta else a[0]
+        b0 = b[0].t() if tb else b[0]
+        ah, bh = a0[:rows].contiguous().cpu().numpy(), b0.contiguous().cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.matmul(ah, bh)
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": 2.0 * rows * cfg.N * cfg.K / dt / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": "batch 0, first %d rows of C (%.2f s)" % (rows, dt)}
+    return res
+
+
 def bench_capsule(torch, mdh, W, name, steps, warmup, cpu):
     """MCC_Capsule at the first-layer shape of ResNet-50 (training): MCC on 4 x 4 matrices."""
     cfg = W.CONFIGS["mcc_resnet50_first"]
@@ -539,6 +576,8 @@ BENCHES = {
     "mcc_resnet50_first": bench_mcc,
     "matmul_resnet50_fc": bench_matmul_ex,
     "matmul_vgg16_fc": bench_matmul_ex,
+    "bmatmul_16x1024": bench_bmatmul,
+    "matmul_t_4096": bench_bmatmul,
     "mcc_capsule_resnet50_first": bench_capsule,
     "scan_2p28": bench_scan,
     "scan_rows_65536x4096": bench_scan,

@@ -91,6 +91,16 @@ class MatmulCfg:
 
 
 @dataclass(frozen=True)
+class BMatmulCfg:
+    batch: int
+    M: int
+    N: int
+    K: int
+    trans: Tuple[int, int, int]  # views of A, B, C transposed
+    seed: int
+
+
+@dataclass(frozen=True)
 class StencilCfg:
     nx: int
     ny: int
@@ -133,6 +143,9 @@ CONFIGS: Dict[str, object] = {
     "mcc_resnet50_first": MccCfg(16, 230, 230, 3, 64, 7, 7, (2, 2), SEED_BASE + 9),
     "matmul_resnet50_fc": MatmulCfg(16, 1000, 2048, SEED_BASE + 10),
     "matmul_vgg16_fc": MatmulCfg(16, 4096, 25088, SEED_BASE + 11),
+    # bMatMul and MatMul^T of the paper's example table (Section "Examples"), at sizes that fill the chip
+    "bmatmul_16x1024": BMatmulCfg(16, 1024, 1024, 1024, (0, 0, 0), SEED_BASE + 16),
+    "matmul_t_4096": BMatmulCfg(1, 4096, 4096, 4096, (1, 1, 1), SEED_BASE + 17),
 }
 
 
@@ -142,6 +155,14 @@ def matmul_inputs(cfg: MatmulCfg):
         uniform(cfg.seed, 1, (cfg.M, cfg.K), -1.0, 1.0),
         uniform(cfg.seed, 2, (cfg.K, cfg.N), -1.0, 1.0),
     )
+
+
+def bmatmul_inputs(cfg: BMatmulCfg):
+    """A and B as the (possibly transposed) views store them: A[b,k,i] / B[b,j,k] when transposed."""
+    ta, tb, _ = cfg.trans
+    a = uniform(cfg.seed, 1, (cfg.batch, cfg.K, cfg.M) if ta else (cfg.batch, cfg.M, cfg.K), -1.0, 1.0)
+    b = uniform(cfg.seed, 2, (cfg.batch, cfg.N, cfg.K) if tb else (cfg.batch, cfg.K, cfg.N), -1.0, 1.0)
+    return a, b
 
 
 def stencil_inputs(cfg: StencilCfg):

@@ -142,6 +142,45 @@ def test_small_m_every_candidate(shape):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("views", [(0, 0, 0), (1, 0, 0), (0, 1, 0), (1, 1, 1)])
+def test_many_tiles_many_batches(views):
+    # more than eight tile rows (banded tile order), a workgroup count divisible by 8 (the XCD-aware
+    # order), ragged edges in every dimension, k-tiles of 16 and of 32
+    ta, tb, tc = views
+    for nb, M, N, K in ((8, 1300, 520, 200), (2, 1100, 260, 1060)):
+        A = W.uniform(W.SEED_BASE + 65, 1, (nb, K, M) if ta else (nb, M, K), -1, 1)
+        Bm = W.uniform(W.SEED_BASE + 65, 2, (nb, N, K) if tb else (nb, K, N), -1, 1)
+        ref, refabs = reference(A, Bm, ta, tb, tc)
+        got, _ = run(A, Bm, ta, tb, tc, None)
+        assert np.all(np.isfinite(got))
+        assert float(np.max(np.abs(got - ref) / refabs)) <= TOL, (nb, M, N, K, views)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", ["bmatmul_16x1024", "matmul_t_4096"])
+def test_bench_sizes_sampled(name):
+    cfg = W.CONFIGS[name]
+    ta, tb, tc = cfg.trans
+    A, Bm = W.bmatmul_inputs(cfg)
+    got, _ = run(A, Bm, ta, tb, tc, None)
+    assert np.all(np.isfinite(got))
+    rng = np.random.default_rng(7)
+    for b in sorted({0, cfg.batch - 1, int(rng.integers(0, cfg.batch))}):
+        a2 = np.ascontiguousarray(A[b].T) if ta else A[b]
+        b2 = np.ascontiguousarray(Bm[b].T) if tb else Bm[b]
+        i = np.concatenate([rng.integers(0, cfg.M, 600), [0, cfg.M - 1, 127, 128]])
+        j = np.concatenate([rng.integers(0, cfg.N, 600), [0, cfg.N - 1, 128, 127]])
+        ref, refabs = oracle.matmul_at(a2, b2, i, j)
+        mine = got[b][j, i] if tc else got[b][i, j]
+        assert float(np.max(np.abs(mine - ref) / refabs)) <= TOL, (name, b)
+        # property at any size: column sums of the logical C, 1^T C = (1^T A) B, in fp64 on the host
+        Cb = got[b].T if tc else got[b]
+        want = a2.astype(np.float64).sum(axis=0) @ b2.astype(np.float64)
+        scale = np.abs(a2.astype(np.float64)).sum(axis=0) @ np.abs(b2.astype(np.float64))
+        assert np.max(np.abs(Cb.sum(axis=0) - want) / scale) <= TOL
+
+
+@pytest.mark.gpu
 def test_paper_shapes_small_m():
     # MatMul sizes of the paper's deep-learning study: (M, N, K) = (16, 1000, 2048) and (1, 1000, 2048)
     for M in (16, 1):
