@@ -166,7 +166,7 @@ int pow2_floor(int64_t x) {
 // lanes: `nt` lanes, first along the fast dimension, the rest along the largest other dimension
 // (concatenation dimensions preferred); workgroup parts: all of the concatenation dimensions, and
 // the reduced dimensions `split` ways in total while every part keeps at least 8 sequential steps.
-CustomPlan make_plan(const mdh_custom_desc* d, int nt, int64_t split, int vreg = 1) {
+CustomPlan make_plan(const mdh_custom_desc* d, int nt, int64_t split, int vreg = 1, int vec = 1) {
   CustomPlan pl;
   fill_from_desc(d, &pl);
   int left = nt;
@@ -195,6 +195,10 @@ CustomPlan make_plan(const mdh_custom_desc* d, int nt, int64_t split, int vreg =
       vt *= vreg;
     }
   }
+  // `vec` consecutive indices of the fast dimension per lane whether or not anything is reused
+  // across them: neighbouring register parts read and write neighbouring addresses
+  if (vec > 1 && pl.scan < 0 && !pl.red[pl.fast] && pl.V[pl.fast] == 1 && pl.N[pl.fast] >= 2 * pl.L[pl.fast] * vec)
+    pl.V[pl.fast] = vec;
   for (int i = 0; i < pl.D; ++i)
     if (!pl.red[i] && i != pl.scan) pl.WG[i] = cdiv(pl.N[i], pl.L[i] * pl.V[i]);
   // sequential parts of the concatenation dimensions only when the grid would not fit
@@ -249,7 +253,14 @@ CustomPlan default_plan(const mdh_custom_desc* d) {
     if (probe.scan < 0 && probe.red[probe.fast] && cc >= 2048 && probe.N[probe.fast] >= 1024) nt = 64;
     bool any_red = false;
     for (int i = 0; i < probe.D; ++i) any_red = any_red || probe.red[i] || i == probe.scan;
-    if (!any_red && cc >= (1 << 20)) nt = 1024;  // nothing but concatenation: Jacobi1D 2^26 4.0 against 3.5 TB/s
+    // nothing but concatenation: four consecutive indices of the fast dimension per lane, so that
+    // neighbouring parts share 16-byte accesses (Jacobi1D 2^26: 6.0 TB/s against 3.8 TB/s with one
+    // index per lane; 64, 256 and 1024 lanes per workgroup within 1 %), while that leaves 1024 workgroups
+    if (!any_red) {
+      CustomPlan pl = make_plan(d, 256, 1, 1, 4);
+      if (pl.CG >= 1024 && d->out_elem_bytes <= 16) return pl;
+      if (cc >= (1 << 20)) nt = 1024;
+    }
   }
   // an access that depends on every dimension streams its buffer once whatever the blocking
   // (MatVec's matrix): register parts then only cost lanes (MatVec 8192^2: 6.4 TB/s without them,
@@ -305,6 +316,8 @@ int candidates(const mdh_custom_desc* d, CustomPlan* out, int cap) {
       if (s > 1 && !any_red) continue;
       push(make_plan(d, nt, s));
     }
+  for (int vec : {4, 2})
+    for (int nt : {256, 1024, 64}) push(make_plan(d, nt, any_red ? 16 : 1, 1, vec));
   static const int vregs[] = {2, 4, 8};
   for (int v : vregs)
     for (int nt : {256, 64})
@@ -489,17 +502,24 @@ std::string generate(const mdh_custom_desc* d, const CustomPlan& pl) {
   // the V register parts of the concatenation dimensions: unrolled loops v<d>, flat index vf.
   // In the scalar phase the indices are clamped to the index space (a ragged edge then computes a
   // duplicate that is never stored), so that validity does not enter the inner loops.
+  // lanes whose register parts all lie inside the index space take copies of the scalar phase and
+  // of the stores without clamps and bounds checks on the register-blocked dimensions (see below)
+  bool clamp_now = true;
+  auto covers = [&](int i) { return pl.WG[i] * pl.Q[i] * pl.L[i] * pl.V[i] == pl.N[i]; };
+  bool inside_now = false;
   auto open_v = [&](std::string& in, bool clamp) {
     std::string vf = "0", ok = "true";
     for (int i : outer) {
       o.f("%s_Pragma(\"unroll\") for (int v%d = 0; v%d < %lld; ++v%d) {", in.c_str(), i, i, (long long)pl.V[i], i);
       in += "  ";
-      if (clamp)
+      // (a dimension whose parts cover its extent exactly needs no clamp: consecutive register parts
+      // then read consecutive addresses, which the compiler merges into 8- and 16-byte accesses)
+      if (clamp && !covers(i) && (clamp_now || pl.V[i] == 1))
         o.f("%sconst i64 i%d = b%d + v%d < N%d ? b%d + v%d : N%d - 1;", in.c_str(), i, i, i, i, i, i, i);
       else
         o.f("%sconst i64 i%d = b%d + v%d;", in.c_str(), i, i, i);
       vf = "(" + vf + ") * " + std::to_string(pl.V[i]) + " + v" + std::to_string(i);
-      ok += " && i" + std::to_string(i) + " < N" + std::to_string(i);
+      if (!covers(i) && (!inside_now || pl.V[i] == 1)) ok += " && i" + std::to_string(i) + " < N" + std::to_string(i);
     }
     o.line(in + "const int vf = " + vf + ";");
     if (!clamp) o.line(in + "const bool cc_ok = " + ok + "; (void)cc_ok;");
@@ -535,62 +555,85 @@ std::string generate(const mdh_custom_desc* d, const CustomPlan& pl) {
   std::vector<int> reds;
   for (int i = 0; i < D; ++i)
     if (pl.red[i]) reds.push_back(i);
-  if (reds.empty()) {
-    o.line(ind + "{");
-    o.line(ind + "  const bool had = false;");
-    emit_body(ind + "  ", true);
-    o.line(ind + "  have = true;");
-    o.line(ind + "}");
-  } else {
-    // outer reduced dimensions: plain loops that skip indices beyond the index space
-    std::string ind2 = ind;
-    for (size_t k = 0; k + 1 < reds.size(); ++k) {
-      const int i = reds[k];
-      o.f("%sfor (int q%d = 0; q%d < %lld; ++q%d) {", ind2.c_str(), i, i, (long long)pl.Q[i], i);
+  auto emit_scalar_phase = [&](std::string ind) {
+    if (reds.empty()) {
+      o.line(ind + "{");
+      o.line(ind + "  const bool had = false;");
+      emit_body(ind + "  ", true);
+      o.line(ind + "  have = true;");
+      o.line(ind + "}");
+    } else {
+      // outer reduced dimensions: plain loops that skip indices beyond the index space
+      std::string ind2 = ind;
+      for (size_t k = 0; k + 1 < reds.size(); ++k) {
+        const int i = reds[k];
+        o.f("%sfor (int q%d = 0; q%d < %lld; ++q%d) {", ind2.c_str(), i, i, (long long)pl.Q[i], i);
+        ind2 += "  ";
+        o.f("%sconst i64 i%d = %s + 0;", ind2.c_str(), i, index_expr(pl, i).c_str());
+        o.f("%sif (i%d >= N%d) continue;", ind2.c_str(), i, i);
+      }
+      // innermost reduced dimension: the first step may start the part (no neutral element); after it
+      // a lane either has a value or has no index at all in this row, so the remaining steps combine
+      // unconditionally; rows that lie completely inside the index space run without bounds checks
+      const int r = reds.back();
+      const long long step = pl.strided ? (long long)(pl.WG[r] * pl.L[r]) : (long long)pl.L[r];
+      o.f("%s{", ind2.c_str());
       ind2 += "  ";
-      o.f("%sconst i64 i%d = %s + 0;", ind2.c_str(), i, index_expr(pl, i).c_str());
-      o.f("%sif (i%d >= N%d) continue;", ind2.c_str(), i, i);
-    }
-    // innermost reduced dimension: the first step may start the part (no neutral element); after it
-    // a lane either has a value or has no index at all in this row, so the remaining steps combine
-    // unconditionally; rows that lie completely inside the index space run without bounds checks
-    const int r = reds.back();
-    const long long step = pl.strided ? (long long)(pl.WG[r] * pl.L[r]) : (long long)pl.L[r];
-    o.f("%s{", ind2.c_str());
-    ind2 += "  ";
-    o.f("%sconst int q%d = 0; (void)q%d;", ind2.c_str(), r, r);
-    o.f("%sconst i64 r0_ = %s + 0;", ind2.c_str(), index_expr(pl, r).c_str());
-    o.f("%sif (r0_ < N%d) {", ind2.c_str(), r);
-    o.f("%s  const bool had = have;", ind2.c_str());
-    o.f("%s  const i64 i%d = r0_;", ind2.c_str(), r);
-    emit_body(ind2 + "  ", true);
-    o.f("%s  have = true;", ind2.c_str());
-    o.f("%s}", ind2.c_str());
-    if (pl.Q[r] > 1) {
-      o.f("%sif (r0_ + %lldLL < N%d) {", ind2.c_str(), (long long)(pl.Q[r] - 1) * step, r);
-      o.f("%s  _Pragma(\"unroll 4\") for (int s_ = 1; s_ < %lld; ++s_) {", ind2.c_str(), (long long)pl.Q[r]);
-      o.f("%s    const i64 i%d = r0_ + s_ * %lldLL;", ind2.c_str(), r, step);
-      emit_body(ind2 + "    ", false);
-      o.f("%s  }", ind2.c_str());
-      o.f("%s} else {", ind2.c_str());
-      o.f("%s  for (int s_ = 1; s_ < %lld; ++s_) {", ind2.c_str(), (long long)pl.Q[r]);
-      o.f("%s    const i64 i%d = r0_ + s_ * %lldLL;", ind2.c_str(), r, step);
-      o.f("%s    if (i%d >= N%d) break;", ind2.c_str(), r, r);
-      emit_body(ind2 + "    ", false);
-      o.f("%s  }", ind2.c_str());
+      o.f("%sconst int q%d = 0; (void)q%d;", ind2.c_str(), r, r);
+      o.f("%sconst i64 r0_ = %s + 0;", ind2.c_str(), index_expr(pl, r).c_str());
+      o.f("%sif (r0_ < N%d) {", ind2.c_str(), r);
+      o.f("%s  const bool had = have;", ind2.c_str());
+      o.f("%s  const i64 i%d = r0_;", ind2.c_str(), r);
+      emit_body(ind2 + "  ", true);
+      o.f("%s  have = true;", ind2.c_str());
       o.f("%s}", ind2.c_str());
-    }
-    ind2.resize(ind2.size() - 2);
-    o.f("%s}", ind2.c_str());
-    for (size_t k = 0; k + 1 < reds.size(); ++k) {
+      if (pl.Q[r] > 1) {
+        o.f("%sif (r0_ + %lldLL < N%d) {", ind2.c_str(), (long long)(pl.Q[r] - 1) * step, r);
+        o.f("%s  _Pragma(\"unroll 4\") for (int s_ = 1; s_ < %lld; ++s_) {", ind2.c_str(), (long long)pl.Q[r]);
+        o.f("%s    const i64 i%d = r0_ + s_ * %lldLL;", ind2.c_str(), r, step);
+        emit_body(ind2 + "    ", false);
+        o.f("%s  }", ind2.c_str());
+        o.f("%s} else {", ind2.c_str());
+        o.f("%s  for (int s_ = 1; s_ < %lld; ++s_) {", ind2.c_str(), (long long)pl.Q[r]);
+        o.f("%s    const i64 i%d = r0_ + s_ * %lldLL;", ind2.c_str(), r, step);
+        o.f("%s    if (i%d >= N%d) break;", ind2.c_str(), r, r);
+        emit_body(ind2 + "    ", false);
+        o.f("%s  }", ind2.c_str());
+        o.f("%s}", ind2.c_str());
+      }
       ind2.resize(ind2.size() - 2);
       o.f("%s}", ind2.c_str());
+      for (size_t k = 0; k + 1 < reds.size(); ++k) {
+        ind2.resize(ind2.size() - 2);
+        o.f("%s}", ind2.c_str());
+      }
     }
+  };
+  // ragged register-blocked dimensions: the clamp (a select on every index) and the bounds check
+  // of every store would keep the compiler from merging the accesses of neighbouring parts, so a
+  // lane whose parts all lie inside the index space -- all but those at the edge -- runs a copy
+  // without them
+  std::string inside;
+  for (int i : outer)
+    if (i != pl.scan && pl.V[i] > 1 && !covers(i)) {
+      char buf[96];
+      snprintf(buf, sizeof buf, "%sb%d + %lld <= N%d", inside.empty() ? "" : " && ", i, (long long)pl.V[i], i);
+      inside += buf;
+    }
+  if (inside.empty()) {
+    emit_scalar_phase(ind);
+  } else {
+    o.line(ind + "if (" + inside + ") {");
+    clamp_now = false;
+    emit_scalar_phase(ind + "  ");
+    clamp_now = true;
+    o.line(ind + "} else {");
+    emit_scalar_phase(ind + "  ");
+    o.line(ind + "}");
   }
   // re-composition of every register part: lane -> workgroup in an LDS tree over the lanes of the
   // reduced dimensions, then the output view or the workspace
-  {
-    std::string in3 = ind;
+  auto emit_recompose = [&](std::string in3) {
     open_v(in3, false);
     o.line(in3 + "mdh_T a_ = acc[vf];");
     o.line(in3 + "bool h_ = have;");
@@ -629,6 +672,17 @@ std::string generate(const mdh_custom_desc* d, const CustomPlan& pl) {
       o.line(in3 + "  out[" + (d->out_index ? d->out_index : "cc_") + "] = " + val + "; (void)cc_;");
     o.f("%s}", in3.c_str());
     close_v(in3);
+  };
+  if (!inside.empty() && pl.RL == 1) {  // no barrier in the re-composition: lanes may take different copies
+    o.line(ind + "if (" + inside + ") {");
+    inside_now = true;
+    emit_recompose(ind + "  ");
+    inside_now = false;
+    o.line(ind + "} else {");
+    emit_recompose(ind + "  ");
+    o.line(ind + "}");
+  } else {
+    emit_recompose(ind);
   }
   for (size_t i = 0; i < outer.size(); ++i) {
     ind.resize(ind.size() - 2);

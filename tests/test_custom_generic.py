@@ -128,8 +128,20 @@ def test_register_parts_of_concatenation_dimensions():
     q = p.copy()
     q.prt[B.L_VGPR][2], q.prt[B.L_HBM][2] = 2, q.prt[B.L_HBM][2] // 2
     assert mdh.mdh_custom_validate_params(d, q) == 6
-    # Jacobi1D: every access depends on the only dimension: nothing to re-use, no blocking
-    assert mdh.mdh_custom_default_params(d_jacobi1d(1 << 20, 0.5)).prt[B.L_VGPR][0] == 1
+    # Jacobi1D: every access depends on the only dimension, nothing to re-use -- but four consecutive
+    # indices per lane share 16-byte accesses; where the extent is ragged the interior lanes run a
+    # copy of the scalar phase and of the stores without clamps and bounds checks
+    pj = mdh.mdh_custom_default_params(d_jacobi1d(1 << 20, 0.5))
+    assert pj.prt[B.L_VGPR][0] == 4 and pj.prt[B.L_LANE][0] == 256 and not pj.ragged
+    src = mdh.mdh_custom_source(mdh.mdh_custom_create(d_jacobi1d(1 << 20, 0.5), pj))
+    assert "N0 - 1" not in src and "b0 + 4 <= N0" not in src
+    dj = d_jacobi1d((1 << 20) + 3, 0.5)
+    pj = mdh.mdh_custom_default_params(dj)
+    assert pj.prt[B.L_VGPR][0] == 4 and pj.ragged
+    src = mdh.mdh_custom_source(mdh.mdh_custom_create(dj, pj))
+    assert src.count("if (b0 + 4 <= N0) {") == 2 and src.count("N0 - 1") == 1
+    # too few points for 1024 workgroups of four-index lanes: one index per lane
+    assert mdh.mdh_custom_default_params(d_jacobi1d(1 << 16, 0.5)).prt[B.L_VGPR][0] == 1
 
 
 def test_planner_rejects_bad_tables():
@@ -235,6 +247,47 @@ def test_small_against_generic_evaluator():
     for p in all_params(dm):
         got = run(dm, [dev(v)], torch.full((1,), 99, dtype=torch.int32, device="cuda"), p)
         assert got.item() == G.reduce_op(min, v.tolist())
+
+
+@pytest.mark.gpu
+def test_pure_concatenation_several_indices_per_lane():
+    # Jacobi1D with a ragged extent, every candidate (1, 2 and 4 consecutive indices per lane, the
+    # interior lanes on the copy without clamps) against the definitional evaluator; integers: exact
+    rng = np.random.default_rng(11)
+    n = 2051
+    x = rng.integers(0, 10, n + 2).astype(np.float32)
+    want = G.jacobi1d(x.astype(int).tolist(), 2)
+    d = d_jacobi1d(n, 2.0)
+    seen = set()
+    for p in all_params(d):
+        seen.add((p or mdh.mdh_custom_default_params(d)).prt[B.L_VGPR][0])
+        got = run(d, [dev(x)], torch.full((n,), float("nan"), device="cuda"), p)
+        assert got.cpu().tolist() == want, p and p.table()
+    assert {1, 2, 4} <= seen
+    # two concatenation dimensions, the fast one ragged: out[i,j] = a[i,j] + b[j]
+    from oracle import mdhom as H
+    M, N = 3, 601
+    a = rng.integers(-9, 10, (M, N)).astype(np.float32)
+    b = rng.integers(-9, 10, N).astype(np.float32)
+    iv = H.inp_view([[lambda i, j: (i, j)], [lambda i, j: (j,)]])
+    h = H.md_hom(lambda t: t[0] + t[1], (H.concat(0), H.concat(1)))
+    (o,) = H.out_view([[lambda i, j: (i, j)]])(h(iv([a.astype(int).tolist(), b.astype(int).tolist()], [range(M), range(N)])))
+    want = [[o[(i, j)] for j in range(N)] for i in range(M)]
+    d2 = mdh.custom_desc((M, N), (0, 0), ["float", "float"], [(0, "i0*N1+i1"), (1, "i1")], "float", 4, "r = a0 + a1;")
+    seen = set()
+    for p in all_params(d2):
+        seen.add((p or mdh.mdh_custom_default_params(d2)).prt[B.L_VGPR][1])
+        got = run(d2, [dev(a), dev(b)], torch.full((M, N), float("nan"), device="cuda"), p)
+        assert got.cpu().tolist() == want, p and p.table()
+    assert {1, 4} <= seen
+    # at a size where the default takes four indices per lane, ragged and not: the closed form for
+    # x[i] = i, out[i] = 2 * (3i + 3), exact in fp32 below 2^24
+    for n in ((1 << 21) + 3, 1 << 21):
+        d = d_jacobi1d(n, 2.0)
+        assert mdh.mdh_custom_default_params(d).prt[B.L_VGPR][0] == 4
+        xs = torch.arange(n + 2, dtype=torch.float32, device="cuda")
+        got = run(d, [xs], torch.full((n,), float("nan"), device="cuda"))
+        assert np.array_equal(got.cpu().numpy(), (6 * np.arange(n) + 6).astype(np.float32))
 
 
 @pytest.mark.gpu
