@@ -37,22 +37,24 @@ PRL_LANE_OPS_PER_PAIR = 24.0
 # None until measured for that workload
 TRAFFIC_BYTES = {
     # profiles/all_kernels_hbm_traffic_pmc.md (all kernels of a step)
-    "jacobi3d_512": 1110138640,
-    "dot_2p28": 2147348249,
-    "matvec_16384": 1074468558,
-    "matmul_4096": 604066186,
-    "matmul_ts": 1102097670,
-    "mcc_resnet": 891753253,
-    "prl_2p16_2p18": 154105210,
-    "matmul_256": 1939164,
-    "mcc_resnet50_first": 62430680,
-    "matmul_resnet50_fc": 13577190,
-    "matmul_vgg16_fc": 426313928,
-    "mcc_capsule_resnet50_first": 1072648289,
-    "scan_2p28": 2151803943,
-    "scan_rows_65536x4096": 2147503399,
-    "histo_generic_256x2p24": 204977349,
-    "prl_generic_2p16_2p18": 271641353,
+    "jacobi3d_512": 1110416009,
+    "dot_2p28": 2147389203,
+    "matvec_16384": 1074488255,
+    "matmul_4096": 604076427,
+    "matmul_ts": 1102264408,
+    "mcc_resnet": 892945099,
+    "prl_2p16_2p18": 154071885,
+    "matmul_256": 1939196,
+    "mcc_resnet50_first": 62431311,
+    "matmul_resnet50_fc": 13577438,
+    "matmul_vgg16_fc": 426322180,
+    "bmatmul_16x1024": 201454135,
+    "matmul_t_4096": 604047254,
+    "mcc_capsule_resnet50_first": 1072652885,
+    "scan_2p28": 2151693493,
+    "scan_rows_65536x4096": 2147531895,
+    "histo_generic_256x2p24": 205332319,
+    "prl_generic_2p16_2p18": 271642345,
 }
 
 
