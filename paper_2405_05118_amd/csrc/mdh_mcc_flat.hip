@@ -333,6 +333,10 @@ mdh_status launch_mcc_flat(const MccPlan& pl, int64_t N, int64_t H, int64_t W, i
   MDH_FL(32, 1, 1, 4, 1)  // 4 x 32 pixels x 32 channels
   MDH_FL(16, 2, 2, 2, 2)  // 8 x 16 pixels x 128 channels
   MDH_FL(32, 2, 2, 2, 2)  // 4 x 32 pixels x 128 channels
+  MDH_FL(16, 1, 1, 4, 2)  // 8 x 16 pixels x 64 channels, eight wavefronts
+  MDH_FL(32, 1, 1, 4, 2)  // 4 x 32 pixels x 64 channels, eight wavefronts
+  MDH_FL(16, 1, 1, 8, 1)  // 16 x 16 pixels x 32 channels, eight wavefronts
+  MDH_FL(32, 1, 1, 8, 1)  // 8 x 32 pixels x 32 channels, eight wavefronts
 #undef MDH_FL
   return MDH_ERR_UNSUPPORTED;
 }
