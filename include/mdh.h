@@ -22,6 +22,11 @@
  *   - every buffer pointer is a DEVICE pointer owned by the caller; the library
  *     never allocates, frees or synchronises; a call only enqueues kernels on
  *     `stream` (a hipStream_t passed as void*, NULL = the default stream);
+ *     workspaces are cleared by kernels, not memsets, so a call may be captured
+ *     into a HIP graph once one eager call with the same sizes and parameters
+ *     has run on that device (the first use of a kernel sets its dynamic-LDS
+ *     attribute and caches device properties; mdh_custom_run loads its module);
+ *     the tune calls are the exception, they time candidates and synchronise;
  *   - inputs are never written; outputs are fully overwritten (the paper's
  *     re-composition overrides on first write, it does not accumulate into the
  *     destination: Appendix "Code Generation", re-composition phase);
