@@ -551,7 +551,11 @@ static PrlPlan prl_default(const int64_t* s) {
   const int64_t wgs_a = cdiv(s[0], (int64_t)pl.WA * 64 * pl.RA);
   int S = 1;
   // split B over workgroups until there are ~64 wavefronts per SIMD of the chip to draw from
-  // (2^16 x 2^18: 10.35 ms with 4 parts, 10.0 with 8, 9.8 with 16, 9.75 with 32)
+  // (2^16 x 2^18: 10.35 ms with 4 parts, 10.0 with 8, 9.8 with 16, 9.75 with 32) while a wavefront
+  // keeps 256 records of B; with few records of A first of all a workgroup per compute unit, down to
+  // 32 records of B per wavefront (2^10 x 2^14: 30 us with 32 parts, 41 with 16, 69 with 8;
+  // 2^8 x 2^18: 104 us with 128 parts, 129 with 256)
+  while (wgs_a * S < 256 && S < 256 && s[1] / (2ll * S * pl.WB) >= 32) S *= 2;
   while (wgs_a * S * pl.WB * pl.WA < 65536 && S < 256 && s[1] / (2ll * S * pl.WB) >= 256) S *= 2;
   pl.S = S;
   pl.ragged = prl_ragged(s, pl);

@@ -41,6 +41,8 @@ static DotPlan dot_default(const int64_t* s) {
   DotPlan pl{8, 1, 0};
   int S = 1;
   while (S < 256 && s[0] / (2ll * S) >= (int64_t)pl.WAVES * 256 * 8) S *= 2;
+  // a few KiB in all: one workgroup and no second pass (2^16 elements: 8.8 us against 12.3 us)
+  if (s[0] <= (1 << 17)) S = 1;
   pl.S = S;
   pl.ragged = dot_ragged(s, pl);
   return pl;
