@@ -11,8 +11,9 @@
 //                     the BN x CK filter slice of a tap is staged in LDS (double buffered)
 //   wavefront layer : rows of the patch x (BN/WN)
 //   VGPR layer      : (WM/32) x (WN/32) accumulator blocks per wavefront
-//   block           : 32 consecutive q x 32 output channels x 2 input channels per
-//                     v_mfma_f32_32x32x2_f32
+//   block           : (32/TQ rows of p) x (TQ consecutive q) x 32 output channels x 2 input channels
+//                     per v_mfma_f32_32x32x2_f32; TQ = 32, or 16 / 8 for images narrower than 32
+//                     output columns (a block then spans 2 / 4 output rows instead of idle lanes)
 // The three + dimensions are re-composed inside the MFMA accumulators (register region); the
 // order c-chunk, r, s, c is free because + is their common combine operator.
 #include "mdh_internal.h"
@@ -26,9 +27,11 @@ typedef float f16 __attribute__((ext_vector_type(16)));
 
 template <int TP, int TQ, int BN, int CK, int WM, int WN>
 struct MccCfg {
-  static_assert(TQ == 32, "one MFMA block spans 32 consecutive q");
+  static_assert(TQ == 32 || TQ == 16 || TQ == 8, "an MFMA block spans 32 pixels: 32/TQ rows of TQ columns");
+  static constexpr int RB = 32 / TQ;  // output rows per block
   static constexpr int MI = WM / 32, NI = WN / 32;
-  static constexpr int WAVES_M = TP / MI, WAVES_N = BN / WN;
+  static_assert(TP % (MI * RB) == 0, "rows of the tile = wavefronts x blocks x rows per block");
+  static constexpr int WAVES_M = TP / (MI * RB), WAVES_N = BN / WN;
   static constexpr int NT = WAVES_M * WAVES_N * 64;
   static constexpr int PC = CK + 4;  // floats per staged pixel / filter row (c contiguous)
   static constexpr int F_STAGE = BN * PC;
@@ -109,7 +112,8 @@ __device__ __forceinline__ void mcc_tile(const float* __restrict__ in, const flo
   struct Frag {
     f4 a[Cf::MI], b[Cf::NI];
   };
-  const int a_row = sh * PW * Cf::PC;  // LDS distance between consecutive output rows of the patch
+  const int a_row = Cf::RB * sh * PW * Cf::PC;  // LDS distance between consecutive blocks of a wavefront
+  const int dp = l32 / TQ, dq = l32 % TQ;      // the lane's pixel inside a block
   auto load_frag = [&](Frag& f, const float* as, const float* bs, int cc) {
 #pragma unroll
     for (int mi = 0; mi < Cf::MI; ++mi) f.a[mi] = *(const f4*)(as + mi * a_row + cc);
@@ -126,7 +130,7 @@ __device__ __forceinline__ void mcc_tile(const float* __restrict__ in, const flo
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[mi][t], f.b[ni][t], acc[mi][ni], 0, 0, 0);
   };
   auto compute = [&](const float* fst, int r, int s) {
-    const float* as = ps + (((wm * Cf::MI) * sh + r) * PW + l32 * sw + s) * Cf::PC + lh * 4;
+    const float* as = ps + (((wm * Cf::MI * Cf::RB + dp) * sh + r) * PW + dq * sw + s) * Cf::PC + lh * 4;
     const float* bs = fst + (wn * WN + l32) * Cf::PC + lh * 4;
 #pragma unroll
     for (int cc = 0; cc < CK; cc += 8) {
@@ -164,13 +168,14 @@ __device__ __forceinline__ void mcc_tile(const float* __restrict__ in, const flo
   // output view (n,p,q,k,0,0,0) -> out[n,p,q,k]
 #pragma unroll
   for (int mi = 0; mi < Cf::MI; ++mi) {
-    const int p = p0 + wm * Cf::MI + mi;
 #pragma unroll
     for (int ni = 0; ni < Cf::NI; ++ni) {
       const int k = k0 + wn * WN + ni * 32 + l32;
 #pragma unroll
       for (int rg = 0; rg < 16; ++rg) {
-        const int q = q0 + 8 * (rg / 4) + 4 * lh + (rg % 4);
+        const int pix = 8 * (rg / 4) + 4 * lh + (rg % 4);  // pixel of the block this register holds
+        const int p = p0 + (wm * Cf::MI + mi) * Cf::RB + pix / TQ;
+        const int q = q0 + pix % TQ;
         if (!GUARD || (p < P && q < Q && k < K))
           out[(((int64_t)n * P + p) * Q + q) * K + k] = acc[mi][ni][rg];
       }
@@ -238,6 +243,10 @@ mdh_status launch_mcc(const MccPlan& pl, int64_t N, int64_t H, int64_t W, int64_
   MDH_MCC(8, 32, 128, 16, 128, 64)
   MDH_MCC(2, 32, 64, 16, 32, 32)
   MDH_MCC(4, 32, 64, 16, 64, 32)
+  MDH_MCC(8, 16, 128, 16, 64, 64)  // blocks of 2 x 16 pixels
+  MDH_MCC(8, 16, 64, 16, 64, 32)
+  MDH_MCC(8, 8, 128, 16, 32, 64)   // blocks of 4 x 8 pixels
+  MDH_MCC(8, 8, 64, 16, 32, 32)
 #undef MDH_MCC
   return MDH_ERR_UNSUPPORTED;
 }

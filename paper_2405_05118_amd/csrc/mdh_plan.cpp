@@ -320,6 +320,10 @@ static const MccInst kMccMenu[] = {  // channel-chunked kernel
     {8, 32, 128, 16, 128, 64},
     {2, 32, 64, 16, 32, 32},
     {4, 32, 64, 16, 64, 32},
+    {8, 16, 128, 16, 64, 64},  // blocks of 2 x 16 pixels (images narrower than 32 output columns)
+    {8, 16, 64, 16, 64, 32},
+    {8, 8, 128, 16, 32, 64},   // blocks of 4 x 8 pixels
+    {8, 8, 64, 16, 32, 32},
 };
 // few-channel kernel (s and c fused): TP rows x TQ = QB columns of pixels, BN channels, WM, WN
 static const MccInst kMccFlatMenu[] = {
@@ -369,15 +373,16 @@ void params_from_plan(const int64_t* s, const MccPlan& pl, mdh_tile_params* p) {
     p->prt[MDH_L_WAVE][1] = pl.TP / (rb * mi);
     p->prt[MDH_L_VGPR][1] = mi;
   } else {
-    p->blk[2] = 32;  // 32 consecutive q of one output row
-    p->blk[4] = 2;   // 2 input channels per MFMA
+    // the block: 32 pixels = (32/TQ rows of p) x (TQ consecutive q), 2 input channels per MFMA
+    const int rb = 32 / pl.TQ, mi = pl.WM / 32;
+    p->blk[1] = rb;
+    p->blk[2] = pl.TQ;
+    p->blk[4] = 2;
     p->prt[MDH_L_HBM][4] = (int32_t)cdiv(s[4], pl.CK);
     p->prt[MDH_L_LDS][4] = pl.CK / 2;
-    // wavefront grid: (TP*TQ/WM) along the pixels (rows of p first), BN/WN along k
-    const int wm_rows = pl.WM / pl.TQ > 0 ? pl.WM / pl.TQ : 1;  // output rows per wavefront
-    p->prt[MDH_L_WAVE][1] = pl.TP / wm_rows;
-    p->prt[MDH_L_VGPR][1] = wm_rows;
-    p->prt[MDH_L_VGPR][2] = pl.TQ / 32;
+    // wavefront grid: TP/(mi*rb) along p, BN/WN along k; mi blocks along p per wavefront
+    p->prt[MDH_L_WAVE][1] = pl.TP / (mi * rb);
+    p->prt[MDH_L_VGPR][1] = mi;
   }
   static const int dims[7] = {0, 1, 2, 3, 4, 5, 6};
   set_order(p, dims);
@@ -442,8 +447,33 @@ static MccPlan mcc_default(const int64_t* s) {
     MccPlan f = mcc_flat_plan(s);
     if (mcc_lds_bytes(f, s) <= kLdsBytesPerWG) return f;
   }
-  MccPlan pl{4, 32, 128, 16, 64, 64, 0, 0};
-  if (s[3] <= 64) pl = MccPlan{4, 32, 64, 16, 64, 32, 0, 0};
+  // Pixel block: 32 consecutive q of one row, 2 x 16 or 4 x 8 pixels -- the shape whose tiles (4 x 32,
+  // 8 x 16, 8 x 8 pixels) pad the image least; on a tie the widest.  Squarer tiles also stage less
+  // halo.  Measured against blocks of 32 columns throughout: 32 x 112 x 112 x 64 -> 32, 3 x 3: 0.144
+  // against 0.191 ms; 16 x 56 x 56, 1 x 1, 256 -> 64 / 64 -> 256: 28 / 32 us against 41 / 55 us;
+  // 16 x 14 x 14 x 256 -> 256, 3 x 3: 122 against 137 us.
+  const int64_t P = s[1] > 0 ? s[1] : 1, Q = s[2] > 0 ? s[2] : 1;
+  // (on a tie the widest that still gives two workgroups per compute unit at 64 channels per
+  // workgroup, else the narrowest: 16 x 14 x 14 x 256 -> 256: 122 us with 4 x 8, 143 us with 2 x 16)
+  int tq = 32, tp = 4;
+  int64_t area = -1;
+  bool enough = false;
+  for (int t : {32, 16, 8}) {
+    const int rows = t == 32 ? 4 : 8;
+    const int64_t a = cdiv(P, rows) * rows * cdiv(Q, t) * t;
+    const bool many = (s[0] > 0 ? s[0] : 1) * cdiv(P, rows) * cdiv(Q, t) * cdiv(s[3] > 0 ? s[3] : 1, 64) >= 512;
+    if (area < 0 || a < area || (a == area && !enough)) area = a, tq = t, tp = rows, enough = many;
+  }
+  const int wm = tq == 8 ? 32 : 64;  // two blocks along p per wavefront, one for the 4 x 8 block
+  MccPlan pl{tp, tq, 128, 16, wm, 64, 0, 0};
+  if (s[3] <= 64) pl = MccPlan{tp, tq, 64, 16, wm, 32, 0, 0};
+  // small images: narrower channel slices when there are fewer than two workgroups per compute unit
+  // (16 x 28 x 28 x 128 -> 128, 3 x 3: 76 us against 124 us; 7 x 7 x 512: 283 against 462 us; fewer
+  // rows per workgroup on top of that measured slower)
+  auto wgs = [&](const MccPlan& m) {
+    return (s[0] > 0 ? s[0] : 1) * cdiv(P, m.TP) * cdiv(Q, m.TQ) * cdiv(s[3] > 0 ? s[3] : 1, m.BN);
+  };
+  if (wgs(pl) < 512 && pl.BN == 128) pl = MccPlan{tp, tq, 64, 16, wm, 32, 0, 0};
   pl.ragged = mcc_ragged(s, pl);
   return pl;
 }
@@ -499,9 +529,10 @@ mdh_status plan_mcc(const int64_t* s, const mdh_tile_params* p, MccPlan* out) {
     // a workgroup part of q that owns no tile is not a partition of the columns
     if ((int64_t)(p->prt[MDH_L_WG][2] - 1) * pl.QT * pl.TQ >= (s[2] > 0 ? s[2] : 1)) return MDH_ERR_TILE_NOT_DIVIDING;
   } else {
-    pl.TQ = p->prt[MDH_L_VGPR][2] * 32;
-    pl.TP = p->prt[MDH_L_WAVE][1] * p->prt[MDH_L_VGPR][1];
-    pl.WM = p->prt[MDH_L_VGPR][1] * pl.TQ;
+    pl.TQ = p->blk[2];
+    if (pl.TQ != 8 && pl.TQ != 16 && pl.TQ != 32) return MDH_ERR_UNSUPPORTED;
+    pl.WM = p->prt[MDH_L_VGPR][1] * 32;
+    pl.TP = p->prt[MDH_L_WAVE][1] * p->prt[MDH_L_VGPR][1] * (32 / pl.TQ);
     pl.CK = p->prt[MDH_L_LDS][4] * 2;
   }
   pl.ragged = ragged;

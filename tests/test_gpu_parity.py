@@ -166,6 +166,8 @@ MCC_SMALL = [
     (2, 15, 17, 5, 9, 3, 2, (2, 2)),      # strided, ragged everything, C not a multiple of 4
     (1, 9, 9, 3, 4, 1, 1, (1, 1)),        # 1x1 filter
     (3, 1, 1, 40, 7, 1, 1, (1, 1)),       # reduces to a matmul
+    (2, 16, 16, 24, 40, 3, 3, (1, 1)),    # 14 x 14 outputs: blocks of 2 x 16 and 4 x 8 pixels pay off
+    (3, 15, 15, 16, 130, 3, 3, (2, 2)),   # 7 x 7 outputs, strided, ragged channels
 ]
 
 
