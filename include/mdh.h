@@ -221,6 +221,9 @@ mdh_status mdh_stencil(int64_t nx, int64_t ny, int64_t nz, const float* in, floa
  *   in: N x H x W x C (NHWC), filt: K x R x S x C (KRSC), out: N x P x Q x K,
  *   P = (H-R)/stride_h + 1, Q = (W-S)/stride_w + 1 (no implicit padding),
  *   fp32, device.  C, R, S >= 1; H >= R; W >= S; strides >= 1.
+ * Tile parameters: blk[p] x blk[q] is the pixel shape of the 32-pixel MFMA block
+ * (1 x 32, 2 x 16 or 4 x 8), blk[k] = 32; blk[c] = 2 selects the channel-chunked
+ * kernel, blk[c] = 1 the few-channel kernel that walks s and c as one dimension.
  */
 mdh_status mdh_mcc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
                    int64_t stride_h, int64_t stride_w, const float* in, const float* filt,
