@@ -194,7 +194,8 @@ def bench_mcc(torch, mdh, W, name, steps, warmup, cpu):
     x = W.device_normal(cfg.seed, 1, (cfg.N, cfg.H, cfg.W, cfg.C))
     f = W.device_normal(cfg.seed, 2, (cfg.K, cfg.R, cfg.S, cfg.C))
     o = torch.empty((cfg.N, P, Q, cfg.K), dtype=torch.float32, device="cuda")
-    ms, wall = _events_ms(torch, lambda: mdh.mdh_mcc(x, f, o, cfg.stride), steps, warmup)
+    ws = _ws(torch, mdh, mdh.MDH_MCC, (cfg.N, P, Q, cfg.K, cfg.C, cfg.R, cfg.S, cfg.stride[0], cfg.stride[1]))
+    ms, wall = _events_ms(torch, lambda: mdh.mdh_mcc(x, f, o, cfg.stride, None, ws), steps, warmup)
     flop = 2.0 * cfg.N * P * Q * cfg.K * cfg.C * cfg.R * cfg.S
     tf = flop / ms / 1e9
     res = {

@@ -224,6 +224,11 @@ mdh_status mdh_stencil(int64_t nx, int64_t ny, int64_t nz, const float* in, floa
  * Tile parameters: blk[p] x blk[q] is the pixel shape of the 32-pixel MFMA block
  * (1 x 32, 2 x 16 or 4 x 8), blk[k] = 32; blk[c] = 2 selects the channel-chunked
  * kernel, blk[c] = 1 the few-channel kernel that walks s and c as one dimension.
+ * prt[MDH_L_WG][c] = S > 1 splits the reduction dimension c over workgroups: the S
+ * partial outputs go to `workspace` (S * N*P*Q*K floats, see mdh_workspace_size) and
+ * a second kernel adds them in ascending part order.  The library default does
+ * that for small images with many channels, so pass the workspace
+ * mdh_workspace_size asks for; it may be NULL when that size is 0.
  */
 mdh_status mdh_mcc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
                    int64_t stride_h, int64_t stride_w, const float* in, const float* filt,

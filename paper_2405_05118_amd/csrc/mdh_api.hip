@@ -62,8 +62,6 @@ mdh_status mdh_mcc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_
                    int64_t stride_h, int64_t stride_w, const float* in, const float* filt,
                    float* out, const mdh_tile_params* params, void* workspace,
                    size_t workspace_bytes, void* stream) {
-  (void)workspace;
-  (void)workspace_bytes;
   if (N < 0 || K < 0 || C < 1 || R < 1 || S < 1 || stride_h < 1 || stride_w < 1) return MDH_ERR_SIZE;
   if (H < R || W < S) return MDH_ERR_SIZE;
   if (too_big(N) || too_big(H) || too_big(W) || too_big(C) || too_big(K) || too_big(R) || too_big(S))
@@ -80,7 +78,12 @@ mdh_status mdh_mcc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_
   if (!in || !filt || !out) return MDH_ERR_NULL;
   if (pl.flat)
     return launch_mcc_flat(pl, N, H, W, C, K, R, S, stride_h, stride_w, in, filt, out, (hipStream_t)stream);
-  return launch_mcc(pl, N, H, W, C, K, R, S, stride_h, stride_w, in, filt, out, (hipStream_t)stream);
+  if (pl.S > 1) {
+    if (too_big((int64_t)pl.S * N * P * Q * K)) return MDH_ERR_SIZE;
+    const size_t need = (size_t)pl.S * (size_t)(N * P * Q * K) * sizeof(float);
+    if (!workspace || workspace_bytes < need) return MDH_ERR_WORKSPACE;
+  }
+  return launch_mcc(pl, N, H, W, C, K, R, S, stride_h, stride_w, in, filt, out, workspace, (hipStream_t)stream);
 }
 
 mdh_status mdh_mcc_capsule(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,

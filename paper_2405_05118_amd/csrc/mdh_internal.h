@@ -34,6 +34,7 @@ struct MccPlan {
   int ragged;
   int flat;    // 1: few-channel kernel that walks s and c as one fused dimension (TQ = block width)
   int QT = 1;  // few-channel kernel: column tiles a workgroup walks with its filter slice resident
+  int S = 1;   // channel-chunked kernel: workgroup-layer parts of the reduction dimension c
 };
 
 // Custom reduce: RA records of A per lane, WB wavefronts of a workgroup split B,
@@ -155,7 +156,7 @@ mdh_status launch_matmul(const GemmPlan& pl, int64_t M, int64_t N, int64_t K, co
                          const float* B, float* C, void* ws, hipStream_t st);
 mdh_status launch_mcc(const MccPlan& pl, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
                       int64_t R, int64_t S, int64_t sh, int64_t sw, const float* in,
-                      const float* filt, float* out, hipStream_t st);
+                      const float* filt, float* out, void* ws, hipStream_t st);
 mdh_status launch_mcc_flat(const MccPlan& pl, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
                            int64_t R, int64_t S, int64_t sh, int64_t sw, const float* in,
                            const float* filt, float* out, hipStream_t st);

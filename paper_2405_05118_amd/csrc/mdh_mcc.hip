@@ -3,9 +3,12 @@
 // (paper: Section "Examples", Subfigure 2: index functions p+r, q+s read neighbouring cells).
 //
 // De-composition, dims (n,p,q,k,c,r,s):
-//   workgroup layer : N x (P/TP) x (Q/TQ) x (K/BN)   -- one TP x TQ patch of output pixels of one
-//                     image and BN output channels per workgroup
-//   HBM layer       : C/CK sequential channel chunks; per chunk the (TP-1)*sh+R by (TQ-1)*sw+S
+//   workgroup layer : N x (P/TP) x (Q/TQ) x (K/BN) x SC -- one TP x TQ patch of output pixels of one
+//                     image and BN output channels per workgroup; SC > 1 splits the reduction
+//                     dimension c (small images with many channels would otherwise leave compute
+//                     units idle): the SC partial outputs go to a device-memory workspace and the
+//                     second pass of MatMul adds them in ascending part order
+//   HBM layer       : C/(SC*CK) sequential channel chunks; per chunk the (TP-1)*sh+R by (TQ-1)*sw+S
 //                     input patch is staged ONCE in LDS and reused by all R*S filter taps
 //   LDS layer       : R x S filter taps x CK/2 channel steps, sequential inside the staged patch;
 //                     the BN x CK filter slice of a tap is staged in LDS (double buffered)
@@ -43,7 +46,7 @@ template <int TP, int TQ, int BN, int CK, int WM, int WN, bool GUARD>
 __device__ __forceinline__ void mcc_tile(const float* __restrict__ in, const float* __restrict__ filt,
                                          float* __restrict__ out, int H, int W, int C, int K, int R,
                                          int S, int sh, int sw, int P, int Q, int n, int p0, int q0,
-                                         int k0, float* lds) {
+                                         int k0, int cbeg, int cend, float* lds) {
   using Cf = MccCfg<TP, TQ, BN, CK, WM, WN>;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -76,7 +79,7 @@ __device__ __forceinline__ void mcc_tile(const float* __restrict__ in, const flo
         } else if (k0 + kk < K) {
 #pragma unroll
           for (int e = 0; e < 4; ++e)
-            if (c0 + c4 * 4 + e < C) v[e] = p[e];
+            if (c0 + c4 * 4 + e < cend) v[e] = p[e];
         }
       }
       gf[x] = v;
@@ -103,7 +106,7 @@ __device__ __forceinline__ void mcc_tile(const float* __restrict__ in, const flo
       } else if (hy < H && wx < W) {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          if (c0 + c4 * 4 + e < C) v[e] = p[e];
+          if (c0 + c4 * 4 + e < cend) v[e] = p[e];
       }
       *(f4*)(ps + pix * Cf::PC + c4 * 4) = v;
     }
@@ -141,7 +144,7 @@ __device__ __forceinline__ void mcc_tile(const float* __restrict__ in, const flo
   };
 
   const int taps = R * S;
-  for (int c0 = 0; c0 < C; c0 += CK) {
+  for (int c0 = cbeg; c0 < cend; c0 += CK) {
     __syncthreads();  // every wavefront is done with the previous patch and filter stages
     stage_patch(c0);
     load_filter(0, 0, c0);
@@ -189,8 +192,9 @@ __device__ __forceinline__ void mcc_tile(const float* __restrict__ in, const flo
 template <int TP, int TQ, int BN, int CK, int WM, int WN>
 __global__ __launch_bounds__((MccCfg<TP, TQ, BN, CK, WM, WN>::NT),
                              (MccCfg<TP, TQ, BN, CK, WM, WN>::MI * MccCfg<TP, TQ, BN, CK, WM, WN>::NI <= 4 ? 3 : 1)) void mcc_kernel(
-    const float* __restrict__ in, const float* __restrict__ filt, float* __restrict__ out, int H,
-    int W, int C, int K, int R, int S, int sh, int sw, int P, int Q, int tp_n, int tq_n, int tk_n) {
+    const float* __restrict__ in, const float* __restrict__ filt, float* __restrict__ out,
+    float* __restrict__ ws, int H, int W, int C, int K, int R, int S, int sh, int sw, int P, int Q,
+    int tp_n, int tq_n, int tk_n, int n_img, int SC, int cchunk) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   // XCD-aware order: each of the 8 XCDs gets a contiguous run of tiles; inside a run the
   // channel tiles of one pixel patch come first (they share the patch), then q, p, n.
@@ -200,18 +204,23 @@ __global__ __launch_bounds__((MccCfg<TP, TQ, BN, CK, WM, WN>::NT),
   const int tk = b % tk_n;
   const int tq = (b / tk_n) % tq_n;
   const int tp = (b / (tk_n * tq_n)) % tp_n;
-  const int n = b / (tk_n * tq_n * tp_n);
+  const int n = (b / (tk_n * tq_n * tp_n)) % n_img;
+  const int sc = b / (tk_n * tq_n * tp_n * n_img);  // part of the reduction dimension c
   const int p0 = tp * TP, q0 = tq * TQ, k0 = tk * BN;
-  const bool full = (p0 + TP <= P) && (q0 + TQ <= Q) && (k0 + BN <= K) && (C % CK == 0);
+  const int cbeg = sc * cchunk, cend = min(C, cbeg + cchunk);
+  float* dst = SC > 1 ? ws + (int64_t)sc * n_img * P * Q * K : out;
+  const bool full = (p0 + TP <= P) && (q0 + TQ <= Q) && (k0 + BN <= K) && ((cend - cbeg) % CK == 0);
   if (full)
-    mcc_tile<TP, TQ, BN, CK, WM, WN, false>(in, filt, out, H, W, C, K, R, S, sh, sw, P, Q, n, p0, q0, k0, lds);
+    mcc_tile<TP, TQ, BN, CK, WM, WN, false>(in, filt, dst, H, W, C, K, R, S, sh, sw, P, Q, n, p0, q0, k0, cbeg,
+                                            cend, lds);
   else
-    mcc_tile<TP, TQ, BN, CK, WM, WN, true>(in, filt, out, H, W, C, K, R, S, sh, sw, P, Q, n, p0, q0, k0, lds);
+    mcc_tile<TP, TQ, BN, CK, WM, WN, true>(in, filt, dst, H, W, C, K, R, S, sh, sw, P, Q, n, p0, q0, k0, cbeg,
+                                           cend, lds);
 }
 
 template <int TP, int TQ, int BN, int CK, int WM, int WN>
-mdh_status launch_t(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
-                    int64_t sh, int64_t sw, const float* in, const float* filt, float* out,
+mdh_status launch_t(int SC, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                    int64_t sh, int64_t sw, const float* in, const float* filt, float* out, void* ws,
                     hipStream_t st) {
   using Cf = MccCfg<TP, TQ, BN, CK, WM, WN>;
   const int64_t P = (H - R) / sh + 1, Q = (W - S) / sw + 1;
@@ -222,23 +231,28 @@ mdh_status launch_t(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64
   static int64_t lds_allowed[kMaxDevices] = {};
   if (allow_dynamic_lds((const void*)kern, lds_bytes, lds_allowed) != MDH_OK) return MDH_ERR_LAUNCH;
   const int64_t tp_n = cdiv(P, TP), tq_n = cdiv(Q, TQ), tk_n = cdiv(K, BN);
-  const int64_t nblocks = N * tp_n * tq_n * tk_n;
+  if (SC < 1) return MDH_ERR_UNSUPPORTED;
+  const int64_t cchunk = cdiv(cdiv(C, SC), CK) * CK;
+  if ((SC - 1) * cchunk >= C) return MDH_ERR_TILE_NOT_DIVIDING;  // a part without channels
+  const int64_t nblocks = N * tp_n * tq_n * tk_n * SC;
   if (nblocks > 0x7fffffff) return MDH_ERR_SIZE;
   clear_stale_error();
   hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cf::NT), (size_t)lds_bytes, st, in, filt, out,
-                     (int)H, (int)W, (int)C, (int)K, (int)R, (int)S, (int)sh, (int)sw, (int)P, (int)Q,
-                     (int)tp_n, (int)tq_n, (int)tk_n);
-  return launch_status();
+                     (float*)ws, (int)H, (int)W, (int)C, (int)K, (int)R, (int)S, (int)sh, (int)sw, (int)P,
+                     (int)Q, (int)tp_n, (int)tq_n, (int)tk_n, (int)N, SC, (int)cchunk);
+  mdh_status r = launch_status();
+  if (r != MDH_OK || SC <= 1) return r;
+  return launch_combine_sum((const float*)ws, out, N * P * Q * K, SC, st);
 }
 
 }  // namespace
 
 mdh_status launch_mcc(const MccPlan& pl, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
                       int64_t R, int64_t S, int64_t sh, int64_t sw, const float* in,
-                      const float* filt, float* out, hipStream_t st) {
+                      const float* filt, float* out, void* ws, hipStream_t st) {
 #define MDH_MCC(tp, tq, bn, ck, wm, wn)                                                          \
   if (pl.TP == tp && pl.TQ == tq && pl.BN == bn && pl.CK == ck && pl.WM == wm && pl.WN == wn)    \
-    return launch_t<tp, tq, bn, ck, wm, wn>(N, H, W, C, K, R, S, sh, sw, in, filt, out, st);
+    return launch_t<tp, tq, bn, ck, wm, wn>(pl.S, N, H, W, C, K, R, S, sh, sw, in, filt, out, ws, st);
   MDH_MCC(4, 32, 128, 16, 64, 64)
   MDH_MCC(8, 32, 128, 16, 128, 64)
   MDH_MCC(2, 32, 64, 16, 32, 32)

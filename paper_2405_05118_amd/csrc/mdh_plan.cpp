@@ -378,7 +378,8 @@ void params_from_plan(const int64_t* s, const MccPlan& pl, mdh_tile_params* p) {
     p->blk[1] = rb;
     p->blk[2] = pl.TQ;
     p->blk[4] = 2;
-    p->prt[MDH_L_HBM][4] = (int32_t)cdiv(s[4], pl.CK);
+    p->prt[MDH_L_WG][4] = pl.S;  // parts of the reduction dimension c over workgroups
+    p->prt[MDH_L_HBM][4] = (int32_t)cdiv(cdiv(s[4], pl.S), pl.CK);
     p->prt[MDH_L_LDS][4] = pl.CK / 2;
     // wavefront grid: TP/(mi*rb) along p, BN/WN along k; mi blocks along p per wavefront
     p->prt[MDH_L_WAVE][1] = pl.TP / (mi * rb);
@@ -396,7 +397,7 @@ void params_from_plan(const int64_t* s, const MccPlan& pl, mdh_tile_params* p) {
 
 static int mcc_ragged(const int64_t* s, const MccPlan& pl) {
   if (pl.flat) return (s[1] % pl.TP) || (s[2] % ((int64_t)pl.TQ * pl.QT)) || (s[3] % pl.BN);
-  return (s[1] % pl.TP) || (s[2] % pl.TQ) || (s[3] % pl.BN) || (s[4] % pl.CK);
+  return (s[1] % pl.TP) || (s[2] % pl.TQ) || (s[3] % pl.BN) || (s[4] % ((int64_t)pl.S * pl.CK));
 }
 
 // Column tiles per workgroup of the few-channel kernel: at most `want`, fewer while the grid would
@@ -454,14 +455,16 @@ static MccPlan mcc_default(const int64_t* s) {
   // 16 x 14 x 14 x 256 -> 256, 3 x 3: 122 against 137 us.
   const int64_t P = s[1] > 0 ? s[1] : 1, Q = s[2] > 0 ? s[2] : 1;
   // (on a tie the widest that still gives two workgroups per compute unit at 64 channels per
-  // workgroup, else the narrowest: 16 x 14 x 14 x 256 -> 256: 122 us with 4 x 8, 143 us with 2 x 16)
+  // workgroup and with c split as far as it goes, else the narrowest)
   int tq = 32, tp = 4;
   int64_t area = -1;
   bool enough = false;
   for (int t : {32, 16, 8}) {
     const int rows = t == 32 ? 4 : 8;
     const int64_t a = cdiv(P, rows) * rows * cdiv(Q, t) * t;
-    const bool many = (s[0] > 0 ? s[0] : 1) * cdiv(P, rows) * cdiv(Q, t) * cdiv(s[3] > 0 ? s[3] : 1, 64) >= 512;
+    int smax = 1;  // parts the reduction dimension c can be split into (at least one chunk each)
+    while (smax < 8 && s[4] / (2 * smax) >= 16) smax *= 2;
+    const bool many = (s[0] > 0 ? s[0] : 1) * cdiv(P, rows) * cdiv(Q, t) * cdiv(s[3] > 0 ? s[3] : 1, 64) * smax >= 512;
     if (area < 0 || a < area || (a == area && !enough)) area = a, tq = t, tp = rows, enough = many;
   }
   const int wm = tq == 8 ? 32 : 64;  // two blocks along p per wavefront, one for the 4 x 8 block
@@ -474,6 +477,14 @@ static MccPlan mcc_default(const int64_t* s) {
     return (s[0] > 0 ? s[0] : 1) * cdiv(P, m.TP) * cdiv(Q, m.TQ) * cdiv(s[3] > 0 ? s[3] : 1, m.BN);
   };
   if (wgs(pl) < 512 && pl.BN == 128) pl = MccPlan{tp, tq, 64, 16, wm, 32, 0, 0};
+  // still few workgroups: parts of the reduction dimension c over workgroups (partial outputs in the
+  // workspace + second pass) up to ~450 workgroups, every part keeping at least one channel chunk.
+  // 16 x 7 x 7 x 512 -> 512, 3 x 3: 85 us with 4 or 8 parts, 137 us with 2, 267 us unsplit (MIOpen
+  // 118 us); 16 x 14 x 14 x 256 -> 256: 68 us with 4 parts, 80 with 2, 143 unsplit; 16 x 28 x 28 x 128
+  // -> 128: 69 us with 2 parts, 73 with 4, 75 unsplit; 1 x 28 x 28 x 128: 15 us with 8 parts, 41 with 2.
+  while (wgs(pl) * pl.S < 448 && pl.S < 8 && s[4] / (2 * pl.S) >= pl.CK) pl.S *= 2;
+  // parts are whole channel chunks: no part may end up without channels (e.g. 200 channels in 8 parts)
+  while (pl.S > 1 && (int64_t)(pl.S - 1) * cdiv(cdiv(s[4], pl.S), pl.CK) * pl.CK >= s[4]) pl.S /= 2;
   pl.ragged = mcc_ragged(s, pl);
   return pl;
 }
@@ -486,12 +497,22 @@ int mcc_candidates(const int64_t* s, MccPlan* out, int cap) {
     pl.ragged = mcc_ragged(s, pl);
     for (int i = 0; i < n; ++i)
       if (out[i].flat == pl.flat && out[i].TP == pl.TP && out[i].TQ == pl.TQ && out[i].BN == pl.BN &&
-          out[i].WM == pl.WM && out[i].WN == pl.WN && out[i].QT == pl.QT)
+          out[i].WM == pl.WM && out[i].WN == pl.WN && out[i].QT == pl.QT && out[i].S == pl.S)
         return;
     out[n++] = pl;
   };
   push(mcc_default(s));
   for (auto& m : kMccMenu) push(MccPlan{m.TP, m.TQ, m.BN, m.CK, m.WM, m.WN, 0, 0});
+  // the reduction dimension c over workgroups, where the concatenation dimensions leave the chip empty
+  for (int S : {2, 4, 8})
+    for (auto& m : kMccMenu) {
+      MccPlan pl{m.TP, m.TQ, m.BN, m.CK, m.WM, m.WN, 0, 0};
+      pl.S = S;
+      const int64_t wg = (s[0] > 0 ? s[0] : 1) * cdiv(s[1] > 0 ? s[1] : 1, m.TP) * cdiv(s[2] > 0 ? s[2] : 1, m.TQ) *
+                         cdiv(s[3] > 0 ? s[3] : 1, m.BN);
+      if (wg * (S / 2) >= 1024 || (int64_t)(S - 1) * cdiv(cdiv(s[4], S), m.CK) * m.CK >= s[4]) continue;
+      push(pl);
+    }
   if (s[4] <= 16)
     for (int want : {1, 2, 4, 8, 16})
       for (auto& m : kMccFlatMenu) {
@@ -534,6 +555,10 @@ mdh_status plan_mcc(const int64_t* s, const mdh_tile_params* p, MccPlan* out) {
     pl.WM = p->prt[MDH_L_VGPR][1] * 32;
     pl.TP = p->prt[MDH_L_WAVE][1] * p->prt[MDH_L_VGPR][1] * (32 / pl.TQ);
     pl.CK = p->prt[MDH_L_LDS][4] * 2;
+    pl.S = p->prt[MDH_L_WG][4];
+    // a workgroup part of c that owns no channel would leave its partial output unset
+    if (pl.S > 1 && pl.CK > 0 && (int64_t)(pl.S - 1) * cdiv(cdiv(s[4], pl.S), pl.CK) * pl.CK >= s[4])
+      return MDH_ERR_TILE_NOT_DIVIDING;
   }
   pl.ragged = ragged;
   if (mcc_lds_bytes(pl, s) > kLdsBytesPerWG) return MDH_ERR_TILE_RESOURCES;
@@ -817,6 +842,11 @@ size_t mdh_workspace_size(mdh_instance inst, const int64_t* sizes, const mdh_til
       GemmPlan pl;
       if (plan_matmul(sizes, params, &pl) != MDH_OK || pl.S <= 1) return 0;
       return (size_t)pl.S * (size_t)sizes[0] * (size_t)sizes[1] * sizeof(float);
+    }
+    case MDH_MCC: {
+      MccPlan pl;
+      if (plan_mcc(sizes, params, &pl) != MDH_OK || pl.flat || pl.S <= 1) return 0;
+      return (size_t)pl.S * (size_t)(sizes[0] * sizes[1] * sizes[2] * sizes[3]) * sizeof(float);
     }
     case MDH_CUSTOM_REDUCE: {
       PrlPlan pl;

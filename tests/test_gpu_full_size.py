@@ -104,7 +104,8 @@ def test_mcc_full_size_sampled():
     P = (cfg.H - cfg.R) // cfg.stride[0] + 1
     Q = (cfg.W - cfg.S) // cfg.stride[1] + 1
     out = torch.full((cfg.N, P, Q, cfg.K), float("nan"), dtype=torch.float32, device="cuda")
-    mdh.mdh_mcc(dev(x), dev(f), out, cfg.stride)
+    sizes = (cfg.N, P, Q, cfg.K, cfg.C, cfg.R, cfg.S, cfg.stride[0], cfg.stride[1])
+    mdh.mdh_mcc(dev(x), dev(f), out, cfg.stride, None, ws_for(mdh.MDH_MCC, sizes))
     torch.cuda.synchronize()
     got = out.cpu().numpy()
     del out

@@ -154,7 +154,7 @@ def run_mcc(x, f, stride, p):
     K, R, S, _ = f.shape
     P, Q = (H - R) // stride[0] + 1, (Wd - S) // stride[1] + 1
     out = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
-    mdh.mdh_mcc(dev(x), dev(f), out, stride, p)
+    mdh.mdh_mcc(dev(x), dev(f), out, stride, p, workspace(mdh.MDH_MCC, (N, P, Q, K, C, R, S, stride[0], stride[1]), p))
     torch.cuda.synchronize()
     return out.cpu().numpy().astype(np.float64)
 
@@ -168,6 +168,7 @@ MCC_SMALL = [
     (3, 1, 1, 40, 7, 1, 1, (1, 1)),       # reduces to a matmul
     (2, 16, 16, 24, 40, 3, 3, (1, 1)),    # 14 x 14 outputs: blocks of 2 x 16 and 4 x 8 pixels pay off
     (3, 15, 15, 16, 130, 3, 3, (2, 2)),   # 7 x 7 outputs, strided, ragged channels
+    (2, 9, 9, 200, 70, 3, 3, (1, 1)),     # many input channels, few pixels: c split over workgroups
 ]
 
 

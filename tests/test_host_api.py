@@ -233,3 +233,24 @@ def test_size_errors_of_the_later_entry_points():
     d.acc_buf[0] = 3  # no such input buffer
     assert L.mdh_custom_default_params(ctypes.byref(d), ctypes.byref(mdh.TileParams())) == E_SIZE
     assert mdh.mdh_custom_workspace_size(mdh.CustomOp(None, "")) == 0
+
+
+def test_mcc_defaults_and_candidates_validate_for_any_channel_count():
+    # the reduction dimension c is split over workgroups in whole channel chunks: whatever the channel
+    # count, no part of the default or of a candidate may be left without channels
+    for C in list(range(9, 600, 13)) + [16, 32, 64, 128, 200, 256, 512, 1000, 2048]:
+        for (N, P, Q, K) in ((2, 7, 7, 70), (1, 28, 28, 128), (16, 14, 14, 256), (3, 5, 9, 33)):
+            sizes = (N, P, Q, K, C, 3, 3, 1, 1)
+            p = mdh.mdh_default_params(mdh.MDH_MCC, sizes)
+            assert mdh.mdh_validate_params(mdh.MDH_MCC, sizes, p) == 0, sizes
+            S = p.prt[3][4]
+            assert (mdh.mdh_workspace_size(mdh.MDH_MCC, sizes, p) == (S * N * P * Q * K * 4 if S > 1 else 0)), sizes
+            for i in range(mdh.mdh_num_candidates(mdh.MDH_MCC, sizes)):
+                assert mdh.mdh_validate_params(mdh.MDH_MCC, sizes, mdh.mdh_candidate(mdh.MDH_MCC, sizes, i)) == 0, (sizes, i)
+    # a split that would leave a part empty is rejected: 200 channels in 8 parts of whole 16-channel chunks
+    sizes = (2, 7, 7, 70, 200, 3, 3, 1, 1)
+    p = mdh.mdh_default_params(mdh.MDH_MCC, sizes)
+    assert p.prt[3][4] == 4
+    q = p.copy()
+    q.prt[3][4], q.prt[0][4] = 8, 2
+    assert mdh.mdh_validate_params(mdh.MDH_MCC, sizes, q) == 3

@@ -57,7 +57,9 @@ def run(x, f, stride, p):
     K, R, S, _ = f.shape
     P, Q = (H - R) // stride[0] + 1, (Wd - S) // stride[1] + 1
     out = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
-    mdh.mdh_mcc(dev(x), dev(f), out, stride, p)
+    n = mdh.mdh_workspace_size(mdh.MDH_MCC, (N, P, Q, K, x.shape[3], R, S, stride[0], stride[1]), p)
+    ws = torch.empty(max(n, 4) // 4, dtype=torch.int32, device="cuda") if n else None
+    mdh.mdh_mcc(dev(x), dev(f), out, stride, p, ws)
     torch.cuda.synchronize()
     return out.cpu().numpy().astype(np.float64)
 
