@@ -41,7 +41,7 @@ struct GemmCfg {
 #endif
 };
 
-template <int BM, int BN, int BK, int WM, int WN, bool GUARD>
+template <int BM, int BN, int BK, int WM, int WN, int MODE>
 __device__ __forceinline__ void gemm_tile(const float* __restrict__ A, const float* __restrict__ B,
                                           float* __restrict__ Cout, int M, int N, int K, int m0,
                                           int n0, int kbeg, int kend, float* lds) {
@@ -56,7 +56,12 @@ __device__ __forceinline__ void gemm_tile(const float* __restrict__ A, const flo
     f4 a[C::A_LD], b[C::B_LD];
   };
 
+  // MODE 0: interior tile, the reduction extent a multiple of BK -- no checks at all;
+  // MODE 1: interior tile, ragged reduction extent -- only the last k-tile is checked (a
+  //         workgroup-uniform test per k-tile);  MODE 2: the tile touches the edge of M or N.
+  constexpr bool GUARD = MODE == 2;
   auto load_global = [&](Staged& g, int k0) {
+    const bool fast = MODE == 0 || (MODE == 1 && k0 + BK <= kend);
 #pragma unroll
     for (int x = 0; x < C::A_LD; ++x) {
       const int f = tid + x * C::NT;
@@ -64,12 +69,17 @@ __device__ __forceinline__ void gemm_tile(const float* __restrict__ A, const flo
       f4 v = {0.f, 0.f, 0.f, 0.f};
       if (C::A_F4 % C::NT == 0 || f < C::A_F4) {
         const float* p = A + (int64_t)(m0 + row) * K + (k0 + c4 * 4);
-        if (!GUARD) {
+        if (fast) {
           v = *(const f4u*)p;
         } else if (m0 + row < M) {
+          // edge tiles and ragged k: still one 16-byte load wherever all four elements exist
+          if (k0 + c4 * 4 + 3 < kend) {
+            v = *(const f4u*)p;
+          } else {
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (k0 + c4 * 4 + e < kend) v[e] = p[e];
+            for (int e = 0; e < 4; ++e)
+              if (k0 + c4 * 4 + e < kend) v[e] = p[e];
+          }
         }
       }
       g.a[x] = v;
@@ -81,12 +91,16 @@ __device__ __forceinline__ void gemm_tile(const float* __restrict__ A, const flo
       f4 v = {0.f, 0.f, 0.f, 0.f};
       if (C::B_F4 % C::NT == 0 || f < C::B_F4) {
         const float* p = B + (int64_t)(k0 + row) * N + (n0 + c4 * 4);
-        if (!GUARD) {
+        if (fast) {
           v = *(const f4u*)p;
         } else if (k0 + row < kend) {
+          if (n0 + c4 * 4 + 3 < N) {
+            v = *(const f4u*)p;
+          } else {
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (n0 + c4 * 4 + e < N) v[e] = p[e];
+            for (int e = 0; e < 4; ++e)
+              if (n0 + c4 * 4 + e < N) v[e] = p[e];
+          }
         }
       }
       g.b[x] = v;
@@ -254,11 +268,13 @@ __global__ __launch_bounds__((GemmCfg<BM, BN, BK, WM, WN>::NT)) void matmul_kern
   const int kbeg = s * kchunk;
   const int kend = min(K, kbeg + kchunk);
   float* out = S > 1 ? ws + (int64_t)s * M * N : C;
-  const bool full = (m0 + BM <= M) && (n0 + BN <= N) && kend > kbeg && ((kend - kbeg) % BK == 0);
-  if (full)
-    gemm_tile<BM, BN, BK, WM, WN, false>(A, B, out, M, N, K, m0, n0, kbeg, kend, lds);
+  const bool full = (m0 + BM <= M) && (n0 + BN <= N) && kend > kbeg;
+  if (full && (kend - kbeg) % BK == 0)
+    gemm_tile<BM, BN, BK, WM, WN, 0>(A, B, out, M, N, K, m0, n0, kbeg, kend, lds);
+  else if (full)
+    gemm_tile<BM, BN, BK, WM, WN, 1>(A, B, out, M, N, K, m0, n0, kbeg, kend, lds);
   else
-    gemm_tile<BM, BN, BK, WM, WN, true>(A, B, out, M, N, K, m0, n0, kbeg, kend, lds);
+    gemm_tile<BM, BN, BK, WM, WN, 2>(A, B, out, M, N, K, m0, n0, kbeg, kend, lds);
 }
 
 // Second pass of the re-composition: C = part_0 + part_1 + ... + part_{S-1}, in that order.

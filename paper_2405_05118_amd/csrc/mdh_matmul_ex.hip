@@ -36,10 +36,14 @@ struct Operand {
   f4 r[LD];
 
   // f0: first free index of the tile, flim: extent of the free dimension; k0/klim likewise
-  template <bool GUARD>
+  // MODE 0: interior tile, the reduction extent a multiple of BK -- no checks at all;
+  // MODE 1: interior tile, ragged reduction extent -- only the last k-tile is checked (a
+  //         workgroup-uniform test per k-tile);  MODE 2: the tile touches an edge of C.
+  template <int MODE>
   __device__ __forceinline__ void load(const float* __restrict__ base, int64_t ld, int f0, int flim,
                                        int k0, int klim) {
     const int tid = threadIdx.x;
+    const bool fast = MODE == 0 || (MODE == 1 && k0 + BK <= klim);
 #pragma unroll
     for (int x = 0; x < LD; ++x) {
       const int f = tid + x * NT;
@@ -49,12 +53,17 @@ struct Operand {
         const int grow = (KC ? f0 : k0) + row, gcol = (KC ? k0 : f0) + c4 * 4;
         const int rlim = KC ? flim : klim, clim = KC ? klim : flim;
         const float* p = base + (int64_t)grow * ld + gcol;
-        if (!GUARD) {
+        if (fast) {
           v = *(const f4u*)p;
         } else if (grow < rlim) {
+          // edge tiles and ragged k: still one 16-byte load wherever all four elements exist
+          if (gcol + 3 < clim) {
+            v = *(const f4u*)p;
+          } else {
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (gcol + e < clim) v[e] = p[e];
+            for (int e = 0; e < 4; ++e)
+              if (gcol + e < clim) v[e] = p[e];
+          }
         }
       }
       r[x] = v;
@@ -86,10 +95,11 @@ struct Operand {
   }
 };
 
-template <int BM, int BN, int BK, int WM, int WN, bool TA, bool TB, bool TC, bool GUARD>
+template <int BM, int BN, int BK, int WM, int WN, bool TA, bool TB, bool TC, int MODE>
 __device__ __forceinline__ void gemm_ex_tile(const float* __restrict__ A, const float* __restrict__ B,
                                              float* __restrict__ Cout, int M, int N, int K, int m0,
                                              int n0, int kbeg, int kend, float* lds) {
+  constexpr bool GUARD = MODE == 2;
   constexpr int WAVES_N = BN / WN, NT = (BM / WM) * WAVES_N * 64;
   constexpr int MI = WM / 32, NI = WN / 32;
   using OpA = Operand<BM, BK, !TA, NT>;
@@ -167,8 +177,8 @@ __device__ __forceinline__ void gemm_ex_tile(const float* __restrict__ A, const 
     OpB b;
   };
   auto load_global = [&](Staged& g, int k0) {
-    g.a.template load<GUARD>(A, lda, m0, M, k0, kend);
-    g.b.template load<GUARD>(B, ldb, n0, N, k0, kend);
+    g.a.template load<MODE>(A, lda, m0, M, k0, kend);
+    g.b.template load<MODE>(B, ldb, n0, N, k0, kend);
   };
   auto store_lds = [&](const Staged& g, float* st) {
     g.a.store(st);
@@ -253,11 +263,13 @@ __global__ __launch_bounds__(((BM / WM) * (BN / WN) * 64)) void matmul_ex_kernel
   const float* Ab = A + (int64_t)batch * M * K;
   const float* Bb = B + (int64_t)batch * K * N;
   float* out = S > 1 ? ws + ((int64_t)s * nbatch + batch) * mn : C + (int64_t)batch * mn;
-  const bool full = (m0 + BM <= M) && (n0 + BN <= N) && kend > kbeg && ((kend - kbeg) % BK == 0);
-  if (full)
-    gemm_ex_tile<BM, BN, BK, WM, WN, TA, TB, TC, false>(Ab, Bb, out, M, N, K, m0, n0, kbeg, kend, lds);
+  const bool full = (m0 + BM <= M) && (n0 + BN <= N) && kend > kbeg;
+  if (full && (kend - kbeg) % BK == 0)
+    gemm_ex_tile<BM, BN, BK, WM, WN, TA, TB, TC, 0>(Ab, Bb, out, M, N, K, m0, n0, kbeg, kend, lds);
+  else if (full)
+    gemm_ex_tile<BM, BN, BK, WM, WN, TA, TB, TC, 1>(Ab, Bb, out, M, N, K, m0, n0, kbeg, kend, lds);
   else
-    gemm_ex_tile<BM, BN, BK, WM, WN, TA, TB, TC, true>(Ab, Bb, out, M, N, K, m0, n0, kbeg, kend, lds);
+    gemm_ex_tile<BM, BN, BK, WM, WN, TA, TB, TC, 2>(Ab, Bb, out, M, N, K, m0, n0, kbeg, kend, lds);
 }
 
 template <int BM, int BN, int BK, int WM, int WN, bool TA, bool TB, bool TC>

@@ -42,7 +42,7 @@ struct MccCfg {
   static constexpr int F_LD = (F_F4 + NT - 1) / NT;
 };
 
-template <int TP, int TQ, int BN, int CK, int WM, int WN, bool GUARD>
+template <int TP, int TQ, int BN, int CK, int WM, int WN, int MODE>
 __device__ __forceinline__ void mcc_tile(const float* __restrict__ in, const float* __restrict__ filt,
                                          float* __restrict__ out, int H, int W, int C, int K, int R,
                                          int S, int sh, int sw, int P, int Q, int n, int p0, int q0,
@@ -66,7 +66,12 @@ __device__ __forceinline__ void mcc_tile(const float* __restrict__ in, const flo
       for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
   f4 gf[Cf::F_LD];
+  // MODE 0: interior tile, whole channel chunks -- no checks at all;  MODE 1: interior tile, the
+  // last channel chunk incomplete -- only that chunk is checked (a workgroup-uniform test per
+  // chunk);  MODE 2: the tile touches the edge of p, q or k.
+  constexpr bool GUARD = MODE == 2;
   auto load_filter = [&](int r, int s, int c0) {
+    const bool fast = MODE == 0 || (MODE == 1 && c0 + CK <= cend);
 #pragma unroll
     for (int x = 0; x < Cf::F_LD; ++x) {
       const int f = tid + x * Cf::NT;
@@ -74,12 +79,17 @@ __device__ __forceinline__ void mcc_tile(const float* __restrict__ in, const flo
       f4 v = {0.f, 0.f, 0.f, 0.f};
       if (Cf::F_F4 % Cf::NT == 0 || f < Cf::F_F4) {
         const float* p = filt + (((int64_t)(k0 + kk) * R + r) * S + s) * C + c0 + c4 * 4;
-        if (!GUARD) {
+        if (fast) {
           v = *(const f4u*)p;
         } else if (k0 + kk < K) {
+          // edge tiles and ragged channel counts: one 16-byte load wherever all four channels exist
+          if (c0 + c4 * 4 + 3 < cend) {
+            v = *(const f4u*)p;
+          } else {
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (c0 + c4 * 4 + e < cend) v[e] = p[e];
+            for (int e = 0; e < 4; ++e)
+              if (c0 + c4 * 4 + e < cend) v[e] = p[e];
+          }
         }
       }
       gf[x] = v;
@@ -94,6 +104,7 @@ __device__ __forceinline__ void mcc_tile(const float* __restrict__ in, const flo
     }
   };
   auto stage_patch = [&](int c0) {
+    const bool fast = MODE == 0 || (MODE == 1 && c0 + CK <= cend);
     const int total = npix * (CK / 4);
     for (int f = tid; f < total; f += Cf::NT) {
       const int pix = f / (CK / 4), c4 = f % (CK / 4);
@@ -101,12 +112,16 @@ __device__ __forceinline__ void mcc_tile(const float* __restrict__ in, const flo
       const int hy = p0 * sh + ph, wx = q0 * sw + pw;
       f4 v = {0.f, 0.f, 0.f, 0.f};
       const float* p = in + (((int64_t)n * H + hy) * W + wx) * C + c0 + c4 * 4;
-      if (!GUARD) {
+      if (fast) {
         v = *(const f4u*)p;
       } else if (hy < H && wx < W) {
+        if (c0 + c4 * 4 + 3 < cend) {
+          v = *(const f4u*)p;
+        } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          if (c0 + c4 * 4 + e < cend) v[e] = p[e];
+          for (int e = 0; e < 4; ++e)
+            if (c0 + c4 * 4 + e < cend) v[e] = p[e];
+        }
       }
       *(f4*)(ps + pix * Cf::PC + c4 * 4) = v;
     }
@@ -209,13 +224,13 @@ __global__ __launch_bounds__((MccCfg<TP, TQ, BN, CK, WM, WN>::NT),
   const int p0 = tp * TP, q0 = tq * TQ, k0 = tk * BN;
   const int cbeg = sc * cchunk, cend = min(C, cbeg + cchunk);
   float* dst = SC > 1 ? ws + (int64_t)sc * n_img * P * Q * K : out;
-  const bool full = (p0 + TP <= P) && (q0 + TQ <= Q) && (k0 + BN <= K) && ((cend - cbeg) % CK == 0);
-  if (full)
-    mcc_tile<TP, TQ, BN, CK, WM, WN, false>(in, filt, dst, H, W, C, K, R, S, sh, sw, P, Q, n, p0, q0, k0, cbeg,
-                                            cend, lds);
+  const bool full = (p0 + TP <= P) && (q0 + TQ <= Q) && (k0 + BN <= K);
+  if (full && (cend - cbeg) % CK == 0)
+    mcc_tile<TP, TQ, BN, CK, WM, WN, 0>(in, filt, dst, H, W, C, K, R, S, sh, sw, P, Q, n, p0, q0, k0, cbeg, cend, lds);
+  else if (full)
+    mcc_tile<TP, TQ, BN, CK, WM, WN, 1>(in, filt, dst, H, W, C, K, R, S, sh, sw, P, Q, n, p0, q0, k0, cbeg, cend, lds);
   else
-    mcc_tile<TP, TQ, BN, CK, WM, WN, true>(in, filt, dst, H, W, C, K, R, S, sh, sw, P, Q, n, p0, q0, k0, cbeg,
-                                           cend, lds);
+    mcc_tile<TP, TQ, BN, CK, WM, WN, 2>(in, filt, dst, H, W, C, K, R, S, sh, sw, P, Q, n, p0, q0, k0, cbeg, cend, lds);
 }
 
 template <int TP, int TQ, int BN, int CK, int WM, int WN>
