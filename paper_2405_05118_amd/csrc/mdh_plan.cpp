@@ -240,6 +240,13 @@ static GemmPlan gemm_default(const int64_t* s) {
   } else if (cdiv(M, 128) * cdiv(N, 128) < 512) {
     pl = GemmPlan{128, 64, 32, 64, 32, 1, 0};
     if (cdiv(M, 128) * cdiv(N, 64) < 512) pl = GemmPlan{64, 64, 32, 32, 32, 1, 0};
+  } else {
+    // wave quantisation: 512 tiles of 128 x 128 run at once; when the last round would be mostly
+    // empty the 64 x 64 tile (about 0.8 of the rate, but four times the tiles) is faster.  Measured:
+    // 3000^3 (576 tiles) 0.66 -> 0.52 ms; 4100 x 4096 x 4096 (1056 tiles) 1.32 -> 1.18 ms.
+    const double rounds = (double)(cdiv(M, 128) * cdiv(N, 128)) / 512.0;
+    const double whole = (double)cdiv(cdiv(M, 128) * cdiv(N, 128), 512);
+    if (whole > 1.3 * rounds) pl = GemmPlan{64, 64, 32, 32, 32, 1, 0};
   }
   // Split the reduction dimension over workgroups only while there is less than one workgroup per
   // compute unit (two for the narrow shapes, whose tiles are small) AND every part keeps at least 8
