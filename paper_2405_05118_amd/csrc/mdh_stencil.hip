@@ -8,7 +8,8 @@
 //   workgroup layer : (nx/SI) x (ny/TJ) x (nz/KT) parts, TJ = TY*RJ, KT = 4*LK
 //   HBM layer       : SI consecutive planes of dimension i, streamed sequentially
 //   wavefront layer : TY lane-rows along j  x  LK/64 wavefronts along k
-//   lane layer      : 64 lanes along k (k is the contiguous dimension -> coalescing)
+//   lane layer      : 64 lanes along k (k is the contiguous dimension -> coalescing); for narrow
+//                     grids LK = 32 or 16 lanes along k and 2 or 4 lane-rows of j per wavefront
 //   VGPR layer      : RJ rows (j) x 4 columns (k) per lane
 // Input staging (parameter D3): the plane being processed lives in LDS so that the j- and
 // k-neighbours owned by other lanes are read from LDS instead of HBM/L2; the i-neighbours
@@ -246,6 +247,8 @@ mdh_status launch_stencil(const StencilPlan& pl, int64_t nx, int64_t ny, int64_t
   MDH_ST(4, 4, 64)
   MDH_ST(2, 4, 64)
   MDH_ST(4, 2, 64)
+  MDH_ST(4, 8, 32)   // narrow grids (nz <= 128): a wavefront spans 2 lane-rows of 32 lanes
+  MDH_ST(4, 16, 16)  // nz <= 64: 4 lane-rows of 16 lanes
 #undef MDH_ST
   return MDH_ERR_UNSUPPORTED;
 }

@@ -123,6 +123,20 @@ def test_stencil_small_all_candidates(shape):
         assert rel_err(got, ref) <= TOL_STENCIL, (shape, p and p.table())
 
 
+@pytest.mark.parametrize("shape", [(33, 200, 40), (70, 130, 100), (20, 64, 128), (9, 70, 64)])
+def test_stencil_narrow_grids_every_candidate(shape):
+    # nz <= 128: the default tiles have 32 or 16 lanes along k and several lane-rows per wavefront
+    cfg = W.StencilCfg(*shape, 0.5, float(np.float32(1.0 / 12.0)), W.SEED_BASE + 22)
+    x = W.stencil_inputs(cfg)
+    ref = oracle.jacobi3d(x, cfg.c0, cfg.c1)
+    d = mdh.mdh_default_params(mdh.MDH_STENCIL, shape)
+    assert d.prt[B.L_LANE][2] == (16 if shape[2] <= 64 else 32) and d.prt[B.L_LANE][1] * d.prt[B.L_LANE][2] == 64
+    for p in candidates(mdh.MDH_STENCIL, shape):
+        got = run_stencil(x, cfg.c0, cfg.c1, p)
+        assert np.all(np.isfinite(got)), "output not fully overwritten"
+        assert rel_err(got, ref) <= TOL_STENCIL, (shape, p and p.table())
+
+
 def test_stencil_closed_forms_and_halo_untouched():
     nx, ny, nz = 20, 24, 36
     c0, c1 = 0.5, float(np.float32(1.0 / 12.0))
