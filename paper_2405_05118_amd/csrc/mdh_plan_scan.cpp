@@ -81,8 +81,8 @@ static ScanPlan scan_wave_plan(const int64_t* s) {
 }
 
 static ScanPlan scan_default(const int64_t* s) {
-  // many short rows: a wavefront per row (no LDS, no barriers)
-  if (s[1] <= 2048 && s[0] >= 4096) return scan_wave_plan(s);
+  // many short rows: a wavefront per row (no LDS, no barriers); measured best up to 768 elements
+  if (s[1] <= 768 && s[0] >= 4096) return scan_wave_plan(s);
   // enough rows: one workgroup per row walks the whole row (one pass over the data); few rows:
   // chunks of j over workgroups until ~2048 workgroups, chunk totals scanned by a second kernel
   const int64_t rows = s[0] > 0 ? s[0] : 1;
@@ -95,7 +95,9 @@ static ScanPlan scan_default(const int64_t* s) {
     // beyond 4096 elements with 16 wavefronts, which keeps the tiles per lane few)
     const ScanPlan res = s[1] <= 4096 ? scan_onepass_plan(s, 8, 8) : scan_onepass_plan(s, 16, 8);
     if (res.C == 1 && res.onepass) return res;
-    return scan_plan(s, 8, 1);
+    // rows of one or two tiles of 1024: four wavefronts (65536 x 1000: 84 us against 128 us with
+    // eight wavefronts and half of them idle; 65536 x 1536: 126 against 146 us)
+    return scan_plan(s, s[1] <= 1536 ? 4 : 8, 1);
   }
   // few long rows: chunks of j over workgroups, a chunk resident in registers (one pass over the
   // input); as many tiles per chunk as still give a workgroup per compute unit
