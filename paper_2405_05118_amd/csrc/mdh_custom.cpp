@@ -250,7 +250,7 @@ CustomPlan default_plan(const mdh_custom_desc* d) {
     int64_t cc = 1;
     for (int i = 0; i < probe.D; ++i)
       if (!probe.red[i] && i != probe.scan) cc *= probe.N[i];
-    if (probe.scan < 0 && probe.red[probe.fast] && cc >= 2048 && probe.N[probe.fast] >= 1024) nt = 64;
+    if (probe.scan < 0 && probe.red[probe.fast] && cc >= 2048 && probe.N[probe.fast] >= 64) nt = 64;
     bool any_red = false;
     for (int i = 0; i < probe.D; ++i) any_red = any_red || probe.red[i] || i == probe.scan;
     // nothing but concatenation: four consecutive indices of the fast dimension per lane, so that
@@ -285,9 +285,19 @@ CustomPlan default_plan(const mdh_custom_desc* d) {
       if (pl.red[i]) steps *= pl.Q[i];
     // split up to ~2048 workgroups, and further while a lane would walk more than ~1024 steps
     // (custom reduce 2^16 x 2^18: 10.0 ms with 1024 steps per lane, 13.9 ms with 32768)
+    // ... as long as the second pass stays small beside the first: a part keeps at least 32 points of
+    // the reduced dimensions, and at least 256 when there are few output points, because the second
+    // pass folds the parts of a point sequentially in one lane and few points mean few lanes
+    // (custom reduce 2^10 x 2^14: 83 us with 64 parts, 236 us with 512; MatMul 512^3 is fastest
+    // with 16 parts of 32)
+    int64_t points = 1;
+    for (int i = 0; i < pl.D; ++i)
+      if (pl.red[i]) points *= pl.N[i];
+    const int64_t per_part = pl.CCN < 4096 && pl.CCN >= 256 ? 256 : 32;
+    const int64_t cap = points / per_part > 1 ? points / per_part : 1;
     int64_t split = 1;
-    while (grid * split < 2048 && grid < 1024) split *= 2;
-    while (steps / split > 1024 && grid * split < 32768) split *= 2;
+    while (grid * split < 2048 && grid < 1024 && split * 2 <= cap) split *= 2;
+    while (steps / split > 1024 && grid * split < 32768 && split * 2 <= cap) split *= 2;
     if (split > 1) pl = make_plan(d, nt, split, vreg);
     if (pl.SG * pl.CG >= 512) break;
   }
