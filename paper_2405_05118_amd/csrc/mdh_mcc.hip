@@ -276,6 +276,12 @@ mdh_status launch_mcc(const MccPlan& pl, int64_t N, int64_t H, int64_t W, int64_
   MDH_MCC(8, 16, 64, 16, 64, 32)
   MDH_MCC(8, 8, 128, 16, 32, 64)   // blocks of 4 x 8 pixels
   MDH_MCC(8, 8, 64, 16, 32, 32)
+  MDH_MCC(4, 32, 128, 32, 64, 64)  // channel chunks of 32
+  MDH_MCC(4, 32, 64, 32, 64, 32)
+  MDH_MCC(8, 16, 128, 32, 64, 64)
+  MDH_MCC(8, 16, 64, 32, 64, 32)
+  MDH_MCC(8, 8, 128, 32, 32, 64)
+  MDH_MCC(8, 8, 64, 32, 32, 32)
 #undef MDH_MCC
   return MDH_ERR_UNSUPPORTED;
 }

@@ -343,6 +343,12 @@ static const MccInst kMccMenu[] = {  // channel-chunked kernel
     {8, 16, 64, 16, 64, 32},
     {8, 8, 128, 16, 32, 64},   // blocks of 4 x 8 pixels
     {8, 8, 64, 16, 32, 32},
+    {4, 32, 128, 32, 64, 64},  // channel chunks of 32: twice the MFMAs between two barriers
+    {4, 32, 64, 32, 64, 32},
+    {8, 16, 128, 32, 64, 64},
+    {8, 16, 64, 32, 64, 32},
+    {8, 8, 128, 32, 32, 64},
+    {8, 8, 64, 32, 32, 32},
 };
 // few-channel kernel (s and c fused): TP rows x TQ = QB columns of pixels, BN channels, WM, WN
 static const MccInst kMccFlatMenu[] = {
@@ -502,6 +508,14 @@ static MccPlan mcc_default(const int64_t* s) {
   // 118 us); 16 x 14 x 14 x 256 -> 256: 68 us with 4 parts, 80 with 2, 143 unsplit; 16 x 28 x 28 x 128
   // -> 128: 69 us with 2 parts, 73 with 4, 75 unsplit; 1 x 28 x 28 x 128: 15 us with 8 parts, 41 with 2.
   while (wgs(pl) * pl.S < 448 && pl.S < 8 && s[4] / (2 * pl.S) >= pl.CK) pl.S *= 2;
+  // many channels per part: chunks of 32 channels, twice the MFMAs between two barriers (16 x 14 x 14
+  // x 256 -> 256: 55.5 against 58.8 us; 16 x 7 x 7 x 2048 -> 512, 1 x 1: 37.5 against 44.3 us; with 32
+  // channels in all, or 7 x 7 taps on 64, chunks of 16 are as fast or faster)
+  if (s[4] / pl.S >= 128 || (s[4] / pl.S >= 64 && s[5] * s[6] <= 9)) {
+    MccPlan w = pl;
+    w.CK = 32;
+    if (mcc_lds_bytes(w, s) <= kLdsBytesPerWG) pl = w;
+  }
   // parts are whole channel chunks: no part may end up without channels (e.g. 200 channels in 8 parts)
   while (pl.S > 1 && (int64_t)(pl.S - 1) * cdiv(cdiv(s[4], pl.S), pl.CK) * pl.CK >= s[4]) pl.S /= 2;
   pl.ragged = mcc_ragged(s, pl);
@@ -515,7 +529,7 @@ int mcc_candidates(const int64_t* s, MccPlan* out, int cap) {
     if (mcc_lds_bytes(pl, s) > kLdsBytesPerWG) return;
     pl.ragged = mcc_ragged(s, pl);
     for (int i = 0; i < n; ++i)
-      if (out[i].flat == pl.flat && out[i].TP == pl.TP && out[i].TQ == pl.TQ && out[i].BN == pl.BN &&
+      if (out[i].flat == pl.flat && out[i].TP == pl.TP && out[i].TQ == pl.TQ && out[i].BN == pl.BN && out[i].CK == pl.CK &&
           out[i].WM == pl.WM && out[i].WN == pl.WN && out[i].QT == pl.QT && out[i].S == pl.S)
         return;
     out[n++] = pl;
