@@ -194,7 +194,10 @@ size_t mdh_workspace_size(mdh_instance inst, const int64_t* sizes, const mdh_til
  *   M == 0 or N == 0 is a valid empty call.
  *   FP32 MFMA arithmetic, fp32 accumulation; if prt[MDH_L_WG][k] = S > 1 the
  *   S partial results go to `workspace` (S*M*N floats) and a second kernel adds
- *   them in ascending part order.
+ *   them in ascending part order.  The library default splits k for small
+ *   outputs, so pass the workspace mdh_workspace_size asks for.  This entry point
+ *   always runs the LDS-tiled kernel; for M <= 16 mdh_matmul_ex (batch 1) has a
+ *   kernel that streams B once without LDS and is several times faster.
  */
 mdh_status mdh_matmul(int64_t M, int64_t N, int64_t K, const float* A, const float* B, float* C,
                       const mdh_tile_params* params, void* workspace, size_t workspace_bytes,
