@@ -18,6 +18,11 @@
 // large-tile kernel does it (lane group g owns k in {4g..4g+3} of a step): + combines them.
 // Re-composition: registers (MFMA accumulators) -> LDS across the WAVES_K wavefronts of a
 // workgroup -> workspace + second kernel across the S workgroup parts.
+//
+// Transposed view of B (B stored [N][K], the layout of a weight matrix applied as x * W^T): k is
+// contiguous for both operands.  A block's 16 columns are then 16 consecutive columns, a lane
+// loads 4 consecutive k of its column (16 bytes) for four steps of 16 k at once, so that a row of B
+// is read in runs of 256 bytes, and the output view writes 64-byte runs.
 #include "mdh_internal.h"
 
 namespace mdh {
@@ -28,7 +33,7 @@ typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));  // dword-ali
 
 constexpr int SK_PF = 2;  // 16-row steps requested together by a wavefront
 
-template <int WAVES_N, int WAVES_K>
+template <int WAVES_N, int WAVES_K, bool TB>
 __global__ __launch_bounds__((WAVES_N * WAVES_K * 64)) void matmul_skinny_kernel(
     const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C,
     float* __restrict__ ws, int M, int N, int K, int tiles_m, int tiles_n, int S, int kchunk,
@@ -60,6 +65,48 @@ __global__ __launch_bounds__((WAVES_N * WAVES_K * 64)) void matmul_skinny_kernel
   f4 acc[4];
 #pragma unroll
   for (int c = 0; c < 4; ++c) acc[c] = (f4){0.f, 0.f, 0.f, 0.f};
+
+  if (TB) {
+    // B[b, j, k]: block c of the strip = columns n0 + 16c + l16; lane group g owns k = 4g..4g+3 of
+    // every 16
+    const float* bt = Bb + (int64_t)(n0 + l16) * K + 4 * g;
+    auto mma_t = [&](const f4& a, const f4 (&b)[4]) {
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[tt], b[c][tt], acc[c], 0, 0, 0);
+    };
+    int k = kbeg + wk * 64;
+    if (cols_full) {
+      for (; k + 64 <= kend; k += 64 * WAVES_K) {
+        f4 a[4], b[4][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          a[j] = arow_ok ? *(const f4u*)(ap + k + 16 * j) : (f4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            b[j][c] = __builtin_nontemporal_load((const f4u*)(bt + (int64_t)(16 * c) * K + k + 16 * j));
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) mma_t(a[j], b[j]);
+      }
+    }
+    // the wavefront's remaining chunks (ragged columns, the ragged end of k): every element predicated
+    for (; k < kend; k += 64 * WAVES_K)
+      for (int kk = k; kk < kend && kk < k + 64; kk += 16) {
+        f4 a, b[4];
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+          const bool kin = kk + 4 * g + tt < kend;
+          a[tt] = (arow_ok && kin) ? ap[kk + tt] : 0.f;
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            b[c][tt] = (kin && n0 + 16 * c + l16 < N) ? bt[(int64_t)(16 * c) * K + kk + tt] : 0.f;
+        }
+        mma_t(a, b);
+      }
+  } else {
 
   auto mma = [&](const f4& a, const f4 (&b)[4]) {
 #pragma unroll
@@ -100,6 +147,7 @@ __global__ __launch_bounds__((WAVES_N * WAVES_K * 64)) void matmul_skinny_kernel
     }
     mma(a, b);
   }
+  }  // plain view of B
 
   // wavefront -> workgroup: the wavefronts that split k add their blocks in LDS, in a fixed order
   if (WAVES_K > 1) {
@@ -115,13 +163,18 @@ __global__ __launch_bounds__((WAVES_N * WAVES_K * 64)) void matmul_skinny_kernel
       for (int c = 0; c < 4; ++c) acc[c] += part[(((w - 1) * WAVES_N + wn) * 4 + c) * 64 + lane];
   }
 
-  // output view: register r of block c is C[m0 + 4g + r][col + c]
+  // output view: register r of block c is C[m0 + 4g + r][col + c]; with the transposed view of B,
+  // C[m0 + 4g + r][n0 + 16c + l16]
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int row = m0 + 4 * g + r;
     if (row >= M) continue;
     float* p = out + (int64_t)row * N + col;
-    if (cols_full) {
+    if (TB) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (n0 + 16 * c + l16 < N) out[(int64_t)row * N + n0 + 16 * c + l16] = acc[c][r];
+    } else if (cols_full) {
       *(f4u*)p = (f4){acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
     } else {
 #pragma unroll
@@ -131,16 +184,17 @@ __global__ __launch_bounds__((WAVES_N * WAVES_K * 64)) void matmul_skinny_kernel
   }
 }
 
-template <int WAVES_N, int WAVES_K>
+template <int WAVES_N, int WAVES_K, bool TB>
 mdh_status launch_t(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, int64_t K,
                     const float* A, const float* B, float* C, void* ws, hipStream_t st) {
   const int S = pl.g.S;
   const int64_t tm = cdiv(M, 16), tn = cdiv(N, 64 * WAVES_N);
-  const int64_t kchunk = cdiv(cdiv(K, S), 16) * 16;
+  const int64_t kstep = TB ? 64 : 16;  // k a wavefront takes per step
+  const int64_t kchunk = cdiv(cdiv(K, S), kstep) * kstep;
   const int64_t nblocks = tm * tn * S;
   if (nblocks > 0x7fffffff || batch > 65535) return MDH_ERR_SIZE;
   clear_stale_error();
-  hipLaunchKernelGGL((matmul_skinny_kernel<WAVES_N, WAVES_K>), dim3((unsigned)nblocks, (unsigned)batch),
+  hipLaunchKernelGGL((matmul_skinny_kernel<WAVES_N, WAVES_K, TB>), dim3((unsigned)nblocks, (unsigned)batch),
                      dim3(WAVES_N * WAVES_K * 64), 0, st, A, B, C, (float*)ws, (int)M, (int)N, (int)K,
                      (int)tm, (int)tn, S, (int)kchunk, (int)batch);
   mdh_status r = launch_status();
@@ -152,9 +206,11 @@ mdh_status launch_t(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, i
 
 mdh_status launch_matmul_skinny(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, int64_t K,
                                 const float* A, const float* B, float* C, void* ws, hipStream_t st) {
-  if (pl.ta || pl.tb || pl.tc) return MDH_ERR_UNSUPPORTED;
-#define MDH_SK(wn, wk) \
-  if (pl.g.BN == 64 * wn && pl.WK == wk) return launch_t<wn, wk>(pl, batch, M, N, K, A, B, C, ws, st);
+  if (pl.ta || pl.tc) return MDH_ERR_UNSUPPORTED;
+#define MDH_SK(wn, wk)                                                                                   \
+  if (pl.g.BN == 64 * wn && pl.WK == wk)                                                                 \
+    return pl.tb ? launch_t<wn, wk, true>(pl, batch, M, N, K, A, B, C, ws, st)                           \
+                 : launch_t<wn, wk, false>(pl, batch, M, N, K, A, B, C, ws, st);
   MDH_SK(1, 4)
   MDH_SK(1, 8)
   MDH_SK(2, 2)

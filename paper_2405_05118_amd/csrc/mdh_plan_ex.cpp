@@ -37,16 +37,17 @@ static void skinny_params(const int64_t* s, const GemmExPlan& pl, mdh_tile_param
   p->blk[1] = 16;
   p->blk[2] = 16;
   p->blk[3] = 4;
-  const int64_t kchunk = cdiv(cdiv(s[3], g.S), 16) * 16;
+  const int64_t kstep = pl.tb ? 64 : 16;  // k a wavefront takes per step (four 16-steps at once when B is transposed)
+  const int64_t kchunk = cdiv(cdiv(s[3], g.S), kstep) * kstep;
   p->prt[MDH_L_WG][0] = (int32_t)s[0];
   p->prt[MDH_L_WG][1] = (int32_t)cdiv(s[1], 16);
   p->prt[MDH_L_WG][2] = (int32_t)cdiv(s[2], g.BN);
   p->prt[MDH_L_WG][3] = g.S;
-  p->prt[MDH_L_HBM][3] = (int32_t)cdiv(kchunk, 16 * pl.WK);
+  p->prt[MDH_L_HBM][3] = (int32_t)cdiv(kchunk, kstep * pl.WK);
   p->prt[MDH_L_WAVE][2] = g.BN / 64;
   p->prt[MDH_L_WAVE][3] = pl.WK;
   p->prt[MDH_L_VGPR][2] = 4;
-  p->prt[MDH_L_VGPR][3] = 4;
+  p->prt[MDH_L_VGPR][3] = (int32_t)(kstep / 4);
   static const int dims[4] = {0, 1, 2, 3};
   set_order(p, dims);
   p->strided = 1;  // the wavefronts along k interleave their 16-row parts
@@ -54,21 +55,24 @@ static void skinny_params(const int64_t* s, const GemmExPlan& pl, mdh_tile_param
   p->in_region[0] = MDH_MR_VGPR;
   p->in_region[1] = MDH_MR_VGPR;
   p->out_region = MDH_MR_VGPR;
+  p->in_transposed[1] = (uint8_t)pl.tb;
   p->ragged = (uint8_t)g.ragged;
 }
 
 static int skinny_ragged(const int64_t* s, const GemmExPlan& pl) {
-  const int64_t kchunk = cdiv(cdiv(s[3], pl.g.S), 16) * 16;
-  return (s[1] % 16) || (s[2] % pl.g.BN) || (s[3] != (int64_t)pl.g.S * cdiv(kchunk, 16 * pl.WK) * pl.WK * 16);
+  const int64_t kstep = pl.tb ? 64 : 16;
+  const int64_t kchunk = cdiv(cdiv(s[3], pl.g.S), kstep) * kstep;
+  return (s[1] % 16) || (s[2] % pl.g.BN) || (s[3] != (int64_t)pl.g.S * cdiv(kchunk, kstep * pl.WK) * pl.WK * kstep);
 }
 
 static GemmExPlan skinny_plan(const int64_t* s, int wn, int wk, int S) {
-  GemmExPlan pl{GemmPlan{16, 64 * wn, 16, 16, 64, S, 0}, 0, 0, 0, 1, wk};
+  GemmExPlan pl{GemmPlan{16, 64 * wn, 16, 16, 64, S, 0}, 0, (int)s[5], 0, 1, wk};
   pl.g.ragged = skinny_ragged(s, pl);
   return pl;
 }
 
-static bool skinny_applies(const int64_t* s) { return s[1] <= 16 && !s[4] && !s[5] && !s[6]; }
+// plain views, or B transposed (B stored [N][K])
+static bool skinny_applies(const int64_t* s) { return s[1] <= 16 && !s[4] && !s[6]; }
 
 // sizes: batch, M, N, K, trans_a, trans_b, trans_c
 void params_from_plan(const int64_t* s, const GemmExPlan& pl, mdh_tile_params* p) {
@@ -206,7 +210,7 @@ mdh_status plan_matmul_ex(const int64_t* s, const mdh_tile_params* p, GemmExPlan
   if ((st = check_lanes(p)) != MDH_OK) return st;
   if (p->blk[1] == 16) {  // the small-M kernel
     const int wn = p->prt[MDH_L_WAVE][2], wk = p->prt[MDH_L_WAVE][3];
-    if (!skinny_inst(wn, wk) || s[4] || s[5] || s[6]) return MDH_ERR_UNSUPPORTED;
+    if (!skinny_inst(wn, wk) || s[4] || s[6]) return MDH_ERR_UNSUPPORTED;
     GemmExPlan pl = skinny_plan(s, wn, wk, p->prt[MDH_L_WG][3]);
     mdh_tile_params chk;
     params_from_plan(s, pl, &chk);

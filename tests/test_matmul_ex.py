@@ -79,8 +79,14 @@ def test_small_m_default_streams_operands_to_registers():
         assert list(p.blk[:4]) == [1, 16, 16, 4]
         assert p.in_region[0] == 2 and p.in_region[1] == 2
         assert p.prt[B.L_WAVE][3] > 1
-    # transposed views or more rows: the LDS-tiled kernel
-    for sizes in ((1, 16, 1000, 2048, 0, 1, 0), (1, 17, 1000, 2048, 0, 0, 0)):
+    # B transposed (a weight matrix stored [N][K]): the same kernel, a lane then takes 4 consecutive k of
+    # its column for four steps of 16 at once (16 register-layer parts of k instead of 4)
+    p = mdh.mdh_default_params(mdh.MDH_BMATMUL, (1, 16, 1000, 2048, 0, 1, 0))
+    assert list(p.blk[:4]) == [1, 16, 16, 4] and p.in_transposed[1] == 1 and p.prt[B.L_VGPR][3] == 16
+    assert mdh.mdh_validate_params(mdh.MDH_BMATMUL, (1, 16, 1000, 2048, 0, 1, 0), p) == 0
+    assert mdh.mdh_validate_params(mdh.MDH_BMATMUL, (1, 16, 1000, 2048, 0, 0, 0), p) == 6
+    # A or C transposed, or more rows: the LDS-tiled kernel
+    for sizes in ((1, 16, 1000, 2048, 1, 0, 0), (1, 16, 1000, 2048, 0, 0, 1), (1, 17, 1000, 2048, 0, 0, 0)):
         p = mdh.mdh_default_params(mdh.MDH_BMATMUL, sizes)
         assert list(p.blk[:4]) == [1, 32, 32, 2]
 
