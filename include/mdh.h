@@ -351,6 +351,10 @@ mdh_status mdh_matvec(int64_t M, int64_t K, const float* A, const float* x, floa
  * For mdh_default_params etc. the `sizes` of MDH_BMATMUL are
  * (batch, M, N, K, trans_a, trans_b, trans_c); a configuration's in_transposed[0..1]
  * and out_transposed must equal the call's flags.
+ * Two kernels: blk = (1,32,32,2), LDS-tiled, any views; blk = (1,16,16,4) for M <= 16
+ * with A and C plain (B plain or transposed), which streams both operands from
+ * device memory straight into MFMA operand registers and parallelises k over
+ * wavefronts and workgroups (the library default for those shapes).
  */
 mdh_status mdh_matmul_ex(int64_t batch, int64_t M, int64_t N, int64_t K, const float* A,
                          int32_t trans_a, const float* B, int32_t trans_b, float* C,
