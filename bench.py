@@ -37,24 +37,24 @@ PRL_LANE_OPS_PER_PAIR = 24.0
 # None until measured for that workload
 TRAFFIC_BYTES = {
     # profiles/all_kernels_hbm_traffic_pmc.md (all kernels of a step)
-    "jacobi3d_512": 1112687463,
-    "dot_2p28": 2147340074,
-    "matvec_16384": 1074464374,
-    "matmul_4096": 604532004,
-    "matmul_ts": 1099077265,
-    "mcc_resnet": 961048711,
-    "prl_2p16_2p18": 154121854,
-    "matmul_256": 1945483,
-    "mcc_resnet50_first": 62491614,
-    "matmul_resnet50_fc": 13576624,
-    "matmul_vgg16_fc": 426312361,
-    "bmatmul_16x1024": 201477767,
-    "matmul_t_4096": 604050473,
-    "mcc_capsule_resnet50_first": 1072647222,
-    "scan_2p28": 2151825723,
-    "scan_rows_65536x4096": 2147503702,
-    "histo_generic_256x2p24": 204127128,
-    "prl_generic_2p16_2p18": 271647116,
+    "jacobi3d_512": 1113284630,
+    "dot_2p28": 2147382564,
+    "matvec_16384": 1074485506,
+    "matmul_4096": 604298687,
+    "matmul_ts": 1099104252,
+    "mcc_resnet": 960276490,
+    "prl_2p16_2p18": 154085758,
+    "matmul_256": 1945520,
+    "mcc_resnet50_first": 62487876,
+    "matmul_resnet50_fc": 13576907,
+    "matmul_vgg16_fc": 426320825,
+    "bmatmul_16x1024": 201480501,
+    "matmul_t_4096": 604059746,
+    "mcc_capsule_resnet50_first": 1072652097,
+    "scan_2p28": 2151970803,
+    "scan_rows_65536x4096": 2147515826,
+    "histo_generic_256x2p24": 204059256,
+    "prl_generic_2p16_2p18": 271648869,
 }
 
 
