@@ -96,3 +96,23 @@ def test_scan_defaults_on_rows_of_about_a_thousand(shape):
     torch.cuda.synchronize()
     ref, refabs = oracle.scan_rows(X, with_abs=True)
     assert float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - ref) / np.where(refabs > 0, refabs, 1.0))) <= 1e-5
+
+
+def test_mcc_tune_with_and_without_workspace():
+    # with a workspace the search may pick a configuration that splits the channel dimension over
+    # workgroups; without one those candidates are skipped and the result needs no workspace
+    cfg = W.MccCfg(4, 9, 9, 256, 128, 3, 3, (1, 1), W.SEED_BASE + 99)
+    x, f = W.mcc_inputs(cfg)
+    sizes = (4, 7, 7, 128, 256, 3, 3, 1, 1)
+    out = torch.full((4, 7, 7, 128), float("nan"), dtype=torch.float32, device="cuda")
+    ref, refabs = oracle.mcc(x, f, (1, 1), with_abs=True)
+    big = torch.empty(8 * out.numel(), dtype=torch.float32, device="cuda")
+    for ws in (big, None):
+        best, ms = mdh.mdh_tune(mdh.MDH_MCC, sizes, [dev(x), dev(f), out], workspace=ws, reps=2)
+        assert ms > 0 and mdh.mdh_validate_params(mdh.MDH_MCC, sizes, best) == 0
+        need = mdh.mdh_workspace_size(mdh.MDH_MCC, sizes, best)
+        assert need <= (big.numel() * 4 if ws is not None else 0)
+        out.fill_(float("nan"))
+        mdh.mdh_mcc(dev(x), dev(f), out, (1, 1), best, ws)
+        torch.cuda.synchronize()
+        assert float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - ref) / refabs)) <= TOL
