@@ -26,40 +26,47 @@ METRIC = "per-instance GFLOP/s or GB/s and % of roofline on 1 MI355X"
 # MI355X published peaks
 PEAK_HBM_GBS = 8000.0
 PEAK_FP32_MFMA_TFLOPS = 157.3
-# plain 32-bit integer vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
-PEAK_INT_VALU_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# Vector ALU: 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz = 78.6 T lane-op/s.  This is the width behind the
+# published FP32 vector peak (157.3 TFLOP/s = 78.6 T fused multiply-adds a second), and no instruction
+# kind issues faster: moves, 32-bit add / subtract, bitwise logic and fp32 add / multiply / FMA on
+# vector-register operands measure 2.2-2.4 cycles per wavefront instruction, the other kinds (compare,
+# select, min / max, three-operand and 24-bit multiply-add forms, anything with a scalar-register or
+# inline-constant operand) 4.0-4.2 cycles, i.e. 16 lanes a cycle = 39.3 T lane-op/s.  A kernel bound
+# by VALU issue is priced against the full width; the 16-lane figure and the measured rate of a
+# register-resident loop of the kernel's own instruction mix are reported beside it.
+PEAK_VALU_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
+PEAK_VALU_16LANE_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
-# lane-ops the emitted instruction mix spends per (a,b) pair at nF = 8: 8 compares,
-# 8 selects, 4.5 three-operand adds, compare + max + select for max_idx, 0.5 index move
-PRL_LANE_OPS_PER_PAIR = 24.0
+# Counter readings that bench.py quotes come from ONE tracked file, written by
+# paper_2405_05118_amd/profile_summary.py from the same rocprofv3 --pmc runs as profiles/*.md:
+#   traffic_bytes[workload]        HBM bytes per step (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy)
+#   valu_insts_per_pair[workload]  SQ_INSTS_VALU x 64 / pairs of the custom-reduce kernels
+with open(os.path.join(ROOT, "paper_2405_05118_amd", "measured_counters.json")) as _fh:
+    MEASURED = json.load(_fh)
+TRAFFIC_BYTES = MEASURED["traffic_bytes"]
+VALU_PER_PAIR = MEASURED["valu_insts_per_pair"]
 
-# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/);
-# None until measured for that workload
-TRAFFIC_BYTES = {
-    # profiles/all_kernels_hbm_traffic_pmc.md (all kernels of a step)
-    "jacobi3d_512": 1113284630,
-    "dot_2p28": 2147382564,
-    "matvec_16384": 1074485506,
-    "matmul_4096": 604298687,
-    "matmul_ts": 1099104252,
-    "mcc_resnet": 960276490,
-    "prl_2p16_2p18": 154085758,
-    "matmul_256": 1945520,
-    "mcc_resnet50_first": 62487876,
-    "matmul_resnet50_fc": 13576907,
-    "matmul_vgg16_fc": 426320825,
-    "bmatmul_16x1024": 201480501,
-    "matmul_t_4096": 604059746,
-    "mcc_capsule_resnet50_first": 1072652097,
-    "scan_2p28": 2151970803,
-    "scan_rows_65536x4096": 2147515826,
-    "histo_generic_256x2p24": 204059256,
-    "prl_generic_2p16_2p18": 271648869,
-}
+# Inputs of a step stay in the 256 MB last-level cache from one step to the next when the working set is
+# smaller than that: such rows say so ("cache_resident"), and an HBM-bound row among them rotates through
+# enough copies of its streamed operand that every step really reads it from HBM.
+LLC_BYTES = 256 * 1024 * 1024
 
 
 LAST_SPREAD = {}
 MIN_WARM_MS = 0.0
+
+
+# Student t, two-sided 99 %, by degrees of freedom (the next lower listed value is used)
+_T99 = {9: 3.250, 14: 2.977, 19: 2.861, 24: 2.797, 29: 2.756, 39: 2.708, 49: 2.680, 59: 2.660, 79: 2.640, 99: 2.626}
+ADAPTIVE = False       # per-instance table: keep timing until the 99 % confidence interval is within 5 %
+CI_TARGET = 0.05
+MAX_GROUPS = 100
+MAX_TIMED_S = 4.0
+GROUP_MS = 2.0
+
+
+def _t99(dof):
+    return _T99[max(k for k in _T99 if k <= dof)] if dof >= 9 else 3.250
 
 
 def _events_ms(torch, fn, steps, warmup):
@@ -67,7 +74,10 @@ def _events_ms(torch, fn, steps, warmup):
     HIP events on the launch stream give the device time, the host clock the whole-job time.
     Events recorded every steps/10 launches inside the same timed region give the spread of the
     per-step time (half-width of the 99 % confidence interval of the mean, relative), kept in
-    LAST_SPREAD for the caller."""
+    LAST_SPREAD for the caller.  With ADAPTIVE set (the per-instance table, not the headline, which
+    times exactly `steps`), further groups of steps/10 launches are timed until that half-width is
+    within 5 % of the mean (the paper's protocol, Section "Experimental Setup"), up to MAX_GROUPS
+    groups or MAX_TIMED_S seconds; every group counts in the reported time."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
@@ -81,28 +91,55 @@ def _events_ms(torch, fn, steps, warmup):
         torch.cuda.synchronize()
     groups = 10 if steps >= 20 else 1
     per = steps // groups
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(groups + 1)]
-    t0 = time.perf_counter()
-    marks[0].record()
-    done = 0
-    for g in range(groups):
-        n = per if g < groups - 1 else steps - done
-        for _ in range(n):
+    if ADAPTIVE:
+        # group length from a pilot of five launches: about GROUP_MS of device time per group, so that a
+        # group of 10 us kernels is not two launches long
+        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        p0.record()
+        for _ in range(5):
             fn()
-        done += n
-        marks[g + 1].record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
+        p1.record()
+        torch.cuda.synchronize()
+        groups = 10
+        per = int(max(2, min(200, GROUP_MS / max(p0.elapsed_time(p1) / 5, 1e-4))))
+        steps = groups * per
+    seg = []  # (start event, end event, launches) of every timed group
+
+    def batch(sizes):
+        """Time len(sizes) groups back to back; returns the host seconds around them."""
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(sizes) + 1)]
+        t0 = time.perf_counter()
+        ev[0].record()
+        for g, n in enumerate(sizes):
+            for _ in range(n):
+                fn()
+            ev[g + 1].record()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        seg.extend((ev[g], ev[g + 1], n) for g, n in enumerate(sizes))
+        return dt
+
+    wall_s = batch([per] * (groups - 1) + [steps - per * (groups - 1)])
+
+    def spread():
+        t = [a.elapsed_time(b) / n for a, b, n in seg]
+        mean = sum(t) / len(t)
+        var = sum((x - mean) ** 2 for x in t) / (len(t) - 1)
+        return {"groups": len(t), "ci99_rel": _t99(len(t) - 1) * (var / len(t)) ** 0.5 / mean,
+                "min_ms": min(t), "max_ms": max(t)}
+
     LAST_SPREAD.clear()
     if groups > 1:
-        sizes = [per] * (groups - 1) + [steps - per * (groups - 1)]
-        t = [marks[g].elapsed_time(marks[g + 1]) / sizes[g] for g in range(groups)]
-        mean = sum(t) / groups
-        var = sum((x - mean) ** 2 for x in t) / (groups - 1)
-        # Student t, 9 degrees of freedom, 99 % two-sided: 3.25
-        LAST_SPREAD.update({"groups": groups, "ci99_rel": 3.25 * (var / groups) ** 0.5 / mean,
-                            "min_ms": min(t), "max_ms": max(t)})
-    return marks[0].elapsed_time(marks[groups]) / steps, wall_ms / steps
+        sp = spread()
+        while ADAPTIVE and sp["ci99_rel"] > CI_TARGET and len(seg) < MAX_GROUPS and wall_s < MAX_TIMED_S:
+            wall_s += batch([per] * 10)  # ten more groups, timed like the first ten; all of them count
+            sp = spread()
+        sp["steps_timed"] = sum(n for _, _, n in seg)
+        sp["ci99_within_5pct"] = bool(sp["ci99_rel"] <= CI_TARGET)
+        LAST_SPREAD.update(sp)
+    total = sum(n for _, _, n in seg)
+    dev_ms = sum(a.elapsed_time(b) for a, b, _ in seg)
+    return dev_ms / total, wall_s * 1e3 / total
 
 
 def _ws(torch, mdh, inst, sizes):
@@ -173,6 +210,7 @@ def bench_matmul(torch, mdh, W, name, steps, warmup, cpu, split=None):
                      "frac": tf / PEAK_FP32_MFMA_TFLOPS, "traffic": TRAFFIC_BYTES.get(name)},
         "algorithmic_flop": flop,
         "algorithmic_bytes": 4 * (cfg.M * cfg.K + cfg.K * cfg.N + cfg.M * cfg.N),
+        "cache_resident": 4 * (cfg.M * cfg.K + cfg.K * cfg.N + cfg.M * cfg.N) < LLC_BYTES,
     }
     if cpu:
         import oracle
@@ -205,6 +243,7 @@ def bench_mcc(torch, mdh, W, name, steps, warmup, cpu):
                      "frac": tf / PEAK_FP32_MFMA_TFLOPS, "traffic": TRAFFIC_BYTES.get(name)},
         "algorithmic_flop": flop,
         "algorithmic_bytes": 4 * (x.numel() + f.numel() + o.numel()),
+        "cache_resident": 4 * (x.numel() + f.numel() + o.numel()) < LLC_BYTES,
     }
     if cpu:
         import numpy as np
@@ -235,18 +274,21 @@ def bench_prl(torch, mdh, W, name, steps, warmup, cpu):
     s = torch.empty(cfg.nA, dtype=torch.int32, device="cuda")
     i = torch.empty(cfg.nA, dtype=torch.int32, device="cuda")
     ws = _ws(torch, mdh, mdh.MDH_CUSTOM_REDUCE, sizes)
+    before = valu_calibration(torch, mdh, kinds=("prl_mix",))
     ms, wall = _events_ms(torch, lambda: mdh.mdh_custom_reduce(A, B, wp, wm, s, i, None, ws), steps, warmup)
+    after = valu_calibration(torch, mdh, kinds=("prl_mix",))
     pairs = float(cfg.nA) * cfg.nB
-    tops = pairs * PRL_LANE_OPS_PER_PAIR / ms / 1e9
+    per_pair = VALU_PER_PAIR[name]  # SQ_INSTS_VALU of this kernel x 64 lanes / pairs
+    tops = pairs * per_pair / ms / 1e9
     nbytes = 4 * (A.numel() + B.numel() + 2 * cfg.nF + 2 * cfg.nA)
     res = {
         "value": pairs / wall / 1e6, "unit": "Gpairs/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "i32",
         "kernel": "prl_kernel + combine_maxidx_kernel",
-        "roofline": {"bound": "alu", "achieved": tops, "peak": PEAK_INT_VALU_TOPS, "unit": "Tlane-op/s",
-                     "frac": tops / PEAK_INT_VALU_TOPS, "traffic": TRAFFIC_BYTES.get(name)},
-        "lane_ops_per_pair": PRL_LANE_OPS_PER_PAIR,
+        "roofline": _alu_roofline(tops, before, after, TRAFFIC_BYTES.get(name)),
+        "lane_ops_per_pair": per_pair,
         "algorithmic_bytes": nbytes,
         "hbm_GBs_algorithmic": nbytes / ms / 1e6,
+        "cache_resident": True,
     }
     if cpu:
         import oracle
@@ -330,9 +372,19 @@ def bench_matmul_ex(torch, mdh, W, name, steps, warmup, cpu):
     c = torch.empty((1, cfg.M, cfg.N), dtype=torch.float32, device="cuda")
     p = mdh.mdh_default_params(mdh.MDH_BMATMUL, sizes)
     ws = _ws(torch, mdh, mdh.MDH_BMATMUL, sizes)
-    ms, wall = _events_ms(torch, lambda: mdh.mdh_matmul_ex(a, b, c, False, False, False, None, ws), steps, warmup)
     flop = 2.0 * cfg.M * cfg.N * cfg.K
     nbytes = 4 * (cfg.M * cfg.K + cfg.K * cfg.N + cfg.M * cfg.N)
+    # B is the operand that streams; when it would stay in the last-level cache from step to step, the
+    # steps rotate through enough identical copies of it (twice the cache in total) to read it from HBM
+    copies = 1 if 4 * b.numel() >= LLC_BYTES else -(-2 * LLC_BYTES // (4 * b.numel()))
+    bs = [b] + [b.clone() for _ in range(copies - 1)]
+    turn = [0]
+
+    def step():
+        turn[0] = (turn[0] + 1) % copies
+        mdh.mdh_matmul_ex(a, bs[turn[0]], c, False, False, False, None, ws)
+
+    ms, wall = _events_ms(torch, step, steps, warmup)
     gbs = nbytes / ms / 1e6
     # 2M/4 FLOP per byte of B: far below the ridge (19.7 FLOP/B), so B streaming from HBM is the bound
     res = {
@@ -342,6 +394,7 @@ def bench_matmul_ex(torch, mdh, W, name, steps, warmup, cpu):
                      "frac": gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES.get(name)},
         "algorithmic_flop": flop,
         "algorithmic_bytes": nbytes,
+        "rotating_copies_of_B": copies,
     }
     if cpu:
         import oracle
@@ -478,17 +531,19 @@ def bench_histo_generic(torch, mdh, W, name, steps, warmup, cpu):
     op = mdh.mdh_custom_create(desc)
     n = mdh.mdh_custom_workspace_size(op)
     ws = torch.empty(max(n, 4), dtype=torch.uint8, device="cuda") if n else None
+    before = valu_calibration(torch, mdh, kinds=("cmp_select",))
     ms, wall = _events_ms(torch, lambda: mdh.mdh_custom_run(op, [elems, bins], out, ws), steps, warmup)
+    after = valu_calibration(torch, mdh, kinds=("cmp_select",))
     pairs = float(nb) * ne
     # per (bin, element) pair at least a compare and a conditional add: 2 lane-ops
     tops = pairs * 2.0 / ms / 1e9
     res = {
         "value": pairs / wall / 1e6, "unit": "Gpairs/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "i32",
         "kernel": "mdh_custom_main + mdh_custom_combine (hipRTC)", "bins": nb, "elements": ne,
-        "roofline": {"bound": "alu", "achieved": tops, "peak": PEAK_INT_VALU_TOPS, "unit": "Tlane-op/s",
-                     "frac": tops / PEAK_INT_VALU_TOPS, "traffic": TRAFFIC_BYTES.get(name)},
+        "roofline": _alu_roofline(tops, before, after, TRAFFIC_BYTES.get(name), "cmp_select"),
         "lane_ops_per_pair": 2.0,
         "algorithmic_bytes": 4 * (ne + 2 * nb),
+        "cache_resident": True,
     }
     if cpu:
         import numpy as np
@@ -526,18 +581,77 @@ def bench_prl_generic(torch, mdh, W, name, steps, warmup, cpu):
     op = mdh.mdh_custom_create(desc)
     n = mdh.mdh_custom_workspace_size(op)
     ws = torch.empty(max(n, 4), dtype=torch.uint8, device="cuda") if n else None
+    before = valu_calibration(torch, mdh, kinds=("prl_mix",))
     ms, wall = _events_ms(torch, lambda: mdh.mdh_custom_run(op, [A, B, wp, wm], out, ws), steps, warmup)
+    after = valu_calibration(torch, mdh, kinds=("prl_mix",))
     pairs = float(cfg.nA) * cfg.nB
-    tops = pairs * PRL_LANE_OPS_PER_PAIR / ms / 1e9  # priced with the hand-written kernel's instruction count
+    per_pair = VALU_PER_PAIR[name]  # this kernel's own SQ_INSTS_VALU x 64 lanes / pairs
+    tops = pairs * per_pair / ms / 1e9
     res = {
         "value": pairs / wall / 1e6, "unit": "Gpairs/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "i32",
         "kernel": "mdh_custom_main + mdh_custom_combine (hipRTC)",
-        "roofline": {"bound": "alu", "achieved": tops, "peak": PEAK_INT_VALU_TOPS, "unit": "Tlane-op/s",
-                     "frac": tops / PEAK_INT_VALU_TOPS, "traffic": TRAFFIC_BYTES.get(name)},
-        "lane_ops_per_pair": PRL_LANE_OPS_PER_PAIR,
+        "roofline": _alu_roofline(tops, before, after, TRAFFIC_BYTES.get(name)),
+        "lane_ops_per_pair": per_pair,
+        "cache_resident": True,
     }
     mdh.mdh_custom_destroy(op)
     return res
+
+
+VALU_KINDS = {"xor_max": 0, "cmp_select": 1, "add3": 2, "prl_mix": 3, "fma_f32_vgpr": 4, "add_u32_vgpr": 5}
+_CAL_BUFS = {}
+
+
+def valu_calibration(torch, mdh, kinds=tuple(VALU_KINDS)):
+    """Issue rate (T lane-op/s) of the register-resident loop of each instruction kind, the shader clock
+    read inside the kernel, and from both the issue cost in shader-clock cycles per wavefront
+    instruction and SIMD.  Five launches each, HIP events on the launch stream."""
+    B = mdh.binding
+    if not _CAL_BUFS:
+        g = torch.Generator(device="cpu").manual_seed(7)
+        w = torch.cat([torch.randint(1, 1 << 16, (8,), generator=g), -torch.randint(0, 1 << 16, (8,), generator=g),
+                       torch.randint(0, 16, (256 * 2 * 8,), generator=g)]).to(torch.int32)
+        _CAL_BUFS.update(out=torch.empty(B.MDH_CALIB_BLOCKS * 256, dtype=torch.int32, device="cuda"),
+                         w=w.cuda(), clk=torch.zeros(2, dtype=torch.int64, device="cuda"),
+                         hz=mdh.mdh_calib_realtime_hz())
+    out, w, clk, hz = _CAL_BUFS["out"], _CAL_BUFS["w"], _CAL_BUFS["clk"], _CAL_BUFS["hz"]
+    res = {}
+    for k in kinds:
+        ops = [0]
+
+        def run():
+            ops[0] = mdh.mdh_calib_valu_kind(VALU_KINDS[k], out, 8192, w, clk)
+
+        run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 5
+        c = clk.cpu().tolist()
+        ghz = c[0] / c[1] * hz / 1e9 if c[1] > 0 and hz > 0 else None
+        rate = ops[0] / ms / 1e9
+        res[k] = {"Tlaneops": rate, "shader_clock_GHz": ghz,
+                  # wavefront instructions per second and SIMD = rate / 64 lanes / 1024 SIMDs
+                  "cycles_per_wave_inst": ghz * 1e9 / (rate * 1e12 / 64 / 1024) if ghz else None}
+    return res
+
+
+def _alu_roofline(tops, before, after, traffic, kind="prl_mix"):
+    """Roofline object of a VALU-issue-bound row: the peak is the full vector-ALU width (32 lanes a cycle
+    and SIMD at 2.4 GHz, the width of the published FP32 vector peak), which no instruction kind
+    exceeds; beside it the 16-lane figure that the compare / select / min / max kinds are held to, and
+    the measured rate of a register-resident loop of the same instruction kinds taken right before and
+    right after the timed region, with the shader clock read inside that loop."""
+    loop = max(before[kind]["Tlaneops"], after[kind]["Tlaneops"])
+    return {"bound": "alu", "achieved": tops, "peak": PEAK_VALU_TOPS, "unit": "Tlane-op/s", "frac": tops / PEAK_VALU_TOPS,
+            "traffic": traffic, "peak_16_lanes": PEAK_VALU_16LANE_TOPS, "frac_of_16_lanes": tops / PEAK_VALU_16LANE_TOPS,
+            "same_kinds_loop_Tlaneops": loop, "same_kinds_loop": kind,
+            "shader_clock_GHz": after[kind]["shader_clock_GHz"],
+            "cycles_per_wave_inst": (after[kind]["shader_clock_GHz"] or 2.4) * 1e9 / (tops * 1e12 / 64 / 1024)}
 
 
 def calibration(torch, mdh):
@@ -569,11 +683,28 @@ def calibration(torch, mdh):
 
     ms, _ = _events_ms(torch, va, 20, 3)
     res["int_valu_Tlaneops"] = ops[0] / ms / 1e9
+    res["int_valu_by_kind"] = valu_calibration(torch, mdh)
     res["peaks"] = {"hbm_GBs": PEAK_HBM_GBS, "fp32_mfma_TFLOPs": PEAK_FP32_MFMA_TFLOPS,
-                    "int_valu_Tlaneops": PEAK_INT_VALU_TOPS}
+                    "valu_Tlaneops": PEAK_VALU_TOPS, "valu_16_lanes_Tlaneops": PEAK_VALU_16LANE_TOPS}
     del src, dst, out, outi
     torch.cuda.empty_cache()
     return res
+
+
+# the benchmark's five configurations (config 3 is two shapes) and the split-k line of the tall-skinny one
+BASELINE_ROWS = ("matmul_256", "jacobi3d_512", "matmul_4096", "matmul_ts", "matmul_ts_split_k4", "mcc_resnet",
+                 "prl_2p16_2p18")
+
+
+def _rounded(x):
+    """Floats to 6 significant digits (keeps the one JSON line short); everything else unchanged."""
+    if isinstance(x, float):
+        return float("%.6g" % x)
+    if isinstance(x, dict):
+        return {k: _rounded(v) for k, v in x.items()}
+    if isinstance(x, (list, tuple)):
+        return [_rounded(v) for v in x]
+    return x
 
 
 BENCHES = {
@@ -608,6 +739,8 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="run a 512 MiB device copy first (reference kernel for --pmc byte counters)")
+    ap.add_argument("--valu-kinds", action="store_true",
+                    help="run the register-resident VALU loop of every instruction kind once first (for --pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.stderr.write("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -636,6 +769,9 @@ def main() -> int:
         del src, dst
         torch.cuda.empty_cache()
 
+    if args.valu_kinds:
+        valu_calibration(torch, mdh)
+
     torch.cuda.synchronize()
     head = BENCHES[args.workload](torch, mdh, W, args.workload, args.steps, args.warmup, not args.no_cpu)
     head["spread"] = dict(LAST_SPREAD)
@@ -663,27 +799,43 @@ def main() -> int:
     line["detail"] = {k: v for k, v in head.items() if k not in ("roofline", "cpu_baseline", "value", "unit")}
 
     if not args.no_instances:
-        global MIN_WARM_MS
+        global MIN_WARM_MS, ADAPTIVE
         MIN_WARM_MS = 20.0
+        ADAPTIVE = True  # keep timing each instance until the 99 % confidence interval is within 5 %
         inst = {}
-        for name, fn in BENCHES.items():
+        # the BASELINE configurations come last, so that they survive in a record that keeps only the
+        # end of this line
+        order = [n for n in BENCHES if n not in BASELINE_ROWS] + [n for n in BASELINE_ROWS if n in BENCHES]
+        for name in order:
             if name == args.workload:
                 continue
-            steps = max(5, min(args.steps, 30 if name in ("mcc_resnet", "prl_2p16_2p18", "mcc_capsule_resnet50_first", "prl_generic_2p16_2p18") else 100))
-            inst[name] = fn(torch, mdh, W, name, steps, max(2, min(args.warmup, 5)), not args.no_cpu)
+            inst[name] = BENCHES[name](torch, mdh, W, name, 20, max(2, min(args.warmup, 5)), not args.no_cpu)
             inst[name]["spread"] = dict(LAST_SPREAD)
             torch.cuda.synchronize()
             torch.cuda.empty_cache()
-        # the tall-skinny MatMul again with the reduction dimension split over workgroups
-        # (partial results in a device-memory workspace + second-pass combine)
-        inst["matmul_ts_split_k4"] = bench_matmul(torch, mdh, W, "matmul_ts", 100, 5, False, split=4)
-        inst["matmul_ts_split_k4"]["spread"] = dict(LAST_SPREAD)
-        torch.cuda.synchronize()
-        torch.cuda.empty_cache()
-        line["instances"] = inst
+            if name == "matmul_ts":
+                # the tall-skinny MatMul again with the reduction dimension split over workgroups
+                # (partial results in a device-memory workspace + second-pass combine)
+                inst["matmul_ts_split_k4"] = bench_matmul(torch, mdh, W, "matmul_ts", 20, 5, False, split=4)
+                inst["matmul_ts_split_k4"]["spread"] = dict(LAST_SPREAD)
+                torch.cuda.synchronize()
+                torch.cuda.empty_cache()
+        ADAPTIVE = False
         line["calibration"] = calibration(torch, mdh)
+        line["instances"] = inst
+        # compact table of the BASELINE configurations (and the split-k line), last in the line:
+        # [value, unit, ms_per_step, roofline.frac, roofline.bound, cpu_baseline value or null, ci99_rel]
+        rows = {}
+        everything = dict(inst)
+        everything[args.workload] = head
+        for name in BASELINE_ROWS:
+            r = everything.get(name)
+            if r is not None:
+                rows[name] = [r["value"], r["unit"], r["ms_per_step"], r["roofline"]["frac"], r["roofline"]["bound"],
+                              r.get("cpu_baseline", {}).get("value"), r.get("spread", {}).get("ci99_rel")]
+        line["baseline_rows"] = rows
 
-    print(json.dumps(line))
+    print(json.dumps(_rounded(line)))
     return 0
 
 

@@ -523,6 +523,48 @@ mdh_status mdh_calib_read(const void* src, int64_t bytes, float* out, void* stre
 mdh_status mdh_calib_mfma(float* out, int32_t iters, int64_t* flop, void* stream);
 mdh_status mdh_calib_valu(int32_t* out, int32_t iters, int64_t* lane_ops, void* stream);
 
+/*
+ * Integer VALU issue rate by instruction kind, with the shader clock read beside it
+ * (the ceiling the custom reduce is measured against; paper: Section "Examples",
+ * Subfigure 5 is the instance, its inner loop is what these loops are made of).
+ * Every kernel is a register-resident loop of MDH_CALIB_BLOCKS workgroups x 256 lanes,
+ * eight independent chains per lane, issuing ONE kind of instruction:
+ *   MDH_CALIB_KIND_XOR_MAX     v_xor + v_max pairs (the loop of mdh_calib_valu)
+ *   MDH_CALIB_KIND_CMP_SELECT  compare against a scalar-register operand + select
+ *   MDH_CALIB_KIND_ADD3        three-operand add
+ *   MDH_CALIB_KIND_FMA_F32     fp32 fused multiply-add on vector-register operands
+ *   MDH_CALIB_KIND_ADD_VGPR    32-bit add on vector-register operands (these two are of
+ *                              the kind the vector ALU issues at 32 lanes a cycle)
+ *   MDH_CALIB_KIND_PRL_MIX     the custom reduce's own inner loop at nF = 8 and two
+ *                              records of A per lane (per pair: 8 compares against a
+ *                              scalar operand, 8 selects, 4.5 adds, compare + max +
+ *                              select + half a move = 24 instructions), with the
+ *                              records of B made up on the scalar unit, not loaded
+ *   out      MDH_CALIB_BLOCKS*256 int32 (device), overwritten
+ *   weights  PRL_MIX only (else may be NULL): MDH_CALIB_MIX_WEIGHTS int32 (device):
+ *            8 agree weights, 8 disagree weights, then 256 lanes x 2 records x 8 fields
+ *   iters    loop trips; *lane_ops (host, may be NULL) receives lanes x VALU instructions
+ *            issued inside the loops of the launch
+ *   clocks   device, 2 x int64, may be NULL: the first wavefront of workgroup 0 writes
+ *            the shader-clock cycles and the constant-rate real-time ticks
+ *            (mdh_calib_realtime_hz() per second) that passed around its loop, so
+ *            shader clock = clocks[0] / clocks[1] * mdh_calib_realtime_hz()
+ * Errors: MDH_ERR_NULL, MDH_ERR_SIZE, MDH_ERR_UNSUPPORTED (kind), MDH_ERR_LAUNCH.
+ */
+enum {
+  MDH_CALIB_KIND_XOR_MAX = 0,
+  MDH_CALIB_KIND_CMP_SELECT = 1,
+  MDH_CALIB_KIND_ADD3 = 2,
+  MDH_CALIB_KIND_PRL_MIX = 3,
+  MDH_CALIB_KIND_FMA_F32 = 4,
+  MDH_CALIB_KIND_ADD_VGPR = 5
+};
+#define MDH_CALIB_MIX_WEIGHTS (16 + 256 * 2 * 8)
+mdh_status mdh_calib_valu_kind(int32_t kind, int32_t* out, const int32_t* weights, int32_t iters,
+                               int64_t* lane_ops, int64_t* clocks, void* stream);
+/* Rate of the real-time counter of the current device in Hz (host only; 0 if unknown). */
+int64_t mdh_calib_realtime_hz(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,11 +25,13 @@ EXPORTS = (
     "mdh_matmul_ex", "mdh_scan", "mdh_mcc_capsule", "mdh_calib_copy", "mdh_calib_read", "mdh_calib_mfma", "mdh_calib_valu",
     "mdh_custom_default_params", "mdh_custom_validate_params", "mdh_custom_num_candidates", "mdh_custom_candidate",
     "mdh_custom_create", "mdh_custom_source", "mdh_custom_workspace_size", "mdh_custom_run", "mdh_custom_destroy",
-    "mdh_custom_tune",
+    "mdh_custom_tune", "mdh_calib_valu_kind", "mdh_calib_realtime_hz",
 )
 MDH_CUSTOM_MAX_IN, MDH_CUSTOM_MAX_ACC = 4, 8
 MDH_CALIB_BLOCKS = 2048
 MDH_CALIB_STREAM_LANES = 256 * 512
+MDH_CALIB_KIND_XOR_MAX, MDH_CALIB_KIND_CMP_SELECT, MDH_CALIB_KIND_ADD3, MDH_CALIB_KIND_PRL_MIX, MDH_CALIB_KIND_FMA_F32, MDH_CALIB_KIND_ADD_VGPR = range(6)
+MDH_CALIB_MIX_WEIGHTS = 16 + 256 * 2 * 8
 
 
 class TileParams(ctypes.Structure):
@@ -134,6 +136,9 @@ def lib() -> ctypes.CDLL:
         L.mdh_calib_read.argtypes = [vp, i64, vp, vp]
         L.mdh_calib_mfma.argtypes = [vp, i32, p64, vp]
         L.mdh_calib_valu.argtypes = [vp, i32, p64, vp]
+        L.mdh_calib_valu_kind.argtypes = [i32, vp, vp, i32, p64, vp, vp]
+        L.mdh_calib_realtime_hz.restype = i64
+        L.mdh_calib_realtime_hz.argtypes = []
         L.mdh_num_candidates.restype = i32
         L.mdh_num_candidates.argtypes = [ctypes.c_int, p64]
         L.mdh_candidate.argtypes = [ctypes.c_int, p64, i32, pp]
@@ -511,6 +516,28 @@ def mdh_calib_valu(out, iters: int) -> int:
     _check(lib().mdh_calib_valu(_dev(out, torch.int32, "out"), iters, ctypes.byref(n), ctypes.c_void_p(_stream())),
            "mdh_calib_valu")
     return n.value
+
+
+def mdh_calib_valu_kind(kind: int, out, iters: int, weights=None, clocks=None) -> int:
+    """Register-resident loop of one VALU instruction kind (or the custom reduce's mix); returns lanes x
+    VALU instructions of the launch.  `clocks` (2 x int64 on the GPU) receives shader-clock cycles and
+    real-time ticks around the loop of workgroup 0."""
+    import torch
+
+    assert out.numel() >= MDH_CALIB_BLOCKS * 256
+    assert weights is None or weights.numel() >= MDH_CALIB_MIX_WEIGHTS
+    assert clocks is None or clocks.numel() >= 2
+    n = ctypes.c_int64()
+    st = lib().mdh_calib_valu_kind(int(kind), _dev(out, torch.int32, "out"),
+                                   _dev(weights, torch.int32, "weights") if weights is not None else None, iters,
+                                   ctypes.byref(n), _dev(clocks, torch.int64, "clocks") if clocks is not None else None,
+                                   ctypes.c_void_p(_stream()))
+    _check(st, "mdh_calib_valu_kind")
+    return n.value
+
+
+def mdh_calib_realtime_hz() -> int:
+    return int(lib().mdh_calib_realtime_hz())
 
 
 def mdh_tune(inst: int, sizes: Sequence[int], buffers, scalars=None, workspace=None, reps: int = 3):

@@ -5,6 +5,8 @@
 //   mdh_calib_read : streaming read with a per-lane sum (the access pattern of Dot / MatVec)
 //   mdh_calib_mfma : a register-resident loop of independent v_mfma_f32_32x32x2_f32
 //   mdh_calib_valu : a register-resident loop of independent 32-bit integer VALU instructions
+#include <limits.h>
+
 #include "mdh_internal.h"
 
 namespace mdh {
@@ -103,6 +105,179 @@ __global__ __launch_bounds__(CALIB_NT) void calib_valu_kernel(int32_t* __restric
   out[(int64_t)blockIdx.x * CALIB_NT + threadIdx.x] = s;
 }
 
+// ---- VALU issue rate by instruction kind, with the shader clock measured beside it ----
+//
+// The custom reduce is bound by integer VALU issue.  Its inner loop is made of a few instruction
+// kinds; each loop below is register resident, has eight independent chains per lane and issues ONE
+// kind (or the custom reduce's own mix), so that rate(kind) / (SIMDs x shader clock) is the issue cost of
+// that kind in cycles per wavefront instruction.  The shader clock itself is read in the kernel: the
+// wavefront of lane 0 of workgroup 0 samples the shader-clock counter and the constant-rate real-time
+// counter before and after its loop.
+struct Ticks {
+  long long shader, real;
+};
+__device__ __forceinline__ Ticks ticks_now() {
+  Ticks t;
+  t.shader = (long long)__builtin_readcyclecounter();       // counts shader-clock cycles
+  t.real = (long long)__builtin_amdgcn_s_memrealtime();     // counts at a constant rate
+  return t;
+}
+__device__ __forceinline__ void ticks_store(long long* clk, const Ticks& t0) {
+  if (clk && blockIdx.x == 0 && threadIdx.x == 0) {
+    const Ticks t1 = ticks_now();
+    clk[0] = t1.shader - t0.shader;
+    clk[1] = t1.real - t0.real;
+  }
+}
+
+// kind 1: compare against a wavefront-uniform (scalar-register) operand, then select: 2 instructions a step
+__global__ __launch_bounds__(CALIB_NT) void calib_cmpsel_kernel(int32_t* __restrict__ out, int iters,
+                                                                int seed, long long* __restrict__ clk) {
+  int32_t v[8], w[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j] = (int32_t)threadIdx.x * (j + 3), w[j] = (int32_t)threadIdx.x + j;
+  const Ticks t0 = ticks_now();
+  int s = seed;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      s = s * 5 + 1;  // scalar unit
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = (v[j] == s + j) ? w[j] : v[j];
+    }
+  }
+  ticks_store(clk, t0);
+  int32_t r = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) r ^= v[j];
+  out[(int64_t)blockIdx.x * CALIB_NT + threadIdx.x] = r;
+}
+
+// kind 2: three-operand add (two vector registers and a scalar register): 1 instruction a step
+__global__ __launch_bounds__(CALIB_NT) void calib_add3_kernel(int32_t* __restrict__ out, int iters,
+                                                              int seed, long long* __restrict__ clk) {
+  uint32_t v[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j] = threadIdx.x * (j + 3);
+  const Ticks t0 = ticks_now();
+  uint32_t s = (uint32_t)seed;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      s = s * 5u + 1u;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = v[j] + v[(j + 3) & 7] + s;
+    }
+  }
+  ticks_store(clk, t0);
+  uint32_t r = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) r ^= v[j];
+  out[(int64_t)blockIdx.x * CALIB_NT + threadIdx.x] = (int32_t)r;
+}
+
+// kind 3: the custom reduce's own inner loop (8 fields, 2 records of A per lane) with the records of
+// B made up on the scalar unit instead of loaded: per pair 8 compares against a scalar operand, 8
+// selects, 4.5 adds, and compare + max + select + half a move for max_idx = 24 instructions.
+__global__ __launch_bounds__(CALIB_NT) void calib_prlmix_kernel(int32_t* __restrict__ out, int iters,
+                                                                int seed, const int32_t* __restrict__ wts,
+                                                                long long* __restrict__ clk) {
+  constexpr int NF = 8, RA = 2;
+  unsigned dw[NF];
+  unsigned base = 0;
+#pragma unroll
+  for (int f = 0; f < NF; ++f) {
+    dw[f] = (unsigned)wts[f] - (unsigned)wts[NF + f];
+    base += (unsigned)wts[NF + f];
+  }
+  int ar[RA][NF];
+#pragma unroll
+  for (int ra = 0; ra < RA; ++ra)
+#pragma unroll
+    for (int f = 0; f < NF; ++f) ar[ra][f] = wts[2 * NF + (threadIdx.x * RA + ra) * NF + f];
+  int bs[RA], bi[RA];
+#pragma unroll
+  for (int ra = 0; ra < RA; ++ra) bs[ra] = INT_MIN, bi[ra] = INT_MAX;
+  const Ticks t0 = ticks_now();
+  int s = seed;
+  for (int b = 0; b < iters; ++b) {
+    int br[NF];  // wavefront-uniform "record of B": scalar registers
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+      s = s * 5 + 1;
+      br[f] = (s >> 9) & 15;
+    }
+#pragma unroll
+    for (int ra = 0; ra < RA; ++ra) {
+      unsigned sc = base;
+#pragma unroll
+      for (int f = 0; f < NF; ++f) sc += (ar[ra][f] == br[f]) ? dw[f] : 0u;
+      const int v = (int)sc;
+      const bool take = v > bs[ra];
+      bs[ra] = take ? v : bs[ra];
+      bi[ra] = take ? b : bi[ra];
+    }
+  }
+  ticks_store(clk, t0);
+  int32_t r = 0;
+#pragma unroll
+  for (int ra = 0; ra < RA; ++ra) r ^= bs[ra] ^ bi[ra];
+  out[(int64_t)blockIdx.x * CALIB_NT + threadIdx.x] = r;
+}
+
+// kinds 4 and 5: instructions of the kind the vector ALU issues at twice the rate (32 lanes a cycle:
+// moves, 32-bit add / subtract, bitwise logic, fp32 add / multiply / fused multiply-add, all on
+// vector-register operands).  Written as single instructions so that the compiler cannot fold a chain
+// of them; nothing here needs a wait state (no scalar operand, no condition code).
+template <bool FMA>
+__global__ __launch_bounds__(CALIB_NT) void calib_fastkind_kernel(int32_t* __restrict__ out, int iters,
+                                                                  int seed, long long* __restrict__ clk) {
+  int32_t v[8], w[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    v[j] = FMA ? __float_as_int(0.5f + (float)(threadIdx.x & 7) * 0.0625f) : (int32_t)threadIdx.x * (j + 3);
+    w[j] = FMA ? __float_as_int(0.25f + (float)j * 0.03125f) : (int32_t)threadIdx.x + j + seed;
+  }
+  const Ticks t0 = ticks_now();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (FMA)
+          asm volatile("v_fma_f32 %0, %0, %1, %1" : "+v"(v[j]) : "v"(w[j]));  // x <- x*w + w, stays in (0, 1)
+        else
+          asm volatile("v_add_u32 %0, %0, %1" : "+v"(v[j]) : "v"(w[j]));
+      }
+  }
+  ticks_store(clk, t0);
+  int32_t r = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) r ^= v[j];
+  out[(int64_t)blockIdx.x * CALIB_NT + threadIdx.x] = r;
+}
+
+// kind 0 with the clock readings: the loop of calib_valu_kernel
+__global__ __launch_bounds__(CALIB_NT) void calib_xormax_kernel(int32_t* __restrict__ out, int iters,
+                                                                int seed, long long* __restrict__ clk) {
+  int32_t v[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j] = (int32_t)threadIdx.x * (j + 3);
+  const int32_t c = (int32_t)blockIdx.x | seed | 1;
+  const Ticks t0 = ticks_now();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = max(v[j] ^ c, j + u - 40);
+  }
+  ticks_store(clk, t0);
+  int32_t r = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) r ^= v[j];
+  out[(int64_t)blockIdx.x * CALIB_NT + threadIdx.x] = r;
+}
+
 }  // namespace
 }  // namespace mdh
 
@@ -147,6 +322,54 @@ mdh_status mdh_calib_valu(int32_t* out, int32_t iters, int64_t* lane_ops, void* 
   // per lane and iteration: 32 xors + 32 maxima
   if (lane_ops) *lane_ops = (int64_t)MDH_CALIB_BLOCKS * CALIB_NT * iters * 64;
   return launch_status();
+}
+
+mdh_status mdh_calib_valu_kind(int32_t kind, int32_t* out, const int32_t* weights, int32_t iters,
+                               int64_t* lane_ops, int64_t* clocks, void* stream) {
+  if (!out || (kind == MDH_CALIB_KIND_PRL_MIX && !weights)) return MDH_ERR_NULL;
+  if (iters <= 0) return MDH_ERR_SIZE;
+  clear_stale_error();
+  const dim3 g(MDH_CALIB_BLOCKS), b(CALIB_NT);
+  hipStream_t st = (hipStream_t)stream;
+  long long* clk = (long long*)clocks;
+  int64_t per_lane = 0;  // VALU instructions a lane issues inside the loop
+  switch (kind) {
+    case MDH_CALIB_KIND_XOR_MAX:
+      hipLaunchKernelGGL(calib_xormax_kernel, g, b, 0, st, out, iters, 0, clk);
+      per_lane = (int64_t)iters * 64;  // 32 xors + 32 maxima
+      break;
+    case MDH_CALIB_KIND_CMP_SELECT:
+      hipLaunchKernelGGL(calib_cmpsel_kernel, g, b, 0, st, out, iters, 12345, clk);
+      per_lane = (int64_t)iters * 64;  // 32 compares + 32 selects
+      break;
+    case MDH_CALIB_KIND_ADD3:
+      hipLaunchKernelGGL(calib_add3_kernel, g, b, 0, st, out, iters, 12345, clk);
+      per_lane = (int64_t)iters * 64;  // 64 three-operand adds
+      break;
+    case MDH_CALIB_KIND_PRL_MIX:
+      hipLaunchKernelGGL(calib_prlmix_kernel, g, b, 0, st, out, iters, 12345, weights, clk);
+      per_lane = (int64_t)iters * 48;  // two pairs of 24 instructions
+      break;
+    case MDH_CALIB_KIND_FMA_F32:
+      hipLaunchKernelGGL(calib_fastkind_kernel<true>, g, b, 0, st, out, iters, 0, clk);
+      per_lane = (int64_t)iters * 64;  // 64 fused multiply-adds on vector registers
+      break;
+    case MDH_CALIB_KIND_ADD_VGPR:
+      hipLaunchKernelGGL(calib_fastkind_kernel<false>, g, b, 0, st, out, iters, 12345, clk);
+      per_lane = (int64_t)iters * 64;  // 64 two-operand adds on vector registers
+      break;
+    default:
+      return MDH_ERR_UNSUPPORTED;
+  }
+  if (lane_ops) *lane_ops = (int64_t)MDH_CALIB_BLOCKS * CALIB_NT * per_lane;
+  return launch_status();
+}
+
+int64_t mdh_calib_realtime_hz(void) {
+  int dev = 0, khz = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess) return 0;
+  return (int64_t)khz * 1000;
 }
 
 }  // extern "C"

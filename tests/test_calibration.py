@@ -40,3 +40,51 @@ def test_mfma_and_valu_counts():
     assert ops == B.MDH_CALIB_BLOCKS * 256 * 4 * 64
     with pytest.raises(mdh.MdhError):
         mdh.mdh_calib_mfma(out, 0)
+
+
+@pytest.mark.gpu
+def test_valu_kinds_count_and_compute():
+    import numpy as np
+
+    outi = torch.empty(B.MDH_CALIB_BLOCKS * 256, dtype=torch.int32, device="cuda")
+    clk = torch.zeros(2, dtype=torch.int64, device="cuda")
+    for kind in (B.MDH_CALIB_KIND_XOR_MAX, B.MDH_CALIB_KIND_CMP_SELECT, B.MDH_CALIB_KIND_ADD3, B.MDH_CALIB_KIND_FMA_F32,
+                 B.MDH_CALIB_KIND_ADD_VGPR):
+        ops = mdh.mdh_calib_valu_kind(kind, outi, 64, None, clk)
+        torch.cuda.synchronize()
+        assert ops == B.MDH_CALIB_BLOCKS * 256 * 64 * 64
+        c = clk.cpu().numpy()
+        assert c[0] > 0 and c[1] > 0
+    hz = mdh.mdh_calib_realtime_hz()
+    assert hz > 0
+    # the instruction-mix loop really evaluates the max-with-index reduction it is modelled on: redo it
+    # on the host for the 256 lanes of a workgroup (every workgroup computes the same)
+    rng = np.random.default_rng(11)
+    w = np.concatenate([rng.integers(1, 1000, 8), rng.integers(-1000, 0, 8), rng.integers(0, 16, 256 * 2 * 8)]).astype(np.int32)
+    iters = 200
+    ops = mdh.mdh_calib_valu_kind(B.MDH_CALIB_KIND_PRL_MIX, outi, iters, torch.from_numpy(w).cuda(), clk)
+    torch.cuda.synchronize()
+    assert ops == B.MDH_CALIB_BLOCKS * 256 * iters * 48
+    ar = w[16:].reshape(256, 2, 8).astype(np.int64)
+    dw = (w[:8].astype(np.int64) - w[8:16].astype(np.int64))
+    base = int(w[8:16].astype(np.int64).sum())
+    bs = np.full((256, 2), -2**31, dtype=np.int64)
+    bi = np.full((256, 2), 2**31 - 1, dtype=np.int64)
+    s = 12345
+    for b in range(iters):
+        br = np.empty(8, dtype=np.int64)
+        for f in range(8):
+            s = (s * 5 + 1) & 0xFFFFFFFF
+            br[f] = (s >> 9) & 15
+        sc = base + ((ar == br) * dw).sum(axis=2)
+        take = sc > bs
+        bs = np.where(take, sc, bs)
+        bi = np.where(take, b, bi)
+    want = (bs[:, 0] ^ bi[:, 0] ^ bs[:, 1] ^ bi[:, 1]).astype(np.int64)
+    want = ((want + 2**31) % 2**32 - 2**31).astype(np.int32)
+    got = outi.cpu().numpy().reshape(-1, 256)
+    assert np.array_equal(got[0], want) and np.array_equal(got[-1], want)
+    ghz = clk.cpu().numpy()[0] / clk.cpu().numpy()[1] * hz / 1e9
+    assert 0.3 < ghz < 4.0, ghz
+    with pytest.raises(mdh.MdhError):
+        mdh.mdh_calib_valu_kind(7, outi, 4)

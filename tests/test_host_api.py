@@ -222,6 +222,9 @@ def test_size_errors_of_the_later_entry_points():
     assert L.mdh_calib_copy(one, one, 24, null) == E_SIZE  # not a multiple of 16 bytes
     assert L.mdh_calib_copy(null, one, 32, null) == E_NULL
     assert L.mdh_calib_mfma(null, 8, null, null) == E_NULL
+    assert L.mdh_calib_valu_kind(0, null, null, 8, null, null, null) == E_NULL
+    assert L.mdh_calib_valu_kind(3, one, null, 8, null, null, null) == E_NULL  # the mix needs its weights
+    assert L.mdh_calib_valu_kind(0, one, null, 0, null, null, null) == E_SIZE
     # generic path: description limits
     d = mdh.custom_desc((8,), (1,), ["float"], [(0, "i0")], "float", 4, "r = a0;", "r = x + y;")
     d.D = 0
