@@ -55,7 +55,9 @@ typedef enum mdh_status {
                                     LDS or register budget exceeded                             */
   MDH_ERR_WORKSPACE = 5,         /* workspace missing or too small for a split reduction        */
   MDH_ERR_UNSUPPORTED = 6,       /* valid in the paper's space but no kernel instantiation      */
-  MDH_ERR_LAUNCH = 7             /* the HIP runtime refused the launch                          */
+  MDH_ERR_LAUNCH = 7,            /* the HIP runtime refused the launch                          */
+  MDH_ERR_STATIC_LIMIT = 8       /* mdh_custom_reduce_static: the call needs more scratch memory
+                                    than the library's static buffer holds                      */
 } mdh_status;
 
 /* Instances (index into the library's table of md_hom expressions). */
@@ -260,6 +262,29 @@ mdh_status mdh_custom_reduce(int64_t nA, int64_t nB, int32_t nF, const int32_t* 
                              int32_t* out_score, int32_t* out_index,
                              const mdh_tile_params* params, void* workspace,
                              size_t workspace_bytes, void* stream);
+
+/*
+ * mdh_custom_reduce for callers that cannot allocate device memory -- code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * operation, arguments, results (bit for bit) and errors as mdh_custom_reduce, but
+ * without the workspace arguments: the partial results of a reduction split over
+ * workgroups (2 * S * nA int32, S = prt[MDH_L_WG][b]) go to a static device array
+ * inside the library, mdh_static_scratch_bytes() = 8 MiB per GPU, which the GPU
+ * holds until the process ends.  A call whose partial results do not fit returns
+ * MDH_ERR_STATIC_LIMIT and enqueues nothing (at the default configuration of
+ * 2^16 x 2^18 records, S = 16, they fit exactly); pass a configuration with a
+ * smaller S, or use mdh_custom_reduce with a workspace.  The call allocates and
+ * frees nothing and synchronises nothing; the first call on a device looks up the
+ * array's device address.  All calls on one GPU share that array: calls that may
+ * overlap (different streams, or threads) race on it and must be ordered by the
+ * caller; calls on one stream are ordered by the stream.
+ */
+mdh_status mdh_custom_reduce_static(int64_t nA, int64_t nB, int32_t nF, const int32_t* A,
+                                    const int32_t* B, const int32_t* w_agree,
+                                    const int32_t* w_disagree, int32_t* out_score,
+                                    int32_t* out_index, const mdh_tile_params* params, void* stream);
+/* Size in bytes of the static scratch array of mdh_custom_reduce_static (host only). */
+size_t mdh_static_scratch_bytes(void);
 
 /*
  * MCC_Capsule: MCC on 4 x 4 matrices instead of scalars,

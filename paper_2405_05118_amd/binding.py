@@ -25,7 +25,8 @@ EXPORTS = (
     "mdh_matmul_ex", "mdh_scan", "mdh_mcc_capsule", "mdh_calib_copy", "mdh_calib_read", "mdh_calib_mfma", "mdh_calib_valu",
     "mdh_custom_default_params", "mdh_custom_validate_params", "mdh_custom_num_candidates", "mdh_custom_candidate",
     "mdh_custom_create", "mdh_custom_source", "mdh_custom_workspace_size", "mdh_custom_run", "mdh_custom_destroy",
-    "mdh_custom_tune", "mdh_calib_valu_kind", "mdh_calib_realtime_hz",
+    "mdh_custom_tune", "mdh_calib_valu_kind", "mdh_calib_realtime_hz", "mdh_custom_reduce_static",
+    "mdh_static_scratch_bytes",
 )
 MDH_CUSTOM_MAX_IN, MDH_CUSTOM_MAX_ACC = 4, 8
 MDH_CALIB_BLOCKS = 2048
@@ -111,6 +112,9 @@ def lib() -> ctypes.CDLL:
         L.mdh_mcc.argtypes = [i64] * 9 + [vp, vp, vp, pp, vp, sz, vp]
         L.mdh_custom_reduce.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, pp, vp, sz, vp]
         L.mdh_matmul_ex.argtypes = [i64, i64, i64, i64, vp, i32, vp, i32, vp, i32, pp, vp, sz, vp]
+        L.mdh_custom_reduce_static.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, pp, vp]
+        L.mdh_static_scratch_bytes.restype = sz
+        L.mdh_static_scratch_bytes.argtypes = []
         L.mdh_dot.argtypes = [i64, vp, vp, vp, pp, vp, sz, vp]
         L.mdh_scan.argtypes = [i64, i64, vp, vp, pp, vp, sz, vp]
         L.mdh_mcc_capsule.argtypes = [i64] * 9 + [vp, vp, vp, pp, vp]
@@ -280,6 +284,26 @@ def mdh_custom_reduce(A, B, w_agree, w_disagree, out_score, out_index, params: O
                                  _dev(out_index, i32, "out_index"), _pref(params), wp, wb, ctypes.c_void_p(_stream()))
     _check(st, "mdh_custom_reduce")
     return out_score, out_index
+
+
+def mdh_custom_reduce_static(A, B, w_agree, w_disagree, out_score, out_index, params: Optional[TileParams] = None):
+    """mdh_custom_reduce without a workspace: split-reduction partial results go to the library's static array."""
+    import torch
+
+    nA, nF = A.shape
+    nB, nF2 = B.shape
+    assert nF == nF2 == w_agree.numel() == w_disagree.numel()
+    assert out_score.numel() == nA and out_index.numel() == nA
+    i32 = torch.int32
+    st = lib().mdh_custom_reduce_static(nA, nB, nF, _dev(A, i32, "A"), _dev(B, i32, "B"), _dev(w_agree, i32, "w_agree"),
+                                        _dev(w_disagree, i32, "w_disagree"), _dev(out_score, i32, "out_score"),
+                                        _dev(out_index, i32, "out_index"), _pref(params), ctypes.c_void_p(_stream()))
+    _check(st, "mdh_custom_reduce_static")
+    return out_score, out_index
+
+
+def mdh_static_scratch_bytes() -> int:
+    return int(lib().mdh_static_scratch_bytes())
 
 
 def mdh_matmul_ex(A, B, C, trans_a=False, trans_b=False, trans_c=False, params: Optional[TileParams] = None,

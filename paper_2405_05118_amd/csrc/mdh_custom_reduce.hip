@@ -17,7 +17,16 @@
 // second kernel (workgroup results combine in device memory only).
 #include <limits.h>
 
+#include <mutex>
+
 #include "mdh_internal.h"
+
+// Scratch memory of mdh_custom_reduce_static, the entry point for callers that cannot allocate: the
+// partial (score, index) results of a reduction split over workgroups, 2 * S * nA int32.  One copy per
+// GPU, held until the process ends.  In host code the name is a stand-in, not a device address: the
+// address is looked up once per device (scratch_of_current_device) and only that pointer is used.
+#define MDH_STATIC_SCRATCH_INTS (1u << 21)  // 8 MiB
+static __device__ __align__(256) int32_t scratch[MDH_STATIC_SCRATCH_INTS];
 
 namespace mdh {
 namespace {
@@ -175,6 +184,27 @@ mdh_status launch_nf(const PrlPlan& pl, int64_t nA, int64_t nB, int nF, const in
   return launch_t<16, false, RA, WB, WA>(pl, nA, nB, nF, A, B, wp, wm, score, index, ws, st);
 }
 
+std::mutex g_scratch_mutex;
+int32_t* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, looked up on the first call per device.
+mdh_status scratch_of_current_device(int32_t** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MDH_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      g_last_launch_error = e;
+      return MDH_ERR_LAUNCH;
+    }
+    g_scratch_ptr[dev] = (int32_t*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MDH_OK;
+}
+
 }  // namespace
 
 mdh_status launch_prl(const PrlPlan& pl, int64_t nA, int64_t nB, int nF, const int32_t* A,
@@ -196,3 +226,29 @@ mdh_status launch_prl(const PrlPlan& pl, int64_t nA, int64_t nB, int nF, const i
 }
 
 }  // namespace mdh
+
+extern "C" mdh_status mdh_custom_reduce_static(int64_t nA, int64_t nB, int32_t nF, const int32_t* A,
+                                               const int32_t* B, const int32_t* w_agree,
+                                               const int32_t* w_disagree, int32_t* out_score,
+                                               int32_t* out_index, const mdh_tile_params* params,
+                                               void* stream) {
+  using namespace mdh;
+  constexpr int64_t kMaxElems = 0x7fffffff;
+  if (nA < 0 || nB < 1 || nF < 1 || nF > 16) return MDH_ERR_SIZE;
+  if (nA > kMaxElems || nB > kMaxElems || nA * nF > kMaxElems || nB * nF > kMaxElems) return MDH_ERR_SIZE;
+  const int64_t sizes[2] = {nA, nB};
+  PrlPlan pl;
+  mdh_status st = plan_prl(sizes, params, &pl);
+  if (st != MDH_OK) return st;
+  if (nA == 0) return MDH_OK;
+  if (!A || !B || !w_agree || !w_disagree || !out_score || !out_index) return MDH_ERR_NULL;
+  // the split reduction's partial results must fit the static array; nothing is allocated instead
+  if (pl.S > 1 && (int64_t)pl.S * nA * 2 > (int64_t)MDH_STATIC_SCRATCH_INTS) return MDH_ERR_STATIC_LIMIT;
+  int32_t* ws = nullptr;
+  if (pl.S > 1 && (st = scratch_of_current_device(&ws)) != MDH_OK) return st;
+  // every (part, record) slot the second pass reads is written by the first kernel of this call:
+  // nothing left by an earlier call is read, so nothing has to be cleared
+  return launch_prl(pl, nA, nB, nF, A, B, w_agree, w_disagree, out_score, out_index, ws, (hipStream_t)stream);
+}
+
+extern "C" size_t mdh_static_scratch_bytes(void) { return (size_t)MDH_STATIC_SCRATCH_INTS * sizeof(int32_t); }

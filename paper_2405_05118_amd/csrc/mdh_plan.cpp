@@ -727,6 +727,7 @@ const char* mdh_strerror(mdh_status s) {
     case MDH_ERR_WORKSPACE: return "workspace missing or too small for the split reduction";
     case MDH_ERR_UNSUPPORTED: return "no kernel instantiation for this configuration";
     case MDH_ERR_LAUNCH: return "HIP launch failed";
+    case MDH_ERR_STATIC_LIMIT: return "the call needs more scratch memory than the library's static buffer holds";
   }
   return "unknown status";
 }

@@ -11,7 +11,7 @@ from paper_2405_05118_amd import binding as B
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
-OK, E_NULL, E_SIZE, E_NOTDIV, E_RES, E_WS, E_UNSUP, E_LAUNCH = range(8)
+OK, E_NULL, E_SIZE, E_NOTDIV, E_RES, E_WS, E_UNSUP, E_LAUNCH, E_STATIC = range(9)
 
 CASES = [
     (mdh.MDH_MATMUL, (256, 256, 256)),
@@ -218,6 +218,13 @@ def test_size_errors_of_the_later_entry_points():
     assert L.mdh_mcc_capsule(0, 8, 8, 3, 8, 3, 3, 1, 1, null, null, null, null, null) == OK
     assert L.mdh_mcc_capsule(1, 8, 8, 3, 8, 3, 3, 1, 1, null, null, null, null, null) == E_NULL
     assert L.mdh_mcc_capsule(1, 38, 38, 64, 8, 7, 7, 1, 1, one, one, one, null, null) == E_RES
+    # the entry point without allocations: same checks, plus the limit of the static scratch array
+    assert L.mdh_custom_reduce_static(8, 0, 8, one, one, one, one, one, one, null, null) == E_SIZE
+    assert L.mdh_custom_reduce_static(0, 8, 8, null, null, null, null, null, null, null, null) == OK
+    assert L.mdh_custom_reduce_static(8, 8, 8, null, one, one, one, one, one, null, null) == E_NULL
+    assert L.mdh_custom_reduce_static((1 << 17) + 128, 1 << 18, 8, one, one, one, one, one, one, null, null) == E_STATIC  # S = 8
+    assert L.mdh_static_scratch_bytes() == 8 << 20
+    assert "static" in mdh.mdh_strerror(E_STATIC)
     # calibration kernels
     assert L.mdh_calib_copy(one, one, 24, null) == E_SIZE  # not a multiple of 16 bytes
     assert L.mdh_calib_copy(null, one, 32, null) == E_NULL
