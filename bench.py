@@ -204,7 +204,9 @@ def bench_matmul(torch, mdh, W, name, steps, warmup, cpu, split=None):
     tf = flop / ms / 1e9
     res = {
         "value": flop / wall / 1e6, "unit": "GFLOP/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "f32",
-        "kernel": "matmul_kernel" + (" + combine_sum_kernel" if p.prt[3][2] > 1 else ""),
+        "kernel": ("matmul_ksplit16_kernel" if p.blk[0] == 16 else "matmul_ksplit_kernel" if p.prt[4][2] > 1 else "matmul_kernel")
+        + (" + combine_sum_kernel" if p.prt[3][2] > 1 else ""),
+        "wavefront_parts_of_k": int(p.prt[4][2]),
         "split_k": int(p.prt[3][2]),
         "roofline": {"bound": "mfma", "achieved": tf, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": tf / PEAK_FP32_MFMA_TFLOPS, "traffic": TRAFFIC_BYTES.get(name)},

@@ -196,10 +196,15 @@ size_t mdh_workspace_size(mdh_instance inst, const int64_t* sizes, const mdh_til
  *   M == 0 or N == 0 is a valid empty call.
  *   FP32 MFMA arithmetic, fp32 accumulation; if prt[MDH_L_WG][k] = S > 1 the
  *   S partial results go to `workspace` (S*M*N floats) and a second kernel adds
- *   them in ascending part order.  The library default splits k for small
- *   outputs, so pass the workspace mdh_workspace_size asks for.  This entry point
- *   always runs the LDS-tiled kernel; for M <= 16 mdh_matmul_ex (batch 1) has a
- *   kernel that streams B once without LDS and is several times faster.
+ *   them in ascending part order.  The library default may split k, so pass the
+ *   workspace mdh_workspace_size asks for.  Two kernels, told apart in the table by
+ *   prt[MDH_L_WAVE][k]: 1 = the wavefronts of a workgroup tile its output tile,
+ *   operands staged in LDS (in_region = MDH_MR_LDS); WK > 1 = every wavefront owns
+ *   the whole (small) output tile and 1/WK of the k-range, operands go straight to
+ *   registers (in_region = MDH_MR_VGPR) and the WK results are added in LDS in
+ *   ascending wavefront order (out_region = MDH_MR_LDS) -- the default for outputs
+ *   of few tiles, blk = (16,16,4) or (32,32,2).  For M <= 16 mdh_matmul_ex (batch 1)
+ *   has a kernel that streams B once and is several times faster still.
  */
 mdh_status mdh_matmul(int64_t M, int64_t N, int64_t K, const float* A, const float* B, float* C,
                       const mdh_tile_params* params, void* workspace, size_t workspace_bytes,

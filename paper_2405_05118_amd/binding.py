@@ -163,9 +163,21 @@ def _check(st: int, where: str):
         raise MdhError(st, where)
 
 
+_raw_stream = None
+
+
 def _stream() -> int:
+    """Handle of torch's current stream on the current device.  torch's C entry point for it is several
+    times cheaper than building a torch.cuda.Stream object per call, which matters for kernels of a few
+    microseconds; the portable form is the fallback."""
+    global _raw_stream
     import torch
 
+    if _raw_stream is None:
+        f = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+        _raw_stream = f if f is not None else False
+    if _raw_stream:
+        return int(_raw_stream(torch.cuda.current_device()))
     return int(torch.cuda.current_stream().cuda_stream)
 
 

@@ -20,6 +20,7 @@ SOURCES = [
     "mdh_api.hip",
     "mdh_stencil.hip",
     "mdh_matmul.hip",
+    "mdh_matmul_ksplit.hip",
     "mdh_mcc.hip",
     "mdh_mcc_flat.hip",
     "mdh_calib.hip",

@@ -31,6 +31,19 @@ mdh_status mdh_matmul(int64_t M, int64_t N, int64_t K, const float* A, const flo
   if (too_big(M) || too_big(N) || too_big(K) || too_big(M * K) || too_big(K * N) || too_big(M * N))
     return MDH_ERR_SIZE;
   const int64_t sizes[3] = {M, N, K};
+  if (small_m_matmul(sizes, params)) {
+    // at most 16 rows: the small-M kernel of the batched instance (one batch entry, plain views)
+    GemmExPlan ex;
+    mdh_status st = plan_matmul_small_m(sizes, params, &ex);
+    if (st != MDH_OK) return st;
+    if (M == 0 || N == 0) return MDH_OK;
+    if (!A || !B || !C) return MDH_ERR_NULL;
+    if (ex.g.S > 1) {
+      const size_t need = (size_t)ex.g.S * (size_t)M * (size_t)N * sizeof(float);
+      if (!workspace || workspace_bytes < need) return MDH_ERR_WORKSPACE;
+    }
+    return launch_matmul_ex(ex, 1, M, N, K, A, B, C, workspace, (hipStream_t)stream);
+  }
   GemmPlan pl;
   mdh_status st = plan_matmul(sizes, params, &pl);
   if (st != MDH_OK) return st;

@@ -26,6 +26,10 @@ struct GemmPlan {
   int BM, BN, BK, WM, WN;
   int S;  // workgroup-layer parts of the reduction dimension
   int ragged;
+  // wavefront-layer parts of the reduction dimension.  1: the LDS-tiled kernel (wavefronts tile the
+  // output).  > 1: the kernel whose WK wavefronts all own the whole BM x BN tile and split k, operands
+  // straight from device memory to registers, results combined in LDS (then WM = BM, WN = BN, BK = 8).
+  int WK = 1;
 };
 
 // MCC: workgroup tile TP x TQ output pixels x BN output channels, CK channels per LDS stage.
@@ -60,6 +64,8 @@ struct DotPlan {
   int WAVES;
   int S;
   int ragged;
+  int strided = 1;  // lanes interleave 4-element parts (1) or own one contiguous part each (0)
+  int fused = 1;    // S > 1: the last workgroup part to arrive folds the partial sums (one launch)
 };
 
 // MatVec: a wavefront owns RM rows; WM wavefronts along i, WK wavefronts along k per
@@ -68,6 +74,7 @@ struct MatVecPlan {
   int RM, WM, WK;
   int S;
   int ragged;
+  int strided = 1;  // lanes interleave 4-element parts of k (1) or own one contiguous part each (0)
 };
 
 // Row-wise scan: a workgroup owns one chunk of one row = TPC sequential tiles of WAVES*256
@@ -110,7 +117,13 @@ struct GemmExPlan {
   // skinny = 1: the small-M kernel (16 x 16 x 4 block, operands straight to registers); then
   // g.BM = 16, g.BN = 64 * wavefronts along j, g.BK = 16 and WK = wavefronts along k
   int skinny = 0, WK = 1;
+  // small-M kernel with S > 1: 1 = the last workgroup part of an output strip to arrive adds the S
+  // partial results itself (one launch), 0 = a second kernel does
+  int fused = 0;
 };
+// Counters of arriving workgroup parts live in static device arrays of this many words per kernel
+// family; a split reduction with more output parts than that takes the second-kernel path.
+constexpr int kArrivalCounters = 4096;
 mdh_status plan_matmul_ex(const int64_t* sizes, const mdh_tile_params* p, GemmExPlan* out);
 void params_from_plan(const int64_t* sizes, const GemmExPlan& pl, mdh_tile_params* out);
 int matmul_ex_candidates(const int64_t* sizes, GemmExPlan* out, int cap);
@@ -118,8 +131,20 @@ mdh_status launch_matmul_ex(const GemmExPlan& pl, int64_t batch, int64_t M, int6
                             const float* A, const float* B, float* C, void* ws, hipStream_t st);
 mdh_status launch_matmul_skinny(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, int64_t K,
                                 const float* A, const float* B, float* C, void* ws, hipStream_t st);
+mdh_status launch_matmul_ksplit(const GemmPlan& pl, int64_t M, int64_t N, int64_t K, const float* A,
+                                const float* B, float* C, void* ws, hipStream_t st);
 // dst[i] = part_0[i] + ... + part_{S-1}[i], i < n (defined in mdh_matmul.hip)
 mdh_status launch_combine_sum(const float* ws, float* dst, int64_t n, int S, hipStream_t st);
+
+// MatMul with at most 16 rows is evaluated by the small-M kernel of the batched entry point (batch 1,
+// plain views).  small_m_matmul: does (sizes, p) of the MatMul instance select that kernel -- the
+// default for 0 < M <= 16, or a table with its signature (16 x 16 x 4 block, four register parts of j).
+// lift_batch / drop_batch convert between the 3-dimensional MatMul table and the 4-dimensional table of
+// the batched instance with one batch entry.
+bool small_m_matmul(const int64_t* sizes3, const mdh_tile_params* p);
+void lift_batch(const mdh_tile_params& p3, mdh_tile_params* p4);
+void drop_batch(const mdh_tile_params& p4, mdh_tile_params* p3);
+mdh_status plan_matmul_small_m(const int64_t* sizes3, const mdh_tile_params* p, GemmExPlan* out);
 
 mdh_status plan_dot(const int64_t* sizes, const mdh_tile_params* p, DotPlan* out);
 mdh_status plan_matvec(const int64_t* sizes, const mdh_tile_params* p, MatVecPlan* out);

@@ -327,6 +327,7 @@ mdh_status launch_combine_sum(const float* ws, float* dst, int64_t n, int S, hip
 
 mdh_status launch_matmul(const GemmPlan& pl, int64_t M, int64_t N, int64_t K, const float* A,
                          const float* B, float* C, void* ws, hipStream_t st) {
+  if (pl.WK > 1) return launch_matmul_ksplit(pl, M, N, K, A, B, C, ws, st);
 #define MDH_MM(bm, bn, bk, wm, wn)                                                   \
   if (pl.BM == bm && pl.BN == bn && pl.BK == bk && pl.WM == wm && pl.WN == wn)       \
     return launch_t<bm, bn, bk, wm, wn>(pl, M, N, K, A, B, C, ws, st);

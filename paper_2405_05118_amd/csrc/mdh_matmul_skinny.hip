@@ -33,11 +33,16 @@ typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));  // dword-ali
 
 constexpr int SK_PF = 2;  // 16-row steps requested together by a wavefront
 
+// One counter per output strip (batch entry, tile, wavefront along j): how many of the S workgroup
+// parts of k have stored their partial strip.  Zero when the library is loaded; the S-th arrival wraps
+// it back to zero (atomicInc with bound S-1), so every call leaves it as it found it.
+static __device__ unsigned g_strip_arrivals[kArrivalCounters];
+
 template <int WAVES_N, int WAVES_K, bool TB>
 __global__ __launch_bounds__((WAVES_N * WAVES_K * 64)) void matmul_skinny_kernel(
     const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C,
     float* __restrict__ ws, int M, int N, int K, int tiles_m, int tiles_n, int S, int kchunk,
-    int nbatch) {
+    int nbatch, int fused) {
   __shared__ f4 part[WAVES_K > 1 ? (WAVES_K - 1) * WAVES_N * 4 * 64 : 1];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -165,23 +170,66 @@ __global__ __launch_bounds__((WAVES_N * WAVES_K * 64)) void matmul_skinny_kernel
 
   // output view: register r of block c is C[m0 + 4g + r][col + c]; with the transposed view of B,
   // C[m0 + 4g + r][n0 + 16c + l16]
+  auto store_strip = [&](float* dst) {
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int row = m0 + 4 * g + r;
-    if (row >= M) continue;
-    float* p = out + (int64_t)row * N + col;
-    if (TB) {
+    for (int r = 0; r < 4; ++r) {
+      const int row = m0 + 4 * g + r;
+      if (row >= M) continue;
+      float* p = dst + (int64_t)row * N + col;
+      if (TB) {
 #pragma unroll
-      for (int c = 0; c < 4; ++c)
-        if (n0 + 16 * c + l16 < N) out[(int64_t)row * N + n0 + 16 * c + l16] = acc[c][r];
-    } else if (cols_full) {
-      *(f4u*)p = (f4){acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
-    } else {
+        for (int c = 0; c < 4; ++c)
+          if (n0 + 16 * c + l16 < N) dst[(int64_t)row * N + n0 + 16 * c + l16] = acc[c][r];
+      } else if (cols_full) {
+        *(f4u*)p = (f4){acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
+      } else {
 #pragma unroll
-      for (int c = 0; c < 4; ++c)
-        if (col + c < N) p[c] = acc[c][r];
+        for (int c = 0; c < 4; ++c)
+          if (col + c < N) p[c] = acc[c][r];
+      }
+    }
+  };
+  store_strip(out);
+  if (S <= 1 || !fused) return;
+
+  // workgroup layer -> grid in the same launch: the wavefront that stores the S-th partial strip adds
+  // all S of them, in ascending part order (the order of the second kernel: same bits), into C.  Only
+  // this wavefront is left in its workgroup for this strip; no barrier is involved.
+  __threadfence();  // this wavefront's partial strip is visible to the whole device before it is counted
+  unsigned seen = 0;
+  if (lane == 0) seen = atomicInc(&g_strip_arrivals[((unsigned)batch * tiles + t) * WAVES_N + wn], (unsigned)S - 1);
+  seen = __builtin_amdgcn_readfirstlane(seen);
+  if (seen != (unsigned)S - 1) return;
+  __threadfence();  // the other parts' strips, counted before this one, are visible to this wavefront
+  const int64_t part_stride = (int64_t)nbatch * mn;
+  const float* w0 = ws + (int64_t)batch * mn;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) acc[c] = (f4){0.f, 0.f, 0.f, 0.f};
+  for (int sp = 0; sp < S; ++sp) {
+    const float* src = w0 + (int64_t)sp * part_stride;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = m0 + 4 * g + r;
+      if (row >= M) continue;
+      const float* p = src + (int64_t)row * N + col;
+      f4 v = {0.f, 0.f, 0.f, 0.f};
+      if (TB) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          if (n0 + 16 * c + l16 < N) v[c] = src[(int64_t)row * N + n0 + 16 * c + l16];
+      } else if (cols_full) {
+        v = *(const f4u*)p;
+      } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          if (col + c < N) v[c] = p[c];
+      }
+      // part 0 overrides (first write, no neutral element), later parts are added
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[c][r] = sp == 0 ? v[c] : acc[c][r] + v[c];
     }
   }
+  store_strip(C + (int64_t)batch * mn);
 }
 
 template <int WAVES_N, int WAVES_K, bool TB>
@@ -194,11 +242,12 @@ mdh_status launch_t(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, i
   const int64_t nblocks = tm * tn * S;
   if (nblocks > 0x7fffffff || batch > 65535) return MDH_ERR_SIZE;
   clear_stale_error();
+  const int fused = (S > 1 && pl.fused && batch * tm * tn * WAVES_N <= kArrivalCounters) ? 1 : 0;
   hipLaunchKernelGGL((matmul_skinny_kernel<WAVES_N, WAVES_K, TB>), dim3((unsigned)nblocks, (unsigned)batch),
                      dim3(WAVES_N * WAVES_K * 64), 0, st, A, B, C, (float*)ws, (int)M, (int)N, (int)K,
-                     (int)tm, (int)tn, S, (int)kchunk, (int)batch);
+                     (int)tm, (int)tn, S, (int)kchunk, (int)batch, fused);
   mdh_status r = launch_status();
-  if (r != MDH_OK || S <= 1) return r;
+  if (r != MDH_OK || S <= 1 || fused) return r;
   return launch_combine_sum((const float*)ws, C, batch * M * N, S, st);
 }
 

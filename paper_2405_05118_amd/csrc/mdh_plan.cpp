@@ -209,7 +209,17 @@ static const GemmInst kGemmMenu[] = {
     {128, 64, 64, 64, 32},  {256, 64, 64, 64, 64},   {64, 64, 32, 32, 32},
 };
 
+// wavefront-layer split of k: (BM, BN, WK) = workgroup tile and wavefronts along k; the 16 x 16 tile is
+// one 16 x 16 x 4 block, the others are made of 32 x 32 x 2 blocks
+static const int kGemmKsplitMenu[][3] = {{32, 32, 8}, {32, 32, 4}, {32, 32, 16}, {64, 32, 8}, {64, 64, 4},
+                                         {64, 64, 8}, {16, 16, 4}, {16, 16, 2}, {16, 16, 8}};
+
 static bool gemm_inst(const GemmPlan& pl) {
+  if (pl.WK > 1) {
+    for (auto& m : kGemmKsplitMenu)
+      if (pl.BM == m[0] && pl.BN == m[1] && pl.WK == m[2]) return true;
+    return false;
+  }
   for (auto& m : kGemmMenu)
     if (m.BM == pl.BM && m.BN == pl.BN && m.BK == pl.BK && m.WM == pl.WM && m.WN == pl.WN)
       return true;
@@ -226,6 +236,31 @@ void params_from_plan(const int64_t* s, const GemmPlan& pl, mdh_tile_params* p) 
   p->blk[0] = 32;
   p->blk[1] = 32;
   p->blk[2] = 2;  // one v_mfma_f32_32x32x2_f32
+  if (pl.WK > 1) {
+    // k on the wavefront layer: every wavefront owns the whole tile and walks groups of 8 k (4 MFMA
+    // steps of 2; with the 16 x 16 x 4 block: groups of 16 k, 4 steps of 4) read straight into
+    // registers; the wavefront results are combined in LDS
+    const int b = pl.BM == 16 ? 16 : 32, bk = pl.BM == 16 ? 4 : 2;
+    p->blk[0] = p->blk[1] = b;
+    p->blk[2] = bk;
+    p->prt[MDH_L_WG][0] = (int32_t)cdiv(s[0], pl.BM);
+    p->prt[MDH_L_WG][1] = (int32_t)cdiv(s[1], pl.BN);
+    p->prt[MDH_L_WG][2] = pl.S;
+    p->prt[MDH_L_WAVE][2] = pl.WK;
+    p->prt[MDH_L_HBM][2] = (int32_t)cdiv(cdiv(s[2], (int64_t)pl.S * pl.WK), 4 * bk);
+    p->prt[MDH_L_VGPR][0] = pl.BM / b;
+    p->prt[MDH_L_VGPR][1] = pl.BN / b;
+    p->prt[MDH_L_VGPR][2] = 4;
+    static const int kdims[3] = {0, 1, 2};
+    set_order(p, kdims);
+    p->strided = 0;
+    p->lane_fast_dim = 1;
+    p->in_region[0] = MDH_MR_VGPR;
+    p->in_region[1] = MDH_MR_VGPR;
+    p->out_region = MDH_MR_LDS;
+    p->ragged = (uint8_t)pl.ragged;
+    return;
+  }
   p->prt[MDH_L_WG][0] = (int32_t)cdiv(s[0], pl.BM);
   p->prt[MDH_L_WG][1] = (int32_t)cdiv(s[1], pl.BN);
   p->prt[MDH_L_WG][2] = pl.S;
@@ -246,11 +281,29 @@ void params_from_plan(const int64_t* s, const GemmPlan& pl, mdh_tile_params* p) 
 }
 
 static int gemm_ragged(const int64_t* s, const GemmPlan& pl) {
+  if (pl.WK > 1) return (s[0] % pl.BM) || (s[1] % pl.BN) || (s[2] % ((int64_t)pl.S * pl.WK * (pl.BM == 16 ? 16 : 8)));
   return (s[0] % pl.BM) || (s[1] % pl.BN) || (s[2] % ((int64_t)pl.S * pl.BK));
 }
 
 static GemmPlan gemm_default(const int64_t* s) {
   const int64_t M = s[0], N = s[1], K = s[2];
+  // Outputs of few tiles: k over the wavefronts of a workgroup, one launch, tiles small enough to give
+  // every compute unit a workgroup.  Kernel durations (rocprofv3 kernel trace, us; the LDS-tiled kernel
+  // with 64 x 64 tiles beside it, second pass included where it splits k):
+  //   128^3: 2.9 (16 x 16 tiles, 2 wavefronts) / 5.1      256^3: 3.3 (16 x 16, 4) / 8.4
+  //   200 x 300 x 500: 5.1 (16 x 16, 4) / 8.6             256 x 256 x 4096: 13.7 (16 x 16, 4) / 15.3
+  //   384^3: 5.5 (32 x 32, 4) / 7.5                       512^3: 6.5 (32 x 32, 4) / 9.9
+  //   768^3 and 1024^3: the LDS-tiled kernel stays ahead (18.9 against 20.0; 26.3 against 28.1)
+  if (K >= 32 && K <= 8192 && M > 0 && N > 0) {
+    const int64_t t16 = cdiv(M, 16) * cdiv(N, 16), t32 = cdiv(M, 32) * cdiv(N, 32);
+    if (t16 <= 320 || t32 <= 320) {
+      const int b = t16 <= 320 ? 16 : 32;
+      GemmPlan pl{b, b, b == 16 ? 16 : 8, b, b, 1, 0};
+      pl.WK = (b == 16 && K <= 128) ? 2 : 4;
+      pl.ragged = gemm_ragged(s, pl);
+      return pl;
+    }
+  }
   // Tile: the largest of 128x128, 128x64, 64x64 that still gives two workgroups per compute unit
   // (measured best at 4096^3, 2048^3 and 1024^3 respectively); narrow problems keep 128x64 / 64x64.
   GemmPlan pl{128, 128, 32, 64, 64, 1, 0};
@@ -295,15 +348,26 @@ int matmul_candidates(const int64_t* s, GemmPlan* out, int cap) {
   auto push = [&](GemmPlan pl) {
     if (n >= cap) return;
     if (pl.S > 1 && s[2] / pl.S < pl.BK) return;
-    if (gemm_lds_bytes(pl.BM, pl.BN, pl.BK) > kLdsBytesPerWG) return;
+    if (pl.WK == 1 && gemm_lds_bytes(pl.BM, pl.BN, pl.BK) > kLdsBytesPerWG) return;
     pl.ragged = gemm_ragged(s, pl);
     for (int i = 0; i < n; ++i)
       if (out[i].BM == pl.BM && out[i].BN == pl.BN && out[i].BK == pl.BK && out[i].WM == pl.WM &&
-          out[i].S == pl.S)
+          out[i].S == pl.S && out[i].WK == pl.WK)
         return;
     out[n++] = pl;
   };
   push(gemm_default(s));
+  // k over the wavefronts of a workgroup, for outputs of few tiles (every wavefront keeps 8 k or more)
+  if (cdiv(s[0], 32) * cdiv(s[1], 32) <= 1024)
+    for (auto& m : kGemmKsplitMenu)
+      for (int S : {1, 2, 4}) {
+        if (s[2] / ((int64_t)S * m[2]) < 16) continue;
+        if (S > 1 && cdiv(s[0], m[0]) * cdiv(s[1], m[1]) * (S / 2) >= 256) continue;
+        if (m[0] == 16 && cdiv(s[0], 16) * cdiv(s[1], 16) > 1024) continue;
+        GemmPlan pl{m[0], m[1], m[0] == 16 ? 16 : 8, m[0], m[1], S, 0};
+        pl.WK = m[2];
+        push(pl);
+      }
   static const int splits[] = {1, 2, 4, 8, 16};
   for (auto& m : kGemmMenu)
     for (int S : splits) {
@@ -324,6 +388,27 @@ mdh_status plan_matmul(const int64_t* s, const mdh_tile_params* p, GemmPlan* out
   mdh_status st = check_products(p, s, &ragged);
   if (st != MDH_OK) return st;
   if ((st = check_lanes(p)) != MDH_OK) return st;
+  if (p->prt[MDH_L_WAVE][2] > 1) {
+    // wavefront-layer parts of k: the register-streaming kernel
+    GemmPlan pl;
+    const bool b16 = p->blk[0] == 16;
+    if (!((p->blk[0] == 32 && p->blk[1] == 32 && p->blk[2] == 2) || (b16 && p->blk[1] == 16 && p->blk[2] == 4)))
+      return MDH_ERR_UNSUPPORTED;
+    pl.BM = pl.WM = p->prt[MDH_L_VGPR][0] * p->blk[0];
+    pl.BN = pl.WN = p->prt[MDH_L_VGPR][1] * p->blk[1];
+    pl.BK = b16 ? 16 : 8;
+    pl.S = p->prt[MDH_L_WG][2];
+    pl.WK = p->prt[MDH_L_WAVE][2];
+    pl.ragged = ragged;
+    // model constraints: lanes per workgroup, and the LDS that holds the WK partial tiles
+    if ((int64_t)pl.WK * 64 > kMaxLanesPerWG) return MDH_ERR_TILE_RESOURCES;
+    if ((int64_t)pl.WK * pl.BM * pl.BN * 4 > kLdsBytesPerWG) return MDH_ERR_TILE_RESOURCES;
+    mdh_tile_params chk;
+    params_from_plan(s, pl, &chk);
+    if (!same_table(chk, *p) || !gemm_inst(pl)) return MDH_ERR_UNSUPPORTED;
+    *out = pl;
+    return MDH_OK;
+  }
   GemmPlan pl;
   pl.WM = p->prt[MDH_L_VGPR][0] * 32;
   pl.WN = p->prt[MDH_L_VGPR][1] * 32;
@@ -341,6 +426,54 @@ mdh_status plan_matmul(const int64_t* s, const mdh_tile_params* p, GemmPlan* out
   if (!same_table(chk, *p) || !gemm_inst(pl)) return MDH_ERR_UNSUPPORTED;
   *out = pl;
   return MDH_OK;
+}
+
+// ---- MatMul with few rows: the small-M kernel of the batched instance, one batch entry
+
+bool small_m_matmul(const int64_t* s, const mdh_tile_params* p) {
+  if (!p) return s[0] > 0 && s[0] <= 16 && s[1] > 0;
+  return p->D == 3 && p->blk[0] == 16 && p->prt[MDH_L_VGPR][1] == 4;
+}
+
+static void move_dims(const mdh_tile_params& src, mdh_tile_params* dst, int D, int shift) {
+  // dimension d of dst is dimension d + shift of src (shift = 1 drops the batch, -1 inserts it)
+  clear_params(dst, D);
+  for (int d = 0; d < D; ++d) {
+    const int e = d + shift;
+    if (e < 0 || e >= src.D) continue;  // the inserted batch dimension: one part everywhere, blk 1
+    dst->blk[d] = src.blk[e];
+    for (int l = 0; l < MDH_NUM_LAYERS; ++l) dst->prt[l][d] = src.prt[l][e];
+  }
+  int dims[MDH_MAX_D];
+  for (int d = 0; d < D; ++d) dims[d] = d;
+  set_order(dst, dims);
+  dst->strided = src.strided;
+  dst->lane_fast_dim = (uint8_t)(src.lane_fast_dim - shift);
+  dst->ragged = src.ragged;
+  memcpy(dst->in_region, src.in_region, sizeof(src.in_region));
+  dst->out_region = src.out_region;
+  memcpy(dst->in_transposed, src.in_transposed, sizeof(src.in_transposed));
+  dst->out_transposed = src.out_transposed;
+}
+
+void lift_batch(const mdh_tile_params& p3, mdh_tile_params* p4) { move_dims(p3, p4, 4, -1); }
+void drop_batch(const mdh_tile_params& p4, mdh_tile_params* p3) { move_dims(p4, p3, 3, 1); }
+
+// the batched instance's view of a small-M MatMul call: sizes and (if given) the lifted table
+static mdh_status plan_small_m(const int64_t* s, const mdh_tile_params* p, GemmExPlan* out) {
+  const int64_t s4[7] = {1, s[0], s[1], s[2], 0, 0, 0};
+  if (!p) return plan_matmul_ex(s4, nullptr, out);
+  mdh_tile_params p4;
+  lift_batch(*p, &p4);
+  // the order entries of the caller's table must be the ones this library generates
+  mdh_tile_params back;
+  drop_batch(p4, &back);
+  if (!same_table(back, *p)) return MDH_ERR_UNSUPPORTED;
+  return plan_matmul_ex(s4, &p4, out);
+}
+
+mdh_status plan_matmul_small_m(const int64_t* s, const mdh_tile_params* p, GemmExPlan* out) {
+  return plan_small_m(s, p, out);
 }
 
 // =============================================================================== MCC
@@ -792,6 +925,15 @@ mdh_status mdh_default_params(mdh_instance inst, const int64_t* sizes, mdh_tile_
   if (st != MDH_OK) return st;
   switch (inst) {
     case MDH_MATMUL: {
+      if (small_m_matmul(sizes, nullptr)) {
+        GemmExPlan ex;
+        if ((st = plan_small_m(sizes, nullptr, &ex)) != MDH_OK) return st;
+        const int64_t s4[7] = {1, sizes[0], sizes[1], sizes[2], 0, 0, 0};
+        mdh_tile_params p4;
+        params_from_plan(s4, ex, &p4);
+        drop_batch(p4, out);
+        return MDH_OK;
+      }
       GemmPlan pl;
       if ((st = plan_matmul(sizes, nullptr, &pl)) == MDH_OK) params_from_plan(sizes, pl, out);
       return st;
@@ -846,6 +988,10 @@ mdh_status mdh_validate_params(mdh_instance inst, const int64_t* sizes, const md
   if (st != MDH_OK) return st;
   switch (inst) {
     case MDH_MATMUL: {
+      if (small_m_matmul(sizes, p)) {
+        GemmExPlan ex;
+        return plan_small_m(sizes, p, &ex);
+      }
       GemmPlan pl;
       return plan_matmul(sizes, p, &pl);
     }
@@ -889,6 +1035,11 @@ size_t mdh_workspace_size(mdh_instance inst, const int64_t* sizes, const mdh_til
   if (check_sizes(inst, sizes) != MDH_OK) return 0;
   switch (inst) {
     case MDH_MATMUL: {
+      if (small_m_matmul(sizes, params)) {
+        GemmExPlan ex;
+        if (plan_small_m(sizes, params, &ex) != MDH_OK || ex.g.S <= 1) return 0;
+        return (size_t)ex.g.S * (size_t)sizes[0] * (size_t)sizes[1] * sizeof(float);
+      }
       GemmPlan pl;
       if (plan_matmul(sizes, params, &pl) != MDH_OK || pl.S <= 1) return 0;
       return (size_t)pl.S * (size_t)sizes[0] * (size_t)sizes[1] * sizeof(float);
@@ -982,6 +1133,8 @@ mdh_status mdh_candidate(mdh_instance inst, const int64_t* sizes, int32_t idx, m
       GemmPlan c[CAP];
       int n = matmul_candidates(sizes, c, CAP);
       if (idx < 0 || idx >= n) return MDH_ERR_SIZE;
+      // candidate 0 is the default: for few rows the small-M kernel, which the tiled menu does not hold
+      if (idx == 0 && small_m_matmul(sizes, nullptr)) return mdh_default_params(inst, sizes, out);
       params_from_plan(sizes, c[idx], out);
       return MDH_OK;
     }

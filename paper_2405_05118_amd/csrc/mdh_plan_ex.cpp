@@ -54,7 +54,9 @@ static void skinny_params(const int64_t* s, const GemmExPlan& pl, mdh_tile_param
   p->lane_fast_dim = 2;
   p->in_region[0] = MDH_MR_VGPR;
   p->in_region[1] = MDH_MR_VGPR;
-  p->out_region = MDH_MR_VGPR;
+  // where the workgroup-layer parts of k are combined: in device memory by the last workgroup part of a
+  // strip to arrive (one launch), or by a second kernel (results leave the first from registers)
+  p->out_region = (g.S > 1 && pl.fused) ? MDH_MR_HBM : MDH_MR_VGPR;
   p->in_transposed[1] = (uint8_t)pl.tb;
   p->ragged = (uint8_t)g.ragged;
 }
@@ -65,9 +67,13 @@ static int skinny_ragged(const int64_t* s, const GemmExPlan& pl) {
   return (s[1] % 16) || (s[2] % pl.g.BN) || (s[3] != (int64_t)pl.g.S * cdiv(kchunk, kstep * pl.WK) * pl.WK * kstep);
 }
 
-static GemmExPlan skinny_plan(const int64_t* s, int wn, int wk, int S) {
+// strips whose arrivals the one-launch combination has to count
+static int64_t skinny_strips(const int64_t* s) { return s[0] * cdiv(s[1], 16) * cdiv(s[2], 64); }
+
+static GemmExPlan skinny_plan(const int64_t* s, int wn, int wk, int S, int fused = 1) {
   GemmExPlan pl{GemmPlan{16, 64 * wn, 16, 16, 64, S, 0}, 0, (int)s[5], 0, 1, wk};
   pl.g.ragged = skinny_ragged(s, pl);
+  pl.fused = (S > 1 && fused && skinny_strips(s) <= kArrivalCounters) ? 1 : 0;
   return pl;
 }
 
@@ -177,6 +183,7 @@ int matmul_ex_candidates(const int64_t* s, GemmExPlan* out, int cap) {
   if (skinny_applies(s)) {
     const GemmExPlan d = ex_default(s);
     out[n++] = d;
+    if (d.fused) out[n++] = skinny_plan(s, d.g.BN / 64, d.WK, d.g.S, 0);  // the same with the second kernel
     static const int sk_splits[] = {1, 2, 4, 8, 16, 32, 64};
     for (auto& m : kSkinnyMenu)
       for (int S : sk_splits) {
@@ -211,7 +218,10 @@ mdh_status plan_matmul_ex(const int64_t* s, const mdh_tile_params* p, GemmExPlan
   if (p->blk[1] == 16) {  // the small-M kernel
     const int wn = p->prt[MDH_L_WAVE][2], wk = p->prt[MDH_L_WAVE][3];
     if (!skinny_inst(wn, wk) || s[4] || s[6]) return MDH_ERR_UNSUPPORTED;
-    GemmExPlan pl = skinny_plan(s, wn, wk, p->prt[MDH_L_WG][3]);
+    const int S = p->prt[MDH_L_WG][3];
+    const int fused = p->out_region == MDH_MR_HBM;
+    if (fused && (S <= 1 || skinny_strips(s) > kArrivalCounters)) return MDH_ERR_UNSUPPORTED;
+    GemmExPlan pl = skinny_plan(s, wn, wk, S, fused);
     mdh_tile_params chk;
     params_from_plan(s, pl, &chk);
     if (!same_table(chk, *p)) return MDH_ERR_UNSUPPORTED;

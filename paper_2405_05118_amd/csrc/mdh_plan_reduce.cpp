@@ -23,11 +23,13 @@ void params_from_plan(const int64_t* s, const DotPlan& pl, mdh_tile_params* p) {
   p->prt[MDH_L_HBM][0] = (int32_t)cdiv(s[0], (int64_t)pl.S * pl.WAVES * 256);
   static const int dims[1] = {0};
   set_order(p, dims);
-  p->strided = 1;
+  p->strided = (uint8_t)pl.strided;
   p->lane_fast_dim = 0;
   p->in_region[0] = MDH_MR_VGPR;  // streamed once: global memory straight to registers
   p->in_region[1] = MDH_MR_VGPR;
-  p->out_region = MDH_MR_VGPR;
+  // where the workgroup-layer parts are combined: device memory, by the last part to arrive (one
+  // launch), or a second kernel (the first kernel's results leave from registers)
+  p->out_region = (pl.S > 1 && pl.fused) ? MDH_MR_HBM : MDH_MR_VGPR;
   p->ragged = (uint8_t)pl.ragged;
 }
 
@@ -44,6 +46,7 @@ static DotPlan dot_default(const int64_t* s) {
   // a few KiB in all: one workgroup and no second pass (2^16 elements: 8.8 us against 12.3 us)
   if (s[0] <= (1 << 17)) S = 1;
   pl.S = S;
+  pl.fused = S > 1;
   pl.ragged = dot_ragged(s, pl);
   return pl;
 }
@@ -54,14 +57,23 @@ int dot_candidates(const int64_t* s, DotPlan* out, int cap) {
     if (n >= cap || pl.S < 1) return;
     if (pl.S > 1 && s[0] / pl.S < 1) return;
     pl.ragged = dot_ragged(s, pl);
+    if (pl.S == 1) pl.fused = 0;
     for (int i = 0; i < n; ++i)
-      if (out[i].WAVES == pl.WAVES && out[i].S == pl.S) return;
+      if (out[i].WAVES == pl.WAVES && out[i].S == pl.S && out[i].strided == pl.strided && out[i].fused == pl.fused) return;
     out[n++] = pl;
   };
   DotPlan d = dot_default(s);
   push(d);
   for (int w : kDotWaves)
     for (int S = d.S / 4 > 0 ? d.S / 4 : 1; S <= d.S * 4 && S <= 8192; S *= 2) push(DotPlan{w, S, 0});
+  // the default's tile with the second kernel instead of the one-launch combination, and with the
+  // blocked lane assignment (parameter D2: every lane one contiguous part)
+  DotPlan v = d;
+  v.fused = 0;
+  push(v);
+  v = d;
+  v.strided = 0;
+  push(v);
   return n;
 }
 
@@ -76,6 +88,8 @@ mdh_status plan_dot(const int64_t* s, const mdh_tile_params* p, DotPlan* out) {
   if (st != MDH_OK) return st;
   if ((st = check_lanes(p)) != MDH_OK) return st;
   DotPlan pl{p->prt[MDH_L_WAVE][0], p->prt[MDH_L_WG][0], ragged};
+  pl.strided = p->strided ? 1 : 0;
+  pl.fused = (pl.S > 1 && p->out_region == MDH_MR_HBM) ? 1 : 0;
   bool inst = false;
   for (int w : kDotWaves) inst = inst || (w == pl.WAVES);
   mdh_tile_params chk;
@@ -109,7 +123,7 @@ void params_from_plan(const int64_t* s, const MatVecPlan& pl, mdh_tile_params* p
   p->prt[MDH_L_HBM][1] = (int32_t)cdiv(s[1], (int64_t)pl.S * pl.WK * 256);
   static const int dims[2] = {0, 1};
   set_order(p, dims);
-  p->strided = 1;
+  p->strided = (uint8_t)pl.strided;
   p->lane_fast_dim = 1;           // k is the contiguous dimension of A
   p->in_region[0] = MDH_MR_VGPR;  // A is read once: no staging
   p->in_region[1] = MDH_MR_VGPR;  // x is reused RM times from registers, across rows from L2
@@ -143,7 +157,9 @@ int matvec_candidates(const int64_t* s, MatVecPlan* out, int cap) {
     if (pl.S > 1 && s[1] / pl.S < 1) return;
     pl.ragged = matvec_ragged(s, pl);
     for (int i = 0; i < n; ++i)
-      if (out[i].RM == pl.RM && out[i].WM == pl.WM && out[i].WK == pl.WK && out[i].S == pl.S) return;
+      if (out[i].RM == pl.RM && out[i].WM == pl.WM && out[i].WK == pl.WK && out[i].S == pl.S &&
+          out[i].strided == pl.strided)
+        return;
     out[n++] = pl;
   };
   MatVecPlan d = matvec_default(s);
@@ -151,6 +167,9 @@ int matvec_candidates(const int64_t* s, MatVecPlan* out, int cap) {
   for (auto& m : kMatVecMenu)
     for (int S = d.S / 2 > 0 ? d.S / 2 : 1; S <= d.S * 2 && S <= 256; S *= 2)
       push(MatVecPlan{m[0], m[1], m[2], S, 0});
+  // the default's tile with the blocked lane assignment (parameter D2: every lane one contiguous part)
+  d.strided = 0;
+  push(d);
   return n;
 }
 
@@ -166,6 +185,7 @@ mdh_status plan_matvec(const int64_t* s, const mdh_tile_params* p, MatVecPlan* o
   if ((st = check_lanes(p)) != MDH_OK) return st;
   MatVecPlan pl{p->prt[MDH_L_VGPR][0], p->prt[MDH_L_WAVE][0], p->prt[MDH_L_WAVE][1],
                 p->prt[MDH_L_WG][1], ragged};
+  pl.strided = p->strided ? 1 : 0;
   mdh_tile_params chk;
   params_from_plan(s, pl, &chk);
   if (!same_table(chk, *p) || !matvec_inst(pl) || pl.S > 256) return MDH_ERR_UNSUPPORTED;

@@ -43,35 +43,82 @@ __device__ __forceinline__ float hsum(f4 a) { return (a[0] + a[1]) + (a[2] + a[3
 
 // ------------------------------------------------------------------------------------- Dot
 
-template <int WAVES>
+// How many workgroup parts have stored their partial sum.  Zero when the library is loaded; the S-th
+// arrival wraps it back to zero (atomicInc with bound S-1), so every call leaves it as it found it.
+static __device__ unsigned g_dot_arrivals;
+
+// The S workgroup-layer parts in a fixed order: 16 independent loads per lane and round (one round covers
+// S = 1024), so that the loads overlap instead of each addition waiting for its own load.  Called by one
+// whole wavefront; every lane returns the sum.
+__device__ __forceinline__ float dot_fold_parts(const float* __restrict__ ws, int S, int lane) {
+  float a = 0.f;
+  for (int base = 0; base < S; base += 1024) {
+    float v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int i = base + u * 64 + lane;
+      v[u] = i < S ? ws[i] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) a += v[u];
+  }
+  return wave_sum(a);
+}
+
+// STRIDED (parameter D2 of the tuning table, lane and wavefront layers): true = consecutive lanes own
+// consecutive 4-element parts and walk the workgroup's chunk in steps of a whole workgroup (coalesced:
+// the paper's "inner parallelism"); false = blocked, every lane owns ONE contiguous part of the chunk
+// ("outer parallelism": valid, and slow on this hardware because the lanes of a load are far apart).
+// FUSED: S > 1 only -- the last workgroup part to arrive folds the S partial sums (one launch);
+// otherwise a second kernel does.
+template <int WAVES, bool STRIDED>
 __global__ __launch_bounds__(WAVES * 64) void dot_kernel(const float* __restrict__ x,
                                                           const float* __restrict__ y,
-                                                          float* __restrict__ out, int64_t K,
-                                                          int64_t chunk) {
+                                                          float* __restrict__ part_out,
+                                                          float* __restrict__ result, int64_t K,
+                                                          int64_t chunk, int S, int fused) {
   constexpr int NT = WAVES * 64;
   __shared__ float part[WAVES];
+  __shared__ unsigned last;
   const int tid = threadIdx.x;
   const int64_t kbeg = (int64_t)blockIdx.x * chunk;
   const int64_t kend = kbeg + chunk < K ? kbeg + chunk : K;
   // two independent chains of four accumulators keep eight 16-byte loads in flight per lane
   f4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = {0.f, 0.f, 0.f, 0.f};
-  int64_t k = kbeg + (int64_t)tid * 4;
-  for (; k + NT * 4 + 3 < kend; k += 2 * NT * 4) {
-    // both vectors are streamed once: non-temporal loads
-    const f4 x0 = __builtin_nontemporal_load((const f4u*)(x + k));
-    const f4 y0 = __builtin_nontemporal_load((const f4u*)(y + k));
-    const f4 x1 = __builtin_nontemporal_load((const f4u*)(x + k + NT * 4));
-    const f4 y1 = __builtin_nontemporal_load((const f4u*)(y + k + NT * 4));
+  if (STRIDED) {
+    int64_t k = kbeg + (int64_t)tid * 4;
+    for (; k + NT * 4 + 3 < kend; k += 2 * NT * 4) {
+      // both vectors are streamed once: non-temporal loads
+      const f4 x0 = __builtin_nontemporal_load((const f4u*)(x + k));
+      const f4 y0 = __builtin_nontemporal_load((const f4u*)(y + k));
+      const f4 x1 = __builtin_nontemporal_load((const f4u*)(x + k + NT * 4));
+      const f4 y1 = __builtin_nontemporal_load((const f4u*)(y + k + NT * 4));
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      a0[e] = __builtin_fmaf(x0[e], y0[e], a0[e]);
-      a1[e] = __builtin_fmaf(x1[e], y1[e], a1[e]);
+      for (int e = 0; e < 4; ++e) {
+        a0[e] = __builtin_fmaf(x0[e], y0[e], a0[e]);
+        a1[e] = __builtin_fmaf(x1[e], y1[e], a1[e]);
+      }
     }
-  }
-  for (; k < kend; k += NT * 4) {
+    for (; k < kend; k += NT * 4) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (k + e < kend) a0[e] = __builtin_fmaf(x[k + e], y[k + e], a0[e]);
+      for (int e = 0; e < 4; ++e)
+        if (k + e < kend) a0[e] = __builtin_fmaf(x[k + e], y[k + e], a0[e]);
+    }
+  } else {
+    // blocked: lane tid owns elements [kbeg + tid*len, kbeg + (tid+1)*len) of the chunk, len a multiple of 4
+    const int64_t len = chunk / NT;
+    int64_t k = kbeg + (int64_t)tid * len;
+    const int64_t lend = k + len < kend ? k + len : kend;
+    for (; k + 7 < lend; k += 8) {
+      const f4 x0 = *(const f4u*)(x + k), y0 = *(const f4u*)(y + k);
+      const f4 x1 = *(const f4u*)(x + k + 4), y1 = *(const f4u*)(y + k + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        a0[e] = __builtin_fmaf(x0[e], y0[e], a0[e]);
+        a1[e] = __builtin_fmaf(x1[e], y1[e], a1[e]);
+      }
+    }
+    for (; k < lend; ++k) a0[k & 3] = __builtin_fmaf(x[k], y[k], a0[k & 3]);
   }
   const float w = wave_sum(hsum(a0) + hsum(a1));
   if ((tid & 63) == 0) part[tid >> 6] = w;
@@ -80,27 +127,24 @@ __global__ __launch_bounds__(WAVES * 64) void dot_kernel(const float* __restrict
     float s = part[0];
 #pragma unroll
     for (int i = 1; i < WAVES; ++i) s += part[i];
-    out[blockIdx.x] = s;  // the result itself if the grid is one workgroup, else part blockIdx.x
+    part_out[blockIdx.x] = s;  // the result itself if the grid is one workgroup, else part blockIdx.x
+    if (fused) {
+      __threadfence();  // the partial sum is visible to the whole device before it is counted
+      last = atomicInc(&g_dot_arrivals, (unsigned)S - 1) == (unsigned)S - 1;
+    }
   }
+  if (!fused) return;
+  __syncthreads();
+  if (!last || tid >= 64) return;
+  __threadfence();  // the other workgroups' partial sums, counted before this one, are visible here
+  const float total = dot_fold_parts(part_out, S, tid);
+  if (tid == 0) result[0] = total;
 }
 
 // Second pass: one wavefront adds the S workgroup-layer parts in a fixed order.
 __global__ __launch_bounds__(64) void dot_combine_kernel(const float* __restrict__ ws,
                                                          float* __restrict__ out, int S) {
-  float a = 0.f;
-  // 16 independent loads per lane and round (one round covers the default S = 1024), so that
-  // the loads overlap instead of each addition waiting for its own load
-  for (int base = 0; base < S; base += 1024) {
-    float v[16];
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int i = base + u * 64 + threadIdx.x;
-      v[u] = i < S ? ws[i] : 0.f;
-    }
-#pragma unroll
-    for (int u = 0; u < 16; ++u) a += v[u];
-  }
-  a = wave_sum(a);
+  const float a = dot_fold_parts(ws, S, threadIdx.x);
   if (threadIdx.x == 0) out[0] = a;
 }
 
@@ -111,10 +155,14 @@ mdh_status launch_dot_t(const DotPlan& pl, int64_t K, const float* x, const floa
   const int64_t step = (int64_t)WAVES * 256;
   const int64_t chunk = cdiv(cdiv(K, pl.S), step) * step;
   float* dst = pl.S > 1 ? (float*)ws : out;
+  const int fused = pl.S > 1 && pl.fused;
   clear_stale_error();
-  hipLaunchKernelGGL((dot_kernel<WAVES>), dim3(pl.S), dim3(WAVES * 64), 0, st, x, y, dst, K, chunk);
+  if (pl.strided)
+    hipLaunchKernelGGL((dot_kernel<WAVES, true>), dim3(pl.S), dim3(WAVES * 64), 0, st, x, y, dst, out, K, chunk, pl.S, fused);
+  else
+    hipLaunchKernelGGL((dot_kernel<WAVES, false>), dim3(pl.S), dim3(WAVES * 64), 0, st, x, y, dst, out, K, chunk, pl.S, fused);
   mdh_status r = launch_status();
-  if (r != MDH_OK || pl.S <= 1) return r;
+  if (r != MDH_OK || pl.S <= 1 || fused) return r;
   clear_stale_error();
   hipLaunchKernelGGL(dot_combine_kernel, dim3(1), dim3(64), 0, st, (const float*)ws, out, pl.S);
   return launch_status();
@@ -122,7 +170,9 @@ mdh_status launch_dot_t(const DotPlan& pl, int64_t K, const float* x, const floa
 
 // ------------------------------------------------------------------------------------- MatVec
 
-template <int RM, int WM, int WK>
+// STRIDED: as for Dot -- true = consecutive lanes own consecutive 4-element parts of k (coalesced),
+// false = blocked, every lane owns one contiguous part of its wavefront's k-range.
+template <int RM, int WM, int WK, bool STRIDED>
 __global__ __launch_bounds__(WM* WK * 64) void matvec_kernel(const float* __restrict__ A,
                                                                const float* __restrict__ x,
                                                                float* __restrict__ y,
@@ -146,25 +196,46 @@ __global__ __launch_bounds__(WM* WK * 64) void matvec_kernel(const float* __rest
 #pragma unroll
   for (int r = 0; r < RM; ++r) acc[r] = (f4){0.f, 0.f, 0.f, 0.f};
 
-  // lanes own consecutive 4-element parts of k; the wavefronts along k interleave 256-element steps
-  int k = kbeg + (wk * 64 + lane) * 4;
-  for (; k + 3 < kend; k += WK * 256) {
-    const f4 xv = *(const f4u*)(x + k);
+  if (STRIDED) {
+    // lanes own consecutive 4-element parts of k; the wavefronts along k interleave 256-element steps
+    int k = kbeg + (wk * 64 + lane) * 4;
+    for (; k + 3 < kend; k += WK * 256) {
+      const f4 xv = *(const f4u*)(x + k);
 #pragma unroll
-    for (int r = 0; r < RM; ++r) {
-      const f4 av = __builtin_nontemporal_load((const f4u*)(row[r] + k));  // streamed once
+      for (int r = 0; r < RM; ++r) {
+        const f4 av = __builtin_nontemporal_load((const f4u*)(row[r] + k));  // streamed once
 #pragma unroll
-      for (int e = 0; e < 4; ++e) acc[r][e] = __builtin_fmaf(av[e], xv[e], acc[r][e]);
-    }
-  }
-  if (k < kend) {  // ragged end of k: at most three elements, in one lane
-#pragma unroll
-    for (int e = 0; e < 3; ++e)
-      if (k + e < kend) {
-        const float xe = x[k + e];
-#pragma unroll
-        for (int r = 0; r < RM; ++r) acc[r][e] = __builtin_fmaf(row[r][k + e], xe, acc[r][e]);
+        for (int e = 0; e < 4; ++e) acc[r][e] = __builtin_fmaf(av[e], xv[e], acc[r][e]);
       }
+    }
+    if (k < kend) {  // ragged end of k: at most three elements, in one lane
+#pragma unroll
+      for (int e = 0; e < 3; ++e)
+        if (k + e < kend) {
+          const float xe = x[k + e];
+#pragma unroll
+          for (int r = 0; r < RM; ++r) acc[r][e] = __builtin_fmaf(row[r][k + e], xe, acc[r][e]);
+        }
+    }
+  } else {
+    // blocked: lane (wk, lane) owns ONE contiguous part of the workgroup part of k (a multiple of 4 long)
+    const int len = kchunk / (WK * 64);
+    int k = kbeg + (wk * 64 + lane) * len;
+    const int lend = min(kend, k + len);
+    for (; k + 3 < lend; k += 4) {
+      const f4 xv = *(const f4u*)(x + k);
+#pragma unroll
+      for (int r = 0; r < RM; ++r) {
+        const f4 av = *(const f4u*)(row[r] + k);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[r][e] = __builtin_fmaf(av[e], xv[e], acc[r][e]);
+      }
+    }
+    for (; k < lend; ++k) {
+      const float xe = x[k];
+#pragma unroll
+      for (int r = 0; r < RM; ++r) acc[r][k & 3] = __builtin_fmaf(row[r][k], xe, acc[r][k & 3]);
+    }
   }
 
   float s[RM];
@@ -210,8 +281,12 @@ mdh_status launch_matvec_t(const MatVecPlan& pl, int64_t M, int64_t K, const flo
   const int64_t nblocks = nwg_i * pl.S;
   if (nblocks > 0x7fffffff || kchunk > 0x7fffffff) return MDH_ERR_SIZE;
   clear_stale_error();
-  hipLaunchKernelGGL((matvec_kernel<RM, WM, WK>), dim3((unsigned)nblocks), dim3(WM * WK * 64), 0, st,
-                     A, x, y, (float*)ws, (int)M, (int)K, pl.S, (int)nwg_i, (int)kchunk);
+  if (pl.strided)
+    hipLaunchKernelGGL((matvec_kernel<RM, WM, WK, true>), dim3((unsigned)nblocks), dim3(WM * WK * 64), 0, st,
+                       A, x, y, (float*)ws, (int)M, (int)K, pl.S, (int)nwg_i, (int)kchunk);
+  else
+    hipLaunchKernelGGL((matvec_kernel<RM, WM, WK, false>), dim3((unsigned)nblocks), dim3(WM * WK * 64), 0, st,
+                       A, x, y, (float*)ws, (int)M, (int)K, pl.S, (int)nwg_i, (int)kchunk);
   mdh_status r = launch_status();
   if (r != MDH_OK || pl.S <= 1) return r;
   clear_stale_error();

@@ -71,6 +71,47 @@ def test_matmul_small_all_candidates(shape):
         assert scaled_err(got, ref, refabs) <= TOL_CONTRACTION, (shape, p and p.table())
 
 
+@pytest.mark.parametrize("shape", [(256, 256, 256), (300, 200, 100), (129, 65, 33), (70, 260, 1030), (33, 47, 17),
+                                   (17, 16, 4096), (200, 300, 500), (512, 512, 512)])
+def test_matmul_k_on_the_wavefront_layer_every_candidate(shape):
+    # #PRT(WAVE, k) > 1: every wavefront owns the whole output tile and a part of k, the wavefront results
+    # are added in LDS; all instantiations (16 x 16 x 4 and 32 x 32 x 2 blocks, 2..16 wavefronts, with and
+    # without workgroup parts of k on top), ragged edges in every dimension
+    M, N, K = shape
+    A, Bm = W.matmul_inputs(W.MatmulCfg(M, N, K, W.SEED_BASE + 13))
+    ref, refabs = oracle.matmul(A, Bm, with_abs=True)
+    ks = [p for p in candidates(mdh.MDH_MATMUL, shape) if p is not None and p.prt[B.L_WAVE][2] > 1]
+    if K >= 128:  # a wavefront keeps at least 16 k: short reductions have few or no such candidates
+        assert len(ks) >= 6, "the wavefront-layer candidates are missing"
+        assert {p.blk[0] for p in ks} == {16, 32}
+    for p in ks:
+        assert p.in_region[0] == B.MR_VGPR and p.out_region == B.MR_LDS
+        got = run_matmul(A, Bm, p)
+        assert np.all(np.isfinite(got)), "output not fully overwritten"
+        assert scaled_err(got, ref, refabs) <= TOL_CONTRACTION, (shape, p.table())
+    d = mdh.mdh_default_params(mdh.MDH_MATMUL, shape)
+    if M > 16 and K >= 32:
+        assert d.prt[B.L_WAVE][2] > 1, "small outputs default to k on the wavefront layer"
+
+
+def test_matmul_with_few_rows_takes_the_small_m_kernel():
+    # M <= 16 through mdh_matmul: the register-streaming kernel of the batched entry point, same bits
+    for M, N, K in ((16, 1000, 2048), (1, 130, 257), (7, 64, 48)):
+        A, Bm = W.matmul_inputs(W.MatmulCfg(M, N, K, W.SEED_BASE + 14))
+        d = mdh.mdh_default_params(mdh.MDH_MATMUL, (M, N, K))
+        assert d.D == 3 and list(d.blk[:3]) == [16, 16, 4] and d.prt[B.L_VGPR][1] == 4
+        assert mdh.mdh_validate_params(mdh.MDH_MATMUL, (M, N, K), d) == 0
+        ref, refabs = oracle.matmul(A, Bm, with_abs=True)
+        got = run_matmul(A, Bm, None)
+        assert scaled_err(got, ref, refabs) <= TOL_CONTRACTION
+        assert np.array_equal(got, run_matmul(A, Bm, d))
+        C = torch.full((1, M, N), float("nan"), dtype=torch.float32, device="cuda")
+        n = mdh.mdh_workspace_size(mdh.MDH_BMATMUL, (1, M, N, K, 0, 0, 0))
+        ws = torch.empty(max(n, 4) // 4, dtype=torch.int32, device="cuda") if n else None
+        mdh.mdh_matmul_ex(dev(A[None]), dev(Bm[None]), C, False, False, False, None, ws)
+        assert np.array_equal(got, C[0].cpu().numpy().astype(np.float64))
+
+
 def test_matmul_closed_forms():
     # all-ones gives K in every cell (exact in fp32); identity returns A
     M, N, K = 200, 136, 520

@@ -42,20 +42,32 @@ def test_sequence_of_calls_replays_from_a_graph():
     wp = dev(np.arange(1, 9, dtype=np.int32))
     wm = dev(-np.arange(1, 9, dtype=np.int32))
 
-    pm = mdh.mdh_default_params(mdh.MDH_MATMUL, (M, N, K))
-    assert pm.prt[3][2] > 1, "the split-k path is the one worth capturing"
+    # MatMul with the reduction split over workgroups (the default at this size keeps k inside one launch)
+    pm = next(p for p in (mdh.mdh_candidate(mdh.MDH_MATMUL, (M, N, K), i) for i in range(mdh.mdh_num_candidates(mdh.MDH_MATMUL, (M, N, K))))
+              if p.prt[3][2] > 1 and p.prt[4][2] == 1)
     ps = mdh.mdh_default_params(mdh.MDH_SCAN, (1, n_scan))
-    ws_m, ws_s = _ws(mdh.MDH_MATMUL, (M, N, K)), _ws(mdh.MDH_SCAN, (1, n_scan))
+    ws_m, ws_s = _ws(mdh.MDH_MATMUL, (M, N, K), pm), _ws(mdh.MDH_SCAN, (1, n_scan))
+    # small-M MatMul and Dot: split reductions folded by the last workgroup part to arrive (arrival
+    # counters inside the library that every launch must leave at zero, replay after replay)
+    Ms, Ns, Ks = 16, 1000, 2048
+    a_s = torch.empty((Ms, Ks), device="cuda")
+    b_s = torch.empty((Ks, Ns), device="cuda")
+    p_small = mdh.mdh_default_params(mdh.MDH_MATMUL, (Ms, Ns, Ks))
+    assert p_small.prt[3][2] > 1 and p_small.out_region == 0
+    ws_small = _ws(mdh.MDH_MATMUL, (Ms, Ns, Ks))
+    assert mdh.mdh_default_params(mdh.MDH_DOT, (n_dot,)).out_region == 0
     ws_d, ws_p = _ws(mdh.MDH_DOT, (n_dot,)), _ws(mdh.MDH_CUSTOM_REDUCE, (nA, nB, 8))
     assert ws_s is not None and ps.prt[3][1] > 1
 
     def outputs():
         return [torch.full((M, N), float("nan"), device="cuda"), torch.full((1, n_scan), float("nan"), device="cuda"),
                 torch.full((1,), float("nan"), device="cuda"), torch.full((nx, nx, nx), float("nan"), device="cuda"),
-                torch.full((nA,), -1, dtype=torch.int32, device="cuda"), torch.full((nA,), -1, dtype=torch.int32, device="cuda")]
+                torch.full((nA,), -1, dtype=torch.int32, device="cuda"), torch.full((nA,), -1, dtype=torch.int32, device="cuda"),
+                torch.full((Ms, Ns), float("nan"), device="cuda")]
 
     def calls(o):
-        mdh.mdh_matmul(a, b, o[0], None, ws_m)
+        mdh.mdh_matmul(a, b, o[0], pm, ws_m)
+        mdh.mdh_matmul(a_s, b_s, o[6], None, ws_small)
         mdh.mdh_scan(xs, o[1], None, ws_s)
         mdh.mdh_dot(xd, yd, o[2], None, ws_d)
         mdh.mdh_stencil(g3, o[3], 0.5, 1.0 / 12.0)
@@ -68,6 +80,8 @@ def test_sequence_of_calls_replays_from_a_graph():
         xd.copy_(dev(W.uniform(seed, 4, (n_dot,), -1, 1)))
         yd.copy_(dev(W.uniform(seed, 5, (n_dot,), -1, 1)))
         g3.copy_(dev(W.uniform(seed, 6, (nx + 2, nx + 2, nx + 2), 0, 1)))
+        a_s.copy_(dev(W.uniform(seed, 9, (Ms, Ks), -1, 1)))
+        b_s.copy_(dev(W.uniform(seed, 10, (Ks, Ns), -1, 1)))
         A8.copy_(dev(W.integers(seed, 7, (nA, 8), 0, 3)))
         B8.copy_(dev(W.integers(seed, 8, (nB, 8), 0, 3)))
 
@@ -98,3 +112,5 @@ def test_sequence_of_calls_replays_from_a_graph():
         if rep == 0:
             ref, refabs = oracle.matmul(a.cpu().numpy(), b.cpu().numpy(), with_abs=True)
             assert float(np.max(np.abs(out_g[0].cpu().numpy() - ref) / refabs)) <= 1e-4
+            ref, refabs = oracle.matmul(a_s.cpu().numpy(), b_s.cpu().numpy(), with_abs=True)
+            assert float(np.max(np.abs(out_g[6].cpu().numpy() - ref) / refabs)) <= 1e-4

@@ -148,6 +148,29 @@ def test_small_m_every_candidate(shape):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("tb", [False, True])
+def test_small_m_one_launch_and_second_kernel_agree_bit_for_bit(tb):
+    # a reduction split over workgroups is combined by the last part of a strip to arrive (the default:
+    # out_region = device memory) or by a second kernel (out_region = registers): same order, same bits;
+    # calls of different shapes in a row share the arrival counters, which every call leaves at zero
+    for rep, (nb, M, N, K) in enumerate(((1, 16, 1000, 2048), (2, 12, 200, 4096), (1, 16, 1000, 2048), (3, 7, 130, 1024))):
+        A = W.uniform(W.SEED_BASE + 66 + rep, 1, (nb, M, K), -1, 1)
+        Bm = W.uniform(W.SEED_BASE + 66 + rep, 2, (nb, N, K) if tb else (nb, K, N), -1, 1)
+        sizes = (nb, M, N, K, 0, int(tb), 0)
+        d = mdh.mdh_default_params(mdh.MDH_BMATMUL, sizes)
+        assert d.blk[1] == 16 and d.prt[B.L_WG][3] > 1 and d.out_region == B.MR_HBM, (sizes, d.table())
+        second = d.copy()
+        second.out_region = B.MR_VGPR
+        assert mdh.mdh_validate_params(mdh.MDH_BMATMUL, sizes, second) == 0
+        g1, _ = run(A, Bm, False, tb, False, d)
+        g2, _ = run(A, Bm, False, tb, False, second)
+        g3, _ = run(A, Bm, False, tb, False, d)
+        assert np.array_equal(g1, g2) and np.array_equal(g1, g3), sizes
+        ref, refabs = reference(A, Bm, False, tb, False)
+        assert float(np.max(np.abs(g1 - ref) / refabs)) <= TOL
+
+
+@pytest.mark.gpu
 @pytest.mark.parametrize("views", [(0, 0, 0), (1, 0, 0), (0, 1, 0), (1, 1, 1)])
 def test_many_tiles_many_batches(views):
     # more than eight tile rows (banded tile order), a workgroup count divisible by 8 (the XCD-aware

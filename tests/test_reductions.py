@@ -165,3 +165,73 @@ def test_reductions_at_benchmark_sizes():
     mdh.mdh_matvec(A, xv, yv, None, ws_for(mdh.MDH_MATVEC, (M, Kc), None))
     ref, refabs = oracle.matvec(A.cpu().numpy(), xv.cpu().numpy(), with_abs=True)
     assert float(np.max(np.abs(yv.cpu().numpy() - ref) / refabs)) <= TOL
+
+
+def _variant(inst, sizes, like, **want):
+    """The candidate with the default's part counts whose named fields have the wanted values."""
+    for i in range(mdh.mdh_num_candidates(inst, sizes)):
+        c = mdh.mdh_candidate(inst, sizes, i)
+        if c.table() == like.table() and all(getattr(c, k) == v for k, v in want.items()):
+            return c
+    return None
+
+
+def test_assignment_and_combination_region_are_choices_of_the_table():
+    # parameter D2 (blocked / strided lane assignment) and R3 of the workgroup layer (partial sums combined
+    # in device memory by the last part to arrive, or by a second kernel) are honoured, not just echoed
+    for inst, sizes in ((mdh.MDH_DOT, (1 << 22,)), (mdh.MDH_MATVEC, (512, 4096))):
+        d = mdh.mdh_default_params(inst, sizes)
+        blocked = _variant(inst, sizes, d, strided=0)
+        assert blocked is not None and mdh.mdh_validate_params(inst, sizes, blocked) == 0
+        bad = d.copy()
+        bad.strided = 2
+        assert mdh.mdh_validate_params(inst, sizes, bad) == 6
+    d = mdh.mdh_default_params(mdh.MDH_DOT, (1 << 22,))
+    assert d.prt[B.L_WG][0] > 1 and d.out_region == B.MR_HBM  # one launch by default
+    second = _variant(mdh.MDH_DOT, (1 << 22,), d, out_region=B.MR_VGPR)
+    assert second is not None
+    one_part = mdh.mdh_default_params(mdh.MDH_DOT, (1000,))
+    assert one_part.prt[B.L_WG][0] == 1 and one_part.out_region == B.MR_VGPR
+    q = one_part.copy()
+    q.out_region = B.MR_HBM  # nothing to combine in device memory with a single part
+    assert mdh.mdh_validate_params(mdh.MDH_DOT, (1000,), q) == 6
+
+
+@pytest.mark.gpu
+def test_dot_one_launch_and_second_kernel_agree_bit_for_bit():
+    # the last workgroup part to arrive folds the partial sums exactly as the second kernel does; calls of
+    # different sizes in a row share the arrival counter, which every call leaves at zero
+    for rep, K in enumerate(((1 << 22) + 5, 1 << 20, 3000001, (1 << 22) + 5)):
+        x = dev(W.uniform(W.SEED_BASE + 53 + rep, 1, (K,), -1, 1))
+        y = dev(W.uniform(W.SEED_BASE + 53 + rep, 2, (K,), -1, 1))
+        d = mdh.mdh_default_params(mdh.MDH_DOT, (K,))
+        assert d.prt[B.L_WG][0] > 1 and d.out_region == B.MR_HBM
+        second = _variant(mdh.MDH_DOT, (K,), d, out_region=B.MR_VGPR)
+        got = []
+        for p in (d, second, d):
+            out = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
+            mdh.mdh_dot(x, y, out, p, ws_for(mdh.MDH_DOT, (K,), p))
+            got.append(float(out.cpu()[0]))
+        assert got[0] == got[1] == got[2], (K, got)
+        ref, refabs = oracle.dot(x.cpu().numpy(), y.cpu().numpy())
+        assert abs(got[0] - ref) / refabs <= TOL
+
+
+@pytest.mark.gpu
+def test_blocked_lane_assignment_matches_the_oracle():
+    K = 1000003
+    x = W.uniform(W.SEED_BASE + 57, 1, (K,), -1, 1)
+    y = W.uniform(W.SEED_BASE + 57, 2, (K,), -1, 1)
+    ref, refabs = oracle.dot(x, y)
+    p = _variant(mdh.MDH_DOT, (K,), mdh.mdh_default_params(mdh.MDH_DOT, (K,)), strided=0)
+    out = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
+    mdh.mdh_dot(dev(x), dev(y), out, p, ws_for(mdh.MDH_DOT, (K,), p))
+    assert abs(float(out.cpu()[0]) - ref) / refabs <= TOL
+    M, Kc = 257, 5001
+    A = W.uniform(W.SEED_BASE + 58, 1, (M, Kc), -1, 1)
+    xv = W.uniform(W.SEED_BASE + 58, 2, (Kc,), -1, 1)
+    ref, refabs = oracle.matvec(A, xv, with_abs=True)
+    p = _variant(mdh.MDH_MATVEC, (M, Kc), mdh.mdh_default_params(mdh.MDH_MATVEC, (M, Kc)), strided=0)
+    yv = torch.full((M,), float("nan"), dtype=torch.float32, device="cuda")
+    mdh.mdh_matvec(dev(A), dev(xv), yv, p, ws_for(mdh.MDH_MATVEC, (M, Kc), p))
+    assert float(np.max(np.abs(yv.cpu().numpy() - ref) / refabs)) <= TOL
