@@ -121,6 +121,28 @@ struct GemmExPlan {
   // partial results itself (one launch), 0 = a second kernel does
   int fused = 0;
 };
+// Device-coherent accesses for results that pass between workgroups of ONE launch (the parts of a split
+// reduction folded by the last part to arrive).  The L2 caches of the chip's eight XCDs are not kept
+// coherent for ordinary loads and stores inside a kernel; a device-scope fence would write back and
+// invalidate a whole L2 (measured: ~10 us per kernel).  Device-scope atomic loads and stores of single
+// words go to the coherent level directly, so: partial results are stored with coherent_store, the
+// storing wavefront waits for its stores (wait_stores_done) before it counts itself in with a
+// device-scope atomic, and the folding workgroup reads with coherent_load.
+#if defined(__HIPCC__)
+__device__ __forceinline__ void coherent_store(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float coherent_load(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// all memory operations this wavefront has issued are complete (vmcnt, expcnt, lgkmcnt = 0)
+__device__ __forceinline__ void wait_stores_done() { __builtin_amdgcn_s_waitcnt(0); }
+// counts the caller in; true for the S-th arrival, which also wraps the counter back to zero
+__device__ __forceinline__ bool arrive_last(unsigned* counter, unsigned S) {
+  return __builtin_amdgcn_atomic_inc32(counter, S - 1, __ATOMIC_RELAXED, "agent") == S - 1;
+}
+#endif
+
 // Counters of arriving workgroup parts live in static device arrays of this many words per kernel
 // family; a split reduction with more output parts than that takes the second-kernel path.
 constexpr int kArrivalCounters = 4096;

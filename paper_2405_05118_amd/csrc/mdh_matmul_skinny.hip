@@ -189,44 +189,58 @@ __global__ __launch_bounds__((WAVES_N * WAVES_K * 64)) void matmul_skinny_kernel
       }
     }
   };
-  store_strip(out);
-  if (S <= 1 || !fused) return;
+  if (S <= 1 || !fused) {
+    store_strip(out);
+    return;
+  }
 
   // workgroup layer -> grid in the same launch: the wavefront that stores the S-th partial strip adds
   // all S of them, in ascending part order (the order of the second kernel: same bits), into C.  Only
   // this wavefront is left in its workgroup for this strip; no barrier is involved.
-  __threadfence();  // this wavefront's partial strip is visible to the whole device before it is counted
-  unsigned seen = 0;
-  if (lane == 0) seen = atomicInc(&g_strip_arrivals[((unsigned)batch * tiles + t) * WAVES_N + wn], (unsigned)S - 1);
-  seen = __builtin_amdgcn_readfirstlane(seen);
-  if (seen != (unsigned)S - 1) return;
-  __threadfence();  // the other parts' strips, counted before this one, are visible to this wavefront
+  // (device-coherent single-word stores and loads instead of fences: see mdh_internal.h)
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = m0 + 4 * g + r;
+    if (row >= M) continue;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int cc = TB ? n0 + 16 * c + l16 : col + c;
+      if (cc < N) coherent_store(out + (int64_t)row * N + cc, acc[c][r]);
+    }
+  }
+  wait_stores_done();  // the partial strip has reached the coherent level before it is counted
+  unsigned last = 0;
+  if (lane == 0) last = arrive_last(&g_strip_arrivals[((unsigned)batch * tiles + t) * WAVES_N + wn], (unsigned)S);
+  if (!__builtin_amdgcn_readfirstlane(last)) return;
   const int64_t part_stride = (int64_t)nbatch * mn;
   const float* w0 = ws + (int64_t)batch * mn;
 #pragma unroll
   for (int c = 0; c < 4; ++c) acc[c] = (f4){0.f, 0.f, 0.f, 0.f};
-  for (int sp = 0; sp < S; ++sp) {
-    const float* src = w0 + (int64_t)sp * part_stride;
+  // four parts are requested together (each load is a round trip to the coherent level), then added in
+  // ascending part order; part 0 overrides (first write, no neutral element)
+  for (int sp0 = 0; sp0 < S; sp0 += 4) {
+    f4 v[4][4];  // [part][row r] -> the lane's 4 columns
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int row = m0 + 4 * g + r;
-      if (row >= M) continue;
-      const float* p = src + (int64_t)row * N + col;
-      f4 v = {0.f, 0.f, 0.f, 0.f};
-      if (TB) {
+    for (int u = 0; u < 4; ++u) {
+      const float* src = w0 + (int64_t)min(sp0 + u, S - 1) * part_stride;
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-          if (n0 + 16 * c + l16 < N) v[c] = src[(int64_t)row * N + n0 + 16 * c + l16];
-      } else if (cols_full) {
-        v = *(const f4u*)p;
-      } else {
+      for (int r = 0; r < 4; ++r) {
+        const int row = min(m0 + 4 * g + r, M - 1);
+        v[u][r] = (f4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-          if (col + c < N) v[c] = p[c];
+        for (int c = 0; c < 4; ++c) {
+          const int cc = TB ? n0 + 16 * c + l16 : col + c;
+          if (cc < N) v[u][r][c] = coherent_load(src + (int64_t)row * N + cc);
+        }
       }
-      // part 0 overrides (first write, no neutral element), later parts are added
+    }
 #pragma unroll
-      for (int c = 0; c < 4; ++c) acc[c][r] = sp == 0 ? v[c] : acc[c][r] + v[c];
+    for (int u = 0; u < 4; ++u) {
+      if (sp0 + u >= S) break;
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c][r] = (sp0 + u == 0) ? v[u][r][c] : acc[c][r] + v[u][r][c];
     }
   }
   store_strip(C + (int64_t)batch * mn);

@@ -50,6 +50,7 @@ static __device__ unsigned g_dot_arrivals;
 // The S workgroup-layer parts in a fixed order: 16 independent loads per lane and round (one round covers
 // S = 1024), so that the loads overlap instead of each addition waiting for its own load.  Called by one
 // whole wavefront; every lane returns the sum.
+template <bool COHERENT>
 __device__ __forceinline__ float dot_fold_parts(const float* __restrict__ ws, int S, int lane) {
   float a = 0.f;
   for (int base = 0; base < S; base += 1024) {
@@ -57,7 +58,7 @@ __device__ __forceinline__ float dot_fold_parts(const float* __restrict__ ws, in
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
       const int i = base + u * 64 + lane;
-      v[u] = i < S ? ws[i] : 0.f;
+      v[u] = i < S ? (COHERENT ? coherent_load(ws + i) : ws[i]) : 0.f;
     }
 #pragma unroll
     for (int u = 0; u < 16; ++u) a += v[u];
@@ -127,24 +128,26 @@ __global__ __launch_bounds__(WAVES * 64) void dot_kernel(const float* __restrict
     float s = part[0];
 #pragma unroll
     for (int i = 1; i < WAVES; ++i) s += part[i];
-    part_out[blockIdx.x] = s;  // the result itself if the grid is one workgroup, else part blockIdx.x
     if (fused) {
-      __threadfence();  // the partial sum is visible to the whole device before it is counted
-      last = atomicInc(&g_dot_arrivals, (unsigned)S - 1) == (unsigned)S - 1;
+      // device-coherent single-word store, complete before the part is counted (see mdh_internal.h)
+      coherent_store(part_out + blockIdx.x, s);
+      wait_stores_done();
+      last = arrive_last(&g_dot_arrivals, (unsigned)S);
+    } else {
+      part_out[blockIdx.x] = s;  // the result itself if the grid is one workgroup, else part blockIdx.x
     }
   }
   if (!fused) return;
   __syncthreads();
   if (!last || tid >= 64) return;
-  __threadfence();  // the other workgroups' partial sums, counted before this one, are visible here
-  const float total = dot_fold_parts(part_out, S, tid);
+  const float total = dot_fold_parts<true>(part_out, S, tid);
   if (tid == 0) result[0] = total;
 }
 
 // Second pass: one wavefront adds the S workgroup-layer parts in a fixed order.
 __global__ __launch_bounds__(64) void dot_combine_kernel(const float* __restrict__ ws,
                                                          float* __restrict__ out, int S) {
-  const float a = dot_fold_parts(ws, S, threadIdx.x);
+  const float a = dot_fold_parts<false>(ws, S, threadIdx.x);
   if (threadIdx.x == 0) out[0] = a;
 }
 
