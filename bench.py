@@ -491,6 +491,7 @@ def bench_scan(torch, mdh, W, name, steps, warmup, cpu):
     ws = _ws(torch, mdh, mdh.MDH_SCAN, (R, n))
     p = mdh.mdh_default_params(mdh.MDH_SCAN, (R, n))
     ms, wall = _events_ms(torch, lambda: mdh.mdh_scan(x, out, None, ws), steps, warmup)
+    assert not mdh.mdh_scan_timed_out(x, None, ws), "a bounded wait of the single-pass scan expired: results invalid"
     nbytes = 8 * R * n  # every element read once and written once
     gbs = nbytes / ms / 1e6
     chunks = int(p.prt[3][1])

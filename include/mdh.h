@@ -239,6 +239,10 @@ mdh_status mdh_stencil(int64_t nx, int64_t ny, int64_t nz, const float* in, floa
  * a second kernel adds them in ascending part order.  The library default does
  * that for small images with many channels, so pass the workspace
  * mdh_workspace_size asks for; it may be NULL when that size is 0.
+ * Precondition of the few-channel kernel (blk[c] = 1, the default for C <= 8): the
+ * input holds finite values.  Its fused (s,c) walk is padded to a multiple of 8 with
+ * zero filter entries whose partners are real neighbouring input cells, and 0 * Inf
+ * or 0 * NaN would put a NaN into an output whose own terms are all finite.
  */
 mdh_status mdh_mcc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
                    int64_t stride_h, int64_t stride_w, const float* in, const float* filt,
@@ -341,6 +345,18 @@ mdh_status mdh_mcc_capsule(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K
 mdh_status mdh_scan(int64_t R, int64_t n, const float* in, float* out,
                     const mdh_tile_params* params, void* workspace, size_t workspace_bytes,
                     void* stream);
+
+/*
+ * Did a bounded wait of the single-pass scan expire in the last mdh_scan call that used
+ * `workspace` with these sizes and parameters?  Synchronises `stream` (pass the stream of
+ * that call), then reads the flag word of the workspace: *timed_out = 1 means the output
+ * of that call is wrong in at least one chunk and must be discarded (the scan of the paper's
+ * Example "Prefix-Sum" has no such failure mode; it belongs to this single-pass kernel).
+ * Configurations without waits (one chunk per row, or three kernels) always report 0.
+ * Host call; not for use under graph capture.
+ */
+mdh_status mdh_scan_timed_out(int64_t R, int64_t n, const mdh_tile_params* params, const void* workspace,
+                              void* stream, int32_t* timed_out);
 
 /*
  * Dot product: out = sum_k x[k] * y[k]  =  md_hom(*, (+)) over (k) with output

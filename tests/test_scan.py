@@ -178,6 +178,11 @@ def test_full_size_row_exact():
         want = (torch.arange(j0, j0 + step, device="cuda", dtype=torch.int64) // 16 + 1).to(torch.float32)
         assert torch.equal(out[j0:j0 + step], want), j0
     assert int(ws[1].item()) == 0  # no wait ran into its bound
+    assert mdh.mdh_scan_timed_out(x, None, ws) is False  # the same word through the library's helper
+    ws[1] = 1  # what a kernel whose wait expired leaves behind
+    assert mdh.mdh_scan_timed_out(x, None, ws) is True
+    # a configuration without waits never reports a time-out, whatever its workspace holds
+    assert mdh.mdh_scan_timed_out(torch.empty((8, 4096), device="cuda"), None, None) is False
 
 
 @pytest.mark.gpu
@@ -190,7 +195,7 @@ def test_full_size_random(shape):
     n = mdh.mdh_workspace_size(mdh.MDH_SCAN, shape)
     ws = torch.empty(max(n, 8) // 8, dtype=torch.float64, device="cuda") if n else None
     mdh.mdh_scan(x, out, None, ws)
-    torch.cuda.synchronize()
+    assert not mdh.mdh_scan_timed_out(x, None, ws)
     ref, refabs = oracle.scan_rows(x.cpu().numpy(), with_abs=True)
     got = out.cpu().numpy()
     del x, out
