@@ -276,17 +276,17 @@ def bench_prl(torch, mdh, W, name, steps, warmup, cpu):
     s = torch.empty(cfg.nA, dtype=torch.int32, device="cuda")
     i = torch.empty(cfg.nA, dtype=torch.int32, device="cuda")
     ws = _ws(torch, mdh, mdh.MDH_CUSTOM_REDUCE, sizes)
-    before = valu_calibration(torch, mdh, kinds=("prl_mix",))
+    before = valu_calibration(torch, mdh, kinds=("prl_fast_mix",))
     ms, wall = _events_ms(torch, lambda: mdh.mdh_custom_reduce(A, B, wp, wm, s, i, None, ws), steps, warmup)
-    after = valu_calibration(torch, mdh, kinds=("prl_mix",))
+    after = valu_calibration(torch, mdh, kinds=("prl_fast_mix",))
     pairs = float(cfg.nA) * cfg.nB
     per_pair = VALU_PER_PAIR[name]  # SQ_INSTS_VALU of this kernel x 64 lanes / pairs
     tops = pairs * per_pair / ms / 1e9
     nbytes = 4 * (A.numel() + B.numel() + 2 * cfg.nF + 2 * cfg.nA)
     res = {
         "value": pairs / wall / 1e6, "unit": "Gpairs/s", "ms_per_step": wall, "kernel_ms": ms, "dtype": "i32",
-        "kernel": "prl_kernel + combine_maxidx_kernel",
-        "roofline": _alu_roofline(tops, before, after, TRAFFIC_BYTES.get(name)),
+        "kernel": "prl_fast_kernel + combine_maxidx_kernel",
+        "roofline": _alu_roofline(tops, before, after, TRAFFIC_BYTES.get(name), "prl_fast_mix"),
         "lane_ops_per_pair": per_pair,
         "algorithmic_bytes": nbytes,
         "hbm_GBs_algorithmic": nbytes / ms / 1e6,
@@ -601,7 +601,7 @@ def bench_prl_generic(torch, mdh, W, name, steps, warmup, cpu):
     return res
 
 
-VALU_KINDS = {"xor_max": 0, "cmp_select": 1, "add3": 2, "prl_mix": 3, "fma_f32_vgpr": 4, "add_u32_vgpr": 5}
+VALU_KINDS = {"xor_max": 0, "cmp_select": 1, "add3": 2, "prl_mix": 3, "fma_f32_vgpr": 4, "add_u32_vgpr": 5, "prl_fast_mix": 6}
 _CAL_BUFS = {}
 
 
@@ -623,7 +623,7 @@ def valu_calibration(torch, mdh, kinds=tuple(VALU_KINDS)):
         ops = [0]
 
         def run():
-            ops[0] = mdh.mdh_calib_valu_kind(VALU_KINDS[k], out, 8192, w, clk)
+            ops[0] = mdh.mdh_calib_valu_kind(VALU_KINDS[k], out, 2048 if k == "prl_fast_mix" else 8192, w, clk)
 
         run()
         torch.cuda.synchronize()

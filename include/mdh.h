@@ -278,10 +278,10 @@ mdh_status mdh_custom_reduce(int64_t nA, int64_t nB, int32_t nF, const int32_t* 
  * operation, arguments, results (bit for bit) and errors as mdh_custom_reduce, but
  * without the workspace arguments: the partial results of a reduction split over
  * workgroups (2 * S * nA int32, S = prt[MDH_L_WG][b]) go to a static device array
- * inside the library, mdh_static_scratch_bytes() = 8 MiB per GPU, which the GPU
+ * inside the library, mdh_static_scratch_bytes() = 16 MiB per GPU, which the GPU
  * holds until the process ends.  A call whose partial results do not fit returns
  * MDH_ERR_STATIC_LIMIT and enqueues nothing (at the default configuration of
- * 2^16 x 2^18 records, S = 16, they fit exactly); pass a configuration with a
+ * 2^16 x 2^18 records, S = 32, they fit exactly); pass a configuration with a
  * smaller S, or use mdh_custom_reduce with a workspace.  The call allocates and
  * frees nothing and synchronises nothing; the first call on a device looks up the
  * array's device address.  All calls on one GPU share that array: calls that may
@@ -586,8 +586,13 @@ mdh_status mdh_calib_valu(int32_t* out, int32_t iters, int64_t* lane_ops, void* 
  *                              scalar operand, 8 selects, 4.5 adds, compare + max +
  *                              select + half a move = 24 instructions), with the
  *                              records of B made up on the scalar unit, not loaded
+ *   MDH_CALIB_KIND_PRL_FAST_MIX the custom reduce's loop for 8 fields as built from the
+ *                              fast kinds (per pair: 8 x (fp32 subtract, multiply with
+ *                              clamp, fused multiply-add), and per block of four records
+ *                              of B two three-operand maxima, a compare and a select),
+ *                              one trip = one block = 8 pairs = 203 instructions
  *   out      MDH_CALIB_BLOCKS*256 int32 (device), overwritten
- *   weights  PRL_MIX only (else may be NULL): MDH_CALIB_MIX_WEIGHTS int32 (device):
+ *   weights  the two PRL kinds only (else may be NULL): MDH_CALIB_MIX_WEIGHTS int32 (device):
  *            8 agree weights, 8 disagree weights, then 256 lanes x 2 records x 8 fields
  *   iters    loop trips; *lane_ops (host, may be NULL) receives lanes x VALU instructions
  *            issued inside the loops of the launch
@@ -603,7 +608,8 @@ enum {
   MDH_CALIB_KIND_ADD3 = 2,
   MDH_CALIB_KIND_PRL_MIX = 3,
   MDH_CALIB_KIND_FMA_F32 = 4,
-  MDH_CALIB_KIND_ADD_VGPR = 5
+  MDH_CALIB_KIND_ADD_VGPR = 5,
+  MDH_CALIB_KIND_PRL_FAST_MIX = 6
 };
 #define MDH_CALIB_MIX_WEIGHTS (16 + 256 * 2 * 8)
 mdh_status mdh_calib_valu_kind(int32_t kind, int32_t* out, const int32_t* weights, int32_t iters,

@@ -31,7 +31,8 @@ EXPORTS = (
 MDH_CUSTOM_MAX_IN, MDH_CUSTOM_MAX_ACC = 4, 8
 MDH_CALIB_BLOCKS = 2048
 MDH_CALIB_STREAM_LANES = 256 * 512
-MDH_CALIB_KIND_XOR_MAX, MDH_CALIB_KIND_CMP_SELECT, MDH_CALIB_KIND_ADD3, MDH_CALIB_KIND_PRL_MIX, MDH_CALIB_KIND_FMA_F32, MDH_CALIB_KIND_ADD_VGPR = range(6)
+(MDH_CALIB_KIND_XOR_MAX, MDH_CALIB_KIND_CMP_SELECT, MDH_CALIB_KIND_ADD3, MDH_CALIB_KIND_PRL_MIX, MDH_CALIB_KIND_FMA_F32,
+ MDH_CALIB_KIND_ADD_VGPR, MDH_CALIB_KIND_PRL_FAST_MIX) = range(7)
 MDH_CALIB_MIX_WEIGHTS = 16 + 256 * 2 * 8
 
 

@@ -257,6 +257,75 @@ __global__ __launch_bounds__(CALIB_NT) void calib_fastkind_kernel(int32_t* __res
   out[(int64_t)blockIdx.x * CALIB_NT + threadIdx.x] = r;
 }
 
+// kind 6: the custom reduce's loop for 8 fields as it is built from the fast kinds (two records of A per
+// lane, blocks of four records of B): per pair 8 x (subtract, multiply with clamp, fused multiply-add) and
+// a quarter of (two three-operand maxima, compare, select) -- with the records of B made up on the
+// scalar unit, not loaded.  Per block of 8 pairs: 192 + 8 instructions, and three moves (block index, copies).
+__global__ __launch_bounds__(CALIB_NT) void calib_prlfast_kernel(int32_t* __restrict__ out, int iters,
+                                                                 int seed, const int32_t* __restrict__ wts,
+                                                                 long long* __restrict__ clk) {
+  constexpr int NF = 8, RA = 2;
+  constexpr unsigned kCode = 0x4B000000u;
+  float ndw[NF];
+  float agree = 0.f;
+#pragma unroll
+  for (int f = 0; f < NF; ++f) {
+    ndw[f] = (float)(wts[NF + f] - wts[f]);
+    agree += (float)wts[f];
+  }
+  float fa[RA][NF];
+#pragma unroll
+  for (int ra = 0; ra < RA; ++ra)
+#pragma unroll
+    for (int f = 0; f < NF; ++f) fa[ra][f] = __uint_as_float(kCode + (unsigned)wts[2 * NF + (threadIdx.x * RA + ra) * NF + f]);
+  float best[RA];
+  int blk[RA];
+#pragma unroll
+  for (int ra = 0; ra < RA; ++ra) best[ra] = -3.0e38f, blk[ra] = 0;
+  const float vbase = agree + __uint_as_float(threadIdx.x & 0);
+  const Ticks t0 = ticks_now();
+  unsigned s = (unsigned)seed;
+  for (int bb = 0; bb < iters; ++bb) {
+    float fb[4][NF];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int f = 0; f < NF; ++f) {
+        s = s * 5u + 1u;  // scalar unit
+        fb[u][f] = __uint_as_float(kCode + ((s >> 9) & 15u));
+      }
+    float acc[4][RA];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+      float t[4][RA];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int ra = 0; ra < RA; ++ra) t[u][ra] = fa[ra][f] - fb[u][f];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int ra = 0; ra < RA; ++ra) asm("v_mul_f32_e64 %0, %1, %1 clamp" : "=v"(t[u][ra]) : "v"(t[u][ra]));
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int ra = 0; ra < RA; ++ra) acc[u][ra] = __builtin_fmaf(t[u][ra], ndw[f], f == 0 ? vbase : acc[u][ra]);
+    }
+#pragma unroll
+    for (int ra = 0; ra < RA; ++ra) {
+      const float m = __builtin_fmaxf(__builtin_fmaxf(acc[0][ra], acc[1][ra]), acc[2][ra]);
+      const float nb = __builtin_fmaxf(__builtin_fmaxf(best[ra], m), acc[3][ra]);
+      blk[ra] = nb > best[ra] ? bb : blk[ra];
+      best[ra] = nb;
+    }
+  }
+  ticks_store(clk, t0);
+  int32_t r = 0;
+#pragma unroll
+  for (int ra = 0; ra < RA; ++ra) r ^= (int32_t)best[ra] ^ blk[ra];
+  out[(int64_t)blockIdx.x * CALIB_NT + threadIdx.x] = r;
+}
+
 // kind 0 with the clock readings: the loop of calib_valu_kernel
 __global__ __launch_bounds__(CALIB_NT) void calib_xormax_kernel(int32_t* __restrict__ out, int iters,
                                                                 int seed, long long* __restrict__ clk) {
@@ -349,6 +418,11 @@ mdh_status mdh_calib_valu_kind(int32_t kind, int32_t* out, const int32_t* weight
     case MDH_CALIB_KIND_PRL_MIX:
       hipLaunchKernelGGL(calib_prlmix_kernel, g, b, 0, st, out, iters, 12345, weights, clk);
       per_lane = (int64_t)iters * 48;  // two pairs of 24 instructions
+      break;
+    case MDH_CALIB_KIND_PRL_FAST_MIX:
+      if (!weights) return MDH_ERR_NULL;
+      hipLaunchKernelGGL(calib_prlfast_kernel, g, b, 0, st, out, iters, 12345, weights, clk);
+      per_lane = (int64_t)iters * 203;  // 8 pairs: 192 + 8 + three moves, as emitted
       break;
     case MDH_CALIB_KIND_FMA_F32:
       hipLaunchKernelGGL(calib_fastkind_kernel<true>, g, b, 0, st, out, iters, 0, clk);

@@ -785,7 +785,9 @@ static int prl_ragged(const int64_t* s, const PrlPlan& pl) {
 }
 
 static PrlPlan prl_default(const int64_t* s) {
-  PrlPlan pl{2, 8, 1, 1, 0};
+  // two records of A per lane, four wavefronts along b (2^16 x 2^18, 8 fields: 7.04 ms with 32 parts of
+  // b over workgroups, 7.22 with 16; eight wavefronts along b: 7.42 / 7.51; four records per lane: 7.16)
+  PrlPlan pl{2, 4, 1, 1, 0};
   const int64_t wgs_a = cdiv(s[0], (int64_t)pl.WA * 64 * pl.RA);
   int S = 1;
   // split B over workgroups until there are ~64 wavefronts per SIMD of the chip to draw from

@@ -84,6 +84,32 @@ def test_valu_kinds_count_and_compute():
     want = ((want + 2**31) % 2**32 - 2**31).astype(np.int32)
     got = outi.cpu().numpy().reshape(-1, 256)
     assert np.array_equal(got[0], want) and np.array_equal(got[-1], want)
+    # the loop built from the fast instruction kinds computes the same reduction (scores exact in fp32),
+    # reported per block of four made-up records
+    blocks = 50
+    ops = mdh.mdh_calib_valu_kind(B.MDH_CALIB_KIND_PRL_FAST_MIX, outi, blocks, torch.from_numpy(w).cuda(), clk)
+    torch.cuda.synchronize()
+    assert ops == B.MDH_CALIB_BLOCKS * 256 * blocks * 203
+    agree = int(w[:8].astype(np.int64).sum())
+    ndw = (w[8:16].astype(np.int64) - w[:8].astype(np.int64))
+    best = np.full((256, 2), -2**62, dtype=np.int64)
+    blk = np.zeros((256, 2), dtype=np.int64)
+    s = 12345
+    for bb in range(blocks):
+        top = np.full((256, 2), -2**62, dtype=np.int64)
+        for u in range(4):
+            br = np.empty(8, dtype=np.int64)
+            for f in range(8):
+                s = (s * 5 + 1) & 0xFFFFFFFF
+                br[f] = (s >> 9) & 15
+            top = np.maximum(top, agree + ((ar != br) * ndw).sum(axis=2))
+        take = top > best
+        blk = np.where(take, bb, blk)
+        best = np.maximum(best, top)
+    want = (best[:, 0] ^ blk[:, 0] ^ best[:, 1] ^ blk[:, 1])
+    want = ((want + 2**31) % 2**32 - 2**31).astype(np.int32)
+    got = outi.cpu().numpy().reshape(-1, 256)
+    assert np.array_equal(got[0], want) and np.array_equal(got[-1], want)
     ghz = clk.cpu().numpy()[0] / clk.cpu().numpy()[1] * hz / 1e9
     assert 0.3 < ghz < 4.0, ghz
     with pytest.raises(mdh.MdhError):

@@ -226,8 +226,8 @@ def test_size_errors_of_the_later_entry_points():
     assert L.mdh_custom_reduce_static(8, 0, 8, one, one, one, one, one, one, null, null) == E_SIZE
     assert L.mdh_custom_reduce_static(0, 8, 8, null, null, null, null, null, null, null, null) == OK
     assert L.mdh_custom_reduce_static(8, 8, 8, null, one, one, one, one, one, null, null) == E_NULL
-    assert L.mdh_custom_reduce_static((1 << 17) + 128, 1 << 18, 8, one, one, one, one, one, one, null, null) == E_STATIC  # S = 8
-    assert L.mdh_static_scratch_bytes() == 8 << 20
+    assert L.mdh_custom_reduce_static((1 << 17) + 128, 1 << 18, 8, one, one, one, one, one, one, null, null) == E_STATIC  # S = 16
+    assert L.mdh_static_scratch_bytes() == 16 << 20
     assert "static" in mdh.mdh_strerror(E_STATIC)
     # calibration kernels
     assert L.mdh_calib_copy(one, one, 24, null) == E_SIZE  # not a multiple of 16 bytes

@@ -43,8 +43,8 @@ def test_static_scratch_matches_workspace_entry_point_twice():
 
 
 def test_static_scratch_limit_is_an_error():
-    # 2 * S * nA int32 beyond the 8 MiB array: refused before anything is enqueued
-    nA, nB = (1 << 17) + 128, 1 << 18  # the default splits b 8 ways here: 2 * 8 * nA int32 > 8 MiB
+    # 2 * S * nA int32 beyond the 16 MiB array: refused before anything is enqueued
+    nA, nB = (1 << 17) + 128, 1 << 18  # the default splits b 16 ways here: 2 * 16 * nA int32 > 16 MiB
     p = mdh.mdh_default_params(mdh.MDH_CUSTOM_REDUCE, (nA, nB, 8))
     assert 2 * p.prt[3][1] * nA * 4 > mdh.mdh_static_scratch_bytes()
     one = torch.zeros(8, dtype=torch.int32, device="cuda")
