@@ -54,6 +54,7 @@ LLC_BYTES = 256 * 1024 * 1024
 
 LAST_SPREAD = {}
 MIN_WARM_MS = 0.0
+ORACLE_SECONDS = 3.0  # host time the oracle gets per BASELINE row (a bounded sample of the workload)
 
 
 # Student t, two-sided 99 %, by degrees of freedom (the next lower listed value is used)
@@ -167,14 +168,14 @@ def bench_stencil(torch, mdh, W, name, steps, warmup, cpu):
         import oracle
 
         xh = x.cpu().numpy()
-        best = None
-        for _ in range(3):
-            t0 = time.perf_counter()
+        oracle.jacobi3d(xh, cfg.c0, cfg.c1)  # untimed: first touch of the output pages
+        sweeps, t0 = 0, time.perf_counter()
+        while sweeps < 3 or time.perf_counter() - t0 < ORACLE_SECONDS:
             oracle.jacobi3d(xh, cfg.c0, cfg.c1)
-            dt = time.perf_counter() - t0
-            best = dt if best is None else min(best, dt)
-        res["cpu_baseline"] = {"value": nbytes / best / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
-                               "kind": "oracle", "sample": "whole %dx%dx%d grid, best of 3 sweeps (%.3f s)" % (cfg.nx, cfg.ny, cfg.nz, best)}
+            sweeps += 1
+        dt = (time.perf_counter() - t0) / sweeps
+        res["cpu_baseline"] = {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": "whole %dx%dx%d grid, mean of %d sweeps (%.3f s each)" % (cfg.nx, cfg.ny, cfg.nz, sweeps, dt)}
         del xh, np
     return res
 
@@ -209,7 +210,8 @@ def bench_matmul(torch, mdh, W, name, steps, warmup, cpu, split=None):
         "wavefront_parts_of_k": int(p.prt[4][2]),
         "split_k": int(p.prt[3][2]),
         "roofline": {"bound": "mfma", "achieved": tf, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": tf / PEAK_FP32_MFMA_TFLOPS, "traffic": TRAFFIC_BYTES.get(name)},
+                     "frac": tf / PEAK_FP32_MFMA_TFLOPS,
+                     "traffic": TRAFFIC_BYTES.get(name if split is None else "%s_split_k%d" % (name, split))},
         "algorithmic_flop": flop,
         "algorithmic_bytes": 4 * (cfg.M * cfg.K + cfg.K * cfg.N + cfg.M * cfg.N),
         "cache_resident": 4 * (cfg.M * cfg.K + cfg.K * cfg.N + cfg.M * cfg.N) < LLC_BYTES,
@@ -217,13 +219,21 @@ def bench_matmul(torch, mdh, W, name, steps, warmup, cpu, split=None):
     if cpu:
         import oracle
 
+        # a probe of a few rows sizes the sample to about ORACLE_SECONDS of work (whole matrix if less)
+        bh = b.cpu().numpy()
         rows = max(1, min(cfg.M, int(6e8 // (cfg.N * cfg.K))))
-        ah, bh = a[:rows].cpu().numpy(), b.cpu().numpy()
         t0 = time.perf_counter()
-        oracle.matmul(ah, bh)
-        dt = time.perf_counter() - t0
+        oracle.matmul(a[:rows].cpu().numpy(), bh)
+        probe = time.perf_counter() - t0
+        rows = max(rows, min(cfg.M, int(rows * ORACLE_SECONDS / max(probe, 1e-6))))
+        ah = a[:rows].cpu().numpy()
+        reps, t0 = 0, time.perf_counter()
+        while reps < 1 or (rows == cfg.M and time.perf_counter() - t0 < ORACLE_SECONDS):
+            oracle.matmul(ah, bh)
+            reps += 1
+        dt = (time.perf_counter() - t0) / reps
         res["cpu_baseline"] = {"value": 2.0 * rows * cfg.N * cfg.K / dt / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(),
-                               "kind": "oracle", "sample": "first %d rows of C (%.2f s)" % (rows, dt)}
+                               "kind": "oracle", "sample": "first %d rows of C, %d time(s) (%.2f s each)" % (rows, reps, dt)}
     return res
 
 
@@ -255,7 +265,7 @@ def bench_mcc(torch, mdh, W, name, steps, warmup, cpu):
         if cfg.C <= 8:
             xh, fh = x[:4].cpu().numpy(), f.cpu().numpy()  # four whole images
         else:
-            xh, fh = x[:1, : cfg.R + 3].cpu().numpy(), f.cpu().numpy()  # 4 output rows of image 0
+            xh, fh = x[:1].cpu().numpy(), f.cpu().numpy()  # image 0, every output row (a few seconds)
         t0 = time.perf_counter()
         r = oracle.mcc(np.ascontiguousarray(xh), fh, cfg.stride)
         dt = time.perf_counter() - t0
@@ -295,7 +305,7 @@ def bench_prl(torch, mdh, W, name, steps, warmup, cpu):
     if cpu:
         import oracle
 
-        rows = list(range(0, cfg.nA, cfg.nA // 512))[:512]
+        rows = list(range(0, cfg.nA, 4))  # every fourth record of A against all of B (a second or so)
         Ah, Bh = A.cpu().numpy(), B.cpu().numpy()
         t0 = time.perf_counter()
         oracle.custom_reduce_rows(Ah, Bh, wp.cpu().numpy(), wm.cpu().numpy(), rows)
@@ -710,12 +720,19 @@ def _rounded(x):
     return x
 
 
+def bench_matmul_ts_split(torch, mdh, W, name, steps, warmup, cpu):
+    """The tall-skinny MatMul with the reduction dimension split four ways over workgroups (partial
+    results in a device-memory workspace + second-pass combine)."""
+    return bench_matmul(torch, mdh, W, "matmul_ts", steps, warmup, False, split=4)
+
+
 BENCHES = {
     "dot_2p28": bench_dot,
     "matvec_16384": bench_matvec,
     "jacobi3d_512": bench_stencil,
     "matmul_4096": bench_matmul,
     "matmul_ts": bench_matmul,
+    "matmul_ts_split_k4": bench_matmul_ts_split,
     "mcc_resnet": bench_mcc,
     "prl_2p16_2p18": bench_prl,
     "matmul_256": bench_matmul,
@@ -816,13 +833,6 @@ def main() -> int:
             inst[name]["spread"] = dict(LAST_SPREAD)
             torch.cuda.synchronize()
             torch.cuda.empty_cache()
-            if name == "matmul_ts":
-                # the tall-skinny MatMul again with the reduction dimension split over workgroups
-                # (partial results in a device-memory workspace + second-pass combine)
-                inst["matmul_ts_split_k4"] = bench_matmul(torch, mdh, W, "matmul_ts", 20, 5, False, split=4)
-                inst["matmul_ts_split_k4"]["spread"] = dict(LAST_SPREAD)
-                torch.cuda.synchronize()
-                torch.cuda.empty_cache()
         ADAPTIVE = False
         line["calibration"] = calibration(torch, mdh)
         line["instances"] = inst

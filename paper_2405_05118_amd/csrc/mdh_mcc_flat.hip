@@ -57,55 +57,6 @@ __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
   float* fs = lds;                    // filter slice [BN][PFR]: row k holds R groups of SCP floats
   float* ps0 = lds + Cf::BN * PFR;    // input patch [2][PH][PWF]: two buffers
 
-  // Staging without integer divisions in the loops: a filter row k is R*SC contiguous floats in
-  // memory, so a lane's elements e = lane, lane+64, ... have the same (r, x) for every k and that
-  // split is computed once; wavefronts take the rows k (filter) and ph (patch) in turn.
-  {
-    constexpr int NW = Cf::NT / 64;
-    const int RSC = R * SC;
-    for (int e0 = 0; e0 < RSC; e0 += 256) {
-      int off[4];  // LDS offset inside a filter row, -1: beyond the row
-      int ge[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int e = e0 + u * 64 + lane;
-        const int r = e / SC;
-        ge[u] = e;
-        off[u] = e < RSC ? r * SCP + (e - r * SC) : -1;
-      }
-      // all loads of a group of 8 rows are issued before the first LDS write: one round trip to
-      // memory per group instead of one per row
-      constexpr int KI = Cf::BN / NW;  // rows k per wavefront
-      constexpr int KG = KI < 8 ? KI : 8;
-#pragma unroll
-      for (int kb = 0; kb < KI; kb += KG) {
-        float v[KG][4];
-#pragma unroll
-        for (int ki = 0; ki < KG; ++ki) {
-          const int k = wave + (kb + ki) * NW;
-          const bool kin = k0 + k < K;
-          const float* src = filt + (int64_t)(k0 + k) * RSC;
-#pragma unroll
-          for (int u = 0; u < 4; ++u) v[ki][u] = (kin && off[u] >= 0) ? src[ge[u]] : 0.f;
-        }
-#pragma unroll
-        for (int ki = 0; ki < KG; ++ki) {
-          const int k = wave + (kb + ki) * NW;
-#pragma unroll
-          for (int u = 0; u < 4; ++u)
-            if (off[u] >= 0) fs[k * PFR + off[u]] = v[ki][u];
-        }
-      }
-    }
-    // zero the padding of every filter row (x in [SC, SCP)): it meets patch values in the MFMAs
-    const int padn = SCP - SC;
-    for (int i = tid; i < Cf::BN * R * padn; i += Cf::NT) {
-      const int row = i / padn, x = SC + (i - row * padn);
-      const int k = row / R, r = row - k * R;
-      fs[k * PFR + r * SCP + x] = 0.f;
-    }
-  }
-
   // Input patch, 16 bytes at a time (rows are only dword aligned); cells outside the image read as
   // 0 (they only meet zero filter entries or outputs that are not stored).  A lane's pieces
   // (row ph, offset x) are the same for every tile; only the column origin moves.
@@ -169,7 +120,57 @@ __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
 
   const int tile0 = tq * QT;
   f4 pv[PV];
-  load_patch(tile0 * Cf::TQ, pv);
+  load_patch(tile0 * Cf::TQ, pv);  // requested first: in flight while the filter slice is staged
+
+  // Staging without integer divisions in the loops: a filter row k is R*SC contiguous floats in
+  // memory, so a lane's elements e = lane, lane+64, ... have the same (r, x) for every k and that
+  // split is computed once; wavefronts take the rows k (filter) and ph (patch) in turn.
+  {
+    constexpr int NW = Cf::NT / 64;
+    const int RSC = R * SC;
+    for (int e0 = 0; e0 < RSC; e0 += 256) {
+      int off[4];  // LDS offset inside a filter row, -1: beyond the row
+      int ge[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int e = e0 + u * 64 + lane;
+        const int r = e / SC;
+        ge[u] = e;
+        off[u] = e < RSC ? r * SCP + (e - r * SC) : -1;
+      }
+      // all loads of a group of 8 rows are issued before the first LDS write: one round trip to
+      // memory per group instead of one per row
+      constexpr int KI = Cf::BN / NW;  // rows k per wavefront
+      constexpr int KG = KI < 8 ? KI : 8;
+#pragma unroll
+      for (int kb = 0; kb < KI; kb += KG) {
+        float v[KG][4];
+#pragma unroll
+        for (int ki = 0; ki < KG; ++ki) {
+          const int k = wave + (kb + ki) * NW;
+          const bool kin = k0 + k < K;
+          const float* src = filt + (int64_t)(k0 + k) * RSC;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) v[ki][u] = (kin && off[u] >= 0) ? src[ge[u]] : 0.f;
+        }
+#pragma unroll
+        for (int ki = 0; ki < KG; ++ki) {
+          const int k = wave + (kb + ki) * NW;
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            if (off[u] >= 0) fs[k * PFR + off[u]] = v[ki][u];
+        }
+      }
+    }
+    // zero the padding of every filter row (x in [SC, SCP)): it meets patch values in the MFMAs
+    const int padn = SCP - SC;
+    for (int i = tid; i < Cf::BN * R * padn; i += Cf::NT) {
+      const int row = i / padn, x = SC + (i - row * padn);
+      const int k = row / R, r = row - k * R;
+      fs[k * PFR + r * SCP + x] = 0.f;
+    }
+  }
+
   store_patch(ps0, pv);
   __syncthreads();
 
