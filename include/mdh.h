@@ -109,15 +109,31 @@ enum { MDH_MR_HBM = 0, MDH_MR_LDS = 1, MDH_MR_VGPR = 2 };
  *                equality)
  * order[]    parameters D1=S1=R1: the fused loop order, outermost first, each
  *            entry = l * MDH_MAX_D + d; only the first MDH_NUM_LAYERS*D entries
- *            are used.  The library supports the order its kernel implements
- *            (returned by mdh_default_params) and rejects any other.
+ *            are used.  Every kernel implements one order (workgroup parts,
+ *            then device-memory tiles, wavefront and lane parts, LDS and register
+ *            parts; returned by mdh_default_params); any other order has no
+ *            instantiation: MDH_ERR_UNSUPPORTED.
  * strided    parameters D2=S2=R2 restricted to two values: 0 = blocked (outer
  *            parallelism: a core owns one contiguous part), 1 = strided.
+ *            A real choice for MDH_DOT and MDH_MATVEC (lane assignment of the
+ *            reduction dimension; both values run, blocked is the slow one) and for
+ *            mdh_custom_* (walk order of the sequential parts); the other
+ *            instances have one assignment per kernel and reject the other value.
  * lane_fast_dim  which md_hom dimension follows the fastest lane index (the
- *            paper's swizzle choice; decides coalescing).
+ *            paper's swizzle choice; decides coalescing).  A real choice for
+ *            mdh_custom_*; fixed per kernel elsewhere (the contiguous dimension).
  * in_region[b] / out_region   parameters D3/S3 and R3/S5: the fastest memory
- *            region input buffer b is staged in / results are combined in.
- * in_transposed[b] / out_transposed  parameters D4/S4, R4/S6 for 2-D tiles.
+ *            region input buffer b is staged in / results are combined in.  Real
+ *            choices: MDH_MATMUL in_region LDS (wavefronts tile the output, operands
+ *            staged in LDS) or VGPR (k on the wavefront layer, operands straight to
+ *            registers, out_region = LDS); MDH_SCAN in_region VGPR (single pass) or
+ *            HBM (three kernels); MDH_DOT and the small-M kernel of MDH_BMATMUL with
+ *            a reduction split over workgroups: out_region HBM (the last workgroup
+ *            part to arrive combines the parts in device memory, one launch) or VGPR
+ *            (a second kernel does).  Other values: MDH_ERR_UNSUPPORTED.
+ * in_transposed[b] / out_transposed  parameters D4/S4, R4/S6 for 2-D tiles:
+ *            for MDH_BMATMUL they are the views of the call (and must equal its
+ *            flags); the other instances have plain layouts only.
  */
 typedef struct mdh_tile_params {
   int32_t D;
