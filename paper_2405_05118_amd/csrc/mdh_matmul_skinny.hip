@@ -246,6 +246,90 @@ __global__ __launch_bounds__((WAVES_N * WAVES_K * 64)) void matmul_skinny_kernel
   store_strip(C + (int64_t)batch * mn);
 }
 
+// Narrow strips: a workgroup owns 16 columns (ONE block column) and all of k, split over its WAVES_K
+// wavefronts in interleaved parts of 128; nothing is combined between workgroups.  For a B of a few
+// MB (16 x 1000 x 2048: 8 MB) a 64-column strip leaves the choice between 16 workgroups (16 compute
+// units pulling 512 KB each) and a split of k over workgroups whose combination costs three more
+// round trips to the coherent level; 16-column strips give N/16 workgroups, each requesting its
+// whole 64 B x K slice of B in one round (a lane loads single words: 4 rows x 64 contiguous bytes per
+// instruction; with the transposed view 16 bytes of its column's row).  Consecutive strips share cache
+// lines where a row of B is not a multiple of 64 bytes, so consecutive strips go to the same XCD.
+// Re-composition: MFMA accumulator -> LDS across the WAVES_K wavefronts, added in ascending order.
+template <int WAVES_K, bool TB>
+__global__ __launch_bounds__((WAVES_K * 64)) void matmul_skinny16_kernel(
+    const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C, int M, int N, int K,
+    int strips, int strips_per_xcd) {
+  __shared__ f4 part[(WAVES_K - 1) * 64];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int g = lane >> 4, l16 = lane & 15;
+  const int batch = blockIdx.y;
+  const int strip = (blockIdx.x & 7) * strips_per_xcd + (blockIdx.x >> 3);
+  if (strip >= strips) return;  // workgroup-uniform
+  const int n0 = strip * 16;
+  const int64_t mn = (int64_t)M * N;
+  const float* Ab = A + (int64_t)batch * M * K;
+  const float* Bb = B + (int64_t)batch * K * N;
+  const bool arow_ok = l16 < M;
+  const float* ap = Ab + (int64_t)(arow_ok ? l16 : 0) * K + 4 * g;  // the lane's row of A, its 4 k of every 16
+  const int col = n0 + l16;
+  const bool col_ok = col < N;
+  // lane group g owns k = 4g..4g+3 of every 16: B[k + 4g + tt][col], or with the transposed view 16
+  // contiguous bytes of row col
+  const float* bp = TB ? Bb + (int64_t)(col_ok ? col : 0) * K + 4 * g : Bb + (int64_t)(4 * g) * N + (col_ok ? col : 0);
+
+  f4 acc = (f4){0.f, 0.f, 0.f, 0.f};
+  constexpr int CH = 128;  // k per wavefront and round: 8 steps of 16, all requested before the first MFMA
+  for (int k = wave * CH; k < K; k += CH * WAVES_K) {
+    f4 a[8], b[8];
+    if (k + CH <= K) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        a[j] = *(const f4u*)(ap + k + 16 * j);
+        if (TB) {
+          b[j] = __builtin_nontemporal_load((const f4u*)(bp + k + 16 * j));
+        } else {
+#pragma unroll
+          for (int tt = 0; tt < 4; ++tt) b[j][tt] = __builtin_nontemporal_load(bp + (int64_t)(k + 16 * j + tt) * N);
+        }
+      }
+    } else {  // the ragged end of k: every element predicated
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+          const int kk = k + 16 * j + tt;  // + 4g is in ap / bp
+          const bool kin = kk + 4 * g < K;
+          a[j][tt] = kin ? ap[kk] : 0.f;
+          b[j][tt] = kin ? (TB ? bp[kk] : bp[(int64_t)kk * N]) : 0.f;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        // rows of A beyond M and columns beyond N hold values of row 0 / column 0: they only reach
+        // outputs that are not stored
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][tt], b[j][tt], acc, 0, 0, 0);
+      }
+  }
+
+  if (WAVES_K > 1) {
+    if (wave > 0) part[(wave - 1) * 64 + lane] = acc;
+    __syncthreads();
+    if (wave > 0) return;
+#pragma unroll
+    for (int w = 1; w < WAVES_K; ++w) acc += part[(w - 1) * 64 + lane];
+  }
+  // register r of the block is C[4g + r][col]
+  if (col_ok) {
+    float* out = C + (int64_t)batch * mn + col;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (4 * g + r < M) out[(int64_t)(4 * g + r) * N] = acc[r];
+  }
+}
+
 template <int WAVES_N, int WAVES_K, bool TB>
 mdh_status launch_t(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, int64_t K,
                     const float* A, const float* B, float* C, void* ws, hipStream_t st) {
@@ -265,11 +349,29 @@ mdh_status launch_t(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, i
   return launch_combine_sum((const float*)ws, C, batch * M * N, S, st);
 }
 
+template <int WAVES_K, bool TB>
+mdh_status launch_narrow(int64_t batch, int64_t M, int64_t N, int64_t K, const float* A, const float* B,
+                         float* C, hipStream_t st) {
+  if (M > 16 || batch > 65535) return MDH_ERR_SIZE;
+  const int64_t strips = cdiv(N, 16), per_xcd = cdiv(strips, 8);
+  if (per_xcd * 8 > 0x7fffffff) return MDH_ERR_SIZE;
+  clear_stale_error();
+  hipLaunchKernelGGL((matmul_skinny16_kernel<WAVES_K, TB>), dim3((unsigned)(per_xcd * 8), (unsigned)batch),
+                     dim3(WAVES_K * 64), 0, st, A, B, C, (int)M, (int)N, (int)K, (int)strips, (int)per_xcd);
+  return launch_status();
+}
+
 }  // namespace
 
 mdh_status launch_matmul_skinny(const GemmExPlan& pl, int64_t batch, int64_t M, int64_t N, int64_t K,
                                 const float* A, const float* B, float* C, void* ws, hipStream_t st) {
   if (pl.ta || pl.tc) return MDH_ERR_UNSUPPORTED;
+  if (pl.g.BN == 16) {  // narrow strips: one block column per workgroup, k inside the workgroup only
+    if (pl.g.S != 1) return MDH_ERR_UNSUPPORTED;
+    if (pl.WK == 16) return pl.tb ? launch_narrow<16, true>(batch, M, N, K, A, B, C, st) : launch_narrow<16, false>(batch, M, N, K, A, B, C, st);
+    if (pl.WK == 8) return pl.tb ? launch_narrow<8, true>(batch, M, N, K, A, B, C, st) : launch_narrow<8, false>(batch, M, N, K, A, B, C, st);
+    return MDH_ERR_UNSUPPORTED;
+  }
 #define MDH_SK(wn, wk)                                                                                   \
   if (pl.g.BN == 64 * wn && pl.WK == wk)                                                                 \
     return pl.tb ? launch_t<wn, wk, true>(pl, batch, M, N, K, A, B, C, ws, st)                           \

@@ -37,16 +37,18 @@ static void skinny_params(const int64_t* s, const GemmExPlan& pl, mdh_tile_param
   p->blk[1] = 16;
   p->blk[2] = 16;
   p->blk[3] = 4;
-  const int64_t kstep = pl.tb ? 64 : 16;  // k a wavefront takes per step (four 16-steps at once when B is transposed)
+  const bool narrow = g.BN == 16;  // a workgroup owns one block column; rounds of 128 k per wavefront
+  // k a wavefront takes per step (four 16-steps at once when B is transposed, eight with narrow strips)
+  const int64_t kstep = narrow ? 128 : pl.tb ? 64 : 16;
   const int64_t kchunk = cdiv(cdiv(s[3], g.S), kstep) * kstep;
   p->prt[MDH_L_WG][0] = (int32_t)s[0];
   p->prt[MDH_L_WG][1] = (int32_t)cdiv(s[1], 16);
   p->prt[MDH_L_WG][2] = (int32_t)cdiv(s[2], g.BN);
   p->prt[MDH_L_WG][3] = g.S;
   p->prt[MDH_L_HBM][3] = (int32_t)cdiv(kchunk, kstep * pl.WK);
-  p->prt[MDH_L_WAVE][2] = g.BN / 64;
+  p->prt[MDH_L_WAVE][2] = narrow ? 1 : g.BN / 64;
   p->prt[MDH_L_WAVE][3] = pl.WK;
-  p->prt[MDH_L_VGPR][2] = 4;
+  p->prt[MDH_L_VGPR][2] = narrow ? 1 : 4;
   p->prt[MDH_L_VGPR][3] = (int32_t)(kstep / 4);
   static const int dims[4] = {0, 1, 2, 3};
   set_order(p, dims);
@@ -62,7 +64,7 @@ static void skinny_params(const int64_t* s, const GemmExPlan& pl, mdh_tile_param
 }
 
 static int skinny_ragged(const int64_t* s, const GemmExPlan& pl) {
-  const int64_t kstep = pl.tb ? 64 : 16;
+  const int64_t kstep = pl.g.BN == 16 ? 128 : pl.tb ? 64 : 16;
   const int64_t kchunk = cdiv(cdiv(s[3], pl.g.S), kstep) * kstep;
   return (s[1] % 16) || (s[2] % pl.g.BN) || (s[3] != (int64_t)pl.g.S * cdiv(kchunk, kstep * pl.WK) * pl.WK * kstep);
 }
@@ -74,6 +76,13 @@ static GemmExPlan skinny_plan(const int64_t* s, int wn, int wk, int S, int fused
   GemmExPlan pl{GemmPlan{16, 64 * wn, 16, 16, 64, S, 0}, 0, (int)s[5], 0, 1, wk};
   pl.g.ragged = skinny_ragged(s, pl);
   pl.fused = (S > 1 && fused && skinny_strips(s) <= kArrivalCounters) ? 1 : 0;
+  return pl;
+}
+
+// narrow strips: 16 columns per workgroup, k over the wk wavefronts of the workgroup only
+static GemmExPlan skinny_narrow_plan(const int64_t* s, int wk) {
+  GemmExPlan pl{GemmPlan{16, 16, 16, 16, 16, 1, 0}, 0, (int)s[5], 0, 1, wk};
+  pl.g.ragged = skinny_ragged(s, pl);
   return pl;
 }
 
@@ -123,6 +132,12 @@ static GemmExPlan ex_default(const int64_t* s) {
     // B streams once from HBM: 8 wavefronts along k per workgroup, and k parts over workgroups until
     // 2048 wavefronts (two per SIMD) are in flight, each still walking at least two steps of 16 rows
     // (measured best on 16 x 1000 x 2048, 16 x 1000 x 4096, 16 x 4096 x 4096 and 16 x 4096 x 25088)
+    // B transposed: a lane reads 16 bytes of its column's row whatever the strip width, so 16-column
+    // strips cost nothing in coalescing and need no combination between workgroups; they win once they
+    // fill the chip or a workgroup's slice of B (64 B x K) is a few rounds of requests
+    // (16 x 1000 x 2048: 10.0 against 14.3 us; 16 x 4096 x 4096: 18.7 against 24.9; 16 x 1000 x 8192 and
+    // 16 x 256 x 8192: the split of k over workgroups wins, 24 against 32 and 21 against 32 us)
+    if (s[5] && (batch * cdiv(N, 16) >= 192 || K <= 3072)) return skinny_narrow_plan(s, 8);
     const int64_t strips = batch * cdiv(M, 16) * cdiv(N, 64);
     int S = 1;
     while (strips * 8 * S < 2048 && S < 64 && K / (2 * S) >= 8 * 16 * 2) S *= 2;
@@ -184,6 +199,8 @@ int matmul_ex_candidates(const int64_t* s, GemmExPlan* out, int cap) {
     const GemmExPlan d = ex_default(s);
     out[n++] = d;
     if (d.fused) out[n++] = skinny_plan(s, d.g.BN / 64, d.WK, d.g.S, 0);  // the same with the second kernel
+    for (int wk : {16, 8})
+      if (!(d.g.BN == 16 && d.WK == wk)) out[n++] = skinny_narrow_plan(s, wk);
     static const int sk_splits[] = {1, 2, 4, 8, 16, 32, 64};
     for (auto& m : kSkinnyMenu)
       for (int S : sk_splits) {
@@ -217,11 +234,14 @@ mdh_status plan_matmul_ex(const int64_t* s, const mdh_tile_params* p, GemmExPlan
   if ((st = check_lanes(p)) != MDH_OK) return st;
   if (p->blk[1] == 16) {  // the small-M kernel
     const int wn = p->prt[MDH_L_WAVE][2], wk = p->prt[MDH_L_WAVE][3];
-    if (!skinny_inst(wn, wk) || s[4] || s[6]) return MDH_ERR_UNSUPPORTED;
+    const bool narrow = p->prt[MDH_L_VGPR][2] == 1;
+    if (s[4] || s[6] || (narrow && s[1] > 16)) return MDH_ERR_UNSUPPORTED;
+    if (narrow ? (wn != 1 || (wk != 8 && wk != 16)) : !skinny_inst(wn, wk)) return MDH_ERR_UNSUPPORTED;
     const int S = p->prt[MDH_L_WG][3];
     const int fused = p->out_region == MDH_MR_HBM;
+    if (narrow && (S != 1 || fused)) return MDH_ERR_UNSUPPORTED;
     if (fused && (S <= 1 || skinny_strips(s) > kArrivalCounters)) return MDH_ERR_UNSUPPORTED;
-    GemmExPlan pl = skinny_plan(s, wn, wk, S, fused);
+    GemmExPlan pl = narrow ? skinny_narrow_plan(s, wk) : skinny_plan(s, wn, wk, S, fused);
     mdh_tile_params chk;
     params_from_plan(s, pl, &chk);
     if (!same_table(chk, *p)) return MDH_ERR_UNSUPPORTED;

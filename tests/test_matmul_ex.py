@@ -81,10 +81,28 @@ def test_small_m_default_streams_operands_to_registers():
         assert p.prt[B.L_WAVE][3] > 1
     # B transposed (a weight matrix stored [N][K]): the same kernel, a lane then takes 4 consecutive k of
     # its column for four steps of 16 at once (16 register-layer parts of k instead of 4)
-    p = mdh.mdh_default_params(mdh.MDH_BMATMUL, (1, 16, 1000, 2048, 0, 1, 0))
+    p = mdh.mdh_default_params(mdh.MDH_BMATMUL, (1, 16, 1000, 8192, 0, 1, 0))
     assert list(p.blk[:4]) == [1, 16, 16, 4] and p.in_transposed[1] == 1 and p.prt[B.L_VGPR][3] == 16
-    assert mdh.mdh_validate_params(mdh.MDH_BMATMUL, (1, 16, 1000, 2048, 0, 1, 0), p) == 0
-    assert mdh.mdh_validate_params(mdh.MDH_BMATMUL, (1, 16, 1000, 2048, 0, 0, 0), p) == 6
+    assert p.prt[B.L_VGPR][2] == 4 and p.prt[B.L_WG][3] > 1
+    assert mdh.mdh_validate_params(mdh.MDH_BMATMUL, (1, 16, 1000, 8192, 0, 1, 0), p) == 0
+    assert mdh.mdh_validate_params(mdh.MDH_BMATMUL, (1, 16, 1000, 8192, 0, 0, 0), p) == 6
+    # a small transposed B, or one with enough columns to fill the chip: strips of ONE block column, all of
+    # k inside the workgroup (rounds of 128 k per wavefront), nothing combined between workgroups
+    for sizes in ((1, 16, 1000, 2048, 0, 1, 0), (1, 16, 4096, 25088, 0, 1, 0)):
+        p = mdh.mdh_default_params(mdh.MDH_BMATMUL, sizes)
+        assert list(p.blk[:4]) == [1, 16, 16, 4] and p.prt[B.L_VGPR][2] == 1 and p.prt[B.L_VGPR][3] == 32
+        assert p.prt[B.L_WG][2] == -(-sizes[2] // 16) and p.prt[B.L_WG][3] == 1 and p.prt[B.L_WAVE][3] == 8
+        assert mdh.mdh_workspace_size(mdh.MDH_BMATMUL, sizes, p) == 0
+        assert mdh.mdh_validate_params(mdh.MDH_BMATMUL, sizes, p) == 0
+        q = p.copy()
+        q.prt[B.L_WG][3] = 2  # narrow strips do not split k over workgroups
+        assert mdh.mdh_validate_params(mdh.MDH_BMATMUL, sizes, q) != 0
+    # the same strips are a candidate for the plain view
+    sizes = (1, 16, 1000, 2048, 0, 0, 0)
+    narrow = [c for c in (mdh.mdh_candidate(mdh.MDH_BMATMUL, sizes, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_BMATMUL, sizes)))
+              if c.blk[1] == 16 and c.prt[B.L_VGPR][2] == 1]
+    assert sorted(c.prt[B.L_WAVE][3] for c in narrow) == [8, 16]
+    assert all(mdh.mdh_validate_params(mdh.MDH_BMATMUL, sizes, c) == 0 for c in narrow)
     # A or C transposed, or more rows: the LDS-tiled kernel
     for sizes in ((1, 16, 1000, 2048, 1, 0, 0), (1, 16, 1000, 2048, 0, 0, 1), (1, 17, 1000, 2048, 0, 0, 0)):
         p = mdh.mdh_default_params(mdh.MDH_BMATMUL, sizes)
@@ -149,6 +167,33 @@ def test_small_m_every_candidate(shape):
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("tb", [False, True])
+@pytest.mark.parametrize("shape", [(1, 16, 1000, 2048), (2, 5, 1000, 2085), (2, 5, 77, 100), (1, 16, 16, 128),
+                                   (3, 13, 250, 4226), (1, 1, 1, 1), (1, 16, 4096, 1024), (1, 9, 33, 127)])
+def test_small_m_narrow_strips(shape, tb):
+    # strips of one block column, k over the wavefronts of a workgroup in rounds of 128: whole rounds and
+    # a ragged last one, a ragged last strip, fewer than 16 rows, fewer rounds than wavefronts, batches;
+    # both views of B, 8 and 16 wavefronts; NaN-filled output shows every element is written
+    nb, M, N, K = shape
+    A = W.uniform(W.SEED_BASE + 68, 1, (nb, M, K), -1, 1)
+    Bm = W.uniform(W.SEED_BASE + 68, 2, (nb, N, K) if tb else (nb, K, N), -1, 1)
+    ref, refabs = reference(A, Bm, False, tb, False)
+    sizes = (nb, M, N, K, 0, int(tb), 0)
+    cands = [mdh.mdh_candidate(mdh.MDH_BMATMUL, sizes, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_BMATMUL, sizes))]
+    d = mdh.mdh_default_params(mdh.MDH_BMATMUL, sizes)
+    narrow = [p for p in [d] + cands if p.blk[1] == 16 and p.prt[B.L_VGPR][2] == 1]
+    assert sorted(set(p.prt[B.L_WAVE][3] for p in narrow)) == [8, 16]
+    for p in narrow:
+        assert mdh.mdh_workspace_size(mdh.MDH_BMATMUL, sizes, p) == 0
+        got, _ = run(A, Bm, False, tb, False, p)
+        assert np.all(np.isfinite(got)), p.table()
+        err = float(np.max(np.abs(got - ref) / np.where(refabs > 0, refabs, 1.0)))
+        assert err <= TOL, (shape, tb, p.table())
+        again, _ = run(A, Bm, False, tb, False, p)
+        assert np.array_equal(got, again)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("tb", [False, True])
 def test_small_m_one_launch_and_second_kernel_agree_bit_for_bit(tb):
     # a reduction split over workgroups is combined by the last part of a strip to arrive (the default:
     # out_region = device memory) or by a second kernel (out_region = registers): same order, same bits;
@@ -158,6 +203,9 @@ def test_small_m_one_launch_and_second_kernel_agree_bit_for_bit(tb):
         Bm = W.uniform(W.SEED_BASE + 66 + rep, 2, (nb, N, K) if tb else (nb, K, N), -1, 1)
         sizes = (nb, M, N, K, 0, int(tb), 0)
         d = mdh.mdh_default_params(mdh.MDH_BMATMUL, sizes)
+        if d.prt[B.L_WG][3] == 1:  # the default is the kernel with narrow strips: take the first candidate that splits k
+            cands = [mdh.mdh_candidate(mdh.MDH_BMATMUL, sizes, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_BMATMUL, sizes))]
+            d = next(c for c in cands if c.blk[1] == 16 and c.prt[B.L_WG][3] > 1 and c.out_region == B.MR_HBM)
         assert d.blk[1] == 16 and d.prt[B.L_WG][3] > 1 and d.out_region == B.MR_HBM, (sizes, d.table())
         second = d.copy()
         second.out_region = B.MR_VGPR
