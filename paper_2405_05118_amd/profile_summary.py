@@ -175,16 +175,21 @@ def main(argv):
              "SQ_LDS_BANK_CONFLICT", "SQ_INSTS_VALU", "SQ_WAIT_INST_ANY", "GRBM_GUI_ACTIVE"]
     lines = []
     per_pair = {}
+    calib_listed = False  # the calibration loops run in every pass: their rows are listed once
     for wl in workloads:
         s, _ = counters(root, "sq", wl)
         insts = 0.0
+        has_calib = any("calib" in key[0] for key in s)
         for key, v in s.items():
             gui = v.get("GRBM_GUI_ACTIVE", 0.0)
             busy = v.get("SQ_VALU_MFMA_BUSY_CYCLES", 0.0) / (1024 * gui / 8) if gui else 0.0
             valu = v.get("SQ_INSTS_VALU", 0.0) * 4 / (1024 * gui / 8) if gui else 0.0
+            if "calib" in key[0] and calib_listed:
+                continue
             lines.append("| %s | %s | %d | %s | %.3f | %.3f |" % (wl, key[0], key[1], " | ".join("%.4g" % v.get(n, 0.0) for n in names), busy, valu))
             if "calib" not in key[0]:
                 insts += v.get("SQ_INSTS_VALU", 0.0)
+        calib_listed = calib_listed or has_calib
         if wl in PAIRS:
             per_pair[wl] = round(insts * 64 / PAIRS[wl], 3)
     with open(os.path.join(ROOT, "profiles", "all_workloads_mfma_lds_valu_pmc.md"), "w") as fh:
@@ -192,7 +197,7 @@ def main(argv):
                  "One pass per workload W (8 SQ counters + 1 GRBM counter):\n\n"
                  "    rocprofv3 --pmc " + " ".join(names) + " --output-format csv -d gpurun_out/profile/sq/W -o p -- " + cmd + " --steps 5 --warmup 1 --valu-kinds\n\n"
                  "Means per dispatch, summed over the chip by the profiler (`--valu-kinds` also runs the calibration loop of every\n"
-                 "instruction kind once).  The last two columns: MFMA pipe busy = SQ_VALU_MFMA_BUSY_CYCLES / (1024 SIMDs x\n"
+                 "instruction kind once in every pass; their rows are listed with the first workload only).  The last two columns: MFMA pipe busy = SQ_VALU_MFMA_BUSY_CYCLES / (1024 SIMDs x\n"
                  "GRBM_GUI_ACTIVE / 8 XCDs), and VALU instructions x 4 cycles over the same SIMD cycles -- above 1.0 where the\n"
                  "instruction kinds that issue in about 2 cycles dominate.\n\n"
                  "| workload | kernel | workgroups | " + " | ".join(names) + " | MFMA busy | VALU insts x 4 / SIMD cycles |\n|---|---|---|" + "---|" * (len(names) + 2) + "\n"
