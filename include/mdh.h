@@ -117,8 +117,11 @@ enum { MDH_MR_HBM = 0, MDH_MR_LDS = 1, MDH_MR_VGPR = 2 };
  *            parallelism: a core owns one contiguous part), 1 = strided.
  *            A real choice for MDH_DOT and MDH_MATVEC (lane assignment of the
  *            reduction dimension; both values run, blocked is the slow one) and for
- *            mdh_custom_* (walk order of the sequential parts); the other
- *            instances have one assignment per kernel and reject the other value.
+ *            mdh_custom_* (walk order of the sequential parts), and for the few-channel
+ *            kernel of MDH_MCC (blk[c] = 1): 0 = a workgroup owns a run of column tiles,
+ *            1 = the tiles of (n, p, q) are dealt out one at a time, in arrival order, to
+ *            the workgroups resident on the chip.  The other instances have one
+ *            assignment per kernel and reject the other value.
  * lane_fast_dim  which md_hom dimension follows the fastest lane index (the
  *            paper's swizzle choice; decides coalescing).  A real choice for
  *            mdh_custom_*; fixed per kernel elsewhere (the contiguous dimension).
@@ -131,6 +134,13 @@ enum { MDH_MR_HBM = 0, MDH_MR_LDS = 1, MDH_MR_VGPR = 2 };
  *            a reduction split over workgroups: out_region HBM (the last workgroup
  *            part to arrive combines the parts in device memory, one launch) or VGPR
  *            (a second kernel does).  Other values: MDH_ERR_UNSUPPORTED.
+ *
+ * Counters inside the library.  The one-launch combination (out_region = MDH_MR_HBM) and
+ * the dealt tiles of the few-channel MCC (strided = 1) count arrivals / hand out tickets
+ * in small counter arrays that live in the library's device image; every launch leaves
+ * them at zero.  Two such calls that overlap on one GPU (different streams or threads)
+ * would share them: order such calls, or choose the other variant (out_region =
+ * MDH_MR_VGPR, strided = 0), which uses nothing but the caller's buffers.
  * in_transposed[b] / out_transposed  parameters D4/S4, R4/S6 for 2-D tiles:
  *            for MDH_BMATMUL they are the views of the call (and must equal its
  *            flags); the other instances have plain layouts only.
@@ -416,7 +426,12 @@ mdh_status mdh_matvec(int64_t M, int64_t K, const float* A, const float* x, floa
  * Two kernels: blk = (1,32,32,2), LDS-tiled, any views; blk = (1,16,16,4) for M <= 16
  * with A and C plain (B plain or transposed), which streams both operands from
  * device memory straight into MFMA operand registers and parallelises k over
- * wavefronts and workgroups (the library default for those shapes).
+ * wavefronts and workgroups (the library default for those shapes).  That kernel
+ * has two strip widths: prt[MDH_L_VGPR][j] = 4 (a wavefront owns 64 columns; k may
+ * be split over workgroups, combined as out_region says) and prt[MDH_L_VGPR][j] = 1
+ * (a workgroup owns 16 columns and all of k: prt[MDH_L_WG][k] = 1, 8 or 16
+ * wavefronts along k, no workspace; the default for trans_b when the strips fill
+ * the chip or K <= 3072).
  */
 mdh_status mdh_matmul_ex(int64_t batch, int64_t M, int64_t N, int64_t K, const float* A,
                          int32_t trans_a, const float* B, int32_t trans_b, float* C,

@@ -39,6 +39,9 @@ struct MccPlan {
   int flat;    // 1: few-channel kernel that walks s and c as one fused dimension (TQ = block width)
   int QT = 1;  // few-channel kernel: column tiles a workgroup walks with its filter slice resident
   int S = 1;   // channel-chunked kernel: workgroup-layer parts of the reduction dimension c
+  // few-channel kernel: 1 = the workgroup-layer parts of (n, p, q) are dealt out to resident workgroups in
+  // arrival order (QT = 1), 0 = a workgroup owns QT consecutive column tiles
+  int dealt = 0;
 };
 
 // Custom reduce: RA records of A per lane, WB wavefronts of a workgroup split B,

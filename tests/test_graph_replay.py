@@ -58,12 +58,21 @@ def test_sequence_of_calls_replays_from_a_graph():
     assert mdh.mdh_default_params(mdh.MDH_DOT, (n_dot,)).out_region == 0
     ws_d, ws_p = _ws(mdh.MDH_DOT, (n_dot,)), _ws(mdh.MDH_CUSTOM_REDUCE, (nA, nB, 8))
     assert ws_s is not None and ps.prt[3][1] > 1
+    # few-channel MCC with its tiles dealt out by a ticket counter (inside the library, left at zero by every
+    # launch): 24 images of 99 x 163 x 3, 5 x 5 filter, stride 2 -- more tiles than resident workgroups
+    cN, cH, cW, cC, cK, cR = 24, 99, 163, 3, 40, 5
+    cP, cQ = (cH - cR) // 2 + 1, (cW - cR) // 2 + 1
+    c_sizes = (cN, cP, cQ, cK, cC, cR, cR, 2, 2)
+    pc = next(p for p in (mdh.mdh_candidate(mdh.MDH_MCC, c_sizes, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_MCC, c_sizes)))
+              if p.blk[4] == 1 and p.strided == 1)
+    cx = torch.empty((cN, cH, cW, cC), device="cuda")
+    cf = torch.empty((cK, cR, cR, cC), device="cuda")
 
     def outputs():
         return [torch.full((M, N), float("nan"), device="cuda"), torch.full((1, n_scan), float("nan"), device="cuda"),
                 torch.full((1,), float("nan"), device="cuda"), torch.full((nx, nx, nx), float("nan"), device="cuda"),
                 torch.full((nA,), -1, dtype=torch.int32, device="cuda"), torch.full((nA,), -1, dtype=torch.int32, device="cuda"),
-                torch.full((Ms, Ns), float("nan"), device="cuda")]
+                torch.full((Ms, Ns), float("nan"), device="cuda"), torch.full((cN, cP, cQ, cK), float("nan"), device="cuda")]
 
     def calls(o):
         mdh.mdh_matmul(a, b, o[0], pm, ws_m)
@@ -72,6 +81,7 @@ def test_sequence_of_calls_replays_from_a_graph():
         mdh.mdh_dot(xd, yd, o[2], None, ws_d)
         mdh.mdh_stencil(g3, o[3], 0.5, 1.0 / 12.0)
         mdh.mdh_custom_reduce(A8, B8, wp, wm, o[4], o[5], None, ws_p)
+        mdh.mdh_mcc(cx, cf, o[7], (2, 2), pc)
 
     def fill(seed):
         a.copy_(dev(W.uniform(seed, 1, (M, K), -1, 1)))
@@ -84,6 +94,8 @@ def test_sequence_of_calls_replays_from_a_graph():
         b_s.copy_(dev(W.uniform(seed, 10, (Ks, Ns), -1, 1)))
         A8.copy_(dev(W.integers(seed, 7, (nA, 8), 0, 3)))
         B8.copy_(dev(W.integers(seed, 8, (nB, 8), 0, 3)))
+        cx.copy_(dev(W.uniform(seed, 11, (cN, cH, cW, cC), -1, 1)))
+        cf.copy_(dev(W.uniform(seed, 12, (cK, cR, cR, cC), -1, 1)))
 
     fill(W.SEED_BASE + 90)
     side = torch.cuda.Stream()
@@ -114,3 +126,5 @@ def test_sequence_of_calls_replays_from_a_graph():
             assert float(np.max(np.abs(out_g[0].cpu().numpy() - ref) / refabs)) <= 1e-4
             ref, refabs = oracle.matmul(a_s.cpu().numpy(), b_s.cpu().numpy(), with_abs=True)
             assert float(np.max(np.abs(out_g[6].cpu().numpy() - ref) / refabs)) <= 1e-4
+            ref, refabs = oracle.mcc(cx.cpu().numpy(), cf.cpu().numpy(), (2, 2), with_abs=True)
+            assert float(np.max(np.abs(out_g[7].cpu().numpy() - ref) / refabs)) <= 1e-4

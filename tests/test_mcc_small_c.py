@@ -30,16 +30,27 @@ def test_default_fuses_s_and_c_for_few_channels():
         assert mdh.mdh_validate_params(mdh.MDH_MCC, s, p) == 0
         for d in range(7):
             assert p.extent(d) >= s[d] if p.ragged else p.extent(d) == s[d]
-    # ResNet's 112 output columns are 7 blocks of 16, not a multiple of 32: no ragged columns; with a
-    # batch of 16 a workgroup walks the whole row of tiles with its filter slice resident
+    # ResNet's 112 output columns are 7 blocks of 16, not a multiple of 32: no ragged columns
     s = sizes_of(1, 230, 230, 3, 64, 7, 7, (2, 2))
     p = mdh.mdh_default_params(mdh.MDH_MCC, s)
-    assert p.blk[2] == 16 and p.extent(2) == 112 and p.prt[B.L_HBM][2] == 1
+    assert p.blk[2] == 16 and p.extent(2) == 112 and p.prt[B.L_HBM][2] == 1 and p.strided == 0
+    # with a batch of 16 the tiles (16 x 16 pixels x 32 channels) are dealt out one at a time to the
+    # workgroups resident on the chip (strided = 1: parts of (n, p, q) not owned by position)
     s = sizes_of(16, 230, 230, 3, 64, 7, 7, (2, 2))
     p = mdh.mdh_default_params(mdh.MDH_MCC, s)
-    assert p.blk[2] == 16 and p.extent(2) == 112 and p.prt[B.L_HBM][2] == 7 and p.prt[B.L_WG][2] == 1
+    assert p.blk[2] == 16 and p.extent(2) == 112 and p.strided == 1
+    assert p.prt[B.L_HBM][2] == 1 and p.prt[B.L_WG][2] == 7 and p.prt[B.L_WG][1] == 7 and p.prt[B.L_WG][3] == 2
+    assert mdh.mdh_validate_params(mdh.MDH_MCC, s, p) == 0
+    q = p.copy()
+    q.prt[B.L_HBM][2], q.prt[B.L_WG][2] = 7, 1  # dealt tiles are single column tiles
+    assert mdh.mdh_validate_params(mdh.MDH_MCC, s, q) != 0
     cands = [mdh.mdh_candidate(mdh.MDH_MCC, s, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_MCC, s))]
     assert any(c.blk[2] == 32 and c.extent(2) == 128 for c in cands)
+    # the owned variant (a workgroup walks the whole row of 7 tiles with its filter slice resident) stays
+    # a candidate, and the default of the 3 x 3 filters (6 steps per tile)
+    assert any(c.blk[4] == 1 and c.strided == 0 and c.prt[B.L_HBM][2] == 7 and c.prt[B.L_WG][2] == 1 for c in cands)
+    v = mdh.mdh_default_params(mdh.MDH_MCC, sizes_of(16, 226, 226, 3, 64, 3, 3, (1, 1)))
+    assert v.blk[4] == 1 and v.strided == 0 and v.prt[B.L_HBM][2] > 1
     # many channels keep the channel-chunked kernel
     p = mdh.mdh_default_params(mdh.MDH_MCC, (16, 224, 224, 128, 64, 7, 7, 1, 1))
     assert p.blk[4] == 2
@@ -89,6 +100,33 @@ def test_small_all_candidates(case):
         assert np.all(np.isfinite(got)), "output not fully overwritten"
         err = float(np.max(np.abs(got - ref) / np.where(refabs > 0, refabs, 1.0)))
         assert err <= TOL, (case, p and p.table(), p and list(p.blk))
+
+
+@pytest.mark.gpu
+def test_dealt_tiles_draw_tickets_and_leave_the_counters_at_zero():
+    # more tiles than resident workgroups: all but the first two tiles of a workgroup come from the ticket
+    # counter of its filter slice (two slices here, the second ragged).  Every dealt candidate against the
+    # oracle and bit for bit against the owned-tile default; calls of other shapes in between and a second
+    # round show that every call leaves the counters at zero.
+    N, H, Wd, C, K, R, S, stride = 40, 99, 163, 3, 40, 5, 5, (2, 2)
+    x, f = W.mcc_inputs(W.MccCfg(N, H, Wd, C, K, R, S, stride, W.SEED_BASE + 74))
+    ref, refabs = oracle.mcc(x, f, stride, with_abs=True)
+    s = sizes_of(N, H, Wd, C, K, R, S, stride)
+    cands = [mdh.mdh_candidate(mdh.MDH_MCC, s, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_MCC, s))]
+    dealt = [p for p in cands if p.blk[4] == 1 and p.strided == 1]
+    owned = [p for p in cands if p.blk[4] == 1 and p.strided == 0]
+    assert len(dealt) >= 6 and owned
+    for p in dealt:  # more tiles than a launch keeps resident (at most 4 workgroups per compute unit)
+        assert p.prt[B.L_WG][0] * p.prt[B.L_WG][1] * p.prt[B.L_WG][2] * p.prt[B.L_WG][3] > 1024
+    base = run(x, f, stride, owned[0])
+    assert float(np.max(np.abs(base - ref) / np.where(refabs > 0, refabs, 1.0))) <= TOL
+    xs, fs = W.mcc_inputs(W.MccCfg(3, 21, 40, 3, 32, 3, 3, (2, 2), W.SEED_BASE + 75))
+    small_ref = run(xs, fs, (2, 2), None)
+    for rnd in range(2):
+        for p in dealt:
+            got = run(x, f, stride, p)
+            assert np.array_equal(got, base), (rnd, p.table(), list(p.blk))
+            assert np.array_equal(run(xs, fs, (2, 2), None), small_ref)
 
 
 @pytest.mark.gpu
