@@ -262,6 +262,15 @@ __device__ __forceinline__ void store_tile(float* obase, const f16 (&acc)[MI][NI
     const int p = prow0 + mi * Cf::RB;
     if (p >= P || q >= Q) continue;
     float* o = obase + (p * Q + q) * K;
+    if (kw0 + NI * 32 <= K) {  // wavefront-uniform: every channel of the wavefront's blocks exists
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *(f4u*)(o + kw0 + ni * 32 + 8 * g + 4 * lh) = (f4){acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1],
+                                                          acc[mi][ni][4 * g + 2], acc[mi][ni][4 * g + 3]};
+      continue;
+    }
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
@@ -335,11 +344,11 @@ __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
 
     f16 acc[MI][NI];
     walk_tile<Cf, MI, NI>(ps + aoff, brow, R, SCP, PWF, PFR, sh, acc);
-    store_tile<Cf, MI, NI>(obase, acc, p0 + wm * MI * Cf::RB + dp, q0 + dq, k0 + wn * NI * 32, lh, P, Q, K);
-
     // the next tile's patch goes to the other buffer (its last readers passed the barrier of the
-    // previous iteration)
+    // previous iteration) BEFORE this tile's results are stored: the wait for the patch loads would
+    // otherwise also wait for the stores issued after them (one in-order counter for both)
     if (more) pp.store(ps0 + ((t + 1) & 1) * PH * PWF, po, pv);
+    store_tile<Cf, MI, NI>(obase, acc, p0 + wm * MI * Cf::RB + dp, q0 + dq, k0 + wn * NI * 32, lh, P, Q, K);
     __syncthreads();
   }
 }
@@ -399,26 +408,32 @@ __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_dealt_kerne
   pp.store(ps0, po, pv);
   __syncthreads();
 
+  // (declared outside the loop: re-initialising the register every tile would make the compiler wait for
+  // the patch loads just issued -- it keeps writes to a register with a pending atomic in order by waiting)
+  unsigned ticket = 0;
   for (int it = 0;; ++it) {
     const bool more = nxt < units;  // workgroup-uniform
     if (more) {  // in flight while this tile is computed
       po = origin(nxt);
       pp.load(po, pv);
     }
-    unsigned ticket = 0;
     if (more && tid == 0) ticket = __builtin_amdgcn_atomic_inc32(&g_flat_tickets[tk], grabs - 1u, __ATOMIC_RELAXED, "agent");
 
     const int tq = cur % tq_n, band = cur / tq_n;
     const int tp = band % tp_n, n = band / tp_n;
     f16 acc[MI][NI];
     walk_tile<Cf, MI, NI>(ps0 + (it & 1) * PH * PWF + aoff, brow, R, SCP, PWF, PFR, sh, acc);
+    // the next tile's patch goes to the other buffer (its last readers passed the barrier of the
+    // previous iteration) BEFORE this tile's results are stored: the wait for the patch loads would
+    // otherwise also wait for the stores issued after them (one in-order counter for both).  The tile
+    // after the next: ticket t is unit 2G + t.
+    if (more) {
+      pp.store(ps0 + ((it + 1) & 1) * PH * PWF, po, pv);
+      if (tid == 0) next_unit[it & 1] = 2 * G + (int)ticket;
+    }
     store_tile<Cf, MI, NI>(out + (int64_t)n * P * Q * K, acc, tp * Cf::TP + wm * MI * Cf::RB + dp,
                            tq * Cf::TQ + dq, k0 + wn * NI * 32, lh, P, Q, K);
     if (!more) break;
-    // the next tile's patch goes to the other buffer (its last readers passed the barrier of the
-    // previous iteration); the tile after it: ticket t is unit 2G + t
-    pp.store(ps0 + ((it + 1) & 1) * PH * PWF, po, pv);
-    if (tid == 0) next_unit[it & 1] = 2 * G + (int)ticket;
     __syncthreads();
     cur = nxt;
     // (rewritten two iterations on, after every lane has passed the next barrier; the same value in
