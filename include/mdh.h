@@ -109,10 +109,14 @@ enum { MDH_MR_HBM = 0, MDH_MR_LDS = 1, MDH_MR_VGPR = 2 };
  *                equality)
  * order[]    parameters D1=S1=R1: the fused loop order, outermost first, each
  *            entry = l * MDH_MAX_D + d; only the first MDH_NUM_LAYERS*D entries
- *            are used.  Every kernel implements one order (workgroup parts,
+ *            are used.  The layers come in one order in every kernel (workgroup parts,
  *            then device-memory tiles, wavefront and lane parts, LDS and register
- *            parts; returned by mdh_default_params); any other order has no
- *            instantiation: MDH_ERR_UNSUPPORTED.
+ *            parts; returned by mdh_default_params).  A real choice inside the
+ *            workgroup layer of MDH_MATMUL's LDS-tiled kernel: (WG,i) before (WG,j) =
+ *            tiles dealt to the chip in bands of 8 tile rows, (WG,j) before (WG,i) =
+ *            in bands of 8 tile columns (which panels of A and B the tiles that run
+ *            together share).  Any other order has no instantiation:
+ *            MDH_ERR_UNSUPPORTED.
  * strided    parameters D2=S2=R2 restricted to two values: 0 = blocked (outer
  *            parallelism: a core owns one contiguous part), 1 = strided.
  *            A real choice for MDH_DOT and MDH_MATVEC (lane assignment of the

@@ -30,6 +30,10 @@ struct GemmPlan {
   // output).  > 1: the kernel whose WK wavefronts all own the whole BM x BN tile and split k, operands
   // straight from device memory to registers, results combined in LDS (then WM = BM, WN = BN, BK = 8).
   int WK = 1;
+  // LDS-tiled kernel, loop order of the workgroup layer (parameter D1): 0 = tiles walked in bands of 8 tile
+  // rows, i fastest inside a band (order (WG,i),(WG,j),(WG,k)); 1 = bands of 8 tile columns, j fastest
+  // (order (WG,j),(WG,i),(WG,k)).  Decides which panels of A and B the tiles resident together share.
+  int jmajor = 0;
 };
 
 // MCC: workgroup tile TP x TQ output pixels x BN output channels, CK channels per LDS stage.

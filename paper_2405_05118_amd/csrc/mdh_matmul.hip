@@ -226,11 +226,12 @@ __device__ __forceinline__ void gemm_tile(const float* __restrict__ A, const flo
 template <int BM, int BN, int BK, int WM, int WN>
 __global__ __launch_bounds__((GemmCfg<BM, BN, BK, WM, WN>::NT)) void matmul_kernel(
     const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C,
-    float* __restrict__ ws, int M, int N, int K, int tiles_m, int tiles_n, int S, int kchunk) {
+    float* __restrict__ ws, int M, int N, int K, int tiles_m, int tiles_n, int S, int kchunk, int jmajor) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   // XCD-aware tile order: workgroup ids are dealt round-robin to the 8 XCDs; hand each XCD a
   // contiguous run of tiles, walked in bands of 8 tile-rows so that the tiles resident on one
-  // XCD at a time share few panels of A and B in that XCD's L2.
+  // XCD at a time share few panels of A and B in that XCD's L2.  jmajor: the other loop order of the
+  // workgroup layer -- bands of 8 tile-columns, j fastest inside a band.
   int b = blockIdx.x;
   const int nb = gridDim.x;
   if ((nb & 7) == 0) b = (b & 7) * (nb >> 3) + (b >> 3);
@@ -238,11 +239,13 @@ __global__ __launch_bounds__((GemmCfg<BM, BN, BK, WM, WN>::NT)) void matmul_kern
   const int s = b / tiles;
   int t = b % tiles;
   constexpr int GM = 8;
-  const int band = t / (GM * tiles_n);
-  const int band_rows = min(GM, tiles_m - band * GM);
-  const int in_band = t - band * GM * tiles_n;
-  const int tm = band * GM + in_band % band_rows;
-  const int tn = in_band / band_rows;
+  const int fast_n = jmajor ? tiles_n : tiles_m, slow_n = jmajor ? tiles_m : tiles_n;  // banded / walked dimension
+  const int band = t / (GM * slow_n);
+  const int band_w = min(GM, fast_n - band * GM);
+  const int in_band = t - band * GM * slow_n;
+  const int tf = band * GM + in_band % band_w;
+  const int tsl = in_band / band_w;
+  const int tm = jmajor ? tsl : tf, tn = jmajor ? tf : tsl;
 
   const int m0 = tm * BM, n0 = tn * BN;
   const int kbeg = s * kchunk;
@@ -287,7 +290,7 @@ mdh_status launch_t(const GemmPlan& pl, int64_t M, int64_t N, int64_t K, const f
   if (nblocks > 0x7fffffff) return MDH_ERR_SIZE;
   clear_stale_error();
   hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(Cfg::NT), Cfg::LDS_BYTES, st, A, B, C,
-                     (float*)ws, (int)M, (int)N, (int)K, (int)tm, (int)tn, pl.S, (int)kchunk);
+                     (float*)ws, (int)M, (int)N, (int)K, (int)tm, (int)tn, pl.S, (int)kchunk, pl.jmajor);
   mdh_status r = launch_status();
   if (r != MDH_OK || pl.S <= 1) return r;
   const int64_t n = M * N;

@@ -272,6 +272,10 @@ void params_from_plan(const int64_t* s, const GemmPlan& pl, mdh_tile_params* p) 
   p->prt[MDH_L_VGPR][1] = pl.WN / 32;
   static const int dims[3] = {0, 1, 2};
   set_order(p, dims);
+  if (pl.jmajor) {  // workgroup layer: j before i
+    p->order[0] = (uint8_t)(MDH_L_WG * MDH_MAX_D + 1);
+    p->order[1] = (uint8_t)(MDH_L_WG * MDH_MAX_D + 0);
+  }
   p->strided = 0;
   p->lane_fast_dim = 1;
   p->in_region[0] = MDH_MR_LDS;
@@ -352,11 +356,18 @@ int matmul_candidates(const int64_t* s, GemmPlan* out, int cap) {
     pl.ragged = gemm_ragged(s, pl);
     for (int i = 0; i < n; ++i)
       if (out[i].BM == pl.BM && out[i].BN == pl.BN && out[i].BK == pl.BK && out[i].WM == pl.WM &&
-          out[i].S == pl.S && out[i].WK == pl.WK)
+          out[i].S == pl.S && out[i].WK == pl.WK && out[i].jmajor == pl.jmajor)
         return;
     out[n++] = pl;
   };
   push(gemm_default(s));
+  {  // the default's tile with the other loop order of the workgroup layer (column bands)
+    GemmPlan d = gemm_default(s);
+    if (d.WK == 1 && cdiv(s[0], d.BM) > 1 && cdiv(s[1], d.BN) > 1) {
+      d.jmajor = !d.jmajor;
+      push(d);
+    }
+  }
   // k over the wavefronts of a workgroup, for outputs of few tiles (every wavefront keeps 8 k or more)
   if (cdiv(s[0], 32) * cdiv(s[1], 32) <= 1024)
     for (auto& m : kGemmKsplitMenu)
@@ -417,6 +428,9 @@ mdh_status plan_matmul(const int64_t* s, const mdh_tile_params* p, GemmPlan* out
   pl.BK = p->prt[MDH_L_LDS][2] * 2;
   pl.S = p->prt[MDH_L_WG][2];
   pl.ragged = ragged;
+  // parameter D1 on the workgroup layer: (WG,j) before (WG,i) selects the column-band tile order; any
+  // other permutation has no instantiation (the regenerated table below differs)
+  pl.jmajor = (p->order[0] == MDH_L_WG * MDH_MAX_D + 1 && p->order[1] == MDH_L_WG * MDH_MAX_D + 0) ? 1 : 0;
   if (p->blk[0] != 32 || p->blk[1] != 32 || p->blk[2] != 2) return MDH_ERR_UNSUPPORTED;
   if (gemm_lds_bytes(pl.BM, pl.BN, pl.BK) > kLdsBytesPerWG) return MDH_ERR_TILE_RESOURCES;
   if ((int64_t)p->prt[MDH_L_WAVE][0] * p->prt[MDH_L_WAVE][1] * 64 > kMaxLanesPerWG)

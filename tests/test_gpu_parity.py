@@ -71,6 +71,29 @@ def test_matmul_small_all_candidates(shape):
         assert scaled_err(got, ref, refabs) <= TOL_CONTRACTION, (shape, p and p.table())
 
 
+@pytest.mark.parametrize("shape", [(1300, 1100, 96), (2200, 700, 64), (640, 2304, 40)])
+def test_matmul_both_loop_orders_of_the_workgroup_layer(shape):
+    # more than one band of eight tile rows / tile columns, ragged last band, ragged tiles: the two
+    # orders assign the same tiles to other workgroups -- same arithmetic per element, same bits
+    M, N, K = shape
+    A, Bm = W.matmul_inputs(W.MatmulCfg(M, N, K, W.SEED_BASE + 13))
+    ref, refabs = oracle.matmul(A, Bm, with_abs=True)
+    wg = B.L_WG * B.MDH_MAX_D
+    for tile in ((128, 128), (64, 64)):
+        cands = [c for c in candidates(mdh.MDH_MATMUL, shape)[1:]
+                 if c.prt[B.L_WAVE][2] == 1 and c.prt[B.L_WG][2] == 1 and c.extent(0) // c.prt[B.L_WG][0] == tile[0]
+                 and c.extent(1) // c.prt[B.L_WG][1] == tile[1] and list(c.order[:2]) == [wg + 0, wg + 1]]
+        assert cands, tile
+        p = cands[0]
+        q = p.copy()
+        q.order[0], q.order[1] = wg + 1, wg + 0
+        assert mdh.mdh_validate_params(mdh.MDH_MATMUL, shape, q) == 0
+        got_i, got_j = run_matmul(A, Bm, p), run_matmul(A, Bm, q)
+        assert np.all(np.isfinite(got_j))
+        assert scaled_err(got_i, ref, refabs) <= TOL_CONTRACTION
+        assert np.array_equal(got_i, got_j), (shape, tile)
+
+
 @pytest.mark.parametrize("shape", [(256, 256, 256), (300, 200, 100), (129, 65, 33), (70, 260, 1030), (33, 47, 17),
                                    (17, 16, 4096), (200, 300, 500), (512, 512, 512)])
 def test_matmul_k_on_the_wavefront_layer_every_candidate(shape):

@@ -145,6 +145,30 @@ def test_resource_and_support_limits():
     assert mdh.mdh_validate_params(mdh.MDH_STENCIL, s, q) == E_UNSUP
 
 
+def test_matmul_loop_order_of_the_workgroup_layer_is_a_choice():
+    # parameter D1: (WG,i),(WG,j) = bands of tile rows (default), (WG,j),(WG,i) = bands of tile columns;
+    # both run on the LDS-tiled kernel, every other permutation has no instantiation
+    s = (4096, 4096, 4096)
+    p = mdh.mdh_default_params(mdh.MDH_MATMUL, s)
+    wg = B.L_WG * B.MDH_MAX_D
+    assert list(p.order[:3]) == [wg + 0, wg + 1, wg + 2]
+    q = p.copy()
+    q.order[0], q.order[1] = wg + 1, wg + 0
+    assert mdh.mdh_validate_params(mdh.MDH_MATMUL, s, q) == 0
+    cands = [mdh.mdh_candidate(mdh.MDH_MATMUL, s, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_MATMUL, s))]
+    assert any(list(c.order[:3]) == [wg + 1, wg + 0, wg + 2] and c.table() == p.table() for c in cands)
+    q = p.copy()
+    q.order[0], q.order[2] = wg + 2, wg + 0  # k outermost
+    assert mdh.mdh_validate_params(mdh.MDH_MATMUL, s, q) == E_UNSUP
+    q = p.copy()
+    q.order[3], q.order[4] = q.order[4], q.order[3]  # the memory layer: one order only
+    assert mdh.mdh_validate_params(mdh.MDH_MATMUL, s, q) == E_UNSUP
+    # a single row or column of tiles: nothing to choose, no such candidate
+    s = (65536, 64, 4096)
+    cands = [mdh.mdh_candidate(mdh.MDH_MATMUL, s, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_MATMUL, s))]
+    assert all(list(c.order[:2]) == [wg + 0, wg + 1] for c in cands)
+
+
 def test_workspace_only_for_split_reductions():
     s = (65536, 64, 4096)
     for i in range(mdh.mdh_num_candidates(mdh.MDH_MATMUL, s)):
