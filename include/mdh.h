@@ -128,7 +128,10 @@ enum { MDH_MR_HBM = 0, MDH_MR_LDS = 1, MDH_MR_VGPR = 2 };
  *            assignment per kernel and reject the other value.
  * lane_fast_dim  which md_hom dimension follows the fastest lane index (the
  *            paper's swizzle choice; decides coalescing).  A real choice for
- *            mdh_custom_*; fixed per kernel elsewhere (the contiguous dimension).
+ *            mdh_custom_* and for MDH_MATVEC (1 = lanes along k, the contiguous
+ *            dimension of A: the default; 0 = lanes along i, a lane owns a row and walks
+ *            all of k -- loads that do not coalesce, 5.6 times slower at 16384 x 16384);
+ *            fixed per kernel elsewhere (the contiguous dimension).
  * in_region[b] / out_region   parameters D3/S3 and R3/S5: the fastest memory
  *            region input buffer b is staged in / results are combined in.  Real
  *            choices: MDH_MATMUL in_region LDS (wavefronts tile the output, operands

@@ -82,6 +82,9 @@ struct MatVecPlan {
   int S;
   int ragged;
   int strided = 1;  // lanes interleave 4-element parts of k (1) or own one contiguous part each (0)
+  // 1: the lanes run along i (a lane owns a row and walks all of k; lane_fast_dim = 0) -- the assignment
+  // whose loads of A do not coalesce; RM = 1, WM = 4, WK = 1, S = 1
+  int rowlanes = 0;
 };
 
 // Row-wise scan: a workgroup owns one chunk of one row = TPC sequential tiles of WAVES*256

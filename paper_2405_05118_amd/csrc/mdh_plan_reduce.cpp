@@ -113,6 +113,22 @@ static bool matvec_inst(const MatVecPlan& pl) {
 
 void params_from_plan(const int64_t* s, const MatVecPlan& pl, mdh_tile_params* p) {
   clear_params(p, 2);  // dims: 0 i, 1 k
+  if (pl.rowlanes) {  // lanes along i: 4 wavefronts x 64 rows per workgroup, a lane walks all of k in steps of 4
+    p->prt[MDH_L_WG][0] = (int32_t)cdiv(s[0], 256);
+    p->prt[MDH_L_WAVE][0] = 4;
+    p->prt[MDH_L_LANE][0] = 64;
+    p->prt[MDH_L_VGPR][1] = 4;
+    p->prt[MDH_L_HBM][1] = (int32_t)cdiv(s[1], 4);
+    static const int rdims[2] = {0, 1};
+    set_order(p, rdims);
+    p->strided = 0;
+    p->lane_fast_dim = 0;
+    p->in_region[0] = MDH_MR_VGPR;
+    p->in_region[1] = MDH_MR_VGPR;
+    p->out_region = MDH_MR_VGPR;
+    p->ragged = (uint8_t)((s[0] % 256) || (s[1] % 4));
+    return;
+  }
   p->prt[MDH_L_WG][0] = (int32_t)cdiv(s[0], (int64_t)pl.WM * pl.RM);
   p->prt[MDH_L_WG][1] = pl.S;
   p->prt[MDH_L_WAVE][0] = pl.WM;
@@ -170,6 +186,14 @@ int matvec_candidates(const int64_t* s, MatVecPlan* out, int cap) {
   // the default's tile with the blocked lane assignment (parameter D2: every lane one contiguous part)
   d.strided = 0;
   push(d);
+  // lanes along i instead of k (the dimension that follows the fastest lane index)
+  if (n < cap) {
+    MatVecPlan r{1, 4, 1, 1, 0};
+    r.strided = 0;
+    r.rowlanes = 1;
+    r.ragged = (s[0] % 256) || (s[1] % 4);
+    out[n++] = r;
+  }
   return n;
 }
 
@@ -187,6 +211,15 @@ mdh_status plan_matvec(const int64_t* s, const mdh_tile_params* p, MatVecPlan* o
                 p->prt[MDH_L_WG][1], ragged};
   pl.strided = p->strided ? 1 : 0;
   mdh_tile_params chk;
+  if (p->lane_fast_dim == 0) {  // lanes along i
+    pl = MatVecPlan{1, 4, 1, 1, ragged};
+    pl.strided = 0;
+    pl.rowlanes = 1;
+    params_from_plan(s, pl, &chk);
+    if (!same_table(chk, *p)) return MDH_ERR_UNSUPPORTED;
+    *out = pl;
+    return MDH_OK;
+  }
   params_from_plan(s, pl, &chk);
   if (!same_table(chk, *p) || !matvec_inst(pl) || pl.S > 256) return MDH_ERR_UNSUPPORTED;
   *out = pl;

@@ -265,6 +265,26 @@ __global__ __launch_bounds__(WM* WK * 64) void matvec_kernel(const float* __rest
   }
 }
 
+// The other lane assignment (paper: Section "Generic Low-Level Expression", parameters D2 and the
+// choice of the dimension that follows the fastest lane index): lanes along i, a lane owns a row and
+// walks all of k.  A load instruction then touches 64 rows x 16 bytes: nothing coalesces.  Kept as a
+// selectable configuration (lane_fast_dim = 0), not as a default.
+__global__ __launch_bounds__(256) void matvec_rowlane_kernel(const float* __restrict__ A,
+                                                             const float* __restrict__ x,
+                                                             float* __restrict__ y, int M, int K) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  const float* row = A + (int64_t)min(i, M - 1) * K;
+  f4 acc = (f4){0.f, 0.f, 0.f, 0.f};
+  int k = 0;
+  for (; k + 3 < K; k += 4) {
+    const f4 av = *(const f4u*)(row + k), xv = *(const f4u*)(x + k);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(av[e], xv[e], acc[e]);
+  }
+  for (; k < K; ++k) acc[k & 3] = __builtin_fmaf(row[k], x[k], acc[k & 3]);
+  if (i < M) y[i] = hsum(acc);
+}
+
 // Second pass: y[i] = part_0[i] + part_1[i] + ... in that order.
 __global__ __launch_bounds__(256) void matvec_combine_kernel(const float* __restrict__ ws,
                                                              float* __restrict__ y, int M, int S) {
@@ -310,6 +330,12 @@ mdh_status launch_dot(const DotPlan& pl, int64_t K, const float* x, const float*
 
 mdh_status launch_matvec(const MatVecPlan& pl, int64_t M, int64_t K, const float* A, const float* x,
                          float* y, void* ws, hipStream_t st) {
+  if (pl.rowlanes) {
+    if (cdiv(M, 256) > 0x7fffffff || K > 0x7fffffff || M > 0x7fffffff) return MDH_ERR_SIZE;
+    clear_stale_error();
+    hipLaunchKernelGGL(matvec_rowlane_kernel, dim3((unsigned)cdiv(M, 256)), dim3(256), 0, st, A, x, y, (int)M, (int)K);
+    return launch_status();
+  }
 #define MDH_MV(rm, wm, wk) \
   if (pl.RM == rm && pl.WM == wm && pl.WK == wk) return launch_matvec_t<rm, wm, wk>(pl, M, K, A, x, y, ws, st);
   MDH_MV(4, 4, 1)

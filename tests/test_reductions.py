@@ -195,6 +195,16 @@ def test_assignment_and_combination_region_are_choices_of_the_table():
     q = one_part.copy()
     q.out_region = B.MR_HBM  # nothing to combine in device memory with a single part
     assert mdh.mdh_validate_params(mdh.MDH_DOT, (1000,), q) == 6
+    # the dimension that follows the fastest lane index: MatVec with the lanes along i (a lane owns a row)
+    s = (5000, 300)
+    cands = [mdh.mdh_candidate(mdh.MDH_MATVEC, s, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_MATVEC, s))]
+    rows = [c for c in cands if c.lane_fast_dim == 0]
+    assert len(rows) == 1 and rows[0].prt[B.L_LANE][0] == 64 and rows[0].prt[B.L_LANE][1] == 1
+    assert mdh.mdh_validate_params(mdh.MDH_MATVEC, s, rows[0]) == 0 and mdh.mdh_workspace_size(mdh.MDH_MATVEC, s, rows[0]) == 0
+    assert mdh.mdh_default_params(mdh.MDH_MATVEC, s).lane_fast_dim == 1
+    q = mdh.mdh_default_params(mdh.MDH_MATVEC, s)
+    q.lane_fast_dim = 0  # the default's partitioning has its lanes along k
+    assert mdh.mdh_validate_params(mdh.MDH_MATVEC, s, q) == 6
 
 
 @pytest.mark.gpu
@@ -234,4 +244,10 @@ def test_blocked_lane_assignment_matches_the_oracle():
     p = _variant(mdh.MDH_MATVEC, (M, Kc), mdh.mdh_default_params(mdh.MDH_MATVEC, (M, Kc)), strided=0)
     yv = torch.full((M,), float("nan"), dtype=torch.float32, device="cuda")
     mdh.mdh_matvec(dev(A), dev(xv), yv, p, ws_for(mdh.MDH_MATVEC, (M, Kc), p))
+    assert float(np.max(np.abs(yv.cpu().numpy() - ref) / refabs)) <= TOL
+    # lanes along i
+    cands = [mdh.mdh_candidate(mdh.MDH_MATVEC, (M, Kc), i) for i in range(mdh.mdh_num_candidates(mdh.MDH_MATVEC, (M, Kc)))]
+    p = next(c for c in cands if c.lane_fast_dim == 0)
+    yv = torch.full((M,), float("nan"), dtype=torch.float32, device="cuda")
+    mdh.mdh_matvec(dev(A), dev(xv), yv, p, None)
     assert float(np.max(np.abs(yv.cpu().numpy() - ref) / refabs)) <= TOL
