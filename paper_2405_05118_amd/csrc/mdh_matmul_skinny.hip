@@ -44,6 +44,7 @@ __global__ __launch_bounds__((WAVES_N * WAVES_K * 64)) void matmul_skinny_kernel
     float* __restrict__ ws, int M, int N, int K, int tiles_m, int tiles_n, int S, int kchunk,
     int nbatch, int fused) {
   __shared__ f4 part[WAVES_K > 1 ? (WAVES_K - 1) * WAVES_N * 4 * 64 : 1];
+  __shared__ unsigned last_flag;  // "this workgroup stored the last part of its strip", for all its wavefronts
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wn = wave % WAVES_N, wk = wave / WAVES_N;
@@ -138,6 +139,14 @@ __global__ __launch_bounds__((WAVES_N * WAVES_K * 64)) void matmul_skinny_kernel
 #pragma unroll
       for (int u = 0; u < SK_PF; ++u) mma(a[u], b[u]);
     }
+    // whole single steps (a part of k of one step per wavefront, or an odd number of them)
+    for (; k + 16 <= kend; k += KSTEP) {
+      f4 a1, b1[4];
+      a1 = arow_ok ? *(const f4u*)(ap + k) : (f4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) b1[tt] = __builtin_nontemporal_load((const f4u*)(bp + (int64_t)(k + tt) * N));
+      mma(a1, b1);
+    }
   }
   // remaining steps, ragged columns and the ragged end of k: every element predicated
   for (; k < kend; k += KSTEP) {
@@ -155,17 +164,23 @@ __global__ __launch_bounds__((WAVES_N * WAVES_K * 64)) void matmul_skinny_kernel
   }  // plain view of B
 
   // wavefront -> workgroup: the wavefronts that split k add their blocks in LDS, in a fixed order
+  // With one strip per workgroup the combination over workgroups (below) is done by all wavefronts of the
+  // last workgroup to arrive; they stay for it.
+  constexpr bool WG_FOLD = WAVES_N == 1 && WAVES_K >= 4;
+  const bool stay = WG_FOLD && S > 1 && fused;  // workgroup-uniform
   if (WAVES_K > 1) {
     if (wk > 0) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) part[(((wk - 1) * WAVES_N + wn) * 4 + c) * 64 + lane] = acc[c];
     }
     __syncthreads();
-    if (wk > 0) return;
+    if (wk > 0 && !stay) return;
+    if (wk == 0) {
 #pragma unroll
-    for (int w = 1; w < WAVES_K; ++w)
+      for (int w = 1; w < WAVES_K; ++w)
 #pragma unroll
-      for (int c = 0; c < 4; ++c) acc[c] += part[(((w - 1) * WAVES_N + wn) * 4 + c) * 64 + lane];
+        for (int c = 0; c < 4; ++c) acc[c] += part[(((w - 1) * WAVES_N + wn) * 4 + c) * 64 + lane];
+    }
   }
 
   // output view: register r of block c is C[m0 + 4g + r][col + c]; with the transposed view of B,
@@ -195,25 +210,66 @@ __global__ __launch_bounds__((WAVES_N * WAVES_K * 64)) void matmul_skinny_kernel
   }
 
   // workgroup layer -> grid in the same launch: the wavefront that stores the S-th partial strip adds
-  // all S of them, in ascending part order (the order of the second kernel: same bits), into C.  Only
-  // this wavefront is left in its workgroup for this strip; no barrier is involved.
+  // all S of them, in ascending part order (the order of the second kernel: same bits), into C.
   // (device-coherent single-word stores and loads instead of fences: see mdh_internal.h)
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int row = m0 + 4 * g + r;
-    if (row >= M) continue;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const int cc = TB ? n0 + 16 * c + l16 : col + c;
-      if (cc < N) coherent_store(out + (int64_t)row * N + cc, acc[c][r]);
-    }
-  }
-  wait_stores_done();  // the partial strip has reached the coherent level before it is counted
   unsigned last = 0;
-  if (lane == 0) last = arrive_last(&g_strip_arrivals[((unsigned)batch * tiles + t) * WAVES_N + wn], (unsigned)S);
-  if (!__builtin_amdgcn_readfirstlane(last)) return;
+  if (wk == 0) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = m0 + 4 * g + r;
+      if (row >= M) continue;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int cc = TB ? n0 + 16 * c + l16 : col + c;
+        if (cc < N) coherent_store(out + (int64_t)row * N + cc, acc[c][r]);
+      }
+    }
+    wait_stores_done();  // the partial strip has reached the coherent level before it is counted
+    if (lane == 0) last = arrive_last(&g_strip_arrivals[((unsigned)batch * tiles + t) * WAVES_N + wn], (unsigned)S);
+    last = __builtin_amdgcn_readfirstlane(last);
+  }
   const int64_t part_stride = (int64_t)nbatch * mn;
   const float* w0 = ws + (int64_t)batch * mn;
+  if (WG_FOLD) {
+    // All wavefronts of the last workgroup fold: wavefront w takes ROWS rows of the strip, a lane one
+    // column of them (consecutive lanes, consecutive addresses), and requests 16 parts of its elements
+    // together (each load is a round trip to the coherent level): a strip of S = 16 parts is one round
+    // instead of four.
+    if (wk == 0 && lane == 0) last_flag = last;
+    __syncthreads();
+    if (!last_flag) return;  // workgroup-uniform
+    constexpr int ROWS = 16 / WAVES_K;  // 4 or 2
+    constexpr int PR = 16;
+    const int rbase = m0 + wk * ROWS;
+    const int cc = n0 + lane;
+    float sum[ROWS];
+#pragma unroll
+    for (int e = 0; e < ROWS; ++e) sum[e] = 0.f;
+    for (int sp0 = 0; sp0 < S; sp0 += PR) {
+      float v[PR][ROWS];
+#pragma unroll
+      for (int u = 0; u < PR; ++u) {
+        const float* src = w0 + (int64_t)min(sp0 + u, S - 1) * part_stride;
+#pragma unroll
+        for (int e = 0; e < ROWS; ++e) {
+          const int row = min(rbase + e, M - 1);
+          v[u][e] = cc < N ? coherent_load(src + (int64_t)row * N + cc) : 0.f;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < PR; ++u) {
+        if (sp0 + u >= S) break;
+#pragma unroll
+        for (int e = 0; e < ROWS; ++e) sum[e] = (sp0 + u == 0) ? v[u][e] : sum[e] + v[u][e];
+      }
+    }
+    float* dst = C + (int64_t)batch * mn;
+#pragma unroll
+    for (int e = 0; e < ROWS; ++e)
+      if (rbase + e < M && cc < N) dst[(int64_t)(rbase + e) * N + cc] = sum[e];
+    return;
+  }
+  if (!last) return;
 #pragma unroll
   for (int c = 0; c < 4; ++c) acc[c] = (f4){0.f, 0.f, 0.f, 0.f};
   // four parts are requested together (each load is a round trip to the coherent level), then added in

@@ -130,17 +130,26 @@ static GemmExPlan ex_default(const int64_t* s) {
   const int64_t batch = s[0], M = s[1], N = s[2], K = s[3];
   if (skinny_applies(s)) {
     // B streams once from HBM: 8 wavefronts along k per workgroup, and k parts over workgroups until
-    // 2048 wavefronts (two per SIMD) are in flight, each still walking at least two steps of 16 rows
-    // (measured best on 16 x 1000 x 2048, 16 x 1000 x 4096, 16 x 4096 x 4096 and 16 x 4096 x 25088)
+    // 2048 wavefronts (two per SIMD) are in flight, each still walking at least one step of 16 rows: what
+    // a compute unit keeps in flight is bounded (~16 KB per microsecond for cold data), so a small B is
+    // read fastest when every unit reads a little, and the parts are combined by all wavefronts of the
+    // last workgroup in one round of loads
+    // (measured best on 16 x 1000 x 2048, 8 x 1000 x 4096, 16 x 4096 x 4096 and 16 x 4096 x 25088)
     // B transposed: a lane reads 16 bytes of its column's row whatever the strip width, so 16-column
     // strips cost nothing in coalescing and need no combination between workgroups; they win once they
     // fill the chip or a workgroup's slice of B (64 B x K) is a few rounds of requests
     // (16 x 1000 x 2048: 10.0 against 14.3 us; 16 x 4096 x 4096: 18.7 against 24.9; 16 x 1000 x 8192 and
     // 16 x 256 x 8192: the split of k over workgroups wins, 24 against 32 and 21 against 32 us)
     if (s[5] && (batch * cdiv(N, 16) >= 192 || K <= 3072)) return skinny_narrow_plan(s, 8);
+    // plain view: 16-column strips use half of every 128-byte line, which only pays where they fill the
+    // chip and a workgroup's slice is one or two rounds (16 x 4096 x 1024: 7.9 against 9.1 us; 4 x 16 x 1000
+    // x 2048: 14.8 against 17.1 us; 16 x 4096 x 4096: 23.6 against 17.3 us)
+    if (!s[5] && batch * cdiv(N, 16) >= 192 && K <= 2048) return skinny_narrow_plan(s, 8);
     const int64_t strips = batch * cdiv(M, 16) * cdiv(N, 64);
     int S = 1;
-    while (strips * 8 * S < 2048 && S < 64 && K / (2 * S) >= 8 * 16 * 2) S *= 2;
+    // more than 32 parts (a second round of loads in the combination) only where a part still walks four
+    // steps (16 x 256 x 8192: 10.7 us with 32 parts, 14.4 with 64; 16 x 64 x 65536: 19.6 us with 64, 25.8 with 32)
+    while (strips * 8 * S < 2048 && S < 64 && K / (2 * S) >= 8 * 16 && (S < 32 || K / (2 * S) >= 8 * 16 * 4)) S *= 2;
     return skinny_plan(s, 1, 8, S);
   }
   return ex_default_tiled(s);
