@@ -163,12 +163,8 @@ __global__ __launch_bounds__(256 * RW) void capsule_kernel(const float* __restri
   const float* brow = fs + d4 * PFR + h * 16 + m4 * 4;
   const int p = p0 + wave;
 
-  for (int qt = 0; qt < QT; ++qt) {
-    const int q0 = (tq * QT + qt) * CAP_TQ;
-    if (q0 >= Q) break;  // workgroup-uniform
-    // input patch of this tile (cells outside the image read as 0), then the request for the next
-    if (qt) __syncthreads();  // the previous tile's reads are done
-    stash();
+  // pieces of a patch beyond CAP_PV per lane go straight from memory to LDS
+  auto stage_rest = [&](int q0) {
     for (int idx = CAP_PV * CAP_NT + tid; idx < npieces; idx += CAP_NT) {
       const int ph = idx / pw4, x = (idx - ph * pw4) << 2;
       const int hy = p0 * sh + ph;
@@ -177,8 +173,22 @@ __global__ __launch_bounds__(256 * RW) void capsule_kernel(const float* __restri
       if (hy < H && gx < WC16) v = *(const f4u*)(img + hy * WC16 + gx);
       *(f4*)(ps + ph * PWF + x) = v;
     }
-    __syncthreads();
-    if (qt + 1 < QT && q0 + CAP_TQ < Q) fetch(q0 + CAP_TQ);
+  };
+  // input patch of the first tile (cells outside the image read as 0)
+  if (tq * QT * CAP_TQ < Q) {
+    stash();
+    stage_rest(tq * QT * CAP_TQ);
+  }
+  __syncthreads();
+
+  for (int qt = 0; qt < QT; ++qt) {
+    const int q0 = (tq * QT + qt) * CAP_TQ;
+    if (q0 >= Q) break;  // workgroup-uniform
+    // the patch of this tile is in LDS; the next one is requested now and written to LDS after the walk,
+    // BEFORE this tile's results are stored: loads and stores share one in-order counter, and waiting for
+    // the patch after the stores were issued would wait for the stores as well
+    const bool more = qt + 1 < QT && q0 + CAP_TQ < Q;  // workgroup-uniform
+    if (more) fetch(q0 + CAP_TQ);
 
     f16 acc[NI];
 #pragma unroll
@@ -254,7 +264,7 @@ __global__ __launch_bounds__(256 * RW) void capsule_kernel(const float* __restri
 #pragma unroll
           for (int g = 0; g < 16; ++g) c[(ni * 16 + g) * 64] = acc[ni][g];
       }
-      __syncthreads();
+      __syncthreads();  // also: every wavefront is done reading the patch
       if (rw == 0) {
 #pragma unroll
         for (int w = 1; w < RW; ++w) {
@@ -265,6 +275,12 @@ __global__ __launch_bounds__(256 * RW) void capsule_kernel(const float* __restri
             for (int g = 0; g < 16; ++g) acc[ni][g] += c[(ni * 16 + g) * 64];
         }
       }
+    } else if (more) {
+      __syncthreads();  // every wavefront is done reading the patch
+    }
+    if (more) {
+      stash();
+      stage_rest(q0 + CAP_TQ);
     }
 
     // output view (n,p,q,k,mi,mj,0,0,0,0) -> out[n,p,q,k,mi,mj].  The filter is the row operand of
@@ -283,6 +299,7 @@ __global__ __launch_bounds__(256 * RW) void capsule_kernel(const float* __restri
                 (f4){acc[ni][4 * g], acc[ni][4 * g + 1], acc[ni][4 * g + 2], acc[ni][4 * g + 3]};
         }
     }
+    if (more) __syncthreads();  // the next patch is in LDS
   }
 }
 
