@@ -198,7 +198,9 @@ def test_small_m_one_launch_and_second_kernel_agree_bit_for_bit(tb):
     # a reduction split over workgroups is combined by the last part of a strip to arrive (the default:
     # out_region = device memory) or by a second kernel (out_region = registers): same order, same bits;
     # calls of different shapes in a row share the arrival counters, which every call leaves at zero
-    for rep, (nb, M, N, K) in enumerate(((1, 16, 1000, 2048), (2, 12, 200, 4096), (1, 16, 1000, 2048), (3, 7, 130, 1024))):
+    # (the last two shapes split k into 32 and 64 parts: two and four rounds of the combination's loads)
+    for rep, (nb, M, N, K) in enumerate(((1, 16, 1000, 2048), (2, 12, 200, 4096), (1, 16, 1000, 2048), (3, 7, 130, 1024),
+                                         (1, 5, 100, 16384), (1, 16, 64, 65536))):
         A = W.uniform(W.SEED_BASE + 66 + rep, 1, (nb, M, K), -1, 1)
         Bm = W.uniform(W.SEED_BASE + 66 + rep, 2, (nb, N, K) if tb else (nb, K, N), -1, 1)
         sizes = (nb, M, N, K, 0, int(tb), 0)
@@ -207,6 +209,8 @@ def test_small_m_one_launch_and_second_kernel_agree_bit_for_bit(tb):
             cands = [mdh.mdh_candidate(mdh.MDH_BMATMUL, sizes, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_BMATMUL, sizes))]
             d = next(c for c in cands if c.blk[1] == 16 and c.prt[B.L_WG][3] > 1 and c.out_region == B.MR_HBM)
         assert d.blk[1] == 16 and d.prt[B.L_WG][3] > 1 and d.out_region == B.MR_HBM, (sizes, d.table())
+        if K >= 16384:
+            assert d.prt[B.L_WG][3] >= 32, (sizes, d.table())
         second = d.copy()
         second.out_region = B.MR_VGPR
         assert mdh.mdh_validate_params(mdh.MDH_BMATMUL, sizes, second) == 0
