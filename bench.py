@@ -266,12 +266,10 @@ def bench_mcc(torch, mdh, W, name, steps, warmup, cpu):
             xh, fh = x[:4].cpu().numpy(), f.cpu().numpy()  # four whole images
         else:
             xh, fh = x[:1].cpu().numpy(), f.cpu().numpy()  # image 0, every output row (a few seconds)
-        t0 = time.perf_counter()
-        r = oracle.mcc(np.ascontiguousarray(xh), fh, cfg.stride)
-        dt = time.perf_counter() - t0
+        dt, oreps, r = _oracle_seconds(lambda: oracle.mcc(np.ascontiguousarray(xh), fh, cfg.stride))
         res["cpu_baseline"] = {"value": 2.0 * r.size * cfg.C * cfg.R * cfg.S / dt / 1e9, "unit": "GFLOP/s",
                                "cores": oracle.num_threads(), "kind": "oracle",
-                               "sample": "output rows p<%d of the first %d image(s) (%.2f s)" % (r.shape[1], r.shape[0], dt)}
+                               "sample": "output rows p<%d of the first %d image(s), mean of %d call(s) (%.3f s each)" % (r.shape[1], r.shape[0], oreps, dt)}
     return res
 
 
@@ -337,11 +335,9 @@ def bench_dot(torch, mdh, W, name, steps, warmup, cpu):
 
         n = 1 << 26
         xh, yh = x[:n].cpu().numpy(), y[:n].cpu().numpy()
-        t0 = time.perf_counter()
-        oracle.dot(xh, yh)
-        dt = time.perf_counter() - t0
+        dt, oreps, _ = _oracle_seconds(lambda: oracle.dot(xh, yh))
         res["cpu_baseline"] = {"value": 8 * n / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-                               "sample": "first 2^26 elements (%.2f s; the scalar reduction is sequential)" % dt}
+                               "sample": "first 2^26 elements, mean of %d call(s) (%.3f s each; the scalar reduction is sequential)" % (oreps, dt)}
     return res
 
 
@@ -367,11 +363,9 @@ def bench_matvec(torch, mdh, W, name, steps, warmup, cpu):
 
         rows = 4096
         Ah, xh = A[:rows].cpu().numpy(), x.cpu().numpy()
-        t0 = time.perf_counter()
-        oracle.matvec(Ah, xh)
-        dt = time.perf_counter() - t0
+        dt, oreps, _ = _oracle_seconds(lambda: oracle.matvec(Ah, xh))
         res["cpu_baseline"] = {"value": 4 * rows * K / dt / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
-                               "kind": "oracle", "sample": "first %d rows (%.2f s)" % (rows, dt)}
+                               "kind": "oracle", "sample": "first %d rows, mean of %d call(s) (%.4f s each)" % (rows, oreps, dt)}
     return res
 
 
@@ -413,11 +407,9 @@ def bench_matmul_ex(torch, mdh, W, name, steps, warmup, cpu):
 
         cols = max(1, min(cfg.N, int(4e8 // (cfg.M * cfg.K))))
         ah, bh = a[0].cpu().numpy(), b[0, :, :cols].contiguous().cpu().numpy()
-        t0 = time.perf_counter()
-        oracle.matmul(ah, bh)
-        dt = time.perf_counter() - t0
+        dt, oreps, _ = _oracle_seconds(lambda: oracle.matmul(ah, bh))
         res["cpu_baseline"] = {"value": 2.0 * cfg.M * cols * cfg.K / dt / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(),
-                               "kind": "oracle", "sample": "first %d columns of C (%.2f s)" % (cols, dt)}
+                               "kind": "oracle", "sample": "first %d columns of C, mean of %d call(s) (%.4f s each)" % (cols, oreps, dt)}
     return res
 
 
@@ -450,11 +442,9 @@ def bench_bmatmul(torch, mdh, W, name, steps, warmup, cpu):
         a0 = a[0].t() if ta else a[0]
         b0 = b[0].t() if tb else b[0]
         ah, bh = a0[:rows].contiguous().cpu().numpy(), b0.contiguous().cpu().numpy()
-        t0 = time.perf_counter()
-        oracle.matmul(ah, bh)
-        dt = time.perf_counter() - t0
+        dt, oreps, _ = _oracle_seconds(lambda: oracle.matmul(ah, bh))
         res["cpu_baseline"] = {"value": 2.0 * rows * cfg.N * cfg.K / dt / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(),
-                               "kind": "oracle", "sample": "batch 0, first %d rows of C (%.2f s)" % (rows, dt)}
+                               "kind": "oracle", "sample": "batch 0, first %d rows of C, mean of %d call(s) (%.3f s each)" % (rows, oreps, dt)}
     return res
 
 
@@ -483,12 +473,10 @@ def bench_capsule(torch, mdh, W, name, steps, warmup, cpu):
         import oracle
 
         xh, fh = x[:1, : cfg.R + 2 * 7].cpu().numpy(), f.cpu().numpy()  # 8 output rows of image 0
-        t0 = time.perf_counter()
-        r = oracle.mcc_capsule(np.ascontiguousarray(xh), fh, cfg.stride)
-        dt = time.perf_counter() - t0
+        dt, oreps, r = _oracle_seconds(lambda: oracle.mcc_capsule(np.ascontiguousarray(xh), fh, cfg.stride))
         res["cpu_baseline"] = {"value": 2.0 * r.size * cfg.C * cfg.R * cfg.S * 4 / dt / 1e9, "unit": "GFLOP/s",
                                "cores": oracle.num_threads(), "kind": "oracle",
-                               "sample": "output rows p<%d of image 0 (%.2f s)" % (r.shape[1], dt)}
+                               "sample": "output rows p<%d of image 0, mean of %d call(s) (%.3f s each)" % (r.shape[1], oreps, dt)}
     return res
 
 
@@ -524,11 +512,9 @@ def bench_scan(torch, mdh, W, name, steps, warmup, cpu):
         rows = max(1, min(R, (1 << 26) // n))
         cols = min(n, 1 << 26)
         xh = x[:rows, :cols].contiguous().cpu().numpy()
-        t0 = time.perf_counter()
-        oracle.scan_rows(xh)
-        dt = time.perf_counter() - t0
+        dt, oreps, _ = _oracle_seconds(lambda: oracle.scan_rows(xh))
         res["cpu_baseline"] = {"value": 8 * rows * cols / dt / 1e9, "unit": "GB/s", "cores": min(rows, oracle.num_threads()),
-                               "kind": "oracle", "sample": "first %d row(s) x %d columns (%.2f s)" % (rows, cols, dt)}
+                               "kind": "oracle", "sample": "first %d row(s) x %d columns, mean of %d call(s) (%.3f s each)" % (rows, cols, oreps, dt)}
     return res
 
 
@@ -707,6 +693,18 @@ def calibration(torch, mdh):
 # the benchmark's five configurations (config 3 is two shapes) and the split-k line of the tall-skinny one
 BASELINE_ROWS = ("matmul_256", "jacobi3d_512", "matmul_4096", "matmul_ts", "matmul_ts_split_k4", "mcc_resnet",
                  "prl_2p16_2p18")
+
+
+def _oracle_seconds(fn, min_total=0.5, max_reps=200):
+    """Mean time of one oracle call: repeated until min_total seconds have been spent (a sample of a few
+    milliseconds would be timer noise), never tuned."""
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        out = fn()
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt >= min_total or reps >= max_reps:
+            return dt / reps, reps, out
 
 
 def _rounded(x):

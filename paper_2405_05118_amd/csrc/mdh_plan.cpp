@@ -644,8 +644,14 @@ static MccPlan mcc_flat_plan(const int64_t* s) {
   return pl;
 }
 
+// The few-channel kernel reads its input in 16-byte pieces and needs an input of at least four elements;
+// the smallest input these output sizes can have is N x ((P-1) sh + R) x ((Q-1) sw + S) x C.
+static bool flat_input_ok(const int64_t* s) {
+  return (s[0] > 0 ? s[0] : 1) * ((s[1] > 0 ? s[1] - 1 : 0) * s[7] + s[5]) * ((s[2] > 0 ? s[2] - 1 : 0) * s[8] + s[6]) * s[4] >= 4;
+}
+
 static MccPlan mcc_default(const int64_t* s) {
-  if (s[4] <= 8) {  // fewer channels than half a channel chunk: fuse s and c
+  if (s[4] <= 8 && flat_input_ok(s)) {  // fewer channels than half a channel chunk: fuse s and c
     MccPlan f = mcc_flat_plan(s);
     if (mcc_lds_bytes(f, s) <= kLdsBytesPerWG) return f;
   }
@@ -722,7 +728,7 @@ int mcc_candidates(const int64_t* s, MccPlan* out, int cap) {
       if (wg * (S / 2) >= 1024 || (int64_t)(S - 1) * cdiv(cdiv(s[4], S), m.CK) * m.CK >= s[4]) continue;
       push(pl);
     }
-  if (s[4] <= 16)
+  if (s[4] <= 16 && flat_input_ok(s))
     for (int want : {1, 2, 4, 8, 16})
       for (auto& m : kMccFlatMenu) {
         MccPlan pl{m.TP, m.TQ, m.BN, m.CK, m.WM, m.WN, 0, 1};
@@ -755,7 +761,7 @@ mdh_status plan_mcc(const int64_t* s, const mdh_tile_params* p, MccPlan* out) {
   pl.BN = p->prt[MDH_L_WAVE][3] * pl.WN;
   if (pl.flat) {
     pl.TQ = p->blk[2];
-    if (pl.TQ != 16 && pl.TQ != 32) return MDH_ERR_UNSUPPORTED;
+    if ((pl.TQ != 16 && pl.TQ != 32) || !flat_input_ok(s)) return MDH_ERR_UNSUPPORTED;
     pl.WM = p->prt[MDH_L_VGPR][1] * 32;
     pl.TP = p->prt[MDH_L_WAVE][1] * p->prt[MDH_L_VGPR][1] * (32 / pl.TQ);
     pl.CK = 0;

@@ -77,6 +77,9 @@ def run(x, f, stride, p):
 
 SMALL = [
     # N, H, W, C, K, R, S, stride
+    (1, 1, 1, 3, 2, 1, 1, (1, 1)),   # three input elements: fewer than one 16-byte piece
+    (1, 1, 4, 1, 3, 1, 2, (1, 1)),   # exactly four
+    (2, 2, 1, 1, 1, 2, 1, (1, 1)),
     (2, 37, 37, 3, 64, 7, 7, (2, 2)),
     (1, 21, 40, 3, 32, 3, 3, (2, 2)),
     (2, 12, 19, 1, 5, 3, 2, (1, 1)),
@@ -94,7 +97,10 @@ def test_small_all_candidates(case):
     ref, refabs = oracle.mcc(x, f, stride, with_abs=True)
     s = sizes_of(N, H, Wd, C, K, R, S, stride)
     cands = [None] + [mdh.mdh_candidate(mdh.MDH_MCC, s, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_MCC, s))]
-    assert any(p is not None and p.blk[4] == 1 for p in cands), "the fused (s,c) kernel is not among the candidates"
+    if N * H * Wd * C >= 4:  # that kernel reads 16-byte pieces: an input of fewer than four elements has none
+        assert any(p is not None and p.blk[4] == 1 for p in cands), "the fused (s,c) kernel is not among the candidates"
+    else:
+        assert not any(p is not None and p.blk[4] == 1 for p in cands)
     for p in cands:
         got = run(x, f, stride, p)
         assert np.all(np.isfinite(got)), "output not fully overwritten"
