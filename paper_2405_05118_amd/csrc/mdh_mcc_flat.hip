@@ -130,6 +130,18 @@ struct PatchPieces {
   }
 };
 
+// A filter row's s*c values are walked in groups of 8 (4 MFMAs of 2: the lower lane half supplies elements
+// 0..3 of a group, the upper half elements 4..7).  The last group of a row has only v = SC mod 8 values:
+// it takes ceil(v/2) MFMAs instead of 4 when the lower half supplies its first ceil(v/2) values and the
+// upper half the others.  In LDS the group keeps its two 4-float halves (so both halves still read 16
+// aligned bytes): value x of the row sits at
+__device__ __forceinline__ int last_group_slot(int x, int SC) {
+  const int LB = (SC >> 3) << 3, v = SC - LB, nlast = (v + 1) >> 1;
+  if (x < LB) return x;
+  const int k = x - LB;
+  return k < nlast ? LB + k : LB + 4 + (k - nlast);
+}
+
 // Filter slice of a workgroup -> LDS: row k holds R groups of SCP floats (s*c padded with zeros).
 // Staging without integer divisions in the loops: a filter row k is R*SC contiguous floats in memory, so
 // a lane's elements e = lane, lane+64, ... have the same (r, x) for every k and that split is computed
@@ -147,7 +159,7 @@ __device__ __forceinline__ void stage_filter(float* fs, const float* __restrict_
       const int e = e0 + u * 64 + lane;
       const int r = e / SC;
       ge[u] = e;
-      off[u] = e < RSC ? r * SCP + (e - r * SC) : -1;
+      off[u] = e < RSC ? r * SCP + last_group_slot(e - r * SC, SC) : -1;
     }
     // all loads of a group of 8 rows are issued before the first LDS write: one round trip to
     // memory per group instead of one per row
@@ -173,11 +185,13 @@ __device__ __forceinline__ void stage_filter(float* fs, const float* __restrict_
       }
     }
   }
-  // zero the padding of every filter row (x in [SC, SCP)): it meets patch values in the MFMAs
+  // zero the unused slots of every filter row's last group: they meet patch values in the MFMAs
   const int padn = SCP - SC;
+  const int LB = (SC >> 3) << 3, v = SC - LB, nlast = (v + 1) >> 1;
   for (int i = tid; i < Cf::BN * R * padn; i += Cf::NT) {
-    const int row = i / padn, x = SC + (i - row * padn);
+    const int row = i / padn, pi = i - row * padn;
     const int k = row / R, r = row - k * R;
+    const int x = pi < 4 - nlast ? LB + nlast + pi : LB + 4 + (v - nlast) + (pi - (4 - nlast));
     fs[k * PFR + r * SCP + x] = 0.f;
   }
 }
@@ -188,37 +202,46 @@ __device__ __forceinline__ void stage_filter(float* fs, const float* __restrict_
 // wavefront-uniform offsets of a step in the patch / in the filter row (contiguous over r).
 // arow: the lane's first patch element; brow: the lane's first filter element.
 template <class Cf, int MI, int NI>
-__device__ __forceinline__ void walk_tile(const float* arow, const float* brow, int R, int SCP, int PWF,
-                                          int PFR, int sh, f16 (&acc)[MI][NI]) {
+__device__ __forceinline__ void walk_tile(const float* arow, const float* brow, int R, int SC, int SCP, int PWF,
+                                          int PFR, int sh, int lh, f16 (&acc)[MI][NI]) {
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
-  auto ld = [&](f4 (&af)[MI], f4 (&bf)[NI], int sa, int sb) {
+  // the last group of a row (see last_group_slot): nlast MFMAs, and the upper lane half's patch elements
+  // start nlast (not 4) after the lower half's
+  const int vlast = SC & 7;
+  const int nlast = vlast ? (vlast + 1) >> 1 : 4;
+  const int afix = lh * (nlast - 4);
+  auto is_last = [&](int sc) { return vlast != 0 && sc == SCP - 8; };  // wavefront-uniform
+  auto ld = [&](f4 (&af)[MI], f4 (&bf)[NI], int sa, int sb, bool last) {
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
-      const float* a = arow + mi * Cf::RB * sh * PWF + sa;
+      const float* a = arow + mi * Cf::RB * sh * PWF + sa + (last ? afix : 0);
 #pragma unroll
       for (int e = 0; e < 4; ++e) af[mi][e] = a[e];
     }
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) bf[ni] = *(const f4*)(brow + ni * 32 * PFR + sb);
   };
-  auto mma = [&](const f4 (&af)[MI], const f4 (&bf)[NI]) {
+  auto mma = [&](const f4 (&af)[MI], const f4 (&bf)[NI], int n) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
+    for (int e = 0; e < 4; ++e) {
+      if (e >= n) break;  // wavefront-uniform
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(bf[ni][e], af[mi][e], acc[mi][ni], 0, 0, 0);
+    }
   };
   const int nsteps = R * (SCP >> 3);
   f4 a0[MI], b0[NI], a1[MI], b1[NI];
   int sa = 0, sb = 0, sc0 = 0;
-  ld(a0, b0, 0, 0);
+  int n0 = is_last(0) ? nlast : 4, n1 = 4;
+  ld(a0, b0, 0, 0, is_last(0));
   int st = 0;
   for (; st + 2 <= nsteps; st += 2) {
     sb += 8;
@@ -228,9 +251,10 @@ __device__ __forceinline__ void walk_tile(const float* arow, const float* brow, 
       sc0 = 0;
       sa += PWF - SCP;
     }
-    ld(a1, b1, sa, sb);
+    n1 = is_last(sc0) ? nlast : 4;
+    ld(a1, b1, sa, sb, is_last(sc0));
     __builtin_amdgcn_sched_barrier(0);
-    mma(a0, b0);
+    mma(a0, b0, n0);
     __builtin_amdgcn_sched_barrier(0);
     // operands of step st+2; past the end of the walk the reads repeat step st+1 and are unused
     int na = sa + 8, nc = sc0 + 8;
@@ -242,12 +266,13 @@ __device__ __forceinline__ void walk_tile(const float* arow, const float* brow, 
     sa = nxt ? na : sa;
     sb = nxt ? sb + 8 : sb;
     sc0 = nxt ? nc : sc0;
-    ld(a0, b0, sa, sb);
+    n0 = is_last(sc0) ? nlast : 4;
+    ld(a0, b0, sa, sb, is_last(sc0));
     __builtin_amdgcn_sched_barrier(0);
-    mma(a1, b1);
+    mma(a1, b1, n1);
     __builtin_amdgcn_sched_barrier(0);
   }
-  if (st < nsteps) mma(a0, b0);  // odd number of steps
+  if (st < nsteps) mma(a0, b0, n0);  // odd number of steps
 }
 
 // output view (n,p,q,k,0,0,0) -> out[n,p,q,k]; the buffer has fewer than 2^31 elements (checked by the
@@ -343,7 +368,7 @@ __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_kernel(
     }
 
     f16 acc[MI][NI];
-    walk_tile<Cf, MI, NI>(ps + aoff, brow, R, SCP, PWF, PFR, sh, acc);
+    walk_tile<Cf, MI, NI>(ps + aoff, brow, R, SC, SCP, PWF, PFR, sh, lh, acc);
     // the next tile's patch goes to the other buffer (its last readers passed the barrier of the
     // previous iteration) BEFORE this tile's results are stored: the wait for the patch loads would
     // otherwise also wait for the stores issued after them (one in-order counter for both)
@@ -422,7 +447,7 @@ __global__ __launch_bounds__((WAVES_M * WAVES_N * 64)) void mcc_flat_dealt_kerne
     const int tq = cur % tq_n, band = cur / tq_n;
     const int tp = band % tp_n, n = band / tp_n;
     f16 acc[MI][NI];
-    walk_tile<Cf, MI, NI>(ps0 + (it & 1) * PH * PWF + aoff, brow, R, SCP, PWF, PFR, sh, acc);
+    walk_tile<Cf, MI, NI>(ps0 + (it & 1) * PH * PWF + aoff, brow, R, SC, SCP, PWF, PFR, sh, lh, acc);
     // the next tile's patch goes to the other buffer (its last readers passed the barrier of the
     // previous iteration) BEFORE this tile's results are stored: the wait for the patch loads would
     // otherwise also wait for the stores issued after them (one in-order counter for both).  The tile
