@@ -216,6 +216,12 @@ def bench_matmul(torch, mdh, W, name, steps, warmup, cpu, split=None):
         "algorithmic_bytes": 4 * (cfg.M * cfg.K + cfg.K * cfg.N + cfg.M * cfg.N),
         "cache_resident": 4 * (cfg.M * cfg.K + cfg.K * cfg.N + cfg.M * cfg.N) < LLC_BYTES,
     }
+    if flop < 1e9:
+        # launch-bound: the eager figure above is the rate at which this host issues launches; replayed from a
+        # graph of 100 calls the same kernel runs back to back
+        gms = _graph_ms_per_call(torch, lambda: mdh.mdh_matmul(a, b, c, p, ws))
+        res["in_graph"] = {"ms_per_step": gms, "GFLOPs": flop / gms / 1e6, "frac": flop / gms / 1e9 / PEAK_FP32_MFMA_TFLOPS,
+                           "calls_per_graph": 100}
     if cpu:
         import oracle
 
@@ -695,6 +701,33 @@ BASELINE_ROWS = ("matmul_256", "jacobi3d_512", "matmul_4096", "matmul_ts", "matm
                  "prl_2p16_2p18")
 
 
+def _graph_ms_per_call(torch, call, calls=100, reps=20):
+    """Per-call time of `calls` launches captured once into a HIP graph and replayed (the entry points
+    allocate nothing and synchronise nothing, so they can be captured after one eager call): what a
+    launch-bound kernel costs when the host is out of the way."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(3):
+            call()
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        for _ in range(calls):
+            call()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / (reps * calls)
+
+
 def _oracle_seconds(fn, min_total=0.5, max_reps=200):
     """Mean time of one oracle call: repeated until min_total seconds have been spent (a sample of a few
     milliseconds would be timer noise), never tuned."""
@@ -844,6 +877,8 @@ def main() -> int:
             if r is not None:
                 rows[name] = [r["value"], r["unit"], r["ms_per_step"], r["roofline"]["frac"], r["roofline"]["bound"],
                               r.get("cpu_baseline", {}).get("value"), r.get("spread", {}).get("ci99_rel")]
+                if "in_graph" in r:  # launch-bound row: ms per step and roofline fraction when replayed from a graph
+                    rows[name] += [r["in_graph"]["ms_per_step"], r["in_graph"]["frac"]]
         line["baseline_rows"] = rows
 
     print(json.dumps(_rounded(line)))
