@@ -5,14 +5,14 @@ The profiling itself is four rocprofv3 passes per workload (the commands are wri
 each pass runs `bench.py --workload W --no-instances --no-cpu`, so that every library kernel of a pass
 belongs to workload W:
 
-    D=gpurun_out/profile
+    D=<directory for the raw profiler output>
     for W in $(python3 -m paper_2405_05118_amd.profile_summary --workloads); do
       rocprofv3 --kernel-trace --stats --output-format csv -d $D/trace/$W -o p -- python3 bench.py --workload $W --no-instances --no-cpu --steps 50 --warmup 5
       rocprofv3 --pmc FETCH_SIZE --output-format csv -d $D/fetch/$W -o p -- python3 bench.py --workload $W --no-instances --no-cpu --steps 5 --warmup 1 --calibration-copy
       rocprofv3 --pmc WRITE_SIZE --output-format csv -d $D/write/$W -o p -- python3 bench.py --workload $W --no-instances --no-cpu --steps 5 --warmup 1 --calibration-copy
       rocprofv3 --pmc SQ_INSTS_VALU_MFMA_MOPS_F32 SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_INSTS_LDS SQ_LDS_BANK_CONFLICT SQ_INSTS_VALU SQ_WAIT_INST_ANY GRBM_GUI_ACTIVE --output-format csv -d $D/sq/$W -o p -- python3 bench.py --workload $W --no-instances --no-cpu --steps 5 --warmup 1 --valu-kinds
     done
-    python3 -m paper_2405_05118_amd.profile_summary gpurun_out/profile
+    python3 -m paper_2405_05118_amd.profile_summary $D
 
 The byte counters are scaled by what the same counter reads for the plain 512 MiB device copy that
 `--calibration-copy` runs first (FETCH_SIZE counts in units that make that copy read half its size).
@@ -110,7 +110,11 @@ def main(argv):
 
         print(" ".join(bench.BENCHES))
         return 0
-    root = argv[1] if len(argv) > 1 else os.path.join(ROOT, "gpurun_out", "profile")
+    if len(argv) < 2:
+        sys.stderr.write("usage: python3 -m paper_2405_05118_amd.profile_summary <directory of the raw profiler output> | --workloads\n")
+        return 2
+    root = argv[1]
+    shown = os.path.relpath(os.path.abspath(root), ROOT)  # as the summaries print it in their commands
     workloads = sorted(os.path.basename(d) for d in glob.glob(os.path.join(root, "trace", "*")))
     if not workloads:
         sys.stderr.write("no passes under %s\n" % root)
@@ -130,7 +134,7 @@ def main(argv):
     with open(os.path.join(ROOT, "profiles", "all_workloads_kernel_trace.md"), "w") as fh:
         fh.write("# rocprofv3 kernel trace: every kernel of every bench.py workload (MI355X, gfx950)\n\n"
                  "One pass per workload W (from the repository root on the GPU box):\n\n"
-                 "    rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/profile/trace/W -o p -- " + cmd + " --steps 50 --warmup 5\n\n"
+                 "    rocprofv3 --kernel-trace --stats --output-format csv -d " + shown + "/trace/W -o p -- " + cmd + " --steps 50 --warmup 5\n\n"
                  "Per-dispatch durations (ns) from the kernel trace, warm-up launches dropped; a workload with a split\n"
                  "reduction shows its second-pass kernel on a line of its own.  `bench.py` itself times the same launches\n"
                  "with HIP events on the launch stream (`kernel_ms` = all kernels of a step plus the gaps between them).\n\n"
@@ -163,8 +167,8 @@ def main(argv):
     with open(os.path.join(ROOT, "profiles", "all_workloads_hbm_traffic_pmc.md"), "w") as fh:
         fh.write("# rocprofv3 --pmc: HBM traffic of every kernel of every bench.py workload (MI355X, gfx950)\n\n"
                  "Two passes per workload W, one counter each:\n\n"
-                 "    rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/profile/fetch/W -o p -- " + cmd + " --steps 5 --warmup 1 --calibration-copy\n"
-                 "    rocprofv3 --pmc WRITE_SIZE --output-format csv -d gpurun_out/profile/write/W -o p -- " + cmd + " --steps 5 --warmup 1 --calibration-copy\n\n"
+                 "    rocprofv3 --pmc FETCH_SIZE --output-format csv -d " + shown + "/fetch/W -o p -- " + cmd + " --steps 5 --warmup 1 --calibration-copy\n"
+                 "    rocprofv3 --pmc WRITE_SIZE --output-format csv -d " + shown + "/write/W -o p -- " + cmd + " --steps 5 --warmup 1 --calibration-copy\n\n"
                  "Each counter is scaled by what it reads for the plain 512 MiB device copy `--calibration-copy` runs first\n"
                  "(" + scale_note + ").\nMeans per dispatch (KiB as the profiler reports them), scaled bytes per launch, and per step the sum over the\n"
                  "workload's kernels against its algorithmic bytes.\n\n"
@@ -195,7 +199,7 @@ def main(argv):
     with open(os.path.join(ROOT, "profiles", "all_workloads_mfma_lds_valu_pmc.md"), "w") as fh:
         fh.write("# rocprofv3 --pmc: MFMA, LDS and VALU counters of every kernel of every bench.py workload (MI355X, gfx950)\n\n"
                  "One pass per workload W (8 SQ counters + 1 GRBM counter):\n\n"
-                 "    rocprofv3 --pmc " + " ".join(names) + " --output-format csv -d gpurun_out/profile/sq/W -o p -- " + cmd + " --steps 5 --warmup 1 --valu-kinds\n\n"
+                 "    rocprofv3 --pmc " + " ".join(names) + " --output-format csv -d " + shown + "/sq/W -o p -- " + cmd + " --steps 5 --warmup 1 --valu-kinds\n\n"
                  "Means per dispatch, summed over the chip by the profiler (`--valu-kinds` also runs the calibration loop of every\n"
                  "instruction kind once in every pass; their rows are listed with the first workload only).  The last two columns: MFMA pipe busy = SQ_VALU_MFMA_BUSY_CYCLES / (1024 SIMDs x\n"
                  "GRBM_GUI_ACTIVE / 8 XCDs), and VALU instructions x 4 cycles over the same SIMD cycles -- above 1.0 where the\n"
