@@ -437,8 +437,10 @@ mdh_status mdh_matvec(int64_t M, int64_t K, const float* A, const float* x, floa
  * has two strip widths: prt[MDH_L_VGPR][j] = 4 (a wavefront owns 64 columns; k may
  * be split over workgroups, combined as out_region says) and prt[MDH_L_VGPR][j] = 1
  * (a workgroup owns 16 columns and all of k: prt[MDH_L_WG][k] = 1, 8 or 16
- * wavefronts along k, no workspace; the default for trans_b when the strips fill
- * the chip or K <= 3072).
+ * wavefronts along k, no workspace).  With trans_b the 16-column strips also exist
+ * with in_region[0..1] = MDH_MR_LDS (4 or 8 wavefronts along k): rows of A and B are
+ * read as whole runs of k and reach the MFMA operand layout through LDS; the default
+ * for trans_b when the strips fill the chip or K <= 3072.
  */
 mdh_status mdh_matmul_ex(int64_t batch, int64_t M, int64_t N, int64_t K, const float* A,
                          int32_t trans_a, const float* B, int32_t trans_b, float* C,

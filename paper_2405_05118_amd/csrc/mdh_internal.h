@@ -130,6 +130,9 @@ struct GemmExPlan {
   // small-M kernel with S > 1: 1 = the last workgroup part of an output strip to arrive adds the S
   // partial results itself (one launch), 0 = a second kernel does
   int fused = 0;
+  // small-M kernel with narrow strips and B transposed: 1 = both operands staged through LDS
+  // (row-contiguous loads), 0 = read straight into the MFMA layout
+  int lds = 0;
 };
 // Device-coherent accesses for results that pass between workgroups of ONE launch (the parts of a split
 // reduction folded by the last part to arrive).  The L2 caches of the chip's eight XCDs are not kept

@@ -54,8 +54,9 @@ static void skinny_params(const int64_t* s, const GemmExPlan& pl, mdh_tile_param
   set_order(p, dims);
   p->strided = 1;  // the wavefronts along k interleave their 16-row parts
   p->lane_fast_dim = 2;
-  p->in_region[0] = MDH_MR_VGPR;
-  p->in_region[1] = MDH_MR_VGPR;
+  // narrow strips with B transposed: operands read straight into the MFMA layout, or staged through LDS
+  p->in_region[0] = (narrow && pl.lds) ? MDH_MR_LDS : MDH_MR_VGPR;
+  p->in_region[1] = (narrow && pl.lds) ? MDH_MR_LDS : MDH_MR_VGPR;
   // where the workgroup-layer parts of k are combined: in device memory by the last workgroup part of a
   // strip to arrive (one launch), or by a second kernel (results leave the first from registers)
   p->out_region = (g.S > 1 && pl.fused) ? MDH_MR_HBM : MDH_MR_VGPR;
@@ -80,8 +81,9 @@ static GemmExPlan skinny_plan(const int64_t* s, int wn, int wk, int S, int fused
 }
 
 // narrow strips: 16 columns per workgroup, k over the wk wavefronts of the workgroup only
-static GemmExPlan skinny_narrow_plan(const int64_t* s, int wk) {
+static GemmExPlan skinny_narrow_plan(const int64_t* s, int wk, int lds = 0) {
   GemmExPlan pl{GemmPlan{16, 16, 16, 16, 16, 1, 0}, 0, (int)s[5], 0, 1, wk};
+  pl.lds = lds;
   pl.g.ragged = skinny_ragged(s, pl);
   return pl;
 }
@@ -140,7 +142,11 @@ static GemmExPlan ex_default(const int64_t* s) {
     // fill the chip or a workgroup's slice of B (64 B x K) is a few rounds of requests
     // (16 x 1000 x 2048: 10.0 against 14.3 us; 16 x 4096 x 4096: 18.7 against 24.9; 16 x 1000 x 8192 and
     // 16 x 256 x 8192: the split of k over workgroups wins, 24 against 32 and 21 against 32 us)
-    if (s[5] && (batch * cdiv(N, 16) >= 192 || K <= 3072)) return skinny_narrow_plan(s, 8);
+    // B transposed: the strips' rows of B are runs of k, read as whole 512-byte runs and handed to the MFMA
+    // operand layout through LDS (16 x 4096 x 25088: 73 us against 109 with one 16-byte piece per lane and
+    // row; 16 x 8192 x 8192: 46 against 69; 16 x 4096 x 4096: 14.9 against 19.2; 16 x 1000 x 2048: 8.1
+    // against 9.9; four wavefronts a workgroup are as fast as eight or faster)
+    if (s[5] && (batch * cdiv(N, 16) >= 192 || K <= 3072)) return skinny_narrow_plan(s, 4, 1);
     // plain view: 16-column strips use half of every 128-byte line, which only pays where they fill the
     // chip and a workgroup's slice is one or two rounds (16 x 4096 x 1024: 7.9 against 9.1 us; 4 x 16 x 1000
     // x 2048: 14.8 against 17.1 us; 16 x 4096 x 4096: 23.6 against 17.3 us)
@@ -209,7 +215,10 @@ int matmul_ex_candidates(const int64_t* s, GemmExPlan* out, int cap) {
     out[n++] = d;
     if (d.fused) out[n++] = skinny_plan(s, d.g.BN / 64, d.WK, d.g.S, 0);  // the same with the second kernel
     for (int wk : {16, 8})
-      if (!(d.g.BN == 16 && d.WK == wk)) out[n++] = skinny_narrow_plan(s, wk);
+      if (!(d.g.BN == 16 && d.WK == wk && !d.lds)) out[n++] = skinny_narrow_plan(s, wk);
+    if (s[5])
+      for (int wk : {8, 4})
+        if (!(d.g.BN == 16 && d.WK == wk && d.lds)) out[n++] = skinny_narrow_plan(s, wk, 1);
     static const int sk_splits[] = {1, 2, 4, 8, 16, 32, 64};
     for (auto& m : kSkinnyMenu)
       for (int S : sk_splits) {
@@ -245,12 +254,14 @@ mdh_status plan_matmul_ex(const int64_t* s, const mdh_tile_params* p, GemmExPlan
     const int wn = p->prt[MDH_L_WAVE][2], wk = p->prt[MDH_L_WAVE][3];
     const bool narrow = p->prt[MDH_L_VGPR][2] == 1;
     if (s[4] || s[6] || (narrow && s[1] > 16)) return MDH_ERR_UNSUPPORTED;
-    if (narrow ? (wn != 1 || (wk != 8 && wk != 16)) : !skinny_inst(wn, wk)) return MDH_ERR_UNSUPPORTED;
+    const int lds = p->in_region[1] == MDH_MR_LDS;  // narrow strips, B transposed: operands staged through LDS
+    if (lds && (!narrow || !s[5] || (wk != 4 && wk != 8))) return MDH_ERR_UNSUPPORTED;
+    if (narrow ? (wn != 1 || (!lds && wk != 8 && wk != 16)) : !skinny_inst(wn, wk)) return MDH_ERR_UNSUPPORTED;
     const int S = p->prt[MDH_L_WG][3];
     const int fused = p->out_region == MDH_MR_HBM;
     if (narrow && (S != 1 || fused)) return MDH_ERR_UNSUPPORTED;
     if (fused && (S <= 1 || skinny_strips(s) > kArrivalCounters)) return MDH_ERR_UNSUPPORTED;
-    GemmExPlan pl = narrow ? skinny_narrow_plan(s, wk) : skinny_plan(s, wn, wk, S, fused);
+    GemmExPlan pl = narrow ? skinny_narrow_plan(s, wk, lds) : skinny_plan(s, wn, wk, S, fused);
     mdh_tile_params chk;
     params_from_plan(s, pl, &chk);
     if (!same_table(chk, *p)) return MDH_ERR_UNSUPPORTED;

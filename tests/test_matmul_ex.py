@@ -87,11 +87,16 @@ def test_small_m_default_streams_operands_to_registers():
     assert mdh.mdh_validate_params(mdh.MDH_BMATMUL, (1, 16, 1000, 8192, 0, 1, 0), p) == 0
     assert mdh.mdh_validate_params(mdh.MDH_BMATMUL, (1, 16, 1000, 8192, 0, 0, 0), p) == 6
     # a small transposed B, or one with enough columns to fill the chip: strips of ONE block column, all of
-    # k inside the workgroup (rounds of 128 k per wavefront), nothing combined between workgroups
+    # k inside the workgroup (rounds of 128 k per wavefront), nothing combined between workgroups; the rows
+    # of A and B are read as whole runs of k and reach the operand layout through LDS (in_region)
     for sizes in ((1, 16, 1000, 2048, 0, 1, 0), (1, 16, 4096, 25088, 0, 1, 0)):
         p = mdh.mdh_default_params(mdh.MDH_BMATMUL, sizes)
         assert list(p.blk[:4]) == [1, 16, 16, 4] and p.prt[B.L_VGPR][2] == 1 and p.prt[B.L_VGPR][3] == 32
-        assert p.prt[B.L_WG][2] == -(-sizes[2] // 16) and p.prt[B.L_WG][3] == 1 and p.prt[B.L_WAVE][3] == 8
+        assert p.prt[B.L_WG][2] == -(-sizes[2] // 16) and p.prt[B.L_WG][3] == 1 and p.prt[B.L_WAVE][3] == 4
+        assert p.in_region[0] == B.MR_LDS and p.in_region[1] == B.MR_LDS
+        q = p.copy()
+        q.in_region[0] = q.in_region[1] = B.MR_VGPR  # four wavefronts only with the staged operands
+        assert mdh.mdh_validate_params(mdh.MDH_BMATMUL, sizes, q) != 0
         assert mdh.mdh_workspace_size(mdh.MDH_BMATMUL, sizes, p) == 0
         assert mdh.mdh_validate_params(mdh.MDH_BMATMUL, sizes, p) == 0
         q = p.copy()
@@ -103,6 +108,10 @@ def test_small_m_default_streams_operands_to_registers():
               if c.blk[1] == 16 and c.prt[B.L_VGPR][2] == 1]
     assert sorted(c.prt[B.L_WAVE][3] for c in narrow) == [8, 16]
     assert all(mdh.mdh_validate_params(mdh.MDH_BMATMUL, sizes, c) == 0 for c in narrow)
+    assert all(c.in_region[1] == B.MR_VGPR for c in narrow)  # staging whole runs of k needs B transposed
+    q = narrow[0].copy()
+    q.in_region[0] = q.in_region[1] = B.MR_LDS
+    assert mdh.mdh_validate_params(mdh.MDH_BMATMUL, sizes, q) != 0
     # A or C transposed, or more rows: the LDS-tiled kernel
     for sizes in ((1, 16, 1000, 2048, 1, 0, 0), (1, 16, 1000, 2048, 0, 0, 1), (1, 17, 1000, 2048, 0, 0, 0)):
         p = mdh.mdh_default_params(mdh.MDH_BMATMUL, sizes)
@@ -172,7 +181,8 @@ def test_small_m_every_candidate(shape):
 def test_small_m_narrow_strips(shape, tb):
     # strips of one block column, k over the wavefronts of a workgroup in rounds of 128: whole rounds and
     # a ragged last one, a ragged last strip, fewer than 16 rows, fewer rounds than wavefronts, batches;
-    # both views of B, 8 and 16 wavefronts; NaN-filled output shows every element is written
+    # both views of B, 8 and 16 wavefronts (4 and 8 with the operands staged through LDS); NaN-filled output
+    # shows every element is written
     nb, M, N, K = shape
     A = W.uniform(W.SEED_BASE + 68, 1, (nb, M, K), -1, 1)
     Bm = W.uniform(W.SEED_BASE + 68, 2, (nb, N, K) if tb else (nb, K, N), -1, 1)
@@ -181,7 +191,9 @@ def test_small_m_narrow_strips(shape, tb):
     cands = [mdh.mdh_candidate(mdh.MDH_BMATMUL, sizes, i) for i in range(mdh.mdh_num_candidates(mdh.MDH_BMATMUL, sizes))]
     d = mdh.mdh_default_params(mdh.MDH_BMATMUL, sizes)
     narrow = [p for p in [d] + cands if p.blk[1] == 16 and p.prt[B.L_VGPR][2] == 1]
-    assert sorted(set(p.prt[B.L_WAVE][3] for p in narrow)) == [8, 16]
+    assert sorted(set(p.prt[B.L_WAVE][3] for p in narrow if p.in_region[1] == B.MR_VGPR)) == [8, 16]
+    # B transposed: also the variant that reads whole runs of k and stages both operands through LDS
+    assert sorted(set(p.prt[B.L_WAVE][3] for p in narrow if p.in_region[1] == B.MR_LDS)) == ([4, 8] if tb else [])
     for p in narrow:
         assert mdh.mdh_workspace_size(mdh.MDH_BMATMUL, sizes, p) == 0
         got, _ = run(A, Bm, False, tb, False, p)
