@@ -446,7 +446,9 @@ mdh_status plan_matmul(const int64_t* s, const mdh_tile_params* p, GemmPlan* out
 
 bool small_m_matmul(const int64_t* s, const mdh_tile_params* p) {
   if (!p) return s[0] > 0 && s[0] <= 16 && s[1] > 0;
-  return p->D == 3 && p->blk[0] == 16 && p->prt[MDH_L_VGPR][1] == 4;
+  // both strip widths of that kernel (64 or 16 columns per wavefront); the kernel that splits k over
+  // wavefronts has 16 x 16 x 4 blocks too, but combines in LDS
+  return p->D == 3 && p->blk[0] == 16 && (p->prt[MDH_L_VGPR][1] == 4 || p->out_region != MDH_MR_LDS);
 }
 
 static void move_dims(const mdh_tile_params& src, mdh_tile_params* dst, int D, int shift) {

@@ -119,10 +119,13 @@ def test_matmul_k_on_the_wavefront_layer_every_candidate(shape):
 
 def test_matmul_with_few_rows_takes_the_small_m_kernel():
     # M <= 16 through mdh_matmul: the register-streaming kernel of the batched entry point, same bits
-    for M, N, K in ((16, 1000, 2048), (1, 130, 257), (7, 64, 48)):
+    # (both strip widths of that kernel: 64 columns per wavefront, and 16 per workgroup where those fill
+    # the chip and the reduction is short -- the last two shapes)
+    for M, N, K in ((16, 1000, 2048), (1, 130, 257), (7, 64, 48), (8, 3512, 40), (16, 4096, 1024)):
         A, Bm = W.matmul_inputs(W.MatmulCfg(M, N, K, W.SEED_BASE + 14))
         d = mdh.mdh_default_params(mdh.MDH_MATMUL, (M, N, K))
-        assert d.D == 3 and list(d.blk[:3]) == [16, 16, 4] and d.prt[B.L_VGPR][1] == 4
+        assert d.D == 3 and list(d.blk[:3]) == [16, 16, 4]
+        assert d.prt[B.L_VGPR][1] == (1 if N >= 3512 else 4)
         assert mdh.mdh_validate_params(mdh.MDH_MATMUL, (M, N, K), d) == 0
         ref, refabs = oracle.matmul(A, Bm, with_abs=True)
         got = run_matmul(A, Bm, None)

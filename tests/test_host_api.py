@@ -292,3 +292,53 @@ def test_mcc_defaults_and_candidates_validate_for_any_channel_count():
     q = p.copy()
     q.prt[3][4], q.prt[0][4] = 8, 2
     assert mdh.mdh_validate_params(mdh.MDH_MCC, sizes, q) == 3
+
+
+def test_planner_over_a_seeded_sweep_of_sizes():
+    # ~1300 seeded random shapes over every instance: the default configuration exists and validates, its
+    # parts cover the sizes (exactly unless it says ragged), every candidate validates, and the workspace
+    # size is defined for each of them.  Host only; the sizes are log-uniform so that tiny, ragged and
+    # large extents all occur.
+    import numpy as np
+
+    rng = np.random.default_rng(20240511)
+
+    def ri(lo, hi):
+        return int(np.clip(np.exp(rng.uniform(np.log(lo), np.log(hi + 1))), lo, hi))
+
+    def shapes():
+        for _ in range(120):
+            yield mdh.MDH_MATMUL, (ri(1, 5000), ri(1, 5000), ri(1, 9000)), None
+            tr = [int(rng.integers(2)) for _ in range(3)]
+            yield mdh.MDH_BMATMUL, (ri(1, 20), ri(1, 600), ri(1, 5000), ri(1, 30000), *tr), None
+            yield mdh.MDH_BMATMUL, (ri(1, 4), ri(1, 16), ri(1, 9000), ri(1, 70000), 0, int(rng.integers(2)), 0), None
+            yield mdh.MDH_STENCIL, (ri(1, 600), ri(1, 600), ri(1, 600)), None
+            R, S = ri(1, 7), ri(1, 7)
+            yield mdh.MDH_MCC, (ri(1, 32), ri(1, 120), ri(1, 120), ri(1, 300), ri(1, 600), R, S, ri(1, 3), ri(1, 3)), None
+            yield mdh.MDH_MCC, (ri(1, 32), ri(1, 120), ri(1, 120), ri(1, 130), ri(1, 8), R, S, ri(1, 3), ri(1, 3)), None
+            c = (ri(1, 16), ri(1, 60), ri(1, 60), ri(1, 70), ri(1, 4), R, S, ri(1, 2), ri(1, 2))
+            yield mdh.MDH_MCC_CAPSULE, c, (c[0], c[1], c[2], c[3], 4, 4, c[4], c[5], c[6], 4)
+            yield mdh.MDH_CUSTOM_REDUCE, (ri(1, 100000), ri(1, 300000), ri(1, 8)), None
+            yield mdh.MDH_DOT, (ri(1, 1 << 28),), None
+            yield mdh.MDH_MATVEC, (ri(1, 40000), ri(1, 40000)), None
+            yield mdh.MDH_SCAN, (ri(1, 100000), ri(1, 1 << 20)), None
+
+    n_checked = 0
+    for inst, sizes, ext in shapes():
+        try:
+            p = mdh.mdh_default_params(inst, sizes)
+        except mdh.MdhError as e:
+            # the capsule kernel keeps its filter slice in LDS: large filters have no configuration
+            assert inst == mdh.MDH_MCC_CAPSULE and e.status == E_RES, (inst, sizes, e.status)
+            continue
+        assert mdh.mdh_validate_params(inst, sizes, p) == OK, (inst, sizes)
+        ext = ext or sizes
+        for d in range(p.D):
+            e = p.extent(d)
+            assert (e >= ext[d]) if p.ragged else (e == ext[d]), (inst, sizes, d, e)
+        for i in range(mdh.mdh_num_candidates(inst, sizes)):
+            c = mdh.mdh_candidate(inst, sizes, i)
+            assert mdh.mdh_validate_params(inst, sizes, c) == OK, (inst, sizes, i)
+            assert mdh.mdh_workspace_size(inst, sizes, c) >= 0
+        n_checked += 1
+    assert n_checked > 1200
