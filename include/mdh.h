@@ -588,8 +588,8 @@ mdh_status mdh_custom_tune(const mdh_custom_desc* desc, const void* const* input
  * peak (paper: Section "Experimental Results" measures against hand-tuned
  * libraries instead) can then be read against the attainable rate as well.
  * Every call enqueues one kernel (the arithmetic ones MDH_CALIB_BLOCKS workgroups x
- * 256 lanes; the streaming ones one workgroup of 512 lanes per compute unit, the
- * launch shape measured fastest).
+ * 256 lanes; the streaming read one workgroup of 512 lanes per compute unit, the copy
+ * one workgroup of 256 lanes per 16 KB piece: the launch shapes measured fastest).
  *   mdh_calib_copy : dst[0..bytes) = src[0..bytes), 16-byte non-temporal accesses;
  *                    bytes > 0 and a multiple of 16, both pointers 16-byte aligned.
  *   mdh_calib_read : streams src once; the first MDH_CALIB_STREAM_LANES floats of
